@@ -1,0 +1,180 @@
+/*
+ * last.h -- C ABI of the MI355X (gfx950) lattice library.
+ *
+ * The library computes, on one GPU, the semiring shortest distance over the
+ * complete recognition lattice of a globally normalised transducer
+ * (arXiv 2304.13134, Sections 2.1 and 3), its gradient (the arc marginals of
+ * Eq. 1, obtained by forward-backward as in Section 4.2.2), the shortest
+ * distance on the lattice intersected with a reference label string
+ * (Section 2.1, the numerator of the globally normalised loss), and the
+ * tropical shortest path with integer backpointers (Sections 2.3, 4.2.3).
+ *
+ * Lattice (Section 3): context dependency = full n-gram of context size
+ * `order` over `vocab` labels; alignment lattice = frame dependent (exactly
+ * one arc, a label or the empty label, per frame; Figure 1b); weight function
+ * = a dense tensor, or the shared-embedding function evaluated on the fly
+ * (Section 4.1) as tanh(f[b][t] + e[q]) @ W.
+ *
+ * Index conventions (part of this ABI):
+ *   labels y in 0..V, y = 0 is the empty label; it keeps the context state.
+ *   context states q in 0..C-1; 0 = empty history;
+ *     order 1: state a (1..V) = "last label a";               C = 1 + V
+ *     order 2: (a) -> a, (a,b) -> 1 + V + (a-1)V + (b-1);     C = 1 + V + V^2
+ *   next(q, y>0): order 1 -> y; order 2: () -> (y), (a) -> (a,y), (a,b) -> (b,y).
+ *   every state (len[b], q) is final with weight 0.
+ *   dense weights: w[b][t][q][y], float32, C-contiguous [B][T][C][V+1].
+ *   semirings: higher is better; (+) = log-add-exp (LAST_LOG) or max
+ *   (LAST_TROPICAL), (x) = +, zero = -inf, one = 0.
+ *
+ * Memory and execution:
+ *   Pointers marked "dev" are device (HBM) pointers owned by the caller; the
+ *   library never allocates, frees or keeps them.  Structs are host memory.
+ *   All work is enqueued on `hip_stream` (a hipStream_t passed as void*;
+ *   NULL = the default stream) and the calls return without synchronising.
+ *   `ws` is a dev scratch buffer of at least last_workspace_bytes() bytes,
+ *   256-byte aligned, contents undefined before and after a call.  Outputs
+ *   must not alias inputs.
+ *
+ * Errors: the return value reports what the host can check (null pointers,
+ * bad shapes, num_states inconsistent with (vocab, order), workspace too
+ * small, unsupported combination, HIP launch failure); on error nothing is
+ * enqueued.  Data-dependent conditions are reported per item in the optional
+ * dev array item_status[B]:
+ *   0 ok; 1 length outside [0,T]; 2 reference label outside [1,V];
+ *   3 reference length outside [0,Umax]; 4 infeasible (reference longer than
+ *   the number of frames: numerator = -inf, its marginals are 0);
+ *   5 the cooperating workgroups of an item timed out waiting for each other
+ *   (results of that item are undefined; never expected in normal operation).
+ * Items with status 1..3 get dist = NaN and zero gradients.
+ * Frames t >= len[b] do not exist for item b: their weights are never read
+ * into a result, their marginals are 0 and their path entries are -1.
+ */
+#ifndef LAST_H_
+#define LAST_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LAST_OK = 0,
+    LAST_ERR_NULL = 1,        /* a required pointer is NULL                    */
+    LAST_ERR_SHAPE = 2,       /* a size is non-positive or too large           */
+    LAST_ERR_CONTEXT = 3,     /* order not in {1,2} or num_states inconsistent */
+    LAST_ERR_SEMIRING = 4,    /* unknown semiring                              */
+    LAST_ERR_WORKSPACE = 5,   /* ws NULL, misaligned or too small              */
+    LAST_ERR_UNSUPPORTED = 6, /* combination not implemented                   */
+    LAST_ERR_HIP = 7          /* a HIP call failed                             */
+} last_status_t;
+
+typedef enum { LAST_LOG = 0, LAST_TROPICAL = 1 } last_semiring_t;
+
+typedef enum {
+    LAST_OP_SHORTEST_DISTANCE = 0,
+    LAST_OP_ARC_POSTERIORS = 1,
+    LAST_OP_INTERSECT_REFERENCE = 2,
+    LAST_OP_SHORTEST_PATH = 3
+} last_op_t;
+
+/* Context dependency: full n-gram (Section 3; Figure 1a is order 1). */
+typedef struct {
+    int32_t vocab;      /* V >= 1                                  */
+    int32_t order;      /* context size n: 1 or 2                  */
+    int32_t num_states; /* C, must equal sum_{k<=n} V^k            */
+} last_context_t;
+
+enum { LAST_WEIGHTS_DENSE = 0, LAST_WEIGHTS_SHARED_EMB = 1 };
+
+/* Weight function (Section 3).  kind = dense: `w` dev float32 [B][T][C][V+1].
+ * kind = shared_emb: f dev bf16 [B][T][hidden], e dev bf16 [C][hidden],
+ * W dev bf16 [hidden][V+1] (bf16 = upper 16 bits of a float32); the hidden
+ * vector tanh(f + e) is rounded to bf16 before the float32-accumulated
+ * contraction with W; the weights are never stored. */
+typedef struct {
+    int32_t kind;
+    int32_t B, T;
+    const float* w;
+    const uint16_t* f;
+    const uint16_t* e;
+    const uint16_t* W;
+    int32_t hidden;
+} last_weights_t;
+
+/* Where gradients go.  dense: dw dev float32 [B][T][C][V+1].  shared_emb:
+ * df dev float32 [B][T][hidden], de dev float32 [C][hidden], dW dev float32
+ * [hidden][V+1].  accumulate = 0: out = scale * marginal (every element of the
+ * tensor is written); accumulate = 1: out += scale * marginal. */
+typedef struct {
+    float* dw;
+    float* df;
+    float* de;
+    float* dW;
+    int32_t accumulate;
+    float scale;
+} last_grads_t;
+
+/* Scratch bytes `op` needs for these shapes (Umax only matters for
+ * LAST_OP_INTERSECT_REFERENCE).  Returns 0 on invalid arguments. */
+size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t* context,
+                            int32_t op, int32_t Umax);
+
+/* Shortest distance over the complete lattice (Section 2.1; Eq. 2 visited in
+ * increasing t as in Section 4.1).  lengths: dev int32 [B].  dist: dev
+ * float32 [B] = (+)-sum over all accepting paths (LAST_LOG) or the best path
+ * score (LAST_TROPICAL). */
+last_status_t last_shortest_distance(const last_weights_t* weights, const int32_t* lengths,
+                                     const last_context_t* context, last_semiring_t semiring,
+                                     float* dist, int32_t* item_status,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Log-semiring shortest distance and its gradient, the arc marginals of
+ * Eq. 1, by forward-backward (Section 4.2.2: only alpha and beta are kept,
+ * O(|Q|) extra space).  dist: dev float32 [B].  out: see last_grads_t. */
+last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* lengths,
+                                  const last_context_t* context, float* dist,
+                                  const last_grads_t* out, int32_t* item_status,
+                                  void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Intersection with the reference string and log-semiring shortest distance
+ * on it (Section 2.1; Table 1 "GNAT, intersected": O(TU) states and arcs).
+ * State (t,u): u reference labels read, context ctx(u) = next(ctx(u-1), ref[u]);
+ * arcs: empty label to (t+1,u) with weight w[t][ctx(u)][0], label ref[u+1] to
+ * (t+1,u+1) with weight w[t][ctx(u)][ref[u+1]]; only (len, U) is final.
+ * refs: dev int32 [B][Umax] labels in 1..V; ref_lengths: dev int32 [B].
+ * numerator: dev float32 [B].  out (or NULL): marginals of the intersected
+ * lattice scattered onto the arcs of the complete lattice they ride on
+ * (dense weights only), normally with accumulate = 1, scale = -1 after
+ * last_arc_posteriors so that dw = d(dist - numerator)/dw. */
+last_status_t last_intersect_reference(const last_weights_t* weights, const int32_t* lengths,
+                                       const last_context_t* context,
+                                       const int32_t* refs, const int32_t* ref_lengths,
+                                       int32_t Umax, float* numerator,
+                                       const last_grads_t* out, int32_t* item_status,
+                                       void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Tropical shortest path (Sections 2.1, 2.3, 4.2.3): one float32 add per arc,
+ * arg max kept per state as the flat arc index q*(V+1)+y, ties to the lowest
+ * flat index, final ties to the lowest state; then a backtrace.
+ * labels: dev int32 [B][T]; states: dev int32 [B][T+1]; entries past len are
+ * -1.  score: dev float32 [B]. */
+last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* lengths,
+                                 const last_context_t* context,
+                                 int32_t* labels, int32_t* states, float* score,
+                                 int32_t* item_status,
+                                 void* ws, size_t ws_bytes, void* hip_stream);
+
+const char* last_status_string(last_status_t status);
+
+/* Library version and the kernel variant a call would use, for diagnostics:
+ * 0 = one workgroup per item, 1 = cooperating workgroups per item. */
+int32_t last_version(void);
+int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t* context,
+                            int32_t op);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAST_H_ */

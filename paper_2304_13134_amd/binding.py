@@ -1,0 +1,219 @@
+"""Thin ctypes binding of the C-ABI library declared in ``include/last.h``.
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels.  PyTorch supplies device memory and the current stream, nothing else.
+There is no CPU fallback: if ``liblast_hip.so`` has not been built
+(``python -m paper_2304_13134_amd.build``) the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblast_hip.so")
+
+LAST_LOG, LAST_TROPICAL = 0, 1
+OP_SHORTEST_DISTANCE, OP_ARC_POSTERIORS, OP_INTERSECT_REFERENCE, OP_SHORTEST_PATH = 0, 1, 2, 3
+WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
+
+EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
+           "last_intersect_reference", "last_shortest_path", "last_status_string",
+           "last_version", "last_kernel_variant"]
+
+
+class LastContext(ctypes.Structure):
+    _fields_ = [("vocab", ctypes.c_int32), ("order", ctypes.c_int32),
+                ("num_states", ctypes.c_int32)]
+
+
+class LastWeights(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("w", ctypes.c_void_p), ("f", ctypes.c_void_p), ("e", ctypes.c_void_p),
+                ("W", ctypes.c_void_p), ("hidden", ctypes.c_int32)]
+
+
+class LastGrads(ctypes.Structure):
+    _fields_ = [("dw", ctypes.c_void_p), ("df", ctypes.c_void_p), ("de", ctypes.c_void_p),
+                ("dW", ctypes.c_void_p), ("accumulate", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class LastError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("liblast_hip: status %d (%s)" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load liblast_hip.so (no GPU needed to load it) and set the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("liblast_hip.so is not built; run `python -m paper_2304_13134_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.last_workspace_bytes.restype = sz
+    lib.last_workspace_bytes.argtypes = [ctypes.POINTER(LastWeights), ctypes.POINTER(LastContext), i32, i32]
+    lib.last_shortest_distance.restype = i32
+    lib.last_shortest_distance.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                           i32, vp, vp, vp, sz, vp]
+    lib.last_arc_posteriors.restype = i32
+    lib.last_arc_posteriors.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                        vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
+    lib.last_intersect_reference.restype = i32
+    lib.last_intersect_reference.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                             vp, vp, i32, vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
+    lib.last_shortest_path.restype = i32
+    lib.last_shortest_path.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                       vp, vp, vp, vp, vp, sz, vp]
+    lib.last_status_string.restype = ctypes.c_char_p
+    lib.last_status_string.argtypes = [i32]
+    lib.last_version.restype = i32
+    lib.last_kernel_variant.restype = i32
+    lib.last_kernel_variant.argtypes = [ctypes.POINTER(LastWeights), ctypes.POINTER(LastContext), i32]
+    _lib = lib
+    return lib
+
+
+def _check(code):
+    if code != 0:
+        raise LastError(code, load_library().last_status_string(code).decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_tensor(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous device tensor of dtype %s" % (name, dtype))
+    return t
+
+
+_workspaces = {}
+
+
+def workspace(nbytes, device):
+    """A cached device scratch buffer (grown on demand, 256-byte aligned by the allocator)."""
+    key = torch.device(device).index or 0
+    buf = _workspaces.get(key)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _workspaces[key] = buf
+    return buf
+
+
+def context(V, order):
+    C = 1 + V if order == 1 else 1 + V + V * V
+    return LastContext(V, order, C)
+
+
+def dense_weights(w):
+    _dev_tensor(w, torch.float32, "w")
+    B, T, C, V1 = w.shape
+    return LastWeights(WEIGHTS_DENSE, B, T, w.data_ptr(), None, None, None, 0)
+
+
+def shared_emb_weights(f, e, W):
+    for t, n in ((f, "f"), (e, "e"), (W, "W")):
+        _dev_tensor(t, torch.bfloat16, n)
+    B, T, H = f.shape
+    return LastWeights(WEIGHTS_SHARED_EMB, B, T, None, f.data_ptr(), e.data_ptr(), W.data_ptr(), H)
+
+
+def _dense_ctx(w, order):
+    V = w.shape[3] - 1
+    cx = context(V, order)
+    if cx.num_states != w.shape[2]:
+        raise ValueError("w.shape[2] does not match the context dependency")
+    return cx
+
+
+def last_workspace_bytes(weights, cx, op, Umax=0):
+    return int(load_library().last_workspace_bytes(ctypes.byref(weights), ctypes.byref(cx), op, Umax))
+
+
+def last_kernel_variant(weights, cx, op):
+    return int(load_library().last_kernel_variant(ctypes.byref(weights), ctypes.byref(cx), op))
+
+
+def last_shortest_distance(w, lengths, order=1, semiring="log", item_status=None):
+    """dist [B] float32 (device).  semiring: "log" or "tropical"."""
+    lib = load_library()
+    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    dist = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    ws = workspace(last_workspace_bytes(wt, cx, OP_SHORTEST_DISTANCE), w.device)
+    sr = LAST_LOG if semiring == "log" else LAST_TROPICAL
+    _check(lib.last_shortest_distance(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), sr,
+                                      _ptr(dist), _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
+    return dist
+
+
+def last_arc_posteriors(w, lengths, order=1, dw=None, scale=1.0, accumulate=False,
+                        item_status=None):
+    """(dist [B], dw [B,T,C,V+1]) on the device; dw = scale * arc marginals."""
+    lib = load_library()
+    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    if dw is None:
+        dw = torch.empty_like(w)
+    _dev_tensor(dw, torch.float32, "dw")
+    dist = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
+    ws = workspace(last_workspace_bytes(wt, cx, OP_ARC_POSTERIORS), w.device)
+    _check(lib.last_arc_posteriors(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), _ptr(dist),
+                                   ctypes.byref(g), _ptr(item_status), _ptr(ws), ws.numel(),
+                                   _stream()))
+    return dist, dw
+
+
+def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, scale=-1.0,
+                             accumulate=True, item_status=None):
+    """numerator [B] float32; if dw is given, scale * (marginals of the
+    intersected lattice) is added to (accumulate) or written over dw."""
+    lib = load_library()
+    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    _dev_tensor(refs, torch.int32, "refs")
+    _dev_tensor(ref_lengths, torch.int32, "ref_lengths")
+    Umax = refs.shape[1]
+    num = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    g = None
+    if dw is not None:
+        _dev_tensor(dw, torch.float32, "dw")
+        g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
+    ws = workspace(last_workspace_bytes(wt, cx, OP_INTERSECT_REFERENCE, Umax), w.device)
+    _check(lib.last_intersect_reference(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx),
+                                        _ptr(refs), _ptr(ref_lengths), Umax, _ptr(num),
+                                        ctypes.byref(g) if g is not None else None,
+                                        _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
+    return num
+
+
+def last_shortest_path(w, lengths, order=1, item_status=None):
+    """(labels [B,T] int32, states [B,T+1] int32, score [B] float32) on the device."""
+    lib = load_library()
+    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    B, T = w.shape[0], w.shape[1]
+    labels = torch.empty((B, T), dtype=torch.int32, device=w.device)
+    states = torch.empty((B, T + 1), dtype=torch.int32, device=w.device)
+    score = torch.empty(B, dtype=torch.float32, device=w.device)
+    ws = workspace(last_workspace_bytes(wt, cx, OP_SHORTEST_PATH), w.device)
+    _check(lib.last_shortest_path(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), _ptr(labels),
+                                  _ptr(states), _ptr(score), _ptr(item_status), _ptr(ws),
+                                  ws.numel(), _stream()))
+    return labels, states, score

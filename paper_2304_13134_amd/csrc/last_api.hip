@@ -1,0 +1,348 @@
+// C ABI of the lattice library (see include/last.h): argument validation,
+// workspace planning and kernel launches.  No allocation, no synchronisation.
+#include "../../include/last.h"
+
+#include <hip/hip_runtime.h>
+
+#include "common.hpp"
+#include "solo_kernels.hpp"
+#include "numerator_kernels.hpp"
+
+using namespace last;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+// bump allocator over the caller's workspace; with base == nullptr it only measures
+struct Carver {
+    char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base((char*)p) {}
+    template <typename T>
+    T* take(size_t count)
+    {
+        T* p = base ? (T*)(base + used) : nullptr;
+        used += align_up(count * sizeof(T));
+        return p;
+    }
+};
+
+struct Shape {
+    int B, T, V, V1, C, order;
+};
+
+last_status_t check_common(const last_weights_t* wt, const last_context_t* cx, Shape* s)
+{
+    if (!wt || !cx) return LAST_ERR_NULL;
+    if (cx->order != 1 && cx->order != 2) return LAST_ERR_CONTEXT;
+    if (cx->vocab < 1) return LAST_ERR_CONTEXT;
+    const long long V = cx->vocab;
+    const long long C = cx->order == 1 ? 1 + V : 1 + V + V * V;
+    if (C != cx->num_states || C > (1 << 24)) return LAST_ERR_CONTEXT;
+    if (wt->B < 1 || wt->T < 0) return LAST_ERR_SHAPE;
+    if (wt->B > 65535 || wt->T > (1 << 24)) return LAST_ERR_SHAPE;
+    if (wt->kind == LAST_WEIGHTS_DENSE) {
+        if (!wt->w) return LAST_ERR_NULL;
+    } else if (wt->kind == LAST_WEIGHTS_SHARED_EMB) {
+        if (!wt->f || !wt->e || !wt->W) return LAST_ERR_NULL;
+        if (wt->hidden < 1) return LAST_ERR_SHAPE;
+    } else {
+        return LAST_ERR_UNSUPPORTED;
+    }
+    s->B = wt->B;
+    s->T = wt->T;
+    s->V = cx->vocab;
+    s->V1 = cx->vocab + 1;
+    s->C = (int)C;
+    s->order = cx->order;
+    return LAST_OK;
+}
+
+Ctx make_ctx(const Shape& s) { return Ctx{s.V, s.order, s.C, s.V1}; }
+
+// thread layout of the one-workgroup-per-item forward kernels
+struct SoloLayout {
+    int CPAD, R;
+    size_t lds_forward, lds_viterbi, lds_backward;
+};
+
+SoloLayout solo_layout(const Shape& s)
+{
+    SoloLayout l;
+    int cpad = (s.C + 63) / 64 * 64;
+    if (cpad > 1024) cpad = 1024;
+    l.CPAD = cpad;
+    l.R = 1024 / cpad;
+    l.lds_forward = (size_t)(2 * s.C + 2 * l.R * l.CPAD + 32) * sizeof(float);
+    l.lds_viterbi = (size_t)(2 * s.C + 2 * l.R * l.CPAD + 64) * sizeof(float);
+    l.lds_backward = (size_t)(2 * s.C + 32) * sizeof(float);
+    return l;
+}
+
+constexpr size_t kMaxLds = 64 * 1024;
+
+struct PosteriorWs {
+    float* alpha;
+    double* offs;
+    double* D;
+};
+
+PosteriorWs carve_posteriors(Carver& cv, const Shape& s)
+{
+    PosteriorWs p;
+    p.alpha = cv.take<float>((size_t)s.B * (s.T + 1) * s.C);
+    p.offs = cv.take<double>((size_t)s.B * (s.T + 1));
+    p.D = cv.take<double>((size_t)s.B);
+    return p;
+}
+
+struct PathWs {
+    int* bp;
+    int* final_state;
+};
+
+PathWs carve_path(Carver& cv, const Shape& s)
+{
+    PathWs p;
+    p.bp = cv.take<int>((size_t)s.B * (s.T > 0 ? s.T : 1) * s.C);
+    p.final_state = cv.take<int>((size_t)s.B);
+    return p;
+}
+
+struct NumWs {
+    float2* wi;
+    double* a;
+    double* bk;
+    double* N;
+    int* status;
+};
+
+NumWs carve_num(Carver& cv, const Shape& s, int Umax)
+{
+    NumWs p;
+    const size_t U1 = (size_t)Umax + 1;
+    p.wi = cv.take<float2>((size_t)s.B * (s.T > 0 ? s.T : 1) * U1);
+    p.a = cv.take<double>((size_t)s.B * (s.T + 1) * U1);
+    p.bk = cv.take<double>((size_t)s.B * (s.T + 1) * U1);
+    p.N = cv.take<double>((size_t)s.B);
+    p.status = cv.take<int>((size_t)s.B);
+    return p;
+}
+
+last_status_t check_ws(void* ws, size_t have, size_t need)
+{
+    if (need == 0) return LAST_OK;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || have < need) return LAST_ERR_WORKSPACE;
+    return LAST_OK;
+}
+
+last_status_t hip_status()
+{
+    return hipGetLastError() == hipSuccess ? LAST_OK : LAST_ERR_HIP;
+}
+
+template <typename F>
+void dispatch_group(int V1, F&& f)
+{
+    if (V1 <= 4) f(std::integral_constant<int, 4>());
+    else if (V1 <= 8) f(std::integral_constant<int, 8>());
+    else if (V1 <= 16) f(std::integral_constant<int, 16>());
+    else if (V1 <= 48) f(std::integral_constant<int, 32>());
+    else f(std::integral_constant<int, 64>());
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t last_version(void) { return 1; }
+
+const char* last_status_string(last_status_t status)
+{
+    switch (status) {
+    case LAST_OK: return "ok";
+    case LAST_ERR_NULL: return "a required pointer is NULL";
+    case LAST_ERR_SHAPE: return "invalid shape";
+    case LAST_ERR_CONTEXT: return "invalid context dependency";
+    case LAST_ERR_SEMIRING: return "unknown semiring";
+    case LAST_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LAST_ERR_UNSUPPORTED: return "combination not supported";
+    case LAST_ERR_HIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t* context,
+                            int32_t op)
+{
+    Shape s;
+    if (check_common(weights, context, &s) != LAST_OK) return -1;
+    (void)op;
+    return 0;
+}
+
+size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t* context,
+                            int32_t op, int32_t Umax)
+{
+    Shape s;
+    if (check_common(weights, context, &s) != LAST_OK) return 0;
+    Carver cv(nullptr);
+    switch (op) {
+    case LAST_OP_SHORTEST_DISTANCE:
+        cv.take<double>(1);
+        break;
+    case LAST_OP_ARC_POSTERIORS:
+        carve_posteriors(cv, s);
+        break;
+    case LAST_OP_INTERSECT_REFERENCE:
+        if (Umax < 0) return 0;
+        carve_num(cv, s, Umax);
+        break;
+    case LAST_OP_SHORTEST_PATH:
+        carve_path(cv, s);
+        break;
+    default:
+        return 0;
+    }
+    return cv.used;
+}
+
+last_status_t last_shortest_distance(const last_weights_t* weights, const int32_t* lengths,
+                                     const last_context_t* context, last_semiring_t semiring,
+                                     float* dist, int32_t* item_status,
+                                     void* ws, size_t ws_bytes, void* hip_stream)
+{
+    Shape s;
+    last_status_t rc = check_common(weights, context, &s);
+    if (rc != LAST_OK) return rc;
+    if (!lengths || !dist) return LAST_ERR_NULL;
+    if (semiring != LAST_LOG && semiring != LAST_TROPICAL) return LAST_ERR_SEMIRING;
+    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_SHORTEST_DISTANCE, 0));
+    if (rc != LAST_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const SoloLayout l = solo_layout(s);
+    const Ctx c = make_ctx(s);
+    if (semiring == LAST_LOG) {
+        if (l.lds_forward > kMaxLds) return LAST_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
+                           weights->w, lengths, c, s.T, l.CPAD, l.R,
+                           (float*)nullptr, (double*)nullptr, (double*)nullptr, dist, item_status);
+    } else {
+        if (l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st,
+                           weights->w, lengths, c, s.T, l.CPAD, l.R,
+                           (int*)nullptr, (int*)nullptr, dist, item_status);
+    }
+    return hip_status();
+}
+
+last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* lengths,
+                                  const last_context_t* context, float* dist,
+                                  const last_grads_t* out, int32_t* item_status,
+                                  void* ws, size_t ws_bytes, void* hip_stream)
+{
+    Shape s;
+    last_status_t rc = check_common(weights, context, &s);
+    if (rc != LAST_OK) return rc;
+    if (!lengths || !dist || !out) return LAST_ERR_NULL;
+    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    if (!out->dw) return LAST_ERR_NULL;
+    rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0));
+    if (rc != LAST_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const SoloLayout l = solo_layout(s);
+    if (l.lds_forward > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    const Ctx c = make_ctx(s);
+    Carver cv(ws);
+    PosteriorWs p = carve_posteriors(cv, s);
+    hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
+                       weights->w, lengths, c, s.T, l.CPAD, l.R, p.alpha, p.offs, p.D, dist,
+                       item_status);
+    if (s.T > 0) {
+        dispatch_group(s.V1, [&](auto G) {
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(solo_backward_log<decltype(G)::value>), dim3(s.B),
+                               dim3(1024), l.lds_backward, st, weights->w, lengths, c, s.T,
+                               (const float*)p.alpha, (const double*)p.offs, (const double*)p.D,
+                               out->dw, out->scale, out->accumulate);
+        });
+    }
+    return hip_status();
+}
+
+last_status_t last_intersect_reference(const last_weights_t* weights, const int32_t* lengths,
+                                       const last_context_t* context,
+                                       const int32_t* refs, const int32_t* ref_lengths,
+                                       int32_t Umax, float* numerator,
+                                       const last_grads_t* out, int32_t* item_status,
+                                       void* ws, size_t ws_bytes, void* hip_stream)
+{
+    Shape s;
+    last_status_t rc = check_common(weights, context, &s);
+    if (rc != LAST_OK) return rc;
+    if (!lengths || !ref_lengths || !numerator) return LAST_ERR_NULL;
+    if (Umax < 0 || Umax > (1 << 20)) return LAST_ERR_SHAPE;
+    if (Umax > 0 && !refs) return LAST_ERR_NULL;
+    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    if (out && !out->dw) return LAST_ERR_NULL;
+    const size_t lds = (size_t)2 * (Umax + 2) * sizeof(double);
+    if (lds > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    rc = check_ws(ws, ws_bytes,
+                  last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax));
+    if (rc != LAST_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const Ctx c = make_ctx(s);
+    Carver cv(ws);
+    NumWs p = carve_num(cv, s, Umax);
+    const int U1 = Umax + 1;
+    hipLaunchKernelGGL(num_check_kernel, dim3(s.B), dim3(256), 0, st, lengths, refs, ref_lengths,
+                       s.T, s.V, Umax, p.status);
+    const dim3 pgrid((U1 + 127) / 128, s.T > 0 ? s.T : 1, s.B);
+    if (s.T > 0)
+        hipLaunchKernelGGL(num_gather_kernel, pgrid, dim3(128), 0, st, weights->w, lengths, refs,
+                           ref_lengths, (const int*)p.status, c, s.T, Umax, p.wi);
+    hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
+                       (const float2*)p.wi, lengths, ref_lengths, (const int*)p.status, s.T, Umax,
+                       p.a, p.bk, p.N, numerator, item_status);
+    if (out && s.T > 0) {
+        if (!out->accumulate) {
+            const size_t n = (size_t)s.B * s.T * s.C * s.V1;
+            hipLaunchKernelGGL(zero_fill_kernel, dim3(2048), dim3(256), 0, st, out->dw, n);
+        }
+        hipLaunchKernelGGL(num_scatter_kernel, pgrid, dim3(128), 0, st, (const float2*)p.wi,
+                           lengths, refs, ref_lengths, (const int*)p.status, c, s.T, Umax,
+                           (const double*)p.a, (const double*)p.bk, (const double*)p.N, out->dw,
+                           out->scale);
+    }
+    return hip_status();
+}
+
+last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* lengths,
+                                 const last_context_t* context,
+                                 int32_t* labels, int32_t* states, float* score,
+                                 int32_t* item_status,
+                                 void* ws, size_t ws_bytes, void* hip_stream)
+{
+    Shape s;
+    last_status_t rc = check_common(weights, context, &s);
+    if (rc != LAST_OK) return rc;
+    if (!lengths || !labels || !states || !score) return LAST_ERR_NULL;
+    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_SHORTEST_PATH, 0));
+    if (rc != LAST_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const SoloLayout l = solo_layout(s);
+    if (l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    const Ctx c = make_ctx(s);
+    Carver cv(ws);
+    PathWs p = carve_path(cv, s);
+    hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,
+                       c, s.T, l.CPAD, l.R, p.bp, p.final_state, score, item_status);
+    hipLaunchKernelGGL(backtrace_kernel, dim3(s.B), dim3(256), 0, st, (const int*)p.bp, lengths,
+                       (const int*)p.final_state, s.C, s.V1, s.T, labels, states);
+    return hip_status();
+}
+
+}  // extern "C"

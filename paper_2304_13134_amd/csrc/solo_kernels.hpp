@@ -1,0 +1,312 @@
+// One-workgroup-per-item kernels: the general, range-robust path (any context
+// order, any vocabulary size).  Everything is kept in the log domain with
+// per-destination maxima, and the state vector of the current frame lives in
+// LDS for the whole recursion (Eq. 2 of arXiv 2304.13134 visited frame by
+// frame, Section 4.1).  States are rescaled per frame, alpha~_t = alpha_t - A_t,
+// with the scalar offsets A_t accumulated in float64, so that every float32
+// quantity stays O(10) although log-partition values reach several thousand.
+#pragma once
+#include "common.hpp"
+
+namespace last {
+
+__device__ __forceinline__ void lse_acc(float v, float& m, float& s)
+{
+    if (v == LAST_NEG_INF) return;
+    if (v > m) {
+        s = s * expf(m - v) + 1.f;   // m = -inf: s is still 0 and exp(-inf) = 0
+        m = v;
+    } else {
+        s += expf(v - m);
+    }
+}
+
+// Thread layout of the forward kernels: the workgroup is viewed as R groups of
+// CPAD threads; thread (g, dl) accumulates, for destination state d0 + dl, the
+// incoming label arcs i = g, g + R, ...; group 0 also takes the empty-label arc.
+// Lanes are adjacent destinations, so for a fixed source row the loads are
+// contiguous.
+
+// Shortest distance in the log semiring (Section 2.1; Eq. 2).
+//   alpha_ws [B][T+1][C] rescaled forward weights (may be null: not stored)
+//   offs     [B][T+1]    A_t (may be null)
+//   Dws      [B]         D in float64 (may be null);  dist [B] float32
+__global__ __launch_bounds__(1024) void solo_forward_log(
+    const float* __restrict__ w, const int* __restrict__ len, Ctx c, int T, int CPAD, int R,
+    float* __restrict__ alpha_ws, double* __restrict__ offs, double* __restrict__ Dws,
+    float* __restrict__ dist, int* __restrict__ item_status)
+{
+    extern __shared__ float smem[];
+    float* cur = smem;
+    float* nxt = cur + c.C;
+    float* pm = nxt + c.C;
+    float* ps = pm + R * CPAD;
+    float* red = ps + R * CPAD;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int L = len[b];
+    if (L < 0 || L > T) {
+        if (tid == 0) {
+            if (item_status) item_status[b] = kItemBadLength;
+            dist[b] = __builtin_nanf("");
+            if (Dws) Dws[b] = __builtin_nan("");
+        }
+        return;
+    }
+    if (tid == 0 && item_status) item_status[b] = kItemOk;
+    const int g = tid / CPAD, dl = tid - g * CPAD;
+    const size_t fr = (size_t)c.C * c.V1;
+    float* al = alpha_ws ? alpha_ws + (size_t)b * (T + 1) * c.C : nullptr;
+    for (int d = tid; d < c.C; d += blockDim.x) {
+        const float v = d == 0 ? 0.f : LAST_NEG_INF;
+        cur[d] = v;
+        if (al) al[d] = v;
+    }
+    if (tid == 0 && offs) offs[(size_t)b * (T + 1)] = 0.0;
+    double A = 0.0;
+    __syncthreads();
+    for (int t = 0; t < L; ++t) {
+        const float* wt = w + ((size_t)b * T + t) * fr;
+        for (int d0 = 0; d0 < c.C; d0 += CPAD) {
+            const int d = d0 + dl;
+            if (g < R && d < c.C) {
+                float m = LAST_NEG_INF, s = 0.f;
+                const int n = ctx_num_in(c, d);
+                const int y = d > 0 ? ctx_in_label(c, d) : 0;
+                for (int i = g; i < n; i += R) {
+                    const int q = ctx_in_source(c, d, i);
+                    lse_acc(cur[q] + wt[(size_t)q * c.V1 + y], m, s);
+                }
+                if (g == 0) lse_acc(cur[d] + wt[(size_t)d * c.V1], m, s);
+                pm[g * CPAD + dl] = m;
+                ps[g * CPAD + dl] = s;
+            }
+            __syncthreads();
+            if (g == 0 && d < c.C) {
+                float M = LAST_NEG_INF;
+                for (int k = 0; k < R; ++k) M = fmaxf(M, pm[k * CPAD + dl]);
+                float S = 0.f;
+                if (M != LAST_NEG_INF)
+                    for (int k = 0; k < R; ++k) {
+                        const float mk = pm[k * CPAD + dl];
+                        if (mk != LAST_NEG_INF) S += ps[k * CPAD + dl] * expf(mk - M);
+                    }
+                nxt[d] = (M == LAST_NEG_INF) ? LAST_NEG_INF : M + logf(S);
+            }
+            __syncthreads();
+        }
+        float mx = LAST_NEG_INF;
+        for (int d = tid; d < c.C; d += blockDim.x) mx = fmaxf(mx, nxt[d]);
+        mx = block_max(mx, red);
+        if (mx == LAST_NEG_INF) mx = 0.f;   // no state reachable: keep -inf everywhere
+        A += (double)mx;
+        for (int d = tid; d < c.C; d += blockDim.x) {
+            const float v = nxt[d] - mx;
+            cur[d] = v;
+            if (al) al[(size_t)(t + 1) * c.C + d] = v;
+        }
+        if (tid == 0 && offs) offs[(size_t)b * (T + 1) + t + 1] = A;
+        __syncthreads();
+    }
+    // all states of the last frame are final with weight 0
+    float mx = LAST_NEG_INF;
+    for (int d = tid; d < c.C; d += blockDim.x) mx = fmaxf(mx, cur[d]);
+    mx = block_max(mx, red);
+    float s = 0.f;
+    if (mx != LAST_NEG_INF)
+        for (int d = tid; d < c.C; d += blockDim.x) s += expf(cur[d] - mx);
+    s = block_sum(s, red);
+    if (tid == 0) {
+        const double D = (mx == LAST_NEG_INF) ? (double)LAST_NEG_INF
+                                              : A + (double)mx + (double)logf(s);
+        dist[b] = (float)D;
+        if (Dws) Dws[b] = D;
+    }
+}
+
+// Backward weights and arc marginals (Eq. 1; Section 4.2.2).  A group of G
+// lanes owns one source state (a row of the frame, contiguous in memory) and
+// strides over its V+1 arcs.  gamma = exp(alpha~_t[q] + w + beta~_{t+1}[next]
+// + (A_t + B_{t+1} - D)), the bracket formed in float64.
+template <int G>
+__global__ __launch_bounds__(1024) void solo_backward_log(
+    const float* __restrict__ w, const int* __restrict__ len, Ctx c, int T,
+    const float* __restrict__ alpha_ws, const double* __restrict__ offs,
+    const double* __restrict__ Dws, float* __restrict__ dw, float scale, int accumulate)
+{
+    extern __shared__ float smem[];
+    float* bn = smem;          // beta~_{t+1}
+    float* bc = bn + c.C;      // beta_t before rescaling
+    float* red = bc + c.C;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const size_t fr = (size_t)c.C * c.V1;
+    float* gw = dw + (size_t)b * T * fr;
+    int L = len[b];
+    const bool bad = (L < 0 || L > T);
+    if (bad) L = 0;
+    if (!accumulate)
+        for (size_t i = (size_t)L * fr + tid; i < (size_t)T * fr; i += blockDim.x) gw[i] = 0.f;
+    if (bad) return;
+    for (int d = tid; d < c.C; d += blockDim.x) bn[d] = 0.f;
+    const double D = Dws[b];
+    double Boff = 0.0;
+    const int NR = blockDim.x / G, r = tid / G, l = tid - r * G;
+    __syncthreads();
+    for (int t = L - 1; t >= 0; --t) {
+        const float* wt = w + ((size_t)b * T + t) * fr;
+        float* gt = gw + (size_t)t * fr;
+        const float* at = alpha_ws + ((size_t)b * (T + 1) + t) * c.C;
+        const float K = (float)(offs[(size_t)b * (T + 1) + t] + Boff - D);
+        for (int q0 = 0; q0 < c.C; q0 += NR) {
+            const int q = q0 + r;
+            const bool valid = q < c.C;
+            const float* row = wt + (size_t)q * c.V1;
+            float m = LAST_NEG_INF;
+            if (valid)
+                for (int y = l; y < c.V1; y += G) m = fmaxf(m, row[y] + bn[ctx_next(c, q, y)]);
+            m = group_max<G>(m);
+            float s = 0.f;
+            if (valid && m != LAST_NEG_INF)
+                for (int y = l; y < c.V1; y += G) s += expf(row[y] + bn[ctx_next(c, q, y)] - m);
+            s = group_sum<G>(s);
+            if (valid) {
+                if (l == 0) bc[q] = (m == LAST_NEG_INF) ? LAST_NEG_INF : m + logf(s);
+                const float a = at[q];
+                float* grow = gt + (size_t)q * c.V1;
+                for (int y = l; y < c.V1; y += G) {
+                    float p = 0.f;
+                    if (a != LAST_NEG_INF) p = scale * expf(row[y] + bn[ctx_next(c, q, y)] + a + K);
+                    if (accumulate) grow[y] += p; else grow[y] = p;
+                }
+            }
+        }
+        __syncthreads();
+        float mx = LAST_NEG_INF;
+        for (int d = tid; d < c.C; d += blockDim.x) mx = fmaxf(mx, bc[d]);
+        mx = block_max(mx, red);
+        if (mx == LAST_NEG_INF) mx = 0.f;
+        Boff += (double)mx;
+        for (int d = tid; d < c.C; d += blockDim.x) bn[d] = bc[d] - mx;
+        __syncthreads();
+    }
+}
+
+// zero the gradient of items whose length is invalid (used by the clustered path too)
+__global__ void zero_fill_kernel(float* __restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0.f;
+}
+
+// Tropical shortest distance with arg-max backpointers (Section 4.2.3): one
+// float32 add per arc, exact comparisons, no rescaling.  Ties: lowest flat arc
+// index q*(V+1)+y.  bp [B][T][C] (may be null), final_state [B] (may be null).
+__device__ __forceinline__ void trop_acc(float v, int flat, float& best, int& bflat)
+{
+    if (v > best || (v == best && v != LAST_NEG_INF && flat < bflat)) { best = v; bflat = flat; }
+}
+
+__global__ __launch_bounds__(1024) void solo_viterbi(
+    const float* __restrict__ w, const int* __restrict__ len, Ctx c, int T, int CPAD, int R,
+    int* __restrict__ bp, int* __restrict__ final_state, float* __restrict__ score,
+    int* __restrict__ item_status)
+{
+    extern __shared__ float smem[];
+    float* cur = smem;
+    float* nxt = cur + c.C;
+    float* pv = nxt + c.C;
+    int* pi = (int*)(pv + R * CPAD);
+    float* redv = (float*)(pi + R * CPAD);
+    int* redi = (int*)(redv + 32);
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int L = len[b];
+    if (L < 0 || L > T) {
+        if (tid == 0) {
+            if (item_status) item_status[b] = kItemBadLength;
+            score[b] = __builtin_nanf("");
+            if (final_state) final_state[b] = -1;
+        }
+        return;
+    }
+    if (tid == 0 && item_status) item_status[b] = kItemOk;
+    const int g = tid / CPAD, dl = tid - g * CPAD;
+    const size_t fr = (size_t)c.C * c.V1;
+    for (int d = tid; d < c.C; d += blockDim.x) cur[d] = d == 0 ? 0.f : LAST_NEG_INF;
+    __syncthreads();
+    for (int t = 0; t < L; ++t) {
+        const float* wt = w + ((size_t)b * T + t) * fr;
+        for (int d0 = 0; d0 < c.C; d0 += CPAD) {
+            const int d = d0 + dl;
+            if (g < R && d < c.C) {
+                float best = LAST_NEG_INF;
+                int bflat = 0x7fffffff;
+                const int n = ctx_num_in(c, d);
+                const int y = d > 0 ? ctx_in_label(c, d) : 0;
+                for (int i = g; i < n; i += R) {
+                    const int q = ctx_in_source(c, d, i);
+                    trop_acc(__fadd_rn(cur[q], wt[(size_t)q * c.V1 + y]), q * c.V1 + y, best, bflat);
+                }
+                if (g == 0) trop_acc(__fadd_rn(cur[d], wt[(size_t)d * c.V1]), d * c.V1, best, bflat);
+                pv[g * CPAD + dl] = best;
+                pi[g * CPAD + dl] = bflat;
+            }
+            __syncthreads();
+            if (g == 0 && d < c.C) {
+                float best = LAST_NEG_INF;
+                int bflat = 0x7fffffff;
+                for (int k = 0; k < R; ++k) trop_acc(pv[k * CPAD + dl], pi[k * CPAD + dl], best, bflat);
+                nxt[d] = best;
+                if (bp) bp[((size_t)b * T + t) * c.C + d] = (bflat == 0x7fffffff) ? -1 : bflat;
+            }
+            __syncthreads();
+        }
+        for (int d = tid; d < c.C; d += blockDim.x) cur[d] = nxt[d];
+        __syncthreads();
+    }
+    // best final state, lowest index among equals
+    float best = LAST_NEG_INF;
+    int bidx = 0x7fffffff;
+    for (int d = tid; d < c.C; d += blockDim.x)
+        if (cur[d] > best || (cur[d] == best && d < bidx)) { best = cur[d]; bidx = d; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(bidx, o, kWave);
+        if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
+    }
+    const int wid = tid / kWave, nw = blockDim.x / kWave;
+    if ((tid & (kWave - 1)) == 0) { redv[wid] = best; redi[wid] = bidx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < nw; ++k)
+            if (redv[k] > best || (redv[k] == best && redi[k] < bidx)) { best = redv[k]; bidx = redi[k]; }
+        score[b] = best;
+        if (final_state) final_state[b] = bidx;
+    }
+}
+
+// Follow the backpointers from the best final state (the 0/1 arc mask of the
+// tropical gradient, Section 2.3, returned as indices).
+__global__ void backtrace_kernel(const int* __restrict__ bp, const int* __restrict__ len,
+                                 const int* __restrict__ final_state, int C, int V1, int T,
+                                 int* __restrict__ labels, int* __restrict__ states)
+{
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int L = len[b];
+    if (L < 0 || L > T) L = -1;
+    for (int t = tid; t < T; t += blockDim.x)
+        if (t >= L) labels[(size_t)b * T + t] = -1;
+    for (int t = tid; t <= T; t += blockDim.x)
+        if (t > L) states[(size_t)b * (T + 1) + t] = -1;
+    if (tid != 0 || L < 0) return;
+    int q = final_state[b];
+    states[(size_t)b * (T + 1) + L] = q;
+    for (int t = L - 1; t >= 0; --t) {
+        const int arc = bp[((size_t)b * T + t) * C + q];
+        q = arc / V1;
+        labels[(size_t)b * T + t] = arc - q * V1;
+        states[(size_t)b * (T + 1) + t] = q;
+    }
+}
+
+}  // namespace last

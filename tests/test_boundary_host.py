@@ -1,0 +1,91 @@
+"""Host-only checks of the C-ABI boundary: the library loads without a GPU,
+exports every symbol include/last.h declares, and rejects bad arguments before
+anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2304_13134_amd import binding as lb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2304_13134_amd.build import build_library
+        build_library()
+    return lb.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "last.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(last_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(lb.EXPORTS) == set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    for code in range(8):
+        assert len(lib.last_status_string(code)) > 0
+    assert lib.last_version() >= 1
+
+
+def _wt(B=2, T=5, w=0x1000):
+    return lb.LastWeights(lb.WEIGHTS_DENSE, B, T, w, None, None, None, 0)
+
+
+def test_workspace_bytes_and_context_validation(lib):
+    cx = lb.context(3, 1)
+    wt = _wt()
+    n = lb.last_workspace_bytes(wt, cx, lb.OP_ARC_POSTERIORS)
+    assert n >= 2 * 6 * 4 * 4 and n % 256 == 0
+    assert lb.last_workspace_bytes(wt, cx, lb.OP_SHORTEST_PATH) >= 2 * 5 * 4 * 4
+    assert lb.last_workspace_bytes(wt, cx, lb.OP_INTERSECT_REFERENCE, 3) > 0
+    assert lb.last_workspace_bytes(wt, cx, 99) == 0
+    bad = lb.LastContext(3, 1, 5)
+    assert lb.last_workspace_bytes(wt, bad, lb.OP_ARC_POSTERIORS) == 0
+    assert lb.context(32, 2).num_states == 1057          # Table 2 of the paper
+    assert lb.last_workspace_bytes(_wt(), lb.LastContext(3, 3, 40), 0) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    cx = lb.context(3, 1)
+    wt = _wt()
+    vp = ctypes.c_void_p
+    dummy = vp(0x2000)
+    # null pointers
+    assert lib.last_shortest_distance(None, dummy, ctypes.byref(cx), 0, dummy, None, dummy, 1 << 20, None) == 1
+    assert lib.last_shortest_distance(ctypes.byref(wt), None, ctypes.byref(cx), 0, dummy, None, dummy, 1 << 20, None) == 1
+    nullw = _wt(w=None)
+    assert lib.last_shortest_distance(ctypes.byref(nullw), dummy, ctypes.byref(cx), 0, dummy, None, dummy, 1 << 20, None) == 1
+    # shape, context, semiring
+    assert lib.last_shortest_distance(ctypes.byref(_wt(B=0)), dummy, ctypes.byref(cx), 0, dummy, None, dummy, 1 << 20, None) == 2
+    bad = lb.LastContext(3, 1, 7)
+    assert lib.last_shortest_distance(ctypes.byref(wt), dummy, ctypes.byref(bad), 0, dummy, None, dummy, 1 << 20, None) == 3
+    assert lib.last_shortest_distance(ctypes.byref(wt), dummy, ctypes.byref(cx), 7, dummy, None, dummy, 1 << 20, None) == 4
+    # workspace: null, misaligned, too small
+    g = lb.LastGrads(0x3000, None, None, None, 0, 1.0)
+    assert lib.last_arc_posteriors(ctypes.byref(wt), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None, None, 1 << 20, None) == 5
+    assert lib.last_arc_posteriors(ctypes.byref(wt), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None, vp(0x2001), 1 << 20, None) == 5
+    assert lib.last_arc_posteriors(ctypes.byref(wt), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None, dummy, 16, None) == 5
+    gnull = lb.LastGrads(None, None, None, None, 0, 1.0)
+    assert lib.last_arc_posteriors(ctypes.byref(wt), dummy, ctypes.byref(cx), dummy, ctypes.byref(gnull), None, dummy, 1 << 20, None) == 1
+    # unsupported weight kind
+    unk = lb.LastWeights(9, 2, 5, 0x1000, None, None, None, 0)
+    assert lib.last_shortest_path(ctypes.byref(unk), dummy, ctypes.byref(cx), dummy, dummy, dummy, None, dummy, 1 << 20, None) == 6
+    assert lib.last_intersect_reference(ctypes.byref(wt), dummy, ctypes.byref(cx), dummy, dummy, -1, dummy, None, None, dummy, 1 << 20, None) == 2
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        lb.last_shortest_distance(torch.zeros(1, 2, 4, 4), torch.zeros(1, dtype=torch.int32))
