@@ -1,0 +1,733 @@
+// Clustered forward-backward for the bigram (context size 1) complete lattice
+// with dense weights: the bandwidth path.
+//
+// The recursion of Eq. 2 (arXiv 2304.13134) is serial in t, but a single frame
+// of one item is a C x C slab (264 KB at C = 257), far more than one compute
+// unit can stream.  Each item is therefore spread over a cluster of 2K
+// persistent workgroups that live on one XCD (workgroup ids are dealt
+// round-robin over the 8 XCDs, so a cluster takes ids with equal id % 8):
+//   K "alpha" workgroups run the forward weights from frame 0 upwards,
+//   K "beta"  workgroups run the backward weights from frame len-1 downwards,
+// both at the same time.  They meet in the middle: once alpha has reached
+// frame mid = len/2 and beta has come down to it, D is known
+// (D = log sum_q alpha_mid[q] beta_mid[q]) and each side keeps going over the
+// other half, now also writing the arc marginals of Eq. 1 against the state
+// vectors the other side stored on its way (forward-backward with O(|Q|)
+// extra space, Section 4.2.2).  Every weight is read twice and every marginal
+// written once (12 bytes per arc) in len serial steps instead of 2 len.
+//
+// Work split inside a role: workgroup k owns the source states (rows)
+// [k*RPW, (k+1)*RPW) of every frame, a contiguous chunk of memory.
+//   alpha: thread <-> destination column; partial column sums over the own
+//          rows are exchanged (reduce-scatter: workgroup k only needs the
+//          sums for its own states);
+//   beta : wavefront <-> row, lanes <-> columns; complete row sums are
+//          exchanged (all-gather).
+// Arithmetic is in the scaled linear domain: E = 2^(w*log2(e) - s) with an
+// integer shift s per column (alpha) or per row (beta) chosen from the data so
+// that E <= 1, state vectors carry a common integer exponent (Sa, Sb), and
+// partial results travel as (float value, int16 shift).  exp(w) does not depend
+// on the recursion, so it is evaluated while the previous step's exchange is in
+// flight; the serial chain per frame is: FMA loop, publish, poll, rescale.
+//
+// Exchange: 64-bit words [value:32 | shift:16 | tag:16] written and polled with
+// relaxed agent-scope atomics; the tag (a running step counter) makes each word
+// self-validating, so no fences are needed on the per-frame path.  Two slots
+// (step parity) suffice: nobody can publish step s+2 before everybody has
+// consumed step s.  One wavefront per workgroup (the "comm" wave) does all
+// polling so that the streaming loads of the compute waves never sit in front
+// of a poll in the in-order load return queue.  Every poll loop is bounded.
+#pragma once
+#include <type_traits>
+
+#include "common.hpp"
+
+namespace last {
+
+typedef unsigned long long u64;
+
+constexpr int kClMaxR = 34;      // max rows owned by one workgroup (two halves of kClRT rows)
+constexpr int kClRT = 17;        // rows per alpha thread: each workgroup splits its rows in two halves
+constexpr int kClHW = 5;         // compute waves per half (alpha): 5 * 64 >= kClMaxC columns
+constexpr int kClWaves = 10;     // compute waves per workgroup
+constexpr int kClRW = 4;         // max rows per compute wave (beta): ceil(34 / 10)
+constexpr int kClNC = 5;         // max columns per lane (beta): ceil(320 / 64)
+constexpr int kClMaxC = 320;     // max number of states / labels on this path
+constexpr int kClThreads = (kClWaves + 1) * kWave;
+constexpr int kClMaxK = 10;      // max workgroups per role
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kShiftNone = -30000;
+constexpr unsigned kTagInvalid = 0xFFFFu;
+
+struct ClusterArgs {
+    const float* w;
+    const int* len;
+    float* dw;
+    float* dist;
+    int* item_status;
+    float* ahat;   // [B][T+1][C] forward vectors (scaled), rows t <= mid
+    float* bhat;   // [B][T+1][C] backward vectors (scaled), rows t >= mid
+    int* Sa;       // [B][T+1] binary exponent of ahat rows
+    int* Sb;       // [B][T+1]
+    u64* xa;       // [ncl_total][2][2K][XS] alpha partials of each half (+ header word at index C)
+    u64* xb;       // [ncl_total][2][XSB]   beta values
+    u64* ph;       // [ncl_total][32]       phase flags
+    int B, T, C;
+    int K, RPW, ncl;   // workgroups per role, rows per workgroup, clusters per XCD
+    int XS, XSB;
+    float scale;
+    int accumulate;
+    int spin_limit;
+};
+
+// ---- cross-lane helpers on DPP (the critical path cannot afford LDS permutes)
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_f(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL,
+                                                      ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_i(int old, int v)
+{
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+// full-wave sum / max, result broadcast to every lane
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v += dpp_f<0x111>(0.f, v);
+    v += dpp_f<0x112>(0.f, v);
+    v += dpp_f<0x114>(0.f, v);
+    v += dpp_f<0x118>(0.f, v);
+    v += dpp_f<0x142, 0xa>(0.f, v);
+    v += dpp_f<0x143, 0xc>(0.f, v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_dpp(float v)
+{
+    v = fmaxf(v, dpp_f<0x111>(v, v));
+    v = fmaxf(v, dpp_f<0x112>(v, v));
+    v = fmaxf(v, dpp_f<0x114>(v, v));
+    v = fmaxf(v, dpp_f<0x118>(v, v));
+    v = fmaxf(v, dpp_f<0x142, 0xa>(v, v));
+    v = fmaxf(v, dpp_f<0x143, 0xc>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ int wave_max_dpp(int v)
+{
+    v = max(v, dpp_i<0x111>(v, v));
+    v = max(v, dpp_i<0x112>(v, v));
+    v = max(v, dpp_i<0x114>(v, v));
+    v = max(v, dpp_i<0x118>(v, v));
+    v = max(v, dpp_i<0x142, 0xa>(v, v));
+    v = max(v, dpp_i<0x143, 0xc>(v, v));
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+__device__ __forceinline__ u64 xload(const u64* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void xstore(u64* p, u64 v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u64 pack_word(float v, int shift, unsigned tag)
+{
+    return (u64)__float_as_uint(v) | ((u64)(unsigned)(shift & 0xFFFF) << 32) | ((u64)(tag & 0xFFFFu) << 48);
+}
+__device__ __forceinline__ float word_value(u64 x) { return __uint_as_float((unsigned)x); }
+__device__ __forceinline__ int word_shift(u64 x) { return (int)(short)(unsigned short)(x >> 32); }
+__device__ __forceinline__ unsigned word_tag(u64 x) { return (unsigned)(x >> 48); }
+__device__ __forceinline__ u64 pack_header(int h, int m, unsigned tag)
+{
+    return (u64)(unsigned)(h & 0xFFFF) | ((u64)(unsigned)(m & 0xFFFF) << 16) | ((u64)(tag & 0xFFFFu) << 48);
+}
+__device__ __forceinline__ int header_h(u64 x) { return (int)(short)(unsigned short)x; }
+__device__ __forceinline__ int header_m(u64 x) { return (int)(short)(unsigned short)(x >> 16); }
+
+__device__ __forceinline__ int float_exponent(float x)   // floor(log2 x) for normal x > 0; -127 for 0
+{
+    return (int)((__float_as_uint(x) >> 23) & 0xFFu) - 127;
+}
+__device__ __forceinline__ int shift_for(float mx)        // integer s >= mx*log2(e)
+{
+    if (!(mx > -3.0e4f)) return kShiftNone;
+    float s = ceilf(mx * kLog2e);
+    return (int)fminf(s, 30000.f);
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// poll one word until its tag matches; gives up after `limit` polls (dead = 1)
+__device__ __forceinline__ u64 poll_word(const u64* p, unsigned tag, int limit, int& dead)
+{
+    u64 x = xload(p);
+    if (dead) return x;
+    int n = 0;
+    while (word_tag(x) != tag) {
+        if (++n > limit) { dead = 1; break; }
+        __builtin_amdgcn_s_sleep(1);
+        x = xload(p);
+    }
+    return x;
+}
+
+struct ClusterGeom {
+    int role;     // 0 alpha, 1 beta
+    int k;        // workgroup index inside the role
+    int cg;       // global cluster index
+    int r0, nr;   // owned rows
+};
+
+// barrier among the 2K workgroups of a cluster with release/acquire semantics
+// for plain global stores (used once per item, at the meeting frame)
+__device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const ClusterGeom& g, unsigned tag,
+                                             int& dead, int* dead_s)
+{
+    __threadfence();
+    __syncthreads();
+    u64* flags = a.ph + (size_t)g.cg * 32;
+    const int me = g.role * a.K + g.k;
+    const u64 target = (u64)tag + 1;          // flags count items; ~0 = never written
+    if (threadIdx.x == 0) xstore(flags + me, target);
+    if (threadIdx.x < 2 * a.K && !dead) {
+        int n = 0;
+        for (;;) {
+            const u64 x = xload(flags + threadIdx.x);
+            if (x != ~0ull && x >= target) break;
+            if (++n > a.spin_limit) { *dead_s = 1; break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+    __syncthreads();
+    dead = *dead_s;
+    __threadfence();
+}
+
+// ------------------------------------------------------------------ alpha role
+template <int D, bool GAMMA>
+__device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
+                                           unsigned& gstep, unsigned& ptag)
+{
+    // LDS carve
+    float* ap_s = smem;                       // [2][kClMaxR] partial-sum part of a_t
+    float* bl_s = ap_s + 2 * kClMaxR;         // [2][kClMaxR] empty-label products
+    float* bv_s = bl_s + 2 * kClMaxR;         // [2][kClMaxC] bhat_{t+1} staging (GAMMA)
+    // ctl: [0..1] dl, [2..5] s0[par][half], [6..7] sig, [8..39] hw[2][16], [40] dead
+    int* ctl_s = (int*)(bv_s + 2 * kClMaxC);
+    float* red = (float*)(ctl_s + 48);        // [32]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, keep it scalar
+    const bool comm = wave == kClWaves;
+    const int half = wave >= kClHW ? 1 : 0;   // which half of the workgroup's rows
+    const int c = tid - half * kClHW * kWave; // column of a compute thread
+    const int C = a.C, V1 = a.C;
+    const bool colok = !comm && c < C;
+
+    for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
+        int L = a.len[b];
+        const bool bad = L < 0 || L > a.T;
+        if (bad) L = 0;
+        const int mid = L / 2;
+        const int n = GAMMA ? L : mid;               // iterations of this role
+        const int nex = GAMMA ? (L > 0 ? L - 1 : 0) : mid;   // iterations that exchange
+        const size_t fr = (size_t)C * V1;
+        const float* wb = a.w + (size_t)b * a.T * fr + (size_t)g.r0 * V1;
+        float* gb = GAMMA ? a.dw + (size_t)b * a.T * fr + (size_t)g.r0 * V1 : nullptr;
+        float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
+        const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
+        int* Sa = a.Sa + (size_t)b * (a.T + 1);
+        const int* Sb = a.Sb + (size_t)b * (a.T + 1);
+        u64* xbase = a.xa + (size_t)g.cg * 2 * 2 * a.K * a.XS;
+
+        if (tid == 0) ctl_s[40] = 0;
+        // state 0: a_0 = unit vector at state 0, exponent 0; no empty-label carry-in
+        if (tid < kClMaxR) {
+            ap_s[tid] = (g.r0 + tid == 0 && tid < g.nr) ? 1.f : 0.f;
+            ap_s[kClMaxR + tid] = 0.f;
+            bl_s[tid] = 0.f;
+            bl_s[kClMaxR + tid] = 0.f;
+        }
+        if (tid == 0) { ctl_s[0] = 0; ctl_s[4] = kShiftNone; ctl_s[5] = kShiftNone; ctl_s[6] = 0; }
+        int dead = 0;
+        int sig = 0;          // comm wave: exponent of the current state vector
+        int m_own = (g.r0 == 0 && g.nr > 0) ? 0 : -127;
+        double D2 = 0.0;
+        float E[D][kClRT];
+        int sc[D];
+        const int rb = half * kClRT;          // first row (inside the workgroup) of this thread
+        float bcol[2] = {0.f, 0.f};
+        int sbn[2] = {0, 0};
+
+        // Byte offsets of this thread's elements inside a frame (the same for every frame and for
+        // the marginals, which share the layout of w): one scalar frame base + these per load.
+        // Rows beyond the owned range are clamped to the last owned row: their a-values are 0.
+        unsigned voff[kClRT];
+#pragma unroll
+        for (int r = 0; r < kClRT; ++r)
+            voff[r] = (unsigned)((min(rb + r, g.nr - 1) * V1 + c) * (int)sizeof(float));
+        const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
+        auto issue = [&](int slot, int f) __attribute__((always_inline)) {
+            const char* fb = (const char*)(wb + (size_t)f * fr);
+#pragma unroll
+            for (int r = 0; r < kClRT; ++r)
+                E[slot][r] = __builtin_nontemporal_load((const float*)(fb + voff[r]));
+        };
+        auto prep = [&](int slot) __attribute__((always_inline)) {
+            float mx = E[slot][0];
+#pragma unroll
+            for (int r = 1; r < kClRT; ++r) mx = fmaxf(mx, E[slot][r]);
+            const int s = shift_for(mx);
+            sc[slot] = s;
+            const float fs = (float)s;
+#pragma unroll
+            for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
+            return s;
+        };
+
+        if (colok) {
+#pragma unroll
+            for (int f = 0; f < D - 1; ++f)
+                if (f < n) issue(f, f);
+        }
+        __syncthreads();
+        int hcur = kShiftNone;   // compute waves: max column shift of the frame in slot 0
+        if (colok && n > 0) hcur = prep(0);
+        if (!comm) {
+            const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
+            if (lane == 0) ctl_s[8 + wave] = hw;
+        }
+        __syncthreads();
+
+        auto body = [&](auto SLOT, int i) __attribute__((always_inline)) {
+            constexpr int S = decltype(SLOT)::value;
+            const int par = i & 1;
+            const bool exch = i < nex;
+            const unsigned tag = (gstep % 65535u);
+            u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
+            if (!comm) {
+                if (colok) {
+                    const int dl = ctl_s[par];
+                    const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
+                    float fac = 0.f;
+                    if (GAMMA && i >= mid) {
+                        const float kx = (float)((double)(ctl_s[6 + par] + sbn[par]) - D2);
+                        fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
+                    }
+                    float av[kClRT];
+                    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+                    for (int r = 0; r < kClRT; ++r) {
+                        av[r] = ap_s[par * kClMaxR + rb + r]
+                                + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
+                        if (r & 1) acc1 = fmaf(av[r], E[S][r], acc1);
+                        else acc0 = fmaf(av[r], E[S][r], acc0);
+                    }
+                    const float acc = acc0 + acc1;
+                    if (exch && c >= 1)
+                        xstore(xs + (size_t)(2 * g.k + half) * a.XS + c, pack_word(acc, sc[S], tag));
+                    if (c == 0) {
+#pragma unroll
+                        for (int r = 0; r < kClRT; ++r) bl_s[par * kClMaxR + rb + r] = av[r] * E[S][r];
+                        ctl_s[2 + par * 2 + half] = sc[S];
+                    }
+                    if (GAMMA && i >= mid) {
+                        char* gfb = (char*)(gb + (size_t)i * fr);
+                        // the empty label (column 0) returns to the row's own state
+                        auto gval = [&](int r) __attribute__((always_inline)) {
+                            const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + min(rb + r, g.nr - 1)] : fac;
+                            return av[r] * E[S][r] * f2;
+                        };
+                        if (a.accumulate) {
+#pragma unroll
+                            for (int r = 0; r < kClRT; ++r)
+                                if (r < nrt) *(float*)(gfb + voff[r]) += gval(r);
+                        } else if (nrt == kClRT) {
+#pragma unroll
+                            for (int r = 0; r < kClRT; ++r)
+                                __builtin_nontemporal_store(gval(r), (float*)(gfb + voff[r]));
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < kClRT; ++r)
+                                if (r < nrt) __builtin_nontemporal_store(gval(r), (float*)(gfb + voff[r]));
+                        }
+                    }
+                    // state vectors of the other side for the marginals two frames ahead
+                    if (GAMMA && i >= mid && i + 2 < n) {
+                        bcol[par] = bh[(size_t)(i + 3) * C + c];
+                        sbn[par] = Sb[i + 3];
+                    }
+                    if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
+                    if (i + 1 < n) hcur = prep((S + 1) % D);
+                    if (GAMMA && i + 1 < n && i + 1 >= mid) bv_s[(par ^ 1) * kClMaxC + c] = bcol[par ^ 1];
+                }
+                if (i + 1 < n) {
+                    const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
+                    if (lane == 0) ctl_s[8 + (par ^ 1) * 16 + wave] = hw;
+                }
+            } else {
+                // ---- comm wave: header, then gather the partial sums for the own states
+                if (exch) {
+                    int h = kShiftNone;
+                    if (lane < kClWaves) h = ctl_s[8 + par * 16 + lane];
+                    h = wave_max_dpp(h);
+                    if (lane == 0) xstore(xs + (size_t)(2 * g.k) * a.XS + C, pack_header(h, m_own, tag));
+                    // headers of all workgroups of the role
+                    int hh = kShiftNone, mm = -127;
+                    if (lane < a.K) {
+                        const u64 x = poll_word(xs + (size_t)(2 * lane) * a.XS + C, tag, a.spin_limit, dead);
+                        hh = header_h(x);
+                        mm = header_m(x);
+                    }
+                    const int dl = wave_max_dpp(hh) + wave_max_dpp(mm);
+                    float v = 0.f;
+                    // only the empty label enters the start state: no partial sums exist for q = 0
+                    if (lane < g.nr && g.r0 + lane != 0) {
+                        u64 x[2 * kClMaxK];
+#pragma unroll
+                        for (int j = 0; j < 2 * kClMaxK; ++j)
+                            if (j < 2 * a.K) x[j] = xload(xs + (size_t)j * a.XS + g.r0 + lane);
+#pragma unroll
+                        for (int j = 0; j < 2 * kClMaxK; ++j)
+                            if (j < 2 * a.K) {
+                                if (word_tag(x[j]) != tag)
+                                    x[j] = poll_word(xs + (size_t)j * a.XS + g.r0 + lane, tag, a.spin_limit, dead);
+                                v += __builtin_ldexpf(word_value(x[j]), word_shift(x[j]) - dl);
+                            }
+                    }
+                    if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v;
+                    sig += dl;
+                    if (lane == 0) { ctl_s[par ^ 1] = dl; ctl_s[6 + (par ^ 1)] = sig; }
+                }
+                if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
+            }
+            if (exch) gstep += 1;
+            __syncthreads();
+            // ---- top of state i+1: the comm wave completes the vector, stores it, takes its magnitude
+            if (comm && exch) {
+                const int p1 = par ^ 1;
+                float av = 0.f;
+                if (lane < g.nr)
+                    av = ap_s[p1 * kClMaxR + lane]
+                         + __builtin_ldexpf(bl_s[par * kClMaxR + lane],
+                                            ctl_s[2 + par * 2 + (lane >= kClRT ? 1 : 0)] - ctl_s[p1]);
+                int e = (lane < g.nr) ? float_exponent(av) : -127;
+                m_own = wave_max_dpp(e);
+                if (i + 1 <= mid) {
+                    if (lane < g.nr) ah[(size_t)(i + 1) * C + g.r0 + lane] = av;
+                    if (lane == 0 && g.k == 0) Sa[i + 1] = sig;
+                }
+            }
+        };
+
+        for (int i = 0;; ++i) {
+            if (i == 0 && comm) {
+                if (lane < g.nr) ah[g.r0 + lane] = (g.r0 + lane == 0) ? 1.f : 0.f;
+                if (lane == 0 && g.k == 0) Sa[0] = 0;
+            }
+            if (i == mid) {
+                dead = ctl_s[40];
+                cluster_sync(a, g, ptag, dead, &ctl_s[40]);
+                ptag += 1;
+                // D = (Sa_mid + Sb_mid) ln 2 + log sum_q ahat_mid[q] bhat_mid[q]
+                float part = 0.f;
+                for (int q = tid; q < C; q += blockDim.x)
+                    part += ah[(size_t)mid * C + q] * bh[(size_t)mid * C + q];
+                const float tot = block_sum(part, red);
+                D2 = (double)(Sa[mid] + Sb[mid]) + (double)__log2f(tot);
+                if (bad) D2 = __builtin_nan("");
+                if (g.k == 0 && tid == 0) {
+                    a.dist[b] = (float)(D2 * 0.6931471805599453);
+                    if (a.item_status) a.item_status[b] = bad ? kItemBadLength : (dead ? kItemTimeout : kItemOk);
+                }
+                if (GAMMA && colok) {
+                    // first two frames of the second half: fetch the other side's vectors now
+                    if (mid < n) { bcol[mid & 1] = bh[(size_t)(mid + 1) * C + c]; sbn[mid & 1] = Sb[mid + 1]; }
+                    if (mid + 1 < n) { bcol[(mid + 1) & 1] = bh[(size_t)(mid + 2) * C + c]; sbn[(mid + 1) & 1] = Sb[mid + 2]; }
+                    if (mid < n) bv_s[(mid & 1) * kClMaxC + c] = bcol[mid & 1];
+                }
+                __syncthreads();
+            }
+            if (i >= n) break;
+            switch (i % D) {
+            case 0: body(std::integral_constant<int, 0>(), i); break;
+            case 1: body(std::integral_constant<int, 1>(), i); break;
+            case 2: body(std::integral_constant<int, 2>(), i); break;
+            default: if constexpr (D > 3) body(std::integral_constant<int, 3>(), i); break;
+            }
+        }
+        __syncthreads();
+        if (g.k == 0 && tid == 0 && ctl_s[40] && a.item_status && !bad) a.item_status[b] = kItemTimeout;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------- beta role
+template <int D, bool GAMMA>
+__device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
+                                          unsigned& gstep, unsigned& ptag)
+{
+    float* b_s = smem;                        // [2][kClMaxC] b_{t+1} (all states)
+    int* ctl_s = (int*)(b_s + 2 * kClMaxC);   // [0..1] sigb, [24] dead
+    float* red = (float*)(ctl_s + 32);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, keep it scalar
+    const bool comm = wave == kClWaves;
+    const int C = a.C, V1 = a.C;
+    // rows of this wave: wave, wave + 5, ... (index inside the workgroup's rows)
+    int nrw = 0;
+    if (!comm) nrw = (g.nr - wave + kClWaves - 1) / kClWaves;
+    if (nrw < 0) nrw = 0;
+    const int ncol = (C + 63) / 64;
+
+    for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
+        int L = a.len[b];
+        const bool bad = L < 0 || L > a.T;
+        if (bad) L = 0;
+        const int mid = L / 2;
+        const int n = GAMMA ? L : L - mid;
+        // the last frame's result is not needed, except that b_mid must exist (L = 1: mid = 0)
+        const int nex = GAMMA ? max(L - 1, L - mid) : L - mid;
+        const int ph1 = L - mid;                     // iteration at which state index reaches mid
+        const size_t fr = (size_t)C * V1;
+        const float* wb = a.w + (size_t)b * a.T * fr + (size_t)g.r0 * V1;
+        float* gb = GAMMA ? a.dw + (size_t)b * a.T * fr + (size_t)g.r0 * V1 : nullptr;
+        const float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
+        float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
+        const int* Sa = a.Sa + (size_t)b * (a.T + 1);
+        int* Sb = a.Sb + (size_t)b * (a.T + 1);
+        u64* xbase = a.xb + (size_t)g.cg * 2 * a.XSB;
+
+        if (tid == 0) { ctl_s[24] = 0; ctl_s[0] = 0; }
+        for (int q = tid; q < C; q += blockDim.x) b_s[q] = 1.f;
+        int dead = 0;
+        int sig = 0;
+        double D2 = 0.0;
+        float E[D][kClRW][kClNC];
+        int sr[D][kClRW];
+        float apre[2] = {0.f, 0.f};   // lane ri < nrw holds ahat_t[row ri] two frames ahead
+        int san[2] = {0, 0};
+
+        // Byte offsets of this lane's elements inside a frame (shared by w and the marginals).
+        // Rows / columns beyond the valid range are clamped: such rows are never published or
+        // stored, such columns meet a zero in the b vector.
+        unsigned voff[kClRW][kClNC];
+#pragma unroll
+        for (int ri = 0; ri < kClRW; ++ri)
+#pragma unroll
+            for (int j = 0; j < kClNC; ++j)
+                voff[ri][j] = (unsigned)((min(wave + ri * kClWaves, g.nr - 1) * V1 + min(lane + 64 * j, C - 1))
+                                         * (int)sizeof(float));
+        auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
+            const char* fb = (const char*)(wb + (size_t)(L - 1 - f) * fr);
+#pragma unroll
+            for (int ri = 0; ri < kClRW; ++ri)
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j)
+                    E[slot][ri][j] = __builtin_nontemporal_load((const float*)(fb + voff[ri][j]));
+        };
+        auto prep = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+            for (int ri = 0; ri < kClRW; ++ri) {
+                float mx = E[slot][ri][0];
+#pragma unroll
+                for (int j = 1; j < kClNC; ++j) mx = fmaxf(mx, E[slot][ri][j]);
+                mx = wave_max_dpp(mx);
+                const int s = shift_for(mx);
+                sr[slot][ri] = s;
+                const float fs = (float)s;
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j)
+                    E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
+            }
+        };
+
+        if (!comm) {
+#pragma unroll
+            for (int f = 0; f < D - 1; ++f)
+                if (f < n) issue(f, f);
+            if (n > 0) prep(0);
+        }
+        __syncthreads();
+
+        auto body = [&](auto SLOT, int i) __attribute__((always_inline)) {
+            constexpr int S = decltype(SLOT)::value;
+            const int par = i & 1;
+            const int t = L - 1 - i;
+            const bool exch = i < nex;
+            const unsigned tag = (gstep % 65535u);
+            u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
+            if (!comm) {
+                float bv[kClNC];
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j)
+                    bv[j] = (j < ncol && lane + 64 * j < C) ? b_s[par * kClMaxC + lane + 64 * j] : 0.f;
+                float kx = 0.f;
+                if (GAMMA && i >= ph1) kx = (float)((double)(san[par] + ctl_s[par]) - D2);
+#pragma unroll
+                for (int ri = 0; ri < kClRW; ++ri) {
+                    const int row = g.r0 + min(wave + ri * kClWaves, g.nr - 1);
+                    const float brow = b_s[par * kClMaxC + row];
+                    // the empty label (column 0) returns to the row's own state
+                    float acc = E[S][ri][0] * (lane == 0 ? brow : bv[0]);
+#pragma unroll
+                    for (int j = 1; j < kClNC; ++j) acc = fmaf(E[S][ri][j], bv[j], acc);
+                    const float tot = wave_sum_dpp(acc);
+                    if (exch && lane == 0 && ri < nrw) xstore(xs + row, pack_word(tot, sr[S][ri], tag));
+                }
+                if (GAMMA && i >= ph1) {
+                    char* gfb = (char*)(gb + (size_t)t * fr);
+#pragma unroll
+                    for (int ri = 0; ri < kClRW; ++ri)
+                        if (ri < nrw) {
+                            const int row = g.r0 + wave + ri * kClWaves;
+                            const float brow = b_s[par * kClMaxC + row];
+                            const float arow = __shfl(apre[par], ri, 64);
+                            const float fac = a.scale * arow * fast_exp2(kx + (float)sr[S][ri]);
+#pragma unroll
+                            for (int j = 0; j < kClNC; ++j)
+                                if (j < ncol && lane + 64 * j < C) {
+                                    const float bb = (j == 0 && lane == 0) ? brow : bv[j];
+                                    const float gv = E[S][ri][j] * bb * fac;
+                                    float* gp = (float*)(gfb + voff[ri][j]);
+                                    if (a.accumulate) *gp += gv;
+                                    else __builtin_nontemporal_store(gv, gp);
+                                }
+                        }
+                }
+                // forward vector of the frame two steps ahead (second half only)
+                if (GAMMA && i >= ph1 && i + 2 < n) {
+                    const int t2 = t - 2;
+                    apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                    san[par] = Sa[t2];
+                }
+                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
+                if (i + 1 < n) prep((S + 1) % D);
+            } else {
+                if (exch) {
+                    u64 x[kClNC];
+                    int e = -40000;
+#pragma unroll
+                    for (int j = 0; j < kClNC; ++j)
+                        if (j < ncol && lane + 64 * j < C) x[j] = xload(xs + lane + 64 * j);
+#pragma unroll
+                    for (int j = 0; j < kClNC; ++j)
+                        if (j < ncol && lane + 64 * j < C) {
+                            if (word_tag(x[j]) != tag)
+                                x[j] = poll_word(xs + lane + 64 * j, tag, a.spin_limit, dead);
+                            const float v = word_value(x[j]);
+                            if (v > 0.f) e = max(e, word_shift(x[j]) + float_exponent(v) + 1);
+                        }
+                    int dl = wave_max_dpp(e);
+                    if (dl < -30000) dl = 0;
+                    sig += dl;
+#pragma unroll
+                    for (int j = 0; j < kClNC; ++j)
+                        if (j < ncol && lane + 64 * j < C) {
+                            const int q = lane + 64 * j;
+                            const float v = __builtin_ldexpf(word_value(x[j]), word_shift(x[j]) - dl);
+                            b_s[(par ^ 1) * kClMaxC + q] = v;
+                            if (t >= mid && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)t * C + q] = v;
+                        }
+                    if (lane == 0) {
+                        ctl_s[par ^ 1] = sig;
+                        if (t >= mid && g.k == 0) Sb[t] = sig;
+                    }
+                }
+                if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[24] = 1;
+            }
+            if (exch) gstep += 1;
+            __syncthreads();
+        };
+
+        for (int i = 0;; ++i) {
+            if (i == 0 && comm) {
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) {
+                    const int q = lane + 64 * j;
+                    if (j < ncol && q < C && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)L * C + q] = 1.f;
+                }
+                if (lane == 0 && g.k == 0) Sb[L] = 0;
+            }
+            if (i == ph1) {
+                dead = ctl_s[24];
+                cluster_sync(a, g, ptag, dead, &ctl_s[24]);
+                ptag += 1;
+                float part = 0.f;
+                for (int q = tid; q < C; q += blockDim.x)
+                    part += ah[(size_t)mid * C + q] * bh[(size_t)mid * C + q];
+                const float tot = block_sum(part, red);
+                D2 = (double)(Sa[mid] + Sb[mid]) + (double)__log2f(tot);
+                if (GAMMA && !comm) {
+                    // forward vectors for the first two frames of the second half
+                    if (ph1 < n) {
+                        const int t0 = L - 1 - ph1;
+                        apre[ph1 & 1] = (lane < nrw) ? ah[(size_t)t0 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                        san[ph1 & 1] = Sa[t0];
+                    }
+                    if (ph1 + 1 < n) {
+                        const int t1 = L - 2 - ph1;
+                        apre[(ph1 + 1) & 1] = (lane < nrw) ? ah[(size_t)t1 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                        san[(ph1 + 1) & 1] = Sa[t1];
+                    }
+                }
+                __syncthreads();
+            }
+            if (i >= n) break;
+            switch (i % D) {
+            case 0: body(std::integral_constant<int, 0>(), i); break;
+            case 1: body(std::integral_constant<int, 1>(), i); break;
+            case 2: body(std::integral_constant<int, 2>(), i); break;
+            default: if constexpr (D > 3) body(std::integral_constant<int, 3>(), i); break;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Zero the marginals of frames t >= len (they do not exist) and of items with
+// an invalid length; the 2K workgroups of a cluster share the work.
+__device__ __forceinline__ void cluster_zero_padding(const ClusterArgs& a, const ClusterGeom& g)
+{
+    const int nwg = 2 * a.K, me = g.role * a.K + g.k;
+    const size_t fr = (size_t)a.C * a.C;
+    for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
+        int L = a.len[b];
+        if (L < 0 || L > a.T) L = 0;
+        float* p = a.dw + ((size_t)b * a.T + L) * fr;
+        const size_t cnt = (size_t)(a.T - L) * fr;
+        for (size_t i = (size_t)me * blockDim.x + threadIdx.x; i < cnt; i += (size_t)nwg * blockDim.x)
+            __builtin_nontemporal_store(0.f, p + i);
+    }
+}
+
+template <int D, bool GAMMA>
+__global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
+{
+    __shared__ float smem[2 * kClMaxR * 2 + 2 * kClMaxC + 48 + 32 + 64];
+    ClusterGeom g;
+    const int id = blockIdx.x;
+    const int x = id & 7, slot = id >> 3;
+    const int cl = slot / (2 * a.K), member = slot - cl * 2 * a.K;
+    g.cg = x + 8 * cl;
+    g.role = member / a.K;
+    g.k = member - g.role * a.K;
+    g.r0 = g.k * a.RPW;
+    g.nr = min(a.RPW, a.C - g.r0);
+    if (g.nr < 0) g.nr = 0;
+    if (g.r0 > a.C) g.r0 = a.C;
+    unsigned gstep = 0, ptag = 0;
+    if (GAMMA && !a.accumulate) cluster_zero_padding(a, g);
+    if (g.role == 0) alpha_role<D, GAMMA>(a, g, smem, gstep, ptag);
+    else beta_role<D, GAMMA>(a, g, smem, gstep, ptag);
+}
+
+// set every exchange word to "invalid tag"
+__global__ void cluster_clear_kernel(u64* p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = ~0ull;
+}
+
+}  // namespace last

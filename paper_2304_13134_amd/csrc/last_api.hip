@@ -7,6 +7,10 @@
 #include "common.hpp"
 #include "solo_kernels.hpp"
 #include "numerator_kernels.hpp"
+#include "cluster_kernels.hpp"
+
+#include <cstdlib>
+#include <type_traits>
 
 using namespace last;
 
@@ -131,6 +135,80 @@ NumWs carve_num(Carver& cv, const Shape& s, int Umax)
     return p;
 }
 
+// geometry of the clustered bigram path (see cluster_kernels.hpp)
+struct ClusterPlan {
+    bool ok;
+    int K, RPW, ncl, XS, XSB, grid;
+};
+
+ClusterPlan cluster_plan(const Shape& s, int kind)
+{
+    ClusterPlan p{};
+    const char* force = std::getenv("LAST_FORCE_SOLO");
+    if (force && force[0] == '1') return p;
+    if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.T < 1) return p;
+    p.K = (s.C + 32) / 33;                   // at most 33 rows per workgroup
+    if (p.K > kClMaxK) return p;
+    p.RPW = (s.C + p.K - 1) / p.K;
+    if (s.C - (p.K - 1) * p.RPW < 1) return p;   // every workgroup must own at least one row
+    const int max_ncl = 32 / (2 * p.K);      // one workgroup per compute unit: 32 per XCD
+    if (max_ncl < 1) return p;
+    int want = (s.B + 7) / 8;
+    p.ncl = want < max_ncl ? want : max_ncl;
+    p.XS = (s.C + 1 + 15) / 16 * 16;
+    p.XSB = (s.C + 15) / 16 * 16;
+    p.grid = 8 * p.ncl * 2 * p.K;
+    p.ok = true;
+    return p;
+}
+
+struct ClusterWs {
+    float* ahat;
+    float* bhat;
+    int* Sa;
+    int* Sb;
+    u64* xa;
+    u64* xb;
+    u64* ph;
+    size_t xwords;
+};
+
+ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
+{
+    ClusterWs c;
+    const size_t st = (size_t)s.B * (s.T + 1);
+    c.ahat = cv.take<float>(st * s.C);
+    c.bhat = cv.take<float>(st * s.C);
+    c.Sa = cv.take<int>(st);
+    c.Sb = cv.take<int>(st);
+    const size_t ncl = (size_t)8 * p.ncl;
+    const size_t nxa = ncl * 2 * 2 * p.K * p.XS, nxb = ncl * 2 * p.XSB, nph = ncl * 32;
+    // one contiguous block so that a single launch clears all tags
+    c.xa = cv.take<u64>(nxa + nxb + nph);
+    c.xb = c.xa ? c.xa + nxa : nullptr;
+    c.ph = c.xb ? c.xb + nxb : nullptr;
+    c.xwords = nxa + nxb + nph;
+    return c;
+}
+
+template <bool GAMMA>
+void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, const float* w,
+                    const int* lengths, float* dist, int* item_status, float* dw, float scale,
+                    int accumulate, hipStream_t st)
+{
+    hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, c.xa, c.xwords);
+    ClusterArgs a;
+    a.w = w; a.len = lengths; a.dw = dw; a.dist = dist; a.item_status = item_status;
+    a.ahat = c.ahat; a.bhat = c.bhat; a.Sa = c.Sa; a.Sb = c.Sb;
+    a.xa = c.xa; a.xb = c.xb; a.ph = c.ph;
+    a.B = s.B; a.T = s.T; a.C = s.C;
+    a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
+    a.scale = scale; a.accumulate = accumulate;
+    a.spin_limit = 1 << 20;
+    hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA>), dim3(p.grid), dim3(kClThreads),
+                       0, st, a);
+}
+
 last_status_t check_ws(void* ws, size_t have, size_t need)
 {
     if (need == 0) return LAST_OK;
@@ -179,7 +257,8 @@ int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t*
 {
     Shape s;
     if (check_common(weights, context, &s) != LAST_OK) return -1;
-    (void)op;
+    if (op == LAST_OP_SHORTEST_DISTANCE || op == LAST_OP_ARC_POSTERIORS)
+        return cluster_plan(s, weights->kind).ok ? 1 : 0;
     return 0;
 }
 
@@ -189,12 +268,15 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
     Shape s;
     if (check_common(weights, context, &s) != LAST_OK) return 0;
     Carver cv(nullptr);
+    const ClusterPlan plan = cluster_plan(s, weights->kind);
     switch (op) {
     case LAST_OP_SHORTEST_DISTANCE:
-        cv.take<double>(1);
+        if (plan.ok) carve_cluster(cv, s, plan);
+        else cv.take<double>(1);
         break;
     case LAST_OP_ARC_POSTERIORS:
-        carve_posteriors(cv, s);
+        if (plan.ok) carve_cluster(cv, s, plan);
+        else carve_posteriors(cv, s);
         break;
     case LAST_OP_INTERSECT_REFERENCE:
         if (Umax < 0) return 0;
@@ -225,7 +307,12 @@ last_status_t last_shortest_distance(const last_weights_t* weights, const int32_
     hipStream_t st = (hipStream_t)hip_stream;
     const SoloLayout l = solo_layout(s);
     const Ctx c = make_ctx(s);
-    if (semiring == LAST_LOG) {
+    const ClusterPlan plan = cluster_plan(s, weights->kind);
+    if (semiring == LAST_LOG && plan.ok) {
+        Carver cv(ws);
+        const ClusterWs cw = carve_cluster(cv, s, plan);
+        launch_cluster<false>(s, plan, cw, weights->w, lengths, dist, item_status, nullptr, 1.f, 0, st);
+    } else if (semiring == LAST_LOG) {
         if (l.lds_forward > kMaxLds) return LAST_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
                            weights->w, lengths, c, s.T, l.CPAD, l.R,
@@ -253,6 +340,14 @@ last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* 
     rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0));
     if (rc != LAST_OK) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
+    const ClusterPlan plan = cluster_plan(s, weights->kind);
+    if (plan.ok) {
+        Carver cvc(ws);
+        const ClusterWs cw = carve_cluster(cvc, s, plan);
+        launch_cluster<true>(s, plan, cw, weights->w, lengths, dist, item_status, out->dw, out->scale,
+                             out->accumulate, st);
+        return hip_status();
+    }
     const SoloLayout l = solo_layout(s);
     if (l.lds_forward > kMaxLds) return LAST_ERR_UNSUPPORTED;
     const Ctx c = make_ctx(s);
