@@ -158,6 +158,31 @@ __device__ __forceinline__ int shift_for(float mx)        // integer s >= mx*log
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Streaming access through buffer descriptors: one descriptor per item (4 scalar registers),
+// a loop-invariant 32-bit per-thread byte offset and a scalar per-frame byte offset.  This keeps
+// the address arithmetic of the 17-20 loads per thread and frame out of the vector registers.
+typedef __amdgpu_buffer_rsrc_t buf_t;
+__device__ __forceinline__ buf_t make_buf(const void* p, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load_nt(buf_t r, unsigned voff, unsigned soff)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 2));
+}
+__device__ __forceinline__ void buf_store_nt(float v, buf_t r, unsigned voff, unsigned soff)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 2);
+}
+__device__ __forceinline__ float buf_load(buf_t r, unsigned voff, unsigned soff)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ void buf_store(float v, buf_t r, unsigned voff, unsigned soff)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
+}
+
 // poll one word until its tag matches; gives up after `limit` polls (dead = 1)
 __device__ __forceinline__ u64 poll_word(const u64* p, unsigned tag, int limit, int& dead)
 {
@@ -204,18 +229,34 @@ __device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const Cluster
     __threadfence();
 }
 
+// D at the meeting frame: (Sa_mid + Sb_mid) + log2 sum_q ahat_mid[q] bhat_mid[q], in units of ln 2.
+// Called by every thread of the workgroup (contains workgroup barriers).
+__device__ __forceinline__ double meeting_value(const float* ah, const float* bh, const int* Sa,
+                                                const int* Sb, int mid, int C, float* red)
+{
+    float part = 0.f;
+    for (int q = threadIdx.x; q < C; q += blockDim.x)
+        part += ah[(size_t)mid * C + q] * bh[(size_t)mid * C + q];
+    const float tot = block_sum(part, red);
+    return (double)(Sa[mid] + Sb[mid]) + (double)__log2f(tot);
+}
+
 // ------------------------------------------------------------------ alpha role
-template <int D, bool GAMMA>
+// LDS protocol (par = i & 1 is the parity of the state index i):
+//   ap_s[par][r]   partial-sum part of a_i for the workgroup's rows, already scaled by 2^-dl
+//   bl_s[par][r]   empty-label products a_i[r] * E_i[r][0] written during step i (for a_{i+1})
+//   ctl: [par] dl_{i-1}, [2 + 2 par + half] column-0 shift of step i, [6 + par] exponent of a_i,
+//        [8 + 16 par + wave] per-wave max column shift of frame i, [40] timeout flag
+//   a_i[r] = ap_s[par][r] + ldexp(bl_s[par^1][r], s0_{i-1} - dl_{i-1})
+template <int D, bool GAMMA, bool ACC>
 __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
-    // LDS carve
-    float* ap_s = smem;                       // [2][kClMaxR] partial-sum part of a_t
-    float* bl_s = ap_s + 2 * kClMaxR;         // [2][kClMaxR] empty-label products
-    float* bv_s = bl_s + 2 * kClMaxR;         // [2][kClMaxC] bhat_{t+1} staging (GAMMA)
-    // ctl: [0..1] dl, [2..5] s0[par][half], [6..7] sig, [8..39] hw[2][16], [40] dead
+    float* ap_s = smem;
+    float* bl_s = ap_s + 2 * kClMaxR;
+    float* bv_s = bl_s + 2 * kClMaxR;         // [2][kClMaxC] bhat_{i+1} staging (GAMMA)
     int* ctl_s = (int*)(bv_s + 2 * kClMaxC);
-    float* red = (float*)(ctl_s + 48);        // [32]
+    float* red = (float*)(ctl_s + 48);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, keep it scalar
     const bool comm = wave == kClWaves;
@@ -223,156 +264,77 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
     const int c = tid - half * kClHW * kWave; // column of a compute thread
     const int C = a.C, V1 = a.C;
     const bool colok = !comm && c < C;
+    const int rb = half * kClRT;              // first row (inside the workgroup) of this thread
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
         const bool bad = L < 0 || L > a.T;
         if (bad) L = 0;
         const int mid = L / 2;
-        const int n = GAMMA ? L : mid;               // iterations of this role
-        const int nex = GAMMA ? (L > 0 ? L - 1 : 0) : mid;   // iterations that exchange
+        const int n = GAMMA ? L : mid;                        // steps of this role
+        const int nex = GAMMA ? (L > 0 ? L - 1 : 0) : mid;    // steps that exchange
         const size_t fr = (size_t)C * V1;
-        const float* wb = a.w + (size_t)b * a.T * fr + (size_t)g.r0 * V1;
-        float* gb = GAMMA ? a.dw + (size_t)b * a.T * fr + (size_t)g.r0 * V1 : nullptr;
+        const unsigned frb = (unsigned)(fr * sizeof(float));  // bytes per frame
         float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
         const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
         int* Sa = a.Sa + (size_t)b * (a.T + 1);
         const int* Sb = a.Sb + (size_t)b * (a.T + 1);
         u64* xbase = a.xa + (size_t)g.cg * 2 * 2 * a.K * a.XS;
 
-        if (tid == 0) ctl_s[40] = 0;
-        // state 0: a_0 = unit vector at state 0, exponent 0; no empty-label carry-in
         if (tid < kClMaxR) {
             ap_s[tid] = (g.r0 + tid == 0 && tid < g.nr) ? 1.f : 0.f;
             ap_s[kClMaxR + tid] = 0.f;
             bl_s[tid] = 0.f;
             bl_s[kClMaxR + tid] = 0.f;
         }
-        if (tid == 0) { ctl_s[0] = 0; ctl_s[4] = kShiftNone; ctl_s[5] = kShiftNone; ctl_s[6] = 0; }
-        int dead = 0;
-        int sig = 0;          // comm wave: exponent of the current state vector
-        int m_own = (g.r0 == 0 && g.nr > 0) ? 0 : -127;
-        double D2 = 0.0;
-        float E[D][kClRT];
-        int sc[D];
-        const int rb = half * kClRT;          // first row (inside the workgroup) of this thread
-        float bcol[2] = {0.f, 0.f};
-        int sbn[2] = {0, 0};
-
-        // Byte offsets of this thread's elements inside a frame (the same for every frame and for
-        // the marginals, which share the layout of w): one scalar frame base + these per load.
-        // Rows beyond the owned range are clamped to the last owned row: their a-values are 0.
-        unsigned voff[kClRT];
-#pragma unroll
-        for (int r = 0; r < kClRT; ++r)
-            voff[r] = (unsigned)((min(rb + r, g.nr - 1) * V1 + c) * (int)sizeof(float));
-        const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
-        auto issue = [&](int slot, int f) __attribute__((always_inline)) {
-            const char* fb = (const char*)(wb + (size_t)f * fr);
-#pragma unroll
-            for (int r = 0; r < kClRT; ++r)
-                E[slot][r] = __builtin_nontemporal_load((const float*)(fb + voff[r]));
-        };
-        auto prep = [&](int slot) __attribute__((always_inline)) {
-            float mx = E[slot][0];
-#pragma unroll
-            for (int r = 1; r < kClRT; ++r) mx = fmaxf(mx, E[slot][r]);
-            const int s = shift_for(mx);
-            sc[slot] = s;
-            const float fs = (float)s;
-#pragma unroll
-            for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
-            return s;
-        };
-
-        if (colok) {
-#pragma unroll
-            for (int f = 0; f < D - 1; ++f)
-                if (f < n) issue(f, f);
-        }
-        __syncthreads();
-        int hcur = kShiftNone;   // compute waves: max column shift of the frame in slot 0
-        if (colok && n > 0) hcur = prep(0);
-        if (!comm) {
-            const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
-            if (lane == 0) ctl_s[8 + wave] = hw;
+        if (tid == 0) {
+            ctl_s[40] = 0; ctl_s[0] = 0; ctl_s[4] = kShiftNone; ctl_s[5] = kShiftNone; ctl_s[6] = 0;
         }
         __syncthreads();
 
-        auto body = [&](auto SLOT, int i) __attribute__((always_inline)) {
-            constexpr int S = decltype(SLOT)::value;
-            const int par = i & 1;
-            const bool exch = i < nex;
-            const unsigned tag = (gstep % 65535u);
-            u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
-            if (!comm) {
-                if (colok) {
-                    const int dl = ctl_s[par];
-                    const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
-                    float fac = 0.f;
-                    if (GAMMA && i >= mid) {
-                        const float kx = (float)((double)(ctl_s[6 + par] + sbn[par]) - D2);
-                        fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
+        if (comm) {
+            // ================= comm wave: exchange only =================
+            int dead = 0, sig = 0;
+            int m_own = (g.r0 == 0) ? 0 : -127;
+            __syncthreads();       // the compute waves have published the column shifts of frame 0
+            for (int i = 0;; ++i) {
+                const int par = i & 1;
+                // complete a_i, store it for the other side, take its magnitude
+                if (i == 0) {
+                    if (lane < g.nr) ah[g.r0 + lane] = (g.r0 + lane == 0) ? 1.f : 0.f;
+                    if (lane == 0 && g.k == 0) Sa[0] = 0;
+                } else if (i <= nex) {
+                    float av = 0.f;
+                    if (lane < g.nr)
+                        av = ap_s[par * kClMaxR + lane]
+                             + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + lane],
+                                                ctl_s[2 + (par ^ 1) * 2 + (lane >= kClRT ? 1 : 0)] - ctl_s[par]);
+                    m_own = wave_max_dpp((lane < g.nr) ? float_exponent(av) : -127);
+                    if (i <= mid) {
+                        if (lane < g.nr) ah[(size_t)i * C + g.r0 + lane] = av;
+                        if (lane == 0 && g.k == 0) Sa[i] = sig;
                     }
-                    float av[kClRT];
-                    float acc0 = 0.f, acc1 = 0.f;
-#pragma unroll
-                    for (int r = 0; r < kClRT; ++r) {
-                        av[r] = ap_s[par * kClMaxR + rb + r]
-                                + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
-                        if (r & 1) acc1 = fmaf(av[r], E[S][r], acc1);
-                        else acc0 = fmaf(av[r], E[S][r], acc0);
-                    }
-                    const float acc = acc0 + acc1;
-                    if (exch && c >= 1)
-                        xstore(xs + (size_t)(2 * g.k + half) * a.XS + c, pack_word(acc, sc[S], tag));
-                    if (c == 0) {
-#pragma unroll
-                        for (int r = 0; r < kClRT; ++r) bl_s[par * kClMaxR + rb + r] = av[r] * E[S][r];
-                        ctl_s[2 + par * 2 + half] = sc[S];
-                    }
-                    if (GAMMA && i >= mid) {
-                        char* gfb = (char*)(gb + (size_t)i * fr);
-                        // the empty label (column 0) returns to the row's own state
-                        auto gval = [&](int r) __attribute__((always_inline)) {
-                            const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + min(rb + r, g.nr - 1)] : fac;
-                            return av[r] * E[S][r] * f2;
-                        };
-                        if (a.accumulate) {
-#pragma unroll
-                            for (int r = 0; r < kClRT; ++r)
-                                if (r < nrt) *(float*)(gfb + voff[r]) += gval(r);
-                        } else if (nrt == kClRT) {
-#pragma unroll
-                            for (int r = 0; r < kClRT; ++r)
-                                __builtin_nontemporal_store(gval(r), (float*)(gfb + voff[r]));
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < kClRT; ++r)
-                                if (r < nrt) __builtin_nontemporal_store(gval(r), (float*)(gfb + voff[r]));
-                        }
-                    }
-                    // state vectors of the other side for the marginals two frames ahead
-                    if (GAMMA && i >= mid && i + 2 < n) {
-                        bcol[par] = bh[(size_t)(i + 3) * C + c];
-                        sbn[par] = Sb[i + 3];
-                    }
-                    if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
-                    if (i + 1 < n) hcur = prep((S + 1) % D);
-                    if (GAMMA && i + 1 < n && i + 1 >= mid) bv_s[(par ^ 1) * kClMaxC + c] = bcol[par ^ 1];
                 }
-                if (i + 1 < n) {
-                    const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
-                    if (lane == 0) ctl_s[8 + (par ^ 1) * 16 + wave] = hw;
+                if (i == mid) {
+                    if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
+                    cluster_sync(a, g, ptag, dead, &ctl_s[40]);
+                    ptag += 1;
+                    const double D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                    if (g.k == 0 && lane == 0) {
+                        a.dist[b] = bad ? __builtin_nanf("") : (float)(D2 * 0.6931471805599453);
+                        if (a.item_status)
+                            a.item_status[b] = bad ? kItemBadLength : (dead ? kItemTimeout : kItemOk);
+                    }
+                    __syncthreads();
                 }
-            } else {
-                // ---- comm wave: header, then gather the partial sums for the own states
-                if (exch) {
+                if (i >= n) break;
+                if (i < nex) {
+                    const unsigned tag = gstep % 65535u;
+                    u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
                     int h = kShiftNone;
                     if (lane < kClWaves) h = ctl_s[8 + par * 16 + lane];
                     h = wave_max_dpp(h);
                     if (lane == 0) xstore(xs + (size_t)(2 * g.k) * a.XS + C, pack_header(h, m_own, tag));
-                    // headers of all workgroups of the role
                     int hh = kShiftNone, mm = -127;
                     if (lane < a.K) {
                         const u64 x = poll_word(xs + (size_t)(2 * lane) * a.XS + C, tag, a.spin_limit, dead);
@@ -383,98 +345,170 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     float v = 0.f;
                     // only the empty label enters the start state: no partial sums exist for q = 0
                     if (lane < g.nr && g.r0 + lane != 0) {
-                        u64 x[2 * kClMaxK];
-#pragma unroll
-                        for (int j = 0; j < 2 * kClMaxK; ++j)
-                            if (j < 2 * a.K) x[j] = xload(xs + (size_t)j * a.XS + g.r0 + lane);
-#pragma unroll
-                        for (int j = 0; j < 2 * kClMaxK; ++j)
-                            if (j < 2 * a.K) {
-                                if (word_tag(x[j]) != tag)
-                                    x[j] = poll_word(xs + (size_t)j * a.XS + g.r0 + lane, tag, a.spin_limit, dead);
-                                v += __builtin_ldexpf(word_value(x[j]), word_shift(x[j]) - dl);
-                            }
+                        const u64* xp = xs + g.r0 + lane;
+                        for (int j = 0; j < 2 * a.K; ++j) {
+                            const u64 x = poll_word(xp + (size_t)j * a.XS, tag, a.spin_limit, dead);
+                            v += __builtin_ldexpf(word_value(x), word_shift(x) - dl);
+                        }
                     }
                     if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v;
                     sig += dl;
                     if (lane == 0) { ctl_s[par ^ 1] = dl; ctl_s[6 + (par ^ 1)] = sig; }
-                }
-                if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
-            }
-            if (exch) gstep += 1;
-            __syncthreads();
-            // ---- top of state i+1: the comm wave completes the vector, stores it, takes its magnitude
-            if (comm && exch) {
-                const int p1 = par ^ 1;
-                float av = 0.f;
-                if (lane < g.nr)
-                    av = ap_s[p1 * kClMaxR + lane]
-                         + __builtin_ldexpf(bl_s[par * kClMaxR + lane],
-                                            ctl_s[2 + par * 2 + (lane >= kClRT ? 1 : 0)] - ctl_s[p1]);
-                int e = (lane < g.nr) ? float_exponent(av) : -127;
-                m_own = wave_max_dpp(e);
-                if (i + 1 <= mid) {
-                    if (lane < g.nr) ah[(size_t)(i + 1) * C + g.r0 + lane] = av;
-                    if (lane == 0 && g.k == 0) Sa[i + 1] = sig;
-                }
-            }
-        };
-
-        for (int i = 0;; ++i) {
-            if (i == 0 && comm) {
-                if (lane < g.nr) ah[g.r0 + lane] = (g.r0 + lane == 0) ? 1.f : 0.f;
-                if (lane == 0 && g.k == 0) Sa[0] = 0;
-            }
-            if (i == mid) {
-                dead = ctl_s[40];
-                cluster_sync(a, g, ptag, dead, &ctl_s[40]);
-                ptag += 1;
-                // D = (Sa_mid + Sb_mid) ln 2 + log sum_q ahat_mid[q] bhat_mid[q]
-                float part = 0.f;
-                for (int q = tid; q < C; q += blockDim.x)
-                    part += ah[(size_t)mid * C + q] * bh[(size_t)mid * C + q];
-                const float tot = block_sum(part, red);
-                D2 = (double)(Sa[mid] + Sb[mid]) + (double)__log2f(tot);
-                if (bad) D2 = __builtin_nan("");
-                if (g.k == 0 && tid == 0) {
-                    a.dist[b] = (float)(D2 * 0.6931471805599453);
-                    if (a.item_status) a.item_status[b] = bad ? kItemBadLength : (dead ? kItemTimeout : kItemOk);
-                }
-                if (GAMMA && colok) {
-                    // first two frames of the second half: fetch the other side's vectors now
-                    if (mid < n) { bcol[mid & 1] = bh[(size_t)(mid + 1) * C + c]; sbn[mid & 1] = Sb[mid + 1]; }
-                    if (mid + 1 < n) { bcol[(mid + 1) & 1] = bh[(size_t)(mid + 2) * C + c]; sbn[(mid + 1) & 1] = Sb[mid + 2]; }
-                    if (mid < n) bv_s[(mid & 1) * kClMaxC + c] = bcol[mid & 1];
+                    gstep += 1;
                 }
                 __syncthreads();
             }
-            if (i >= n) break;
-            switch (i % D) {
-            case 0: body(std::integral_constant<int, 0>(), i); break;
-            case 1: body(std::integral_constant<int, 1>(), i); break;
-            case 2: body(std::integral_constant<int, 2>(), i); break;
-            default: if constexpr (D > 3) body(std::integral_constant<int, 3>(), i); break;
+            if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0 && g.k == 0 && a.item_status && !bad)
+                a.item_status[b] = kItemTimeout;
+        } else {
+            // ================= compute waves =================
+            const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+            const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+            // Byte offsets of this thread's elements inside a frame (the same for every frame and
+            // for the marginals, which share the layout of w).  Rows beyond the owned range are
+            // clamped to the last owned row: their a-values are 0.
+            const unsigned coff = (unsigned)(min(c, C - 1) * (int)sizeof(float));     // per thread
+            const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
+            auto roff = [&](int r) __attribute__((always_inline)) {               // scalar
+                return (unsigned)(g.r0 + min(rb + r, g.nr - 1)) * pitch;
+            };
+            const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
+            float E[D][kClRT];
+            int sc[D];
+            float bcol[2] = {0.f, 0.f};
+            int sbn[2] = {0, 0};
+            double D2 = 0.0;
+            int hcur = kShiftNone;
+
+            auto issue = [&](int slot, int f) __attribute__((always_inline)) {
+#pragma unroll
+                for (int r = 0; r < kClRT; ++r) E[slot][r] = buf_load_nt(wrs, coff, (unsigned)f * frb + roff(r));
+            };
+            auto prep = [&](int slot) __attribute__((always_inline)) {
+                float mx = E[slot][0];
+#pragma unroll
+                for (int r = 1; r < kClRT; ++r) mx = fmaxf(mx, E[slot][r]);
+                const int s = shift_for(mx);
+                sc[slot] = s;
+                const float fs = (float)s;
+#pragma unroll
+                for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
+                return s;
+            };
+#pragma unroll
+            for (int f = 0; f < D - 1; ++f)
+                if (f < n) issue(f, f);
+            if (n > 0) hcur = prep(0);
+            {
+                const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
+                if (lane == 0) ctl_s[8 + wave] = hw;
+            }
+            __syncthreads();       // frame 0 is prepared: its column shifts are visible to the comm wave
+
+            int i = 0;
+            auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
+                constexpr int S = decltype(SLOT)::value;
+                const int par = i & 1;
+                if (i == mid) {
+                    int dead = 0;
+                    cluster_sync(a, g, ptag, dead, &ctl_s[40]);
+                    ptag += 1;
+                    D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                    if (GAMMA && colok) {
+                        // first two frames of the second half: fetch the other side's vectors now
+                        if (mid < n) { bcol[mid & 1] = bh[(size_t)(mid + 1) * C + c]; sbn[mid & 1] = Sb[mid + 1]; }
+                        if (mid + 1 < n) { bcol[(mid + 1) & 1] = bh[(size_t)(mid + 2) * C + c]; sbn[(mid + 1) & 1] = Sb[mid + 2]; }
+                        if (mid < n) bv_s[(mid & 1) * kClMaxC + c] = bcol[mid & 1];
+                    }
+                    __syncthreads();
+                }
+                if (i >= n) return false;
+                const bool exch = i < nex;
+                const unsigned tag = gstep % 65535u;
+                u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
+                const int dl = ctl_s[par];
+                const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
+                float av[kClRT];
+                float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+                for (int r = 0; r < kClRT; ++r) {
+                    av[r] = ap_s[par * kClMaxR + rb + r]
+                            + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
+                    if (r & 1) acc1 = fmaf(av[r], E[S][r], acc1);
+                    else acc0 = fmaf(av[r], E[S][r], acc0);
+                }
+                const float acc = acc0 + acc1;
+                if (exch && colok && c >= 1)
+                    xstore(xs + (size_t)(2 * g.k + half) * a.XS + c, pack_word(acc, sc[S], tag));
+                if (c == 0) {
+#pragma unroll
+                    for (int r = 0; r < kClRT; ++r) bl_s[par * kClMaxR + rb + r] = av[r] * E[S][r];
+                    ctl_s[2 + par * 2 + half] = sc[S];
+                }
+                if (GAMMA && i >= mid && colok) {
+                    const float kx = (float)((double)(ctl_s[6 + par] + sbn[par]) - D2);
+                    const float fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
+                    const unsigned gso = (unsigned)i * frb;
+                    // the empty label (column 0) returns to the row's own state
+                    auto gval = [&](int r) __attribute__((always_inline)) {
+                        const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + min(rb + r, g.nr - 1)] : fac;
+                        return av[r] * E[S][r] * f2;
+                    };
+                    if (ACC) {
+#pragma unroll
+                        for (int r = 0; r < kClRT; ++r)
+                            if (r < nrt) buf_store(buf_load(grs, coff, gso + roff(r)) + gval(r), grs, coff, gso + roff(r));
+                    } else if (nrt == kClRT) {
+#pragma unroll
+                        for (int r = 0; r < kClRT; ++r) buf_store_nt(gval(r), grs, coff, gso + roff(r));
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < kClRT; ++r)
+                            if (r < nrt) buf_store_nt(gval(r), grs, coff, gso + roff(r));
+                    }
+                }
+                // state vectors of the other side for the marginals two frames ahead
+                if (GAMMA && i >= mid && i + 2 < n && colok) {
+                    bcol[par] = bh[(size_t)(i + 3) * C + c];
+                    sbn[par] = Sb[i + 3];
+                }
+                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
+                if (i + 1 < n) {
+                    hcur = prep((S + 1) % D);
+                    const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
+                    if (lane == 0) ctl_s[8 + (par ^ 1) * 16 + wave] = hw;
+                }
+                if (GAMMA && i + 1 < n && i + 1 >= mid && colok) bv_s[(par ^ 1) * kClMaxC + c] = bcol[par ^ 1];
+                if (exch) gstep += 1;
+                __syncthreads();
+                ++i;
+                return true;
+            };
+            for (;;) {
+                if (!step(std::integral_constant<int, 0>())) break;
+                if (!step(std::integral_constant<int, 1>())) break;
+                if (!step(std::integral_constant<int, 2>())) break;
+                if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
             }
         }
-        __syncthreads();
-        if (g.k == 0 && tid == 0 && ctl_s[40] && a.item_status && !bad) a.item_status[b] = kItemTimeout;
         __syncthreads();
     }
 }
 
 // ------------------------------------------------------------------- beta role
-template <int D, bool GAMMA>
+// LDS: b_s[par][q] = b_{t+1} for all states (par = step parity), ctl[par] = its exponent.
+template <int D, bool GAMMA, bool ACC>
 __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                           unsigned& gstep, unsigned& ptag)
 {
-    float* b_s = smem;                        // [2][kClMaxC] b_{t+1} (all states)
-    int* ctl_s = (int*)(b_s + 2 * kClMaxC);   // [0..1] sigb, [24] dead
+    float* b_s = smem;                        // [2][kClMaxC]
+    int* ctl_s = (int*)(b_s + 2 * kClMaxC);   // [0..1] exponent, [24] timeout flag
     float* red = (float*)(ctl_s + 32);
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, keep it scalar
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool comm = wave == kClWaves;
     const int C = a.C, V1 = a.C;
-    // rows of this wave: wave, wave + 5, ... (index inside the workgroup's rows)
+    // rows of this wave: wave, wave + 10, ... (index inside the workgroup's rows)
     int nrw = 0;
     if (!comm) nrw = (g.nr - wave + kClWaves - 1) / kClWaves;
     if (nrw < 0) nrw = 0;
@@ -488,10 +522,9 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
         const int n = GAMMA ? L : L - mid;
         // the last frame's result is not needed, except that b_mid must exist (L = 1: mid = 0)
         const int nex = GAMMA ? max(L - 1, L - mid) : L - mid;
-        const int ph1 = L - mid;                     // iteration at which state index reaches mid
+        const int ph1 = L - mid;                     // step at which the state index reaches mid
         const size_t fr = (size_t)C * V1;
-        const float* wb = a.w + (size_t)b * a.T * fr + (size_t)g.r0 * V1;
-        float* gb = GAMMA ? a.dw + (size_t)b * a.T * fr + (size_t)g.r0 * V1 : nullptr;
+        const unsigned frb = (unsigned)(fr * sizeof(float));
         const float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
         float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
         const int* Sa = a.Sa + (size_t)b * (a.T + 1);
@@ -499,122 +532,41 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
         u64* xbase = a.xb + (size_t)g.cg * 2 * a.XSB;
 
         if (tid == 0) { ctl_s[24] = 0; ctl_s[0] = 0; }
-        for (int q = tid; q < C; q += blockDim.x) b_s[q] = 1.f;
-        int dead = 0;
-        int sig = 0;
-        double D2 = 0.0;
-        float E[D][kClRW][kClNC];
-        int sr[D][kClRW];
-        float apre[2] = {0.f, 0.f};   // lane ri < nrw holds ahat_t[row ri] two frames ahead
-        int san[2] = {0, 0};
-
-        // Byte offsets of this lane's elements inside a frame (shared by w and the marginals).
-        // Rows / columns beyond the valid range are clamped: such rows are never published or
-        // stored, such columns meet a zero in the b vector.
-        unsigned voff[kClRW][kClNC];
-#pragma unroll
-        for (int ri = 0; ri < kClRW; ++ri)
-#pragma unroll
-            for (int j = 0; j < kClNC; ++j)
-                voff[ri][j] = (unsigned)((min(wave + ri * kClWaves, g.nr - 1) * V1 + min(lane + 64 * j, C - 1))
-                                         * (int)sizeof(float));
-        auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
-            const char* fb = (const char*)(wb + (size_t)(L - 1 - f) * fr);
-#pragma unroll
-            for (int ri = 0; ri < kClRW; ++ri)
-#pragma unroll
-                for (int j = 0; j < kClNC; ++j)
-                    E[slot][ri][j] = __builtin_nontemporal_load((const float*)(fb + voff[ri][j]));
-        };
-        auto prep = [&](int slot) __attribute__((always_inline)) {
-#pragma unroll
-            for (int ri = 0; ri < kClRW; ++ri) {
-                float mx = E[slot][ri][0];
-#pragma unroll
-                for (int j = 1; j < kClNC; ++j) mx = fmaxf(mx, E[slot][ri][j]);
-                mx = wave_max_dpp(mx);
-                const int s = shift_for(mx);
-                sr[slot][ri] = s;
-                const float fs = (float)s;
-#pragma unroll
-                for (int j = 0; j < kClNC; ++j)
-                    E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
-            }
-        };
-
-        if (!comm) {
-#pragma unroll
-            for (int f = 0; f < D - 1; ++f)
-                if (f < n) issue(f, f);
-            if (n > 0) prep(0);
-        }
+        // both slots: entries for columns >= C stay 0 for the whole item (clamped loads meet them)
+        for (int q = tid; q < 2 * kClMaxC; q += blockDim.x) b_s[q] = q < C ? 1.f : 0.f;
         __syncthreads();
 
-        auto body = [&](auto SLOT, int i) __attribute__((always_inline)) {
-            constexpr int S = decltype(SLOT)::value;
-            const int par = i & 1;
-            const int t = L - 1 - i;
-            const bool exch = i < nex;
-            const unsigned tag = (gstep % 65535u);
-            u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
-            if (!comm) {
-                float bv[kClNC];
+        if (comm) {
+            // ================= comm wave =================
+            int dead = 0, sig = 0;
+            for (int i = 0;; ++i) {
+                const int par = i & 1;
+                const int t = L - 1 - i;
+                if (i == 0) {
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j)
-                    bv[j] = (j < ncol && lane + 64 * j < C) ? b_s[par * kClMaxC + lane + 64 * j] : 0.f;
-                float kx = 0.f;
-                if (GAMMA && i >= ph1) kx = (float)((double)(san[par] + ctl_s[par]) - D2);
-#pragma unroll
-                for (int ri = 0; ri < kClRW; ++ri) {
-                    const int row = g.r0 + min(wave + ri * kClWaves, g.nr - 1);
-                    const float brow = b_s[par * kClMaxC + row];
-                    // the empty label (column 0) returns to the row's own state
-                    float acc = E[S][ri][0] * (lane == 0 ? brow : bv[0]);
-#pragma unroll
-                    for (int j = 1; j < kClNC; ++j) acc = fmaf(E[S][ri][j], bv[j], acc);
-                    const float tot = wave_sum_dpp(acc);
-                    if (exch && lane == 0 && ri < nrw) xstore(xs + row, pack_word(tot, sr[S][ri], tag));
+                    for (int j = 0; j < kClNC; ++j) {
+                        const int q = lane + 64 * j;
+                        if (q < C && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)L * C + q] = 1.f;
+                    }
+                    if (lane == 0 && g.k == 0) Sb[L] = 0;
                 }
-                if (GAMMA && i >= ph1) {
-                    char* gfb = (char*)(gb + (size_t)t * fr);
-#pragma unroll
-                    for (int ri = 0; ri < kClRW; ++ri)
-                        if (ri < nrw) {
-                            const int row = g.r0 + wave + ri * kClWaves;
-                            const float brow = b_s[par * kClMaxC + row];
-                            const float arow = __shfl(apre[par], ri, 64);
-                            const float fac = a.scale * arow * fast_exp2(kx + (float)sr[S][ri]);
-#pragma unroll
-                            for (int j = 0; j < kClNC; ++j)
-                                if (j < ncol && lane + 64 * j < C) {
-                                    const float bb = (j == 0 && lane == 0) ? brow : bv[j];
-                                    const float gv = E[S][ri][j] * bb * fac;
-                                    float* gp = (float*)(gfb + voff[ri][j]);
-                                    if (a.accumulate) *gp += gv;
-                                    else __builtin_nontemporal_store(gv, gp);
-                                }
-                        }
+                if (i == ph1) {
+                    if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[24] = 1;
+                    cluster_sync(a, g, ptag, dead, &ctl_s[24]);
+                    ptag += 1;
+                    (void)meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                    __syncthreads();
                 }
-                // forward vector of the frame two steps ahead (second half only)
-                if (GAMMA && i >= ph1 && i + 2 < n) {
-                    const int t2 = t - 2;
-                    apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
-                    san[par] = Sa[t2];
-                }
-                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
-                if (i + 1 < n) prep((S + 1) % D);
-            } else {
-                if (exch) {
+                if (i >= n) break;
+                if (i < nex) {
+                    const unsigned tag = gstep % 65535u;
+                    u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
                     u64 x[kClNC];
                     int e = -40000;
 #pragma unroll
                     for (int j = 0; j < kClNC; ++j)
-                        if (j < ncol && lane + 64 * j < C) x[j] = xload(xs + lane + 64 * j);
-#pragma unroll
-                    for (int j = 0; j < kClNC; ++j)
                         if (j < ncol && lane + 64 * j < C) {
-                            if (word_tag(x[j]) != tag)
-                                x[j] = poll_word(xs + lane + 64 * j, tag, a.spin_limit, dead);
+                            x[j] = poll_word(xs + lane + 64 * j, tag, a.spin_limit, dead);
                             const float v = word_value(x[j]);
                             if (v > 0.f) e = max(e, word_shift(x[j]) + float_exponent(v) + 1);
                         }
@@ -633,52 +585,137 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                         ctl_s[par ^ 1] = sig;
                         if (t >= mid && g.k == 0) Sb[t] = sig;
                     }
-                }
-                if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[24] = 1;
-            }
-            if (exch) gstep += 1;
-            __syncthreads();
-        };
-
-        for (int i = 0;; ++i) {
-            if (i == 0 && comm) {
-#pragma unroll
-                for (int j = 0; j < kClNC; ++j) {
-                    const int q = lane + 64 * j;
-                    if (j < ncol && q < C && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)L * C + q] = 1.f;
-                }
-                if (lane == 0 && g.k == 0) Sb[L] = 0;
-            }
-            if (i == ph1) {
-                dead = ctl_s[24];
-                cluster_sync(a, g, ptag, dead, &ctl_s[24]);
-                ptag += 1;
-                float part = 0.f;
-                for (int q = tid; q < C; q += blockDim.x)
-                    part += ah[(size_t)mid * C + q] * bh[(size_t)mid * C + q];
-                const float tot = block_sum(part, red);
-                D2 = (double)(Sa[mid] + Sb[mid]) + (double)__log2f(tot);
-                if (GAMMA && !comm) {
-                    // forward vectors for the first two frames of the second half
-                    if (ph1 < n) {
-                        const int t0 = L - 1 - ph1;
-                        apre[ph1 & 1] = (lane < nrw) ? ah[(size_t)t0 * C + g.r0 + wave + lane * kClWaves] : 0.f;
-                        san[ph1 & 1] = Sa[t0];
-                    }
-                    if (ph1 + 1 < n) {
-                        const int t1 = L - 2 - ph1;
-                        apre[(ph1 + 1) & 1] = (lane < nrw) ? ah[(size_t)t1 * C + g.r0 + wave + lane * kClWaves] : 0.f;
-                        san[(ph1 + 1) & 1] = Sa[t1];
-                    }
+                    gstep += 1;
                 }
                 __syncthreads();
             }
-            if (i >= n) break;
-            switch (i % D) {
-            case 0: body(std::integral_constant<int, 0>(), i); break;
-            case 1: body(std::integral_constant<int, 1>(), i); break;
-            case 2: body(std::integral_constant<int, 2>(), i); break;
-            default: if constexpr (D > 3) body(std::integral_constant<int, 3>(), i); break;
+        } else {
+            // ================= compute waves =================
+            const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+            const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+            // Byte offsets of this lane's elements inside a frame (shared by w and the marginals).
+            // Rows / columns beyond the valid range are clamped: such rows are never published or
+            // stored, such columns meet a zero in the b vector.
+            unsigned coff[kClNC];                                                    // per lane
+#pragma unroll
+            for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
+            const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
+            auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
+                return (unsigned)(g.r0 + min(wave + ri * kClWaves, g.nr - 1)) * pitch;
+            };
+            float E[D][kClRW][kClNC];
+            int sr[D][kClRW];
+            float apre[2] = {0.f, 0.f};   // lane ri < nrw holds ahat_t[row ri] two frames ahead
+            int san[2] = {0, 0};
+            double D2 = 0.0;
+
+            auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
+                const unsigned so = (unsigned)(L - 1 - f) * frb;
+#pragma unroll
+                for (int ri = 0; ri < kClRW; ++ri)
+#pragma unroll
+                    for (int j = 0; j < kClNC; ++j) E[slot][ri][j] = buf_load_nt(wrs, coff[j], so + roff(ri));
+            };
+            auto prep = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+                for (int ri = 0; ri < kClRW; ++ri) {
+                    float mx = E[slot][ri][0];
+#pragma unroll
+                    for (int j = 1; j < kClNC; ++j) mx = fmaxf(mx, E[slot][ri][j]);
+                    mx = wave_max_dpp(mx);
+                    const int s = shift_for(mx);
+                    sr[slot][ri] = s;
+                    const float fs = (float)s;
+#pragma unroll
+                    for (int j = 0; j < kClNC; ++j)
+                        E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
+                }
+            };
+#pragma unroll
+            for (int f = 0; f < D - 1; ++f)
+                if (f < n) issue(f, f);
+            if (n > 0) prep(0);
+
+            int i = 0;
+            auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
+                constexpr int S = decltype(SLOT)::value;
+                const int par = i & 1;
+                const int t = L - 1 - i;
+                if (i == ph1) {
+                    int dead = 0;
+                    cluster_sync(a, g, ptag, dead, &ctl_s[24]);
+                    ptag += 1;
+                    D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                    if (GAMMA) {
+                        // forward vectors for the first two frames of the second half
+                        if (ph1 < n) {
+                            const int t0 = L - 1 - ph1;
+                            apre[ph1 & 1] = (lane < nrw) ? ah[(size_t)t0 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                            san[ph1 & 1] = Sa[t0];
+                        }
+                        if (ph1 + 1 < n) {
+                            const int t1 = L - 2 - ph1;
+                            apre[(ph1 + 1) & 1] = (lane < nrw) ? ah[(size_t)t1 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                            san[(ph1 + 1) & 1] = Sa[t1];
+                        }
+                    }
+                    __syncthreads();
+                }
+                if (i >= n) return false;
+                const bool exch = i < nex;
+                const unsigned tag = gstep % 65535u;
+                u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
+                float bv[kClNC];
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) bv[j] = b_s[par * kClMaxC + lane + 64 * j];
+                float brow[kClRW];
+#pragma unroll
+                for (int ri = 0; ri < kClRW; ++ri) {
+                    const int row = g.r0 + min(wave + ri * kClWaves, g.nr - 1);
+                    brow[ri] = b_s[par * kClMaxC + row];
+                    // the empty label (column 0) returns to the row's own state
+                    float acc = E[S][ri][0] * (lane == 0 ? brow[ri] : bv[0]);
+#pragma unroll
+                    for (int j = 1; j < kClNC; ++j) acc = fmaf(E[S][ri][j], bv[j], acc);
+                    const float tot = wave_sum_dpp(acc);
+                    if (exch && lane == 0 && ri < nrw) xstore(xs + row, pack_word(tot, sr[S][ri], tag));
+                }
+                if (GAMMA && i >= ph1) {
+                    const float kx = (float)((double)(san[par] + ctl_s[par]) - D2);
+                    const unsigned gso = (unsigned)t * frb;
+#pragma unroll
+                    for (int ri = 0; ri < kClRW; ++ri)
+                        if (ri < nrw) {
+                            const float arow = __shfl(apre[par], ri, 64);
+                            const float fac = a.scale * arow * fast_exp2(kx + (float)sr[S][ri]);
+#pragma unroll
+                            for (int j = 0; j < kClNC; ++j)
+                                if (j < ncol && lane + 64 * j < C) {
+                                    const float bb = (j == 0 && lane == 0) ? brow[ri] : bv[j];
+                                    const float gv = E[S][ri][j] * bb * fac;
+                                    if (ACC) buf_store(buf_load(grs, coff[j], gso + roff(ri)) + gv, grs, coff[j], gso + roff(ri));
+                                    else buf_store_nt(gv, grs, coff[j], gso + roff(ri));
+                                }
+                        }
+                }
+                // forward vector of the frame two steps ahead (second half only)
+                if (GAMMA && i >= ph1 && i + 2 < n) {
+                    const int t2 = t - 2;
+                    apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                    san[par] = Sa[t2];
+                }
+                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
+                if (i + 1 < n) prep((S + 1) % D);
+                if (exch) gstep += 1;
+                __syncthreads();
+                ++i;
+                return true;
+            };
+            for (;;) {
+                if (!step(std::integral_constant<int, 0>())) break;
+                if (!step(std::integral_constant<int, 1>())) break;
+                if (!step(std::integral_constant<int, 2>())) break;
+                if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
             }
         }
         __syncthreads();
@@ -701,7 +738,7 @@ __device__ __forceinline__ void cluster_zero_padding(const ClusterArgs& a, const
     }
 }
 
-template <int D, bool GAMMA>
+template <int D, bool GAMMA, bool ACC>
 __global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
 {
     __shared__ float smem[2 * kClMaxR * 2 + 2 * kClMaxC + 48 + 32 + 64];
@@ -717,9 +754,9 @@ __global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
     if (g.nr < 0) g.nr = 0;
     if (g.r0 > a.C) g.r0 = a.C;
     unsigned gstep = 0, ptag = 0;
-    if (GAMMA && !a.accumulate) cluster_zero_padding(a, g);
-    if (g.role == 0) alpha_role<D, GAMMA>(a, g, smem, gstep, ptag);
-    else beta_role<D, GAMMA>(a, g, smem, gstep, ptag);
+    if (GAMMA && !ACC) cluster_zero_padding(a, g);
+    if (g.role == 0) alpha_role<D, GAMMA, ACC>(a, g, smem, gstep, ptag);
+    else beta_role<D, GAMMA, ACC>(a, g, smem, gstep, ptag);
 }
 
 // set every exchange word to "invalid tag"

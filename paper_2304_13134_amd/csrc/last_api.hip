@@ -147,6 +147,8 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     const char* force = std::getenv("LAST_FORCE_SOLO");
     if (force && force[0] == '1') return p;
     if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.T < 1) return p;
+    // one item must fit a 32-bit buffer descriptor
+    if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;
     p.K = (s.C + 32) / 33;                   // at most 33 rows per workgroup
     if (p.K > kClMaxK) return p;
     p.RPW = (s.C + p.K - 1) / p.K;
@@ -205,8 +207,12 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
     a.scale = scale; a.accumulate = accumulate;
     a.spin_limit = 1 << 20;
-    hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA>), dim3(p.grid), dim3(kClThreads),
-                       0, st, a);
+    if (GAMMA && accumulate)
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, true>), dim3(p.grid),
+                           dim3(kClThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, false>), dim3(p.grid),
+                           dim3(kClThreads), 0, st, a);
 }
 
 last_status_t check_ws(void* ws, size_t have, size_t need)
