@@ -54,10 +54,23 @@ constexpr int kClRW = 4;         // max rows per compute wave (beta): ceil(34 / 
 constexpr int kClNC = 5;         // max columns per lane (beta): ceil(320 / 64)
 constexpr int kClMaxC = 320;     // max number of states / labels on this path
 constexpr int kClThreads = (kClWaves + 1) * kWave;
-constexpr int kClMaxK = 10;      // max workgroups per role
+constexpr int kClMaxK = 8;       // max workgroups per role
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kShiftNone = -30000;
 constexpr unsigned kTagInvalid = 0xFFFFu;
+
+// Optional cycle-counter marks for tuning (compiled out unless LAST_TRACE is defined):
+// trace[((workgroup * 2 + is_comm) * 64 + step) * 4 + k] = clock of mark k
+#ifdef LAST_TRACE
+#define LAST_MARK(a, iscomm, step, k)                                                          \
+    do {                                                                                       \
+        if ((a).trace && (step) < 64 && (threadIdx.x & 63) == 0 &&                             \
+            ((iscomm) || threadIdx.x == 0))                                                    \
+            (a).trace[(((size_t)blockIdx.x * 2 + (iscomm)) * 64 + (step)) * 4 + (k)] = clock64(); \
+    } while (0)
+#else
+#define LAST_MARK(a, iscomm, step, k) do { } while (0)
+#endif
 
 struct ClusterArgs {
     const float* w;
@@ -69,7 +82,8 @@ struct ClusterArgs {
     float* bhat;   // [B][T+1][C] backward vectors (scaled), rows t >= mid
     int* Sa;       // [B][T+1] binary exponent of ahat rows
     int* Sb;       // [B][T+1]
-    u64* xa;       // [ncl_total][2][2K][XS] alpha partials of each half (+ header word at index C)
+    u64* xa;       // [ncl_total][2][XS][2K] alpha partials: row = destination (row C = headers),
+                   //                        column = producer half-workgroup
     u64* xb;       // [ncl_total][2][XSB]   beta values
     u64* ph;       // [ncl_total][32]       phase flags
     int B, T, C;
@@ -78,6 +92,9 @@ struct ClusterArgs {
     float scale;
     int accumulate;
     int spin_limit;
+#ifdef LAST_TRACE
+    unsigned long long* trace;
+#endif
 };
 
 // ---- cross-lane helpers on DPP (the critical path cannot afford LDS permutes)
@@ -197,6 +214,72 @@ __device__ __forceinline__ u64 poll_word(const u64* p, unsigned tag, int limit, 
     return x;
 }
 
+// Poll N words (those with want[j] set) until every tag matches.  All outstanding words are
+// re-read together in each round, so the wait costs one round trip after the last word lands
+// rather than one round trip per word.
+template <int N>
+__device__ __forceinline__ void poll_words(const u64* base, size_t stride, int count, u64 (&x)[N],
+                                           unsigned tag, int limit, int& dead)
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        if (j < count) x[j] = xload(base + j * stride);
+    if (dead) return;
+    int n = 0;
+    for (;;) {
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j < count && word_tag(x[j]) != tag) ok = false;
+        if (ok) break;
+        if (++n > limit) { dead = 1; break; }
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j < count && word_tag(x[j]) != tag) x[j] = xload(base + j * stride);
+    }
+}
+
+// Poll one row of 2*K consecutive words (16-byte aligned) with 16-byte loads: a destination's
+// partial sums from all producers sit in one cache line.  Volatile vector loads bypass the
+// vector L1; every 8-byte word was written by a single store, so it is read whole.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bool pair_ready(v4u v, unsigned tag)
+{
+    return (v.y >> 16) == tag && (v.w >> 16) == tag;
+}
+// sum of the 2*K partial values of a row, each scaled by 2^(shift - dl)
+template <int K>
+__device__ __forceinline__ float poll_row_sum(const u64* row, unsigned tag, int dl, int limit, int& dead)
+{
+    const volatile v4u* p = (const volatile v4u*)row;
+    v4u v[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j)
+        v[j] = p[j];
+    if (!dead) {
+        int n = 0;
+        for (;;) {
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < K; ++j)
+                if (!pair_ready(v[j], tag)) ok = false;
+            if (ok) break;
+            if (++n > limit) { dead = 1; break; }
+#pragma unroll
+            for (int j = 0; j < K; ++j)
+                if (!pair_ready(v[j], tag)) v[j] = p[j];
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < K; ++j)
+        {
+            s += __builtin_ldexpf(__uint_as_float(v[j].x), (int)(short)(v[j].y & 0xFFFFu) - dl);
+            s += __builtin_ldexpf(__uint_as_float(v[j].z), (int)(short)(v[j].w & 0xFFFFu) - dl);
+        }
+    return s;
+}
+
 struct ClusterGeom {
     int role;     // 0 alpha, 1 beta
     int k;        // workgroup index inside the role
@@ -248,7 +331,7 @@ __device__ __forceinline__ double meeting_value(const float* ah, const float* bh
 //   ctl: [par] dl_{i-1}, [2 + 2 par + half] column-0 shift of step i, [6 + par] exponent of a_i,
 //        [8 + 16 par + wave] per-wave max column shift of frame i, [40] timeout flag
 //   a_i[r] = ap_s[par][r] + ldexp(bl_s[par^1][r], s0_{i-1} - dl_{i-1})
-template <int D, bool GAMMA, bool ACC>
+template <int D, bool GAMMA, bool ACC, int KT>
 __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
@@ -279,7 +362,8 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
         const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
         int* Sa = a.Sa + (size_t)b * (a.T + 1);
         const int* Sb = a.Sb + (size_t)b * (a.T + 1);
-        u64* xbase = a.xa + (size_t)g.cg * 2 * 2 * a.K * a.XS;
+        constexpr int XK = 2 * KT;                                // words per row
+        u64* xbase = a.xa + (size_t)g.cg * 2 * a.XS * XK;
 
         if (tid < kClMaxR) {
             ap_s[tid] = (g.r0 + tid == 0 && tid < g.nr) ? 1.f : 0.f;
@@ -330,27 +414,26 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 if (i >= n) break;
                 if (i < nex) {
                     const unsigned tag = gstep % 65535u;
-                    u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
+                    u64* xs = xbase + (size_t)(gstep & 1) * a.XS * XK;
+                    LAST_MARK(a, 1, i, 0);
                     int h = kShiftNone;
                     if (lane < kClWaves) h = ctl_s[8 + par * 16 + lane];
                     h = wave_max_dpp(h);
-                    if (lane == 0) xstore(xs + (size_t)(2 * g.k) * a.XS + C, pack_header(h, m_own, tag));
+                    if (lane == 0) xstore(xs + (size_t)C * XK + 2 * g.k, pack_header(h, m_own, tag));
                     int hh = kShiftNone, mm = -127;
-                    if (lane < a.K) {
-                        const u64 x = poll_word(xs + (size_t)(2 * lane) * a.XS + C, tag, a.spin_limit, dead);
+                    if (lane < KT) {
+                        const u64 x = poll_word(xs + (size_t)C * XK + 2 * lane, tag, a.spin_limit, dead);
                         hh = header_h(x);
                         mm = header_m(x);
                     }
                     const int dl = wave_max_dpp(hh) + wave_max_dpp(mm);
+                    LAST_MARK(a, 1, i, 1);
                     float v = 0.f;
                     // only the empty label enters the start state: no partial sums exist for q = 0
                     if (lane < g.nr && g.r0 + lane != 0) {
-                        const u64* xp = xs + g.r0 + lane;
-                        for (int j = 0; j < 2 * a.K; ++j) {
-                            const u64 x = poll_word(xp + (size_t)j * a.XS, tag, a.spin_limit, dead);
-                            v += __builtin_ldexpf(word_value(x), word_shift(x) - dl);
-                        }
+                        v = poll_row_sum<KT>(xs + (size_t)(g.r0 + lane) * XK, tag, dl, a.spin_limit, dead);
                     }
+                    LAST_MARK(a, 1, i, 2);
                     if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v;
                     sig += dl;
                     if (lane == 0) { ctl_s[par ^ 1] = dl; ctl_s[6 + (par ^ 1)] = sig; }
@@ -369,9 +452,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             // clamped to the last owned row: their a-values are 0.
             const unsigned coff = (unsigned)(min(c, C - 1) * (int)sizeof(float));     // per thread
             const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
-            auto roff = [&](int r) __attribute__((always_inline)) {               // scalar
-                return (unsigned)(g.r0 + min(rb + r, g.nr - 1)) * pitch;
-            };
+            const unsigned rbase = (unsigned)(g.r0 + rb) * pitch;                    // scalar
             const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
             float E[D][kClRT];
             int sc[D];
@@ -380,14 +461,20 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             double D2 = 0.0;
             int hcur = kShiftNone;
 
+            // Rows beyond the owned range are read anyway (in bounds of the item, or answered
+            // with 0 by the buffer bounds check) and then forced to -inf, i.e. E = 0.
             auto issue = [&](int slot, int f) __attribute__((always_inline)) {
+                const unsigned fo = (unsigned)f * frb + rbase;
 #pragma unroll
-                for (int r = 0; r < kClRT; ++r) E[slot][r] = buf_load_nt(wrs, coff, (unsigned)f * frb + roff(r));
+                for (int r = 0; r < kClRT; ++r) E[slot][r] = buf_load_nt(wrs, coff, fo + (unsigned)r * pitch);
             };
             auto prep = [&](int slot) __attribute__((always_inline)) {
-                float mx = E[slot][0];
+                float mx = LAST_NEG_INF;
 #pragma unroll
-                for (int r = 1; r < kClRT; ++r) mx = fmaxf(mx, E[slot][r]);
+                for (int r = 0; r < kClRT; ++r) {
+                    if (r >= nrt) E[slot][r] = LAST_NEG_INF;
+                    mx = fmaxf(mx, E[slot][r]);
+                }
                 const int s = shift_for(mx);
                 sc[slot] = s;
                 const float fs = (float)s;
@@ -395,10 +482,13 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
                 return s;
             };
+            // Loads and the exp pass are unconditional (the frame index is clamped to the last
+            // frame of this role): conditional ones would leave registers "possibly pending" at
+            // control-flow joins and force full memory waits on the serial path.
+            const int nlast = max(n - 1, 0);
 #pragma unroll
-            for (int f = 0; f < D - 1; ++f)
-                if (f < n) issue(f, f);
-            if (n > 0) hcur = prep(0);
+            for (int f = 0; f < D - 1; ++f) issue(f, min(f, nlast));
+            hcur = prep(0);
             {
                 const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
                 if (lane == 0) ctl_s[8 + wave] = hw;
@@ -425,61 +515,55 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 if (i >= n) return false;
                 const bool exch = i < nex;
                 const unsigned tag = gstep % 65535u;
-                u64* xs = xbase + (size_t)(gstep & 1) * 2 * a.K * a.XS;
+                u64* xs = xbase + (size_t)(gstep & 1) * a.XS * XK;
+                LAST_MARK(a, 0, i, 0);
                 const int dl = ctl_s[par];
                 const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
-                float av[kClRT];
                 float acc0 = 0.f, acc1 = 0.f;
+                auto a_of = [&](int r) __attribute__((always_inline)) {        // a_i[rb + r]
+                    return ap_s[par * kClMaxR + rb + r]
+                           + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
+                };
 #pragma unroll
                 for (int r = 0; r < kClRT; ++r) {
-                    av[r] = ap_s[par * kClMaxR + rb + r]
-                            + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
-                    if (r & 1) acc1 = fmaf(av[r], E[S][r], acc1);
-                    else acc0 = fmaf(av[r], E[S][r], acc0);
+                    const float pr = a_of(r) * E[S][r];
+                    if (r & 1) acc1 += pr; else acc0 += pr;
+                    if (c == 0) bl_s[par * kClMaxR + rb + r] = pr;
                 }
                 const float acc = acc0 + acc1;
                 if (exch && colok && c >= 1)
-                    xstore(xs + (size_t)(2 * g.k + half) * a.XS + c, pack_word(acc, sc[S], tag));
-                if (c == 0) {
-#pragma unroll
-                    for (int r = 0; r < kClRT; ++r) bl_s[par * kClMaxR + rb + r] = av[r] * E[S][r];
-                    ctl_s[2 + par * 2 + half] = sc[S];
-                }
+                    xstore(xs + (size_t)c * XK + 2 * g.k + half, pack_word(acc, sc[S], tag));
+                if (c == 0) ctl_s[2 + par * 2 + half] = sc[S];
+                LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= mid && colok) {
                     const float kx = (float)((double)(ctl_s[6 + par] + sbn[par]) - D2);
                     const float fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
-                    const unsigned gso = (unsigned)i * frb;
-                    // the empty label (column 0) returns to the row's own state
-                    auto gval = [&](int r) __attribute__((always_inline)) {
-                        const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + min(rb + r, g.nr - 1)] : fac;
-                        return av[r] * E[S][r] * f2;
-                    };
-                    if (ACC) {
+                    const unsigned gso = (unsigned)i * frb + rbase;
 #pragma unroll
-                        for (int r = 0; r < kClRT; ++r)
-                            if (r < nrt) buf_store(buf_load(grs, coff, gso + roff(r)) + gval(r), grs, coff, gso + roff(r));
-                    } else if (nrt == kClRT) {
-#pragma unroll
-                        for (int r = 0; r < kClRT; ++r) buf_store_nt(gval(r), grs, coff, gso + roff(r));
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < kClRT; ++r)
-                            if (r < nrt) buf_store_nt(gval(r), grs, coff, gso + roff(r));
-                    }
+                    for (int r = 0; r < kClRT; ++r)
+                        if (r < nrt) {
+                            // the empty label (column 0) returns to the row's own state
+                            const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + rb + r] : fac;
+                            const float gv = a_of(r) * E[S][r] * f2;
+                            if (ACC) buf_store(buf_load(grs, coff, gso + (unsigned)r * pitch) + gv, grs, coff, gso + (unsigned)r * pitch);
+                            else buf_store_nt(gv, grs, coff, gso + (unsigned)r * pitch);
+                        }
                 }
                 // state vectors of the other side for the marginals two frames ahead
                 if (GAMMA && i >= mid && i + 2 < n && colok) {
                     bcol[par] = bh[(size_t)(i + 3) * C + c];
                     sbn[par] = Sb[i + 3];
                 }
-                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
-                if (i + 1 < n) {
+                issue((S + D - 1) % D, min(i + D - 1, nlast));
+                LAST_MARK(a, 0, i, 2);
+                {
                     hcur = prep((S + 1) % D);
                     const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
                     if (lane == 0) ctl_s[8 + (par ^ 1) * 16 + wave] = hw;
                 }
                 if (GAMMA && i + 1 < n && i + 1 >= mid && colok) bv_s[(par ^ 1) * kClMaxC + c] = bcol[par ^ 1];
                 if (exch) gstep += 1;
+                LAST_MARK(a, 0, i, 3);
                 __syncthreads();
                 ++i;
                 return true;
@@ -497,7 +581,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
 
 // ------------------------------------------------------------------- beta role
 // LDS: b_s[par][q] = b_{t+1} for all states (par = step parity), ctl[par] = its exponent.
-template <int D, bool GAMMA, bool ACC>
+template <int D, bool GAMMA, bool ACC, int KT>
 __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                           unsigned& gstep, unsigned& ptag)
 {
@@ -561,15 +645,19 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                 if (i < nex) {
                     const unsigned tag = gstep % 65535u;
                     u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
+                    LAST_MARK(a, 1, i, 0);
                     u64 x[kClNC];
                     int e = -40000;
+                    // lane l takes the words l, l + 64, ...: count of valid ones for this lane
+                    const int cnt = lane < C ? (C - 1 - lane) / 64 + 1 : 0;
+                    poll_words(xs + lane, (size_t)64, cnt, x, tag, a.spin_limit, dead);
 #pragma unroll
                     for (int j = 0; j < kClNC; ++j)
-                        if (j < ncol && lane + 64 * j < C) {
-                            x[j] = poll_word(xs + lane + 64 * j, tag, a.spin_limit, dead);
+                        if (j < cnt) {
                             const float v = word_value(x[j]);
                             if (v > 0.f) e = max(e, word_shift(x[j]) + float_exponent(v) + 1);
                         }
+                    LAST_MARK(a, 1, i, 1);
                     int dl = wave_max_dpp(e);
                     if (dl < -30000) dl = 0;
                     sig += dl;
@@ -585,6 +673,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                         ctl_s[par ^ 1] = sig;
                         if (t >= mid && g.k == 0) Sb[t] = sig;
                     }
+                    LAST_MARK(a, 1, i, 2);
                     gstep += 1;
                 }
                 __syncthreads();
@@ -610,7 +699,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
             double D2 = 0.0;
 
             auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
-                const unsigned so = (unsigned)(L - 1 - f) * frb;
+                const unsigned so = (unsigned)max(L - 1 - f, 0) * frb;
 #pragma unroll
                 for (int ri = 0; ri < kClRW; ++ri)
 #pragma unroll
@@ -631,10 +720,10 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                         E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
                 }
             };
+            const int nlast = max(n - 1, 0);     // see the alpha role: unconditional, clamped
 #pragma unroll
-            for (int f = 0; f < D - 1; ++f)
-                if (f < n) issue(f, f);
-            if (n > 0) prep(0);
+            for (int f = 0; f < D - 1; ++f) issue(f, min(f, nlast));
+            prep(0);
 
             int i = 0;
             auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
@@ -665,6 +754,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                 const bool exch = i < nex;
                 const unsigned tag = gstep % 65535u;
                 u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
+                LAST_MARK(a, 0, i, 0);
                 float bv[kClNC];
 #pragma unroll
                 for (int j = 0; j < kClNC; ++j) bv[j] = b_s[par * kClMaxC + lane + 64 * j];
@@ -680,6 +770,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     const float tot = wave_sum_dpp(acc);
                     if (exch && lane == 0 && ri < nrw) xstore(xs + row, pack_word(tot, sr[S][ri], tag));
                 }
+                LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= ph1) {
                     const float kx = (float)((double)(san[par] + ctl_s[par]) - D2);
                     const unsigned gso = (unsigned)t * frb;
@@ -704,9 +795,11 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
                     san[par] = Sa[t2];
                 }
-                if (i + D - 1 < n) issue((S + D - 1) % D, i + D - 1);
-                if (i + 1 < n) prep((S + 1) % D);
+                issue((S + D - 1) % D, min(i + D - 1, nlast));
+                LAST_MARK(a, 0, i, 2);
+                prep((S + 1) % D);
                 if (exch) gstep += 1;
+                LAST_MARK(a, 0, i, 3);
                 __syncthreads();
                 ++i;
                 return true;
@@ -738,7 +831,7 @@ __device__ __forceinline__ void cluster_zero_padding(const ClusterArgs& a, const
     }
 }
 
-template <int D, bool GAMMA, bool ACC>
+template <int D, bool GAMMA, bool ACC, int KT>
 __global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
 {
     __shared__ float smem[2 * kClMaxR * 2 + 2 * kClMaxC + 48 + 32 + 64];
@@ -755,8 +848,8 @@ __global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
     if (g.r0 > a.C) g.r0 = a.C;
     unsigned gstep = 0, ptag = 0;
     if (GAMMA && !ACC) cluster_zero_padding(a, g);
-    if (g.role == 0) alpha_role<D, GAMMA, ACC>(a, g, smem, gstep, ptag);
-    else beta_role<D, GAMMA, ACC>(a, g, smem, gstep, ptag);
+    if (g.role == 0) alpha_role<D, GAMMA, ACC, KT>(a, g, smem, gstep, ptag);
+    else beta_role<D, GAMMA, ACC, KT>(a, g, smem, gstep, ptag);
 }
 
 // set every exchange word to "invalid tag"

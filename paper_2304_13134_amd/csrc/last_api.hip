@@ -207,12 +207,25 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
     a.scale = scale; a.accumulate = accumulate;
     a.spin_limit = 1 << 20;
-    if (GAMMA && accumulate)
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, true>), dim3(p.grid),
-                           dim3(kClThreads), 0, st, a);
-    else
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, false>), dim3(p.grid),
-                           dim3(kClThreads), 0, st, a);
+    auto go = [&](auto KC) {
+        constexpr int KT = decltype(KC)::value;
+        if (GAMMA && accumulate)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, GAMMA, KT>), dim3(p.grid),
+                               dim3(kClThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster_fb_kernel<3, GAMMA, false, KT>), dim3(p.grid),
+                               dim3(kClThreads), 0, st, a);
+    };
+    switch (p.K) {
+    case 1: go(std::integral_constant<int, 1>()); break;
+    case 2: go(std::integral_constant<int, 2>()); break;
+    case 3: go(std::integral_constant<int, 3>()); break;
+    case 4: go(std::integral_constant<int, 4>()); break;
+    case 5: go(std::integral_constant<int, 5>()); break;
+    case 6: go(std::integral_constant<int, 6>()); break;
+    case 7: go(std::integral_constant<int, 7>()); break;
+    default: go(std::integral_constant<int, 8>()); break;
+    }
 }
 
 last_status_t check_ws(void* ws, size_t have, size_t need)
