@@ -420,21 +420,50 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     if (lane < kClWaves) h = ctl_s[8 + par * 16 + lane];
                     h = wave_max_dpp(h);
                     if (lane == 0) xstore(xs + (size_t)C * XK + 2 * g.k, pack_header(h, m_own, tag));
-                    int hh = kShiftNone, mm = -127;
-                    if (lane < KT) {
-                        const u64 x = poll_word(xs + (size_t)C * XK + 2 * lane, tag, a.spin_limit, dead);
-                        hh = header_h(x);
-                        mm = header_m(x);
+                    // one batch: this lane's row of partial sums (16-byte loads) and, on the first
+                    // KT lanes, one header word each; poll until every tag matches
+                    const bool wantrow = lane < g.nr && g.r0 + lane != 0;   // q = 0 has no partials
+                    const volatile v4u* rowp = (const volatile v4u*)(xs + (size_t)(g.r0 + (wantrow ? lane : 0)) * XK);
+                    const u64* hp = xs + (size_t)C * XK + 2 * (lane < KT ? lane : 0);
+                    v4u v[KT];
+                    u64 hx = 0;
+#pragma unroll
+                    for (int j = 0; j < KT; ++j) v[j] = rowp[j];
+                    hx = xload(hp);
+                    if (!dead) {
+                        int np = 0;
+                        for (;;) {
+                            bool ok = !(lane < KT) || word_tag(hx) == tag;
+                            if (wantrow) {
+#pragma unroll
+                                for (int j = 0; j < KT; ++j)
+                                    if (!pair_ready(v[j], tag)) ok = false;
+                            }
+                            if (ok) break;
+                            if (++np > a.spin_limit) { dead = 1; break; }
+                            if (lane < KT && word_tag(hx) != tag) hx = xload(hp);
+                            if (wantrow) {
+#pragma unroll
+                                for (int j = 0; j < KT; ++j)
+                                    if (!pair_ready(v[j], tag)) v[j] = rowp[j];
+                            }
+                        }
                     }
+                    // every lane must know all headers: wait for the slowest lane of the wave
+                    const int hh = lane < KT ? header_h(hx) : kShiftNone;
+                    const int mm = lane < KT ? header_m(hx) : -127;
                     const int dl = wave_max_dpp(hh) + wave_max_dpp(mm);
                     LAST_MARK(a, 1, i, 1);
-                    float v = 0.f;
-                    // only the empty label enters the start state: no partial sums exist for q = 0
-                    if (lane < g.nr && g.r0 + lane != 0) {
-                        v = poll_row_sum<KT>(xs + (size_t)(g.r0 + lane) * XK, tag, dl, a.spin_limit, dead);
+                    float v_sum = 0.f;
+                    if (wantrow) {
+#pragma unroll
+                        for (int j = 0; j < KT; ++j) {
+                            v_sum += __builtin_ldexpf(__uint_as_float(v[j].x), (int)(short)(v[j].y & 0xFFFFu) - dl);
+                            v_sum += __builtin_ldexpf(__uint_as_float(v[j].z), (int)(short)(v[j].w & 0xFFFFu) - dl);
+                        }
                     }
                     LAST_MARK(a, 1, i, 2);
-                    if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v;
+                    if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v_sum;
                     sig += dl;
                     if (lane == 0) { ctl_s[par ^ 1] = dl; ctl_s[6 + (par ^ 1)] = sig; }
                     gstep += 1;
@@ -517,6 +546,9 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 const unsigned tag = gstep % 65535u;
                 u64* xs = xbase + (size_t)(gstep & 1) * a.XS * XK;
                 LAST_MARK(a, 0, i, 0);
+                // Stream first: the vector memory pipeline returns in order, so loads issued later
+                // in the step would sit in front of the comm wave's next polls for longer.
+                issue((S + D - 1) % D, min(i + D - 1, nlast));
                 const int dl = ctl_s[par];
                 const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
                 float acc0 = 0.f, acc1 = 0.f;
@@ -554,7 +586,6 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     bcol[par] = bh[(size_t)(i + 3) * C + c];
                     sbn[par] = Sb[i + 3];
                 }
-                issue((S + D - 1) % D, min(i + D - 1, nlast));
                 LAST_MARK(a, 0, i, 2);
                 {
                     hcur = prep((S + 1) % D);
@@ -755,6 +786,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                 const unsigned tag = gstep % 65535u;
                 u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
                 LAST_MARK(a, 0, i, 0);
+                issue((S + D - 1) % D, min(i + D - 1, nlast));      // stream first (see the alpha role)
                 float bv[kClNC];
 #pragma unroll
                 for (int j = 0; j < kClNC; ++j) bv[j] = b_s[par * kClMaxC + lane + 64 * j];
@@ -795,7 +827,6 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
                     san[par] = Sa[t2];
                 }
-                issue((S + D - 1) % D, min(i + D - 1, nlast));
                 LAST_MARK(a, 0, i, 2);
                 prep((S + 1) % D);
                 if (exch) gstep += 1;

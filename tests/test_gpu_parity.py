@@ -203,3 +203,89 @@ def test_numerator_edge_cases():
     assert_dist_close(num[:2], o["N"])
     gnum = oracle.numerator_posteriors_dense(o, good["refs"], good["ref_lengths"], good["w"].shape)
     assert np.max(np.abs(dw.cpu().numpy()[:2] - gnum)) <= TOL_POST_ABS
+
+
+# ------------------------------------------------------------------ full sizes
+@pytest.fixture(scope="module")
+def config3_full():
+    """Configs 2 and 3 at full size (B=16, T=500, V=256): the lattice the benchmark times."""
+    announce("building config 3 (2.1 GB) and its oracle forward / backward weights")
+    cfg = workloads.config(3)
+    alpha, D = oracle.forward(cfg["w"], cfg["lengths"], 1)
+    beta = oracle.backward(cfg["w"], cfg["lengths"], 1)
+    return cfg, alpha, beta, D
+
+
+def test_config2_full_size_sampled_marginals_and_invariants(config3_full):
+    announce("config 2 full size: D, sampled marginals, per-frame sums")
+    cfg, alpha, beta, D_o = config3_full
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    st = torch.full((cfg["B"],), -1, dtype=torch.int32, device="cuda")
+    dist, dw = lb.last_arc_posteriors(w, lengths, item_status=st)
+    dist2 = lb.last_shortest_distance(w, lengths)
+    torch.cuda.synchronize()
+    assert torch.all(st == 0)
+    assert_dist_close(dist.cpu().numpy(), D_o)
+    assert_dist_close(dist2.cpu().numpy(), D_o)
+    # every frame's marginals sum to 1 (one arc per frame in a frame dependent lattice)
+    sums = dw.sum(dim=(2, 3), dtype=torch.float64).cpu().numpy()
+    assert np.max(np.abs(sums - 1.0)) < 1e-4
+    assert not torch.isnan(dw).any()
+    # 400k sampled arcs + the largest marginals, each checked against Eq. 1 one by one
+    rng = np.random.default_rng(11)
+    n = 400_000
+    idx = np.stack([rng.integers(0, cfg["B"], n), rng.integers(0, cfg["T"], n),
+                    rng.integers(0, cfg["C"], n), rng.integers(0, cfg["V"] + 1, n)], axis=1)
+    top = torch.topk(dw.view(-1), 20000).indices.cpu().numpy()
+    tidx = np.stack(np.unravel_index(top, cfg["w"].shape), axis=1)
+    idx = np.concatenate([idx, tidx])
+    want = oracle.posterior_samples(cfg["w"], cfg["lengths"], 1, alpha, beta, D_o, idx)
+    got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    assert np.max(np.abs(got - want)) <= TOL_POST_ABS
+    # frames 0 and 1: unreachable states carry exact zeros
+    assert torch.all(dw[:, 0, 1:, :] == 0)
+
+
+def test_config2_full_size_shortest_path(config3_full):
+    announce("config 2 full size: tropical shortest path, bit-exact indices")
+    cfg, _, _, _ = config3_full
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    labels, states, score = lb.last_shortest_path(w, lengths)
+    torch.cuda.synchronize()
+    l_o, s_o, sc_o = oracle.viterbi(cfg["w"], cfg["lengths"], 1, "f32")
+    assert np.array_equal(labels.cpu().numpy(), l_o)
+    assert np.array_equal(states.cpu().numpy(), s_o)
+    assert np.array_equal(score.cpu().numpy(), sc_o)
+
+
+def test_config3_full_size_loss_and_gradient(config3_full):
+    announce("config 3 full size: numerator, loss, gradient on the numerator's arcs")
+    cfg, alpha, beta, D_o = config3_full
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    refs, ulen = dev(cfg["refs"]), dev(cfg["ref_lengths"])
+    dist, dw = lb.last_arc_posteriors(w, lengths)
+    num = lb.last_intersect_reference(w, lengths, refs, ulen, dw=dw, scale=-1.0, accumulate=True)
+    torch.cuda.synchronize()
+    o = oracle.numerator(cfg["w"], cfg["lengths"], cfg["refs"], cfg["ref_lengths"], 1)
+    assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
+    assert np.all(o["N"] <= D_o)
+    # gradient on every arc the intersected lattice rides on, for two items
+    for b in (0, 9):
+        U = int(cfg["ref_lengths"][b])
+        T = cfg["T"]
+        gnum = {}
+        for u in range(U + 1):
+            q = int(o["ctx"][b, u])
+            for t in range(T):
+                gnum[(t, q, 0)] = gnum.get((t, q, 0), 0.0) + o["pb"][b, t, u]
+                if u < U:
+                    y = int(cfg["refs"][b, u])
+                    gnum[(t, q, y)] = gnum.get((t, q, y), 0.0) + o["pl"][b, t, u]
+        keys = np.array(list(gnum.keys()))
+        idx = np.concatenate([np.full((len(keys), 1), b), keys], axis=1)
+        den = oracle.posterior_samples(cfg["w"], cfg["lengths"], 1, alpha, beta, D_o, idx)
+        want = den - np.array(list(gnum.values()))
+        got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+        assert np.max(np.abs(got - want)) <= 2 * TOL_POST_ABS
+    sums = dw.sum(dim=(2, 3), dtype=torch.float64).cpu().numpy()
+    assert np.max(np.abs(sums)) < 1e-4                 # denominator and numerator marginals cancel
