@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run plain device copies of the weight tensor (known size) so that a "
+                         "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--B", type=int, default=16)
     ap.add_argument("--T", type=int, default=500)
     ap.add_argument("--V", type=int, default=256)
@@ -110,6 +113,11 @@ def main():
 
     def step():
         lb.last_arc_posteriors(w, lengths, order=1, dw=dw)
+
+    if args.pmc_calibration:
+        for _ in range(3):
+            dw.copy_(w)                 # reads and writes w.numel() * 4 bytes
+        torch.cuda.synchronize()
 
     ms, wall_ms = time_region(step, args.steps, args.warmup)
     value = arcs / (ms * 1e-3)

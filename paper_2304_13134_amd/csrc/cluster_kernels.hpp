@@ -18,25 +18,31 @@
 //
 // Work split inside a role: workgroup k owns the source states (rows)
 // [k*RPW, (k+1)*RPW) of every frame, a contiguous chunk of memory.
-//   alpha: thread <-> destination column; partial column sums over the own
-//          rows are exchanged (reduce-scatter: workgroup k only needs the
-//          sums for its own states);
+//   alpha: thread <-> destination column (two half-workgroups of 5 waves share
+//          the rows); partial column sums over the own rows are exchanged
+//          (reduce-scatter: workgroup k only needs the sums for its own states);
 //   beta : wavefront <-> row, lanes <-> columns; complete row sums are
 //          exchanged (all-gather).
 // Arithmetic is in the scaled linear domain: E = 2^(w*log2(e) - s) with an
 // integer shift s per column (alpha) or per row (beta) chosen from the data so
-// that E <= 1, state vectors carry a common integer exponent (Sa, Sb), and
-// partial results travel as (float value, int16 shift).  exp(w) does not depend
-// on the recursion, so it is evaluated while the previous step's exchange is in
-// flight; the serial chain per frame is: FMA loop, publish, poll, rescale.
+// that E <= 1; state vectors carry a common integer binary exponent (Sa, Sb)
+// that advances by a predicted amount P every step, P being derived from the
+// magnitudes seen one or two steps earlier so that all workgroups agree on it
+// without an extra round trip.  exp(w) does not depend on the recursion, so it
+// is evaluated while the previous step's exchange is in flight; the serial
+// chain per frame is: FMA loop, publish, poll, add.
 //
-// Exchange: 64-bit words [value:32 | shift:16 | tag:16] written and polled with
-// relaxed agent-scope atomics; the tag (a running step counter) makes each word
+// Exchange: 64-bit words [value:32 | tag:32] written with relaxed agent-scope
+// atomic stores; the tag (a running step counter) makes each word
 // self-validating, so no fences are needed on the per-frame path.  Two slots
 // (step parity) suffice: nobody can publish step s+2 before everybody has
-// consumed step s.  One wavefront per workgroup (the "comm" wave) does all
-// polling so that the streaming loads of the compute waves never sit in front
-// of a poll in the in-order load return queue.  Every poll loop is bounded.
+// consumed step s.  Words are polled through the SCALAR memory path (64-byte
+// scalar loads that bypass the scalar cache): the vector memory pipeline
+// returns loads in order, so a vector poll would queue behind the streaming
+// loads of the same compute unit, while the scalar path is independent of
+// them.  This needs the cluster on one XCD (one L2); if the placement ever
+// differs the polls time out and the item reports status 5 instead of a
+// wrong result.  Every poll loop is bounded.
 #pragma once
 #include <type_traits>
 
@@ -46,18 +52,20 @@ namespace last {
 
 typedef unsigned long long u64;
 
-constexpr int kClMaxR = 34;      // max rows owned by one workgroup (two halves of kClRT rows)
+constexpr int kClMaxR = 34;      // LDS row slots per workgroup (two halves of kClRT rows; <= 33 used)
 constexpr int kClRT = 17;        // rows per alpha thread: each workgroup splits its rows in two halves
 constexpr int kClHW = 5;         // compute waves per half (alpha): 5 * 64 >= kClMaxC columns
 constexpr int kClWaves = 10;     // compute waves per workgroup
 constexpr int kClRW = 4;         // max rows per compute wave (beta): ceil(34 / 10)
 constexpr int kClNC = 5;         // max columns per lane (beta): ceil(320 / 64)
-constexpr int kClMaxC = 320;     // max number of states / labels on this path
+constexpr int kClMaxC = 264;     // max number of states / labels on this path (11 waves x 24 words)
 constexpr int kClThreads = (kClWaves + 1) * kWave;
 constexpr int kClMaxK = 8;       // max workgroups per role
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kShiftNone = -30000;
-constexpr unsigned kTagInvalid = 0xFFFFu;
+constexpr int kClXK = 8;         // words per exchange row (alpha): one 64-byte scalar load
+constexpr int kClCH = 24;        // exchange words gathered per wave: three 64-byte scalar loads
+constexpr int kClLds = 2 * kClMaxR * 2 + 2 * 320 + 320 + 64 + 32 + 64;   // floats
 
 // Optional cycle-counter marks for tuning (compiled out unless LAST_TRACE is defined):
 // trace[((workgroup * 2 + is_comm) * 64 + step) * 4 + k] = clock of mark k
@@ -149,19 +157,14 @@ __device__ __forceinline__ void xstore(u64* p, u64 v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ u64 pack_word(float v, int shift, unsigned tag)
+__device__ __forceinline__ u64 pack_word(float v, unsigned tag)
 {
-    return (u64)__float_as_uint(v) | ((u64)(unsigned)(shift & 0xFFFF) << 32) | ((u64)(tag & 0xFFFFu) << 48);
+    return (u64)__float_as_uint(v) | ((u64)tag << 32);
 }
-__device__ __forceinline__ float word_value(u64 x) { return __uint_as_float((unsigned)x); }
-__device__ __forceinline__ int word_shift(u64 x) { return (int)(short)(unsigned short)(x >> 32); }
-__device__ __forceinline__ unsigned word_tag(u64 x) { return (unsigned)(x >> 48); }
-__device__ __forceinline__ u64 pack_header(int h, int m, unsigned tag)
+__device__ __forceinline__ u64 pack_int(int v, unsigned tag)
 {
-    return (u64)(unsigned)(h & 0xFFFF) | ((u64)(unsigned)(m & 0xFFFF) << 16) | ((u64)(tag & 0xFFFFu) << 48);
+    return (u64)(unsigned)v | ((u64)tag << 32);
 }
-__device__ __forceinline__ int header_h(u64 x) { return (int)(short)(unsigned short)x; }
-__device__ __forceinline__ int header_m(u64 x) { return (int)(short)(unsigned short)(x >> 16); }
 
 __device__ __forceinline__ int float_exponent(float x)   // floor(log2 x) for normal x > 0; -127 for 0
 {
@@ -200,83 +203,40 @@ __device__ __forceinline__ void buf_store(float v, buf_t r, unsigned voff, unsig
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
 }
 
-// poll one word until its tag matches; gives up after `limit` polls (dead = 1)
-__device__ __forceinline__ u64 poll_word(const u64* p, unsigned tag, int limit, int& dead)
+// ---- scalar-path gathers -------------------------------------------------------
+// Three (or four) 64-byte scalar loads that bypass the scalar cache, issued and
+// awaited inside one asm statement so that no compiler-generated code can touch
+// the destination registers while the loads are in flight.
+typedef unsigned v16u __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ void sgather3(const void* p, v16u& a, v16u& b, v16u& c)
 {
-    u64 x = xload(p);
-    if (dead) return x;
-    int n = 0;
-    while (word_tag(x) != tag) {
-        if (++n > limit) { dead = 1; break; }
-        __builtin_amdgcn_s_sleep(1);
-        x = xload(p);
-    }
-    return x;
+    asm volatile("s_load_dwordx16 %0, %3, 0x0 glc\n\t"
+                 "s_load_dwordx16 %1, %3, 0x40 glc\n\t"
+                 "s_load_dwordx16 %2, %3, 0x80 glc\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(a), "=&s"(b), "=&s"(c) : "s"(p) : "memory");
 }
-
-// Poll N words (those with want[j] set) until every tag matches.  All outstanding words are
-// re-read together in each round, so the wait costs one round trip after the last word lands
-// rather than one round trip per word.
-template <int N>
-__device__ __forceinline__ void poll_words(const u64* base, size_t stride, int count, u64 (&x)[N],
-                                           unsigned tag, int limit, int& dead)
+__device__ __forceinline__ void sgather1(const void* p, v16u& a)
 {
-#pragma unroll
-    for (int j = 0; j < N; ++j)
-        if (j < count) x[j] = xload(base + j * stride);
-    if (dead) return;
-    int n = 0;
-    for (;;) {
-        bool ok = true;
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-            if (j < count && word_tag(x[j]) != tag) ok = false;
-        if (ok) break;
-        if (++n > limit) { dead = 1; break; }
-#pragma unroll
-        for (int j = 0; j < N; ++j)
-            if (j < count && word_tag(x[j]) != tag) x[j] = xload(base + j * stride);
-    }
+    asm volatile("s_load_dwordx16 %0, %1, 0x0 glc\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(a) : "s"(p) : "memory");
 }
-
-// Poll one row of 2*K consecutive words (16-byte aligned) with 16-byte loads: a destination's
-// partial sums from all producers sit in one cache line.  Volatile vector loads bypass the
-// vector L1; every 8-byte word was written by a single store, so it is read whole.
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bool pair_ready(v4u v, unsigned tag)
+// number of leading words (of 8) whose tag matches, and their sum in fixed order
+__device__ __forceinline__ bool block_ready(const v16u& v, int count, unsigned tag)
 {
-    return (v.y >> 16) == tag && (v.w >> 16) == tag;
+    bool ok = true;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < count && v[2 * j + 1] != tag) ok = false;
+    return ok;
 }
-// sum of the 2*K partial values of a row, each scaled by 2^(shift - dl)
-template <int K>
-__device__ __forceinline__ float poll_row_sum(const u64* row, unsigned tag, int dl, int limit, int& dead)
+__device__ __forceinline__ float block_sum8(const v16u& v, int count)
 {
-    const volatile v4u* p = (const volatile v4u*)row;
-    v4u v[K];
-#pragma unroll
-    for (int j = 0; j < K; ++j)
-        v[j] = p[j];
-    if (!dead) {
-        int n = 0;
-        for (;;) {
-            bool ok = true;
-#pragma unroll
-            for (int j = 0; j < K; ++j)
-                if (!pair_ready(v[j], tag)) ok = false;
-            if (ok) break;
-            if (++n > limit) { dead = 1; break; }
-#pragma unroll
-            for (int j = 0; j < K; ++j)
-                if (!pair_ready(v[j], tag)) v[j] = p[j];
-        }
-    }
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < K; ++j)
-        {
-            s += __builtin_ldexpf(__uint_as_float(v[j].x), (int)(short)(v[j].y & 0xFFFFu) - dl);
-            s += __builtin_ldexpf(__uint_as_float(v[j].z), (int)(short)(v[j].w & 0xFFFFu) - dl);
-        }
+    for (int j = 0; j < 8; ++j)
+        if (j < count) s += __uint_as_float(v[2 * j]);
     return s;
 }
 
@@ -287,10 +247,21 @@ struct ClusterGeom {
     int r0, nr;   // owned rows
 };
 
+// poll one word (vector path; only used outside the per-frame loop)
+__device__ __forceinline__ bool poll_flag(const u64* p, u64 target, int limit)
+{
+    for (int n = 0; n <= limit; ++n) {
+        const u64 x = xload(p);
+        if (x != ~0ull && x >= target) return true;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
+}
+
 // barrier among the 2K workgroups of a cluster with release/acquire semantics
 // for plain global stores (used once per item, at the meeting frame)
 __device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const ClusterGeom& g, unsigned tag,
-                                             int& dead, int* dead_s)
+                                             int* dead_s)
 {
     __threadfence();
     __syncthreads();
@@ -298,17 +269,9 @@ __device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const Cluster
     const int me = g.role * a.K + g.k;
     const u64 target = (u64)tag + 1;          // flags count items; ~0 = never written
     if (threadIdx.x == 0) xstore(flags + me, target);
-    if (threadIdx.x < 2 * a.K && !dead) {
-        int n = 0;
-        for (;;) {
-            const u64 x = xload(flags + threadIdx.x);
-            if (x != ~0ull && x >= target) break;
-            if (++n > a.spin_limit) { *dead_s = 1; break; }
-            __builtin_amdgcn_s_sleep(2);
-        }
-    }
+    if (threadIdx.x < 2 * a.K && !*dead_s)
+        if (!poll_flag(flags + threadIdx.x, target, a.spin_limit)) *dead_s = 1;
     __syncthreads();
-    dead = *dead_s;
     __threadfence();
 }
 
@@ -326,28 +289,33 @@ __device__ __forceinline__ double meeting_value(const float* ah, const float* bh
 
 // ------------------------------------------------------------------ alpha role
 // LDS protocol (par = i & 1 is the parity of the state index i):
-//   ap_s[par][r]   partial-sum part of a_i for the workgroup's rows, already scaled by 2^-dl
-//   bl_s[par][r]   empty-label products a_i[r] * E_i[r][0] written during step i (for a_{i+1})
-//   ctl: [par] dl_{i-1}, [2 + 2 par + half] column-0 shift of step i, [6 + par] exponent of a_i,
-//        [8 + 16 par + wave] per-wave max column shift of frame i, [40] timeout flag
-//   a_i[r] = ap_s[par][r] + ldexp(bl_s[par^1][r], s0_{i-1} - dl_{i-1})
+//   ap_s[par][r]   sum of the partial column sums for the workgroup's rows (part of a_i)
+//   bl_s[par][r]   empty-label contribution a_i[r] E_i[r][0], written during step i (part of a_{i+1})
+//   a_i[r] = ap_s[par][r] + bl_s[par^1][r]
+//   ctl: [par] P_i (exponent step applied to the results of step i), [2 + par] exponent of a_i,
+//        [40] timeout flag, [44..48] half-workgroup handshake flags
 template <int D, bool GAMMA, bool ACC, int KT>
 __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
     float* ap_s = smem;
     float* bl_s = ap_s + 2 * kClMaxR;
-    float* bv_s = bl_s + 2 * kClMaxR;         // [2][kClMaxC] bhat_{i+1} staging (GAMMA)
-    int* ctl_s = (int*)(bv_s + 2 * kClMaxC);
-    float* red = (float*)(ctl_s + 48);
+    float* bv_s = bl_s + 2 * kClMaxR;         // [2][320] bhat_{i+1} staging (GAMMA)
+    float* pacc_s = bv_s + 2 * 320;           // [320] scaled partial sums of the second half
+    int* ctl_s = (int*)(pacc_s + 320);        // [64]
+    float* red = (float*)(ctl_s + 64);        // [32]
+    volatile int* flag_s = ctl_s + 44;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, keep it scalar
-    const bool comm = wave == kClWaves;
+    const bool aux = wave == kClWaves;        // the eleventh wave streams nothing
     const int half = wave >= kClHW ? 1 : 0;   // which half of the workgroup's rows
     const int c = tid - half * kClHW * kWave; // column of a compute thread
     const int C = a.C, V1 = a.C;
-    const bool colok = !comm && c < C;
+    const bool colok = !aux && c < C;
     const int rb = half * kClRT;              // first row (inside the workgroup) of this thread
+    // rows gathered by this wave: [3 wave, 3 wave + 3) within the workgroup's rows
+    const int gr0 = 3 * wave;
+    const int grn = max(0, min(3, g.nr - gr0));
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -362,8 +330,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
         const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
         int* Sa = a.Sa + (size_t)b * (a.T + 1);
         const int* Sb = a.Sb + (size_t)b * (a.T + 1);
-        constexpr int XK = 2 * KT;                                // words per row
-        u64* xbase = a.xa + (size_t)g.cg * 2 * a.XS * XK;
+        u64* xbase = a.xa + (size_t)g.cg * 2 * a.XS * kClXK;
 
         if (tid < kClMaxR) {
             ap_s[tid] = (g.r0 + tid == 0 && tid < g.nr) ? 1.f : 0.f;
@@ -371,211 +338,127 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             bl_s[tid] = 0.f;
             bl_s[kClMaxR + tid] = 0.f;
         }
-        if (tid == 0) {
-            ctl_s[40] = 0; ctl_s[0] = 0; ctl_s[4] = kShiftNone; ctl_s[5] = kShiftNone; ctl_s[6] = 0;
-        }
+        if (tid == 0) { ctl_s[40] = 0; ctl_s[0] = 0; ctl_s[1] = 0; ctl_s[2] = 0; ctl_s[3] = 0; }
+        if (tid < 8) ctl_s[44 + tid] = 0;
         __syncthreads();
 
-        if (comm) {
-            // ================= comm wave: exchange only =================
-            int dead = 0, sig = 0;
-            int m_own = (g.r0 == 0) ? 0 : -127;
-            __syncthreads();       // the compute waves have published the column shifts of frame 0
-            for (int i = 0;; ++i) {
-                const int par = i & 1;
-                // complete a_i, store it for the other side, take its magnitude
-                if (i == 0) {
-                    if (lane < g.nr) ah[g.r0 + lane] = (g.r0 + lane == 0) ? 1.f : 0.f;
-                    if (lane == 0 && g.k == 0) Sa[0] = 0;
-                } else if (i <= nex) {
-                    float av = 0.f;
-                    if (lane < g.nr)
-                        av = ap_s[par * kClMaxR + lane]
-                             + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + lane],
-                                                ctl_s[2 + (par ^ 1) * 2 + (lane >= kClRT ? 1 : 0)] - ctl_s[par]);
-                    m_own = wave_max_dpp((lane < g.nr) ? float_exponent(av) : -127);
-                    if (i <= mid) {
-                        if (lane < g.nr) ah[(size_t)i * C + g.r0 + lane] = av;
-                        if (lane == 0 && g.k == 0) Sa[i] = sig;
-                    }
+        // ---- per-wave state ----
+        const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+        const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        const unsigned coff = (unsigned)(min(c, C - 1) * (int)sizeof(float));     // per thread
+        const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
+        const unsigned rbase = (unsigned)(g.r0 + rb) * pitch;                    // scalar
+        const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
+        float E[D][kClRT];
+        int sc[D];
+        float bcol[2] = {0.f, 0.f};
+        int sbn[2] = {0, 0};
+        double D2 = 0.0;
+        int dead = 0;
+        // aux wave bookkeeping (identical in every alpha workgroup of the cluster)
+        int sig = 0, P_cur = 0, P_prev = 0, mu_prev = 0;
+
+        // Rows beyond the owned range are read anyway (in bounds of the item, or answered
+        // with 0 by the buffer bounds check) and then forced to -inf, i.e. E = 0.
+        auto issue = [&](int slot, int f) __attribute__((always_inline)) {
+            const unsigned fo = (unsigned)f * frb + rbase;
+#pragma unroll
+            for (int r = 0; r < kClRT; ++r) E[slot][r] = buf_load_nt(wrs, coff, fo + (unsigned)r * pitch);
+        };
+        auto prep = [&](int slot) __attribute__((always_inline)) {
+            float mx = LAST_NEG_INF;
+#pragma unroll
+            for (int r = 0; r < kClRT; ++r) {
+                if (r >= nrt) E[slot][r] = LAST_NEG_INF;
+                mx = fmaxf(mx, E[slot][r]);
+            }
+            const int s = shift_for(mx);
+            sc[slot] = s;
+            const float fs = (float)s;
+#pragma unroll
+            for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
+        };
+        // Loads and the exp pass are unconditional (the frame index is clamped to the last
+        // frame of this role): conditional ones would leave registers "possibly pending" at
+        // control-flow joins and force full memory waits on the serial path.
+        const int nlast = max(n - 1, 0);
+        if (!aux) {
+#pragma unroll
+            for (int f = 0; f < D - 1; ++f) issue(f, min(f, nlast));
+            prep(0);
+        }
+
+        int i = 0;
+        auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
+            constexpr int S = decltype(SLOT)::value;
+            const int par = i & 1;
+            // ---- top of state i: the aux wave completes a_i, stores it, publishes its magnitude
+            const unsigned tag = gstep + 1;
+            u64* xs = xbase + (size_t)(gstep & 1) * a.XS * kClXK;
+            if (aux) {
+                float av = 0.f;
+                if (lane < g.nr) av = ap_s[par * kClMaxR + lane] + bl_s[(par ^ 1) * kClMaxR + lane];
+                const int mu_own = wave_max_dpp((lane < g.nr) ? float_exponent(av) : -127);
+                if (i <= mid) {
+                    if (lane < g.nr) ah[(size_t)i * C + g.r0 + lane] = av;
+                    if (lane == 0 && g.k == 0) Sa[i] = sig;
                 }
-                if (i == mid) {
-                    if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
-                    cluster_sync(a, g, ptag, dead, &ctl_s[40]);
-                    ptag += 1;
-                    const double D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
-                    if (g.k == 0 && lane == 0) {
-                        a.dist[b] = bad ? __builtin_nanf("") : (float)(D2 * 0.6931471805599453);
-                        if (a.item_status)
-                            a.item_status[b] = bad ? kItemBadLength : (dead ? kItemTimeout : kItemOk);
-                    }
-                    __syncthreads();
+                if (i < nex && lane == 0) xstore(xs + (size_t)C * kClXK + g.k, pack_int(mu_own, tag));
+            }
+            if (i == mid) {
+                if (aux && __builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
+                cluster_sync(a, g, ptag, &ctl_s[40]);
+                ptag += 1;
+                D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                if (g.k == 0 && tid == 0) {
+                    a.dist[b] = bad ? __builtin_nanf("") : (float)(D2 * 0.6931471805599453);
+                    if (a.item_status)
+                        a.item_status[b] = bad ? kItemBadLength : (ctl_s[40] ? kItemTimeout : kItemOk);
                 }
-                if (i >= n) break;
-                if (i < nex) {
-                    const unsigned tag = gstep % 65535u;
-                    u64* xs = xbase + (size_t)(gstep & 1) * a.XS * XK;
-                    LAST_MARK(a, 1, i, 0);
-                    int h = kShiftNone;
-                    if (lane < kClWaves) h = ctl_s[8 + par * 16 + lane];
-                    h = wave_max_dpp(h);
-                    if (lane == 0) xstore(xs + (size_t)C * XK + 2 * g.k, pack_header(h, m_own, tag));
-                    // one batch: this lane's row of partial sums (16-byte loads) and, on the first
-                    // KT lanes, one header word each; poll until every tag matches
-                    const bool wantrow = lane < g.nr && g.r0 + lane != 0;   // q = 0 has no partials
-                    const volatile v4u* rowp = (const volatile v4u*)(xs + (size_t)(g.r0 + (wantrow ? lane : 0)) * XK);
-                    const u64* hp = xs + (size_t)C * XK + 2 * (lane < KT ? lane : 0);
-                    v4u v[KT];
-                    u64 hx = 0;
-#pragma unroll
-                    for (int j = 0; j < KT; ++j) v[j] = rowp[j];
-                    hx = xload(hp);
-                    if (!dead) {
-                        int np = 0;
-                        for (;;) {
-                            bool ok = !(lane < KT) || word_tag(hx) == tag;
-                            if (wantrow) {
-#pragma unroll
-                                for (int j = 0; j < KT; ++j)
-                                    if (!pair_ready(v[j], tag)) ok = false;
-                            }
-                            if (ok) break;
-                            if (++np > a.spin_limit) { dead = 1; break; }
-                            if (lane < KT && word_tag(hx) != tag) hx = xload(hp);
-                            if (wantrow) {
-#pragma unroll
-                                for (int j = 0; j < KT; ++j)
-                                    if (!pair_ready(v[j], tag)) v[j] = rowp[j];
-                            }
-                        }
-                    }
-                    // every lane must know all headers: wait for the slowest lane of the wave
-                    const int hh = lane < KT ? header_h(hx) : kShiftNone;
-                    const int mm = lane < KT ? header_m(hx) : -127;
-                    const int dl = wave_max_dpp(hh) + wave_max_dpp(mm);
-                    LAST_MARK(a, 1, i, 1);
-                    float v_sum = 0.f;
-                    if (wantrow) {
-#pragma unroll
-                        for (int j = 0; j < KT; ++j) {
-                            v_sum += __builtin_ldexpf(__uint_as_float(v[j].x), (int)(short)(v[j].y & 0xFFFFu) - dl);
-                            v_sum += __builtin_ldexpf(__uint_as_float(v[j].z), (int)(short)(v[j].w & 0xFFFFu) - dl);
-                        }
-                    }
-                    LAST_MARK(a, 1, i, 2);
-                    if (lane < kClMaxR) ap_s[(par ^ 1) * kClMaxR + lane] = v_sum;
-                    sig += dl;
-                    if (lane == 0) { ctl_s[par ^ 1] = dl; ctl_s[6 + (par ^ 1)] = sig; }
-                    gstep += 1;
+                if (GAMMA && colok) {
+                    // first two frames of the second half: fetch the other side's vectors now
+                    if (mid < n) { bcol[mid & 1] = bh[(size_t)(mid + 1) * C + c]; sbn[mid & 1] = Sb[mid + 1]; }
+                    if (mid + 1 < n) { bcol[(mid + 1) & 1] = bh[(size_t)(mid + 2) * C + c]; sbn[(mid + 1) & 1] = Sb[mid + 2]; }
+                    if (mid < n) bv_s[(mid & 1) * 320 + c] = bcol[mid & 1];
                 }
                 __syncthreads();
             }
-            if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0 && g.k == 0 && a.item_status && !bad)
-                a.item_status[b] = kItemTimeout;
-        } else {
-            // ================= compute waves =================
-            const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
-            const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
-            // Byte offsets of this thread's elements inside a frame (the same for every frame and
-            // for the marginals, which share the layout of w).  Rows beyond the owned range are
-            // clamped to the last owned row: their a-values are 0.
-            const unsigned coff = (unsigned)(min(c, C - 1) * (int)sizeof(float));     // per thread
-            const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
-            const unsigned rbase = (unsigned)(g.r0 + rb) * pitch;                    // scalar
-            const int nrt = max(0, min(kClRT, g.nr - rb));      // real rows of this thread
-            float E[D][kClRT];
-            int sc[D];
-            float bcol[2] = {0.f, 0.f};
-            int sbn[2] = {0, 0};
-            double D2 = 0.0;
-            int hcur = kShiftNone;
-
-            // Rows beyond the owned range are read anyway (in bounds of the item, or answered
-            // with 0 by the buffer bounds check) and then forced to -inf, i.e. E = 0.
-            auto issue = [&](int slot, int f) __attribute__((always_inline)) {
-                const unsigned fo = (unsigned)f * frb + rbase;
-#pragma unroll
-                for (int r = 0; r < kClRT; ++r) E[slot][r] = buf_load_nt(wrs, coff, fo + (unsigned)r * pitch);
-            };
-            auto prep = [&](int slot) __attribute__((always_inline)) {
-                float mx = LAST_NEG_INF;
-#pragma unroll
-                for (int r = 0; r < kClRT; ++r) {
-                    if (r >= nrt) E[slot][r] = LAST_NEG_INF;
-                    mx = fmaxf(mx, E[slot][r]);
-                }
-                const int s = shift_for(mx);
-                sc[slot] = s;
-                const float fs = (float)s;
-#pragma unroll
-                for (int r = 0; r < kClRT; ++r) E[slot][r] = fast_exp2(fmaf(E[slot][r], kLog2e, -fs));
-                return s;
-            };
-            // Loads and the exp pass are unconditional (the frame index is clamped to the last
-            // frame of this role): conditional ones would leave registers "possibly pending" at
-            // control-flow joins and force full memory waits on the serial path.
-            const int nlast = max(n - 1, 0);
-#pragma unroll
-            for (int f = 0; f < D - 1; ++f) issue(f, min(f, nlast));
-            hcur = prep(0);
-            {
-                const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
-                if (lane == 0) ctl_s[8 + wave] = hw;
-            }
-            __syncthreads();       // frame 0 is prepared: its column shifts are visible to the comm wave
-
-            int i = 0;
-            auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
-                constexpr int S = decltype(SLOT)::value;
-                const int par = i & 1;
-                if (i == mid) {
-                    int dead = 0;
-                    cluster_sync(a, g, ptag, dead, &ctl_s[40]);
-                    ptag += 1;
-                    D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
-                    if (GAMMA && colok) {
-                        // first two frames of the second half: fetch the other side's vectors now
-                        if (mid < n) { bcol[mid & 1] = bh[(size_t)(mid + 1) * C + c]; sbn[mid & 1] = Sb[mid + 1]; }
-                        if (mid + 1 < n) { bcol[(mid + 1) & 1] = bh[(size_t)(mid + 2) * C + c]; sbn[(mid + 1) & 1] = Sb[mid + 2]; }
-                        if (mid < n) bv_s[(mid & 1) * kClMaxC + c] = bcol[mid & 1];
-                    }
-                    __syncthreads();
-                }
-                if (i >= n) return false;
-                const bool exch = i < nex;
-                const unsigned tag = gstep % 65535u;
-                u64* xs = xbase + (size_t)(gstep & 1) * a.XS * XK;
-                LAST_MARK(a, 0, i, 0);
-                // Stream first: the vector memory pipeline returns in order, so loads issued later
-                // in the step would sit in front of the comm wave's next polls for longer.
-                issue((S + D - 1) % D, min(i + D - 1, nlast));
-                const int dl = ctl_s[par];
-                const int blsh = ctl_s[2 + (par ^ 1) * 2 + half] - dl;
+            if (i >= n) return false;
+            const bool exch = i < nex;
+            LAST_MARK(a, aux ? 1 : 0, i, 0);
+            if (!aux) {
+                // ---- FMA loop, hand-over between the two halves, publish
+                const int P = ctl_s[par];
                 float acc0 = 0.f, acc1 = 0.f;
                 auto a_of = [&](int r) __attribute__((always_inline)) {        // a_i[rb + r]
-                    return ap_s[par * kClMaxR + rb + r]
-                           + __builtin_ldexpf(bl_s[(par ^ 1) * kClMaxR + rb + r], blsh);
+                    return ap_s[par * kClMaxR + rb + r] + bl_s[(par ^ 1) * kClMaxR + rb + r];
                 };
 #pragma unroll
                 for (int r = 0; r < kClRT; ++r) {
                     const float pr = a_of(r) * E[S][r];
                     if (r & 1) acc1 += pr; else acc0 += pr;
-                    if (c == 0) bl_s[par * kClMaxR + rb + r] = pr;
+                    if (c == 0) bl_s[par * kClMaxR + rb + r] = __builtin_ldexpf(pr, sc[S] - P);
                 }
-                const float acc = acc0 + acc1;
-                if (exch && colok && c >= 1)
-                    xstore(xs + (size_t)c * XK + 2 * g.k + half, pack_word(acc, sc[S], tag));
-                if (c == 0) ctl_s[2 + par * 2 + half] = sc[S];
+                float pub = __builtin_ldexpf(acc0 + acc1, sc[S] - P);
+                if (half == 1) {
+                    pacc_s[c] = pub;
+                    if (lane == 0) flag_s[wave - kClHW] = i + 1;
+                } else {
+                    int spins = 0;
+                    while (flag_s[wave] != i + 1 && ++spins < (1 << 22)) { }
+                    pub += ((volatile float*)pacc_s)[c];
+                    if (exch && colok && c >= 1) xstore(xs + (size_t)c * kClXK + g.k, pack_word(pub, tag));
+                }
                 LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= mid && colok) {
-                    const float kx = (float)((double)(ctl_s[6 + par] + sbn[par]) - D2);
+                    const float kx = (float)((double)(ctl_s[2 + par] + sbn[par]) - D2);
                     const float fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
                     const unsigned gso = (unsigned)i * frb + rbase;
 #pragma unroll
                     for (int r = 0; r < kClRT; ++r)
                         if (r < nrt) {
                             // the empty label (column 0) returns to the row's own state
-                            const float f2 = (c == 0) ? fac * bv_s[par * kClMaxC + g.r0 + rb + r] : fac;
+                            const float f2 = (c == 0) ? fac * bv_s[par * 320 + g.r0 + rb + r] : fac;
                             const float gv = a_of(r) * E[S][r] * f2;
                             if (ACC) buf_store(buf_load(grs, coff, gso + (unsigned)r * pitch) + gv, grs, coff, gso + (unsigned)r * pitch);
                             else buf_store_nt(gv, grs, coff, gso + (unsigned)r * pitch);
@@ -586,48 +469,103 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     bcol[par] = bh[(size_t)(i + 3) * C + c];
                     sbn[par] = Sb[i + 3];
                 }
+                issue((S + D - 1) % D, min(i + D - 1, nlast));
                 LAST_MARK(a, 0, i, 2);
-                {
-                    hcur = prep((S + 1) % D);
-                    const int hw = wave_max_dpp(colok ? hcur : kShiftNone);
-                    if (lane == 0) ctl_s[8 + (par ^ 1) * 16 + wave] = hw;
-                }
-                if (GAMMA && i + 1 < n && i + 1 >= mid && colok) bv_s[(par ^ 1) * kClMaxC + c] = bcol[par ^ 1];
-                if (exch) gstep += 1;
+                prep((S + 1) % D);
+                if (GAMMA && i + 1 < n && i + 1 >= mid && colok) bv_s[(par ^ 1) * 320 + c] = bcol[par ^ 1];
                 LAST_MARK(a, 0, i, 3);
-                __syncthreads();
-                ++i;
-                return true;
-            };
-            for (;;) {
-                if (!step(std::integral_constant<int, 0>())) break;
-                if (!step(std::integral_constant<int, 1>())) break;
-                if (!step(std::integral_constant<int, 2>())) break;
-                if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
             }
+            if (exch) {
+                // ---- gather: every wave sums the partial columns of three of the own rows
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+                int mu = 0;
+                if ((grn > 0 || aux) && !dead) {
+                    v16u v0, v1, v2, vh;
+                    // rows beyond the owned range are still loaded (inside the buffer) and ignored
+                    const void* rowp = xs + (size_t)(g.r0 + min(gr0, g.nr - 1)) * kClXK;
+                    // the start state (q = 0) receives no label arcs: its row is never written
+                    const bool skip0 = g.r0 + gr0 == 0;
+                    int np = 0;
+                    for (;;) {
+                        sgather3(rowp, v0, v1, v2);
+                        bool ok = (grn < 1 || skip0 || block_ready(v0, KT, tag))
+                                  && (grn < 2 || block_ready(v1, KT, tag))
+                                  && (grn < 3 || block_ready(v2, KT, tag));
+                        if (aux) {
+                            sgather1(xs + (size_t)C * kClXK, vh);
+                            ok = ok && block_ready(vh, KT, tag);
+                        }
+                        if (ok) break;
+                        if (++np > a.spin_limit) { dead = 1; break; }
+                    }
+                    s0 = skip0 ? 0.f : block_sum8(v0, KT);
+                    s1 = block_sum8(v1, KT);
+                    s2 = block_sum8(v2, KT);
+                    if (aux) {
+                        mu = -127;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (j < KT) mu = max(mu, (int)vh[2 * j]);
+                    }
+                }
+                if (aux) LAST_MARK(a, 1, i, 1);
+                if (lane == 0) {
+                    if (grn > 0) ap_s[(par ^ 1) * kClMaxR + gr0] = s0;
+                    if (grn > 1) ap_s[(par ^ 1) * kClMaxR + gr0 + 1] = s1;
+                    if (grn > 2) ap_s[(par ^ 1) * kClMaxR + gr0 + 2] = s2;
+                }
+                if (aux) {
+                    // exponent step for the next publish, from magnitudes every workgroup has seen
+                    const int G = mu - mu_prev + P_prev;          // growth observed in step i - 1
+                    const int P_next = mu + 2 * G - P_cur;
+                    sig += P_cur;
+                    if (lane == 0) { ctl_s[par ^ 1] = P_next; ctl_s[2 + (par ^ 1)] = sig; }
+                    mu_prev = mu; P_prev = P_cur; P_cur = P_next;
+                    if (dead && lane == 0) ctl_s[40] = 1;
+                } else if (dead && lane == 0) {
+                    ctl_s[40] = 1;
+                }
+                gstep += 1;
+            }
+            __syncthreads();
+            ++i;
+            return true;
+        };
+        for (;;) {
+            if (!step(std::integral_constant<int, 0>())) break;
+            if (!step(std::integral_constant<int, 1>())) break;
+            if (!step(std::integral_constant<int, 2>())) break;
+            if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
         }
+        __syncthreads();
+        if (g.k == 0 && tid == 0 && ctl_s[40] && a.item_status && !bad) a.item_status[b] = kItemTimeout;
         __syncthreads();
     }
 }
 
 // ------------------------------------------------------------------- beta role
-// LDS: b_s[par][q] = b_{t+1} for all states (par = step parity), ctl[par] = its exponent.
+// LDS: b_s[par][q] = b_{t+1} for all states (par = step parity); mu_s[par][wave] = largest
+// binary exponent among the words gathered by each wave; every wave keeps (mu, P, exponent)
+// of the current vector in registers, identically.
 template <int D, bool GAMMA, bool ACC, int KT>
 __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                           unsigned& gstep, unsigned& ptag)
 {
-    float* b_s = smem;                        // [2][kClMaxC]
-    int* ctl_s = (int*)(b_s + 2 * kClMaxC);   // [0..1] exponent, [24] timeout flag
-    float* red = (float*)(ctl_s + 32);
+    float* b_s = smem;                        // [2][320]
+    int* ctl_s = (int*)(b_s + 2 * 320);       // [0..31] mu_s[2][16], [40] timeout flag
+    float* red = (float*)(ctl_s + 64);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool comm = wave == kClWaves;
+    const bool aux = wave == kClWaves;
     const int C = a.C, V1 = a.C;
     // rows of this wave: wave, wave + 10, ... (index inside the workgroup's rows)
     int nrw = 0;
-    if (!comm) nrw = (g.nr - wave + kClWaves - 1) / kClWaves;
+    if (!aux) nrw = (g.nr - wave + kClWaves - 1) / kClWaves;
     if (nrw < 0) nrw = 0;
     const int ncol = (C + 63) / 64;
+    // exchange words gathered by this wave: [24 wave, 24 wave + 24) of the C state values
+    const int gq0 = kClCH * wave;
+    const int gqn = max(0, min(kClCH, C - gq0));
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -646,165 +584,116 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
         int* Sb = a.Sb + (size_t)b * (a.T + 1);
         u64* xbase = a.xb + (size_t)g.cg * 2 * a.XSB;
 
-        if (tid == 0) { ctl_s[24] = 0; ctl_s[0] = 0; }
+        if (tid == 0) ctl_s[40] = 0;
+        if (tid < 32) ctl_s[tid] = -127;                     // no words gathered yet
         // both slots: entries for columns >= C stay 0 for the whole item (clamped loads meet them)
-        for (int q = tid; q < 2 * kClMaxC; q += blockDim.x) b_s[q] = q < C ? 1.f : 0.f;
+        for (int q = tid; q < 2 * 320; q += blockDim.x) b_s[q] = q < C ? 1.f : 0.f;
+        // b_L = 1 with exponent 0
+        if (g.k == 0) {
+            for (int q = tid; q < C; q += blockDim.x) bh[(size_t)L * C + q] = 1.f;
+            if (tid == 0) Sb[L] = 0;
+        }
         __syncthreads();
 
-        if (comm) {
-            // ================= comm wave =================
-            int dead = 0, sig = 0;
-            for (int i = 0;; ++i) {
-                const int par = i & 1;
-                const int t = L - 1 - i;
-                if (i == 0) {
+        const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+        const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        // Byte offsets of this lane's elements inside a frame (shared by w and the marginals).
+        // Rows / columns beyond the valid range are clamped: such rows are never published or
+        // stored, such columns meet a zero in the b vector.
+        unsigned coff[kClNC];                                                    // per lane
 #pragma unroll
-                    for (int j = 0; j < kClNC; ++j) {
-                        const int q = lane + 64 * j;
-                        if (q < C && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)L * C + q] = 1.f;
-                    }
-                    if (lane == 0 && g.k == 0) Sb[L] = 0;
-                }
-                if (i == ph1) {
-                    if (__builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[24] = 1;
-                    cluster_sync(a, g, ptag, dead, &ctl_s[24]);
-                    ptag += 1;
-                    (void)meeting_value(ah, bh, Sa, Sb, mid, C, red);
-                    __syncthreads();
-                }
-                if (i >= n) break;
-                if (i < nex) {
-                    const unsigned tag = gstep % 65535u;
-                    u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
-                    LAST_MARK(a, 1, i, 0);
-                    u64 x[kClNC];
-                    int e = -40000;
-                    // lane l takes the words l, l + 64, ...: count of valid ones for this lane
-                    const int cnt = lane < C ? (C - 1 - lane) / 64 + 1 : 0;
-                    poll_words(xs + lane, (size_t)64, cnt, x, tag, a.spin_limit, dead);
-#pragma unroll
-                    for (int j = 0; j < kClNC; ++j)
-                        if (j < cnt) {
-                            const float v = word_value(x[j]);
-                            if (v > 0.f) e = max(e, word_shift(x[j]) + float_exponent(v) + 1);
-                        }
-                    LAST_MARK(a, 1, i, 1);
-                    int dl = wave_max_dpp(e);
-                    if (dl < -30000) dl = 0;
-                    sig += dl;
-#pragma unroll
-                    for (int j = 0; j < kClNC; ++j)
-                        if (j < ncol && lane + 64 * j < C) {
-                            const int q = lane + 64 * j;
-                            const float v = __builtin_ldexpf(word_value(x[j]), word_shift(x[j]) - dl);
-                            b_s[(par ^ 1) * kClMaxC + q] = v;
-                            if (t >= mid && q >= g.r0 && q < g.r0 + g.nr) bh[(size_t)t * C + q] = v;
-                        }
-                    if (lane == 0) {
-                        ctl_s[par ^ 1] = sig;
-                        if (t >= mid && g.k == 0) Sb[t] = sig;
-                    }
-                    LAST_MARK(a, 1, i, 2);
-                    gstep += 1;
-                }
-                __syncthreads();
-            }
-        } else {
-            // ================= compute waves =================
-            const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
-            const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
-            // Byte offsets of this lane's elements inside a frame (shared by w and the marginals).
-            // Rows / columns beyond the valid range are clamped: such rows are never published or
-            // stored, such columns meet a zero in the b vector.
-            unsigned coff[kClNC];                                                    // per lane
-#pragma unroll
-            for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
-            const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
-            auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
-                return (unsigned)(g.r0 + min(wave + ri * kClWaves, g.nr - 1)) * pitch;
-            };
-            float E[D][kClRW][kClNC];
-            int sr[D][kClRW];
-            float apre[2] = {0.f, 0.f};   // lane ri < nrw holds ahat_t[row ri] two frames ahead
-            int san[2] = {0, 0};
-            double D2 = 0.0;
+        for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
+        const unsigned pitch = (unsigned)(V1 * (int)sizeof(float));
+        auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
+            return (unsigned)(g.r0 + min(wave + ri * kClWaves, g.nr - 1)) * pitch;
+        };
+        float E[D][kClRW][kClNC];
+        int sr[D][kClRW];
+        float apre[2] = {0.f, 0.f};   // lane ri < nrw holds ahat_t[row ri] two frames ahead
+        int san[2] = {0, 0};
+        double D2 = 0.0;
+        int dead = 0;
+        int sig = 0, P_cur = 0, mu_cur = 0;     // exponent bookkeeping, identical in every wave
 
-            auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
-                const unsigned so = (unsigned)max(L - 1 - f, 0) * frb;
+        auto issue = [&](int slot, int f) __attribute__((always_inline)) {       // frame t = L-1-f
+            const unsigned so = (unsigned)max(L - 1 - f, 0) * frb;
 #pragma unroll
-                for (int ri = 0; ri < kClRW; ++ri)
+            for (int ri = 0; ri < kClRW; ++ri)
 #pragma unroll
-                    for (int j = 0; j < kClNC; ++j) E[slot][ri][j] = buf_load_nt(wrs, coff[j], so + roff(ri));
-            };
-            auto prep = [&](int slot) __attribute__((always_inline)) {
+                for (int j = 0; j < kClNC; ++j) E[slot][ri][j] = buf_load_nt(wrs, coff[j], so + roff(ri));
+        };
+        auto prep = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
-                for (int ri = 0; ri < kClRW; ++ri) {
-                    float mx = E[slot][ri][0];
+            for (int ri = 0; ri < kClRW; ++ri) {
+                float mx = E[slot][ri][0];
 #pragma unroll
-                    for (int j = 1; j < kClNC; ++j) mx = fmaxf(mx, E[slot][ri][j]);
-                    mx = wave_max_dpp(mx);
-                    const int s = shift_for(mx);
-                    sr[slot][ri] = s;
-                    const float fs = (float)s;
+                for (int j = 1; j < kClNC; ++j) mx = fmaxf(mx, E[slot][ri][j]);
+                mx = wave_max_dpp(mx);
+                const int s = shift_for(mx);
+                sr[slot][ri] = s;
+                const float fs = (float)s;
 #pragma unroll
-                    for (int j = 0; j < kClNC; ++j)
-                        E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
-                }
-            };
-            const int nlast = max(n - 1, 0);     // see the alpha role: unconditional, clamped
+                for (int j = 0; j < kClNC; ++j)
+                    E[slot][ri][j] = fast_exp2(fmaf(E[slot][ri][j], kLog2e, -fs));
+            }
+        };
+        const int nlast = max(n - 1, 0);     // see the alpha role: unconditional, clamped
+        if (!aux) {
 #pragma unroll
             for (int f = 0; f < D - 1; ++f) issue(f, min(f, nlast));
             prep(0);
+        }
 
-            int i = 0;
-            auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
-                constexpr int S = decltype(SLOT)::value;
-                const int par = i & 1;
-                const int t = L - 1 - i;
-                if (i == ph1) {
-                    int dead = 0;
-                    cluster_sync(a, g, ptag, dead, &ctl_s[24]);
-                    ptag += 1;
-                    D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
-                    if (GAMMA) {
-                        // forward vectors for the first two frames of the second half
-                        if (ph1 < n) {
-                            const int t0 = L - 1 - ph1;
-                            apre[ph1 & 1] = (lane < nrw) ? ah[(size_t)t0 * C + g.r0 + wave + lane * kClWaves] : 0.f;
-                            san[ph1 & 1] = Sa[t0];
-                        }
-                        if (ph1 + 1 < n) {
-                            const int t1 = L - 2 - ph1;
-                            apre[(ph1 + 1) & 1] = (lane < nrw) ? ah[(size_t)t1 * C + g.r0 + wave + lane * kClWaves] : 0.f;
-                            san[(ph1 + 1) & 1] = Sa[t1];
-                        }
+        int i = 0;
+        auto step = [&](auto SLOT) __attribute__((always_inline)) -> bool {
+            constexpr int S = decltype(SLOT)::value;
+            const int par = i & 1;
+            const int t = L - 1 - i;
+            if (i == ph1) {
+                if (dead && lane == 0) ctl_s[40] = 1;
+                cluster_sync(a, g, ptag, &ctl_s[40]);
+                ptag += 1;
+                D2 = meeting_value(ah, bh, Sa, Sb, mid, C, red);
+                if (GAMMA && !aux) {
+                    // forward vectors for the first two frames of the second half
+                    if (ph1 < n) {
+                        const int t0 = L - 1 - ph1;
+                        apre[ph1 & 1] = (lane < nrw) ? ah[(size_t)t0 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                        san[ph1 & 1] = Sa[t0];
                     }
-                    __syncthreads();
+                    if (ph1 + 1 < n) {
+                        const int t1 = L - 2 - ph1;
+                        apre[(ph1 + 1) & 1] = (lane < nrw) ? ah[(size_t)t1 * C + g.r0 + wave + lane * kClWaves] : 0.f;
+                        san[(ph1 + 1) & 1] = Sa[t1];
+                    }
                 }
-                if (i >= n) return false;
-                const bool exch = i < nex;
-                const unsigned tag = gstep % 65535u;
-                u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
-                LAST_MARK(a, 0, i, 0);
-                issue((S + D - 1) % D, min(i + D - 1, nlast));      // stream first (see the alpha role)
+                __syncthreads();
+            }
+            if (i >= n) return false;
+            const bool exch = i < nex;
+            const unsigned tag = gstep + 1;
+            u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
+            LAST_MARK(a, aux ? 1 : 0, i, 0);
+            if (!aux) {
                 float bv[kClNC];
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) bv[j] = b_s[par * kClMaxC + lane + 64 * j];
+                for (int j = 0; j < kClNC; ++j) bv[j] = b_s[par * 320 + lane + 64 * j];
                 float brow[kClRW];
 #pragma unroll
                 for (int ri = 0; ri < kClRW; ++ri) {
                     const int row = g.r0 + min(wave + ri * kClWaves, g.nr - 1);
-                    brow[ri] = b_s[par * kClMaxC + row];
+                    brow[ri] = b_s[par * 320 + row];
                     // the empty label (column 0) returns to the row's own state
                     float acc = E[S][ri][0] * (lane == 0 ? brow[ri] : bv[0]);
 #pragma unroll
                     for (int j = 1; j < kClNC; ++j) acc = fmaf(E[S][ri][j], bv[j], acc);
                     const float tot = wave_sum_dpp(acc);
-                    if (exch && lane == 0 && ri < nrw) xstore(xs + row, pack_word(tot, sr[S][ri], tag));
+                    if (exch && lane == 0 && ri < nrw)
+                        xstore(xs + row, pack_word(__builtin_ldexpf(tot, sr[S][ri] - P_cur), tag));
                 }
                 LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= ph1) {
-                    const float kx = (float)((double)(san[par] + ctl_s[par]) - D2);
+                    const float kx = (float)((double)(san[par] + sig) - D2);
                     const unsigned gso = (unsigned)t * frb;
 #pragma unroll
                     for (int ri = 0; ri < kClRW; ++ri)
@@ -827,20 +716,72 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     apre[par] = (lane < nrw) ? ah[(size_t)t2 * C + g.r0 + wave + lane * kClWaves] : 0.f;
                     san[par] = Sa[t2];
                 }
+                issue((S + D - 1) % D, min(i + D - 1, nlast));
                 LAST_MARK(a, 0, i, 2);
                 prep((S + 1) % D);
-                if (exch) gstep += 1;
                 LAST_MARK(a, 0, i, 3);
-                __syncthreads();
-                ++i;
-                return true;
-            };
-            for (;;) {
-                if (!step(std::integral_constant<int, 0>())) break;
-                if (!step(std::integral_constant<int, 1>())) break;
-                if (!step(std::integral_constant<int, 2>())) break;
-                if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
             }
+            if (exch) {
+                // ---- gather: every wave fetches 24 of the C state values through the scalar path
+                if (gqn > 0) {
+                    v16u v0, v1, v2;
+                    const void* rowp = xs + gq0;
+                    int np = 0;
+                    if (!dead)
+                        for (;;) {
+                            sgather3(rowp, v0, v1, v2);
+                            const bool ok = block_ready(v0, gqn, tag) && block_ready(v1, gqn - 8, tag)
+                                            && block_ready(v2, gqn - 16, tag);
+                            if (ok) break;
+                            if (++np > a.spin_limit) { dead = 1; break; }
+                        }
+                    else
+                        sgather3(rowp, v0, v1, v2);
+                    // scatter the 24 scalar values over the first 24 lanes of one register
+                    float val = 0.f;
+                    int mu = -127;
+                    auto put = [&](unsigned bits, int l) __attribute__((always_inline)) {
+                        if (l < gqn) {
+                            val = (lane == l) ? __uint_as_float(bits) : val;
+                            mu = max(mu, (int)((bits >> 23) & 0xFFu) - 127);
+                        }
+                    };
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        put(v0[2 * j], j);
+                        put(v1[2 * j], 8 + j);
+                        put(v2[2 * j], 16 + j);
+                    }
+                    if (lane < gqn) {
+                        b_s[(par ^ 1) * 320 + gq0 + lane] = val;
+                        if (t >= mid && g.k == 0) bh[(size_t)t * C + gq0 + lane] = val;
+                    }
+                    if (lane == 0) ctl_s[(par ^ 1) * 16 + wave] = mu;
+                    if (dead && lane == 0) ctl_s[40] = 1;
+                }
+                if (aux) LAST_MARK(a, 1, i, 1);
+                gstep += 1;
+            }
+            __syncthreads();
+            if (exch) {
+                // exponent bookkeeping for b_t (now in b_s[par ^ 1]): every wave, identically
+                int mu = -127;
+#pragma unroll
+                for (int j = 0; j < kClWaves + 1; ++j) mu = max(mu, ctl_s[(par ^ 1) * 16 + j]);
+                const int G = mu - mu_cur + P_cur;        // growth observed in this step
+                sig += P_cur;
+                if (t >= mid && g.k == 0 && tid == 0) Sb[t] = sig;
+                P_cur = mu + G;
+                mu_cur = mu;
+            }
+            ++i;
+            return true;
+        };
+        for (;;) {
+            if (!step(std::integral_constant<int, 0>())) break;
+            if (!step(std::integral_constant<int, 1>())) break;
+            if (!step(std::integral_constant<int, 2>())) break;
+            if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
         }
         __syncthreads();
     }
@@ -865,7 +806,7 @@ __device__ __forceinline__ void cluster_zero_padding(const ClusterArgs& a, const
 template <int D, bool GAMMA, bool ACC, int KT>
 __global__ __launch_bounds__(kClThreads) void cluster_fb_kernel(ClusterArgs a)
 {
-    __shared__ float smem[2 * kClMaxR * 2 + 2 * kClMaxC + 48 + 32 + 64];
+    __shared__ float smem[kClLds];
     ClusterGeom g;
     const int id = blockIdx.x;
     const int x = id & 7, slot = id >> 3;

@@ -157,8 +157,8 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     if (max_ncl < 1) return p;
     int want = (s.B + 7) / 8;
     p.ncl = want < max_ncl ? want : max_ncl;
-    p.XS = (s.C + 1 + 15) / 16 * 16;
-    p.XSB = (s.C + 15) / 16 * 16;
+    p.XS = s.C + 4;                          // exchange rows: C states, 1 header row, read-ahead pad
+    p.XSB = kClMaxC;                         // 11 waves x 24 words
     p.grid = 8 * p.ncl * 2 * p.K;
     p.ok = true;
     return p;
@@ -184,7 +184,7 @@ ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
     c.Sa = cv.take<int>(st);
     c.Sb = cv.take<int>(st);
     const size_t ncl = (size_t)8 * p.ncl;
-    const size_t nxa = ncl * 2 * 2 * p.K * p.XS, nxb = ncl * 2 * p.XSB, nph = ncl * 32;
+    const size_t nxa = ncl * 2 * p.XS * kClXK, nxb = ncl * 2 * p.XSB, nph = ncl * 32;
     // one contiguous block so that a single launch clears all tags
     c.xa = cv.take<u64>(nxa + nxb + nph);
     c.xb = c.xa ? c.xa + nxa : nullptr;
