@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblast_hip.so")
+# LAST_HIP_LIB selects another build of the same library (e.g. one compiled with other tuning macros)
+LIB_PATH = os.environ.get("LAST_HIP_LIB") or os.path.join(_HERE, "liblast_hip.so")
 
 LAST_LOG, LAST_TROPICAL = 0, 1
 OP_SHORTEST_DISTANCE, OP_ARC_POSTERIORS, OP_INTERSECT_REFERENCE, OP_SHORTEST_PATH = 0, 1, 2, 3

@@ -52,7 +52,9 @@ namespace last {
 
 typedef unsigned long long u64;
 
-constexpr int kClMaxR = 34;      // LDS row slots per workgroup (two halves of kClRT rows; <= 33 used)
+constexpr int kClMaxR = 40;      // LDS row slots per workgroup and parity: rows 0..16 at [0..16],
+                                 // rows 17..33 at [20..36], so that both halves start 16-byte aligned
+__device__ __forceinline__ int lds_row(int r) { return r < 17 ? r : r + 3; }
 constexpr int kClRT = 17;        // rows per alpha thread: each workgroup splits its rows in two halves
 constexpr int kClHW = 5;         // compute waves per half (alpha): 5 * 64 >= kClMaxC columns
 constexpr int kClWaves = 10;     // compute waves per workgroup
@@ -100,6 +102,7 @@ struct ClusterArgs {
     float scale;
     int accumulate;
     int spin_limit;
+    int aux_delay;     // units of 256 clocks the aux wave waits before its first poll
 #ifdef LAST_TRACE
     unsigned long long* trace;
 #endif
@@ -157,6 +160,13 @@ __device__ __forceinline__ void xstore(u64* p, u64 v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Per-frame publish: a plain 8-byte store that lands in the XCD's L2, where the scalar-path
+// polls of the other workgroups of the cluster read it.  (An agent-scope store would be written
+// through to memory, one partial line at a time.)
+__device__ __forceinline__ void xpublish(u64* p, u64 v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 __device__ __forceinline__ u64 pack_word(float v, unsigned tag)
 {
     return (u64)__float_as_uint(v) | ((u64)tag << 32);
@@ -181,6 +191,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Streaming access through buffer descriptors: one descriptor per item (4 scalar registers),
 // a loop-invariant 32-bit per-thread byte offset and a scalar per-frame byte offset.  This keeps
 // the address arithmetic of the 17-20 loads per thread and frame out of the vector registers.
+#ifndef LAST_LOAD_AUX
+#define LAST_LOAD_AUX 0    // cache policy of the streaming loads (2 = non-temporal measured slower)
+#endif
+#ifndef LAST_STORE_AUX
+#define LAST_STORE_AUX 0   // cache policy of the streaming stores
+#endif
 typedef __amdgpu_buffer_rsrc_t buf_t;
 __device__ __forceinline__ buf_t make_buf(const void* p, unsigned bytes)
 {
@@ -188,11 +204,11 @@ __device__ __forceinline__ buf_t make_buf(const void* p, unsigned bytes)
 }
 __device__ __forceinline__ float buf_load_nt(buf_t r, unsigned voff, unsigned soff)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 2));
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, LAST_LOAD_AUX));
 }
 __device__ __forceinline__ void buf_store_nt(float v, buf_t r, unsigned voff, unsigned soff)
 {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 2);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, LAST_STORE_AUX);
 }
 __device__ __forceinline__ float buf_load(buf_t r, unsigned voff, unsigned soff)
 {
@@ -216,11 +232,14 @@ __device__ __forceinline__ void sgather3(const void* p, v16u& a, v16u& b, v16u& 
                  "s_waitcnt lgkmcnt(0)"
                  : "=&s"(a), "=&s"(b), "=&s"(c) : "s"(p) : "memory");
 }
-__device__ __forceinline__ void sgather1(const void* p, v16u& a)
+__device__ __forceinline__ void sgather4(const void* p, const void* q, v16u& a, v16u& b, v16u& c, v16u& d)
 {
-    asm volatile("s_load_dwordx16 %0, %1, 0x0 glc\n\t"
+    asm volatile("s_load_dwordx16 %0, %4, 0x0 glc\n\t"
+                 "s_load_dwordx16 %1, %4, 0x40 glc\n\t"
+                 "s_load_dwordx16 %2, %4, 0x80 glc\n\t"
+                 "s_load_dwordx16 %3, %5, 0x0 glc\n\t"
                  "s_waitcnt lgkmcnt(0)"
-                 : "=&s"(a) : "s"(p) : "memory");
+                 : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d) : "s"(p), "s"(q) : "memory");
 }
 // number of leading words (of 8) whose tag matches, and their sum in fixed order
 __device__ __forceinline__ bool block_ready(const v16u& v, int count, unsigned tag)
@@ -333,7 +352,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
         u64* xbase = a.xa + (size_t)g.cg * 2 * a.XS * kClXK;
 
         if (tid < kClMaxR) {
-            ap_s[tid] = (g.r0 + tid == 0 && tid < g.nr) ? 1.f : 0.f;
+            ap_s[tid] = (g.r0 == 0 && tid == 0) ? 1.f : 0.f;
             ap_s[kClMaxR + tid] = 0.f;
             bl_s[tid] = 0.f;
             bl_s[kClMaxR + tid] = 0.f;
@@ -397,13 +416,13 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             u64* xs = xbase + (size_t)(gstep & 1) * a.XS * kClXK;
             if (aux) {
                 float av = 0.f;
-                if (lane < g.nr) av = ap_s[par * kClMaxR + lane] + bl_s[(par ^ 1) * kClMaxR + lane];
+                if (lane < g.nr) av = ap_s[par * kClMaxR + lds_row(lane)] + bl_s[(par ^ 1) * kClMaxR + lds_row(lane)];
                 const int mu_own = wave_max_dpp((lane < g.nr) ? float_exponent(av) : -127);
                 if (i <= mid) {
                     if (lane < g.nr) ah[(size_t)i * C + g.r0 + lane] = av;
                     if (lane == 0 && g.k == 0) Sa[i] = sig;
                 }
-                if (i < nex && lane == 0) xstore(xs + (size_t)C * kClXK + g.k, pack_int(mu_own, tag));
+                if (i < nex && lane == 0) xpublish(xs + (size_t)C * kClXK + g.k, pack_int(mu_own, tag));
             }
             if (i == mid) {
                 if (aux && __builtin_amdgcn_ballot_w64(dead != 0) != 0 && lane == 0) ctl_s[40] = 1;
@@ -429,15 +448,28 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             if (!aux) {
                 // ---- FMA loop, hand-over between the two halves, publish
                 const int P = ctl_s[par];
+                // a_i for the 17 rows of this half: five 16-byte LDS reads per array, issued together
+                float av[20];
+                {
+                    const float4* pa = (const float4*)(ap_s + par * kClMaxR + half * 20);
+                    const float4* pb = (const float4*)(bl_s + (par ^ 1) * kClMaxR + half * 20);
+#pragma unroll
+                    for (int q4 = 0; q4 < 5; ++q4) {
+                        const float4 x = pa[q4], y = pb[q4];
+                        av[4 * q4] = x.x + y.x; av[4 * q4 + 1] = x.y + y.y;
+                        av[4 * q4 + 2] = x.z + y.z; av[4 * q4 + 3] = x.w + y.w;
+                    }
+                }
+                auto a_of = [&](int r) __attribute__((always_inline)) { return av[r]; };
                 float acc0 = 0.f, acc1 = 0.f;
-                auto a_of = [&](int r) __attribute__((always_inline)) {        // a_i[rb + r]
-                    return ap_s[par * kClMaxR + rb + r] + bl_s[(par ^ 1) * kClMaxR + rb + r];
-                };
 #pragma unroll
                 for (int r = 0; r < kClRT; ++r) {
-                    const float pr = a_of(r) * E[S][r];
-                    if (r & 1) acc1 += pr; else acc0 += pr;
-                    if (c == 0) bl_s[par * kClMaxR + rb + r] = __builtin_ldexpf(pr, sc[S] - P);
+                    if (r & 1) acc1 = fmaf(av[r], E[S][r], acc1); else acc0 = fmaf(av[r], E[S][r], acc0);
+                }
+                if (c == 0) {
+#pragma unroll
+                    for (int r = 0; r < kClRT; ++r)
+                        bl_s[par * kClMaxR + half * 20 + r] = __builtin_ldexpf(av[r] * E[S][r], sc[S] - P);
                 }
                 float pub = __builtin_ldexpf(acc0 + acc1, sc[S] - P);
                 if (half == 1) {
@@ -447,7 +479,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     int spins = 0;
                     while (flag_s[wave] != i + 1 && ++spins < (1 << 22)) { }
                     pub += ((volatile float*)pacc_s)[c];
-                    if (exch && colok && c >= 1) xstore(xs + (size_t)c * kClXK + g.k, pack_word(pub, tag));
+                    if (exch && colok && c >= 1) xpublish(xs + (size_t)c * kClXK + g.k, pack_word(pub, tag));
                 }
                 LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= mid && colok) {
@@ -481,20 +513,22 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 int mu = 0;
                 if ((grn > 0 || aux) && !dead) {
                     v16u v0, v1, v2, vh;
+                    // the aux wave has nothing else to do: do not poll before the producers can
+                    // have published (a poll served too early costs a whole extra round trip)
+                    if (aux)
+                        for (int dly = 0; dly < a.aux_delay; ++dly) __builtin_amdgcn_s_sleep(4);
                     // rows beyond the owned range are still loaded (inside the buffer) and ignored
                     const void* rowp = xs + (size_t)(g.r0 + min(gr0, g.nr - 1)) * kClXK;
                     // the start state (q = 0) receives no label arcs: its row is never written
                     const bool skip0 = g.r0 + gr0 == 0;
                     int np = 0;
                     for (;;) {
-                        sgather3(rowp, v0, v1, v2);
+                        if (aux) sgather4(rowp, xs + (size_t)C * kClXK, v0, v1, v2, vh);
+                        else sgather3(rowp, v0, v1, v2);
                         bool ok = (grn < 1 || skip0 || block_ready(v0, KT, tag))
                                   && (grn < 2 || block_ready(v1, KT, tag))
                                   && (grn < 3 || block_ready(v2, KT, tag));
-                        if (aux) {
-                            sgather1(xs + (size_t)C * kClXK, vh);
-                            ok = ok && block_ready(vh, KT, tag);
-                        }
+                        if (aux) ok = ok && block_ready(vh, KT, tag);
                         if (ok) break;
                         if (++np > a.spin_limit) { dead = 1; break; }
                     }
@@ -510,9 +544,9 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                 }
                 if (aux) LAST_MARK(a, 1, i, 1);
                 if (lane == 0) {
-                    if (grn > 0) ap_s[(par ^ 1) * kClMaxR + gr0] = s0;
-                    if (grn > 1) ap_s[(par ^ 1) * kClMaxR + gr0 + 1] = s1;
-                    if (grn > 2) ap_s[(par ^ 1) * kClMaxR + gr0 + 2] = s2;
+                    if (grn > 0) ap_s[(par ^ 1) * kClMaxR + lds_row(gr0)] = s0;
+                    if (grn > 1) ap_s[(par ^ 1) * kClMaxR + lds_row(gr0 + 1)] = s1;
+                    if (grn > 2) ap_s[(par ^ 1) * kClMaxR + lds_row(gr0 + 2)] = s2;
                 }
                 if (aux) {
                     // exponent step for the next publish, from magnitudes every workgroup has seen
@@ -689,7 +723,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     for (int j = 1; j < kClNC; ++j) acc = fmaf(E[S][ri][j], bv[j], acc);
                     const float tot = wave_sum_dpp(acc);
                     if (exch && lane == 0 && ri < nrw)
-                        xstore(xs + row, pack_word(__builtin_ldexpf(tot, sr[S][ri] - P_cur), tag));
+                        xpublish(xs + row, pack_word(__builtin_ldexpf(tot, sr[S][ri] - P_cur), tag));
                 }
                 LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= ph1) {

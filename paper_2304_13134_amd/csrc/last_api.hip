@@ -207,6 +207,8 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
     a.scale = scale; a.accumulate = accumulate;
     a.spin_limit = 1 << 20;
+    a.aux_delay = 4;
+    if (const char* e = std::getenv("LAST_AUX_DELAY")) a.aux_delay = std::atoi(e);
     auto go = [&](auto KC) {
         constexpr int KT = decltype(KC)::value;
         if (GAMMA && accumulate)
