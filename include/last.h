@@ -168,6 +168,9 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
 
 const char* last_status_string(last_status_t status);
 
+/* Text of the HIP error behind the most recent LAST_ERR_HIP (diagnostics). */
+const char* last_hip_error_string(void);
+
 /* Library version and the kernel variant a call would use, for diagnostics:
  * 0 = one workgroup per item, 1 = cooperating workgroups per item. */
 int32_t last_version(void);

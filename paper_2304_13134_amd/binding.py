@@ -22,7 +22,7 @@ WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
 
 EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
            "last_intersect_reference", "last_shortest_path", "last_status_string",
-           "last_version", "last_kernel_variant"]
+           "last_version", "last_kernel_variant", "last_hip_error_string"]
 
 
 class LastContext(ctypes.Structure):
@@ -78,6 +78,7 @@ def load_library():
     lib.last_status_string.restype = ctypes.c_char_p
     lib.last_status_string.argtypes = [i32]
     lib.last_version.restype = i32
+    lib.last_hip_error_string.restype = ctypes.c_char_p
     lib.last_kernel_variant.restype = i32
     lib.last_kernel_variant.argtypes = [ctypes.POINTER(LastWeights), ctypes.POINTER(LastContext), i32]
     _lib = lib
@@ -86,7 +87,10 @@ def load_library():
 
 def _check(code):
     if code != 0:
-        raise LastError(code, load_library().last_status_string(code).decode())
+        text = load_library().last_status_string(code).decode()
+        if code == 7:
+            text += ": " + load_library().last_hip_error_string().decode()
+        raise LastError(code, text)
 
 
 def _ptr(t):
@@ -134,6 +138,26 @@ def shared_emb_weights(f, e, W):
     return LastWeights(WEIGHTS_SHARED_EMB, B, T, None, f.data_ptr(), e.data_ptr(), W.data_ptr(), H)
 
 
+class SharedEmb(tuple):
+    """Inputs of the on-the-fly weight function: (f [B,T,H], e [C,H], W [H,V+1]), bfloat16."""
+
+    def __new__(cls, f, e, W):
+        return super().__new__(cls, (f, e, W))
+
+
+def _weights_and_context(w, order):
+    """(LastWeights, LastContext, device, B) for a dense tensor or a SharedEmb triple."""
+    if isinstance(w, SharedEmb):
+        f, e, W = w
+        wt = shared_emb_weights(f, e, W)
+        V = W.shape[1] - 1
+        cx = context(V, order)
+        if cx.num_states != e.shape[0] or e.shape[1] != f.shape[2] or W.shape[0] != f.shape[2]:
+            raise ValueError("f, e, W do not match the context dependency")
+        return wt, cx, f.device, f.shape[0]
+    return dense_weights(w), _dense_ctx(w, order), w.device, w.shape[0]
+
+
 def _dense_ctx(w, order):
     V = w.shape[3] - 1
     cx = context(V, order)
@@ -153,10 +177,13 @@ def last_kernel_variant(weights, cx, op):
 def last_shortest_distance(w, lengths, order=1, semiring="log", item_status=None):
     """dist [B] float32 (device).  semiring: "log" or "tropical"."""
     lib = load_library()
-    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    wt, cx, device, B = _weights_and_context(w, order)
     _dev_tensor(lengths, torch.int32, "lengths")
-    dist = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
-    ws = workspace(last_workspace_bytes(wt, cx, OP_SHORTEST_DISTANCE), w.device)
+    dist = torch.empty(B, dtype=torch.float32, device=device)
+    nbytes = last_workspace_bytes(wt, cx, OP_SHORTEST_DISTANCE)
+    if nbytes == 0:
+        raise LastError(6, "combination not supported")
+    ws = workspace(nbytes, device)
     sr = LAST_LOG if semiring == "log" else LAST_TROPICAL
     _check(lib.last_shortest_distance(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), sr,
                                       _ptr(dist), _ptr(item_status), _ptr(ws), ws.numel(), _stream()))

@@ -1,0 +1,302 @@
+// Trigram (context size 2) lattice with arc weights computed on the fly
+// (arXiv 2304.13134, Section 4.1: weights are produced frame by frame during
+// the topological visit and never stored), for the shared-embedding weight
+// function  w[t][q][:] = bf16(tanh(f[t] + e[q])) @ W  with float32 accumulation.
+//
+// Ownership follows the structure of the full 2-gram context dependency: the
+// label arcs into state (b,y) all leave states whose LAST label is b, i.e.
+// (b) and (a,b) for every a.  One workgroup per item and last label b owns
+// exactly those V+1 source states (plus a private copy of the start state):
+//   * their rows of e stay in LDS for the whole pass,
+//   * per frame it forms the hidden tile tanh(f_t + e_q) (bf16, in LDS), runs
+//     the [rows x hidden] x [hidden x (V+1)] contraction on the matrix cores
+//     (v_mfma_f32_16x16x32_bf16; the W fragments live in registers), and feeds
+//     the resulting weights straight into the log-sum-exp of the recursion,
+//   * the fully reduced forward weight of (b,y) is sent to workgroup y, which
+//     owns (b,y) as a source state and adds the empty-label arc itself.
+// The per-frame exchange is therefore a V x V transpose between the V
+// workgroups of an item (64-bit words [value|tag], agent-scope atomics, bounded
+// polls; the workgroups of one item span more than one XCD).
+// Values are log-domain float32 relative to a running offset that advances by a
+// predicted amount per frame (same predictor as the bigram cluster kernel), so
+// magnitudes stay O(10) while log-partition values reach several thousand.
+#pragma once
+#include <type_traits>
+
+#include "common.hpp"
+#include "cluster_kernels.hpp"
+
+namespace last {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kFuThreads = 512;
+constexpr int kFuMaxRows = 80;      // V + 2 rows padded to a multiple of 16
+constexpr int kFuMaxNT = 5;         // (V + 1) labels in tiles of 16
+constexpr int kFuWS = 81;           // row stride of the weight tile in LDS (floats)
+constexpr int kFuMaxKS = 16;        // hidden / 32
+
+struct FusedArgs {
+    const __bf16* f;     // [B][T][H]
+    const __bf16* e;     // [C][H]
+    const __bf16* W;     // [H][V+1]
+    const int* len;
+    float* dist;
+    int* item_status;
+    float* alpha_ws;     // [B][T+1][C] forward weights relative to offs (null: not stored)
+    double* offs;        // [B][T+1] running offset
+    float* part;         // [B][V] per-workgroup log-sum-exp of the last frame
+    double* Aend;        // [B] running offset of the last frame (NaN for an invalid length)
+    u64* xb;             // [ncl][2][V+1][XW] exchange words; row V = headers
+    int B, T, V, H, C;
+    int ncl, XW;
+    int spin_limit;
+};
+
+__device__ __forceinline__ float word_value(u64 x) { return __uint_as_float((unsigned)x); }
+
+__device__ __forceinline__ float fast_tanh(float x)
+{
+    // 1 - 2 / (1 + 2^(2 x log2 e)); saturates correctly at both ends
+    const float ex = __builtin_amdgcn_exp2f(x * (2.f * kLog2e));
+    return fmaf(-2.f, __builtin_amdgcn_rcpf(1.f + ex), 1.f);
+}
+
+__device__ __forceinline__ float log_add_f(float x, float y)
+{
+    const float m = fmaxf(x, y);
+    if (m == LAST_NEG_INF) return m;
+    return m + __logf(1.f + __expf(fminf(x, y) - m));
+}
+
+__device__ __forceinline__ u64 poll_tag32(const u64* p, unsigned tag, int limit, int& dead)
+{
+    u64 x = xload(p);
+    if (dead) return x;
+    int n = 0;
+    while ((unsigned)(x >> 32) != tag) {
+        if (++n > limit) { dead = 1; break; }
+        __builtin_amdgcn_s_sleep(1);
+        x = xload(p);
+    }
+    return x;
+}
+
+// local row r of workgroup b (1..V): 0 -> start state, 1 -> (b), 1 + a -> (a,b)
+__device__ __forceinline__ int fused_state(int V, int b, int r)
+{
+    if (r == 0) return 0;
+    if (r == 1) return b;
+    return 1 + V + (r - 2) * V + (b - 1);
+}
+
+// Hidden tile + contraction for one frame: leaves w[r][y] (float32) in w_s.
+// e_s [R][H] bf16, hid_s [Mpad][KC + 8] bf16, wfrag: this wave's fragments of W.
+__device__ __forceinline__ void fused_weights_frame(const __bf16* __restrict__ ft, const __bf16* e_s,
+                                                    __bf16* hid_s, float* w_s,
+                                                    const bf16x8 (&wfrag)[kFuMaxKS], int R, int Mpad,
+                                                    int H, int KC, int NT)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int HS = KC + 8;
+    const int nrg = kFuThreads / KC;                 // row groups of the tanh pass
+    const int kh = tid % KC, rg = tid / KC;
+    floatx4 acc[kFuMaxRows / 16];
+#pragma unroll
+    for (int mt = 0; mt < kFuMaxRows / 16; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // the hidden dimension is processed in chunks of KC <= 256 (the fragment index stays static)
+    auto chunk = [&](auto KS0) __attribute__((always_inline)) {
+        constexpr int ks0 = decltype(KS0)::value;
+        const int kc = 32 * ks0;
+        if (rg < nrg) {
+            const float fv = (float)ft[kc + kh];
+            for (int r = rg; r < R; r += nrg) {
+                const float x = fv + (float)e_s[(size_t)r * H + kc + kh];
+                hid_s[r * HS + kh] = (__bf16)fast_tanh(x);
+            }
+        }
+        __syncthreads();
+        if (wave < NT) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                if (32 * ks < KC) {
+#pragma unroll
+                    for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+                        if (16 * mt < Mpad) {
+                            const bf16x8 av = *(const bf16x8*)&hid_s[(16 * mt + (lane & 15)) * HS + 32 * ks + 8 * (lane >> 4)];
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wfrag[ks0 + ks], acc[mt], 0, 0, 0);
+                        }
+                }
+        }
+        __syncthreads();
+    };
+    chunk(std::integral_constant<int, 0>());
+    if (H > 256) chunk(std::integral_constant<int, 8>());
+    if (wave < NT) {
+#pragma unroll
+        for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+            if (16 * mt < Mpad) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
+            }
+    }
+    __syncthreads();
+}
+
+// this wave's fragments of W: lane l holds W[32 ks + 8 (l / 16) + j][16 wave + l % 16], j = 0..7
+__device__ __forceinline__ void fused_load_wfrag(const __bf16* __restrict__ W, int H, int V1,
+                                                 bf16x8 (&wfrag)[kFuMaxKS])
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = 16 * wave + (lane & 15);
+#pragma unroll
+    for (int ks = 0; ks < kFuMaxKS; ++ks) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = 32 * ks + 8 * (lane >> 4) + j;
+            wfrag[ks][j] = (k < H && n < V1) ? W[(size_t)k * V1 + n] : (__bf16)0.f;
+        }
+    }
+}
+
+// Shortest distance in the log semiring with on-the-fly weights (Eq. 2 visited
+// frame by frame, Section 4.1).  Grid: ncl * V workgroups of 512 threads.
+__global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
+{
+    extern __shared__ unsigned char smem_raw[];
+    const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
+    const int Mpad = (R + 15) / 16 * 16;
+    const int KC = H < 256 ? H : 256;
+    const int NT = (V1 + 15) / 16;
+    __bf16* e_s = (__bf16*)smem_raw;                                  // [R][H]
+    __bf16* hid_s = e_s + (size_t)R * H;                              // [Mpad][KC + 8]
+    float* w_s = (float*)(hid_s + (size_t)Mpad * (KC + 8));           // [Mpad][kFuWS]
+    float* al_s = w_s + (size_t)Mpad * kFuWS;                         // [2][kFuMaxRows] forward weights
+    float* bl_s = al_s + 2 * kFuMaxRows;                              // [kFuMaxRows] empty-label terms
+    float* red = bl_s + kFuMaxRows;                                   // [32]
+    float* hdr_s = red + 32;                                          // [64]
+    int* ctl_s = (int*)(hdr_s + 64);                                  // [8]
+
+    const int tid = threadIdx.x;
+    const int cl = blockIdx.x / V, b = blockIdx.x % V + 1;
+    // zero the pad rows of the hidden tile once; they stay zero
+    for (int i = tid; i < Mpad * (KC + 8); i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    // rows of e owned by this workgroup
+    for (int i = tid; i < R * H; i += kFuThreads) {
+        const int r = i / H, k = i - r * H;
+        e_s[i] = a.e[(size_t)fused_state(V, b, r) * H + k];
+    }
+    bf16x8 wfrag[kFuMaxKS];
+    fused_load_wfrag(a.W, H, V1, wfrag);
+    unsigned gstep = 0;
+    __syncthreads();
+
+    for (int item = cl; item < a.B; item += a.ncl) {
+        int L = a.len[item];
+        const bool bad = L < 0 || L > a.T;
+        if (bad) L = 0;
+        u64* xbase = a.xb + (size_t)cl * 2 * (V + 1) * a.XW;
+        float* aws = a.alpha_ws ? a.alpha_ws + (size_t)item * (a.T + 1) * a.C : nullptr;
+        if (tid < kFuMaxRows) al_s[tid] = (tid == 0) ? 0.f : LAST_NEG_INF;
+        if (tid == 0) ctl_s[0] = 0;
+        __syncthreads();
+        if (aws && tid < R && (tid > 0 || b == 1)) aws[fused_state(V, b, tid)] = al_s[tid];
+        if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1)] = 0.0;
+        double A = 0.0;                       // running offset, identical in every workgroup
+        float P_cur = 0.f, P_prev = 0.f, mu_prev = 0.f;
+        int dead = 0;
+        for (int t = 0; t < L; ++t) {
+            const int par = t & 1;
+            const float* al = al_s + par * kFuMaxRows;
+            float* an = al_s + (par ^ 1) * kFuMaxRows;
+            const unsigned tag = gstep + 1;
+            u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
+            // header: largest forward weight among the own states (known since the last frame)
+            {
+                float mx = (tid < R) ? al[tid] : LAST_NEG_INF;
+                mx = block_max(mx, red);
+                if (tid == 0) xstore(xs + (size_t)V * a.XW + (b - 1), pack_word(mx, tag));
+            }
+            fused_weights_frame(a.f + ((size_t)item * a.T + t) * H, e_s, hid_s, w_s, wfrag, R, Mpad, H, KC, NT);
+            // label arcs: (b), (a,b) --y--> (b,y), fully reduced here, sent to workgroup y
+            if (tid >= 1 && tid <= V) {
+                const int y = tid;
+                float m = LAST_NEG_INF;
+                for (int r = 1; r < R; ++r) m = fmaxf(m, al[r] + w_s[r * kFuWS + y]);
+                float p = LAST_NEG_INF;
+                if (m != LAST_NEG_INF) {
+                    float s = 0.f;
+                    for (int r = 1; r < R; ++r) s += __expf(al[r] + w_s[r * kFuWS + y] - m);
+                    p = m + __logf(s) - P_cur;
+                }
+                xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
+            }
+            // empty-label arcs of the own states; label arc start -> (b)
+            if (tid < R) bl_s[tid] = al[tid] + w_s[tid * kFuWS] - P_cur;
+            if (tid == R) bl_s[R] = al[0] + w_s[b] - P_cur;          // row 0, label b
+            __syncthreads();
+            // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
+            float hv = LAST_NEG_INF;
+            if (tid >= 1 && tid <= V) {
+                const u64 x = poll_tag32(xs + (size_t)(b - 1) * a.XW + (tid - 1), tag, a.spin_limit, dead);
+                an[1 + tid] = log_add_f(word_value(x), bl_s[1 + tid]);
+            } else if (tid == 0) {
+                an[0] = bl_s[0];
+                an[1] = log_add_f(bl_s[R], bl_s[1]);
+            } else if (tid >= 128 && tid < 128 + V) {
+                const u64 x = poll_tag32(xs + (size_t)V * a.XW + (tid - 128), tag, a.spin_limit, dead);
+                hv = word_value(x);
+            }
+            const float mu = block_max(hv, red);          // contains the barriers that publish `an`
+            if (__syncthreads_or(dead)) ctl_s[0] = 1;
+            // offset bookkeeping, identical everywhere
+            const float G = mu - mu_prev + P_prev;
+            const float P_next = mu + 2.f * G - P_cur;
+            A += (double)P_cur;
+            mu_prev = mu; P_prev = P_cur; P_cur = P_next;
+            if (aws && tid < R && (tid > 0 || b == 1)) aws[(size_t)(t + 1) * a.C + fused_state(V, b, tid)] = an[tid];
+            if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1) + t + 1] = A;
+            gstep += 1;
+            __syncthreads();
+        }
+        // all states of the last frame are final: per-workgroup log-sum-exp, combined by fused_finalize
+        {
+            const float* al = al_s + (L & 1) * kFuMaxRows;
+            const bool mine = tid < R && (tid > 0 || b == 1);
+            float v = mine ? al[tid] : LAST_NEG_INF;
+            const float mx = block_max(v, red);
+            float s = (mine && mx != LAST_NEG_INF) ? __expf(v - mx) : 0.f;
+            s = block_sum(s, red);
+            if (tid == 0) {
+                a.part[(size_t)item * V + (b - 1)] = (mx == LAST_NEG_INF) ? LAST_NEG_INF : mx + __logf(s);
+                if (b == 1) {
+                    a.Aend[item] = bad ? __builtin_nan("") : A;
+                    if (a.item_status) a.item_status[item] = bad ? kItemBadLength : (ctl_s[0] ? kItemTimeout : kItemOk);
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// D[item] = offset + log-sum-exp over the workgroups' partial values
+__global__ void fused_finalize_kernel(const float* __restrict__ part, const double* __restrict__ Aend,
+                                      int B, int V, float* __restrict__ dist, double* __restrict__ Dws)
+{
+    const int item = blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= B) return;
+    const double A = Aend[item];
+    float mx = LAST_NEG_INF;
+    for (int j = 0; j < V; ++j) mx = fmaxf(mx, part[(size_t)item * V + j]);
+    float s = 0.f;
+    for (int j = 0; j < V; ++j) s += expf(part[(size_t)item * V + j] - mx);
+    const double D = (A != A) ? __builtin_nan("") : A + (double)mx + (double)logf(s);
+    dist[item] = (float)D;
+    if (Dws) Dws[item] = D;
+}
+
+}  // namespace last

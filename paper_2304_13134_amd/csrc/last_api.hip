@@ -8,6 +8,7 @@
 #include "solo_kernels.hpp"
 #include "numerator_kernels.hpp"
 #include "cluster_kernels.hpp"
+#include "fused_kernels.hpp"
 
 #include <cstdlib>
 #include <type_traits>
@@ -230,16 +231,94 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     }
 }
 
+hipError_t g_last_hip_error = hipSuccess;     // diagnostics only: what the last failing HIP call said
+
+last_status_t hip_status()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) g_last_hip_error = e;
+    return e == hipSuccess ? LAST_OK : LAST_ERR_HIP;
+}
+
+// geometry of the fused trigram path (see fused_kernels.hpp)
+constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel also has a little static LDS
+struct FusedPlan {
+    bool ok;
+    int ncl, XW, KC, R, Mpad;
+    size_t lds;
+};
+
+FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
+{
+    FusedPlan p{};
+    if (wt->kind != LAST_WEIGHTS_SHARED_EMB || s.order != 2) return p;
+    const int H = wt->hidden;
+    if (s.V > 64 || H % 32 != 0 || H > 512 || (H > 256 && H % 256 != 0)) return p;
+    p.R = s.V + 2;
+    p.Mpad = (p.R + 15) / 16 * 16;
+    p.KC = H < 256 ? H : 256;
+    p.ncl = 256 / s.V;                        // one workgroup per compute unit
+    if (p.ncl > s.B) p.ncl = s.B;
+    p.XW = (s.V + 7) / 8 * 8;
+    p.lds = (size_t)p.R * H * 2 + (size_t)p.Mpad * (p.KC + 8) * 2 + (size_t)p.Mpad * kFuWS * 4
+            + (size_t)(3 * kFuMaxRows + 32 + 64 + 8) * 4;
+    p.ok = p.lds <= (size_t)kFusedMaxLds;
+    return p;
+}
+
+struct FusedWs {
+    float* alpha;
+    double* offs;
+    float* part;
+    double* Aend;
+    double* D;
+    u64* xb;
+    size_t xwords;
+};
+
+FusedWs carve_fused(Carver& cv, const Shape& s, const FusedPlan& p, bool keep_alpha)
+{
+    FusedWs f;
+    f.alpha = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
+    f.offs = cv.take<double>((size_t)s.B * (s.T + 1));
+    f.part = cv.take<float>((size_t)s.B * s.V);
+    f.Aend = cv.take<double>((size_t)s.B);
+    f.D = cv.take<double>((size_t)s.B);
+    f.xwords = (size_t)p.ncl * 2 * (s.V + 1) * p.XW;
+    f.xb = cv.take<u64>(f.xwords);
+    return f;
+}
+
+last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const FusedWs& f,
+                                   const last_weights_t* wt, const int* lengths, float* dist,
+                                   int* item_status, bool keep_alpha, hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute((const void*)fused_forward_kernel,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kFusedMaxLds);
+        if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
+    FusedArgs a;
+    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.W = (const __bf16*)wt->W;
+    a.len = lengths; a.dist = dist; a.item_status = item_status;
+    a.alpha_ws = keep_alpha ? f.alpha : nullptr; a.offs = f.offs; a.part = f.part; a.Aend = f.Aend;
+    a.xb = f.xb;
+    a.B = s.B; a.T = s.T; a.V = s.V; a.H = wt->hidden; a.C = s.C;
+    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20;
+    hipLaunchKernelGGL(fused_forward_kernel, dim3(p.ncl * s.V), dim3(kFuThreads), p.lds, st, a);
+    hipLaunchKernelGGL(fused_finalize_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st,
+                       (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D);
+    return hip_status();
+}
+
 last_status_t check_ws(void* ws, size_t have, size_t need)
 {
     if (need == 0) return LAST_OK;
     if (!ws || ((uintptr_t)ws % kAlign) != 0 || have < need) return LAST_ERR_WORKSPACE;
     return LAST_OK;
-}
-
-last_status_t hip_status()
-{
-    return hipGetLastError() == hipSuccess ? LAST_OK : LAST_ERR_HIP;
 }
 
 template <typename F>
@@ -257,6 +336,8 @@ void dispatch_group(int V1, F&& f)
 extern "C" {
 
 int32_t last_version(void) { return 1; }
+
+const char* last_hip_error_string(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* last_status_string(last_status_t status)
 {
@@ -289,6 +370,14 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
     Shape s;
     if (check_common(weights, context, &s) != LAST_OK) return 0;
     Carver cv(nullptr);
+    if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
+        const FusedPlan fp = fused_plan(s, weights);
+        if (!fp.ok) return 0;
+        if (op == LAST_OP_SHORTEST_DISTANCE) carve_fused(cv, s, fp, false);
+        else if (op == LAST_OP_ARC_POSTERIORS) carve_fused(cv, s, fp, true);
+        else return 0;
+        return cv.used;
+    }
     const ClusterPlan plan = cluster_plan(s, weights->kind);
     switch (op) {
     case LAST_OP_SHORTEST_DISTANCE:
@@ -322,10 +411,18 @@ last_status_t last_shortest_distance(const last_weights_t* weights, const int32_
     if (rc != LAST_OK) return rc;
     if (!lengths || !dist) return LAST_ERR_NULL;
     if (semiring != LAST_LOG && semiring != LAST_TROPICAL) return LAST_ERR_SEMIRING;
-    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
+        const FusedPlan fp = fused_plan(s, weights);
+        if (!fp.ok || semiring != LAST_LOG) return LAST_ERR_UNSUPPORTED;
+        rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_SHORTEST_DISTANCE, 0));
+        if (rc != LAST_OK) return rc;
+        Carver cvf(ws);
+        const FusedWs fw = carve_fused(cvf, s, fp, false);
+        return launch_fused_forward(s, fp, fw, weights, lengths, dist, item_status, false, st);
+    }
     rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_SHORTEST_DISTANCE, 0));
     if (rc != LAST_OK) return rc;
-    hipStream_t st = (hipStream_t)hip_stream;
     const SoloLayout l = solo_layout(s);
     const Ctx c = make_ctx(s);
     const ClusterPlan plan = cluster_plan(s, weights->kind);
