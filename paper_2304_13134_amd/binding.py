@@ -192,16 +192,30 @@ def last_shortest_distance(w, lengths, order=1, semiring="log", item_status=None
 
 def last_arc_posteriors(w, lengths, order=1, dw=None, scale=1.0, accumulate=False,
                         item_status=None):
-    """(dist [B], dw [B,T,C,V+1]) on the device; dw = scale * arc marginals."""
+    """Dense weights: (dist [B], dw [B,T,C,V+1]) on the device; dw = scale * arc marginals.
+    SharedEmb weights: (dist [B], (df [B,T,H], de [C,H], dW [H,V+1])), float32, the chain of
+    the marginals through the weight function; `dw` may be such a triple to write into."""
     lib = load_library()
-    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    wt, cx, device, B = _weights_and_context(w, order)
     _dev_tensor(lengths, torch.int32, "lengths")
-    if dw is None:
-        dw = torch.empty_like(w)
-    _dev_tensor(dw, torch.float32, "dw")
-    dist = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
-    g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
-    ws = workspace(last_workspace_bytes(wt, cx, OP_ARC_POSTERIORS), w.device)
+    dist = torch.empty(B, dtype=torch.float32, device=device)
+    if isinstance(w, SharedEmb):
+        f, e, W = w
+        if dw is None:
+            dw = tuple(torch.empty(t.shape, dtype=torch.float32, device=device) for t in (f, e, W))
+        for t, n in zip(dw, ("df", "de", "dW")):
+            _dev_tensor(t, torch.float32, n)
+        g = LastGrads(None, dw[0].data_ptr(), dw[1].data_ptr(), dw[2].data_ptr(),
+                      int(bool(accumulate)), float(scale))
+    else:
+        if dw is None:
+            dw = torch.empty_like(w)
+        _dev_tensor(dw, torch.float32, "dw")
+        g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
+    nbytes = last_workspace_bytes(wt, cx, OP_ARC_POSTERIORS)
+    if nbytes == 0:
+        raise LastError(6, "combination not supported")
+    ws = workspace(nbytes, device)
     _check(lib.last_arc_posteriors(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), _ptr(dist),
                                    ctypes.byref(g), _ptr(item_status), _ptr(ws), ws.numel(),
                                    _stream()))

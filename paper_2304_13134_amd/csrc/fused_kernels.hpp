@@ -299,4 +299,386 @@ __global__ void fused_finalize_kernel(const float* __restrict__ part, const doub
     if (Dws) Dws[item] = D;
 }
 
+
+// ---------------------------------------------------------------------------
+// Backward side: beta recursion, arc marginals (Eq. 1) and their chain through
+// the weight function.  With h = bf16(tanh(f_t + e_q)) and gamma the marginals,
+//   dW[k][y] += h[k] gamma[q][y],   dpre[q][k] = (sum_y gamma[q][y] W[k][y]) (1 - h[k]^2),
+//   de[q][k] += dpre[q][k],         df[t][k]   += sum_q dpre[q][k]
+// (the rounding of h is treated as the identity when differentiating).
+// gamma is split into two bf16 halves (hi + lo) so that the matrix-core
+// contractions keep 16 significant bits of it.
+// ---------------------------------------------------------------------------
+
+constexpr int kFuGS = 104;          // row stride (bf16) of the marginal tiles in LDS; 96 used
+constexpr int kFuKT = 4;            // 16-wide tiles of the hidden dimension per wave (8 waves x 4 x 16 = 512)
+
+struct FusedBwdArgs {
+    const __bf16* f;
+    const __bf16* e;
+    const __bf16* W;
+    const bf16x8* Wt;        // W as B-operand fragments of the dpre contraction: [H/16][3][64]
+    const int* len;
+    const float* alpha_ws;   // [B][T+1][C] forward weights relative to offs
+    const double* offs;      // [B][T+1]
+    const double* Dws;       // [B] shortest distance
+    float* beta_ws;          // [B][T+1][C] backward weights relative to (D - offs)
+    float* df;               // [B][T][H]
+    float* de;               // [C][H]
+    float* dW;               // [H][V+1]
+    float scale;
+    int* item_status;
+    u64* xb;
+    int B, T, V, H, C;
+    int ncl, XW;
+    int spin_limit;
+    int nch, TC;             // frame chunks of the dW kernel
+};
+
+// fragments of W for C[r][k] = sum_y A[r][y] B[y][k], B[y][k] = W[k][y]:
+// lane l of fragment (kt, ys) holds W[16 kt + l % 16][32 ys + 8 (l / 16) + j], j = 0..7
+__global__ void fused_pack_wt_kernel(const __bf16* __restrict__ W, int H, int V1, bf16x8* __restrict__ Wt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = (H / 16) * 3 * 64;
+    if (i >= n) return;
+    const int lane = i & 63, ys = (i >> 6) % 3, kt = (i >> 6) / 3;
+    const int k = 16 * kt + (lane & 15);
+    bf16x8 v;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int y = 32 * ys + 8 * (lane >> 4) + j;
+        v[j] = (y < V1) ? W[(size_t)k * V1 + y] : (__bf16)0.f;
+    }
+    Wt[i] = v;
+}
+
+// Hidden tile over the whole hidden dimension (kept for the gradient
+// contractions) + weights of one frame.  e is read from global memory (it stays
+// in L2); hid_s [.][H + 8] bf16, rows >= R stay zero.
+__device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const __bf16* __restrict__ e,
+                                                   int V, int b, __bf16* hid_s, float* w_s,
+                                                   const bf16x8 (&wfrag)[kFuMaxKS], int R, int Mpad,
+                                                   int H, int NT)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int HS = H + 8;
+    const int nrg = kFuThreads / H;
+    const int kh = tid % H, rg = tid / H;
+    if (rg < nrg) {
+        const float fv = (float)ft[kh];
+        for (int r = rg; r < R; r += nrg) {
+            const float x = fv + (float)e[(size_t)fused_state(V, b, r) * H + kh];
+            hid_s[r * HS + kh] = (__bf16)fast_tanh(x);
+        }
+    }
+    __syncthreads();
+    if (wave < NT) {
+        floatx4 acc[kFuMaxRows / 16];
+#pragma unroll
+        for (int mt = 0; mt < kFuMaxRows / 16; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < kFuMaxKS; ++ks)
+            if (32 * ks < H) {
+#pragma unroll
+                for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+                    if (16 * mt < Mpad) {
+                        const bf16x8 av = *(const bf16x8*)&hid_s[(16 * mt + (lane & 15)) * HS + 32 * ks + 8 * (lane >> 4)];
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wfrag[ks], acc[mt], 0, 0, 0);
+                    }
+            }
+#pragma unroll
+        for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+            if (16 * mt < Mpad) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
+            }
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void split_bf16(float g, __bf16& hi, __bf16& lo)
+{
+    hi = (__bf16)g;
+    lo = (__bf16)(g - (float)hi);
+}
+
+// Marginals of one frame for the rows of this workgroup and the backward
+// weights of the frame before: v[r][y] = w[r][y] + beta'[next(r,y)] - P,
+// beta_t[r] = logsumexp_y v[r][y], gamma[r][y] = exp(alpha'_t[r] + v[r][y]).
+// TRANSPOSED selects the LDS layout of gamma: [r][y] (false) or [y][r] (true).
+template <bool TRANSPOSED>
+__device__ __forceinline__ void fused_rows(const float* w_s, const float* bl, const float* bn_s,
+                                           const float* bs_s, const float* aw_s, float P, int V, int R,
+                                           bool own_start, float* bl_new, __bf16* gh_s, __bf16* gl_s)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int r = wave; r < R; r += kFuThreads / 64) {
+        const bool valid = r > 0 || own_start;
+        const float* nb = (r == 0) ? bs_s : bn_s;
+        const int y0 = lane, y1 = lane + 64;
+        float v0 = LAST_NEG_INF, v1 = LAST_NEG_INF;
+        if (y0 <= V) v0 = w_s[r * kFuWS + y0] + (y0 == 0 ? bl[r] : nb[y0]) - P;
+        if (y1 <= V) v1 = w_s[r * kFuWS + y1] + nb[y1] - P;
+        const float m = wave_max(fmaxf(v0, v1));
+        float sum = (y0 <= V ? __expf(v0 - m) : 0.f) + (y1 <= V ? __expf(v1 - m) : 0.f);
+        sum = wave_sum(sum);
+        if (bl_new && lane == 0) bl_new[r] = valid ? m + __logf(sum) : LAST_NEG_INF;
+        const float ar = aw_s[r];
+        const float g0 = (valid && y0 <= V) ? __expf(ar + v0) : 0.f;
+        const float g1 = (valid && y1 <= V) ? __expf(ar + v1) : 0.f;
+        __bf16 hi, lo;
+        if (y0 <= V) {
+            split_bf16(g0, hi, lo);
+            const int idx = TRANSPOSED ? y0 * kFuGS + r : r * kFuGS + y0;
+            gh_s[idx] = hi; gl_s[idx] = lo;
+        }
+        if (y1 <= V) {
+            split_bf16(g1, hi, lo);
+            const int idx = TRANSPOSED ? y1 * kFuGS + r : r * kFuGS + y1;
+            gh_s[idx] = hi; gl_s[idx] = lo;
+        }
+    }
+}
+
+// Backward recursion over the same ownership as the forward kernel.  What a
+// workgroup needs from the others per frame is beta_{t+1}[(b,y)] for every y
+// (state (b,y) is a row of workgroup y), again a V x V transpose; workgroup 1,
+// which also differentiates the start state, additionally needs beta_{t+1}[(y)].
+// Backward weights are kept relative to D - offs[t], which bounds
+// alpha' + beta' <= 0, so no offset has to be negotiated.  Also forms
+// dpre = (gamma W^T)(1 - h^2) on the matrix cores, accumulates de in registers
+// and adds the column sums into df.
+__global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs a)
+{
+    extern __shared__ unsigned char smem_raw[];
+    const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
+    const int Mpad = (R + 15) / 16 * 16;
+    const int NT = (V1 + 15) / 16;
+    const int HS = H + 8;
+    __bf16* hid_s = (__bf16*)smem_raw;                                // [kFuMaxRows][H + 8]
+    float* w_s = (float*)(hid_s + (size_t)kFuMaxRows * HS);           // [kFuMaxRows][kFuWS]
+    __bf16* gh_s = (__bf16*)(w_s + (size_t)kFuMaxRows * kFuWS);       // [kFuMaxRows][kFuGS]
+    __bf16* gl_s = gh_s + (size_t)kFuMaxRows * kFuGS;
+    float* bl_s = (float*)(gl_s + (size_t)kFuMaxRows * kFuGS);        // [2][kFuMaxRows]
+    float* bn_s = bl_s + 2 * kFuMaxRows;                              // [kFuMaxRows]
+    float* bs_s = bn_s + kFuMaxRows;                                  // [kFuMaxRows]
+    float* aw_s = bs_s + kFuMaxRows;                                  // [kFuMaxRows]
+    int* ctl_s = (int*)(aw_s + kFuMaxRows);                           // [8]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cl = blockIdx.x / V, b = blockIdx.x % V + 1;
+    for (int i = tid; i < kFuMaxRows * HS; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < 2 * kFuMaxRows * kFuGS; i += kFuThreads) gh_s[i] = (__bf16)0.f;
+    if (tid < kFuMaxRows) { bn_s[tid] = 0.f; bs_s[tid] = 0.f; aw_s[tid] = LAST_NEG_INF; }
+    bf16x8 wfrag[kFuMaxKS];
+    fused_load_wfrag(a.W, H, V1, wfrag);
+    floatx4 de_acc[kFuKT][kFuMaxRows / 16];
+#pragma unroll
+    for (int kt = 0; kt < kFuKT; ++kt)
+#pragma unroll
+        for (int mt = 0; mt < kFuMaxRows / 16; ++mt) de_acc[kt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    unsigned gstep = 0;
+    int any_dead = 0;
+    __syncthreads();
+
+    for (int item = cl; item < a.B; item += a.ncl) {
+        int L = a.len[item];
+        if (L < 0 || L > a.T) L = 0;
+        if (L == 0) continue;
+        u64* xbase = a.xb + (size_t)cl * 2 * (V + 1) * a.XW;
+        const float* aws = a.alpha_ws + (size_t)item * (a.T + 1) * a.C;
+        float* bws = a.beta_ws + (size_t)item * (a.T + 1) * a.C;
+        const double* offs = a.offs + (size_t)item * (a.T + 1);
+        const float init = (float)(offs[L] - a.Dws[item]);       // beta_L = 0 for every state
+        if (tid < kFuMaxRows) bl_s[tid] = (tid < R) ? init : LAST_NEG_INF;
+        if (tid < R && (tid > 0 || b == 1)) bws[(size_t)L * a.C + fused_state(V, b, tid)] = init;
+        if (tid == 0) ctl_s[0] = 0;
+        int dead = 0;
+        __syncthreads();
+        for (int t = L - 1; t >= 0; --t) {
+            const int par = (L - 1 - t) & 1;
+            const float* bl = bl_s + par * kFuMaxRows;
+            float* bl_new = bl_s + (par ^ 1) * kFuMaxRows;
+            const unsigned tag = gstep + 1;
+            u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
+            // publish beta_{t+1}: state (a,b) goes to workgroup a, state (b) to workgroup 1
+            if (tid >= 1 && tid <= V) xstore(xs + (size_t)(tid - 1) * a.XW + (b - 1), pack_word(bl[1 + tid], tag));
+            else if (tid == V + 1) xstore(xs + (size_t)V * a.XW + (b - 1), pack_word(bl[1], tag));
+            if (tid < R) aw_s[tid] = aws[(size_t)t * a.C + fused_state(V, b, tid)];
+            fused_weights_full(a.f + ((size_t)item * a.T + t) * H, a.e, V, b, hid_s, w_s, wfrag, R, Mpad, H, NT);
+            if (tid >= 1 && tid <= V) {
+                const u64 x = poll_tag32(xs + (size_t)(b - 1) * a.XW + (tid - 1), tag, a.spin_limit, dead);
+                bn_s[tid] = word_value(x);
+            } else if (b == 1 && tid >= 128 && tid < 128 + V) {
+                const u64 x = poll_tag32(xs + (size_t)V * a.XW + (tid - 128), tag, a.spin_limit, dead);
+                bs_s[tid - 127] = word_value(x);
+            }
+            const float P = (float)(offs[t + 1] - offs[t]);
+            if (__syncthreads_or(dead)) any_dead = 1;
+            fused_rows<false>(w_s, bl, bn_s, bs_s, aw_s, P, V, R, b == 1, bl_new, gh_s, gl_s);
+            __syncthreads();
+            if (tid < R && (tid > 0 || b == 1)) bws[(size_t)t * a.C + fused_state(V, b, tid)] = bl_new[tid];
+            // dpre = (gamma W^T) (1 - h^2): this wave owns hidden units [64 wave, 64 wave + 64)
+            float* dft = a.df + ((size_t)item * a.T + t) * H;
+#pragma unroll
+            for (int kt = 0; kt < kFuKT; ++kt) {
+                const int k0 = 16 * (kFuKT * wave + kt);
+                if (k0 < H) {
+                    bf16x8 wt[3];
+#pragma unroll
+                    for (int ys = 0; ys < 3; ++ys) wt[ys] = a.Wt[((size_t)(kFuKT * wave + kt) * 3 + ys) * 64 + lane];
+                    float colsum = 0.f;
+#pragma unroll
+                    for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+                        if (16 * mt < Mpad) {
+                            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int ys = 0; ys < 3; ++ys)
+                                if (32 * ys < V1) {
+                                    const int off = (16 * mt + (lane & 15)) * kFuGS + 32 * ys + 8 * (lane >> 4);
+                                    const bf16x8 ah = *(const bf16x8*)&gh_s[off];
+                                    const bf16x8 al = *(const bf16x8*)&gl_s[off];
+                                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[ys], acc, 0, 0, 0);
+                                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[ys], acc, 0, 0, 0);
+                                }
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float h = (float)hid_s[(16 * mt + 4 * (lane >> 4) + i) * HS + k0 + (lane & 15)];
+                                const float d = acc[i] * (1.f - h * h);
+                                de_acc[kt][mt][i] += d;
+                                colsum += d;
+                            }
+                        }
+                    colsum += __shfl_xor(colsum, 16);
+                    colsum += __shfl_xor(colsum, 32);
+                    if (lane < 16) unsafeAtomicAdd(dft + k0 + lane, a.scale * colsum);
+                }
+            }
+            gstep += 1;
+            __syncthreads();
+        }
+        if (any_dead && b == 1 && tid == 0 && a.item_status && a.item_status[item] == kItemOk)
+            a.item_status[item] = kItemTimeout;
+        any_dead = 0;
+    }
+    // de: rows of different clusters (items) add up
+#pragma unroll
+    for (int kt = 0; kt < kFuKT; ++kt) {
+        const int k0 = 16 * (kFuKT * wave + kt);
+        if (k0 < H) {
+#pragma unroll
+            for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 16 * mt + 4 * (lane >> 4) + i;
+                    if (r < R && (r > 0 || b == 1))
+                        unsafeAtomicAdd(a.de + (size_t)fused_state(V, b, r) * H + k0 + (lane & 15),
+                                        a.scale * de_acc[kt][mt][i]);
+                }
+        }
+    }
+}
+
+// dW = sum over items, frames and states of h^T gamma.  No recursion: grid =
+// B * V * nch workgroups, each owning the rows of one last label b of one item
+// over one chunk of frames; the marginals are rebuilt from the stored forward
+// and backward weights and the recomputed weights of the frame.
+__global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
+{
+    extern __shared__ unsigned char smem_raw[];
+    const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
+    const int Mpad = (R + 15) / 16 * 16;
+    const int NT = (V1 + 15) / 16;
+    const int HS = H + 8;
+    constexpr int kRows = 96;                                         // contraction length of h^T gamma
+    __bf16* hid_s = (__bf16*)smem_raw;                                // [96][H + 8]
+    float* w_s = (float*)(hid_s + (size_t)kRows * HS);                // [kFuMaxRows][kFuWS]
+    __bf16* gh_s = (__bf16*)(w_s + (size_t)kFuMaxRows * kFuWS);       // [kFuMaxRows (y)][kFuGS (r)]
+    __bf16* gl_s = gh_s + (size_t)kFuMaxRows * kFuGS;
+    float* bl_s = (float*)(gl_s + (size_t)kFuMaxRows * kFuGS);        // [kFuMaxRows]
+    float* bn_s = bl_s + kFuMaxRows;
+    float* bs_s = bn_s + kFuMaxRows;
+    float* aw_s = bs_s + kFuMaxRows;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ch = blockIdx.x % a.nch;
+    const int b = (blockIdx.x / a.nch) % V + 1;
+    const int item = blockIdx.x / (a.nch * V);
+    int L = a.len[item];
+    if (L < 0 || L > a.T) L = 0;
+    const int t0 = ch * a.TC, t1 = min(L, t0 + a.TC);
+    if (t0 >= t1) return;
+    for (int i = tid; i < kRows * HS; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < 2 * kFuMaxRows * kFuGS; i += kFuThreads) gh_s[i] = (__bf16)0.f;
+    if (tid < kFuMaxRows) { bl_s[tid] = 0.f; bn_s[tid] = 0.f; bs_s[tid] = 0.f; aw_s[tid] = LAST_NEG_INF; }
+    bf16x8 wfrag[kFuMaxKS];
+    fused_load_wfrag(a.W, H, V1, wfrag);
+    floatx4 acc[kFuKT][kFuMaxNT];
+#pragma unroll
+    for (int kt = 0; kt < kFuKT; ++kt)
+#pragma unroll
+        for (int yt = 0; yt < kFuMaxNT; ++yt) acc[kt][yt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const float* aws = a.alpha_ws + (size_t)item * (a.T + 1) * a.C;
+    const float* bws = a.beta_ws + (size_t)item * (a.T + 1) * a.C;
+    const double* offs = a.offs + (size_t)item * (a.T + 1);
+    __syncthreads();
+    for (int t = t0; t < t1; ++t) {
+        if (tid < R) {
+            const int q = fused_state(V, b, tid);
+            aw_s[tid] = aws[(size_t)t * a.C + q];
+            bl_s[tid] = bws[(size_t)(t + 1) * a.C + q];
+        } else if (tid >= 128 && tid < 128 + V) {
+            const int y = tid - 127;
+            bn_s[y] = bws[(size_t)(t + 1) * a.C + 1 + V + (b - 1) * V + (y - 1)];
+            if (b == 1) bs_s[y] = bws[(size_t)(t + 1) * a.C + y];
+        }
+        fused_weights_full(a.f + ((size_t)item * a.T + t) * H, a.e, V, b, hid_s, w_s, wfrag, R, Mpad, H, NT);
+        const float P = (float)(offs[t + 1] - offs[t]);
+        fused_rows<true>(w_s, bl_s, bn_s, bs_s, aw_s, P, V, R, b == 1, nullptr, gh_s, gl_s);
+        __syncthreads();
+#pragma unroll
+        for (int kt = 0; kt < kFuKT; ++kt) {
+            const int k0 = 16 * (kFuKT * wave + kt);
+            if (k0 < H) {
+#pragma unroll
+                for (int rs = 0; rs < 3; ++rs)
+                    if (32 * rs < R) {
+                        bf16x8 hv;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) hv[j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * HS + k0 + (lane & 15)];
+#pragma unroll
+                        for (int yt = 0; yt < kFuMaxNT; ++yt)
+                            if (yt < NT) {
+                                const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
+                                const bf16x8 gh = *(const bf16x8*)&gh_s[off];
+                                const bf16x8 gl = *(const bf16x8*)&gl_s[off];
+                                acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gh, acc[kt][yt], 0, 0, 0);
+                                acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gl, acc[kt][yt], 0, 0, 0);
+                            }
+                    }
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int kt = 0; kt < kFuKT; ++kt) {
+        const int k0 = 16 * (kFuKT * wave + kt);
+        if (k0 < H) {
+#pragma unroll
+            for (int yt = 0; yt < kFuMaxNT; ++yt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = k0 + 4 * (lane >> 4) + i, y = 16 * yt + (lane & 15);
+                    if (yt < NT && y < V1) unsafeAtomicAdd(a.dW + (size_t)k * V1 + y, a.scale * acc[kt][yt][i]);
+                }
+        }
+    }
+}
+
 }  // namespace last

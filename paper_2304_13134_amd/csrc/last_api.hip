@@ -245,7 +245,10 @@ constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel als
 struct FusedPlan {
     bool ok;
     int ncl, XW, KC, R, Mpad;
-    size_t lds;
+    size_t lds;          // forward kernel
+    size_t lds_bwd;      // backward recursion kernel
+    size_t lds_dw;       // dW kernel
+    int nch, TC;         // frame chunks of the dW kernel
 };
 
 FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
@@ -262,12 +265,22 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     p.XW = (s.V + 7) / 8 * 8;
     p.lds = (size_t)p.R * H * 2 + (size_t)p.Mpad * (p.KC + 8) * 2 + (size_t)p.Mpad * kFuWS * 4
             + (size_t)(3 * kFuMaxRows + 32 + 64 + 8) * 4;
-    p.ok = p.lds <= (size_t)kFusedMaxLds;
+    const size_t tiles = (size_t)kFuMaxRows * kFuWS * 4 + (size_t)2 * kFuMaxRows * kFuGS * 2;
+    p.lds_bwd = (size_t)kFuMaxRows * (H + 8) * 2 + tiles + (size_t)(5 * kFuMaxRows + 8) * 4;
+    p.lds_dw = (size_t)96 * (H + 8) * 2 + tiles + (size_t)(4 * kFuMaxRows) * 4;
+    p.nch = 256 / (s.B * s.V);                // fill the chip when the batch is small
+    if (p.nch > (s.T + 15) / 16) p.nch = (s.T + 15) / 16;
+    if (p.nch < 1) p.nch = 1;
+    p.TC = (s.T + p.nch - 1) / p.nch;
+    p.ok = p.lds <= (size_t)kFusedMaxLds && p.lds_bwd <= (size_t)kFusedMaxLds
+           && p.lds_dw <= (size_t)kFusedMaxLds;
     return p;
 }
 
 struct FusedWs {
     float* alpha;
+    float* beta;
+    bf16x8* Wt;
     double* offs;
     float* part;
     double* Aend;
@@ -280,6 +293,8 @@ FusedWs carve_fused(Carver& cv, const Shape& s, const FusedPlan& p, bool keep_al
 {
     FusedWs f;
     f.alpha = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
+    f.beta = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
+    f.Wt = keep_alpha ? cv.take<bf16x8>((size_t)32 * 3 * 64) : nullptr;
     f.offs = cv.take<double>((size_t)s.B * (s.T + 1));
     f.part = cv.take<float>((size_t)s.B * s.V);
     f.Aend = cv.take<double>((size_t)s.B);
@@ -295,9 +310,12 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
 {
     static bool attr_set = false;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute((const void*)fused_forward_kernel,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kFusedMaxLds);
-        if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+        const void* kernels[3] = {(const void*)fused_forward_kernel, (const void*)fused_backward_kernel,
+                                  (const void*)fused_dw_kernel};
+        for (const void* k : kernels) {
+            const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedMaxLds);
+            if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+        }
         attr_set = true;
     }
     hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
@@ -311,6 +329,34 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
     hipLaunchKernelGGL(fused_forward_kernel, dim3(p.ncl * s.V), dim3(kFuThreads), p.lds, st, a);
     hipLaunchKernelGGL(fused_finalize_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st,
                        (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D);
+    return hip_status();
+}
+
+// beta recursion + gradients of the fused path; the forward pass (with alpha kept) has been enqueued
+last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const FusedWs& f,
+                                    const last_weights_t* wt, const int* lengths, const last_grads_t* out,
+                                    int* item_status, hipStream_t st)
+{
+    const int H = wt->hidden;
+    if (!out->accumulate) {
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, st, out->df, (size_t)s.B * s.T * H);
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, st, out->de, (size_t)s.C * H);
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(256), 0, st, out->dW, (size_t)H * s.V1);
+    }
+    if (s.T == 0) return hip_status();
+    const int nfrag = (H / 16) * 3 * 64;
+    hipLaunchKernelGGL(fused_pack_wt_kernel, dim3((nfrag + 255) / 256), dim3(256), 0, st,
+                       (const __bf16*)wt->W, H, s.V1, f.Wt);
+    hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
+    FusedBwdArgs a;
+    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.W = (const __bf16*)wt->W; a.Wt = f.Wt;
+    a.len = lengths; a.alpha_ws = f.alpha; a.offs = f.offs; a.Dws = f.D; a.beta_ws = f.beta;
+    a.df = out->df; a.de = out->de; a.dW = out->dW; a.scale = out->scale;
+    a.item_status = item_status; a.xb = f.xb;
+    a.B = s.B; a.T = s.T; a.V = s.V; a.H = H; a.C = s.C;
+    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20; a.nch = p.nch; a.TC = p.TC;
+    hipLaunchKernelGGL(fused_backward_kernel, dim3(p.ncl * s.V), dim3(kFuThreads), p.lds_bwd, st, a);
+    hipLaunchKernelGGL(fused_dw_kernel, dim3(s.B * s.V * p.nch), dim3(kFuThreads), p.lds_dw, st, a);
     return hip_status();
 }
 
@@ -453,6 +499,18 @@ last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* 
     last_status_t rc = check_common(weights, context, &s);
     if (rc != LAST_OK) return rc;
     if (!lengths || !dist || !out) return LAST_ERR_NULL;
+    if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
+        const FusedPlan fp = fused_plan(s, weights);
+        if (!fp.ok) return LAST_ERR_UNSUPPORTED;
+        if (!out->df || !out->de || !out->dW) return LAST_ERR_NULL;
+        rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0));
+        if (rc != LAST_OK) return rc;
+        Carver cvf(ws);
+        const FusedWs fw = carve_fused(cvf, s, fp, true);
+        rc = launch_fused_forward(s, fp, fw, weights, lengths, dist, item_status, true, (hipStream_t)hip_stream);
+        if (rc != LAST_OK) return rc;
+        return launch_fused_backward(s, fp, fw, weights, lengths, out, item_status, (hipStream_t)hip_stream);
+    }
     if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
     if (!out->dw) return LAST_ERR_NULL;
     rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0));

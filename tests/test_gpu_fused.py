@@ -45,3 +45,60 @@ def test_fused_shortest_distance_config4_shape_short():
     o = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=False)
     assert st.cpu().tolist() == [0, 0]
     assert_dist_close(dist.cpu().numpy(), o["D"])
+
+
+# Gradients of the fused path: the marginals enter two bf16 matrix-core contractions as hi + lo
+# halves (16 significant bits), tanh is evaluated in float32 before the bf16 rounding (a value
+# that lands within ~1e-6 of a rounding boundary may round the other way than the float64
+# oracle's: one 2^-9 relative step on one hidden unit), and sums run in float32 in a different
+# order.  Bound used: 2e-4 of the largest magnitude of the tensor, plus 1e-5 absolute.
+def assert_grad_close(name, got, want):
+    got = np.asarray(got, dtype=np.float64)
+    tol = 2e-4 * float(np.max(np.abs(want))) + 1e-5
+    err = float(np.max(np.abs(got - want)))
+    assert np.all(np.isfinite(got)), name
+    assert err <= tol, "%s: max abs error %.3g > %.3g (max |ref| %.3g)" % (name, err, tol, np.max(np.abs(want)))
+
+
+def run_fused_grads(s, scale=1.0):
+    B = s["f"].shape[0]
+    st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    dist, (df, de, dW) = lb.last_arc_posteriors(fused_inputs(s), torch.from_numpy(s["lengths"]).cuda(),
+                                                order=2, scale=scale, item_status=st)
+    torch.cuda.synchronize()
+    o = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=True)
+    assert st.cpu().tolist() == [0] * B
+    assert_dist_close(dist.cpu().numpy(), o["D"])
+    assert_grad_close("df", df.cpu().numpy(), scale * o["df"])
+    assert_grad_close("de", de.cpu().numpy(), scale * o["de"])
+    assert_grad_close("dW", dW.cpu().numpy(), scale * o["dW"])
+    return o, (df, de, dW)
+
+
+@pytest.mark.parametrize("B,T,V,H,seed", [(1, 4, 2, 32, 11), (3, 9, 3, 64, 12), (2, 12, 6, 96, 13),
+                                           (2, 7, 17, 128, 14), (5, 10, 5, 512, 15)])
+def test_fused_gradients_small(B, T, V, H, seed):
+    announce("fused forward-backward", B, T, V, H)
+    s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed, len_lo=max(1, T - 3), len_hi=T)
+    o, (df, de, dW) = run_fused_grads(s)
+    # frames past the length of an item get no gradient
+    for b in range(B):
+        assert float(df[b, int(s["lengths"][b]):].abs().max() if s["lengths"][b] < T else 0.0) == 0.0
+
+
+def test_fused_gradients_scale_and_accumulate():
+    announce("fused forward-backward, scale and accumulate")
+    s = workloads.shared_emb(B=2, T=6, V=4, order=2, H=64, seed=21, len_lo=4, len_hi=6)
+    o, (df, de, dW) = run_fused_grads(s, scale=-0.5)
+    lengths = torch.from_numpy(s["lengths"]).cuda()
+    lb.last_arc_posteriors(fused_inputs(s), lengths, order=2, dw=(df, de, dW), scale=1.5, accumulate=True)
+    torch.cuda.synchronize()
+    assert_grad_close("df", df.cpu().numpy(), o["df"])
+    assert_grad_close("de", de.cpu().numpy(), o["de"])
+    assert_grad_close("dW", dW.cpu().numpy(), o["dW"])
+
+
+def test_fused_gradients_config4_shape_short():
+    announce("fused forward-backward, config 4 shape, T=6")
+    s = workloads.config(4, B=2, T=6)
+    run_fused_grads(s)
