@@ -29,18 +29,29 @@
 namespace last {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kFuThreads = 512;
 constexpr int kFuMaxRows = 80;      // V + 2 rows padded to a multiple of 16
 constexpr int kFuMaxNT = 5;         // (V + 1) labels in tiles of 16
 constexpr int kFuWS = 81;           // row stride of the weight tile in LDS (floats)
 constexpr int kFuMaxKS = 16;        // hidden / 32
+constexpr int kFuKC = 128;          // hidden units per chunk of the hidden tile (forward kernel)
+constexpr int kFuNC = 4;            // chunks (hidden <= 512, a multiple of kFuKC)
+constexpr int kFuHS = kFuKC + 8;    // row stride (bf16) of a hidden-tile chunk in LDS
+constexpr int kFuHB = kFuMaxRows * kFuHS;   // elements per chunk buffer
+constexpr int kFuHF = 512 + 8;      // row stride (bf16) of the whole hidden tile (backward kernels)
+constexpr int kFuGS = 104;          // row stride (bf16) of the marginal tiles in LDS; 96 used
+constexpr int kFuKT = 4;            // 16-wide tiles of the hidden dimension per wave (8 waves x 4 x 16 = 512)
+constexpr int kFuER = 9;            // rows of e per thread and frame in the backward kernels
 
 struct FusedArgs {
     const __bf16* f;     // [B][T][H]
     const __bf16* e;     // [C][H]
-    const __bf16* W;     // [H][V+1]
+    const bf16x8* Wf;    // W as operand fragments, see fused_pack_w_kernel
     const int* len;
     float* dist;
     int* item_status;
@@ -70,12 +81,11 @@ __device__ __forceinline__ float log_add_f(float x, float y)
     return m + __logf(1.f + __expf(fminf(x, y) - m));
 }
 
-__device__ __forceinline__ u64 poll_tag32(const u64* p, unsigned tag, int limit, int& dead)
+// wait (bounded) until the exchange word carries `tag`; x is a first look taken earlier
+__device__ __forceinline__ u64 poll_from(const u64* p, u64 x, unsigned tag, int limit, int& dead)
 {
-    u64 x = xload(p);
-    if (dead) return x;
     int n = 0;
-    while ((unsigned)(x >> 32) != tag) {
+    while (!dead && (unsigned)(x >> 32) != tag) {
         if (++n > limit) { dead = 1; break; }
         __builtin_amdgcn_s_sleep(1);
         x = xload(p);
@@ -91,107 +101,193 @@ __device__ __forceinline__ int fused_state(int V, int b, int r)
     return 1 + V + (r - 2) * V + (b - 1);
 }
 
-// Hidden tile + contraction for one frame: leaves w[r][y] (float32) in w_s.
-// e_s [R][H] bf16, hid_s [Mpad][KC + 8] bf16, wfrag: this wave's fragments of W.
-__device__ __forceinline__ void fused_weights_frame(const __bf16* __restrict__ ft, const __bf16* e_s,
-                                                    __bf16* hid_s, float* w_s,
-                                                    const bf16x8 (&wfrag)[kFuMaxKS], int R, int Mpad,
-                                                    int H, int KC, int NT)
+// two adjacent hidden units at once: bf16 pairs in, tanh in float32, bf16 pair out
+__device__ __forceinline__ unsigned tanh_pair(unsigned fbits, unsigned ebits)
 {
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int HS = KC + 8;
-    const int nrg = kFuThreads / KC;                 // row groups of the tanh pass
-    const int kh = tid % KC, rg = tid / KC;
-    floatx4 acc[kFuMaxRows / 16];
-#pragma unroll
-    for (int mt = 0; mt < kFuMaxRows / 16; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    // the hidden dimension is processed in chunks of KC <= 256 (the fragment index stays static)
-    auto chunk = [&](auto KS0) __attribute__((always_inline)) {
-        constexpr int ks0 = decltype(KS0)::value;
-        const int kc = 32 * ks0;
-        if (rg < nrg) {
-            const float fv = (float)ft[kc + kh];
-            for (int r = rg; r < R; r += nrg) {
-                const float x = fv + (float)e_s[(size_t)r * H + kc + kh];
-                hid_s[r * HS + kh] = (__bf16)fast_tanh(x);
-            }
-        }
-        __syncthreads();
-        if (wave < NT) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                if (32 * ks < KC) {
-#pragma unroll
-                    for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
-                        if (16 * mt < Mpad) {
-                            const bf16x8 av = *(const bf16x8*)&hid_s[(16 * mt + (lane & 15)) * HS + 32 * ks + 8 * (lane >> 4)];
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wfrag[ks0 + ks], acc[mt], 0, 0, 0);
-                        }
-                }
-        }
-        __syncthreads();
-    };
-    chunk(std::integral_constant<int, 0>());
-    if (H > 256) chunk(std::integral_constant<int, 8>());
-    if (wave < NT) {
-#pragma unroll
-        for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
-            if (16 * mt < Mpad) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
-            }
-    }
-    __syncthreads();
+    const float x0 = __uint_as_float(fbits << 16) + __uint_as_float(ebits << 16);
+    const float x1 = __uint_as_float(fbits & 0xffff0000u) + __uint_as_float(ebits & 0xffff0000u);
+    const floatx2 h = {fast_tanh(x0), fast_tanh(x1)};
+    const bf16x2 r = __builtin_convertvector(h, bf16x2);
+    return __builtin_bit_cast(unsigned, r);
 }
 
-// this wave's fragments of W: lane l holds W[32 ks + 8 (l / 16) + j][16 wave + l % 16], j = 0..7
-__device__ __forceinline__ void fused_load_wfrag(const __bf16* __restrict__ W, int H, int V1,
-                                                 bf16x8 (&wfrag)[kFuMaxKS])
+// workgroup barrier that orders LDS traffic only: global loads issued before it stay in flight
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// this thread's pairs of frame features, one per chunk
+__device__ __forceinline__ void fused_load_f(const __bf16* __restrict__ ft, int H, unsigned (&fb)[kFuNC])
+{
+    const int kp = threadIdx.x % (kFuKC / 2);
+#pragma unroll
+    for (int c = 0; c < kFuNC; ++c) fb[c] = (kFuKC * c < H) ? *(const unsigned*)(ft + kFuKC * c + 2 * kp) : 0u;
+}
+
+// contraction of hidden-tile chunk C (static, so that the fragment registers are addressed directly)
+template <int MT, int C>
+__device__ __forceinline__ void fused_mfma_chunk(const __bf16* hb, floatx4 (&acc)[MT],
+                                                 const bf16x8 (&wfrag)[kFuMaxKS])
 {
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n = 16 * wave + (lane & 15);
+    const __bf16* hp = hb + (lane & 15) * kFuHS + 8 * (lane >> 4);
 #pragma unroll
-    for (int ks = 0; ks < kFuMaxKS; ++ks) {
+    for (int ks = 0; ks < kFuKC / 32; ++ks) {
+        bf16x8 av[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) av[mt] = *(const bf16x8*)&hp[16 * mt * kFuHS + 32 * ks];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wfrag[(kFuKC / 32) * C + ks], acc[mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Hidden tile + contraction of one frame in NC + 1 phases (NC = H / kFuKC).  Phase
+// p runs the matrix-core contraction of chunk p-1 (waves 0..NT-1) and forms the
+// hidden tile tanh(f + e) of chunk p, so the transcendental work of one chunk
+// overlaps the contraction of the previous one; chunks alternate between two LDS
+// buffers.  Afterwards the accumulators of wave n hold w[r][y] for labels
+// 16 n .. 16 n + 15: lane l, tile mt, element i -> row 16 mt + 4 (l / 16) + i,
+// label 16 n + l % 16.
+// e_s [R][H] bf16, hid_s [2][kFuMaxRows][kFuHS] bf16 (constant strides keep the LDS
+// addresses of the contraction immediate), wfrag: this wave's fragments of W.
+// `early` (may be null): an exchange word this thread will need afterwards; a first
+// look at it is issued after phase 1 and returned in `early_word`.
+template <int MT>
+__device__ __forceinline__ void fused_weights_phases(const unsigned (&fb)[kFuNC], const __bf16* e_s,
+                                                     __bf16* hid_s, floatx4 (&acc)[MT],
+                                                     const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NT,
+                                                     const u64* early, u64& early_word)
+{
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int NC = H / kFuKC;
+    const int kp = tid % (kFuKC / 2), rg = wave;      // 64 pairs x 8 row groups
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int p = 0; p <= NC; ++p) {
+        if (p == 2 && early) early_word = xload(early);
+        if (p >= 1 && wave < NT) {
+            const __bf16* hb = hid_s + ((p - 1) & 1) * kFuHB;
+            switch (p) {
+            case 1: fused_mfma_chunk<MT, 0>(hb, acc, wfrag); break;
+            case 2: fused_mfma_chunk<MT, 1>(hb, acc, wfrag); break;
+            case 3: fused_mfma_chunk<MT, 2>(hb, acc, wfrag); break;
+            default: fused_mfma_chunk<MT, 3>(hb, acc, wfrag); break;
+            }
+        }
+        if (p < NC) {
+            __bf16* hb = hid_s + (p & 1) * kFuHB + 2 * kp;
+            const unsigned f2 = p == 0 ? fb[0] : p == 1 ? fb[1] : p == 2 ? fb[2] : fb[3];
+            const __bf16* ep = e_s + kFuKC * p + 2 * kp;
+            for (int r = rg; r < R; r += 24) {
+                // three rows per trip: the LDS reads go out together
+                const int r1 = r + 8, r2 = r + 16;
+                const unsigned e0 = *(const unsigned*)(ep + (size_t)r * H);
+                const unsigned e1 = *(const unsigned*)(ep + (size_t)(r1 < R ? r1 : r) * H);
+                const unsigned e2 = *(const unsigned*)(ep + (size_t)(r2 < R ? r2 : r) * H);
+                *(unsigned*)(hb + r * kFuHS) = tanh_pair(f2, e0);
+                if (r1 < R) *(unsigned*)(hb + r1 * kFuHS) = tanh_pair(f2, e1);
+                if (r2 < R) *(unsigned*)(hb + r2 * kFuHS) = tanh_pair(f2, e2);
+            }
+            lds_barrier();
+        }
+    }
+}
+
+// W repacked as matrix-core operand fragments (one 16-byte load per lane and fragment):
+//   Wf [kFuMaxNT][kFuMaxKS][64]: lane l of (n, ks) holds W[32 ks + 8 (l / 16) + j][16 n + l % 16]
+//      (B operand of  w[r][y] = sum_k h[r][k] W[k][y])
+//   Wt [H / 16][3][64]:          lane l of (kt, ys) holds W[16 kt + l % 16][32 ys + 8 (l / 16) + j]
+//      (B operand of  d[r][k] = sum_y gamma[r][y] W[k][y]),           j = 0..7, zero outside W
+__global__ void fused_pack_w_kernel(const __bf16* __restrict__ W, int H, int V1, bf16x8* __restrict__ Wf,
+                                    bf16x8* __restrict__ Wt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int nf = kFuMaxNT * kFuMaxKS * 64;
+    if (i < nf) {
+        const int lane = i & 63, ks = (i >> 6) % kFuMaxKS, n = (i >> 6) / kFuMaxKS;
+        const int y = 16 * n + (lane & 15);
+        bf16x8 v;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int k = 32 * ks + 8 * (lane >> 4) + j;
-            wfrag[ks][j] = (k < H && n < V1) ? W[(size_t)k * V1 + n] : (__bf16)0.f;
+            v[j] = (k < H && y < V1) ? W[(size_t)k * V1 + y] : (__bf16)0.f;
         }
+        Wf[i] = v;
+    }
+    const int nt = (H / 16) * 3 * 64;
+    if (Wt && i < nt) {
+        const int lane = i & 63, ys = (i >> 6) % 3, kt = (i >> 6) / 3;
+        const int k = 16 * kt + (lane & 15);
+        bf16x8 v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int y = 32 * ys + 8 * (lane >> 4) + j;
+            v[j] = (y < V1) ? W[(size_t)k * V1 + y] : (__bf16)0.f;
+        }
+        Wt[i] = v;
     }
 }
 
+// this wave's fragments of W (waves >= kFuMaxNT hold none)
+__device__ __forceinline__ void fused_load_wfrag(const bf16x8* __restrict__ Wf, bf16x8 (&wfrag)[kFuMaxKS])
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = wave < kFuMaxNT ? wave : 0;
+#pragma unroll
+    for (int ks = 0; ks < kFuMaxKS; ++ks) wfrag[ks] = Wf[((size_t)n * kFuMaxKS + ks) * 64 + lane];
+}
+
+// largest forward weight among the own states -> header word of this workgroup (wave 0 only)
+__device__ __forceinline__ void fused_publish_header(const float* al, int R, u64* slot, unsigned tag)
+{
+    const int lane = threadIdx.x;            // caller guarantees threadIdx.x < 64
+    float mx = (lane < R) ? al[lane] : LAST_NEG_INF;
+    if (lane + 64 < R) mx = fmaxf(mx, al[lane + 64]);
+    mx = wave_max(mx);
+    if (lane == 0) xstore(slot, pack_word(mx, tag));
+}
+
 // Shortest distance in the log semiring with on-the-fly weights (Eq. 2 visited
-// frame by frame, Section 4.1).  Grid: ncl * V workgroups of 512 threads.
+// frame by frame, Section 4.1).  Grid: ncl * V workgroups of 512 threads; MT =
+// number of 16-row tiles that cover the V + 2 rows of a workgroup.
+// Per frame: the waves that hold the weight tile reduce the label arcs of the
+// own rows column by column in registers and publish the V partial values; the
+// weights of the NEXT frame (independent of the recursion) are then computed
+// while those words travel; finally the own states are assembled from what the
+// other workgroups sent.
+template <int MT>
 __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
-    const int Mpad = (R + 15) / 16 * 16;
-    const int KC = H < 256 ? H : 256;
     const int NT = (V1 + 15) / 16;
     __bf16* e_s = (__bf16*)smem_raw;                                  // [R][H]
-    __bf16* hid_s = e_s + (size_t)R * H;                              // [Mpad][KC + 8]
-    float* w_s = (float*)(hid_s + (size_t)Mpad * (KC + 8));           // [Mpad][kFuWS]
-    float* al_s = w_s + (size_t)Mpad * kFuWS;                         // [2][kFuMaxRows] forward weights
-    float* bl_s = al_s + 2 * kFuMaxRows;                              // [kFuMaxRows] empty-label terms
-    float* red = bl_s + kFuMaxRows;                                   // [32]
-    float* hdr_s = red + 32;                                          // [64]
-    int* ctl_s = (int*)(hdr_s + 64);                                  // [8]
+    __bf16* hid_s = e_s + (size_t)R * H;                              // [2][kFuMaxRows][kFuHS]
+    float* al_s = (float*)(hid_s + 2 * kFuHB);                        // [2][kFuMaxRows] forward weights
+    float* bl_s = al_s + 2 * kFuMaxRows;                              // [kFuMaxRows + 8] empty-label terms
+    float* red = bl_s + kFuMaxRows + 8;                               // [32]
+    int* ctl_s = (int*)(red + 32);                                    // [8]
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cl = blockIdx.x / V, b = blockIdx.x % V + 1;
     // zero the pad rows of the hidden tile once; they stay zero
-    for (int i = tid; i < Mpad * (KC + 8); i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < 2 * kFuHB; i += kFuThreads) hid_s[i] = (__bf16)0.f;
     // rows of e owned by this workgroup
     for (int i = tid; i < R * H; i += kFuThreads) {
         const int r = i / H, k = i - r * H;
         e_s[i] = a.e[(size_t)fused_state(V, b, r) * H + k];
     }
     bf16x8 wfrag[kFuMaxKS];
-    fused_load_wfrag(a.W, H, V1, wfrag);
+    fused_load_wfrag(a.Wf, wfrag);
+    floatx4 acc[MT];
+    unsigned fb[kFuNC];
     unsigned gstep = 0;
     __syncthreads();
 
@@ -201,7 +297,8 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
         if (bad) L = 0;
         u64* xbase = a.xb + (size_t)cl * 2 * (V + 1) * a.XW;
         float* aws = a.alpha_ws ? a.alpha_ws + (size_t)item * (a.T + 1) * a.C : nullptr;
-        if (tid < kFuMaxRows) al_s[tid] = (tid == 0) ? 0.f : LAST_NEG_INF;
+        const __bf16* fi = a.f + (size_t)item * a.T * H;
+        if (tid < 2 * kFuMaxRows) al_s[tid] = (tid == 0) ? 0.f : LAST_NEG_INF;
         if (tid == 0) ctl_s[0] = 0;
         __syncthreads();
         if (aws && tid < R && (tid > 0 || b == 1)) aws[fused_state(V, b, tid)] = al_s[tid];
@@ -209,46 +306,82 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
         double A = 0.0;                       // running offset, identical in every workgroup
         float P_cur = 0.f, P_prev = 0.f, mu_prev = 0.f;
         int dead = 0;
-        for (int t = 0; t < L; ++t) {
+        if (L > 0 && wave == 0)
+            fused_publish_header(al_s, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
+                                 gstep + 1);
+        // iteration t = -1 only computes the weights of frame 0
+        for (int t = (L > 0 ? -1 : 0); t < L; ++t) {
             const int par = t & 1;
             const float* al = al_s + par * kFuMaxRows;
             float* an = al_s + (par ^ 1) * kFuMaxRows;
             const unsigned tag = gstep + 1;
             u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
-            // header: largest forward weight among the own states (known since the last frame)
-            {
-                float mx = (tid < R) ? al[tid] : LAST_NEG_INF;
-                mx = block_max(mx, red);
-                if (tid == 0) xstore(xs + (size_t)V * a.XW + (b - 1), pack_word(mx, tag));
-            }
-            fused_weights_frame(a.f + ((size_t)item * a.T + t) * H, e_s, hid_s, w_s, wfrag, R, Mpad, H, KC, NT);
-            // label arcs: (b), (a,b) --y--> (b,y), fully reduced here, sent to workgroup y
-            if (tid >= 1 && tid <= V) {
-                const int y = tid;
+            // frame features of the next frame (index clamped: unused after the last frame)
+            fused_load_f(fi + (size_t)(t + 1 < L ? t + 1 : t) * H, H, fb);
+            // label arcs (b), (a,b) --y--> (b,y): reduced over the own rows, sent to workgroup y
+            if (t >= 0 && wave < NT) {
+                const int g = lane >> 4, y = 16 * wave + (lane & 15);
+                float v[MT][4];
                 float m = LAST_NEG_INF;
-                for (int r = 1; r < R; ++r) m = fmaxf(m, al[r] + w_s[r * kFuWS + y]);
-                float p = LAST_NEG_INF;
-                if (m != LAST_NEG_INF) {
-                    float s = 0.f;
-                    for (int r = 1; r < R; ++r) s += __expf(al[r] + w_s[r * kFuWS + y] - m);
-                    p = m + __logf(s) - P_cur;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const floatx4 a4 = *(const floatx4*)&al[16 * mt + 4 * g];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int row = 16 * mt + 4 * g + i;
+                        v[mt][i] = a4[i] + acc[mt][i];
+                        if (row >= 1 && row < R) m = fmaxf(m, v[mt][i]);
+                    }
                 }
-                xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
+                m = fmaxf(m, __shfl_xor(m, 16));
+                m = fmaxf(m, __shfl_xor(m, 32));
+                float sum = 0.f;
+                if (m != LAST_NEG_INF) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = 16 * mt + 4 * g + i;
+                            if (row >= 1 && row < R) sum += __expf(v[mt][i] - m);
+                        }
+                }
+                sum += __shfl_xor(sum, 16);
+                sum += __shfl_xor(sum, 32);
+                const float p = (m != LAST_NEG_INF) ? m + __logf(sum) - P_cur : LAST_NEG_INF;
+                if (g == 0 && y >= 1 && y <= V) xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
+                // empty-label arcs of the own states; label arc start -> (b)
+                if (y == 0) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = 16 * mt + 4 * g + i;
+                            if (row < R) bl_s[row] = v[mt][i] - P_cur;
+                        }
+                }
+                if (y == b && g == 0) bl_s[R] = v[0][0] - P_cur;
             }
-            // empty-label arcs of the own states; label arc start -> (b)
-            if (tid < R) bl_s[tid] = al[tid] + w_s[tid * kFuWS] - P_cur;
-            if (tid == R) bl_s[R] = al[0] + w_s[b] - P_cur;          // row 0, label b
-            __syncthreads();
+            lds_barrier();
+            // weights of the next frame while the partial values travel; the first look at the
+            // incoming words is issued half way and consumed afterwards
+            const u64* pw = nullptr;
+            if (t >= 0) {
+                if (tid >= 1 && tid <= V) pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
+                else if (tid >= 128 && tid < 128 + V) pw = xs + (size_t)V * a.XW + (tid - 128);
+            }
+            u64 x = 0;
+            if (t + 1 < L) fused_weights_phases<MT>(fb, e_s, hid_s, acc, wfrag, R, H, NT, pw, x);
+            else if (pw) x = xload(pw);
+            if (t < 0) continue;
             // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
             float hv = LAST_NEG_INF;
+            if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
             if (tid >= 1 && tid <= V) {
-                const u64 x = poll_tag32(xs + (size_t)(b - 1) * a.XW + (tid - 1), tag, a.spin_limit, dead);
                 an[1 + tid] = log_add_f(word_value(x), bl_s[1 + tid]);
             } else if (tid == 0) {
                 an[0] = bl_s[0];
                 an[1] = log_add_f(bl_s[R], bl_s[1]);
-            } else if (tid >= 128 && tid < 128 + V) {
-                const u64 x = poll_tag32(xs + (size_t)V * a.XW + (tid - 128), tag, a.spin_limit, dead);
+            } else if (pw) {
                 hv = word_value(x);
             }
             const float mu = block_max(hv, red);          // contains the barriers that publish `an`
@@ -258,10 +391,12 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
             const float P_next = mu + 2.f * G - P_cur;
             A += (double)P_cur;
             mu_prev = mu; P_prev = P_cur; P_cur = P_next;
+            gstep += 1;
+            if (wave == 0 && t + 1 < L)
+                fused_publish_header(an, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
+                                     gstep + 1);
             if (aws && tid < R && (tid > 0 || b == 1)) aws[(size_t)(t + 1) * a.C + fused_state(V, b, tid)] = an[tid];
             if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1) + t + 1] = A;
-            gstep += 1;
-            __syncthreads();
         }
         // all states of the last frame are final: per-workgroup log-sum-exp, combined by fused_finalize
         {
@@ -299,7 +434,6 @@ __global__ void fused_finalize_kernel(const float* __restrict__ part, const doub
     if (Dws) Dws[item] = D;
 }
 
-
 // ---------------------------------------------------------------------------
 // Backward side: beta recursion, arc marginals (Eq. 1) and their chain through
 // the weight function.  With h = bf16(tanh(f_t + e_q)) and gamma the marginals,
@@ -310,14 +444,11 @@ __global__ void fused_finalize_kernel(const float* __restrict__ part, const doub
 // contractions keep 16 significant bits of it.
 // ---------------------------------------------------------------------------
 
-constexpr int kFuGS = 104;          // row stride (bf16) of the marginal tiles in LDS; 96 used
-constexpr int kFuKT = 4;            // 16-wide tiles of the hidden dimension per wave (8 waves x 4 x 16 = 512)
-
 struct FusedBwdArgs {
     const __bf16* f;
     const __bf16* e;
-    const __bf16* W;
-    const bf16x8* Wt;        // W as B-operand fragments of the dpre contraction: [H/16][3][64]
+    const bf16x8* Wf;        // W as operand fragments, see fused_pack_w_kernel
+    const bf16x8* Wt;
     const int* len;
     const float* alpha_ws;   // [B][T+1][C] forward weights relative to offs
     const double* offs;      // [B][T+1]
@@ -335,68 +466,84 @@ struct FusedBwdArgs {
     int nch, TC;             // frame chunks of the dW kernel
 };
 
-// fragments of W for C[r][k] = sum_y A[r][y] B[y][k], B[y][k] = W[k][y]:
-// lane l of fragment (kt, ys) holds W[16 kt + l % 16][32 ys + 8 (l / 16) + j], j = 0..7
-__global__ void fused_pack_wt_kernel(const __bf16* __restrict__ W, int H, int V1, bf16x8* __restrict__ Wt)
+// Rows of e for one frame of a backward kernel, fetched from global memory (e
+// stays in L2): thread -> 8 adjacent hidden units (one 16-byte load) of rows
+// rg, rg + nrg, ...; all loads of a frame are issued together.
+struct FusedERows {
+    uintx4 v[kFuER];
+};
+
+__device__ __forceinline__ void fused_load_e(const __bf16* __restrict__ e, int V, int b, int R, int H,
+                                             FusedERows& er)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const int n = (H / 16) * 3 * 64;
-    if (i >= n) return;
-    const int lane = i & 63, ys = (i >> 6) % 3, kt = (i >> 6) / 3;
-    const int k = 16 * kt + (lane & 15);
-    bf16x8 v;
+    const int KG = H / 8, nrg = kFuThreads / KG;
+    const int kg = threadIdx.x % KG, rg = threadIdx.x / KG;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int y = 32 * ys + 8 * (lane >> 4) + j;
-        v[j] = (y < V1) ? W[(size_t)k * V1 + y] : (__bf16)0.f;
+    for (int i = 0; i < kFuER; ++i) {
+        const int r = rg + i * nrg;
+        const int rc = (rg < nrg && r < R) ? r : 0;
+        er.v[i] = *(const uintx4*)(e + (size_t)fused_state(V, b, rc) * H + 8 * kg);
     }
-    Wt[i] = v;
 }
 
 // Hidden tile over the whole hidden dimension (kept for the gradient
-// contractions) + weights of one frame.  e is read from global memory (it stays
-// in L2); hid_s [.][H + 8] bf16, rows >= R stay zero.
-__device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const __bf16* __restrict__ e,
-                                                   int V, int b, __bf16* hid_s, float* w_s,
-                                                   const bf16x8 (&wfrag)[kFuMaxKS], int R, int Mpad,
-                                                   int H, int NT)
+// contractions) + weights of one frame into w_s.  hid_s [.][kFuHF] bf16, rows
+// >= R stay zero.
+template <int MT>
+__device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const FusedERows& er,
+                                                   __bf16* hid_s, float* w_s, const bf16x8* __restrict__ Wf,
+                                                   int R, int H, int NT)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int HS = H + 8;
-    const int nrg = kFuThreads / H;
-    const int kh = tid % H, rg = tid / H;
+    const int KG = H / 8, nrg = kFuThreads / KG;
+    const int kg = tid % KG, rg = tid / KG;
+    // this wave's fragments of W: fetched per frame (L2) so that they are not live in the other phases
+    bf16x8 wfrag[kFuMaxKS];
+    if (wave < NT) {
+#pragma unroll
+        for (int ks = 0; ks < kFuMaxKS; ++ks) wfrag[ks] = Wf[((size_t)wave * kFuMaxKS + ks) * 64 + lane];
+    }
     if (rg < nrg) {
-        const float fv = (float)ft[kh];
-        for (int r = rg; r < R; r += nrg) {
-            const float x = fv + (float)e[(size_t)fused_state(V, b, r) * H + kh];
-            hid_s[r * HS + kh] = (__bf16)fast_tanh(x);
+        const uintx4 f4 = *(const uintx4*)(ft + 8 * kg);
+#pragma unroll
+        for (int i = 0; i < kFuER; ++i) {
+            const int r = rg + i * nrg;
+            if (r < R) {
+                uintx4 h;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = tanh_pair(f4[j], er.v[i][j]);
+                *(uintx4*)(hid_s + r * kFuHF + 8 * kg) = h;
+            }
         }
     }
-    __syncthreads();
+    lds_barrier();
     if (wave < NT) {
-        floatx4 acc[kFuMaxRows / 16];
+        floatx4 acc[MT];
 #pragma unroll
-        for (int mt = 0; mt < kFuMaxRows / 16; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const __bf16* hp = hid_s + (lane & 15) * kFuHF + 8 * (lane >> 4);
 #pragma unroll
-        for (int ks = 0; ks < kFuMaxKS; ++ks)
-            if (32 * ks < H) {
+        for (int c = 0; c < kFuNC; ++c)
+            if (kFuKC * c < H) {
 #pragma unroll
-                for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
-                    if (16 * mt < Mpad) {
-                        const bf16x8 av = *(const bf16x8*)&hid_s[(16 * mt + (lane & 15)) * HS + 32 * ks + 8 * (lane >> 4)];
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wfrag[ks], acc[mt], 0, 0, 0);
-                    }
+                for (int ks = 0; ks < kFuKC / 32; ++ks) {
+                    bf16x8 av[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) av[mt] = *(const bf16x8*)&hp[16 * mt * kFuHF + kFuKC * c + 32 * ks];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wfrag[(kFuKC / 32) * c + ks], acc[mt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
 #pragma unroll
-        for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
-            if (16 * mt < Mpad) {
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
-            }
+            for (int r = 0; r < 4; ++r)
+                w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 __device__ __forceinline__ void split_bf16(float g, __bf16& hi, __bf16& lo)
@@ -452,38 +599,33 @@ __device__ __forceinline__ void fused_rows(const float* w_s, const float* bl, co
 // alpha' + beta' <= 0, so no offset has to be negotiated.  Also forms
 // dpre = (gamma W^T)(1 - h^2) on the matrix cores, accumulates de in registers
 // and adds the column sums into df.
+template <int MT>
 __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
-    const int Mpad = (R + 15) / 16 * 16;
     const int NT = (V1 + 15) / 16;
-    const int HS = H + 8;
-    __bf16* hid_s = (__bf16*)smem_raw;                                // [kFuMaxRows][H + 8]
-    float* w_s = (float*)(hid_s + (size_t)kFuMaxRows * HS);           // [kFuMaxRows][kFuWS]
+    __bf16* hid_s = (__bf16*)smem_raw;                                // [kFuMaxRows][kFuHF]
+    float* w_s = (float*)(hid_s + (size_t)kFuMaxRows * kFuHF);        // [kFuMaxRows][kFuWS]
     __bf16* gh_s = (__bf16*)(w_s + (size_t)kFuMaxRows * kFuWS);       // [kFuMaxRows][kFuGS]
     __bf16* gl_s = gh_s + (size_t)kFuMaxRows * kFuGS;
     float* bl_s = (float*)(gl_s + (size_t)kFuMaxRows * kFuGS);        // [2][kFuMaxRows]
     float* bn_s = bl_s + 2 * kFuMaxRows;                              // [kFuMaxRows]
     float* bs_s = bn_s + kFuMaxRows;                                  // [kFuMaxRows]
     float* aw_s = bs_s + kFuMaxRows;                                  // [kFuMaxRows]
-    int* ctl_s = (int*)(aw_s + kFuMaxRows);                           // [8]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cl = blockIdx.x / V, b = blockIdx.x % V + 1;
-    for (int i = tid; i < kFuMaxRows * HS; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < kFuMaxRows * kFuHF; i += kFuThreads) hid_s[i] = (__bf16)0.f;
     for (int i = tid; i < 2 * kFuMaxRows * kFuGS; i += kFuThreads) gh_s[i] = (__bf16)0.f;
     if (tid < kFuMaxRows) { bn_s[tid] = 0.f; bs_s[tid] = 0.f; aw_s[tid] = LAST_NEG_INF; }
-    bf16x8 wfrag[kFuMaxKS];
-    fused_load_wfrag(a.W, H, V1, wfrag);
-    floatx4 de_acc[kFuKT][kFuMaxRows / 16];
+    floatx4 de_acc[kFuKT][MT];
 #pragma unroll
     for (int kt = 0; kt < kFuKT; ++kt)
 #pragma unroll
-        for (int mt = 0; mt < kFuMaxRows / 16; ++mt) de_acc[kt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) de_acc[kt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
     unsigned gstep = 0;
-    int any_dead = 0;
     __syncthreads();
 
     for (int item = cl; item < a.B; item += a.ncl) {
@@ -497,8 +639,7 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
         const float init = (float)(offs[L] - a.Dws[item]);       // beta_L = 0 for every state
         if (tid < kFuMaxRows) bl_s[tid] = (tid < R) ? init : LAST_NEG_INF;
         if (tid < R && (tid > 0 || b == 1)) bws[(size_t)L * a.C + fused_state(V, b, tid)] = init;
-        if (tid == 0) ctl_s[0] = 0;
-        int dead = 0;
+        int dead = 0, any_dead = 0;
         __syncthreads();
         for (int t = L - 1; t >= 0; --t) {
             const int par = (L - 1 - t) & 1;
@@ -509,19 +650,21 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
             // publish beta_{t+1}: state (a,b) goes to workgroup a, state (b) to workgroup 1
             if (tid >= 1 && tid <= V) xstore(xs + (size_t)(tid - 1) * a.XW + (b - 1), pack_word(bl[1 + tid], tag));
             else if (tid == V + 1) xstore(xs + (size_t)V * a.XW + (b - 1), pack_word(bl[1], tag));
+            FusedERows er;
+            fused_load_e(a.e, V, b, R, H, er);
             if (tid < R) aw_s[tid] = aws[(size_t)t * a.C + fused_state(V, b, tid)];
-            fused_weights_full(a.f + ((size_t)item * a.T + t) * H, a.e, V, b, hid_s, w_s, wfrag, R, Mpad, H, NT);
+            fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, NT);
             if (tid >= 1 && tid <= V) {
-                const u64 x = poll_tag32(xs + (size_t)(b - 1) * a.XW + (tid - 1), tag, a.spin_limit, dead);
-                bn_s[tid] = word_value(x);
+                const u64* pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
+                bn_s[tid] = word_value(poll_from(pw, xload(pw), tag, a.spin_limit, dead));
             } else if (b == 1 && tid >= 128 && tid < 128 + V) {
-                const u64 x = poll_tag32(xs + (size_t)V * a.XW + (tid - 128), tag, a.spin_limit, dead);
-                bs_s[tid - 127] = word_value(x);
+                const u64* pw = xs + (size_t)V * a.XW + (tid - 128);
+                bs_s[tid - 127] = word_value(poll_from(pw, xload(pw), tag, a.spin_limit, dead));
             }
             const float P = (float)(offs[t + 1] - offs[t]);
             if (__syncthreads_or(dead)) any_dead = 1;
             fused_rows<false>(w_s, bl, bn_s, bs_s, aw_s, P, V, R, b == 1, bl_new, gh_s, gl_s);
-            __syncthreads();
+            lds_barrier();
             if (tid < R && (tid > 0 || b == 1)) bws[(size_t)t * a.C + fused_state(V, b, tid)] = bl_new[tid];
             // dpre = (gamma W^T) (1 - h^2): this wave owns hidden units [64 wave, 64 wave + 64)
             float* dft = a.df + ((size_t)item * a.T + t) * H;
@@ -534,37 +677,36 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
                     for (int ys = 0; ys < 3; ++ys) wt[ys] = a.Wt[((size_t)(kFuKT * wave + kt) * 3 + ys) * 64 + lane];
                     float colsum = 0.f;
 #pragma unroll
-                    for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
-                        if (16 * mt < Mpad) {
-                            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+                    for (int mt = 0; mt < MT; ++mt) {
+                        floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                            for (int ys = 0; ys < 3; ++ys)
-                                if (32 * ys < V1) {
-                                    const int off = (16 * mt + (lane & 15)) * kFuGS + 32 * ys + 8 * (lane >> 4);
-                                    const bf16x8 ah = *(const bf16x8*)&gh_s[off];
-                                    const bf16x8 al = *(const bf16x8*)&gl_s[off];
-                                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[ys], acc, 0, 0, 0);
-                                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[ys], acc, 0, 0, 0);
-                                }
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const float h = (float)hid_s[(16 * mt + 4 * (lane >> 4) + i) * HS + k0 + (lane & 15)];
-                                const float d = acc[i] * (1.f - h * h);
-                                de_acc[kt][mt][i] += d;
-                                colsum += d;
+                        for (int ys = 0; ys < 3; ++ys)
+                            if (32 * ys < V1) {
+                                const int off = (16 * mt + (lane & 15)) * kFuGS + 32 * ys + 8 * (lane >> 4);
+                                const bf16x8 ah = *(const bf16x8*)&gh_s[off];
+                                const bf16x8 al = *(const bf16x8*)&gl_s[off];
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[ys], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[ys], acc, 0, 0, 0);
                             }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float h = (float)hid_s[(16 * mt + 4 * (lane >> 4) + i) * kFuHF + k0 + (lane & 15)];
+                            const float d = acc[i] * (1.f - h * h);
+                            de_acc[kt][mt][i] += d;
+                            colsum += d;
                         }
+                    }
                     colsum += __shfl_xor(colsum, 16);
                     colsum += __shfl_xor(colsum, 32);
                     if (lane < 16) unsafeAtomicAdd(dft + k0 + lane, a.scale * colsum);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
             gstep += 1;
-            __syncthreads();
+            lds_barrier();
         }
         if (any_dead && b == 1 && tid == 0 && a.item_status && a.item_status[item] == kItemOk)
             a.item_status[item] = kItemTimeout;
-        any_dead = 0;
     }
     // de: rows of different clusters (items) add up
 #pragma unroll
@@ -572,7 +714,7 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
         const int k0 = 16 * (kFuKT * wave + kt);
         if (k0 < H) {
 #pragma unroll
-            for (int mt = 0; mt < kFuMaxRows / 16; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int r = 16 * mt + 4 * (lane >> 4) + i;
@@ -588,16 +730,16 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
 // B * V * nch workgroups, each owning the rows of one last label b of one item
 // over one chunk of frames; the marginals are rebuilt from the stored forward
 // and backward weights and the recomputed weights of the frame.
+template <int MT>
 __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
-    const int Mpad = (R + 15) / 16 * 16;
     const int NT = (V1 + 15) / 16;
-    const int HS = H + 8;
-    constexpr int kRows = 96;                                         // contraction length of h^T gamma
-    __bf16* hid_s = (__bf16*)smem_raw;                                // [96][H + 8]
-    float* w_s = (float*)(hid_s + (size_t)kRows * HS);                // [kFuMaxRows][kFuWS]
+    constexpr int RS = (16 * MT + 31) / 32;                           // 32-row steps of the contraction
+    constexpr int kRows = 32 * RS;
+    __bf16* hid_s = (__bf16*)smem_raw;                                // [kRows][kFuHF]
+    float* w_s = (float*)(hid_s + (size_t)kRows * kFuHF);             // [kFuMaxRows][kFuWS]
     __bf16* gh_s = (__bf16*)(w_s + (size_t)kFuMaxRows * kFuWS);       // [kFuMaxRows (y)][kFuGS (r)]
     __bf16* gl_s = gh_s + (size_t)kFuMaxRows * kFuGS;
     float* bl_s = (float*)(gl_s + (size_t)kFuMaxRows * kFuGS);        // [kFuMaxRows]
@@ -614,11 +756,9 @@ __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
     if (L < 0 || L > a.T) L = 0;
     const int t0 = ch * a.TC, t1 = min(L, t0 + a.TC);
     if (t0 >= t1) return;
-    for (int i = tid; i < kRows * HS; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < kRows * kFuHF; i += kFuThreads) hid_s[i] = (__bf16)0.f;
     for (int i = tid; i < 2 * kFuMaxRows * kFuGS; i += kFuThreads) gh_s[i] = (__bf16)0.f;
     if (tid < kFuMaxRows) { bl_s[tid] = 0.f; bn_s[tid] = 0.f; bs_s[tid] = 0.f; aw_s[tid] = LAST_NEG_INF; }
-    bf16x8 wfrag[kFuMaxKS];
-    fused_load_wfrag(a.W, H, V1, wfrag);
     floatx4 acc[kFuKT][kFuMaxNT];
 #pragma unroll
     for (int kt = 0; kt < kFuKT; ++kt)
@@ -629,6 +769,8 @@ __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
     const double* offs = a.offs + (size_t)item * (a.T + 1);
     __syncthreads();
     for (int t = t0; t < t1; ++t) {
+        FusedERows er;
+        fused_load_e(a.e, V, b, R, H, er);
         if (tid < R) {
             const int q = fused_state(V, b, tid);
             aw_s[tid] = aws[(size_t)t * a.C + q];
@@ -638,33 +780,33 @@ __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
             bn_s[y] = bws[(size_t)(t + 1) * a.C + 1 + V + (b - 1) * V + (y - 1)];
             if (b == 1) bs_s[y] = bws[(size_t)(t + 1) * a.C + y];
         }
-        fused_weights_full(a.f + ((size_t)item * a.T + t) * H, a.e, V, b, hid_s, w_s, wfrag, R, Mpad, H, NT);
+        fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, NT);
         const float P = (float)(offs[t + 1] - offs[t]);
         fused_rows<true>(w_s, bl_s, bn_s, bs_s, aw_s, P, V, R, b == 1, nullptr, gh_s, gl_s);
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int kt = 0; kt < kFuKT; ++kt) {
             const int k0 = 16 * (kFuKT * wave + kt);
             if (k0 < H) {
 #pragma unroll
-                for (int rs = 0; rs < 3; ++rs)
-                    if (32 * rs < R) {
-                        bf16x8 hv;
+                for (int rs = 0; rs < RS; ++rs) {
+                    bf16x8 hv;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) hv[j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * HS + k0 + (lane & 15)];
+                    for (int j = 0; j < 8; ++j) hv[j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * kFuHF + k0 + (lane & 15)];
 #pragma unroll
-                        for (int yt = 0; yt < kFuMaxNT; ++yt)
-                            if (yt < NT) {
-                                const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
-                                const bf16x8 gh = *(const bf16x8*)&gh_s[off];
-                                const bf16x8 gl = *(const bf16x8*)&gl_s[off];
-                                acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gh, acc[kt][yt], 0, 0, 0);
-                                acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gl, acc[kt][yt], 0, 0, 0);
-                            }
-                    }
+                    for (int yt = 0; yt < kFuMaxNT; ++yt)
+                        if (yt < NT) {
+                            const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
+                            const bf16x8 gh = *(const bf16x8*)&gh_s[off];
+                            const bf16x8 gl = *(const bf16x8*)&gl_s[off];
+                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gh, acc[kt][yt], 0, 0, 0);
+                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gl, acc[kt][yt], 0, 0, 0);
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
 #pragma unroll
     for (int kt = 0; kt < kFuKT; ++kt) {

@@ -9,6 +9,7 @@
 #include "numerator_kernels.hpp"
 #include "cluster_kernels.hpp"
 #include "fused_kernels.hpp"
+#include <algorithm>
 
 #include <cstdlib>
 #include <type_traits>
@@ -244,30 +245,38 @@ last_status_t hip_status()
 constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel also has a little static LDS
 struct FusedPlan {
     bool ok;
-    int ncl, XW, KC, R, Mpad;
+    int ncl, XW, KC, R, Mpad, MT;
     size_t lds;          // forward kernel
     size_t lds_bwd;      // backward recursion kernel
     size_t lds_dw;       // dW kernel
     int nch, TC;         // frame chunks of the dW kernel
 };
 
+template <typename F>
+void fused_dispatch(int MT, F&& f)
+{
+    if (MT == 1) f(std::integral_constant<int, 1>());
+    else if (MT == 3) f(std::integral_constant<int, 3>());
+    else f(std::integral_constant<int, 5>());
+}
+
 FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
 {
     FusedPlan p{};
     if (wt->kind != LAST_WEIGHTS_SHARED_EMB || s.order != 2) return p;
     const int H = wt->hidden;
-    if (s.V > 64 || H % 32 != 0 || H > 512 || (H > 256 && H % 256 != 0)) return p;
+    if (s.V > 64 || H % kFuKC != 0 || H < kFuKC || H > 512) return p;
     p.R = s.V + 2;
     p.Mpad = (p.R + 15) / 16 * 16;
-    p.KC = H < 256 ? H : 256;
+    p.KC = H < kFuKC ? H : kFuKC;
     p.ncl = 256 / s.V;                        // one workgroup per compute unit
     if (p.ncl > s.B) p.ncl = s.B;
     p.XW = (s.V + 7) / 8 * 8;
-    p.lds = (size_t)p.R * H * 2 + (size_t)p.Mpad * (p.KC + 8) * 2 + (size_t)p.Mpad * kFuWS * 4
-            + (size_t)(3 * kFuMaxRows + 32 + 64 + 8) * 4;
+    p.lds = (size_t)p.R * H * 2 + (size_t)2 * kFuHB * 2 + (size_t)(3 * kFuMaxRows + 8 + 32 + 8) * 4;
     const size_t tiles = (size_t)kFuMaxRows * kFuWS * 4 + (size_t)2 * kFuMaxRows * kFuGS * 2;
-    p.lds_bwd = (size_t)kFuMaxRows * (H + 8) * 2 + tiles + (size_t)(5 * kFuMaxRows + 8) * 4;
-    p.lds_dw = (size_t)96 * (H + 8) * 2 + tiles + (size_t)(4 * kFuMaxRows) * 4;
+    p.MT = p.Mpad / 16 <= 1 ? 1 : p.Mpad / 16 <= 3 ? 3 : 5;   // instantiated row-tile counts
+    p.lds_bwd = (size_t)kFuMaxRows * kFuHF * 2 + tiles + (size_t)(5 * kFuMaxRows + 8) * 4;
+    p.lds_dw = (size_t)(32 * ((16 * p.MT + 31) / 32)) * kFuHF * 2 + tiles + (size_t)(4 * kFuMaxRows) * 4;
     p.nch = 256 / (s.B * s.V);                // fill the chip when the batch is small
     if (p.nch > (s.T + 15) / 16) p.nch = (s.T + 15) / 16;
     if (p.nch < 1) p.nch = 1;
@@ -280,6 +289,7 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
 struct FusedWs {
     float* alpha;
     float* beta;
+    bf16x8* Wf;
     bf16x8* Wt;
     double* offs;
     float* part;
@@ -294,6 +304,7 @@ FusedWs carve_fused(Carver& cv, const Shape& s, const FusedPlan& p, bool keep_al
     FusedWs f;
     f.alpha = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
     f.beta = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
+    f.Wf = cv.take<bf16x8>((size_t)kFuMaxNT * kFuMaxKS * 64);
     f.Wt = keep_alpha ? cv.take<bf16x8>((size_t)32 * 3 * 64) : nullptr;
     f.offs = cv.take<double>((size_t)s.B * (s.T + 1));
     f.part = cv.take<float>((size_t)s.B * s.V);
@@ -310,8 +321,10 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
 {
     static bool attr_set = false;
     if (!attr_set) {
-        const void* kernels[3] = {(const void*)fused_forward_kernel, (const void*)fused_backward_kernel,
-                                  (const void*)fused_dw_kernel};
+        const void* kernels[9] = {
+            (const void*)fused_forward_kernel<1>, (const void*)fused_forward_kernel<3>, (const void*)fused_forward_kernel<5>,
+            (const void*)fused_backward_kernel<1>, (const void*)fused_backward_kernel<3>, (const void*)fused_backward_kernel<5>,
+            (const void*)fused_dw_kernel<1>, (const void*)fused_dw_kernel<3>, (const void*)fused_dw_kernel<5>};
         for (const void* k : kernels) {
             const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedMaxLds);
             if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
@@ -319,14 +332,20 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
         attr_set = true;
     }
     hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
+    const int npack = std::max(kFuMaxNT * kFuMaxKS * 64, (wt->hidden / 16) * 3 * 64);
+    hipLaunchKernelGGL(fused_pack_w_kernel, dim3((npack + 255) / 256), dim3(256), 0, st,
+                       (const __bf16*)wt->W, wt->hidden, s.V1, f.Wf, f.Wt);
     FusedArgs a;
-    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.W = (const __bf16*)wt->W;
+    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.Wf = f.Wf;
     a.len = lengths; a.dist = dist; a.item_status = item_status;
     a.alpha_ws = keep_alpha ? f.alpha : nullptr; a.offs = f.offs; a.part = f.part; a.Aend = f.Aend;
     a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = wt->hidden; a.C = s.C;
     a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20;
-    hipLaunchKernelGGL(fused_forward_kernel, dim3(p.ncl * s.V), dim3(kFuThreads), p.lds, st, a);
+    fused_dispatch(p.MT, [&](auto MT) {
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_forward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
+                           dim3(kFuThreads), p.lds, st, a);
+    });
     hipLaunchKernelGGL(fused_finalize_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st,
                        (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D);
     return hip_status();
@@ -344,19 +363,20 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
         hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(256), 0, st, out->dW, (size_t)H * s.V1);
     }
     if (s.T == 0) return hip_status();
-    const int nfrag = (H / 16) * 3 * 64;
-    hipLaunchKernelGGL(fused_pack_wt_kernel, dim3((nfrag + 255) / 256), dim3(256), 0, st,
-                       (const __bf16*)wt->W, H, s.V1, f.Wt);
     hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
     FusedBwdArgs a;
-    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.W = (const __bf16*)wt->W; a.Wt = f.Wt;
+    a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.Wf = f.Wf; a.Wt = f.Wt;
     a.len = lengths; a.alpha_ws = f.alpha; a.offs = f.offs; a.Dws = f.D; a.beta_ws = f.beta;
     a.df = out->df; a.de = out->de; a.dW = out->dW; a.scale = out->scale;
     a.item_status = item_status; a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = H; a.C = s.C;
     a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20; a.nch = p.nch; a.TC = p.TC;
-    hipLaunchKernelGGL(fused_backward_kernel, dim3(p.ncl * s.V), dim3(kFuThreads), p.lds_bwd, st, a);
-    hipLaunchKernelGGL(fused_dw_kernel, dim3(s.B * s.V * p.nch), dim3(kFuThreads), p.lds_dw, st, a);
+    fused_dispatch(p.MT, [&](auto MT) {
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_backward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
+                           dim3(kFuThreads), p.lds_bwd, st, a);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_dw_kernel<decltype(MT)::value>), dim3(s.B * s.V * p.nch),
+                           dim3(kFuThreads), p.lds_dw, st, a);
+    });
     return hip_status();
 }
 

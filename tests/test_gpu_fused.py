@@ -20,8 +20,8 @@ def fused_inputs(s):
     return lb.SharedEmb(dev_bf16(s["f"]), dev_bf16(s["e"]), dev_bf16(s["W"]))
 
 
-@pytest.mark.parametrize("B,T,V,H,seed", [(1, 4, 2, 32, 1), (3, 9, 3, 64, 2), (2, 12, 6, 96, 3),
-                                           (2, 7, 17, 128, 4), (5, 10, 5, 512, 5)])
+@pytest.mark.parametrize("B,T,V,H,seed", [(1, 4, 2, 128, 1), (3, 9, 3, 128, 2), (2, 12, 6, 256, 3),
+                                           (2, 7, 17, 384, 4), (5, 10, 5, 512, 5), (2, 5, 40, 128, 6)])
 def test_fused_shortest_distance_small(B, T, V, H, seed):
     announce("fused forward", B, T, V, H)
     s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed, len_lo=max(1, T - 3), len_hi=T)
@@ -75,8 +75,8 @@ def run_fused_grads(s, scale=1.0):
     return o, (df, de, dW)
 
 
-@pytest.mark.parametrize("B,T,V,H,seed", [(1, 4, 2, 32, 11), (3, 9, 3, 64, 12), (2, 12, 6, 96, 13),
-                                           (2, 7, 17, 128, 14), (5, 10, 5, 512, 15)])
+@pytest.mark.parametrize("B,T,V,H,seed", [(1, 4, 2, 128, 11), (3, 9, 3, 128, 12), (2, 12, 6, 256, 13),
+                                           (2, 7, 17, 384, 14), (5, 10, 5, 512, 15), (2, 5, 40, 128, 16)])
 def test_fused_gradients_small(B, T, V, H, seed):
     announce("fused forward-backward", B, T, V, H)
     s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed, len_lo=max(1, T - 3), len_hi=T)
@@ -88,7 +88,7 @@ def test_fused_gradients_small(B, T, V, H, seed):
 
 def test_fused_gradients_scale_and_accumulate():
     announce("fused forward-backward, scale and accumulate")
-    s = workloads.shared_emb(B=2, T=6, V=4, order=2, H=64, seed=21, len_lo=4, len_hi=6)
+    s = workloads.shared_emb(B=2, T=6, V=4, order=2, H=128, seed=21, len_lo=4, len_hi=6)
     o, (df, de, dW) = run_fused_grads(s, scale=-0.5)
     lengths = torch.from_numpy(s["lengths"]).cuda()
     lb.last_arc_posteriors(fused_inputs(s), lengths, order=2, dw=(df, de, dW), scale=1.5, accumulate=True)
