@@ -63,7 +63,20 @@ struct FusedArgs {
     int B, T, V, H, C;
     int ncl, XW;
     int spin_limit;
+#ifdef LAST_TRACE
+    unsigned long long* trace;   // [frames][32] cycle marks of workgroup 0 (tuning builds only)
+#endif
 };
+
+#ifdef LAST_TRACE
+#define FU_MARK(a, t, k)                                                                        \
+    do {                                                                                        \
+        if ((a).trace && blockIdx.x == 0 && threadIdx.x == 0 && (t) >= 0 && (t) < 256)          \
+            (a).trace[(size_t)(t) * 32 + (k)] = __builtin_amdgcn_s_memtime();                    \
+    } while (0)
+#else
+#define FU_MARK(a, t, k) do { } while (0)
+#endif
 
 __device__ __forceinline__ float word_value(u64 x) { return __uint_as_float((unsigned)x); }
 
@@ -117,90 +130,127 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// this thread's pairs of frame features, one per chunk
-__device__ __forceinline__ void fused_load_f(const __bf16* __restrict__ ft, int H, unsigned (&fb)[kFuNC])
-{
-    const int kp = threadIdx.x % (kFuKC / 2);
-#pragma unroll
-    for (int c = 0; c < kFuNC; ++c) fb[c] = (kFuKC * c < H) ? *(const unsigned*)(ft + kFuKC * c + 2 * kp) : 0u;
-}
-
-// contraction of hidden-tile chunk C (static, so that the fragment registers are addressed directly)
-template <int MT, int C>
+// Contraction of hidden-tile chunk C (static, so that the fragment registers are addressed
+// directly).  Label waves (BLANK = false) run the four 32-wide steps of the chunk against their
+// 16 labels; the four blank waves share the single empty-label column: wave 4 + i takes step i
+// of every chunk (fragment wfrag[C]) and the partial sums are added up later.
+template <int MT, int C, bool BLANK>
 __device__ __forceinline__ void fused_mfma_chunk(const __bf16* hb, floatx4 (&acc)[MT],
-                                                 const bf16x8 (&wfrag)[kFuMaxKS])
+                                                 const bf16x8 (&wfrag)[kFuMaxKS], int kstep)
 {
     const int lane = threadIdx.x & 63;
     const __bf16* hp = hb + (lane & 15) * kFuHS + 8 * (lane >> 4);
-#pragma unroll
-    for (int ks = 0; ks < kFuKC / 32; ++ks) {
+    if (BLANK) {
         bf16x8 av[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) av[mt] = *(const bf16x8*)&hp[16 * mt * kFuHS + 32 * ks];
+        for (int mt = 0; mt < MT; ++mt) av[mt] = *(const bf16x8*)&hp[16 * mt * kFuHS + 32 * kstep];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wfrag[(kFuKC / 32) * C + ks], acc[mt], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wfrag[C], acc[mt], 0, 0, 0);
+    } else {
+        // two steps per batch: ten LDS reads in flight, then ten matrix instructions
+#pragma unroll
+        for (int k2 = 0; k2 < kFuKC / 64; ++k2) {
+            bf16x8 av[2][MT];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) av[h][mt] = *(const bf16x8*)&hp[16 * mt * kFuHS + 32 * (2 * k2 + h)];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[h][mt], wfrag[(kFuKC / 32) * C + 2 * k2 + h], acc[mt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
 // Hidden tile + contraction of one frame in NC + 1 phases (NC = H / kFuKC).  Phase
-// p runs the matrix-core contraction of chunk p-1 (waves 0..NT-1) and forms the
-// hidden tile tanh(f + e) of chunk p, so the transcendental work of one chunk
-// overlaps the contraction of the previous one; chunks alternate between two LDS
-// buffers.  Afterwards the accumulators of wave n hold w[r][y] for labels
-// 16 n .. 16 n + 15: lane l, tile mt, element i -> row 16 mt + 4 (l / 16) + i,
-// label 16 n + l % 16.
-// e_s [R][H] bf16, hid_s [2][kFuMaxRows][kFuHS] bf16 (constant strides keep the LDS
-// addresses of the contraction immediate), wfrag: this wave's fragments of W.
+// p runs the matrix-core contraction of chunk p-1 and forms the hidden tile
+// tanh(f + e) of chunk p, so the transcendental work of one chunk overlaps the
+// contraction of the previous one; chunks alternate between two LDS buffers.
+// Columns of the weight tile: waves 0..NTL-1 hold labels 16 n + 1 .. 16 n + 16
+// (lane l, tile mt, element i -> row 16 mt + 4 (l / 16) + i, label 16 n + l % 16 + 1);
+// waves 4..7 hold partial sums of the empty-label column (lanes with l % 16 == 0).
+// One contraction wave of each kind per SIMD keeps the matrix cores evenly loaded.
+// f_s [H] bf16 (features of the frame), e_s [R][H] bf16, hid_s [2][kFuMaxRows][kFuHS]
+// bf16 (constant strides keep the LDS addresses of the contraction immediate).
 // `early` (may be null): an exchange word this thread will need afterwards; a first
 // look at it is issued after phase 1 and returned in `early_word`.
 template <int MT>
-__device__ __forceinline__ void fused_weights_phases(const unsigned (&fb)[kFuNC], const __bf16* e_s,
+__device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __bf16* e_s,
                                                      __bf16* hid_s, floatx4 (&acc)[MT],
-                                                     const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NT,
-                                                     const u64* early, u64& early_word)
+                                                     const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NTL,
+                                                     const u64* early, u64& early_word
+#ifdef LAST_TRACE
+                                                     , unsigned long long* trace_row
+#endif
+                                                     )
 {
+#ifdef LAST_TRACE
+#define FU_PMARK(k) do { if (trace_row && blockIdx.x == 0 && threadIdx.x == 0) trace_row[(k)] = __builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define FU_PMARK(k) do { } while (0)
+#endif
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int NC = H / kFuKC;
-    const int kp = tid % (kFuKC / 2), rg = wave;      // 64 pairs x 8 row groups
+    const int kp = tid % (kFuKC / 2);                 // 64 pairs of hidden units x 8 waves
+    // rows of the tanh pass: the label waves, which carry most of the contraction, take the
+    // first RL rows (wave, wave + 4, ...), the other four waves the rest
+    const int RL = (3 * R) / 8 & ~3;
+    const int r_first = wave < 4 ? wave : RL + (wave - 4);
+    const int r_end = wave < 4 ? RL : R;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
     for (int p = 0; p <= NC; ++p) {
         if (p == 2 && early) early_word = xload(early);
-        if (p >= 1 && wave < NT) {
+        FU_PMARK(8 + 3 * p);
+        if (p >= 1) {
             const __bf16* hb = hid_s + ((p - 1) & 1) * kFuHB;
-            switch (p) {
-            case 1: fused_mfma_chunk<MT, 0>(hb, acc, wfrag); break;
-            case 2: fused_mfma_chunk<MT, 1>(hb, acc, wfrag); break;
-            case 3: fused_mfma_chunk<MT, 2>(hb, acc, wfrag); break;
-            default: fused_mfma_chunk<MT, 3>(hb, acc, wfrag); break;
+            if (wave >= 4) {
+                switch (p) {
+                case 1: fused_mfma_chunk<MT, 0, true>(hb, acc, wfrag, wave - 4); break;
+                case 2: fused_mfma_chunk<MT, 1, true>(hb, acc, wfrag, wave - 4); break;
+                case 3: fused_mfma_chunk<MT, 2, true>(hb, acc, wfrag, wave - 4); break;
+                default: fused_mfma_chunk<MT, 3, true>(hb, acc, wfrag, wave - 4); break;
+                }
+            } else if (wave < NTL) {
+                switch (p) {
+                case 1: fused_mfma_chunk<MT, 0, false>(hb, acc, wfrag, 0); break;
+                case 2: fused_mfma_chunk<MT, 1, false>(hb, acc, wfrag, 0); break;
+                case 3: fused_mfma_chunk<MT, 2, false>(hb, acc, wfrag, 0); break;
+                default: fused_mfma_chunk<MT, 3, false>(hb, acc, wfrag, 0); break;
+                }
             }
         }
+        FU_PMARK(9 + 3 * p);
         if (p < NC) {
             __bf16* hb = hid_s + (p & 1) * kFuHB + 2 * kp;
-            const unsigned f2 = p == 0 ? fb[0] : p == 1 ? fb[1] : p == 2 ? fb[2] : fb[3];
+            const unsigned f2 = *(const unsigned*)(f_s + kFuKC * p + 2 * kp);
             const __bf16* ep = e_s + kFuKC * p + 2 * kp;
-            for (int r = rg; r < R; r += 24) {
+            for (int r = r_first; r < r_end; r += 12) {
                 // three rows per trip: the LDS reads go out together
-                const int r1 = r + 8, r2 = r + 16;
+                const int r1 = r + 4, r2 = r + 8;
                 const unsigned e0 = *(const unsigned*)(ep + (size_t)r * H);
-                const unsigned e1 = *(const unsigned*)(ep + (size_t)(r1 < R ? r1 : r) * H);
-                const unsigned e2 = *(const unsigned*)(ep + (size_t)(r2 < R ? r2 : r) * H);
+                const unsigned e1 = *(const unsigned*)(ep + (size_t)(r1 < r_end ? r1 : r) * H);
+                const unsigned e2 = *(const unsigned*)(ep + (size_t)(r2 < r_end ? r2 : r) * H);
                 *(unsigned*)(hb + r * kFuHS) = tanh_pair(f2, e0);
-                if (r1 < R) *(unsigned*)(hb + r1 * kFuHS) = tanh_pair(f2, e1);
-                if (r2 < R) *(unsigned*)(hb + r2 * kFuHS) = tanh_pair(f2, e2);
+                if (r1 < r_end) *(unsigned*)(hb + r1 * kFuHS) = tanh_pair(f2, e1);
+                if (r2 < r_end) *(unsigned*)(hb + r2 * kFuHS) = tanh_pair(f2, e2);
             }
+            FU_PMARK(10 + 3 * p);
             lds_barrier();
         }
     }
 }
 
 // W repacked as matrix-core operand fragments (one 16-byte load per lane and fragment):
-//   Wf [kFuMaxNT][kFuMaxKS][64]: lane l of (n, ks) holds W[32 ks + 8 (l / 16) + j][16 n + l % 16]
-//      (B operand of  w[r][y] = sum_k h[r][k] W[k][y])
+//   Wf [kFuMaxNT][kFuMaxKS][64]: lane l of (n, ks) holds W[32 ks + 8 (l / 16) + j][label], where
+//      label = 16 n + l % 16 + 1 for the label tiles n = 0..3 and, for tile 4, the empty label 0
+//      in column l % 16 == 0 only (B operand of  w[r][y] = sum_k h[r][k] W[k][y])
 //   Wt [H / 16][3][64]:          lane l of (kt, ys) holds W[16 kt + l % 16][32 ys + 8 (l / 16) + j]
 //      (B operand of  d[r][k] = sum_y gamma[r][y] W[k][y]),           j = 0..7, zero outside W
 __global__ void fused_pack_w_kernel(const __bf16* __restrict__ W, int H, int V1, bf16x8* __restrict__ Wf,
@@ -210,7 +260,7 @@ __global__ void fused_pack_w_kernel(const __bf16* __restrict__ W, int H, int V1,
     const int nf = kFuMaxNT * kFuMaxKS * 64;
     if (i < nf) {
         const int lane = i & 63, ks = (i >> 6) % kFuMaxKS, n = (i >> 6) / kFuMaxKS;
-        const int y = 16 * n + (lane & 15);
+        const int y = n < kFuMaxNT - 1 ? 16 * n + (lane & 15) + 1 : ((lane & 15) == 0 ? 0 : V1);
         bf16x8 v;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -233,14 +283,18 @@ __global__ void fused_pack_w_kernel(const __bf16* __restrict__ W, int H, int V1,
     }
 }
 
-// this wave's fragments of W (waves >= kFuMaxNT hold none)
+// Fragments of W for the forward kernel: waves 0..3 hold all steps of their label tile; wave
+// 4 + i holds, for chunk c, the fragment of the empty-label tile for step 4 c + i in wfrag[c].
 __device__ __forceinline__ void fused_load_wfrag(const bf16x8* __restrict__ Wf, bf16x8 (&wfrag)[kFuMaxKS])
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n = wave < kFuMaxNT ? wave : 0;
 #pragma unroll
-    for (int ks = 0; ks < kFuMaxKS; ++ks) wfrag[ks] = Wf[((size_t)n * kFuMaxKS + ks) * 64 + lane];
+    for (int ks = 0; ks < kFuMaxKS; ++ks) {
+        const int n = wave < 4 ? wave : kFuMaxNT - 1;
+        const int k = wave < 4 ? ks : (kFuKC / 32) * (ks & 3) + (wave - 4);
+        wfrag[ks] = Wf[((size_t)n * kFuMaxKS + k) * 64 + lane];
+    }
 }
 
 // largest forward weight among the own states -> header word of this workgroup (wave 0 only)
@@ -249,7 +303,7 @@ __device__ __forceinline__ void fused_publish_header(const float* al, int R, u64
     const int lane = threadIdx.x;            // caller guarantees threadIdx.x < 64
     float mx = (lane < R) ? al[lane] : LAST_NEG_INF;
     if (lane + 64 < R) mx = fmaxf(mx, al[lane + 64]);
-    mx = wave_max(mx);
+    mx = wave_max_dpp(mx);                   // result broadcast to every lane
     if (lane == 0) xstore(slot, pack_word(mx, tag));
 }
 
@@ -262,17 +316,19 @@ __device__ __forceinline__ void fused_publish_header(const float* al, int R, u64
 // while those words travel; finally the own states are assembled from what the
 // other workgroups sent.
 template <int MT>
-__global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
+__global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
-    const int NT = (V1 + 15) / 16;
+    const int NTL = (V + 15) / 16;                                   // label tiles (waves 0..NTL-1)
     __bf16* e_s = (__bf16*)smem_raw;                                  // [R][H]
     __bf16* hid_s = e_s + (size_t)R * H;                              // [2][kFuMaxRows][kFuHS]
     float* al_s = (float*)(hid_s + 2 * kFuHB);                        // [2][kFuMaxRows] forward weights
-    float* bl_s = al_s + 2 * kFuMaxRows;                              // [kFuMaxRows + 8] empty-label terms
-    float* red = bl_s + kFuMaxRows + 8;                               // [32]
+    float* pb_s = al_s + 2 * kFuMaxRows;                              // [4][kFuMaxRows] partial empty-label weights
+    float* sa_s = pb_s + 4 * kFuMaxRows;                              // [8] label arc start -> (b)
+    float* red = sa_s + 8;                                            // [32]
     int* ctl_s = (int*)(red + 32);                                    // [8]
+    __bf16* f_s = (__bf16*)(ctl_s + 8);                               // [H] features of the frame being prepared
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -287,7 +343,6 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
     bf16x8 wfrag[kFuMaxKS];
     fused_load_wfrag(a.Wf, wfrag);
     floatx4 acc[MT];
-    unsigned fb[kFuNC];
     unsigned gstep = 0;
     __syncthreads();
 
@@ -309,6 +364,8 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
         if (L > 0 && wave == 0)
             fused_publish_header(al_s, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
                                  gstep + 1);
+        // frame features travel two frames ahead: register (frame t + 2) -> LDS (frame t + 1)
+        unsigned fnext = (2 * tid < H && L > 0) ? *(const unsigned*)(fi + 2 * tid) : 0u;
         // iteration t = -1 only computes the weights of frame 0
         for (int t = (L > 0 ? -1 : 0); t < L; ++t) {
             const int par = t & 1;
@@ -316,11 +373,14 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
             float* an = al_s + (par ^ 1) * kFuMaxRows;
             const unsigned tag = gstep + 1;
             u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
-            // frame features of the next frame (index clamped: unused after the last frame)
-            fused_load_f(fi + (size_t)(t + 1 < L ? t + 1 : t) * H, H, fb);
+            FU_MARK(a, t, 0);
+            if (2 * tid < H) {
+                *(unsigned*)(f_s + 2 * tid) = fnext;
+                fnext = *(const unsigned*)(fi + (size_t)(t + 2 < L ? t + 2 : L - 1) * H + 2 * tid);
+            }
             // label arcs (b), (a,b) --y--> (b,y): reduced over the own rows, sent to workgroup y
-            if (t >= 0 && wave < NT) {
-                const int g = lane >> 4, y = 16 * wave + (lane & 15);
+            if (t >= 0 && wave < NTL) {
+                const int g = lane >> 4, y = 16 * wave + (lane & 15) + 1;
                 float v[MT][4];
                 float m = LAST_NEG_INF;
 #pragma unroll
@@ -329,39 +389,37 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int row = 16 * mt + 4 * g + i;
-                        v[mt][i] = a4[i] + acc[mt][i];
-                        if (row >= 1 && row < R) m = fmaxf(m, v[mt][i]);
+                        v[mt][i] = (row >= 1 && row < R) ? a4[i] + acc[mt][i] : LAST_NEG_INF;
+                        m = fmaxf(m, v[mt][i]);
                     }
                 }
+                const float v00 = al[0] + acc[0][0];          // row 0 (lanes with g == 0): start --y--> (y)
                 m = fmaxf(m, __shfl_xor(m, 16));
                 m = fmaxf(m, __shfl_xor(m, 32));
+                const float ms = (m == LAST_NEG_INF) ? 0.f : m;
                 float sum = 0.f;
-                if (m != LAST_NEG_INF) {
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int row = 16 * mt + 4 * g + i;
-                            if (row >= 1 && row < R) sum += __expf(v[mt][i] - m);
-                        }
-                }
+                    for (int i = 0; i < 4; ++i) sum += __expf(v[mt][i] - ms);
                 sum += __shfl_xor(sum, 16);
                 sum += __shfl_xor(sum, 32);
                 const float p = (m != LAST_NEG_INF) ? m + __logf(sum) - P_cur : LAST_NEG_INF;
-                if (g == 0 && y >= 1 && y <= V) xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
-                // empty-label arcs of the own states; label arc start -> (b)
-                if (y == 0) {
+                if (g == 0 && y <= V) xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
+                if (g == 0 && y == b) sa_s[0] = v00 - P_cur;
+            } else if (t >= 0 && wave >= 4) {
+                // partial empty-label weights of the own rows
+                if ((lane & 15) == 0) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int row = 16 * mt + 4 * g + i;
-                            if (row < R) bl_s[row] = v[mt][i] - P_cur;
-                        }
+                        for (int i = 0; i < 4; ++i)
+                            pb_s[(wave - 4) * kFuMaxRows + 16 * mt + 4 * (lane >> 4) + i] = acc[mt][i];
                 }
-                if (y == b && g == 0) bl_s[R] = v[0][0] - P_cur;
             }
+            FU_MARK(a, t, 1);
             lds_barrier();
+            FU_MARK(a, t, 2);
             // weights of the next frame while the partial values travel; the first look at the
             // incoming words is issued half way and consumed afterwards
             const u64* pw = nullptr;
@@ -370,22 +428,42 @@ __global__ __launch_bounds__(kFuThreads) void fused_forward_kernel(FusedArgs a)
                 else if (tid >= 128 && tid < 128 + V) pw = xs + (size_t)V * a.XW + (tid - 128);
             }
             u64 x = 0;
-            if (t + 1 < L) fused_weights_phases<MT>(fb, e_s, hid_s, acc, wfrag, R, H, NT, pw, x);
+#ifdef LAST_TRACE
+            if (t + 1 < L) fused_weights_phases<MT>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x,
+                                                    (a.trace && t >= 0 && t < 256) ? a.trace + (size_t)t * 32 : nullptr);
+#else
+            if (t + 1 < L) fused_weights_phases<MT>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x);
+#endif
             else if (pw) x = xload(pw);
             if (t < 0) continue;
+            FU_MARK(a, t, 3);
             // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
             float hv = LAST_NEG_INF;
             if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
+            FU_MARK(a, t, 4);
+            // empty-label arc of own row r: alpha[r] + w[r][0]
+            auto blank = [&](int r) {
+                return al[r] + ((pb_s[r] + pb_s[kFuMaxRows + r]) + (pb_s[2 * kFuMaxRows + r] + pb_s[3 * kFuMaxRows + r])) - P_cur;
+            };
             if (tid >= 1 && tid <= V) {
-                an[1 + tid] = log_add_f(word_value(x), bl_s[1 + tid]);
+                an[1 + tid] = log_add_f(word_value(x), blank(1 + tid));
             } else if (tid == 0) {
-                an[0] = bl_s[0];
-                an[1] = log_add_f(bl_s[R], bl_s[1]);
+                an[0] = blank(0);
+                an[1] = log_add_f(sa_s[0], blank(1));
             } else if (pw) {
                 hv = word_value(x);
             }
-            const float mu = block_max(hv, red);          // contains the barriers that publish `an`
-            if (__syncthreads_or(dead)) ctl_s[0] = 1;
+            // the header words all sit in wave 2: their maximum goes through LDS; one barrier
+            // publishes it together with the new forward weights
+            if (wave == 2) {
+                const float hm = wave_max_dpp(hv);
+                if (lane == 0) red[0] = hm;
+            }
+            if (dead) ctl_s[0] = 1;
+            FU_MARK(a, t, 5);
+            lds_barrier();
+            const float mu = red[0];
+            FU_MARK(a, t, 6);
             // offset bookkeeping, identical everywhere
             const float G = mu - mu_prev + P_prev;
             const float P_next = mu + 2.f * G - P_cur;
@@ -476,13 +554,13 @@ struct FusedERows {
 __device__ __forceinline__ void fused_load_e(const __bf16* __restrict__ e, int V, int b, int R, int H,
                                              FusedERows& er)
 {
-    const int KG = H / 8, nrg = kFuThreads / KG;
-    const int kg = threadIdx.x % KG, rg = threadIdx.x / KG;
+    // lane -> hidden units 8 lane .. 8 lane + 7 (idle when beyond H), wave -> rows wave, wave + 8, ...
+    const int kg = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int kc = 8 * kg < H ? 8 * kg : 0;
 #pragma unroll
     for (int i = 0; i < kFuER; ++i) {
-        const int r = rg + i * nrg;
-        const int rc = (rg < nrg && r < R) ? r : 0;
-        er.v[i] = *(const uintx4*)(e + (size_t)fused_state(V, b, rc) * H + 8 * kg);
+        const int r = rg + 8 * i;
+        er.v[i] = *(const uintx4*)(e + (size_t)fused_state(V, b, r < R ? r : 0) * H + kc);
     }
 }
 
@@ -492,33 +570,43 @@ __device__ __forceinline__ void fused_load_e(const __bf16* __restrict__ e, int V
 template <int MT>
 __device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const FusedERows& er,
                                                    __bf16* hid_s, float* w_s, const bf16x8* __restrict__ Wf,
-                                                   int R, int H, int NT)
+                                                   int R, int H, int NTL, const u64* early, u64& early_word)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KG = H / 8, nrg = kFuThreads / KG;
-    const int kg = tid % KG, rg = tid / KG;
-    // this wave's fragments of W: fetched per frame (L2) so that they are not live in the other phases
-    bf16x8 wfrag[kFuMaxKS];
-    if (wave < NT) {
+    const int kg = lane, rg = wave;              // same mapping as fused_load_e
+    // contraction waves: 0..NTL-1 -> label tiles, 4 -> the empty-label column.  Their fragments
+    // of W are fetched per frame and chunk (L2), one chunk ahead, so that few of them are live.
+    const bool mm = wave < NTL || wave == 4;
+    const bf16x8* wp = Wf + (size_t)wave * kFuMaxKS * 64 + lane;
+    bf16x8 wcur[kFuKC / 32];
+    if (mm) {
 #pragma unroll
-        for (int ks = 0; ks < kFuMaxKS; ++ks) wfrag[ks] = Wf[((size_t)wave * kFuMaxKS + ks) * 64 + lane];
+        for (int ks = 0; ks < kFuKC / 32; ++ks) wcur[ks] = wp[ks * 64];
     }
-    if (rg < nrg) {
+    if (8 * kg < H) {
         const uintx4 f4 = *(const uintx4*)(ft + 8 * kg);
+        __bf16* hw = hid_s + rg * kFuHF + 8 * kg;
 #pragma unroll
         for (int i = 0; i < kFuER; ++i) {
-            const int r = rg + i * nrg;
+            const int r = rg + 8 * i;
             if (r < R) {
                 uintx4 h;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) h[j] = tanh_pair(f4[j], er.v[i][j]);
-                *(uintx4*)(hid_s + r * kFuHF + 8 * kg) = h;
+                for (int j = 0; j < 4; ++j) {
+                    // opaque copy: keeps the unpacking of the (frame-invariant) rows of e inside the frame
+                    // loop; hoisted, the unpacked values would double the registers they take
+                    unsigned eb = er.v[i][j];
+                    asm volatile("" : "+v"(eb));
+                    h[j] = tanh_pair(f4[j], eb);
+                }
+                *(uintx4*)(hw + 8 * i * kFuHF) = h;
             }
         }
     }
     lds_barrier();
-    if (wave < NT) {
+    if (early) early_word = xload(early);        // first look at the exchange word, consumed by the caller
+    if (mm) {
         floatx4 acc[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -526,6 +614,11 @@ __device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft
 #pragma unroll
         for (int c = 0; c < kFuNC; ++c)
             if (kFuKC * c < H) {
+                bf16x8 wnext[kFuKC / 32];
+                if (kFuKC * (c + 1) < H) {
+#pragma unroll
+                    for (int ks = 0; ks < kFuKC / 32; ++ks) wnext[ks] = wp[((kFuKC / 32) * (c + 1) + ks) * 64];
+                }
 #pragma unroll
                 for (int ks = 0; ks < kFuKC / 32; ++ks) {
                     bf16x8 av[MT];
@@ -533,15 +626,19 @@ __device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft
                     for (int mt = 0; mt < MT; ++mt) av[mt] = *(const bf16x8*)&hp[16 * mt * kFuHF + kFuKC * c + 32 * ks];
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wfrag[(kFuKC / 32) * c + ks], acc[mt], 0, 0, 0);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], wcur[ks], acc[mt], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+#pragma unroll
+                for (int ks = 0; ks < kFuKC / 32; ++ks) wcur[ks] = wnext[ks];
             }
+        const int y = wave < 4 ? 16 * wave + (lane & 15) + 1 : 0;
+        if (wave < 4 || (lane & 15) == 0) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + 16 * wave + (lane & 15)] = acc[mt][r];
+                for (int r = 0; r < 4; ++r) w_s[(16 * mt + 4 * (lane >> 4) + r) * kFuWS + y] = acc[mt][r];
+        }
     }
     lds_barrier();
 }
@@ -570,9 +667,9 @@ __device__ __forceinline__ void fused_rows(const float* w_s, const float* bl, co
         float v0 = LAST_NEG_INF, v1 = LAST_NEG_INF;
         if (y0 <= V) v0 = w_s[r * kFuWS + y0] + (y0 == 0 ? bl[r] : nb[y0]) - P;
         if (y1 <= V) v1 = w_s[r * kFuWS + y1] + nb[y1] - P;
-        const float m = wave_max(fmaxf(v0, v1));
+        const float m = wave_max_dpp(fmaxf(v0, v1));        // result broadcast to every lane
         float sum = (y0 <= V ? __expf(v0 - m) : 0.f) + (y1 <= V ? __expf(v1 - m) : 0.f);
-        sum = wave_sum(sum);
+        sum = wave_sum_dpp(sum);
         if (bl_new && lane == 0) bl_new[r] = valid ? m + __logf(sum) : LAST_NEG_INF;
         const float ar = aw_s[r];
         const float g0 = (valid && y0 <= V) ? __expf(ar + v0) : 0.f;
@@ -600,11 +697,11 @@ __device__ __forceinline__ void fused_rows(const float* w_s, const float* bl, co
 // dpre = (gamma W^T)(1 - h^2) on the matrix cores, accumulates de in registers
 // and adds the column sums into df.
 template <int MT>
-__global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs a)
+__global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_backward_kernel(FusedBwdArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
-    const int NT = (V1 + 15) / 16;
+    const int NTL = (V + 15) / 16;
     __bf16* hid_s = (__bf16*)smem_raw;                                // [kFuMaxRows][kFuHF]
     float* w_s = (float*)(hid_s + (size_t)kFuMaxRows * kFuHF);        // [kFuMaxRows][kFuWS]
     __bf16* gh_s = (__bf16*)(w_s + (size_t)kFuMaxRows * kFuWS);       // [kFuMaxRows][kFuGS]
@@ -625,6 +722,9 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
     for (int kt = 0; kt < kFuKT; ++kt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) de_acc[kt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // the rows of e of this workgroup do not change from frame to frame: they stay in registers
+    FusedERows er;
+    fused_load_e(a.e, V, b, R, H, er);
     unsigned gstep = 0;
     __syncthreads();
 
@@ -650,19 +750,24 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
             // publish beta_{t+1}: state (a,b) goes to workgroup a, state (b) to workgroup 1
             if (tid >= 1 && tid <= V) xstore(xs + (size_t)(tid - 1) * a.XW + (b - 1), pack_word(bl[1 + tid], tag));
             else if (tid == V + 1) xstore(xs + (size_t)V * a.XW + (b - 1), pack_word(bl[1], tag));
-            FusedERows er;
-            fused_load_e(a.e, V, b, R, H, er);
             if (tid < R) aw_s[tid] = aws[(size_t)t * a.C + fused_state(V, b, tid)];
-            fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, NT);
-            if (tid >= 1 && tid <= V) {
-                const u64* pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
-                bn_s[tid] = word_value(poll_from(pw, xload(pw), tag, a.spin_limit, dead));
-            } else if (b == 1 && tid >= 128 && tid < 128 + V) {
-                const u64* pw = xs + (size_t)V * a.XW + (tid - 128);
-                bs_s[tid - 127] = word_value(poll_from(pw, xload(pw), tag, a.spin_limit, dead));
-            }
+            const u64* pw = nullptr;
+            if (tid >= 1 && tid <= V) pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
+            else if (b == 1 && tid >= 128 && tid < 128 + V) pw = xs + (size_t)V * a.XW + (tid - 128);
+            u64 x = 0;
+            fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, NTL, pw, x);
+            if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
+            if (tid >= 1 && tid <= V) bn_s[tid] = word_value(x);
+            else if (pw) bs_s[tid - 127] = word_value(x);
             const float P = (float)(offs[t + 1] - offs[t]);
             if (__syncthreads_or(dead)) any_dead = 1;
+            // fragments of W for the dpre contraction: requested now, used after the row pass
+            bf16x8 wt[kFuKT][3];
+#pragma unroll
+            for (int kt = 0; kt < kFuKT; ++kt)
+#pragma unroll
+                for (int ys = 0; ys < 3; ++ys)
+                    wt[kt][ys] = a.Wt[((size_t)min(kFuKT * wave + kt, H / 16 - 1) * 3 + ys) * 64 + lane];
             fused_rows<false>(w_s, bl, bn_s, bs_s, aw_s, P, V, R, b == 1, bl_new, gh_s, gl_s);
             lds_barrier();
             if (tid < R && (tid > 0 || b == 1)) bws[(size_t)t * a.C + fused_state(V, b, tid)] = bl_new[tid];
@@ -672,9 +777,6 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
             for (int kt = 0; kt < kFuKT; ++kt) {
                 const int k0 = 16 * (kFuKT * wave + kt);
                 if (k0 < H) {
-                    bf16x8 wt[3];
-#pragma unroll
-                    for (int ys = 0; ys < 3; ++ys) wt[ys] = a.Wt[((size_t)(kFuKT * wave + kt) * 3 + ys) * 64 + lane];
                     float colsum = 0.f;
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
@@ -685,8 +787,8 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
                                 const int off = (16 * mt + (lane & 15)) * kFuGS + 32 * ys + 8 * (lane >> 4);
                                 const bf16x8 ah = *(const bf16x8*)&gh_s[off];
                                 const bf16x8 al = *(const bf16x8*)&gl_s[off];
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[ys], acc, 0, 0, 0);
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[ys], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[kt][ys], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[kt][ys], acc, 0, 0, 0);
                             }
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -695,6 +797,7 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
                             de_acc[kt][mt][i] += d;
                             colsum += d;
                         }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     colsum += __shfl_xor(colsum, 16);
                     colsum += __shfl_xor(colsum, 32);
@@ -731,7 +834,7 @@ __global__ __launch_bounds__(kFuThreads) void fused_backward_kernel(FusedBwdArgs
 // over one chunk of frames; the marginals are rebuilt from the stored forward
 // and backward weights and the recomputed weights of the frame.
 template <int MT>
-__global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
+__global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_dw_kernel(FusedBwdArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
@@ -768,9 +871,9 @@ __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
     const float* bws = a.beta_ws + (size_t)item * (a.T + 1) * a.C;
     const double* offs = a.offs + (size_t)item * (a.T + 1);
     __syncthreads();
+    FusedERows er;
+    fused_load_e(a.e, V, b, R, H, er);
     for (int t = t0; t < t1; ++t) {
-        FusedERows er;
-        fused_load_e(a.e, V, b, R, H, er);
         if (tid < R) {
             const int q = fused_state(V, b, tid);
             aw_s[tid] = aws[(size_t)t * a.C + q];
@@ -780,7 +883,9 @@ __global__ __launch_bounds__(kFuThreads) void fused_dw_kernel(FusedBwdArgs a)
             bn_s[y] = bws[(size_t)(t + 1) * a.C + 1 + V + (b - 1) * V + (y - 1)];
             if (b == 1) bs_s[y] = bws[(size_t)(t + 1) * a.C + y];
         }
-        fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, NT);
+        u64 unused_word = 0;
+        fused_weights_full<MT>(a.f + ((size_t)item * a.T + t) * H, er, hid_s, w_s, a.Wf, R, H, (V + 15) / 16, nullptr,
+                               unused_word);
         const float P = (float)(offs[t + 1] - offs[t]);
         fused_rows<true>(w_s, bl_s, bn_s, bs_s, aw_s, P, V, R, b == 1, nullptr, gh_s, gl_s);
         lds_barrier();

@@ -272,7 +272,7 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     p.ncl = 256 / s.V;                        // one workgroup per compute unit
     if (p.ncl > s.B) p.ncl = s.B;
     p.XW = (s.V + 7) / 8 * 8;
-    p.lds = (size_t)p.R * H * 2 + (size_t)2 * kFuHB * 2 + (size_t)(3 * kFuMaxRows + 8 + 32 + 8) * 4;
+    p.lds = (size_t)p.R * H * 2 + (size_t)2 * kFuHB * 2 + (size_t)(6 * kFuMaxRows + 8 + 32 + 8) * 4 + (size_t)H * 2;
     const size_t tiles = (size_t)kFuMaxRows * kFuWS * 4 + (size_t)2 * kFuMaxRows * kFuGS * 2;
     p.MT = p.Mpad / 16 <= 1 ? 1 : p.Mpad / 16 <= 3 ? 3 : 5;   // instantiated row-tile counts
     p.lds_bwd = (size_t)kFuMaxRows * kFuHF * 2 + tiles + (size_t)(5 * kFuMaxRows + 8) * 4;
