@@ -132,6 +132,24 @@ def main():
         extra["full_loss_ms"], _ = time_region(loss_step, k, 1)
         extra["shortest_path_ms"], _ = time_region(lambda: lb.last_shortest_path(w, lengths, order=1), k, 1)
         extra["shortest_distance_log_ms"], _ = time_region(lambda: lb.last_shortest_distance(w, lengths, order=1), k, 1)
+        # the trigram lattice with on-the-fly weights (B=4, T=1000, V=64, hidden 512)
+        c4 = workloads.config(4)
+
+        def bf16(bits):
+            return torch.from_numpy(bits.view(np.int16).copy()).cuda().view(torch.bfloat16)
+        se = lb.SharedEmb(bf16(c4["f"]), bf16(c4["e"]), bf16(c4["W"]))
+        len4 = torch.from_numpy(c4["lengths"]).cuda()
+        _, g4 = lb.last_arc_posteriors(se, len4, order=2)
+        extra["fused_trigram_shortest_distance_ms"], _ = time_region(
+            lambda: lb.last_shortest_distance(se, len4, order=2), 3, 1)
+        extra["fused_trigram_fwd_bwd_ms"], _ = time_region(
+            lambda: lb.last_arc_posteriors(se, len4, order=2, dw=g4), 3, 1)
+        arcs4 = float(np.sum(c4["lengths"].astype(np.int64)) * c4["C"] * (c4["V"] + 1))
+        extra["fused_trigram_arcs_per_s_fwd_bwd"] = arcs4 / (extra["fused_trigram_fwd_bwd_ms"] * 1e-3)
+        # matrix-core work of one forward+backward: the weights three times (forward, beta pass, dW pass)
+        # plus the two gradient contractions, 2*H flops per arc each
+        extra["fused_trigram_tflops"] = 5 * 2.0 * 512 * arcs4 / (extra["fused_trigram_fwd_bwd_ms"] * 1e-3) / 1e12
+        del se, g4
         extra["wall_ms_per_step"] = wall_ms
         wt, cx = lb.dense_weights(w), lb.context(cfg["V"], 1)
         extra["kernel_variant"] = lb.last_kernel_variant(wt, cx, lb.OP_ARC_POSTERIORS)

@@ -102,3 +102,32 @@ def test_fused_gradients_config4_shape_short():
     announce("fused forward-backward, config 4 shape, T=6")
     s = workloads.config(4, B=2, T=6)
     run_fused_grads(s)
+
+
+def test_fused_full_size_against_stored_oracle_results():
+    """Config 4 at full size (B=4, T=1000, V=64, hidden 512), the launch configuration the
+    benchmark times.  The float64 oracle needs about 20 core-minutes for it, so its results are
+    stored: tests/golden/config4_fused.npz, written by tests/golden/make_config4_fused.py, which
+    calls only the oracle (D, dW whole, 4096 seeded samples each of df and de)."""
+    import os
+    announce("fused forward-backward, config 4 full size")
+    gold = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config4_fused.npz"))
+    s = workloads.config(4)
+    B = s["f"].shape[0]
+    st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    dist, (df, de, dW) = lb.last_arc_posteriors(fused_inputs(s), torch.from_numpy(s["lengths"]).cuda(),
+                                                order=2, item_status=st)
+    torch.cuda.synchronize()
+    assert st.cpu().tolist() == [0] * B
+    assert_dist_close(dist.cpu().numpy(), gold["D"])
+    assert_grad_close("dW", dW.cpu().numpy(), gold["dW"])
+    dfs = df.cpu().numpy().ravel()[gold["idx_f"]].astype(np.float64)
+    des = de.cpu().numpy().ravel()[gold["idx_e"]].astype(np.float64)
+    for name, got, want, mx in (("df", dfs, gold["df"], float(gold["df_max"])),
+                                ("de", des, gold["de"], float(gold["de_max"]))):
+        tol = 2e-4 * mx + 1e-5
+        err = float(np.max(np.abs(got - want)))
+        assert np.all(np.isfinite(got)), name
+        assert err <= tol, "%s: max abs error %.3g > %.3g (max |ref| %.3g)" % (name, err, tol, mx)
+    # frames past the length of an item get no gradient; the total is finite
+    assert bool(torch.isfinite(df).all()) and bool(torch.isfinite(de).all())
