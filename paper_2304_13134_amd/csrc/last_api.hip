@@ -380,6 +380,26 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
     return hip_status();
 }
 
+// streaming tropical kernel for the full 1-gram context dependency (129 <= C <= 264); false: not applicable
+bool launch_bigram_viterbi(const Shape& s, const float* w, const int* lengths, int* bp, int* final_state,
+                           float* score, int* item_status, hipStream_t st)
+{
+    if (s.order != 1 || s.C < 129 || s.C > kClMaxC || getenv("LAST_FORCE_SOLO")) return false;
+    if ((size_t)s.T * s.C * s.C * 4 >= ((size_t)1 << 31)) return false;   // one buffer descriptor per item
+    if (s.C <= 256) {
+        const int CPAD = 256;
+        const size_t lds = (size_t)(2 * CPAD + 2 * 4 * CPAD + 64) * sizeof(float);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(bigram_viterbi<64, 4>), dim3(s.B), dim3(1024), lds, st, w, lengths,
+                           s.C, s.T, CPAD, bp, final_state, score, item_status);
+    } else {
+        const int CPAD = 320;
+        const size_t lds = (size_t)(2 * CPAD + 2 * 3 * CPAD + 64) * sizeof(float);
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(bigram_viterbi<88, 3>), dim3(s.B), dim3(1024), lds, st, w, lengths,
+                           s.C, s.T, CPAD, bp, final_state, score, item_status);
+    }
+    return true;
+}
+
 last_status_t check_ws(void* ws, size_t have, size_t need)
 {
     if (need == 0) return LAST_OK;
@@ -503,9 +523,10 @@ last_status_t last_shortest_distance(const last_weights_t* weights, const int32_
                            (float*)nullptr, (double*)nullptr, (double*)nullptr, dist, item_status);
     } else {
         if (l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st,
-                           weights->w, lengths, c, s.T, l.CPAD, l.R,
-                           (int*)nullptr, (int*)nullptr, dist, item_status);
+        if (!launch_bigram_viterbi(s, weights->w, lengths, nullptr, nullptr, dist, item_status, st))
+            hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st,
+                               weights->w, lengths, c, s.T, l.CPAD, l.R,
+                               (int*)nullptr, (int*)nullptr, dist, item_status);
     }
     return hip_status();
 }
@@ -629,8 +650,9 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
     const Ctx c = make_ctx(s);
     Carver cv(ws);
     PathWs p = carve_path(cv, s);
-    hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,
-                       c, s.T, l.CPAD, l.R, p.bp, p.final_state, score, item_status);
+    if (!launch_bigram_viterbi(s, weights->w, lengths, p.bp, p.final_state, score, item_status, st))
+        hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,
+                           c, s.T, l.CPAD, l.R, p.bp, p.final_state, score, item_status);
     hipLaunchKernelGGL(backtrace_kernel, dim3(s.B), dim3(256), 0, st, (const int*)p.bp, lengths,
                        (const int*)p.final_state, s.C, s.V1, s.T, labels, states);
     return hip_status();

@@ -191,6 +191,12 @@ __global__ __launch_bounds__(1024) void solo_backward_log(
 }
 
 // zero the gradient of items whose length is invalid (used by the clustered path too)
+// workgroup barrier that orders LDS traffic only: global loads issued before it stay in flight
+__device__ __forceinline__ void lds_only_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __global__ void zero_fill_kernel(float* __restrict__ p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
@@ -267,6 +273,118 @@ __global__ __launch_bounds__(1024) void solo_viterbi(
     float best = LAST_NEG_INF;
     int bidx = 0x7fffffff;
     for (int d = tid; d < c.C; d += blockDim.x)
+        if (cur[d] > best || (cur[d] == best && d < bidx)) { best = cur[d]; bidx = d; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(bidx, o, kWave);
+        if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
+    }
+    const int wid = tid / kWave, nw = blockDim.x / kWave;
+    if ((tid & (kWave - 1)) == 0) { redv[wid] = best; redi[wid] = bidx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < nw; ++k)
+            if (redv[k] > best || (redv[k] == best && redi[k] < bidx)) { best = redv[k]; bidx = redi[k]; }
+        score[b] = best;
+        if (final_state) final_state[b] = bidx;
+    }
+}
+
+// Tropical recursion for the full 1-gram context dependency (state = last label,
+// C = V + 1), the bandwidth version of solo_viterbi: one workgroup per item, R row
+// groups x CPAD columns.  Thread (g, y) keeps column y of rows g, g + R, ... of
+// the NEXT frame in registers while it consumes the current one, so a whole frame
+// (C*C*4 bytes) is in flight per compute unit and the weights are streamed at
+// what one compute unit can pull from HBM.  Barriers order LDS only, so the loads
+// stay in flight across them.  Same decisions as solo_viterbi: one float32 add per
+// arc, exact comparisons, ties to the lowest flat arc index q*(V+1)+y.
+// Column 0 holds the empty-label arcs q -> q; they are combined per destination.
+template <int NR, int R>
+__global__ __launch_bounds__(1024) void bigram_viterbi(
+    const float* __restrict__ w, const int* __restrict__ len, int C, int T, int CPAD,
+    int* __restrict__ bp, int* __restrict__ final_state, float* __restrict__ score,
+    int* __restrict__ item_status)
+{
+    extern __shared__ float smem[];
+    float* cur = smem;                      // [C] best score per state
+    float* bw = cur + CPAD;                 // [C] empty-label weight of the frame per state
+    float* pv = bw + CPAD;                  // [R][CPAD] partial best values
+    int* pi = (int*)(pv + R * CPAD);        // [R][CPAD] their row-step index
+    float* redv = (float*)(pi + R * CPAD);
+    int* redi = (int*)(redv + 32);
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int L = len[b];
+    if (L < 0 || L > T) {
+        if (tid == 0) {
+            if (item_status) item_status[b] = kItemBadLength;
+            score[b] = __builtin_nanf("");
+            if (final_state) final_state[b] = -1;
+        }
+        return;
+    }
+    if (tid == 0 && item_status) item_status[b] = kItemOk;
+    const int g = tid / CPAD, y = tid - g * CPAD;
+    const bool active = g < R && y < C;
+    const size_t fr = (size_t)C * C;
+    const float* wb = w + (size_t)b * T * fr;
+    // element (row g + R i, column y) of a frame through a buffer descriptor over the item's
+    // weights: per-thread byte offset + scalar offset (frame, row step); rows past the frame read
+    // whatever follows (ignored), reads past the item return 0, so no load needs a guard
+    const int yc = y < C ? y : 0, gc = g < R ? g : 0;
+    const int voff = (gc * C + yc) * 4;
+    const int stride = R * C * 4;
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(wb), 0, (int)((size_t)T * fr * 4), 0x00020000);
+    float reg[NR];
+    for (int d = tid; d < CPAD; d += blockDim.x) cur[d] = d == 0 ? 0.f : LAST_NEG_INF;
+    if (L > 0) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i)
+            reg[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, i * stride, 0));
+    }
+    lds_only_barrier();
+    for (int t = 0; t < L; ++t) {
+        const int fo = (int)((size_t)(t + 1 < L ? t + 1 : t) * fr * 4);
+        float best = LAST_NEG_INF;
+        int bi = -1;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const float wv = reg[i];
+            reg[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, fo + i * stride, 0));
+            const int q = g + R * i;
+            if (q < C) {
+                if (y == 0) {
+                    if (active) bw[q] = wv;
+                } else {
+                    const float v = __fadd_rn(cur[q], wv);
+                    if (v > best) { best = v; bi = i; }          // ascending q: the first maximum stays
+                }
+            }
+        }
+        if (active) { pv[g * CPAD + y] = best; pi[g * CPAD + y] = bi; }
+        lds_only_barrier();
+        if (g == 0 && y < C) {
+            // destination y: label arcs from every q (partial maxima of the row groups), empty label from y itself
+            float bv = LAST_NEG_INF;
+            int bflat = 0x7fffffff;
+            if (y > 0) {
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    const int i = pi[k * CPAD + y];
+                    if (i >= 0) trop_acc(pv[k * CPAD + y], (k + R * i) * C + y, bv, bflat);
+                }
+            }
+            trop_acc(__fadd_rn(cur[y], bw[y]), y * C, bv, bflat);
+            cur[y] = bv;
+            if (bp) bp[((size_t)b * T + t) * C + y] = (bflat == 0x7fffffff) ? -1 : bflat;
+        }
+        lds_only_barrier();
+    }
+    // best final state, lowest index among equals
+    float best = LAST_NEG_INF;
+    int bidx = 0x7fffffff;
+    for (int d = tid; d < C; d += blockDim.x)
         if (cur[d] > best || (cur[d] == best && d < bidx)) { best = cur[d]; bidx = d; }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {

@@ -137,6 +137,11 @@ def test_viterbi_ties_follow_the_lowest_flat_index():
     w = rng.integers(-2, 3, size=(4, 30, 9, 9)).astype(np.float32)   # many exact ties
     cfg = dict(w=w, lengths=np.array([30, 17, 1, 30], np.int32), B=4)
     check_path(cfg)
+    # the streaming kernel of the full 1-gram context dependency (both of its tilings)
+    for C in (129, 200, 256, 257, 264):
+        announce("tie rules on integer weights, C =", C)
+        wc = rng.integers(-1, 2, size=(2, 11, C, C)).astype(np.float32)
+        check_path(dict(w=wc, lengths=np.array([11, 6], np.int32), B=2))
     w0 = np.zeros((1, 5, 4, 4), np.float32)
     labels, states, score = lb.last_shortest_path(dev(w0), dev(np.array([5], np.int32)))
     assert labels.cpu().tolist() == [[0] * 5] and states.cpu().tolist() == [[0] * 6]
