@@ -92,7 +92,10 @@ enum { LAST_WEIGHTS_DENSE = 0, LAST_WEIGHTS_SHARED_EMB = 1 };
  * kind = shared_emb: f dev bf16 [B][T][hidden], e dev bf16 [C][hidden],
  * W dev bf16 [hidden][V+1] (bf16 = upper 16 bits of a float32); the hidden
  * vector tanh(f + e) is rounded to bf16 before the float32-accumulated
- * contraction with W; the weights are never stored. */
+ * contraction with W; the weights are never stored (Section 4.1).  Supported
+ * for context size 2, V <= 64, hidden a multiple of 128 up to 512, in
+ * last_shortest_distance (LAST_LOG) and last_arc_posteriors; f, e, W must be
+ * 16-byte aligned.  Other combinations return LAST_ERR_UNSUPPORTED. */
 typedef struct {
     int32_t kind;
     int32_t B, T;
@@ -172,7 +175,10 @@ const char* last_status_string(last_status_t status);
 const char* last_hip_error_string(void);
 
 /* Library version and the kernel variant a call would use, for diagnostics:
- * 0 = one workgroup per item, 1 = cooperating workgroups per item. */
+ * 0 = one workgroup per item, 1 = cooperating workgroups per item (dense
+ * weights, context size 1), 2 = on-the-fly weights (shared_emb), -1 = the
+ * combination is not supported (the call would return LAST_ERR_UNSUPPORTED or
+ * an argument error). */
 int32_t last_version(void);
 int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t* context,
                             int32_t op);

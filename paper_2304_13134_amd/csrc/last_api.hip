@@ -266,6 +266,8 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     if (wt->kind != LAST_WEIGHTS_SHARED_EMB || s.order != 2) return p;
     const int H = wt->hidden;
     if (s.V > 64 || H % kFuKC != 0 || H < kFuKC || H > 512) return p;
+    // the kernels fetch f and e with 16-byte loads
+    if (((uintptr_t)wt->f | (uintptr_t)wt->e | (uintptr_t)wt->W) % 16 != 0) return p;
     p.R = s.V + 2;
     p.Mpad = (p.R + 15) / 16 * 16;
     p.KC = H < kFuKC ? H : kFuKC;
@@ -445,6 +447,10 @@ int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t*
 {
     Shape s;
     if (check_common(weights, context, &s) != LAST_OK) return -1;
+    if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
+        const bool op_ok = op == LAST_OP_SHORTEST_DISTANCE || op == LAST_OP_ARC_POSTERIORS;
+        return (op_ok && fused_plan(s, weights).ok) ? 2 : -1;
+    }
     if (op == LAST_OP_SHORTEST_DISTANCE || op == LAST_OP_ARC_POSTERIORS)
         return cluster_plan(s, weights->kind).ok ? 1 : 0;
     return 0;

@@ -89,3 +89,37 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(TypeError):
         lb.last_shortest_distance(torch.zeros(1, 2, 4, 4), torch.zeros(1, dtype=torch.int32))
+
+
+def _se(B=4, T=10, H=512):
+    return lb.LastWeights(lb.WEIGHTS_SHARED_EMB, B, T, None, 0x1000, 0x2000, 0x3000, H)
+
+
+def test_shared_embedding_plan_is_checked_on_the_host(lib):
+    cx = lb.context(64, 2)
+    assert cx.num_states == 4161
+    need_d = lb.last_workspace_bytes(_se(), cx, lb.OP_SHORTEST_DISTANCE)
+    need_g = lb.last_workspace_bytes(_se(), cx, lb.OP_ARC_POSTERIORS)
+    # the gradient pass keeps the forward and backward weights of every state-frame
+    assert need_d > 0 and need_g >= need_d + 2 * 4 * 11 * 4161 * 4
+    assert lb.last_kernel_variant(_se(), cx, lb.OP_ARC_POSTERIORS) == 2
+    # unsupported combinations: hidden size, vocabulary, context size, operation
+    assert lb.last_workspace_bytes(_se(H=96), cx, lb.OP_ARC_POSTERIORS) == 0
+    assert lb.last_workspace_bytes(_se(H=640), cx, lb.OP_ARC_POSTERIORS) == 0
+    assert lb.last_workspace_bytes(_se(), lb.context(65, 2), lb.OP_ARC_POSTERIORS) == 0
+    assert lb.last_workspace_bytes(_se(), lb.context(64, 1), lb.OP_ARC_POSTERIORS) == 0
+    assert lb.last_workspace_bytes(_se(), cx, lb.OP_SHORTEST_PATH) == 0
+    assert lb.last_kernel_variant(_se(H=96), cx, lb.OP_ARC_POSTERIORS) == -1
+    vp = ctypes.c_void_p
+    dummy = vp(0x4000)
+    se, bad = _se(), _se(H=96)
+    g = lb.LastGrads(None, 0x5000, 0x6000, 0x7000, 0, 1.0)
+    assert lib.last_arc_posteriors(ctypes.byref(bad), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None,
+                                   dummy, 1 << 30, None) == 6
+    assert lib.last_shortest_distance(ctypes.byref(se), dummy, ctypes.byref(cx), lb.LAST_TROPICAL, dummy, None,
+                                      dummy, 1 << 30, None) == 6
+    gnull = lb.LastGrads(None, None, 0x6000, 0x7000, 0, 1.0)
+    assert lib.last_arc_posteriors(ctypes.byref(se), dummy, ctypes.byref(cx), dummy, ctypes.byref(gnull), None,
+                                   dummy, 1 << 30, None) == 1
+    assert lib.last_arc_posteriors(ctypes.byref(se), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None,
+                                   dummy, 4096, None) == 5
