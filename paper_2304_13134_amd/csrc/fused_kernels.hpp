@@ -889,26 +889,30 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         const float P = (float)(offs[t + 1] - offs[t]);
         fused_rows<true>(w_s, bl_s, bn_s, bs_s, aw_s, P, V, R, b == 1, nullptr, gh_s, gl_s);
         lds_barrier();
+        // row step by row step: the h^T fragments of the wave's four column tiles are formed once,
+        // every gamma fragment is read once and meets all four
+        if (16 * kFuKT * wave < H) {
 #pragma unroll
-        for (int kt = 0; kt < kFuKT; ++kt) {
-            const int k0 = 16 * (kFuKT * wave + kt);
-            if (k0 < H) {
+            for (int rs = 0; rs < RS; ++rs) {
+                bf16x8 hv[kFuKT];
 #pragma unroll
-                for (int rs = 0; rs < RS; ++rs) {
-                    bf16x8 hv;
+                for (int kt = 0; kt < kFuKT; ++kt)
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) hv[j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * kFuHF + k0 + (lane & 15)];
+                    for (int j = 0; j < 8; ++j)
+                        hv[kt][j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * kFuHF + 16 * (kFuKT * wave + kt) + (lane & 15)];
 #pragma unroll
-                    for (int yt = 0; yt < kFuMaxNT; ++yt)
-                        if (yt < NT) {
-                            const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
-                            const bf16x8 gh = *(const bf16x8*)&gh_s[off];
-                            const bf16x8 gl = *(const bf16x8*)&gl_s[off];
-                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gh, acc[kt][yt], 0, 0, 0);
-                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv, gl, acc[kt][yt], 0, 0, 0);
+                for (int yt = 0; yt < kFuMaxNT; ++yt)
+                    if (yt < NT) {
+                        const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
+                        const bf16x8 gh = *(const bf16x8*)&gh_s[off];
+                        const bf16x8 gl = *(const bf16x8*)&gl_s[off];
+#pragma unroll
+                        for (int kt = 0; kt < kFuKT; ++kt) {
+                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gh, acc[kt][yt], 0, 0, 0);
+                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gl, acc[kt][yt], 0, 0, 0);
                         }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         lds_barrier();
