@@ -1,0 +1,740 @@
+// Second generation of the clustered forward-backward for the full 1-gram
+// context dependency (arXiv 2304.13134, Eq. 2 / Eq. 1, Sections 4.1, 4.2.2):
+// ONE exchange per TWO frames.
+//
+// Same decomposition as cluster_kernels.hpp (an item = 2K persistent workgroups
+// on one XCD, K walking frames upwards, K downwards, meeting in the middle;
+// workgroup k owns states [k*RPW, (k+1)*RPW)), but the two frames between
+// exchanges are processed with two different ownerships of the weight matrix
+// M_t[q][y] = exp(w_t[q][y]):
+//   F-step ("from the full vector"): every workgroup knows the whole state vector
+//       and produces its OWN states of the next one without communication;
+//       alpha: a'[y] = sum_q a[q] M[q][y] for its own columns y (reads all rows x own columns),
+//       beta : b'[q] = sum_y M[q][y] b[y] for its own rows q (reads own rows x all columns);
+//   P-step ("partials"): from its own states only, every workgroup produces a
+//       partial result for ALL states,
+//       alpha: p_k[y] = sum_{q own} a[q] M[q][y]   (own rows x all columns),
+//       beta : p_k[q] = sum_{y own} M[q][y] b[y]   (all rows x own columns),
+//       publishes the C partial values, and every workgroup reads all K x C of
+//       them and adds them up in the same order: the whole next vector, bit for
+//       bit the same everywhere.
+// Either way each element of the frame is read by exactly one workgroup, so the
+// traffic is unchanged (12 B/arc with the marginals), the number of latency-bound
+// exchanges is halved, and because the summed vector is complete and identical in
+// every workgroup its binary exponent is taken from the data itself (no predicted
+// exponent steps).  Own parts carry a per-workgroup exponent, so stored state
+// vectors have one exponent per block of RPW states (Sa, Sb: [B][T+1][8]).
+//
+// The empty label (column 0) keeps the state: w[q][0] is an arc q -> q.  In the
+// steps that read "own columns" the workgroup reads column 0 for its own rows
+// separately.
+//
+// Arithmetic as in cluster_kernels.hpp: E = 2^(w log2 e - s) with integer shifts s
+// from the data (per column or per row), evaluated while the exchange of the
+// previous pair is in flight.  Exchange words are [value:32 | tag:32], published
+// with plain stores into the XCD's L2 and gathered with agent-scope loads, 8 + 8
+// per thread in flight; all waits are bounded (status 5 instead of a hang).
+#pragma once
+#include "cluster_kernels.hpp"
+
+namespace last {
+
+constexpr int kC2Threads = 512;   // 8 waves = 2 per SIMD: 256 registers per lane
+constexpr int kC2Waves = 8;
+constexpr int kC2NQ = 33;      // rows per wave when a workgroup reads all rows: 8 * 33 >= 264
+constexpr int kC2Hdr = 264;    // exchange row: C values, the producer's exponent at [kC2Hdr]
+constexpr int kC2XS = 272;     // words per producer and slot
+constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
+constexpr int kC2RT = 33;      // own rows per column thread (alpha P-step)
+constexpr int kC2Own = 40;     // LDS slots for own states
+
+// LDS map (floats / ints)
+constexpr int kC2Full = 0;                          // [320] whole state vector
+constexpr int kC2OwnS = kC2Full + 320;              // [40]  own states
+constexpr int kC2Red = kC2OwnS + kC2Own;            // [8][40] cross-wave partials
+constexpr int kC2Shw = kC2Red + kC2Waves * kC2Own;  // [8][40] shifts per wave (int)
+constexpr int kC2Bl = kC2Shw + kC2Waves * kC2Own;   // [40] empty-label terms
+constexpr int kC2Pacc = kC2Bl + kC2Own;             // [320] partial sums of the second half
+constexpr int kC2Bo = kC2Pacc + 320;                // [40] other side's own-state values (marginals)
+constexpr int kC2Ctl = kC2Bo + kC2Own;              // [32] ints
+constexpr int kC2RedB = kC2Ctl + 32;                // [32] block reductions
+constexpr int kC2Lds = kC2RedB + 32;
+
+#ifdef LAST_TRACE
+#define C2_MARK(a, p, k)                                                                    \
+    do {                                                                                    \
+        if ((a).trace && (p) < 64 && threadIdx.x == 0)                                      \
+            (a).trace[((size_t)blockIdx.x * 64 + (p)) * 8 + (k)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#else
+#define C2_MARK(a, p, k) do { } while (0)
+#endif
+
+__device__ __forceinline__ void c2_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e, zero stays zero
+{
+    return (v == 0.f) ? 0.f : __builtin_ldexpf(v, max(e, -300));
+}
+
+// Read all K x C partial values and the K exponents of one exchange slot, add the values up in
+// producer order relative to the largest exponent, leave the vector in full_s and its exponent
+// in ctl_s[0].  Every thread calls; ends with a workgroup barrier.
+__device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
+                                          int* ctl_s, int limit, int& dead)
+{
+    const int tid = threadIdx.x;
+    float v = 0.f;
+    int hr = 0;
+    if (tid < C) {
+        u64 wv[kClMaxK], hv[kClMaxK];
+        int n = 0;
+        for (;;) {
+            bool ok = true;
+#pragma unroll
+            for (int kk = 0; kk < kClMaxK; ++kk)
+                if (kk < K) {
+                    wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
+                    hv[kk] = xload(xs + (size_t)kk * kC2XS + kC2Hdr);
+                }
+#pragma unroll
+            for (int kk = 0; kk < kClMaxK; ++kk)
+                if (kk < K) ok = ok && (unsigned)(wv[kk] >> 32) == tag && (unsigned)(hv[kk] >> 32) == tag;
+            if (ok || dead) break;
+            if (++n > limit) { dead = 1; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        int href = -(1 << 30);
+#pragma unroll
+        for (int kk = 0; kk < kClMaxK; ++kk)
+            if (kk < K) href = max(href, (int)(unsigned)hv[kk]);
+#pragma unroll
+        for (int kk = 0; kk < kClMaxK; ++kk)
+            if (kk < K) v += c2_scale(__uint_as_float((unsigned)wv[kk]), (int)(unsigned)hv[kk] - href);
+        hr = href;
+    }
+    // renormalise by the largest magnitude actually present, so that mantissas do not drift
+    const int mu = wave_max_dpp(v > 0.f ? float_exponent(v) : -(1 << 20));
+    if ((tid & 63) == 0) ctl_s[24 + (tid >> 6)] = mu;
+    if (dead) ctl_s[8] = 1;
+    c2_barrier();
+    int mx = -(1 << 20);
+#pragma unroll
+    for (int w2 = 0; w2 < kC2Waves; ++w2) mx = max(mx, ctl_s[24 + w2]);
+    if (mx == -(1 << 20)) mx = 0;
+    if (tid < C) full_s[tid] = c2_scale(v, -mx);
+    if (tid == 0) ctl_s[0] = hr + mx;
+    c2_barrier();
+}
+
+// D = log2 sum_q a_mid[q] b_mid[q] with one exponent per block of RPW states on either side
+__device__ __forceinline__ double c2_meeting(const float* ah, const float* bh, const int* Sa, const int* Sb,
+                                             int C, int RPW, int K, float* red)
+{
+    int xmax = -(1 << 30);
+    for (int k = 0; k < K; ++k) xmax = max(xmax, Sa[k] + Sb[k]);
+    float part = 0.f;
+    for (int q = threadIdx.x; q < C; q += blockDim.x) {
+        const int k = q / RPW;
+        part += c2_scale(ah[q] * bh[q], Sa[k] + Sb[k] - xmax);
+    }
+    const float tot = block_sum(part, red);
+    return (double)xmax + (double)__log2f(tot);
+}
+
+// ------------------------------------------------------------------ alpha role
+template <bool GAMMA>
+__device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
+                                            unsigned& gstep, unsigned& ptag)
+{
+    float* full_s = smem + kC2Full;
+    float* own_s = smem + kC2OwnS;
+    float* red_s = smem + kC2Red;
+    int* shw_s = (int*)(smem + kC2Shw);
+    float* bl_s = smem + kC2Bl;
+    float* pacc_s = smem + kC2Pacc;
+    float* bo_s = smem + kC2Bo;
+    int* ctl_s = (int*)(smem + kC2Ctl);       // [0] exponent of full_s, [1] exponent of own_s, [8] timeout
+    float* redb = smem + kC2RedB;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int C = a.C, K = a.K, RPW = a.RPW;
+    // P-step: thread <-> column cP (waves 0..4), all own rows
+    const int cP = tid;
+    const bool colok = cP < C;
+    const int nrtP = g.nr;
+    // F-step: lane <-> own column, wave <-> rows wave, wave + 8, ...
+    const bool fok = lane < g.nr;
+    const int yF = min(g.r0 + lane, C - 1);
+    const bool f_no_label = g.r0 + lane == 0;         // state 0 receives no label arcs
+
+    for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
+        int L = a.len[b];
+        const bool bad = L < 0 || L > a.T;
+        if (bad) L = 0;
+        const int mid = L / 2;
+        const int n = GAMMA ? L : mid;
+        const size_t fr = (size_t)C * C;
+        const unsigned frb = (unsigned)(fr * sizeof(float));
+        const unsigned pitch = (unsigned)(C * (int)sizeof(float));
+        float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
+        const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
+        int* Sa = a.Sa + (size_t)b * (a.T + 1) * kClMaxK;
+        const int* Sb = a.Sb + (size_t)b * (a.T + 1) * kClMaxK;
+        u64* xbase = a.xa + (size_t)g.cg * 2 * kClMaxK * kC2XS;
+        const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+        const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        const unsigned coffP = (unsigned)(min(cP, C - 1) * (int)sizeof(float));
+        const unsigned rbaseP = (unsigned)g.r0 * pitch;
+        const unsigned coffF = (unsigned)(yF * (int)sizeof(float));
+        const unsigned rowF0 = (unsigned)wave * pitch;               // scalar: first row of this wave
+        const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
+        const int nlast = max(n - 1, 0);
+
+        // a_0 = unit vector at the start state, exponent 0
+        for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q == 0 ? 1.f : 0.f;
+        if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; bo_s[tid] = 0.f; }
+        if (tid < 32) ctl_s[tid] = 0;
+        if (tid < g.nr) ah[g.r0 + tid] = (g.r0 + tid == 0) ? 1.f : 0.f;
+        if (tid == 0) Sa[g.k] = 0;
+        __syncthreads();
+
+        float EF[2][kC2NQ], EP[2][kC2RT];
+        float EB[2] = {0.f, 0.f};
+        int shF[2] = {0, 0}, shP[2] = {0, 0}, sigP[2] = {0, 0};
+        float bF[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f};     // other side's vector for the marginals
+        int sbF[2] = {0, 0}, sbP[2] = {0, 0};
+        double D2 = 0.0;
+        int dead = 0;
+        bool met = false;
+
+        // state vectors of the other side for the marginals of pair p (rows t + 1 of its two frames);
+        // fetched one pair ahead, and again right after the meeting for the pairs in flight
+        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            const int tF = min(2 * p, nlast), tP = min(2 * p + 1, nlast);
+            bF[B_] = bh[(size_t)(tF + 1) * C + yF];
+            sbF[B_] = Sb[(size_t)(tF + 1) * kClMaxK + g.k];
+            bPv[B_] = bh[(size_t)(tP + 1) * C + min(cP, C - 1)];
+            sbP[B_] = Sb[(size_t)(tP + 1) * kClMaxK + min(cP, C - 1) / RPW];
+        };
+        auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            const unsigned foF = (unsigned)min(2 * p, nlast) * frb;
+            const unsigned foP = (unsigned)min(2 * p + 1, nlast) * frb;
+#pragma unroll
+            for (int j = 0; j < kC2NQ; ++j) EF[B_][j] = buf_load(wrs, coffF, foF + rowF0 + (unsigned)(kC2Waves * j) * pitch);
+            EB[B_] = buf_load(wrs, 0u, foF + rowB);
+#pragma unroll
+            for (int r = 0; r < kC2RT; ++r) EP[B_][r] = buf_load(wrs, coffP, foP + rbaseP + (unsigned)r * pitch);
+            if (GAMMA) other(BUF, p);
+        };
+        // exp pass of both frames of a pair (contains workgroup barriers)
+        auto prep = [&](auto BUF) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            // F frame: one shift per own column, common to the ten waves
+            float mx = LAST_NEG_INF;
+#pragma unroll
+            for (int j = 0; j < kC2NQ; ++j) {
+                if (wave + kC2Waves * j >= C || f_no_label) EF[B_][j] = LAST_NEG_INF;
+                mx = fmaxf(mx, EF[B_][j]);
+            }
+            if (wave == 0) mx = fmaxf(mx, EB[B_]);
+            if (lane < kC2Own) shw_s[wave * kC2Own + lane] = shift_for(mx);
+            // P frame: one shift per column and thread, the workgroup's largest as reference
+            float mp = LAST_NEG_INF;
+#pragma unroll
+            for (int r = 0; r < kC2RT; ++r) {
+                if (r >= nrtP) EP[B_][r] = LAST_NEG_INF;
+                mp = fmaxf(mp, EP[B_][r]);
+            }
+            const int sp = shift_for(mp);
+            const int wm = wave_max_dpp(colok ? sp : kShiftNone);
+            if (lane == 0) ctl_s[16 + wave] = wm;
+            c2_barrier();
+            int sc = kShiftNone;
+            if (lane < kC2Own) {
+#pragma unroll
+                for (int w2 = 0; w2 < kC2Waves; ++w2) sc = max(sc, shw_s[w2 * kC2Own + lane]);
+            }
+            int sg = kShiftNone;
+#pragma unroll
+            for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
+            const float fsc = (float)sc, fsp = (float)sp;
+#pragma unroll
+            for (int j = 0; j < kC2NQ; ++j) EF[B_][j] = fast_exp2(fmaf(EF[B_][j], kLog2e, -fsc));
+            EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -fsc));
+#pragma unroll
+            for (int r = 0; r < kC2RT; ++r) EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp));
+            shF[B_] = sc; shP[B_] = sp; sigP[B_] = sg;
+            c2_barrier();
+        };
+        auto meet = [&]() __attribute__((always_inline)) {
+            if (dead) ctl_s[8] = 1;
+            cluster_sync(a, g, ptag, &ctl_s[8]);
+            ptag += 1;
+            D2 = c2_meeting(ah + (size_t)mid * C, bh + (size_t)mid * C, Sa + (size_t)mid * kClMaxK,
+                            Sb + (size_t)mid * kClMaxK, C, RPW, K, redb);
+            if (g.k == 0 && tid == 0) {
+                a.dist[b] = bad ? __builtin_nanf("") : (float)(D2 * 0.6931471805599453);
+                if (a.item_status)
+                    a.item_status[b] = bad ? kItemBadLength : (ctl_s[8] ? kItemTimeout : kItemOk);
+            }
+            met = true;
+            __syncthreads();
+        };
+
+        issue(std::integral_constant<int, 0>(), 0);
+        prep(std::integral_constant<int, 0>());
+
+        int p = 0;
+        auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
+            constexpr int B_ = decltype(BUF)::value;
+            const int tF = 2 * p, tP = 2 * p + 1;
+            if (tF >= n) return false;
+            C2_MARK(a, p, 0);
+            issue(std::integral_constant<int, B_ ^ 1>(), p + 1);
+            C2_MARK(a, p, 1);
+            // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
+            if (tF == mid && !met) {
+                meet();
+                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+            }
+            {
+                const int S = ctl_s[0];
+                float ps = 0.f;
+#pragma unroll
+                for (int j = 0; j < kC2NQ; ++j) ps = fmaf(full_s[min(wave + kC2Waves * j, 319)], EF[B_][j], ps);
+                if (lane < kC2Own) red_s[wave * kC2Own + lane] = ps;
+                if (GAMMA && tF >= mid && fok) {
+                    const float fc = a.scale * bF[B_] *
+                                     fast_exp2((float)((double)(sbF[B_] + shF[B_] + S) - D2));
+                    const unsigned gso = (unsigned)tF * frb;
+#pragma unroll
+                    for (int j = 0; j < kC2NQ; ++j)
+                        if (wave + kC2Waves * j < C && !f_no_label)
+                            buf_store(full_s[wave + kC2Waves * j] * EF[B_][j] * fc, grs, coffF,
+                                      gso + rowF0 + (unsigned)(kC2Waves * j) * pitch);
+                    if (wave == 0) buf_store(full_s[yF] * EB[B_] * fc, grs, 0u, gso + rowB);
+                }
+                c2_barrier();
+                if (wave == 0) {
+                    float v = 0.f;
+                    if (fok) {
+#pragma unroll
+                        for (int w2 = 0; w2 < kC2Waves; ++w2) v += red_s[w2 * kC2Own + lane];
+                        v = fmaf(full_s[yF], EB[B_], v);
+                    }
+                    const int sc = (fok && v > 0.f) ? shF[B_] + float_exponent(v) : kShiftNone;
+                    const int ms = wave_max_dpp(sc);
+                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shF[B_] - ms);
+                    if (lane < kC2Own) own_s[lane] = own;
+                    const int ek = (ms == kShiftNone) ? S : S + ms;
+                    if (lane == 0) ctl_s[1] = ek;
+                    if (tF + 1 <= mid) {
+                        if (fok) ah[(size_t)(tF + 1) * C + g.r0 + lane] = own;
+                        if (lane == 0) Sa[(size_t)(tF + 1) * kClMaxK + g.k] = ek;
+                    }
+                }
+                c2_barrier();
+            }
+            if (tP >= n) return false;
+            C2_MARK(a, p, 2);
+            // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
+            if (tP == mid && !met) {
+                meet();
+                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+            }
+            {
+                const unsigned tag = gstep + 1;
+                u64* xs = xbase + (size_t)(gstep & 1) * kClMaxK * kC2XS;
+                const int ek = ctl_s[1];
+                float av[kC2RT];
+#pragma unroll
+                for (int r = 0; r < kC2RT; ++r) av[r] = own_s[r];
+                float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+                for (int r = 0; r < kC2RT; ++r) {
+                    if (r & 1) acc1 = fmaf(av[r], EP[B_][r], acc1); else acc0 = fmaf(av[r], EP[B_][r], acc0);
+                }
+                const int sp = shP[B_], sg = sigP[B_];
+                const float val = (sp == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, sp - sg);
+                if (cP == 0) {
+#pragma unroll
+                    for (int r = 0; r < kC2RT; ++r)
+                        bl_s[r] = (sp == kShiftNone) ? 0.f : c2_scale(av[r] * EP[B_][r], sp - sg);
+                }
+                c2_barrier();
+                const bool exch = !(GAMMA && tP == L - 1);
+                if (colok && exch) {
+                    float pub = (cP == 0) ? 0.f : val;          // column 0 is the empty label, not a label arc
+                    if (cP >= g.r0 && cP < g.r0 + g.nr) pub += bl_s[cP - g.r0];
+                    xpublish(xs + (size_t)g.k * kC2XS + cP, pack_word(pub, tag));
+                }
+                if (tid == 0 && exch)
+                    xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
+                if (GAMMA && tP >= mid) {
+                    // own states of the other side's vector, rescaled to the exponent of block 0 (the
+                    // block of column 0, whose exponent the column-0 threads use)
+                    if (tid < g.nr) bo_s[tid] = c2_scale(bh[(size_t)(tP + 1) * C + g.r0 + tid],
+                                                         Sb[(size_t)(tP + 1) * kClMaxK + g.k]
+                                                             - Sb[(size_t)(tP + 1) * kClMaxK]);
+                    c2_barrier();
+                    if (colok) {
+                        const float kx = (float)((double)(sbP[B_] + sp + ek) - D2);
+                        const float fy = a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
+                        const unsigned gso = (unsigned)tP * frb + rbaseP;
+#pragma unroll
+                        for (int r = 0; r < kC2RT; ++r)
+                            if (r < nrtP) {
+                                // the empty label (column 0) returns to the row's own state
+                                const float f2 = (cP == 0) ? fy * bo_s[r] : fy;
+                                buf_store(av[r] * EP[B_][r] * f2, grs, coffP, gso + (unsigned)r * pitch);
+                            }
+                    }
+                }
+                C2_MARK(a, p, 3);
+                prep(std::integral_constant<int, B_ ^ 1>());
+                C2_MARK(a, p, 4);
+                if (exch) {
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+                    C2_MARK(a, p, 5);
+                    gstep += 1;
+                    if (tP + 1 <= mid) {
+                        if (tid < g.nr) ah[(size_t)(tP + 1) * C + g.r0 + tid] = full_s[g.r0 + tid];
+                        if (tid == 0) Sa[(size_t)(tP + 1) * kClMaxK + g.k] = ctl_s[0];
+                    }
+                }
+            }
+            ++p;
+            return true;
+        };
+        for (;;) {
+            if (!pair(std::integral_constant<int, 0>())) break;
+            if (!pair(std::integral_constant<int, 1>())) break;
+        }
+        __syncthreads();
+        if (!met) meet();
+        if (g.k == 0 && tid == 0 && (ctl_s[8] || dead) && a.item_status && !bad) a.item_status[b] = kItemTimeout;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------- beta role
+template <bool GAMMA>
+__device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
+                                           unsigned& gstep, unsigned& ptag)
+{
+    float* full_s = smem + kC2Full;
+    float* own_s = smem + kC2OwnS;
+    float* red_s = smem + kC2Red;             // [40] row sums of the F-step
+    int* shw_s = (int*)(smem + kC2Shw);
+    float* bl_s = smem + kC2Bl;               // empty-label terms of the P-step
+    float* ao_s = smem + kC2Bo;               // other side's own-state values (marginals)
+    int* ctl_s = (int*)(smem + kC2Ctl);
+    float* redb = smem + kC2RedB;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int C = a.C, K = a.K, RPW = a.RPW;
+    // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns
+    int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
+    if (nrw < 0) nrw = 0;
+    // P-step: lane <-> own column, wave <-> rows wave, wave + 8, ...
+    const bool pok = lane < g.nr;
+    const int yP = min(g.r0 + lane, C - 1);
+    const bool p_no_label = g.r0 + lane == 0;         // column 0 holds the empty label, not a label arc
+
+    for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
+        int L = a.len[b];
+        const bool bad = L < 0 || L > a.T;
+        if (bad) L = 0;
+        const int mid = L / 2;
+        const int n = GAMMA ? L : L - mid;
+        const int ph1 = L - mid;                      // step at which the state index reaches mid
+        const size_t fr = (size_t)C * C;
+        const unsigned frb = (unsigned)(fr * sizeof(float));
+        const unsigned pitch = (unsigned)(C * (int)sizeof(float));
+        const float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
+        float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
+        const int* Sa = a.Sa + (size_t)b * (a.T + 1) * kClMaxK;
+        int* Sb = a.Sb + (size_t)b * (a.T + 1) * kClMaxK;
+        u64* xbase = a.xb + (size_t)g.cg * 2 * kClMaxK * kC2XS;
+        const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
+        const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        unsigned coff[kClNC];
+#pragma unroll
+        for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
+        auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
+            return (unsigned)(g.r0 + min(wave + ri * kC2Waves, g.nr - 1)) * pitch;
+        };
+        const unsigned coffP = (unsigned)(yP * (int)sizeof(float));
+        const unsigned rowP0 = (unsigned)wave * pitch;
+        const unsigned rowB = (unsigned)yP * pitch;
+        const int nlast = max(n - 1, 0);
+
+        // b_L = 1 for every state, exponent 0
+        for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
+        if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; ao_s[tid] = 0.f; }
+        if (tid < 32) ctl_s[tid] = 0;
+        if (tid < g.nr) bh[(size_t)L * C + g.r0 + tid] = 1.f;
+        if (tid == 0) Sb[(size_t)L * kClMaxK + g.k] = 0;
+        __syncthreads();
+
+        float EFb[2][kC2RW][kClNC], EPb[2][kC2NQ];
+        float EB[2] = {0.f, 0.f};
+        int srF[2][kC2RW];
+        int srP[2] = {0, 0};                 // lane j < 27: shift of row wave + 10 j of the P frame
+        int sbl[2] = {0, 0}, sigP[2] = {0, 0};
+        float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
+        int saF[2] = {0, 0}, saP[2] = {0, 0};
+        double D2 = 0.0;
+        int dead = 0;
+        bool met = false;
+
+        // state vectors of the other side for the marginals of pair p (rows t of its two frames);
+        // fetched one pair ahead, and again right after the meeting for the pairs in flight
+        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            const int tF = max(L - 1 - min(2 * p, nlast), 0), tP = max(L - 1 - min(2 * p + 1, nlast), 0);
+            aF[B_] = (lane < kC2RW) ? ah[(size_t)tF * C + g.r0 + min(wave + lane * kC2Waves, g.nr - 1)] : 0.f;
+            saF[B_] = Sa[(size_t)tF * kClMaxK + g.k];
+            const int q = min(wave + kC2Waves * min(lane, kC2NQ - 1), C - 1);
+            aP[B_] = ah[(size_t)tP * C + q];
+            saP[B_] = Sa[(size_t)tP * kClMaxK + q / RPW];
+        };
+        // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
+        auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            const int tF = max(L - 1 - min(2 * p, nlast), 0), tP = max(L - 1 - min(2 * p + 1, nlast), 0);
+            const unsigned foF = (unsigned)tF * frb, foP = (unsigned)tP * frb;
+#pragma unroll
+            for (int ri = 0; ri < kC2RW; ++ri)
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coff[j], foF + roff(ri));
+#pragma unroll
+            for (int j = 0; j < kC2NQ; ++j) EPb[B_][j] = buf_load(wrs, coffP, foP + rowP0 + (unsigned)(kC2Waves * j) * pitch);
+            EB[B_] = buf_load(wrs, 0u, foP + rowB);
+            if (GAMMA) other(BUF, p);
+        };
+        auto prep = [&](auto BUF) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            // F frame: one shift per own row (wave-uniform)
+#pragma unroll
+            for (int ri = 0; ri < kC2RW; ++ri) {
+                float mx = LAST_NEG_INF;
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) {
+                    if (lane + 64 * j >= C) EFb[B_][ri][j] = LAST_NEG_INF;
+                    mx = fmaxf(mx, EFb[B_][ri][j]);
+                }
+                mx = wave_max_dpp(mx);
+                const int s = shift_for(mx);
+                srF[B_][ri] = s;
+                const float fs = (float)s;
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
+            }
+            // P frame: one shift per row (wave-uniform, kept by lane j), over the own columns
+            int srv = kShiftNone, smax = kShiftNone;
+#pragma unroll
+            for (int j = 0; j < kC2NQ; ++j) {
+                const bool valid = pok && !p_no_label && wave + kC2Waves * j < C;
+                if (!valid) EPb[B_][j] = LAST_NEG_INF;
+                const float mx = wave_max_dpp(EPb[B_][j]);
+                const int s = shift_for(mx);
+                srv = (lane == j) ? s : srv;
+                smax = max(smax, s);
+                EPb[B_][j] = fast_exp2(fmaf(EPb[B_][j], kLog2e, -(float)s));
+            }
+            srP[B_] = srv;
+            // empty-label weight of the own states (wave 0 uses it), its own shift per lane
+            const int sb = shift_for(pok ? EB[B_] : LAST_NEG_INF);
+            EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb));
+            sbl[B_] = sb;
+            if (wave == 0) smax = max(smax, wave_max_dpp(sb));
+            if (lane == 0) ctl_s[16 + wave] = smax;
+            c2_barrier();
+            int sg = kShiftNone;
+#pragma unroll
+            for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
+            sigP[B_] = sg;
+            c2_barrier();
+        };
+        auto meet = [&]() __attribute__((always_inline)) {
+            if (dead) ctl_s[8] = 1;
+            cluster_sync(a, g, ptag, &ctl_s[8]);
+            ptag += 1;
+            D2 = c2_meeting(ah + (size_t)mid * C, bh + (size_t)mid * C, Sa + (size_t)mid * kClMaxK,
+                            Sb + (size_t)mid * kClMaxK, C, RPW, K, redb);
+            met = true;
+            __syncthreads();
+        };
+
+        issue(std::integral_constant<int, 0>(), 0);
+        prep(std::integral_constant<int, 0>());
+
+        int p = 0;
+        auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
+            constexpr int B_ = decltype(BUF)::value;
+            const int iF = 2 * p, iP = 2 * p + 1;
+            if (iF >= n) return false;
+            C2_MARK(a, p, 0);
+            issue(std::integral_constant<int, B_ ^ 1>(), p + 1);
+            C2_MARK(a, p, 1);
+            // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
+            if (iF == ph1 && !met) {
+                meet();
+                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+            }
+            {
+                const int tF = L - 1 - iF;
+                const int S = ctl_s[0];
+                float bv[kClNC];
+#pragma unroll
+                for (int j = 0; j < kClNC; ++j) bv[j] = full_s[lane + 64 * j];
+#pragma unroll
+                for (int ri = 0; ri < kC2RW; ++ri) {
+                    const int rloc = min(wave + ri * kC2Waves, g.nr - 1);
+                    const float brow = full_s[g.r0 + rloc];
+                    // the empty label (column 0) returns to the row's own state
+                    float acc = EFb[B_][ri][0] * (lane == 0 ? brow : bv[0]);
+#pragma unroll
+                    for (int j = 1; j < kClNC; ++j) acc = fmaf(EFb[B_][ri][j], bv[j], acc);
+                    const float tot = wave_sum_dpp(acc);
+                    if (lane == 0 && ri < nrw) {
+                        red_s[rloc] = tot;
+                        shw_s[rloc] = srF[B_][ri];
+                    }
+                    if (GAMMA && iF >= ph1 && ri < nrw) {
+                        const float arow = __shfl(aF[B_], ri, 64);
+                        const float fac = a.scale * arow *
+                                          fast_exp2((float)((double)(saF[B_] + srF[B_][ri] + S) - D2));
+                        const unsigned gso = (unsigned)tF * frb + roff(ri);
+#pragma unroll
+                        for (int j = 0; j < kClNC; ++j)
+                            if (lane + 64 * j < C) {
+                                const float bb = (j == 0 && lane == 0) ? brow : bv[j];
+                                buf_store(EFb[B_][ri][j] * bb * fac, grs, coff[j], gso);
+                            }
+                    }
+                }
+                c2_barrier();
+                if (wave == 0) {
+                    const bool ok = lane < g.nr;
+                    const float v = ok ? red_s[lane] : 0.f;
+                    const int sc = (ok && v > 0.f) ? shw_s[lane] + float_exponent(v) : kShiftNone;
+                    const int ms = wave_max_dpp(sc);
+                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shw_s[lane] - ms);
+                    if (lane < kC2Own) own_s[lane] = own;
+                    const int ek = (ms == kShiftNone) ? S : S + ms;
+                    if (lane == 0) ctl_s[1] = ek;
+                    if (tF >= mid) {
+                        if (ok) bh[(size_t)tF * C + g.r0 + lane] = own;
+                        if (lane == 0) Sb[(size_t)tF * kClMaxK + g.k] = ek;
+                    }
+                }
+                c2_barrier();
+            }
+            if (iP >= n) return false;
+            C2_MARK(a, p, 2);
+            // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
+            if (iP == ph1 && !met) {
+                meet();
+                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+            }
+            {
+                const int tP = L - 1 - iP;
+                const unsigned tag = gstep + 1;
+                u64* xs = xbase + (size_t)(gstep & 1) * kClMaxK * kC2XS;
+                const int ek = ctl_s[1];
+                const int sg = sigP[B_];
+                const float bo = own_s[min(lane, kC2Own - 1)];     // b_{t+1} of the own column (0 beyond)
+                // empty-label arcs of the own states: b'[q] += M[q][0] b[q]
+                if (wave == 0 && lane < kC2Own)
+                    bl_s[lane] = (pok && sbl[B_] != kShiftNone) ? c2_scale(EB[B_] * bo, sbl[B_] - sg) : 0.f;
+                float totv = 0.f;
+#pragma unroll
+                for (int j = 0; j < kC2NQ; ++j) {
+                    const float tot = wave_sum_dpp(EPb[B_][j] * bo);
+                    totv = (lane == j) ? tot : totv;
+                }
+                c2_barrier();
+                const bool exch = !(GAMMA && iP == L - 1);
+                const int q = wave + kC2Waves * lane;              // row published by this lane
+                if (lane < kC2NQ && q < C && exch) {
+                    float pub = (srP[B_] == kShiftNone) ? 0.f : c2_scale(totv, srP[B_] - sg);
+                    if (q >= g.r0 && q < g.r0 + g.nr) pub += bl_s[q - g.r0];
+                    xpublish(xs + (size_t)g.k * kC2XS + q, pack_word(pub, tag));
+                }
+                if (tid == 0 && exch)
+                    xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
+                if (GAMMA && iP >= ph1) {
+                    // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
+                    const float rowfac = (lane < kC2NQ && srP[B_] != kShiftNone)
+                        ? a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + srP[B_] + ek) - D2)) : 0.f;
+                    const unsigned gso = (unsigned)tP * frb;
+#pragma unroll
+                    for (int j = 0; j < kC2NQ; ++j) {
+                        const float rf = __shfl(rowfac, j, 64);
+                        if (pok && !p_no_label && wave + kC2Waves * j < C)
+                            buf_store(EPb[B_][j] * bo * rf, grs, coffP, gso + rowP0 + (unsigned)(kC2Waves * j) * pitch);
+                    }
+                    if (wave == 0 && pok) {
+                        // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
+                        const float ao = ah[(size_t)tP * C + g.r0 + lane];
+                        const float f0 = (sbl[B_] == kShiftNone) ? 0.f
+                            : a.scale * ao * fast_exp2((float)((double)(Sa[(size_t)tP * kClMaxK + g.k] + sbl[B_] + ek) - D2));
+                        buf_store(EB[B_] * bo * f0, grs, 0u, gso + rowB);
+                    }
+                }
+                C2_MARK(a, p, 3);
+                prep(std::integral_constant<int, B_ ^ 1>());
+                C2_MARK(a, p, 4);
+                if (exch) {
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+                    C2_MARK(a, p, 5);
+                    gstep += 1;
+                    if (tP >= mid) {
+                        if (tid < g.nr) bh[(size_t)tP * C + g.r0 + tid] = full_s[g.r0 + tid];
+                        if (tid == 0) Sb[(size_t)tP * kClMaxK + g.k] = ctl_s[0];
+                    }
+                }
+            }
+            ++p;
+            return true;
+        };
+        for (;;) {
+            if (!pair(std::integral_constant<int, 0>())) break;
+            if (!pair(std::integral_constant<int, 1>())) break;
+        }
+        __syncthreads();
+        if (!met) meet();
+        __syncthreads();
+    }
+}
+
+template <bool GAMMA>
+__global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
+{
+    __shared__ float smem[kC2Lds];
+    ClusterGeom g;
+    const int id = blockIdx.x;
+    const int x = id & 7, slot = id >> 3;
+    const int cl = slot / (2 * a.K), member = slot - cl * 2 * a.K;
+    g.cg = x + 8 * cl;
+    g.role = member / a.K;
+    g.k = member - g.role * a.K;
+    g.r0 = g.k * a.RPW;
+    g.nr = min(a.RPW, a.C - g.r0);
+    if (g.nr < 0) g.nr = 0;
+    if (g.r0 > a.C) g.r0 = a.C;
+    unsigned gstep = 0, ptag = 0;
+    if (GAMMA) cluster_zero_padding(a, g);
+    if (g.role == 0) alpha2_role<GAMMA>(a, g, smem, gstep, ptag);
+    else beta2_role<GAMMA>(a, g, smem, gstep, ptag);
+}
+
+}  // namespace last

@@ -8,6 +8,7 @@
 #include "solo_kernels.hpp"
 #include "numerator_kernels.hpp"
 #include "cluster_kernels.hpp"
+#include "cluster2_kernels.hpp"
 #include "fused_kernels.hpp"
 #include <algorithm>
 
@@ -140,6 +141,7 @@ NumWs carve_num(Carver& cv, const Shape& s, int Umax)
 // geometry of the clustered bigram path (see cluster_kernels.hpp)
 struct ClusterPlan {
     bool ok;
+    bool v2;             // one exchange per two frames (cluster2_kernels.hpp)
     int K, RPW, ncl, XS, XSB, grid;
 };
 
@@ -163,6 +165,9 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     p.XSB = kClMaxC;                         // 11 waves x 24 words
     p.grid = 8 * p.ncl * 2 * p.K;
     p.ok = true;
+    // the second-generation kernel (one exchange per two frames) is opt-in while it is being tuned
+    const char* v2 = std::getenv("LAST_CLUSTER_V2");
+    p.v2 = v2 && v2[0] == '1' && s.C <= kC2Hdr;
     return p;
 }
 
@@ -183,10 +188,11 @@ ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
     const size_t st = (size_t)s.B * (s.T + 1);
     c.ahat = cv.take<float>(st * s.C);
     c.bhat = cv.take<float>(st * s.C);
-    c.Sa = cv.take<int>(st);
-    c.Sb = cv.take<int>(st);
+    c.Sa = cv.take<int>(st * kClMaxK);      // one exponent per block of states (second-generation kernel)
+    c.Sb = cv.take<int>(st * kClMaxK);
     const size_t ncl = (size_t)8 * p.ncl;
-    const size_t nxa = ncl * 2 * p.XS * kClXK, nxb = ncl * 2 * p.XSB, nph = ncl * 32;
+    const size_t per_role = std::max((size_t)2 * p.XS * kClXK, (size_t)2 * kClMaxK * kC2XS);
+    const size_t nxa = ncl * per_role, nxb = std::max(ncl * 2 * p.XSB, ncl * per_role), nph = ncl * 32;
     // one contiguous block so that a single launch clears all tags
     c.xa = cv.take<u64>(nxa + nxb + nph);
     c.xb = c.xa ? c.xa + nxa : nullptr;
@@ -211,6 +217,10 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.spin_limit = 1 << 20;
     a.aux_delay = 4;
     if (const char* e = std::getenv("LAST_AUX_DELAY")) a.aux_delay = std::atoi(e);
+    if (p.v2 && !(GAMMA && accumulate)) {
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+        return;
+    }
     auto go = [&](auto KC) {
         constexpr int KT = decltype(KC)::value;
         if (GAMMA && accumulate)
