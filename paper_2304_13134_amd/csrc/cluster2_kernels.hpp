@@ -205,7 +205,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         float EF[2][kC2NQ], EP[2][kC2RT];
         float EB[2] = {0.f, 0.f};
         int shF[2] = {0, 0}, shP[2] = {0, 0}, sigP[2] = {0, 0};
-        float bF[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f};     // other side's vector for the marginals
+        float bF[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f}, boP[2] = {0.f, 0.f};   // other side's vector for the marginals
         int sbF[2] = {0, 0}, sbP[2] = {0, 0};
         double D2 = 0.0;
         int dead = 0;
@@ -220,17 +220,35 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             sbF[B_] = Sb[(size_t)(tF + 1) * kClMaxK + g.k];
             bPv[B_] = bh[(size_t)(tP + 1) * C + min(cP, C - 1)];
             sbP[B_] = Sb[(size_t)(tP + 1) * kClMaxK + min(cP, C - 1) / RPW];
+            // own states of that vector, relative to the exponent of block 0 (the block of column 0,
+            // whose exponent the column-0 thread uses for the empty-label arcs)
+            boP[B_] = (tid < g.nr) ? c2_scale(bh[(size_t)(tP + 1) * C + g.r0 + tid],
+                                               Sb[(size_t)(tP + 1) * kClMaxK + g.k] - Sb[(size_t)(tP + 1) * kClMaxK])
+                                   : 0.f;
         };
-        auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
+        // The loads of a pair are issued in four pieces spread over the previous pair: issued in one
+        // go, the whole chip would pull at the HBM limit for a moment and every wave would sit in its
+        // issue slot until the burst has drained.  Lanes beyond the own columns load nothing.
+        auto issueF = [&](auto BUF, int p, int j0, int j1) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foF = (unsigned)min(2 * p, nlast) * frb;
+            if (lane < kC2Own) {
+#pragma unroll
+                for (int j = 0; j < kC2NQ; ++j)
+                    if (j >= j0 && j < j1)
+                        EF[B_][j] = buf_load(wrs, coffF, foF + rowF0 + (unsigned)(kC2Waves * j) * pitch);
+                if (j1 >= kC2NQ) EB[B_] = buf_load(wrs, 0u, foF + rowB);
+            }
+            if (GAMMA && j0 == 0) other(BUF, p);
+        };
+        auto issueP = [&](auto BUF, int p, int r0_, int r1_) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
             const unsigned foP = (unsigned)min(2 * p + 1, nlast) * frb;
+            if (wave < 5) {
 #pragma unroll
-            for (int j = 0; j < kC2NQ; ++j) EF[B_][j] = buf_load(wrs, coffF, foF + rowF0 + (unsigned)(kC2Waves * j) * pitch);
-            EB[B_] = buf_load(wrs, 0u, foF + rowB);
-#pragma unroll
-            for (int r = 0; r < kC2RT; ++r) EP[B_][r] = buf_load(wrs, coffP, foP + rbaseP + (unsigned)r * pitch);
-            if (GAMMA) other(BUF, p);
+                for (int r = 0; r < kC2RT; ++r)
+                    if (r >= r0_ && r < r1_) EP[B_][r] = buf_load(wrs, coffP, foP + rbaseP + (unsigned)r * pitch);
+            }
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
         auto prep = [&](auto BUF) __attribute__((always_inline)) {
@@ -248,7 +266,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             float mp = LAST_NEG_INF;
 #pragma unroll
             for (int r = 0; r < kC2RT; ++r) {
-                if (r >= nrtP) EP[B_][r] = LAST_NEG_INF;
+                if (r >= nrtP || !colok) EP[B_][r] = LAST_NEG_INF;
                 mp = fmaxf(mp, EP[B_][r]);
             }
             const int sp = shift_for(mp);
@@ -287,7 +305,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             __syncthreads();
         };
 
-        issue(std::integral_constant<int, 0>(), 0);
+        issueF(std::integral_constant<int, 0>(), 0, 0, kC2NQ);
+        issueP(std::integral_constant<int, 0>(), 0, 0, kC2RT);
         prep(std::integral_constant<int, 0>());
 
         int p = 0;
@@ -296,7 +315,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= n) return false;
             C2_MARK(a, p, 0);
-            issue(std::integral_constant<int, B_ ^ 1>(), p + 1);
+            issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 17);
             C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             if (tF == mid && !met) {
@@ -309,6 +328,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 #pragma unroll
                 for (int j = 0; j < kC2NQ; ++j) ps = fmaf(full_s[min(wave + kC2Waves * j, 319)], EF[B_][j], ps);
                 if (lane < kC2Own) red_s[wave * kC2Own + lane] = ps;
+                issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 17, kC2NQ);
                 if (GAMMA && tF >= mid && fok) {
                     const float fc = a.scale * bF[B_] *
                                      fast_exp2((float)((double)(sbF[B_] + shF[B_] + S) - D2));
@@ -343,6 +363,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             }
             if (tP >= n) return false;
             C2_MARK(a, p, 2);
+            issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 17);
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) {
                 meet();
@@ -362,11 +383,13 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 }
                 const int sp = shP[B_], sg = sigP[B_];
                 const float val = (sp == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, sp - sg);
+                issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 17, kC2RT);
                 if (cP == 0) {
 #pragma unroll
                     for (int r = 0; r < kC2RT; ++r)
                         bl_s[r] = (sp == kShiftNone) ? 0.f : c2_scale(av[r] * EP[B_][r], sp - sg);
                 }
+                if (GAMMA && tid < kC2Own) bo_s[tid] = boP[B_];
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
                 if (colok && exch) {
@@ -377,12 +400,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (tid == 0 && exch)
                     xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
                 if (GAMMA && tP >= mid) {
-                    // own states of the other side's vector, rescaled to the exponent of block 0 (the
-                    // block of column 0, whose exponent the column-0 threads use)
-                    if (tid < g.nr) bo_s[tid] = c2_scale(bh[(size_t)(tP + 1) * C + g.r0 + tid],
-                                                         Sb[(size_t)(tP + 1) * kClMaxK + g.k]
-                                                             - Sb[(size_t)(tP + 1) * kClMaxK]);
-                    c2_barrier();
                     if (colok) {
                         const float kx = (float)((double)(sbP[B_] + sp + ek) - D2);
                         const float fy = a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
@@ -424,6 +441,13 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
+// row of 33 consecutive floats, read or written in 16-byte pieces (the rows of the weight tensor are
+// only 4-byte aligned; the compiler picks the widest access the target allows for that alignment)
+struct C2Row {
+    float v[kC2RT];
+};
+typedef float c2_f4 __attribute__((ext_vector_type(4), aligned(4)));
+
 template <bool GAMMA>
 __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
@@ -432,8 +456,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     float* own_s = smem + kC2OwnS;
     float* red_s = smem + kC2Red;             // [40] row sums of the F-step
     int* shw_s = (int*)(smem + kC2Shw);
-    float* bl_s = smem + kC2Bl;               // empty-label terms of the P-step
-    float* ao_s = smem + kC2Bo;               // other side's own-state values (marginals)
     int* ctl_s = (int*)(smem + kC2Ctl);
     float* redb = smem + kC2RedB;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -442,10 +464,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns
     int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
     if (nrw < 0) nrw = 0;
-    // P-step: lane <-> own column, wave <-> rows wave, wave + 8, ...
-    const bool pok = lane < g.nr;
-    const int yP = min(g.r0 + lane, C - 1);
-    const bool p_no_label = g.r0 + lane == 0;         // column 0 holds the empty label, not a label arc
+    // P-step: thread <-> row qP of the frame (waves 0..4), its own-column elements in registers
+    const int qP = min(tid, C - 1);
+    const bool rowok = tid < C;
+    const bool rowown = rowok && tid >= g.r0 && tid < g.r0 + g.nr;   // this row's state is an own state
+    const int c_lo = g.r0 == 0 ? 1 : 0;                               // column 0 is the empty label
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -457,67 +480,84 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const size_t fr = (size_t)C * C;
         const unsigned frb = (unsigned)(fr * sizeof(float));
         const unsigned pitch = (unsigned)(C * (int)sizeof(float));
+        const float* wi = a.w + (size_t)b * a.T * fr;
+        float* gi = GAMMA ? a.dw + (size_t)b * a.T * fr : nullptr;
         const float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
         float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
         const int* Sa = a.Sa + (size_t)b * (a.T + 1) * kClMaxK;
         int* Sb = a.Sb + (size_t)b * (a.T + 1) * kClMaxK;
         u64* xbase = a.xb + (size_t)g.cg * 2 * kClMaxK * kC2XS;
-        const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
-        const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        const buf_t wrs = make_buf(wi, (unsigned)a.T * frb);
+        const buf_t grs = make_buf(GAMMA ? (const float*)gi : wi, GAMMA ? (unsigned)a.T * frb : 0u);
         unsigned coff[kClNC];
 #pragma unroll
         for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
         auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
             return (unsigned)(g.r0 + min(wave + ri * kC2Waves, g.nr - 1)) * pitch;
         };
-        const unsigned coffP = (unsigned)(yP * (int)sizeof(float));
-        const unsigned rowP0 = (unsigned)wave * pitch;
-        const unsigned rowB = (unsigned)yP * pitch;
         const int nlast = max(n - 1, 0);
 
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
-        if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; ao_s[tid] = 0.f; }
+        if (tid < kC2Own) own_s[tid] = 0.f;
         if (tid < 32) ctl_s[tid] = 0;
         if (tid < g.nr) bh[(size_t)L * C + g.r0 + tid] = 1.f;
         if (tid == 0) Sb[(size_t)L * kClMaxK + g.k] = 0;
         __syncthreads();
 
-        float EFb[2][kC2RW][kClNC], EPb[2][kC2NQ];
+        float EFb[2][kC2RW][kClNC];
+        C2Row EPb[2];
         float EB[2] = {0.f, 0.f};
         int srF[2][kC2RW];
-        int srP[2] = {0, 0};                 // lane j < 27: shift of row wave + 10 j of the P frame
-        int sbl[2] = {0, 0}, sigP[2] = {0, 0};
+        int srP[2] = {0, 0}, sbl[2] = {0, 0}, sigP[2] = {0, 0};
         float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
         int saF[2] = {0, 0}, saP[2] = {0, 0};
         double D2 = 0.0;
         int dead = 0;
         bool met = false;
 
+        // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
+        auto frameF = [&](int p) { return max(L - 1 - min(2 * p, nlast), 0); };
+        auto frameP = [&](int p) { return max(L - 1 - min(2 * p + 1, nlast), 0); };
         // state vectors of the other side for the marginals of pair p (rows t of its two frames);
         // fetched one pair ahead, and again right after the meeting for the pairs in flight
         auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            const int tF = max(L - 1 - min(2 * p, nlast), 0), tP = max(L - 1 - min(2 * p + 1, nlast), 0);
+            const int tF = frameF(p), tP = frameP(p);
             aF[B_] = (lane < kC2RW) ? ah[(size_t)tF * C + g.r0 + min(wave + lane * kC2Waves, g.nr - 1)] : 0.f;
             saF[B_] = Sa[(size_t)tF * kClMaxK + g.k];
-            const int q = min(wave + kC2Waves * min(lane, kC2NQ - 1), C - 1);
-            aP[B_] = ah[(size_t)tP * C + q];
-            saP[B_] = Sa[(size_t)tP * kClMaxK + q / RPW];
+            aP[B_] = ah[(size_t)tP * C + qP];
+            saP[B_] = Sa[(size_t)tP * kClMaxK + qP / RPW];
         };
-        // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
-        auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
+        auto issueF = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            const int tF = max(L - 1 - min(2 * p, nlast), 0), tP = max(L - 1 - min(2 * p + 1, nlast), 0);
-            const unsigned foF = (unsigned)tF * frb, foP = (unsigned)tP * frb;
+            const unsigned foF = (unsigned)frameF(p) * frb;
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri)
 #pragma unroll
                 for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coff[j], foF + roff(ri));
-#pragma unroll
-            for (int j = 0; j < kC2NQ; ++j) EPb[B_][j] = buf_load(wrs, coffP, foP + rowP0 + (unsigned)(kC2Waves * j) * pitch);
-            EB[B_] = buf_load(wrs, 0u, foP + rowB);
             if (GAMMA) other(BUF, p);
+        };
+        auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
+            constexpr int B_ = decltype(BUF)::value;
+            if (wave < 5) {
+                const float* rp = wi + (size_t)frameP(p) * fr + (size_t)qP * C + g.r0;
+                // full 16-byte pieces inside the own columns, then element by element
+#pragma unroll
+                for (int c4 = 0; c4 < kC2RT / 4; ++c4) {
+                    if (4 * c4 + 3 < g.nr) {
+                        const c2_f4 x = *(const c2_f4*)(rp + 4 * c4);
+                        EPb[B_].v[4 * c4] = x.x; EPb[B_].v[4 * c4 + 1] = x.y;
+                        EPb[B_].v[4 * c4 + 2] = x.z; EPb[B_].v[4 * c4 + 3] = x.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            EPb[B_].v[4 * c4 + e] = (4 * c4 + e < g.nr) ? rp[4 * c4 + e] : LAST_NEG_INF;
+                    }
+                }
+                EPb[B_].v[kC2RT - 1] = (kC2RT - 1 < g.nr) ? rp[kC2RT - 1] : LAST_NEG_INF;
+                EB[B_] = rp[-g.r0];                                   // w[q][0]
+            }
         };
         auto prep = [&](auto BUF) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -537,25 +577,26 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                 for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
             }
-            // P frame: one shift per row (wave-uniform, kept by lane j), over the own columns
-            int srv = kShiftNone, smax = kShiftNone;
+            // P frame: one shift per row = per thread, over the own label columns
+            int sp = kShiftNone, sb = kShiftNone;
+            if (wave < 5) {
+                float mx = LAST_NEG_INF;
 #pragma unroll
-            for (int j = 0; j < kC2NQ; ++j) {
-                const bool valid = pok && !p_no_label && wave + kC2Waves * j < C;
-                if (!valid) EPb[B_][j] = LAST_NEG_INF;
-                const float mx = wave_max_dpp(EPb[B_][j]);
-                const int s = shift_for(mx);
-                srv = (lane == j) ? s : srv;
-                smax = max(smax, s);
-                EPb[B_][j] = fast_exp2(fmaf(EPb[B_][j], kLog2e, -(float)s));
+                for (int c = 0; c < kC2RT; ++c) {
+                    if (c < c_lo || c >= g.nr || !rowok) EPb[B_].v[c] = LAST_NEG_INF;
+                    mx = fmaxf(mx, EPb[B_].v[c]);
+                }
+                sp = shift_for(mx);
+                const float fs = (float)sp;
+#pragma unroll
+                for (int c = 0; c < kC2RT; ++c) EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs));
+                // empty-label weight of an own state, with its own shift
+                sb = shift_for(rowown ? EB[B_] : LAST_NEG_INF);
+                EB[B_] = rowown ? fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb)) : 0.f;
             }
-            srP[B_] = srv;
-            // empty-label weight of the own states (wave 0 uses it), its own shift per lane
-            const int sb = shift_for(pok ? EB[B_] : LAST_NEG_INF);
-            EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb));
-            sbl[B_] = sb;
-            if (wave == 0) smax = max(smax, wave_max_dpp(sb));
-            if (lane == 0) ctl_s[16 + wave] = smax;
+            srP[B_] = sp; sbl[B_] = sb;
+            const int wm = wave_max_dpp(max(sp, sb));
+            if (lane == 0) ctl_s[16 + wave] = wm;
             c2_barrier();
             int sg = kShiftNone;
 #pragma unroll
@@ -573,7 +614,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             __syncthreads();
         };
 
-        issue(std::integral_constant<int, 0>(), 0);
+        issueF(std::integral_constant<int, 0>(), 0);
+        issueP(std::integral_constant<int, 0>(), 0);
         prep(std::integral_constant<int, 0>());
 
         int p = 0;
@@ -582,7 +624,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             const int iF = 2 * p, iP = 2 * p + 1;
             if (iF >= n) return false;
             C2_MARK(a, p, 0);
-            issue(std::integral_constant<int, B_ ^ 1>(), p + 1);
+            issueF(std::integral_constant<int, B_ ^ 1>(), p + 1);
             C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
             if (iF == ph1 && !met) {
@@ -640,6 +682,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             }
             if (iP >= n) return false;
             C2_MARK(a, p, 2);
+            issueP(std::integral_constant<int, B_ ^ 1>(), p + 1);
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) {
                 meet();
@@ -651,45 +694,55 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 u64* xs = xbase + (size_t)(gstep & 1) * kClMaxK * kC2XS;
                 const int ek = ctl_s[1];
                 const int sg = sigP[B_];
-                const float bo = own_s[min(lane, kC2Own - 1)];     // b_{t+1} of the own column (0 beyond)
-                // empty-label arcs of the own states: b'[q] += M[q][0] b[q]
-                if (wave == 0 && lane < kC2Own)
-                    bl_s[lane] = (pok && sbl[B_] != kShiftNone) ? c2_scale(EB[B_] * bo, sbl[B_] - sg) : 0.f;
-                float totv = 0.f;
-#pragma unroll
-                for (int j = 0; j < kC2NQ; ++j) {
-                    const float tot = wave_sum_dpp(EPb[B_][j] * bo);
-                    totv = (lane == j) ? tot : totv;
-                }
-                c2_barrier();
                 const bool exch = !(GAMMA && iP == L - 1);
-                const int q = wave + kC2Waves * lane;              // row published by this lane
-                if (lane < kC2NQ && q < C && exch) {
-                    float pub = (srP[B_] == kShiftNone) ? 0.f : c2_scale(totv, srP[B_] - sg);
-                    if (q >= g.r0 && q < g.r0 + g.nr) pub += bl_s[q - g.r0];
-                    xpublish(xs + (size_t)g.k * kC2XS + q, pack_word(pub, tag));
+                if (wave < 5) {
+                    // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state)
+                    float bo[kC2RT];
+#pragma unroll
+                    for (int c = 0; c < kC2RT; ++c) bo[c] = own_s[c];
+                    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+                    for (int c = 0; c < kC2RT; ++c) {
+                        if (c & 1) acc1 = fmaf(EPb[B_].v[c], bo[c], acc1); else acc0 = fmaf(EPb[B_].v[c], bo[c], acc0);
+                    }
+                    const float bq = rowown ? own_s[tid - g.r0] : 0.f;
+                    if (rowok && exch) {
+                        float pub = (srP[B_] == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, srP[B_] - sg);
+                        if (rowown && sbl[B_] != kShiftNone) pub += c2_scale(EB[B_] * bq, sbl[B_] - sg);
+                        xpublish(xs + (size_t)g.k * kC2XS + tid, pack_word(pub, tag));
+                    }
+                    if (GAMMA && iP >= ph1 && rowok) {
+                        // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
+                        const float rf = (srP[B_] == kShiftNone) ? 0.f
+                            : a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + srP[B_] + ek) - D2));
+                        float* gp = gi + (size_t)tP * fr + (size_t)qP * C + g.r0;
+#pragma unroll
+                        for (int c4 = 0; c4 < kC2RT / 4; ++c4) {
+                            if (4 * c4 + 3 < g.nr && 4 * c4 >= c_lo) {
+                                c2_f4 x;
+                                x.x = EPb[B_].v[4 * c4] * bo[4 * c4] * rf;
+                                x.y = EPb[B_].v[4 * c4 + 1] * bo[4 * c4 + 1] * rf;
+                                x.z = EPb[B_].v[4 * c4 + 2] * bo[4 * c4 + 2] * rf;
+                                x.w = EPb[B_].v[4 * c4 + 3] * bo[4 * c4 + 3] * rf;
+                                *(c2_f4*)(gp + 4 * c4) = x;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (4 * c4 + e < g.nr && 4 * c4 + e >= c_lo)
+                                        gp[4 * c4 + e] = EPb[B_].v[4 * c4 + e] * bo[4 * c4 + e] * rf;
+                            }
+                        }
+                        if (kC2RT - 1 < g.nr) gp[kC2RT - 1] = EPb[B_].v[kC2RT - 1] * bo[kC2RT - 1] * rf;
+                        if (rowown) {
+                            // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
+                            const float f0 = (sbl[B_] == kShiftNone) ? 0.f
+                                : a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + sbl[B_] + ek) - D2));
+                            gp[-g.r0] = EB[B_] * bq * f0;
+                        }
+                    }
                 }
                 if (tid == 0 && exch)
                     xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
-                if (GAMMA && iP >= ph1) {
-                    // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
-                    const float rowfac = (lane < kC2NQ && srP[B_] != kShiftNone)
-                        ? a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + srP[B_] + ek) - D2)) : 0.f;
-                    const unsigned gso = (unsigned)tP * frb;
-#pragma unroll
-                    for (int j = 0; j < kC2NQ; ++j) {
-                        const float rf = __shfl(rowfac, j, 64);
-                        if (pok && !p_no_label && wave + kC2Waves * j < C)
-                            buf_store(EPb[B_][j] * bo * rf, grs, coffP, gso + rowP0 + (unsigned)(kC2Waves * j) * pitch);
-                    }
-                    if (wave == 0 && pok) {
-                        // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
-                        const float ao = ah[(size_t)tP * C + g.r0 + lane];
-                        const float f0 = (sbl[B_] == kShiftNone) ? 0.f
-                            : a.scale * ao * fast_exp2((float)((double)(Sa[(size_t)tP * kClMaxK + g.k] + sbl[B_] + ek) - D2));
-                        buf_store(EB[B_] * bo * f0, grs, 0u, gso + rowB);
-                    }
-                }
                 C2_MARK(a, p, 3);
                 prep(std::integral_constant<int, B_ ^ 1>());
                 C2_MARK(a, p, 4);
