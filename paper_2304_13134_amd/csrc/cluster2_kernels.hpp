@@ -42,18 +42,25 @@ namespace last {
 constexpr int kC2Threads = 512;   // 8 waves = 2 per SIMD: 256 registers per lane
 constexpr int kC2Waves = 8;
 constexpr int kC2NQ = 33;      // rows per wave when a workgroup reads all rows: 8 * 33 >= 264
+constexpr int kC2FG = 3;       // alpha F-step: row groups per wave (17 lanes each, two columns per lane)
+constexpr int kC2FJ = 11;      // alpha F-step: rows per lane, kC2FG * kC2FJ = kC2NQ
 constexpr int kC2Hdr = 264;    // exchange row: C values, the producer's exponent at [kC2Hdr]
 constexpr int kC2XS = 272;     // words per producer and slot
 constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
 constexpr int kC2RT = 33;      // own rows per column thread (alpha P-step)
 constexpr int kC2Own = 40;     // LDS slots for own states
+// A per-lane buffer offset beyond every descriptor's size: the hardware's range check drops the lane's
+// store and returns zero for its load.  Replaces branches around accesses whose mask differs per lane.
+constexpr unsigned kC2Off = 0xFFFFFF00u;
 
 // LDS map (floats / ints)
 constexpr int kC2Full = 0;                          // [320] whole state vector
 constexpr int kC2OwnS = kC2Full + 320;              // [40]  own states
-constexpr int kC2Red = kC2OwnS + kC2Own;            // [8][40] cross-wave partials
-constexpr int kC2Shw = kC2Red + kC2Waves * kC2Own;  // [8][40] shifts per wave (int)
-constexpr int kC2Bl = kC2Shw + kC2Waves * kC2Own;   // [40] empty-label terms
+constexpr int kC2RedN = kC2Waves * kC2FG;           // partial sums per own column (alpha F-step)
+constexpr int kC2Red = kC2OwnS + kC2Own;            // [24][40] partials per wave and row group
+constexpr int kC2Shw = kC2Red + kC2RedN * kC2Own;   // [25][40] shifts per wave and row group, empty label last (int)
+constexpr int kC2Shc = kC2Shw + (kC2RedN + 1) * kC2Own;   // [2][40] shift per own column, per buffer (int)
+constexpr int kC2Bl = kC2Shc + 2 * kC2Own;          // [40] empty-label terms
 constexpr int kC2Pacc = kC2Bl + kC2Own;             // [320] partial sums of the second half
 constexpr int kC2Bo = kC2Pacc + 320;                // [40] other side's own-state values (marginals)
 constexpr int kC2Ctl = kC2Bo + kC2Own;              // [32] ints
@@ -73,6 +80,23 @@ constexpr int kC2Lds = kC2RedB + 32;
 __device__ __forceinline__ void c2_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Keeps a value computed in the shadow of the exchange where it was computed: without it the compiler
+// merges the evaluation at the end of one pair with the one before the loop and moves both behind the
+// exchange, onto the critical path.
+template <typename T>
+__device__ __forceinline__ void c2_pin(T& v)
+{
+    asm volatile("" : "+v"(v));
+}
+
+// Wait for every vector memory load in flight (vmcnt(0); the other counters untouched).  Used on the
+// rare path that reloads prefetched values: the compiler merges the pending state of that path into
+// the common one, and would otherwise make the common path wait for loads it has only just issued.
+__device__ __forceinline__ void c2_wait_loads()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
 __device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e, zero stays zero
@@ -145,6 +169,21 @@ __device__ __forceinline__ double c2_meeting(const float* ah, const float* bh, c
     return (double)xmax + (double)__log2f(tot);
 }
 
+// 8-byte buffer accesses (two neighbouring floats, 4-byte aligned)
+__device__ __forceinline__ float2 buf_load2(buf_t r, unsigned voff, unsigned soff)
+{
+    const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+    static_assert(sizeof(v) == sizeof(float2), "8-byte buffer load");
+    return __builtin_bit_cast(float2, v);
+}
+__device__ __forceinline__ void buf_store2(float x, float y, buf_t r, unsigned voff, unsigned soff)
+{
+    typedef decltype(__builtin_amdgcn_raw_buffer_load_b64(r, 0, 0, 0)) b64_t;
+    float2 f;
+    f.x = x; f.y = y;
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, f), r, (int)voff, (int)soff, 0);
+}
+
 // ------------------------------------------------------------------ alpha role
 template <bool GAMMA>
 __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
@@ -154,6 +193,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
     float* own_s = smem + kC2OwnS;
     float* red_s = smem + kC2Red;
     int* shw_s = (int*)(smem + kC2Shw);
+    int* shc_s = (int*)(smem + kC2Shc);
     float* bl_s = smem + kC2Bl;
     float* pacc_s = smem + kC2Pacc;
     float* bo_s = smem + kC2Bo;
@@ -166,10 +206,18 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
     const int cP = tid;
     const bool colok = cP < C;
     const int nrtP = g.nr;
-    // F-step: lane <-> own column, wave <-> rows wave, wave + 8, ...
-    const bool fok = lane < g.nr;
+    // F-step: wave <-> rows [33 wave, 33 wave + 33); inside the wave three groups of 17 lanes take every
+    // third row, and a lane takes two neighbouring own columns (8-byte accesses): row 33 wave + 3 j + gq,
+    // columns r0 + 2 ci, r0 + 2 ci + 1.  Lanes 51..63 idle.  The sums over rows end in wave 0, lane <-> own column.
+    const int gq = lane / 17, ci = lane - 17 * gq;
+    const bool lact = lane < 17 * kC2FG && 2 * ci < g.nr;
+    const bool v0ok = lact && g.r0 + 2 * ci != 0;      // state 0 receives no label arcs
+    const bool v1ok = lact && 2 * ci + 1 < g.nr;
+    const int qF0 = kC2NQ * wave + gq;                  // first row of this lane
+    const int jlim = lact ? (C - qF0 + kC2FG - 1) / kC2FG : 0;   // rows j < jlim exist
+    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + 2 * ci;
+    const bool fok = lane < g.nr;                       // wave 0: lane <-> own column
     const int yF = min(g.r0 + lane, C - 1);
-    const bool f_no_label = g.r0 + lane == 0;         // state 0 receives no label arcs
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -187,10 +235,14 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         u64* xbase = a.xa + (size_t)g.cg * 2 * kClMaxK * kC2XS;
         const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
         const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
+        const buf_t brs = make_buf(bh, (unsigned)(a.T + 1) * pitch);
+        const buf_t sbrs = make_buf(Sb, (unsigned)(a.T + 1) * (unsigned)(kClMaxK * sizeof(int)));
+        const unsigned yoff = (unsigned)(yF * (int)sizeof(float));
+        const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         const unsigned coffP = (unsigned)(min(cP, C - 1) * (int)sizeof(float));
         const unsigned rbaseP = (unsigned)g.r0 * pitch;
-        const unsigned coffF = (unsigned)(yF * (int)sizeof(float));
-        const unsigned rowF0 = (unsigned)wave * pitch;               // scalar: first row of this wave
+        const unsigned coffF = (unsigned)gq * pitch + (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
         const int nlast = max(n - 1, 0);
 
@@ -198,15 +250,19 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q == 0 ? 1.f : 0.f;
         if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; bo_s[tid] = 0.f; }
         if (tid < 32) ctl_s[tid] = 0;
+        for (int q = tid; q < (kC2RedN + 1) * kC2Own; q += kC2Threads) shw_s[q] = kShiftNone;
+        for (int q = tid; q < kC2RedN * kC2Own; q += kC2Threads) red_s[q] = 0.f;
         if (tid < g.nr) ah[g.r0 + tid] = (g.r0 + tid == 0) ? 1.f : 0.f;
         if (tid == 0) Sa[g.k] = 0;
         __syncthreads();
 
-        float EF[2][kC2NQ], EP[2][kC2RT];
+        float EF0[2][kC2FJ], EF1[2][kC2FJ], EP[2][kC2RT];
         float EB[2] = {0.f, 0.f};
-        int shF[2] = {0, 0}, shP[2] = {0, 0}, sigP[2] = {0, 0};
-        float bF[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f}, boP[2] = {0.f, 0.f};   // other side's vector for the marginals
+        int shP[2] = {0, 0}, sigP[2] = {0, 0};
+        // other side's vector for the marginals
+        float bF0[2] = {0.f, 0.f}, bF1[2] = {0.f, 0.f}, bFb[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f}, boP[2] = {0.f, 0.f};
         int sbF[2] = {0, 0}, sbP[2] = {0, 0};
+        const int kP = min(cP, C - 1) / RPW;          // block of this thread's column
         double D2 = 0.0;
         int dead = 0;
         bool met = false;
@@ -216,15 +272,21 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const int tF = min(2 * p, nlast), tP = min(2 * p + 1, nlast);
-            bF[B_] = bh[(size_t)(tF + 1) * C + yF];
-            sbF[B_] = Sb[(size_t)(tF + 1) * kClMaxK + g.k];
-            bPv[B_] = bh[(size_t)(tP + 1) * C + min(cP, C - 1)];
-            sbP[B_] = Sb[(size_t)(tP + 1) * kClMaxK + min(cP, C - 1) / RPW];
+            // (32-bit offsets into buffer descriptors: 64-bit addresses per lane would cost the registers
+            // this kernel does not have; a column beyond the row reads a neighbour or zero and is unused)
+            const float2 bf = buf_load2(brs, coffF - (unsigned)gq * pitch, (unsigned)(tF + 1) * pitch);
+            bF0[B_] = bf.x; bF1[B_] = bf.y;
+            bFb[B_] = buf_load(brs, yoff, (unsigned)(tF + 1) * pitch);
+            // block exponents: one per lane (lane & 7), picked at the point of use.  A wave-uniform
+            // address would make these scalar loads, and every workgroup barrier waits for those.
+            sbF[B_] = __builtin_bit_cast(int, buf_load(sbrs, koff, (unsigned)(tF + 1) * (unsigned)(kClMaxK * sizeof(int))));
+            bPv[B_] = buf_load(brs, coffP, (unsigned)(tP + 1) * pitch);
+            sbP[B_] = __builtin_bit_cast(int, buf_load(sbrs, koff, (unsigned)(tP + 1) * (unsigned)(kClMaxK * sizeof(int))));
             // own states of that vector, relative to the exponent of block 0 (the block of column 0,
             // whose exponent the column-0 thread uses for the empty-label arcs)
-            boP[B_] = (tid < g.nr) ? c2_scale(bh[(size_t)(tP + 1) * C + g.r0 + tid],
-                                               Sb[(size_t)(tP + 1) * kClMaxK + g.k] - Sb[(size_t)(tP + 1) * kClMaxK])
-                                   : 0.f;
+            // (only loads here: arithmetic on the loaded values would wait for every load in flight)
+            boP[B_] = buf_load(brs, yoff, (unsigned)(tP + 1) * pitch);       // wave 0: own state of this lane
+
         };
         // The loads of a pair are issued in four pieces spread over the previous pair: issued in one
         // go, the whole chip would pull at the HBM limit for a moment and every wave would sit in its
@@ -232,13 +294,16 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         auto issueF = [&](auto BUF, int p, int j0, int j1) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foF = (unsigned)min(2 * p, nlast) * frb;
-            if (lane < kC2Own) {
+            int jl = jlim;
+            c2_pin(jl);          // the masked offsets are made where they are used, not kept in registers
 #pragma unroll
-                for (int j = 0; j < kC2NQ; ++j)
-                    if (j >= j0 && j < j1)
-                        EF[B_][j] = buf_load(wrs, coffF, foF + rowF0 + (unsigned)(kC2Waves * j) * pitch);
-                if (j1 >= kC2NQ) EB[B_] = buf_load(wrs, 0u, foF + rowB);
-            }
+            for (int j = 0; j < kC2FJ; ++j)
+                if (j >= j0 && j < j1) {
+                    const float2 x = buf_load2(wrs, j < jl ? coffF : kC2Off, foF + rowF0 + (unsigned)(kC2FG * j) * pitch);
+                    EF0[B_][j] = x.x;
+                    EF1[B_][j] = x.y;
+                }
+            if (j1 >= kC2FJ && wave == 0 && lane < kC2Own) EB[B_] = buf_load(wrs, rowB, foF);
             if (GAMMA && j0 == 0) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p, int r0_, int r1_) __attribute__((always_inline)) {
@@ -253,15 +318,24 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         // exp pass of both frames of a pair (contains workgroup barriers)
         auto prep = [&](auto BUF) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            // F frame: one shift per own column, common to the ten waves
-            float mx = LAST_NEG_INF;
+            // F frame: one shift per own column, common to all waves and row groups
+            float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
 #pragma unroll
-            for (int j = 0; j < kC2NQ; ++j) {
-                if (wave + kC2Waves * j >= C || f_no_label) EF[B_][j] = LAST_NEG_INF;
-                mx = fmaxf(mx, EF[B_][j]);
+            for (int j = 0; j < kC2FJ; ++j) {
+                if (j >= jlim || !v0ok) EF0[B_][j] = LAST_NEG_INF;
+                if (j >= jlim || !v1ok) EF1[B_][j] = LAST_NEG_INF;
+                m0 = fmaxf(m0, EF0[B_][j]);
+                m1 = fmaxf(m1, EF1[B_][j]);
             }
-            if (wave == 0) mx = fmaxf(mx, EB[B_]);
-            if (lane < kC2Own) shw_s[wave * kC2Own + lane] = shift_for(mx);
+            if (lane < 17 * kC2FG) {
+                int2 sw;
+                sw.x = shift_for(m0); sw.y = shift_for(m1);
+                *(int2*)&shw_s[slotF] = sw;
+            }
+            if (wave == 0 && lane < kC2Own) {
+                if (!fok) EB[B_] = LAST_NEG_INF;
+                shw_s[kC2RedN * kC2Own + lane] = shift_for(EB[B_]);
+            }
             // P frame: one shift per column and thread, the workgroup's largest as reference
             float mp = LAST_NEG_INF;
 #pragma unroll
@@ -273,22 +347,41 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const int wm = wave_max_dpp(colok ? sp : kShiftNone);
             if (lane == 0) ctl_s[16 + wave] = wm;
             c2_barrier();
-            int sc = kShiftNone;
-            if (lane < kC2Own) {
+            if (wave == 0) {
+                if (lane < kC2Own) {
+                    int sc = kShiftNone;
 #pragma unroll
-                for (int w2 = 0; w2 < kC2Waves; ++w2) sc = max(sc, shw_s[w2 * kC2Own + lane]);
+                    for (int x = 0; x <= kC2RedN; ++x) sc = max(sc, shw_s[x * kC2Own + lane]);
+                    shc_s[B_ * kC2Own + lane] = sc;
+                }
+                int sg = kShiftNone;
+#pragma unroll
+                for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
+                if (lane == 0) ctl_s[2 + B_] = sg;
             }
-            int sg = kShiftNone;
+            // the P frame does not depend on the shifts the other waves are waiting for
+            const float fsp = (float)sp;
 #pragma unroll
-            for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
-            const float fsc = (float)sc, fsp = (float)sp;
-#pragma unroll
-            for (int j = 0; j < kC2NQ; ++j) EF[B_][j] = fast_exp2(fmaf(EF[B_][j], kLog2e, -fsc));
-            EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -fsc));
-#pragma unroll
-            for (int r = 0; r < kC2RT; ++r) EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp));
-            shF[B_] = sc; shP[B_] = sp; sigP[B_] = sg;
+            for (int r = 0; r < kC2RT; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
             c2_barrier();
+            const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
+            const float fs0 = (float)sc2.x, fs1 = (float)sc2.y;
+#pragma unroll
+            for (int j = 0; j < kC2FJ; ++j) {
+                EF0[B_][j] = fast_exp2(fmaf(EF0[B_][j], kLog2e, -fs0));
+                EF1[B_][j] = fast_exp2(fmaf(EF1[B_][j], kLog2e, -fs1));
+                c2_pin(EF0[B_][j]); c2_pin(EF1[B_][j]);
+            }
+            if (wave == 0) EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)shc_s[B_ * kC2Own + min(lane, kC2Own - 1)]));
+            c2_pin(EB[B_]);
+            shP[B_] = sp; sigP[B_] = ctl_s[2 + B_];
+            if (GAMMA) {
+                // The prefetched values of the other side have arrived with the frame.  Touching them here
+                // keeps the compiler from guarding their later uses with waits counted along the shortest
+                // path, which on the waves that load more would stall on loads issued in between.
+                c2_pin(bF0[B_]); c2_pin(bF1[B_]); c2_pin(bFb[B_]); c2_pin(bPv[B_]); c2_pin(boP[B_]);
+                c2_pin(sbF[B_]); c2_pin(sbP[B_]);
+            }
         };
         auto meet = [&]() __attribute__((always_inline)) {
             if (dead) ctl_s[8] = 1;
@@ -315,42 +408,75 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= n) return false;
             C2_MARK(a, p, 0);
-            issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 17);
             C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             if (tF == mid && !met) {
                 meet();
-                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+                if (GAMMA) {
+                    other(std::integral_constant<int, B_>(), p);
+                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    c2_wait_loads();
+                }
             }
             {
                 const int S = ctl_s[0];
-                float ps = 0.f;
+                float aq[kC2FJ];
 #pragma unroll
-                for (int j = 0; j < kC2NQ; ++j) ps = fmaf(full_s[min(wave + kC2Waves * j, 319)], EF[B_][j], ps);
-                if (lane < kC2Own) red_s[wave * kC2Own + lane] = ps;
-                issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 17, kC2NQ);
-                if (GAMMA && tF >= mid && fok) {
-                    const float fc = a.scale * bF[B_] *
-                                     fast_exp2((float)((double)(sbF[B_] + shF[B_] + S) - D2));
+                for (int j = 0; j < kC2FJ; ++j) aq[j] = full_s[min(qF0 + kC2FG * j, 319)];
+                float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+                for (int j = 0; j < kC2FJ; ++j) {
+                    ps0 = fmaf(aq[j], EF0[B_][j], ps0);
+                    ps1 = fmaf(aq[j], EF1[B_][j], ps1);
+                }
+                if (lane < 17 * kC2FG) {
+                    float2 pw;
+                    pw.x = ps0; pw.y = ps1;
+                    *(float2*)&red_s[slotF] = pw;
+                }
+                C2_MARK(a, p, 6);
+                // next pair's F frame: issued behind the sums, which would otherwise wait for these loads
+                issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, kC2FJ);
+                if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
+                    const int sbk = __builtin_amdgcn_readlane(sbF[B_], g.k);
+                    {
+                        // lanes with both columns store 8 bytes; the few with one (the odd last column, the
+                        // column next to the start state) store it with a second instruction
+                        const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
+                        const float fc0 = a.scale * bF0[B_] * fast_exp2((float)((double)(sbk + S + sc2.x) - D2));
+                        const float fc1 = a.scale * bF1[B_] * fast_exp2((float)((double)(sbk + S + sc2.y) - D2));
+                        const unsigned off2 = (v0ok && v1ok) ? coffF : kC2Off;
+                        const unsigned off1 = (v0ok == v1ok) ? kC2Off : (v0ok ? coffF : coffF + 4u);
+                        int jl = jlim;
+                        c2_pin(jl);
 #pragma unroll
-                    for (int j = 0; j < kC2NQ; ++j)
-                        if (wave + kC2Waves * j < C && !f_no_label)
-                            buf_store(full_s[wave + kC2Waves * j] * EF[B_][j] * fc, grs, coffF,
-                                      gso + rowF0 + (unsigned)(kC2Waves * j) * pitch);
-                    if (wave == 0) buf_store(full_s[yF] * EB[B_] * fc, grs, 0u, gso + rowB);
+                        for (int j = 0; j < kC2FJ; ++j) {
+                            const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
+                            const float g0 = aq[j] * EF0[B_][j] * fc0, g1 = aq[j] * EF1[B_][j] * fc1;
+                            buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
+                            buf_store(v0ok ? g0 : g1, grs, j < jl ? off1 : kC2Off, so);
+                            __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
+                        }
+                    }
+                    if (wave == 0 && fok) {
+                        const float fcb = a.scale * bFb[B_] * fast_exp2((float)((double)(sbk + S + shc_s[B_ * kC2Own + lane]) - D2));
+                        buf_store(full_s[yF] * EB[B_] * fcb, grs, rowB, gso);
+                    }
                 }
                 c2_barrier();
+                C2_MARK(a, p, 7);
                 if (wave == 0) {
                     float v = 0.f;
+                    const int shFl = shc_s[B_ * kC2Own + min(lane, kC2Own - 1)];
                     if (fok) {
 #pragma unroll
-                        for (int w2 = 0; w2 < kC2Waves; ++w2) v += red_s[w2 * kC2Own + lane];
+                        for (int x = 0; x < kC2RedN; ++x) v += red_s[x * kC2Own + lane];
                         v = fmaf(full_s[yF], EB[B_], v);
                     }
-                    const int sc = (fok && v > 0.f) ? shF[B_] + float_exponent(v) : kShiftNone;
+                    const int sc = (fok && v > 0.f) ? shFl + float_exponent(v) : kShiftNone;
                     const int ms = wave_max_dpp(sc);
-                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shF[B_] - ms);
+                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shFl - ms);
                     if (lane < kC2Own) own_s[lane] = own;
                     const int ek = (ms == kShiftNone) ? S : S + ms;
                     if (lane == 0) ctl_s[1] = ek;
@@ -367,19 +493,20 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) {
                 meet();
-                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+                if (GAMMA) {
+                    other(std::integral_constant<int, B_>(), p);
+                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    c2_wait_loads();
+                }
             }
             {
                 const unsigned tag = gstep + 1;
                 u64* xs = xbase + (size_t)(gstep & 1) * kClMaxK * kC2XS;
                 const int ek = ctl_s[1];
-                float av[kC2RT];
-#pragma unroll
-                for (int r = 0; r < kC2RT; ++r) av[r] = own_s[r];
                 float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
                 for (int r = 0; r < kC2RT; ++r) {
-                    if (r & 1) acc1 = fmaf(av[r], EP[B_][r], acc1); else acc0 = fmaf(av[r], EP[B_][r], acc0);
+                    if (r & 1) acc1 = fmaf(own_s[r], EP[B_][r], acc1); else acc0 = fmaf(own_s[r], EP[B_][r], acc0);
                 }
                 const int sp = shP[B_], sg = sigP[B_];
                 const float val = (sp == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, sp - sg);
@@ -387,9 +514,12 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (cP == 0) {
 #pragma unroll
                     for (int r = 0; r < kC2RT; ++r)
-                        bl_s[r] = (sp == kShiftNone) ? 0.f : c2_scale(av[r] * EP[B_][r], sp - sg);
+                        bl_s[r] = (sp == kShiftNone) ? 0.f : c2_scale(own_s[r] * EP[B_][r], sp - sg);
                 }
-                if (GAMMA && tid < kC2Own) bo_s[tid] = boP[B_];
+                if (GAMMA && wave == 0) {
+                    const int dk = __builtin_amdgcn_readlane(sbP[B_], g.k) - __builtin_amdgcn_readlane(sbP[B_], 0);
+                    if (lane < kC2Own) bo_s[lane] = lane < g.nr ? c2_scale(boP[B_], dk) : 0.f;
+                }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
                 if (colok && exch) {
@@ -400,8 +530,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (tid == 0 && exch)
                     xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
                 if (GAMMA && tP >= mid) {
+                    const int sbk = __shfl(sbP[B_], kP, 64);       // every lane takes part
                     if (colok) {
-                        const float kx = (float)((double)(sbP[B_] + sp + ek) - D2);
+                        const float kx = (float)((double)(sbk + sp + ek) - D2);
                         const float fy = a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
                         const unsigned gso = (unsigned)tP * frb + rbaseP;
 #pragma unroll
@@ -409,7 +540,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                             if (r < nrtP) {
                                 // the empty label (column 0) returns to the row's own state
                                 const float f2 = (cP == 0) ? fy * bo_s[r] : fy;
-                                buf_store(av[r] * EP[B_][r] * f2, grs, coffP, gso + (unsigned)r * pitch);
+                                buf_store(own_s[r] * EP[B_][r] * f2, grs, coffP, gso + (unsigned)r * pitch);
                             }
                     }
                 }
@@ -489,13 +620,21 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         u64* xbase = a.xb + (size_t)g.cg * 2 * kClMaxK * kC2XS;
         const buf_t wrs = make_buf(wi, (unsigned)a.T * frb);
         const buf_t grs = make_buf(GAMMA ? (const float*)gi : wi, GAMMA ? (unsigned)a.T * frb : 0u);
-        unsigned coff[kClNC];
-#pragma unroll
-        for (int j = 0; j < kClNC; ++j) coff[j] = (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
+        // columns lane, lane + 64, ...: one register; a column beyond the row is neither read nor written
+        const unsigned coff0 = (unsigned)(lane * (int)sizeof(float));
+        auto coffj = [&](int j) __attribute__((always_inline)) {
+            return lane + 64 * j < C ? coff0 + 256u * (unsigned)j : kC2Off;
+        };
         auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
             return (unsigned)(g.r0 + min(wave + ri * kC2Waves, g.nr - 1)) * pitch;
         };
         const int nlast = max(n - 1, 0);
+        // the other side's vectors through 32-bit offsets (registers)
+        const buf_t ars = make_buf(ah, (unsigned)(a.T + 1) * pitch);
+        const buf_t sars = make_buf(Sa, (unsigned)(a.T + 1) * (unsigned)(kClMaxK * sizeof(int)));
+        const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
+        // lanes 0..4 of a wave: the wave's own rows of the F-step
+        const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
 
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
@@ -524,10 +663,12 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const int tF = frameF(p), tP = frameP(p);
-            aF[B_] = (lane < kC2RW) ? ah[(size_t)tF * C + g.r0 + min(wave + lane * kC2Waves, g.nr - 1)] : 0.f;
-            saF[B_] = Sa[(size_t)tF * kClMaxK + g.k];
-            aP[B_] = ah[(size_t)tP * C + qP];
-            saP[B_] = Sa[(size_t)tP * kClMaxK + qP / RPW];
+            aF[B_] = buf_load(ars, aoffF, (unsigned)tF * pitch);
+            // block exponents: one per lane (lane & 7), picked at the point of use.  A wave-uniform
+            // address would make these scalar loads, and every workgroup barrier waits for those.
+            saF[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tF * (unsigned)(kClMaxK * sizeof(int))));
+            aP[B_] = buf_load(ars, (unsigned)(qP * (int)sizeof(float)), (unsigned)tP * pitch);
+            saP[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tP * (unsigned)(kClMaxK * sizeof(int))));
         };
         auto issueF = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -535,7 +676,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri)
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coff[j], foF + roff(ri));
+                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffj(j), foF + roff(ri));
             if (GAMMA) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
@@ -575,7 +716,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 srF[B_][ri] = s;
                 const float fs = (float)s;
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
+                for (int j = 0; j < kClNC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
             }
             // P frame: one shift per row = per thread, over the own label columns
             int sp = kShiftNone, sb = kShiftNone;
@@ -589,10 +730,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 sp = shift_for(mx);
                 const float fs = (float)sp;
 #pragma unroll
-                for (int c = 0; c < kC2RT; ++c) EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs));
+                for (int c = 0; c < kC2RT; ++c) { EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs)); c2_pin(EPb[B_].v[c]); }
                 // empty-label weight of an own state, with its own shift
                 sb = shift_for(rowown ? EB[B_] : LAST_NEG_INF);
                 EB[B_] = rowown ? fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb)) : 0.f;
+                c2_pin(EB[B_]);
             }
             srP[B_] = sp; sbl[B_] = sb;
             const int wm = wave_max_dpp(max(sp, sb));
@@ -602,6 +744,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
             for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
             sigP[B_] = sg;
+            if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); }
             c2_barrier();
         };
         auto meet = [&]() __attribute__((always_inline)) {
@@ -629,7 +772,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
             if (iF == ph1 && !met) {
                 meet();
-                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+                if (GAMMA) {
+                    other(std::integral_constant<int, B_>(), p);
+                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    c2_wait_loads();
+                }
             }
             {
                 const int tF = L - 1 - iF;
@@ -653,13 +800,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (GAMMA && iF >= ph1 && ri < nrw) {
                         const float arow = __shfl(aF[B_], ri, 64);
                         const float fac = a.scale * arow *
-                                          fast_exp2((float)((double)(saF[B_] + srF[B_][ri] + S) - D2));
+                                          fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
                         const unsigned gso = (unsigned)tF * frb + roff(ri);
 #pragma unroll
                         for (int j = 0; j < kClNC; ++j)
-                            if (lane + 64 * j < C) {
+                            {
                                 const float bb = (j == 0 && lane == 0) ? brow : bv[j];
-                                buf_store(EFb[B_][ri][j] * bb * fac, grs, coff[j], gso);
+                                buf_store(EFb[B_][ri][j] * bb * fac, grs, coffj(j), gso);
                             }
                     }
                 }
@@ -686,7 +833,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) {
                 meet();
-                if (GAMMA) { other(std::integral_constant<int, B_>(), p); other(std::integral_constant<int, B_ ^ 1>(), p + 1); }
+                if (GAMMA) {
+                    other(std::integral_constant<int, B_>(), p);
+                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    c2_wait_loads();
+                }
             }
             {
                 const int tP = L - 1 - iP;
@@ -695,11 +846,10 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const int ek = ctl_s[1];
                 const int sg = sigP[B_];
                 const bool exch = !(GAMMA && iP == L - 1);
+                const int sak = GAMMA ? __shfl(saP[B_], qP / RPW, 64) : 0;       // every lane takes part
                 if (wave < 5) {
                     // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state)
-                    float bo[kC2RT];
-#pragma unroll
-                    for (int c = 0; c < kC2RT; ++c) bo[c] = own_s[c];
+                    const float* bo = own_s;
                     float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
                     for (int c = 0; c < kC2RT; ++c) {
@@ -714,7 +864,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (GAMMA && iP >= ph1 && rowok) {
                         // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
                         const float rf = (srP[B_] == kShiftNone) ? 0.f
-                            : a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + srP[B_] + ek) - D2));
+                            : a.scale * aP[B_] * fast_exp2((float)((double)(sak + srP[B_] + ek) - D2));
                         float* gp = gi + (size_t)tP * fr + (size_t)qP * C + g.r0;
 #pragma unroll
                         for (int c4 = 0; c4 < kC2RT / 4; ++c4) {
@@ -736,7 +886,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                         if (rowown) {
                             // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
                             const float f0 = (sbl[B_] == kShiftNone) ? 0.f
-                                : a.scale * aP[B_] * fast_exp2((float)((double)(saP[B_] + sbl[B_] + ek) - D2));
+                                : a.scale * aP[B_] * fast_exp2((float)((double)(sak + sbl[B_] + ek) - D2));
                             gp[-g.r0] = EB[B_] * bq * f0;
                         }
                     }
@@ -772,7 +922,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 template <bool GAMMA>
 __global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
 {
-    __shared__ float smem[kC2Lds];
+    __shared__ __align__(16) float smem[kC2Lds];
     ClusterGeom g;
     const int id = blockIdx.x;
     const int x = id & 7, slot = id >> 3;
