@@ -104,40 +104,61 @@ __device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e, zero s
     return (v == 0.f) ? 0.f : __builtin_ldexpf(v, max(e, -300));
 }
 
-// Read all K x C partial values and the K exponents of one exchange slot, add the values up in
-// producer order relative to the largest exponent, leave the vector in full_s and its exponent
-// in ctl_s[0].  Every thread calls; ends with a workgroup barrier.
-__device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
-                                          int* ctl_s, int limit, int& dead)
+// Exchange word of this kernel: [value:32 | tag:16 | exponent:16].  The exponent is the producer's,
+// relative to the exponent of the vector both sides already share (the one the pair started from), so
+// that it fits 16 bits whatever the length of the sequence; it is the same in all words of a producer.
+// A slot is rewritten every second exchange, so 16 bits of the step number identify a word.
+__device__ __forceinline__ u64 c2_pack(float v, unsigned tag, int rel)
+{
+    return (u64)__float_as_uint(v) | ((u64)((tag & 0xFFFFu) << 16 | ((unsigned)rel & 0xFFFFu)) << 32);
+}
+
+// Gathering one exchange slot: all K x C partial values, added up in producer order relative to the
+// largest exponent; the vector ends in full_s, its exponent in ctl_s[0].
+// The first look is issued before the exp pass of the next pair (c2_gather_look) and examined after
+// it (c2_gather): by then the words have usually arrived and the round trip to the L2 cache is hidden.
+struct C2Look {
+    u64 wv[kClMaxK];
+};
+
+__device__ __forceinline__ void c2_gather_look(const u64* xs, int K, int C, C2Look& lk)
 {
     const int tid = threadIdx.x;
+    if (tid < C) {
+#pragma unroll
+        for (int kk = 0; kk < kClMaxK; ++kk)
+            if (kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
+    }
+}
+
+// Every thread calls; ends with a workgroup barrier.
+__device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
+                                          int* ctl_s, int limit, int& dead, C2Look& lk)
+{
+    const int tid = threadIdx.x;
+    const int S0 = ctl_s[0];           // exponent the producers' exponents are relative to
     float v = 0.f;
     int hr = 0;
     if (tid < C) {
-        u64 wv[kClMaxK], hv[kClMaxK];
         int n = 0;
         for (;;) {
             bool ok = true;
 #pragma unroll
             for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) {
-                    wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
-                    hv[kk] = xload(xs + (size_t)kk * kC2XS + kC2Hdr);
-                }
-#pragma unroll
-            for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) ok = ok && (unsigned)(wv[kk] >> 32) == tag && (unsigned)(hv[kk] >> 32) == tag;
+                if (kk < K) ok = ok && (unsigned)(lk.wv[kk] >> 48) == (tag & 0xFFFFu);
             if (ok || dead) break;
             if (++n > limit) { dead = 1; break; }
             __builtin_amdgcn_s_sleep(1);
+            c2_gather_look(xs, K, C, lk);
         }
         int href = -(1 << 30);
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K) href = max(href, (int)(unsigned)hv[kk]);
+            if (kk < K) href = max(href, (int)(short)(unsigned short)(lk.wv[kk] >> 32));
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K) v += c2_scale(__uint_as_float((unsigned)wv[kk]), (int)(unsigned)hv[kk] - href);
+            if (kk < K)
+                v += c2_scale(__uint_as_float((unsigned)lk.wv[kk]), (int)(short)(unsigned short)(lk.wv[kk] >> 32) - href);
         hr = href;
     }
     // renormalise by the largest magnitude actually present, so that mantissas do not drift
@@ -150,7 +171,7 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
     for (int w2 = 0; w2 < kC2Waves; ++w2) mx = max(mx, ctl_s[24 + w2]);
     if (mx == -(1 << 20)) mx = 0;
     if (tid < C) full_s[tid] = c2_scale(v, -mx);
-    if (tid == 0) ctl_s[0] = hr + mx;
+    if (tid == 0) ctl_s[0] = S0 + hr + mx;
     c2_barrier();
 }
 
@@ -316,7 +337,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             }
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
-        auto prep = [&](auto BUF) __attribute__((always_inline)) {
+        auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             // F frame: one shift per own column, common to all waves and row groups
             float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
@@ -347,6 +368,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const int wm = wave_max_dpp(colok ? sp : kShiftNone);
             if (lane == 0) ctl_s[16 + wave] = wm;
             c2_barrier();
+            halfway();
             if (wave == 0) {
                 if (lane < kC2Own) {
                     int sc = kShiftNone;
@@ -400,7 +422,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 
         issueF(std::integral_constant<int, 0>(), 0, 0, kC2NQ);
         issueP(std::integral_constant<int, 0>(), 0, 0, kC2RT);
-        prep(std::integral_constant<int, 0>());
+        prep(std::integral_constant<int, 0>(), [] {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
@@ -525,10 +547,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (colok && exch) {
                     float pub = (cP == 0) ? 0.f : val;          // column 0 is the empty label, not a label arc
                     if (cP >= g.r0 && cP < g.r0 + g.nr) pub += bl_s[cP - g.r0];
-                    xpublish(xs + (size_t)g.k * kC2XS + cP, pack_word(pub, tag));
+                    xpublish(xs + (size_t)g.k * kC2XS + cP, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
-                if (tid == 0 && exch)
-                    xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
                 if (GAMMA && tP >= mid) {
                     const int sbk = __shfl(sbP[B_], kP, 64);       // every lane takes part
                     if (colok) {
@@ -545,10 +565,13 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     }
                 }
                 C2_MARK(a, p, 3);
-                prep(std::integral_constant<int, B_ ^ 1>());
+                // first look at the exchange halfway through the exp pass: early enough for the round trip to
+                // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
+                C2Look lk;
+                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
                 C2_MARK(a, p, 4);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk);
                     C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP + 1 <= mid) {
@@ -700,7 +723,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 EB[B_] = rp[-g.r0];                                   // w[q][0]
             }
         };
-        auto prep = [&](auto BUF) __attribute__((always_inline)) {
+        auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             // F frame: one shift per own row (wave-uniform)
 #pragma unroll
@@ -718,6 +741,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                 for (int j = 0; j < kClNC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
             }
+            halfway();
             // P frame: one shift per row = per thread, over the own label columns
             int sp = kShiftNone, sb = kShiftNone;
             if (wave < 5) {
@@ -759,7 +783,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 
         issueF(std::integral_constant<int, 0>(), 0);
         issueP(std::integral_constant<int, 0>(), 0);
-        prep(std::integral_constant<int, 0>());
+        prep(std::integral_constant<int, 0>(), [] {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
@@ -859,7 +883,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (rowok && exch) {
                         float pub = (srP[B_] == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, srP[B_] - sg);
                         if (rowown && sbl[B_] != kShiftNone) pub += c2_scale(EB[B_] * bq, sbl[B_] - sg);
-                        xpublish(xs + (size_t)g.k * kC2XS + tid, pack_word(pub, tag));
+                        xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                     }
                     if (GAMMA && iP >= ph1 && rowok) {
                         // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
@@ -891,13 +915,14 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                         }
                     }
                 }
-                if (tid == 0 && exch)
-                    xpublish(xs + (size_t)g.k * kC2XS + kC2Hdr, pack_int(sg == kShiftNone ? ek : ek + sg, tag));
                 C2_MARK(a, p, 3);
-                prep(std::integral_constant<int, B_ ^ 1>());
+                // first look at the exchange halfway through the exp pass: early enough for the round trip to
+                // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
+                C2Look lk;
+                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
                 C2_MARK(a, p, 4);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk);
                     C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP >= mid) {
