@@ -47,7 +47,10 @@ constexpr int kC2FJ = 11;      // alpha F-step: rows per lane, kC2FG * kC2FJ = k
 constexpr int kC2Hdr = 264;    // exchange row: C values, the producer's exponent at [kC2Hdr]
 constexpr int kC2XS = 272;     // words per producer and slot
 constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
-constexpr int kC2RT = 33;      // own rows per column thread (alpha P-step)
+constexpr int kC2RT = 33;      // own rows (alpha) or own columns (beta) of a workgroup in the P-step
+constexpr int kC2PH = 17;      // ... of which a thread takes one half: [0, 17) or [17, 33)
+constexpr int kC2PC = 256;     // columns (alpha) or rows (beta) that have a thread per half; the few beyond
+                               // ("stragglers", at most 8) are taken by one wave each, lane <-> own row / column
 constexpr int kC2Own = 40;     // LDS slots for own states
 // A per-lane buffer offset beyond every descriptor's size: the hardware's range check drops the lane's
 // store and returns zero for its load.  Replaces branches around accesses whose mask differs per lane.
@@ -65,7 +68,8 @@ constexpr int kC2Pacc = kC2Bl + kC2Own;             // [320] partial sums of the
 constexpr int kC2Bo = kC2Pacc + 320;                // [40] other side's own-state values (marginals)
 constexpr int kC2Ctl = kC2Bo + kC2Own;              // [32] ints
 constexpr int kC2RedB = kC2Ctl + 32;                // [32] block reductions
-constexpr int kC2Lds = kC2RedB + 32;
+constexpr int kC2Strag = kC2RedB + 32;              // [8] partial sums of the straggler columns / rows
+constexpr int kC2Lds = kC2Strag + 8;
 
 #ifdef LAST_TRACE
 #define C2_MARK(a, p, k)                                                                    \
@@ -223,10 +227,17 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int C = a.C, K = a.K, RPW = a.RPW;
-    // P-step: thread <-> column cP (waves 0..4), all own rows
-    const int cP = tid;
+    // P-step: thread <-> column cP = 64 (wave & 3) + lane and half hP = wave >> 2 of the own rows;
+    // straggler column 256 + sS on wave 7 - sS, lane <-> own row
+    float* strag_s = smem + kC2Strag;
+    const int hP = wave >> 2;
+    const int cP = ((wave & 3) << 6) + lane;
     const bool colok = cP < C;
-    const int nrtP = g.nr;
+    const int rP0 = kC2PH * hP;
+    const int nst = max(C - kC2PC, 0);
+    const int sS = kC2Waves - 1 - wave;
+    const bool hasS = sS < nst;
+    const int cS = kC2PC + sS;
     // F-step: wave <-> rows [33 wave, 33 wave + 33); inside the wave three groups of 17 lanes take every
     // third row, and a lane takes two neighbouring own columns (8-byte accesses): row 33 wave + 3 j + gq,
     // columns r0 + 2 ci, r0 + 2 ci + 1.  Lanes 51..63 idle.  The sums over rows end in wave 0, lane <-> own column.
@@ -261,6 +272,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         const unsigned yoff = (unsigned)(yF * (int)sizeof(float));
         const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         const unsigned coffP = (unsigned)(min(cP, C - 1) * (int)sizeof(float));
+        const unsigned coffPm = colok ? (unsigned)(cP * (int)sizeof(float)) : kC2Off;     // nothing beyond the row
+        const unsigned coffS = lane < g.nr ? (unsigned)lane * pitch + (unsigned)(cS * (int)sizeof(float)) : kC2Off;
+        const unsigned soffS = (unsigned)(min(kC2PC + (lane & 7), C - 1) * (int)sizeof(float));
         const unsigned rbaseP = (unsigned)g.r0 * pitch;
         const unsigned coffF = (unsigned)gq * pitch + (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
@@ -277,9 +291,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         if (tid == 0) Sa[g.k] = 0;
         __syncthreads();
 
-        float EF0[2][kC2FJ], EF1[2][kC2FJ], EP[2][kC2RT];
-        float EB[2] = {0.f, 0.f};
-        int shP[2] = {0, 0}, sigP[2] = {0, 0};
+        float EF0[2][kC2FJ], EF1[2][kC2FJ], EP[2][kC2PH];
+        float EB[2] = {0.f, 0.f}, ES[2] = {0.f, 0.f}, bSt[2] = {0.f, 0.f};
+        int shP[2] = {0, 0}, sigP[2] = {0, 0}, ssP[2] = {kShiftNone, kShiftNone};
         // other side's vector for the marginals
         float bF0[2] = {0.f, 0.f}, bF1[2] = {0.f, 0.f}, bFb[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f}, boP[2] = {0.f, 0.f};
         int sbF[2] = {0, 0}, sbP[2] = {0, 0};
@@ -307,7 +321,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             // whose exponent the column-0 thread uses for the empty-label arcs)
             // (only loads here: arithmetic on the loaded values would wait for every load in flight)
             boP[B_] = buf_load(brs, yoff, (unsigned)(tP + 1) * pitch);       // wave 0: own state of this lane
-
+            if (nst > 0) bSt[B_] = buf_load(brs, soffS, (unsigned)(tP + 1) * pitch);   // lanes 0..7: straggler columns
         };
         // The loads of a pair are issued in four pieces spread over the previous pair: issued in one
         // go, the whole chip would pull at the HBM limit for a moment and every wave would sit in its
@@ -330,11 +344,11 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         auto issueP = [&](auto BUF, int p, int r0_, int r1_) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foP = (unsigned)min(2 * p + 1, nlast) * frb;
-            if (wave < 5) {
 #pragma unroll
-                for (int r = 0; r < kC2RT; ++r)
-                    if (r >= r0_ && r < r1_) EP[B_][r] = buf_load(wrs, coffP, foP + rbaseP + (unsigned)r * pitch);
-            }
+            for (int r = 0; r < kC2PH; ++r)
+                if (r >= r0_ && r < r1_)
+                    EP[B_][r] = buf_load(wrs, rP0 + r < g.nr ? coffPm : kC2Off, foP + rbaseP + (unsigned)(rP0 + r) * pitch);
+            if (r1_ >= kC2PH && hasS) ES[B_] = buf_load(wrs, coffS, foP + rbaseP);
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
@@ -360,12 +374,20 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             // P frame: one shift per column and thread, the workgroup's largest as reference
             float mp = LAST_NEG_INF;
 #pragma unroll
-            for (int r = 0; r < kC2RT; ++r) {
-                if (r >= nrtP || !colok) EP[B_][r] = LAST_NEG_INF;
+            for (int r = 0; r < kC2PH; ++r) {
+                if (rP0 + r >= g.nr) EP[B_][r] = LAST_NEG_INF;       // (the same for the whole wave)
                 mp = fmaxf(mp, EP[B_][r]);
             }
-            const int sp = shift_for(mp);
-            const int wm = wave_max_dpp(colok ? sp : kShiftNone);
+            const int sp = colok ? shift_for(mp) : kShiftNone;
+            int wm = wave_max_dpp(sp);
+            int ssp = kShiftNone;
+            if (hasS) {
+                const float e = lane < g.nr ? ES[B_] : LAST_NEG_INF;
+                ssp = shift_for(wave_max_dpp(e));
+                ES[B_] = fast_exp2(fmaf(e, kLog2e, -(float)ssp));
+                c2_pin(ES[B_]);
+                wm = max(wm, ssp);
+            }
             if (lane == 0) ctl_s[16 + wave] = wm;
             c2_barrier();
             halfway();
@@ -382,9 +404,10 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (lane == 0) ctl_s[2 + B_] = sg;
             }
             // the P frame does not depend on the shifts the other waves are waiting for
-            const float fsp = (float)sp;
+            // (a lane without a column loaded zeros: a huge shift turns them into E = 0)
+            const float fsp = sp == kShiftNone ? 3.0e38f : (float)sp;
 #pragma unroll
-            for (int r = 0; r < kC2RT; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
+            for (int r = 0; r < kC2PH; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
             c2_barrier();
             const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
             const float fs0 = (float)sc2.x, fs1 = (float)sc2.y;
@@ -396,8 +419,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             }
             if (wave == 0) EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)shc_s[B_ * kC2Own + min(lane, kC2Own - 1)]));
             c2_pin(EB[B_]);
-            shP[B_] = sp; sigP[B_] = ctl_s[2 + B_];
+            shP[B_] = sp; sigP[B_] = ctl_s[2 + B_]; ssP[B_] = ssp;
             if (GAMMA) {
+                c2_pin(bSt[B_]);
                 // The prefetched values of the other side have arrived with the frame.  Touching them here
                 // keeps the compiler from guarding their later uses with waits counted along the shortest
                 // path, which on the waves that load more would stall on loads issued in between.
@@ -421,7 +445,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         };
 
         issueF(std::integral_constant<int, 0>(), 0, 0, kC2NQ);
-        issueP(std::integral_constant<int, 0>(), 0, 0, kC2RT);
+        issueP(std::integral_constant<int, 0>(), 0, 0, kC2PH);
         prep(std::integral_constant<int, 0>(), [] {});
 
         int p = 0;
@@ -511,7 +535,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             }
             if (tP >= n) return false;
             C2_MARK(a, p, 2);
-            issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 17);
+            issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 9);
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) {
                 meet();
@@ -527,16 +551,21 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 const int ek = ctl_s[1];
                 float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-                for (int r = 0; r < kC2RT; ++r) {
-                    if (r & 1) acc1 = fmaf(own_s[r], EP[B_][r], acc1); else acc0 = fmaf(own_s[r], EP[B_][r], acc0);
+                for (int r = 0; r < kC2PH; ++r) {
+                    if (r & 1) acc1 = fmaf(own_s[rP0 + r], EP[B_][r], acc1); else acc0 = fmaf(own_s[rP0 + r], EP[B_][r], acc0);
                 }
-                const int sp = shP[B_], sg = sigP[B_];
+                const int sp = shP[B_], sg = sigP[B_], ssp = ssP[B_];
                 const float val = (sp == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, sp - sg);
-                issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 17, kC2RT);
+                issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 9, kC2PH);
                 if (cP == 0) {
 #pragma unroll
-                    for (int r = 0; r < kC2RT; ++r)
-                        bl_s[r] = (sp == kShiftNone) ? 0.f : c2_scale(own_s[r] * EP[B_][r], sp - sg);
+                    for (int r = 0; r < kC2PH; ++r)
+                        bl_s[rP0 + r] = (sp == kShiftNone) ? 0.f : c2_scale(own_s[rP0 + r] * EP[B_][r], sp - sg);
+                }
+                if (hP == 1) pacc_s[cP] = val;                 // second half of the own rows
+                if (hasS) {
+                    const float sv = wave_sum_dpp(lane < g.nr ? own_s[lane] * ES[B_] : 0.f);
+                    if (lane == 0) strag_s[sS] = (ssp == kShiftNone) ? 0.f : c2_scale(sv, ssp - sg);
                 }
                 if (GAMMA && wave == 0) {
                     const int dk = __builtin_amdgcn_readlane(sbP[B_], g.k) - __builtin_amdgcn_readlane(sbP[B_], 0);
@@ -544,24 +573,33 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
-                if (colok && exch) {
-                    float pub = (cP == 0) ? 0.f : val;          // column 0 is the empty label, not a label arc
-                    if (cP >= g.r0 && cP < g.r0 + g.nr) pub += bl_s[cP - g.r0];
-                    xpublish(xs + (size_t)g.k * kC2XS + cP, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
+                if (tid < C && exch) {
+                    // threads 0..255 are the first halves of their columns; 256.. publish the stragglers
+                    float pub = tid < kC2PC ? (tid == 0 ? 0.f : val + pacc_s[tid])      // column 0: the empty label
+                                            : strag_s[tid - kC2PC];
+                    if (tid >= g.r0 && tid < g.r0 + g.nr) pub += bl_s[tid - g.r0];
+                    xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
                 if (GAMMA && tP >= mid) {
                     const int sbk = __shfl(sbP[B_], kP, 64);       // every lane takes part
-                    if (colok) {
+                    const unsigned gso = (unsigned)tP * frb + rbaseP;
+                    {
                         const float kx = (float)((double)(sbk + sp + ek) - D2);
-                        const float fy = a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
-                        const unsigned gso = (unsigned)tP * frb + rbaseP;
+                        const float fy = (sp == kShiftNone) ? 0.f : a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
 #pragma unroll
-                        for (int r = 0; r < kC2RT; ++r)
-                            if (r < nrtP) {
-                                // the empty label (column 0) returns to the row's own state
-                                const float f2 = (cP == 0) ? fy * bo_s[r] : fy;
-                                buf_store(own_s[r] * EP[B_][r] * f2, grs, coffP, gso + (unsigned)r * pitch);
-                            }
+                        for (int r = 0; r < kC2PH; ++r) {
+                            // the empty label (column 0) returns to the row's own state
+                            const float f2 = (cP == 0) ? fy * bo_s[rP0 + r] : fy;
+                            buf_store(own_s[rP0 + r] * EP[B_][r] * f2, grs, rP0 + r < g.nr ? coffPm : kC2Off,
+                                      gso + (unsigned)(rP0 + r) * pitch);
+                        }
+                    }
+                    if (hasS) {
+                        const int sbkS = __builtin_amdgcn_readlane(sbP[B_], cS / RPW);
+                        const float bS = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bSt[B_]), sS));
+                        const float fyS = (ssp == kShiftNone) ? 0.f
+                                          : a.scale * bS * fast_exp2((float)((double)(sbkS + ssp + ek) - D2));
+                        buf_store(own_s[min(lane, kC2Own - 1)] * ES[B_] * fyS, grs, coffS, gso);
                     }
                 }
                 C2_MARK(a, p, 3);
@@ -595,10 +633,10 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
-// row of 33 consecutive floats, read or written in 16-byte pieces (the rows of the weight tensor are
-// only 4-byte aligned; the compiler picks the widest access the target allows for that alignment)
+// one half of a row's own columns: 17 consecutive floats, read or written in 16-byte pieces (the rows of
+// the weight tensor are only 4-byte aligned; the compiler picks the widest access the target allows)
 struct C2Row {
-    float v[kC2RT];
+    float v[kC2PH];
 };
 typedef float c2_f4 __attribute__((ext_vector_type(4), aligned(4)));
 
@@ -618,11 +656,23 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns
     int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
     if (nrw < 0) nrw = 0;
-    // P-step: thread <-> row qP of the frame (waves 0..4), its own-column elements in registers
-    const int qP = min(tid, C - 1);
-    const bool rowok = tid < C;
-    const bool rowown = rowok && tid >= g.r0 && tid < g.r0 + g.nr;   // this row's state is an own state
+    // P-step: thread <-> row 64 (wave & 3) + lane and half hP = wave >> 2 of the own columns, whose elements
+    // it keeps in registers; straggler row 256 + sS on wave 7 - sS, lane <-> own column (lane nr: column 0)
+    float* pacc_s = smem + kC2Pacc;
+    float* strag_s = smem + kC2Strag;
+    const int hP = wave >> 2;
+    const int qPr = ((wave & 3) << 6) + lane;
+    const int qP = min(qPr, C - 1);
+    const bool rowok = qPr < C;
+    const bool rowown = rowok && hP == 0 && qPr >= g.r0 && qPr < g.r0 + g.nr;   // own state: the first half adds the empty label
     const int c_lo = g.r0 == 0 ? 1 : 0;                               // column 0 is the empty label
+    const int cP0 = kC2PH * hP;
+    const int nst = max(C - kC2PC, 0);
+    const int sS = kC2Waves - 1 - wave;
+    const bool hasS = sS < nst;
+    const int qS = kC2PC + sS;
+    const bool ownS = qS >= g.r0 && qS < g.r0 + g.nr;
+    const bool validS = (lane >= c_lo && lane < g.nr) || (lane == g.nr && ownS);
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -658,6 +708,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         // lanes 0..4 of a wave: the wave's own rows of the F-step
         const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
+        // straggler row: own columns, then column 0
+        const unsigned coffS = validS ? (unsigned)((lane < g.nr ? g.r0 + lane : 0) * (int)sizeof(float)) : kC2Off;
+        const unsigned soffS = (unsigned)(min(kC2PC + (lane & 7), C - 1) * (int)sizeof(float));
 
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
@@ -669,9 +722,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 
         float EFb[2][kC2RW][kClNC];
         C2Row EPb[2];
-        float EB[2] = {0.f, 0.f};
+        float EB[2] = {0.f, 0.f}, ES[2] = {0.f, 0.f}, aSt[2] = {0.f, 0.f};
         int srF[2][kC2RW];
-        int srP[2] = {0, 0}, sbl[2] = {0, 0}, sigP[2] = {0, 0};
+        int srP[2] = {0, 0}, sbl[2] = {0, 0}, sigP[2] = {0, 0}, ssP[2] = {kShiftNone, kShiftNone};
         float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
         int saF[2] = {0, 0}, saP[2] = {0, 0};
         double D2 = 0.0;
@@ -692,6 +745,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             saF[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tF * (unsigned)(kClMaxK * sizeof(int))));
             aP[B_] = buf_load(ars, (unsigned)(qP * (int)sizeof(float)), (unsigned)tP * pitch);
             saP[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tP * (unsigned)(kClMaxK * sizeof(int))));
+            if (nst > 0) aSt[B_] = buf_load(ars, soffS, (unsigned)tP * pitch);       // lanes 0..7: straggler rows
         };
         auto issueF = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -704,24 +758,25 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            if (wave < 5) {
-                const float* rp = wi + (size_t)frameP(p) * fr + (size_t)qP * C + g.r0;
+            {
+                const float* rp = wi + (size_t)frameP(p) * fr + (size_t)qP * C + g.r0 + cP0;
                 // full 16-byte pieces inside the own columns, then element by element
 #pragma unroll
-                for (int c4 = 0; c4 < kC2RT / 4; ++c4) {
-                    if (4 * c4 + 3 < g.nr) {
+                for (int c4 = 0; c4 < kC2PH / 4; ++c4) {
+                    if (cP0 + 4 * c4 + 3 < g.nr) {
                         const c2_f4 x = *(const c2_f4*)(rp + 4 * c4);
                         EPb[B_].v[4 * c4] = x.x; EPb[B_].v[4 * c4 + 1] = x.y;
                         EPb[B_].v[4 * c4 + 2] = x.z; EPb[B_].v[4 * c4 + 3] = x.w;
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            EPb[B_].v[4 * c4 + e] = (4 * c4 + e < g.nr) ? rp[4 * c4 + e] : LAST_NEG_INF;
+                            EPb[B_].v[4 * c4 + e] = (cP0 + 4 * c4 + e < g.nr) ? rp[4 * c4 + e] : LAST_NEG_INF;
                     }
                 }
-                EPb[B_].v[kC2RT - 1] = (kC2RT - 1 < g.nr) ? rp[kC2RT - 1] : LAST_NEG_INF;
-                EB[B_] = rp[-g.r0];                                   // w[q][0]
+                EPb[B_].v[kC2PH - 1] = (cP0 + kC2PH - 1 < g.nr) ? rp[kC2PH - 1] : LAST_NEG_INF;
+                if (hP == 0) EB[B_] = rp[-g.r0];                      // w[q][0]
             }
+            if (hasS) ES[B_] = buf_load(wrs, coffS, (unsigned)frameP(p) * frb + (unsigned)qS * pitch);
         };
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -742,34 +797,42 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 for (int j = 0; j < kClNC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
             }
             halfway();
-            // P frame: one shift per row = per thread, over the own label columns
+            // P frame: one shift per row and half = per thread, over its own label columns
             int sp = kShiftNone, sb = kShiftNone;
-            if (wave < 5) {
+            {
                 float mx = LAST_NEG_INF;
 #pragma unroll
-                for (int c = 0; c < kC2RT; ++c) {
-                    if (c < c_lo || c >= g.nr || !rowok) EPb[B_].v[c] = LAST_NEG_INF;
+                for (int c = 0; c < kC2PH; ++c) {
+                    if (cP0 + c < c_lo || cP0 + c >= g.nr || !rowok) EPb[B_].v[c] = LAST_NEG_INF;
                     mx = fmaxf(mx, EPb[B_].v[c]);
                 }
                 sp = shift_for(mx);
                 const float fs = (float)sp;
 #pragma unroll
-                for (int c = 0; c < kC2RT; ++c) { EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs)); c2_pin(EPb[B_].v[c]); }
+                for (int c = 0; c < kC2PH; ++c) { EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs)); c2_pin(EPb[B_].v[c]); }
                 // empty-label weight of an own state, with its own shift
                 sb = shift_for(rowown ? EB[B_] : LAST_NEG_INF);
                 EB[B_] = rowown ? fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb)) : 0.f;
                 c2_pin(EB[B_]);
             }
             srP[B_] = sp; sbl[B_] = sb;
-            const int wm = wave_max_dpp(max(sp, sb));
+            int wm = wave_max_dpp(max(sp, sb));
+            int ssp = kShiftNone;
+            if (hasS) {
+                const float e = validS ? ES[B_] : LAST_NEG_INF;
+                ssp = shift_for(wave_max_dpp(e));
+                ES[B_] = fast_exp2(fmaf(e, kLog2e, -(float)ssp));
+                c2_pin(ES[B_]);
+                wm = max(wm, ssp);
+            }
+            ssP[B_] = ssp;
             if (lane == 0) ctl_s[16 + wave] = wm;
             c2_barrier();
             int sg = kShiftNone;
 #pragma unroll
             for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
             sigP[B_] = sg;
-            if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); }
-            c2_barrier();
+            if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); c2_pin(aSt[B_]); }
         };
         auto meet = [&]() __attribute__((always_inline)) {
             if (dead) ctl_s[8] = 1;
@@ -871,28 +934,40 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const int sg = sigP[B_];
                 const bool exch = !(GAMMA && iP == L - 1);
                 const int sak = GAMMA ? __shfl(saP[B_], qP / RPW, 64) : 0;       // every lane takes part
-                if (wave < 5) {
-                    // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state)
-                    const float* bo = own_s;
-                    float acc0 = 0.f, acc1 = 0.f;
+                // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state)
+                const float* bo = own_s + cP0;
+                float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-                    for (int c = 0; c < kC2RT; ++c) {
-                        if (c & 1) acc1 = fmaf(EPb[B_].v[c], bo[c], acc1); else acc0 = fmaf(EPb[B_].v[c], bo[c], acc0);
-                    }
-                    const float bq = rowown ? own_s[tid - g.r0] : 0.f;
-                    if (rowok && exch) {
-                        float pub = (srP[B_] == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, srP[B_] - sg);
-                        if (rowown && sbl[B_] != kShiftNone) pub += c2_scale(EB[B_] * bq, sbl[B_] - sg);
-                        xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
-                    }
-                    if (GAMMA && iP >= ph1 && rowok) {
+                for (int c = 0; c < kC2PH; ++c) {
+                    if (c & 1) acc1 = fmaf(EPb[B_].v[c], bo[c], acc1); else acc0 = fmaf(EPb[B_].v[c], bo[c], acc0);
+                }
+                const float bq = rowown ? own_s[qPr - g.r0] : 0.f;
+                float part = (srP[B_] == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, srP[B_] - sg);
+                if (rowown && sbl[B_] != kShiftNone) part += c2_scale(EB[B_] * bq, sbl[B_] - sg);
+                if (hP == 1) pacc_s[qPr] = part;                // second half of the own columns
+                const int ssp = ssP[B_];
+                float bS = 0.f;
+                if (hasS) {
+                    // straggler row: lanes over its own columns, lane nr its empty-label arc (own state only)
+                    bS = validS ? own_s[min(max(lane < g.nr ? lane : qS - g.r0, 0), kC2Own - 1)] : 0.f;
+                    const float sv = wave_sum_dpp(ES[B_] * bS);
+                    if (lane == 0) strag_s[sS] = (ssp == kShiftNone) ? 0.f : c2_scale(sv, ssp - sg);
+                }
+                c2_barrier();
+                if (tid < C && exch) {
+                    // threads 0..255 are the first halves of their rows; 256.. publish the stragglers
+                    const float pub = tid < kC2PC ? part + pacc_s[tid] : strag_s[tid - kC2PC];
+                    xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
+                }
+                if (GAMMA && iP >= ph1) {
+                    if (rowok) {
                         // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
                         const float rf = (srP[B_] == kShiftNone) ? 0.f
                             : a.scale * aP[B_] * fast_exp2((float)((double)(sak + srP[B_] + ek) - D2));
-                        float* gp = gi + (size_t)tP * fr + (size_t)qP * C + g.r0;
+                        float* gp = gi + (size_t)tP * fr + (size_t)qP * C + g.r0 + cP0;
 #pragma unroll
-                        for (int c4 = 0; c4 < kC2RT / 4; ++c4) {
-                            if (4 * c4 + 3 < g.nr && 4 * c4 >= c_lo) {
+                        for (int c4 = 0; c4 < kC2PH / 4; ++c4) {
+                            if (cP0 + 4 * c4 + 3 < g.nr && cP0 + 4 * c4 >= c_lo) {
                                 c2_f4 x;
                                 x.x = EPb[B_].v[4 * c4] * bo[4 * c4] * rf;
                                 x.y = EPb[B_].v[4 * c4 + 1] * bo[4 * c4 + 1] * rf;
@@ -902,17 +977,24 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                             } else {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (4 * c4 + e < g.nr && 4 * c4 + e >= c_lo)
+                                    if (cP0 + 4 * c4 + e < g.nr && cP0 + 4 * c4 + e >= c_lo)
                                         gp[4 * c4 + e] = EPb[B_].v[4 * c4 + e] * bo[4 * c4 + e] * rf;
                             }
                         }
-                        if (kC2RT - 1 < g.nr) gp[kC2RT - 1] = EPb[B_].v[kC2RT - 1] * bo[kC2RT - 1] * rf;
+                        if (cP0 + kC2PH - 1 < g.nr) gp[kC2PH - 1] = EPb[B_].v[kC2PH - 1] * bo[kC2PH - 1] * rf;
                         if (rowown) {
                             // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
                             const float f0 = (sbl[B_] == kShiftNone) ? 0.f
                                 : a.scale * aP[B_] * fast_exp2((float)((double)(sak + sbl[B_] + ek) - D2));
                             gp[-g.r0] = EB[B_] * bq * f0;
                         }
+                    }
+                    if (hasS) {
+                        const int sakS = __builtin_amdgcn_readlane(saP[B_], qS / RPW);
+                        const float aS = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, aSt[B_]), sS));
+                        const float rfS = (ssp == kShiftNone) ? 0.f
+                                          : a.scale * aS * fast_exp2((float)((double)(sakS + ssp + ek) - D2));
+                        buf_store(ES[B_] * bS * rfS, grs, coffS, (unsigned)tP * frb + (unsigned)qS * pitch);
                     }
                 }
                 C2_MARK(a, p, 3);
