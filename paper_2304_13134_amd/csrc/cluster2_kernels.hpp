@@ -68,8 +68,14 @@ constexpr int kC2Pacc = kC2Bl + kC2Own;             // [320] partial sums of the
 constexpr int kC2Bo = kC2Pacc + 320;                // [40] other side's own-state values (marginals)
 constexpr int kC2Ctl = kC2Bo + kC2Own;              // [32] ints
 constexpr int kC2RedB = kC2Ctl + 32;                // [32] block reductions
-constexpr int kC2Strag = kC2RedB + 32;              // [8] partial sums of the straggler columns / rows
-constexpr int kC2Lds = kC2Strag + 8;
+constexpr int kC2Strag = kC2RedB + 32;              // [8] partial sums of the straggler columns
+constexpr int kC2RowF = kC2Strag + 8;               // [40] beta F-step: row sums
+constexpr int kC2RowS = kC2RowF + kC2Own;           // [40] beta F-step: row shifts (int)
+constexpr int kC2Bt = kC2RowS + kC2Own;             // [40] beta P-step: own states times their columns' shifts
+constexpr int kC2Afull = kC2Bt + kC2Own;            // [320] beta P-step: other side's vector (marginals)
+constexpr int kC2R2S = 20;                          // row pitch of the per-lane partials
+constexpr int kC2Red2 = kC2Afull + 320;             // [264][20] beta P-step: partial sums per row and lane
+constexpr int kC2Lds = kC2Red2 + kC2Waves * kC2NQ * kC2R2S;
 
 #ifdef LAST_TRACE
 #define C2_MARK(a, p, k)                                                                    \
@@ -646,8 +652,14 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 {
     float* full_s = smem + kC2Full;
     float* own_s = smem + kC2OwnS;
-    float* red_s = smem + kC2Red;             // [40] row sums of the F-step
+    float* red_s = smem + kC2RowF;            // [40] row sums of the F-step
+    int* shr_s = (int*)(smem + kC2RowS);      // [40] their shifts
     int* shw_s = (int*)(smem + kC2Shw);
+    int* shc_s = (int*)(smem + kC2Shc);
+    float* bl_s = smem + kC2Bl;
+    float* bt_s = smem + kC2Bt;
+    float* afull_s = smem + kC2Afull;
+    float* red2_s = smem + kC2Red2;
     int* ctl_s = (int*)(smem + kC2Ctl);
     float* redb = smem + kC2RedB;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -656,23 +668,22 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns
     int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
     if (nrw < 0) nrw = 0;
-    // P-step: thread <-> row 64 (wave & 3) + lane and half hP = wave >> 2 of the own columns, whose elements
-    // it keeps in registers; straggler row 256 + sS on wave 7 - sS, lane <-> own column (lane nr: column 0)
-    float* pacc_s = smem + kC2Pacc;
-    float* strag_s = smem + kC2Strag;
-    const int hP = wave >> 2;
-    const int qPr = ((wave & 3) << 6) + lane;
-    const int qP = min(qPr, C - 1);
-    const bool rowok = qPr < C;
-    const bool rowown = rowok && hP == 0 && qPr >= g.r0 && qPr < g.r0 + g.nr;   // own state: the first half adds the empty label
-    const int c_lo = g.r0 == 0 ? 1 : 0;                               // column 0 is the empty label
-    const int cP0 = kC2PH * hP;
-    const int nst = max(C - kC2PC, 0);
-    const int sS = kC2Waves - 1 - wave;
-    const bool hasS = sS < nst;
-    const int qS = kC2PC + sS;
-    const bool ownS = qS >= g.r0 && qS < g.r0 + g.nr;
-    const bool validS = (lane >= c_lo && lane < g.nr) || (lane == g.nr && ownS);
+    // P-step (all rows x own columns), the mirror image of the other role's F-step: wave <-> rows
+    // [33 wave, 33 wave + 33), three groups of 17 lanes take every third row, a lane two neighbouring own
+    // columns (8-byte accesses).  One shift per own column; the lanes' partial sums of a row meet in LDS,
+    // where thread <-> row qT adds them up and publishes.
+    const int gq = lane / 17, ci = lane - 17 * gq;
+    const bool lact = lane < 17 * kC2FG && 2 * ci < g.nr;
+    const bool v0ok = lact && g.r0 + 2 * ci != 0;      // column 0 is the empty label
+    const bool v1ok = lact && 2 * ci + 1 < g.nr;
+    const int qF0 = kC2NQ * wave + gq;                  // first row of this lane
+    const int jlim = lact ? (C - qF0 + kC2FG - 1) / kC2FG : 0;   // rows j < jlim exist
+    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + 2 * ci;
+    const bool fok = lane < g.nr;                       // wave 0: lane <-> own state (empty-label arcs)
+    const int yF = min(g.r0 + lane, C - 1);
+    const int qT = min(tid, C - 1);
+    const bool rowok = tid < C;
+    const bool rowown = rowok && tid >= g.r0 && tid < g.r0 + g.nr;
 
     for (int b = g.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -708,23 +719,25 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         // lanes 0..4 of a wave: the wave's own rows of the F-step
         const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
-        // straggler row: own columns, then column 0
-        const unsigned coffS = validS ? (unsigned)((lane < g.nr ? g.r0 + lane : 0) * (int)sizeof(float)) : kC2Off;
-        const unsigned soffS = (unsigned)(min(kC2PC + (lane & 7), C - 1) * (int)sizeof(float));
+        const unsigned coffF = (unsigned)gq * pitch + (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
+        const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
 
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
         if (tid < kC2Own) own_s[tid] = 0.f;
         if (tid < 32) ctl_s[tid] = 0;
+        for (int q = tid; q < (kC2RedN + 1) * kC2Own; q += kC2Threads) shw_s[q] = kShiftNone;
+        if (tid < kC2Own) { bt_s[tid] = 0.f; bl_s[tid] = 0.f; }
         if (tid < g.nr) bh[(size_t)L * C + g.r0 + tid] = 1.f;
         if (tid == 0) Sb[(size_t)L * kClMaxK + g.k] = 0;
         __syncthreads();
 
         float EFb[2][kC2RW][kClNC];
-        C2Row EPb[2];
-        float EB[2] = {0.f, 0.f}, ES[2] = {0.f, 0.f}, aSt[2] = {0.f, 0.f};
+        float EQ0[2][kC2FJ], EQ1[2][kC2FJ];
+        float EB[2] = {0.f, 0.f};
         int srF[2][kC2RW];
-        int srP[2] = {0, 0}, sbl[2] = {0, 0}, sigP[2] = {0, 0}, ssP[2] = {kShiftNone, kShiftNone};
+        int sigP[2] = {0, 0};
         float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
         int saF[2] = {0, 0}, saP[2] = {0, 0};
         double D2 = 0.0;
@@ -743,9 +756,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             // block exponents: one per lane (lane & 7), picked at the point of use.  A wave-uniform
             // address would make these scalar loads, and every workgroup barrier waits for those.
             saF[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tF * (unsigned)(kClMaxK * sizeof(int))));
-            aP[B_] = buf_load(ars, (unsigned)(qP * (int)sizeof(float)), (unsigned)tP * pitch);
+            aP[B_] = buf_load(ars, (unsigned)(qT * (int)sizeof(float)), (unsigned)tP * pitch);
             saP[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tP * (unsigned)(kClMaxK * sizeof(int))));
-            if (nst > 0) aSt[B_] = buf_load(ars, soffS, (unsigned)tP * pitch);       // lanes 0..7: straggler rows
         };
         auto issueF = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -758,25 +770,16 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            {
-                const float* rp = wi + (size_t)frameP(p) * fr + (size_t)qP * C + g.r0 + cP0;
-                // full 16-byte pieces inside the own columns, then element by element
+            const unsigned foP = (unsigned)frameP(p) * frb;
+            int jl = jlim;
+            c2_pin(jl);          // the masked offsets are made where they are used, not kept in registers
 #pragma unroll
-                for (int c4 = 0; c4 < kC2PH / 4; ++c4) {
-                    if (cP0 + 4 * c4 + 3 < g.nr) {
-                        const c2_f4 x = *(const c2_f4*)(rp + 4 * c4);
-                        EPb[B_].v[4 * c4] = x.x; EPb[B_].v[4 * c4 + 1] = x.y;
-                        EPb[B_].v[4 * c4 + 2] = x.z; EPb[B_].v[4 * c4 + 3] = x.w;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            EPb[B_].v[4 * c4 + e] = (cP0 + 4 * c4 + e < g.nr) ? rp[4 * c4 + e] : LAST_NEG_INF;
-                    }
-                }
-                EPb[B_].v[kC2PH - 1] = (cP0 + kC2PH - 1 < g.nr) ? rp[kC2PH - 1] : LAST_NEG_INF;
-                if (hP == 0) EB[B_] = rp[-g.r0];                      // w[q][0]
+            for (int j = 0; j < kC2FJ; ++j) {
+                const float2 x = buf_load2(wrs, j < jl ? coffF : kC2Off, foP + rowF0 + (unsigned)(kC2FG * j) * pitch);
+                EQ0[B_][j] = x.x;
+                EQ1[B_][j] = x.y;
             }
-            if (hasS) ES[B_] = buf_load(wrs, coffS, (unsigned)frameP(p) * frb + (unsigned)qS * pitch);
+            if (wave == 0 && lane < kC2Own) EB[B_] = buf_load(wrs, rowB, foP);      // w[q][0] of the own states
         };
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
@@ -797,42 +800,49 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 for (int j = 0; j < kClNC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
             }
             halfway();
-            // P frame: one shift per row and half = per thread, over its own label columns
-            int sp = kShiftNone, sb = kShiftNone;
-            {
-                float mx = LAST_NEG_INF;
+            // P frame: one shift per own column, common to all waves and row groups; the empty-label weight
+            // of an own state q shares the shift of the column of q, whose value it multiplies
+            float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
 #pragma unroll
-                for (int c = 0; c < kC2PH; ++c) {
-                    if (cP0 + c < c_lo || cP0 + c >= g.nr || !rowok) EPb[B_].v[c] = LAST_NEG_INF;
-                    mx = fmaxf(mx, EPb[B_].v[c]);
-                }
-                sp = shift_for(mx);
-                const float fs = (float)sp;
-#pragma unroll
-                for (int c = 0; c < kC2PH; ++c) { EPb[B_].v[c] = fast_exp2(fmaf(EPb[B_].v[c], kLog2e, -fs)); c2_pin(EPb[B_].v[c]); }
-                // empty-label weight of an own state, with its own shift
-                sb = shift_for(rowown ? EB[B_] : LAST_NEG_INF);
-                EB[B_] = rowown ? fast_exp2(fmaf(EB[B_], kLog2e, -(float)sb)) : 0.f;
-                c2_pin(EB[B_]);
+            for (int j = 0; j < kC2FJ; ++j) {
+                if (j >= jlim || !v0ok) EQ0[B_][j] = LAST_NEG_INF;
+                if (j >= jlim || !v1ok) EQ1[B_][j] = LAST_NEG_INF;
+                m0 = fmaxf(m0, EQ0[B_][j]);
+                m1 = fmaxf(m1, EQ1[B_][j]);
             }
-            srP[B_] = sp; sbl[B_] = sb;
-            int wm = wave_max_dpp(max(sp, sb));
-            int ssp = kShiftNone;
-            if (hasS) {
-                const float e = validS ? ES[B_] : LAST_NEG_INF;
-                ssp = shift_for(wave_max_dpp(e));
-                ES[B_] = fast_exp2(fmaf(e, kLog2e, -(float)ssp));
-                c2_pin(ES[B_]);
-                wm = max(wm, ssp);
+            if (lane < 17 * kC2FG) {
+                int2 sw;
+                sw.x = shift_for(m0); sw.y = shift_for(m1);
+                *(int2*)&shw_s[slotF] = sw;
             }
-            ssP[B_] = ssp;
-            if (lane == 0) ctl_s[16 + wave] = wm;
+            if (wave == 0 && lane < kC2Own) {
+                if (!fok) EB[B_] = LAST_NEG_INF;
+                shw_s[kC2RedN * kC2Own + lane] = shift_for(EB[B_]);
+            }
             c2_barrier();
-            int sg = kShiftNone;
+            if (wave == 0) {
+                int sc = kShiftNone;
+                if (lane < kC2Own) {
 #pragma unroll
-            for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
-            sigP[B_] = sg;
-            if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); c2_pin(aSt[B_]); }
+                    for (int x = 0; x <= kC2RedN; ++x) sc = max(sc, shw_s[x * kC2Own + lane]);
+                    shc_s[B_ * kC2Own + lane] = sc;
+                }
+                const int sg = wave_max_dpp(fok ? sc : kShiftNone);
+                if (lane == 0) ctl_s[2 + B_] = sg;
+            }
+            c2_barrier();
+            const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
+            const float fs0 = (float)sc2.x, fs1 = (float)sc2.y;
+#pragma unroll
+            for (int j = 0; j < kC2FJ; ++j) {
+                EQ0[B_][j] = fast_exp2(fmaf(EQ0[B_][j], kLog2e, -fs0));
+                EQ1[B_][j] = fast_exp2(fmaf(EQ1[B_][j], kLog2e, -fs1));
+                c2_pin(EQ0[B_][j]); c2_pin(EQ1[B_][j]);
+            }
+            if (wave == 0) EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)shc_s[B_ * kC2Own + min(lane, kC2Own - 1)]));
+            c2_pin(EB[B_]);
+            sigP[B_] = ctl_s[2 + B_];
+            if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); }
         };
         auto meet = [&]() __attribute__((always_inline)) {
             if (dead) ctl_s[8] = 1;
@@ -882,7 +892,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     const float tot = wave_sum_dpp(acc);
                     if (lane == 0 && ri < nrw) {
                         red_s[rloc] = tot;
-                        shw_s[rloc] = srF[B_][ri];
+                        shr_s[rloc] = srF[B_][ri];
                     }
                     if (GAMMA && iF >= ph1 && ri < nrw) {
                         const float arow = __shfl(aF[B_], ri, 64);
@@ -901,10 +911,14 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 if (wave == 0) {
                     const bool ok = lane < g.nr;
                     const float v = ok ? red_s[lane] : 0.f;
-                    const int sc = (ok && v > 0.f) ? shw_s[lane] + float_exponent(v) : kShiftNone;
+                    const int sc = (ok && v > 0.f) ? shr_s[lane] + float_exponent(v) : kShiftNone;
                     const int ms = wave_max_dpp(sc);
-                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shw_s[lane] - ms);
-                    if (lane < kC2Own) own_s[lane] = own;
+                    const float own = (sc == kShiftNone) ? 0.f : c2_scale(v, shr_s[lane] - ms);
+                    if (lane < kC2Own) {
+                        own_s[lane] = own;
+                        // for the P-step: own states times 2^(shift of their column - largest shift)
+                        bt_s[lane] = c2_scale(own, shc_s[B_ * kC2Own + lane] - sigP[B_]);
+                    }
                     const int ek = (ms == kShiftNone) ? S : S + ms;
                     if (lane == 0) ctl_s[1] = ek;
                     if (tF >= mid) {
@@ -933,68 +947,60 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const int ek = ctl_s[1];
                 const int sg = sigP[B_];
                 const bool exch = !(GAMMA && iP == L - 1);
-                const int sak = GAMMA ? __shfl(saP[B_], qP / RPW, 64) : 0;       // every lane takes part
-                // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state)
-                const float* bo = own_s + cP0;
-                float acc0 = 0.f, acc1 = 0.f;
+                C2_MARK(a, p, 6);
+                // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state):
+                // every lane its two columns of its eleven rows, then thread <-> row over the lanes' parts
+                {
+                    const float2 bt = *(const float2*)&bt_s[2 * ci];
 #pragma unroll
-                for (int c = 0; c < kC2PH; ++c) {
-                    if (c & 1) acc1 = fmaf(EPb[B_].v[c], bo[c], acc1); else acc0 = fmaf(EPb[B_].v[c], bo[c], acc0);
+                    for (int j = 0; j < kC2FJ; ++j) {
+                        const float pj = fmaf(EQ0[B_][j], bt.x, EQ1[B_][j] * bt.y);
+                        if (lane < 17 * kC2FG) red2_s[(qF0 + kC2FG * j) * kC2R2S + ci] = pj;
+                    }
+                    if (wave == 0 && lane < kC2Own) bl_s[lane] = EB[B_] * bt_s[lane];
                 }
-                const float bq = rowown ? own_s[qPr - g.r0] : 0.f;
-                float part = (srP[B_] == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, srP[B_] - sg);
-                if (rowown && sbl[B_] != kShiftNone) part += c2_scale(EB[B_] * bq, sbl[B_] - sg);
-                if (hP == 1) pacc_s[qPr] = part;                // second half of the own columns
-                const int ssp = ssP[B_];
-                float bS = 0.f;
-                if (hasS) {
-                    // straggler row: lanes over its own columns, lane nr its empty-label arc (own state only)
-                    bS = validS ? own_s[min(max(lane < g.nr ? lane : qS - g.r0, 0), kC2Own - 1)] : 0.f;
-                    const float sv = wave_sum_dpp(ES[B_] * bS);
-                    if (lane == 0) strag_s[sS] = (ssp == kShiftNone) ? 0.f : c2_scale(sv, ssp - sg);
+                int samax = 0;
+                if (GAMMA && iP >= ph1) {
+                    // the other side's vector for the marginals, all blocks on the largest block exponent
+                    const int sak = __shfl(saP[B_], qT / RPW, 64);
+                    samax = wave_max_dpp(lane < K ? saP[B_] : -(1 << 30));
+                    if (tid < 320) afull_s[tid] = rowok ? c2_scale(aP[B_], sak - samax) : 0.f;
                 }
                 c2_barrier();
-                if (tid < C && exch) {
-                    // threads 0..255 are the first halves of their rows; 256.. publish the stragglers
-                    const float pub = tid < kC2PC ? part + pacc_s[tid] : strag_s[tid - kC2PC];
+                C2_MARK(a, p, 7);
+                if (rowok && exch) {
+                    const float4* rp4 = (const float4*)&red2_s[tid * kC2R2S];
+                    const float4 x0 = rp4[0], x1 = rp4[1], x2 = rp4[2], x3 = rp4[3];
+                    float pub = ((x0.x + x0.y) + (x0.z + x0.w)) + ((x1.x + x1.y) + (x1.z + x1.w)) +
+                                ((x2.x + x2.y) + (x2.z + x2.w)) + ((x3.x + x3.y) + (x3.z + x3.w)) +
+                                red2_s[tid * kC2R2S + 16];
+                    if (rowown) pub += bl_s[tid - g.r0];
                     xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
                 if (GAMMA && iP >= ph1) {
-                    if (rowok) {
-                        // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
-                        const float rf = (srP[B_] == kShiftNone) ? 0.f
-                            : a.scale * aP[B_] * fast_exp2((float)((double)(sak + srP[B_] + ek) - D2));
-                        float* gp = gi + (size_t)tP * fr + (size_t)qP * C + g.r0 + cP0;
+                    // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
+                    const unsigned gso = (unsigned)tP * frb;
+                    const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
+                    const float f0 = a.scale * own_s[2 * ci] * fast_exp2((float)((double)(sc2.x + ek + samax) - D2));
+                    const float f1 = a.scale * own_s[2 * ci + 1] * fast_exp2((float)((double)(sc2.y + ek + samax) - D2));
+                    const unsigned off2 = (v0ok && v1ok) ? coffF : kC2Off;
+                    const unsigned off1 = (v0ok == v1ok) ? kC2Off : (v0ok ? coffF : coffF + 4u);
+                    int jl = jlim;
+                    c2_pin(jl);
 #pragma unroll
-                        for (int c4 = 0; c4 < kC2PH / 4; ++c4) {
-                            if (cP0 + 4 * c4 + 3 < g.nr && cP0 + 4 * c4 >= c_lo) {
-                                c2_f4 x;
-                                x.x = EPb[B_].v[4 * c4] * bo[4 * c4] * rf;
-                                x.y = EPb[B_].v[4 * c4 + 1] * bo[4 * c4 + 1] * rf;
-                                x.z = EPb[B_].v[4 * c4 + 2] * bo[4 * c4 + 2] * rf;
-                                x.w = EPb[B_].v[4 * c4 + 3] * bo[4 * c4 + 3] * rf;
-                                *(c2_f4*)(gp + 4 * c4) = x;
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    if (cP0 + 4 * c4 + e < g.nr && cP0 + 4 * c4 + e >= c_lo)
-                                        gp[4 * c4 + e] = EPb[B_].v[4 * c4 + e] * bo[4 * c4 + e] * rf;
-                            }
-                        }
-                        if (cP0 + kC2PH - 1 < g.nr) gp[kC2PH - 1] = EPb[B_].v[kC2PH - 1] * bo[kC2PH - 1] * rf;
-                        if (rowown) {
-                            // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
-                            const float f0 = (sbl[B_] == kShiftNone) ? 0.f
-                                : a.scale * aP[B_] * fast_exp2((float)((double)(sak + sbl[B_] + ek) - D2));
-                            gp[-g.r0] = EB[B_] * bq * f0;
-                        }
+                    for (int j = 0; j < kC2FJ; ++j) {
+                        const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
+                        const float aq = afull_s[min(qF0 + kC2FG * j, 319)];
+                        const float g0 = aq * EQ0[B_][j] * f0, g1 = aq * EQ1[B_][j] * f1;
+                        buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
+                        buf_store(v0ok ? g0 : g1, grs, j < jl ? off1 : kC2Off, so);
+                        __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                     }
-                    if (hasS) {
-                        const int sakS = __builtin_amdgcn_readlane(saP[B_], qS / RPW);
-                        const float aS = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, aSt[B_]), sS));
-                        const float rfS = (ssp == kShiftNone) ? 0.f
-                                          : a.scale * aS * fast_exp2((float)((double)(sakS + ssp + ek) - D2));
-                        buf_store(ES[B_] * bS * rfS, grs, coffS, (unsigned)tP * frb + (unsigned)qS * pitch);
+                    if (wave == 0 && fok) {
+                        // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
+                        const float fb = a.scale * own_s[lane] *
+                                         fast_exp2((float)((double)(shc_s[B_ * kC2Own + lane] + ek + samax) - D2));
+                        buf_store(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
                     }
                 }
                 C2_MARK(a, p, 3);
