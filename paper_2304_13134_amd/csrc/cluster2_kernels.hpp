@@ -282,11 +282,26 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         const unsigned coffS = lane < g.nr ? (unsigned)lane * pitch + (unsigned)(cS * (int)sizeof(float)) : kC2Off;
         const unsigned soffS = (unsigned)(min(kC2PC + (lane & 7), C - 1) * (int)sizeof(float));
         const unsigned rbaseP = (unsigned)g.r0 * pitch;
-        const unsigned coffF = (unsigned)gq * pitch + (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned colF = (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned coffF = (unsigned)gq * pitch + colF;
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
         const int nlast = max(n - 1, 0);
 
+        // Offset of this lane's element pair in row j of its rows.  A row beyond the matrix is replaced by
+        // the last row: what is loaded there is finite, takes part in no maximum that matters and meets a
+        // zero of the state vector in every sum, so the exp pass needs no mask per element.  A lane without
+        // columns of its own repeats the address of a lane that has some (no traffic of its own); its
+        // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
+        // see through, so that the offsets are made where they are used instead of being kept.)
+        const int gqa = min(gq, kC2FG - 1), cia = min(gq < kC2FG ? ci : 16, max(g.nr - 1, 0) / 2);
+        const unsigned cola = (unsigned)((g.r0 + 2 * cia) * (int)sizeof(float));
+        const unsigned offA0 = (unsigned)(kC2NQ * wave + gqa) * pitch + cola;
+        const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
+        const int jla = max((C - (kC2NQ * wave + gqa) + kC2FG - 1) / kC2FG, 0);
+        auto rowcol = [&](int j, int jl) __attribute__((always_inline)) {
+            return j < jl ? offA0 + (unsigned)(kC2FG * j) * pitch : offAL;
+        };
         // a_0 = unit vector at the start state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q == 0 ? 1.f : 0.f;
         if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; bo_s[tid] = 0.f; }
@@ -315,7 +330,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const int tF = min(2 * p, nlast), tP = min(2 * p + 1, nlast);
             // (32-bit offsets into buffer descriptors: 64-bit addresses per lane would cost the registers
             // this kernel does not have; a column beyond the row reads a neighbour or zero and is unused)
-            const float2 bf = buf_load2(brs, coffF - (unsigned)gq * pitch, (unsigned)(tF + 1) * pitch);
+            const float2 bf = buf_load2(brs, colF, (unsigned)(tF + 1) * pitch);
             bF0[B_] = bf.x; bF1[B_] = bf.y;
             bFb[B_] = buf_load(brs, yoff, (unsigned)(tF + 1) * pitch);
             // block exponents: one per lane (lane & 7), picked at the point of use.  A wave-uniform
@@ -335,12 +350,12 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         auto issueF = [&](auto BUF, int p, int j0, int j1) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foF = (unsigned)min(2 * p, nlast) * frb;
-            int jl = jlim;
-            c2_pin(jl);          // the masked offsets are made where they are used, not kept in registers
+            int jl = jla;
+            c2_pin(jl);
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j)
                 if (j >= j0 && j < j1) {
-                    const float2 x = buf_load2(wrs, j < jl ? coffF : kC2Off, foF + rowF0 + (unsigned)(kC2FG * j) * pitch);
+                    const float2 x = buf_load2(wrs, rowcol(j, jl), foF);
                     EF0[B_][j] = x.x;
                     EF1[B_][j] = x.y;
                 }
@@ -353,7 +368,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 #pragma unroll
             for (int r = 0; r < kC2PH; ++r)
                 if (r >= r0_ && r < r1_)
-                    EP[B_][r] = buf_load(wrs, rP0 + r < g.nr ? coffPm : kC2Off, foP + rbaseP + (unsigned)(rP0 + r) * pitch);
+                    EP[B_][r] = buf_load(wrs, coffPm, foP + rbaseP + (unsigned)min(rP0 + r, g.nr - 1) * pitch);
             if (r1_ >= kC2PH && hasS) ES[B_] = buf_load(wrs, coffS, foP + rbaseP);
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
@@ -363,14 +378,12 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
-                if (j >= jlim || !v0ok) EF0[B_][j] = LAST_NEG_INF;
-                if (j >= jlim || !v1ok) EF1[B_][j] = LAST_NEG_INF;
                 m0 = fmaxf(m0, EF0[B_][j]);
                 m1 = fmaxf(m1, EF1[B_][j]);
             }
             if (lane < 17 * kC2FG) {
                 int2 sw;
-                sw.x = shift_for(m0); sw.y = shift_for(m1);
+                sw.x = shift_for(v0ok ? m0 : LAST_NEG_INF); sw.y = shift_for(v1ok ? m1 : LAST_NEG_INF);
                 *(int2*)&shw_s[slotF] = sw;
             }
             if (wave == 0 && lane < kC2Own) {
@@ -380,10 +393,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             // P frame: one shift per column and thread, the workgroup's largest as reference
             float mp = LAST_NEG_INF;
 #pragma unroll
-            for (int r = 0; r < kC2PH; ++r) {
-                if (rP0 + r >= g.nr) EP[B_][r] = LAST_NEG_INF;       // (the same for the whole wave)
-                mp = fmaxf(mp, EP[B_][r]);
-            }
+            // (a row beyond the own rows was loaded as a copy of the last one and meets a zero in the sums)
+            for (int r = 0; r < kC2PH; ++r) mp = fmaxf(mp, EP[B_][r]);
             const int sp = colok ? shift_for(mp) : kShiftNone;
             int wm = wave_max_dpp(sp);
             int ssp = kShiftNone;
@@ -416,7 +427,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             for (int r = 0; r < kC2PH; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
             c2_barrier();
             const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
-            const float fs0 = (float)sc2.x, fs1 = (float)sc2.y;
+            // (a column this lane does not have: a huge shift makes its E zero)
+            const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
+            const float fs1 = v1ok && sc2.y != kShiftNone ? (float)sc2.y : 3.0e38f;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
                 EF0[B_][j] = fast_exp2(fmaf(EF0[B_][j], kLog2e, -fs0));
@@ -709,6 +722,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         auto coffj = [&](int j) __attribute__((always_inline)) {
             return lane + 64 * j < C ? coff0 + 256u * (unsigned)j : kC2Off;
         };
+        // loads: a column beyond the row is replaced by the last one, which leaves the row's maximum alone
+        // and meets a zero of the state vector in the sum, so the exp pass needs no mask
+        auto coffl = [&](int j) __attribute__((always_inline)) {
+            return (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
+        };
         auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
             return (unsigned)(g.r0 + min(wave + ri * kC2Waves, g.nr - 1)) * pitch;
         };
@@ -719,10 +737,25 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         // lanes 0..4 of a wave: the wave's own rows of the F-step
         const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
-        const unsigned coffF = (unsigned)gq * pitch + (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned colF = (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned coffF = (unsigned)gq * pitch + colF;
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
 
+        // Offset of this lane's element pair in row j of its rows.  A row beyond the matrix is replaced by
+        // the last row: what is loaded there is finite, takes part in no maximum that matters and meets a
+        // zero of the state vector in every sum, so the exp pass needs no mask per element.  A lane without
+        // columns of its own repeats the address of a lane that has some (no traffic of its own); its
+        // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
+        // see through, so that the offsets are made where they are used instead of being kept.)
+        const int gqa = min(gq, kC2FG - 1), cia = min(gq < kC2FG ? ci : 16, max(g.nr - 1, 0) / 2);
+        const unsigned cola = (unsigned)((g.r0 + 2 * cia) * (int)sizeof(float));
+        const unsigned offA0 = (unsigned)(kC2NQ * wave + gqa) * pitch + cola;
+        const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
+        const int jla = max((C - (kC2NQ * wave + gqa) + kC2FG - 1) / kC2FG, 0);
+        auto rowcol = [&](int j, int jl) __attribute__((always_inline)) {
+            return j < jl ? offA0 + (unsigned)(kC2FG * j) * pitch : offAL;
+        };
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
         if (tid < kC2Own) own_s[tid] = 0.f;
@@ -765,17 +798,17 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri)
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffj(j), foF + roff(ri));
+                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffl(j), foF + roff(ri));
             if (GAMMA) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foP = (unsigned)frameP(p) * frb;
-            int jl = jlim;
-            c2_pin(jl);          // the masked offsets are made where they are used, not kept in registers
+            int jl = jla;
+            c2_pin(jl);
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
-                const float2 x = buf_load2(wrs, j < jl ? coffF : kC2Off, foP + rowF0 + (unsigned)(kC2FG * j) * pitch);
+                const float2 x = buf_load2(wrs, rowcol(j, jl), foP);
                 EQ0[B_][j] = x.x;
                 EQ1[B_][j] = x.y;
             }
@@ -788,10 +821,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             for (int ri = 0; ri < kC2RW; ++ri) {
                 float mx = LAST_NEG_INF;
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) {
-                    if (lane + 64 * j >= C) EFb[B_][ri][j] = LAST_NEG_INF;
-                    mx = fmaxf(mx, EFb[B_][ri][j]);
-                }
+                for (int j = 0; j < kClNC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
                 mx = wave_max_dpp(mx);
                 const int s = shift_for(mx);
                 srF[B_][ri] = s;
@@ -805,14 +835,12 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
-                if (j >= jlim || !v0ok) EQ0[B_][j] = LAST_NEG_INF;
-                if (j >= jlim || !v1ok) EQ1[B_][j] = LAST_NEG_INF;
                 m0 = fmaxf(m0, EQ0[B_][j]);
                 m1 = fmaxf(m1, EQ1[B_][j]);
             }
             if (lane < 17 * kC2FG) {
                 int2 sw;
-                sw.x = shift_for(m0); sw.y = shift_for(m1);
+                sw.x = shift_for(v0ok ? m0 : LAST_NEG_INF); sw.y = shift_for(v1ok ? m1 : LAST_NEG_INF);
                 *(int2*)&shw_s[slotF] = sw;
             }
             if (wave == 0 && lane < kC2Own) {
@@ -832,7 +860,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             }
             c2_barrier();
             const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
-            const float fs0 = (float)sc2.x, fs1 = (float)sc2.y;
+            // (a column this lane does not have: a huge shift makes its E zero)
+            const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
+            const float fs1 = v1ok && sc2.y != kShiftNone ? (float)sc2.y : 3.0e38f;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
                 EQ0[B_][j] = fast_exp2(fmaf(EQ0[B_][j], kLog2e, -fs0));
