@@ -165,9 +165,9 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     p.XSB = kClMaxC;                         // 11 waves x 24 words
     p.grid = 8 * p.ncl * 2 * p.K;
     p.ok = true;
-    // the second-generation kernel (one exchange per two frames) is opt-in while it is being tuned
+    // the second-generation kernel (one exchange per two frames) unless LAST_CLUSTER_V2=0 asks for the first
     const char* v2 = std::getenv("LAST_CLUSTER_V2");
-    p.v2 = v2 && v2[0] == '1' && s.C <= kC2Hdr;
+    p.v2 = !(v2 && v2[0] == '0') && s.C <= kC2Hdr;
     return p;
 }
 

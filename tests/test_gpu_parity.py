@@ -99,6 +99,26 @@ def test_ragged_vocabulary_sizes():
         check_path(cfg)
 
 
+def test_state_counts_around_256_and_every_pair_parity():
+    # the clustered kernels give columns and rows beyond 256 to the last wave's tail, walk frames in
+    # pairs from either end and meet in the middle: cover the sizes and the lengths around those edges
+    for V in (254, 255, 256, 257, 263, 264):
+        announce("clustered path, V", V)
+        cfg = workloads.dense(B=6, T=9, V=V, order=1, sigma=2.0, seed=300 + V, len_lo=1, len_hi=9)
+        cfg["lengths"] = np.array([1, 2, 3, 4, 8, 9], dtype=np.int32)
+        check_posteriors(cfg)
+
+
+def test_first_generation_clustered_kernel(monkeypatch):
+    # LAST_CLUSTER_V2=0 selects the kernel with one exchange per frame; it stays covered
+    monkeypatch.setenv("LAST_CLUSTER_V2", "0")
+    announce("first-generation clustered kernel: B=3 T=40 V=256")
+    check_posteriors(workloads.config(2, B=3, T=40))
+    for V in (65, 130, 263):
+        cfg = workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9)
+        check_posteriors(cfg)
+
+
 def test_edge_lengths_and_status():
     announce("edge lengths: 0, 1, T, invalid")
     cfg = workloads.dense(B=5, T=6, V=5, order=1, seed=5)
