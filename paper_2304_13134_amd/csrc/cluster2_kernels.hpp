@@ -588,7 +588,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 }
                 if (GAMMA && wave == 0) {
                     const int dk = __builtin_amdgcn_readlane(sbP[B_], g.k) - __builtin_amdgcn_readlane(sbP[B_], 0);
-                    if (lane < kC2Own) bo_s[lane] = lane < g.nr ? c2_scale(boP[B_], dk) : 0.f;
+                    // own state times the other side's value of the same state: what the empty-label arcs
+                    // (column 0) are multiplied with in place of the own state alone
+                    if (lane < kC2Own) bo_s[lane] = lane < g.nr ? own_s[lane] * c2_scale(boP[B_], dk) : 0.f;
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
@@ -605,13 +607,16 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     {
                         const float kx = (float)((double)(sbk + sp + ek) - D2);
                         const float fy = (sp == kShiftNone) ? 0.f : a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
+                        // the empty label (column 0) returns to the row's own state: its thread reads the
+                        // products instead of the own states; all reads first, then the stores
+                        const float* osrc = (cP == 0 ? bo_s : own_s) + rP0;
+                        float ov[kC2PH];
 #pragma unroll
-                        for (int r = 0; r < kC2PH; ++r) {
-                            // the empty label (column 0) returns to the row's own state
-                            const float f2 = (cP == 0) ? fy * bo_s[rP0 + r] : fy;
-                            buf_store(own_s[rP0 + r] * EP[B_][r] * f2, grs, rP0 + r < g.nr ? coffPm : kC2Off,
+                        for (int r = 0; r < kC2PH; ++r) ov[r] = osrc[r];
+#pragma unroll
+                        for (int r = 0; r < kC2PH; ++r)
+                            buf_store(ov[r] * EP[B_][r] * fy, grs, rP0 + r < g.nr ? coffPm : kC2Off,
                                       gso + (unsigned)(rP0 + r) * pitch);
-                        }
                     }
                     if (hasS) {
                         const int sbkS = __builtin_amdgcn_readlane(sbP[B_], cS / RPW);
@@ -1017,11 +1022,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     const unsigned off1 = (v0ok == v1ok) ? kC2Off : (v0ok ? coffF : coffF + 4u);
                     int jl = jlim;
                     c2_pin(jl);
+                    float aq[kC2FJ];
+#pragma unroll
+                    for (int j = 0; j < kC2FJ; ++j) aq[j] = afull_s[min(qF0 + kC2FG * j, 319)];
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) {
                         const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
-                        const float aq = afull_s[min(qF0 + kC2FG * j, 319)];
-                        const float g0 = aq * EQ0[B_][j] * f0, g1 = aq * EQ1[B_][j] * f1;
+                        const float g0 = aq[j] * EQ0[B_][j] * f0, g1 = aq[j] * EQ1[B_][j] * f1;
                         buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
                         buf_store(v0ok ? g0 : g1, grs, j < jl ? off1 : kC2Off, so);
                         __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
