@@ -47,6 +47,7 @@ constexpr int kC2FJ = 11;      // alpha F-step: rows per lane, kC2FG * kC2FJ = k
 constexpr int kC2Hdr = 264;    // exchange row: C values, the producer's exponent at [kC2Hdr]
 constexpr int kC2XS = 272;     // words per producer and slot
 constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
+constexpr int kC2NC = 4;       // ... in chunks of 64 columns; columns beyond 256 by one more instruction (see beta F-step)
 constexpr int kC2RT = 33;      // own rows (alpha) or own columns (beta) of a workgroup in the P-step
 constexpr int kC2PH = 17;      // ... of which a thread takes one half: [0, 17) or [17, 33)
 constexpr int kC2PC = 256;     // columns (alpha) or rows (beta) that have a thread per half; the few beyond
@@ -305,8 +306,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         // a_0 = unit vector at the start state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q == 0 ? 1.f : 0.f;
         if (tid < kC2Own) { own_s[tid] = 0.f; bl_s[tid] = 0.f; bo_s[tid] = 0.f; }
-        if (tid < 32) ctl_s[tid] = 0;
-        for (int q = tid; q < (kC2RedN + 1) * kC2Own; q += kC2Threads) shw_s[q] = kShiftNone;
+        if (tid < 32) ctl_s[tid] = (tid == 2 || tid == 3) ? kShiftNone : 0;
+        if (tid < 2 * kC2Own) shc_s[tid] = kShiftNone;
         for (int q = tid; q < kC2RedN * kC2Own; q += kC2Threads) red_s[q] = 0.f;
         if (tid < g.nr) ah[g.r0 + tid] = (g.r0 + tid == 0) ? 1.f : 0.f;
         if (tid == 0) Sa[g.k] = 0;
@@ -381,14 +382,14 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 m0 = fmaxf(m0, EF0[B_][j]);
                 m1 = fmaxf(m1, EF1[B_][j]);
             }
+            // (maxima of integers through LDS atomics: the order does not matter, one barrier is enough)
             if (lane < 17 * kC2FG) {
-                int2 sw;
-                sw.x = shift_for(v0ok ? m0 : LAST_NEG_INF); sw.y = shift_for(v1ok ? m1 : LAST_NEG_INF);
-                *(int2*)&shw_s[slotF] = sw;
+                atomicMax(&shc_s[B_ * kC2Own + 2 * ci], shift_for(v0ok ? m0 : LAST_NEG_INF));
+                atomicMax(&shc_s[B_ * kC2Own + 2 * ci + 1], shift_for(v1ok ? m1 : LAST_NEG_INF));
             }
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
-                shw_s[kC2RedN * kC2Own + lane] = shift_for(EB[B_]);
+                atomicMax(&shc_s[B_ * kC2Own + lane], shift_for(EB[B_]));
             }
             // P frame: one shift per column and thread, the workgroup's largest as reference
             float mp = LAST_NEG_INF;
@@ -405,27 +406,16 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 c2_pin(ES[B_]);
                 wm = max(wm, ssp);
             }
-            if (lane == 0) ctl_s[16 + wave] = wm;
+            if (lane == 0) atomicMax(&ctl_s[2 + B_], wm);
             c2_barrier();
+            // every wave is past the pair that is ending: its cells are cleared for the pass after this one
+            if (wave == 1 && lane < kC2Own) shc_s[(B_ ^ 1) * kC2Own + lane] = kShiftNone;
+            if (wave == 1 && lane == 0) ctl_s[2 + (B_ ^ 1)] = kShiftNone;
             halfway();
-            if (wave == 0) {
-                if (lane < kC2Own) {
-                    int sc = kShiftNone;
-#pragma unroll
-                    for (int x = 0; x <= kC2RedN; ++x) sc = max(sc, shw_s[x * kC2Own + lane]);
-                    shc_s[B_ * kC2Own + lane] = sc;
-                }
-                int sg = kShiftNone;
-#pragma unroll
-                for (int w2 = 0; w2 < kC2Waves; ++w2) sg = max(sg, ctl_s[16 + w2]);
-                if (lane == 0) ctl_s[2 + B_] = sg;
-            }
-            // the P frame does not depend on the shifts the other waves are waiting for
             // (a lane without a column loaded zeros: a huge shift turns them into E = 0)
             const float fsp = sp == kShiftNone ? 3.0e38f : (float)sp;
 #pragma unroll
             for (int r = 0; r < kC2PH; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
-            c2_barrier();
             const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
             // (a column this lane does not have: a huge shift makes its E zero)
             const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
@@ -683,9 +673,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int C = a.C, K = a.K, RPW = a.RPW;
-    // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns
+    // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns 0..255 in four chunks; the columns
+    // beyond (at most 8) of all rows of the wave by one more instruction: lane <-> (row lane & 7, column 256 + (lane >> 3))
     int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
     if (nrw < 0) nrw = 0;
+    const int nstF = max(C - kC2PC, 0);
+    const int rS = lane & 7, sI = lane >> 3;
+    const bool validS = rS < nrw && rS < kC2RW && sI < nstF;
     // P-step (all rows x own columns), the mirror image of the other role's F-step: wave <-> rows
     // [33 wave, 33 wave + 33), three groups of 17 lanes take every third row, a lane two neighbouring own
     // columns (8-byte accesses).  One shift per own column; the lanes' partial sums of a row meet in LDS,
@@ -742,6 +736,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned koff = (unsigned)((lane & 7) * (int)sizeof(int));
         // lanes 0..4 of a wave: the wave's own rows of the F-step
         const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
+        const unsigned offSt = validS ? (unsigned)(g.r0 + wave + rS * kC2Waves) * pitch + (unsigned)((kC2PC + sI) * (int)sizeof(float))
+                                      : kC2Off;
         const unsigned colF = (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
         const unsigned coffF = (unsigned)gq * pitch + colF;
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
@@ -765,22 +761,22 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
         if (tid < kC2Own) own_s[tid] = 0.f;
         if (tid < 32) ctl_s[tid] = 0;
-        for (int q = tid; q < (kC2RedN + 1) * kC2Own; q += kC2Threads) shw_s[q] = kShiftNone;
+        if (tid < 2 * kC2Own) shc_s[tid] = kShiftNone;
         if (tid < kC2Own) { bt_s[tid] = 0.f; bl_s[tid] = 0.f; }
         if (tid < g.nr) bh[(size_t)L * C + g.r0 + tid] = 1.f;
         if (tid == 0) Sb[(size_t)L * kClMaxK + g.k] = 0;
         __syncthreads();
 
-        float EFb[2][kC2RW][kClNC];
+        float EFb[2][kC2RW][kC2NC], ESb[2] = {0.f, 0.f};
         float EQ0[2][kC2FJ], EQ1[2][kC2FJ];
         float EB[2] = {0.f, 0.f};
         int srF[2][kC2RW];
-        int sigP[2] = {0, 0};
         float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
         int saF[2] = {0, 0}, saP[2] = {0, 0};
         double D2 = 0.0;
         int dead = 0;
         bool met = false;
+        int p = 0;                // pair counter
 
         // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
         auto frameF = [&](int p) { return max(L - 1 - min(2 * p, nlast), 0); };
@@ -802,8 +798,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             const unsigned foF = (unsigned)frameF(p) * frb;
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri)
+                if (ri < nrw) {
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffl(j), foF + roff(ri));
+                    for (int j = 0; j < kC2NC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffl(j), foF + roff(ri));
+                }
+            if (nstF > 0) ESb[B_] = buf_load(wrs, offSt, foF);
             if (GAMMA) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
@@ -822,18 +821,29 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             // F frame: one shift per own row (wave-uniform)
+            float fsS = 3.0e38f;       // shift of the row of this lane's straggler element
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri) {
-                float mx = LAST_NEG_INF;
+                if (ri < nrw) {
+                    float mx = (validS && rS == ri) ? ESb[B_] : LAST_NEG_INF;
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
-                mx = wave_max_dpp(mx);
-                const int s = shift_for(mx);
-                srF[B_][ri] = s;
-                const float fs = (float)s;
+                    for (int j = 0; j < kC2NC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
+                    mx = wave_max_dpp(mx);
+                    const int s = shift_for(mx);
+                    srF[B_][ri] = s;
+                    const float fs = (float)s;
+                    if (rS == ri) fsS = fs;
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
+                    for (int j = 0; j < kC2NC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
+                } else {
+                    srF[B_][ri] = kShiftNone;
+                }
             }
+            if (nstF > 0) {
+                ESb[B_] = validS ? fast_exp2(fmaf(ESb[B_], kLog2e, -fsS)) : 0.f;
+                c2_pin(ESb[B_]);
+            }
+            C2_MARK(a, p, 6);
             halfway();
             // P frame: one shift per own column, common to all waves and row groups; the empty-label weight
             // of an own state q shares the shift of the column of q, whose value it multiplies
@@ -843,27 +853,24 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 m0 = fmaxf(m0, EQ0[B_][j]);
                 m1 = fmaxf(m1, EQ1[B_][j]);
             }
+            // (maxima of integers through LDS atomics: the order does not matter, one barrier is enough)
             if (lane < 17 * kC2FG) {
-                int2 sw;
-                sw.x = shift_for(v0ok ? m0 : LAST_NEG_INF); sw.y = shift_for(v1ok ? m1 : LAST_NEG_INF);
-                *(int2*)&shw_s[slotF] = sw;
+                atomicMax(&shc_s[B_ * kC2Own + 2 * ci], shift_for(v0ok ? m0 : LAST_NEG_INF));
+                atomicMax(&shc_s[B_ * kC2Own + 2 * ci + 1], shift_for(v1ok ? m1 : LAST_NEG_INF));
             }
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
-                shw_s[kC2RedN * kC2Own + lane] = shift_for(EB[B_]);
+                atomicMax(&shc_s[B_ * kC2Own + lane], shift_for(EB[B_]));
             }
             c2_barrier();
+            C2_MARK(a, p, 7);
+            // every wave is past the pair that is ending: its cells are cleared for the pass after this one
+            if (wave == 1 && lane < kC2Own) shc_s[(B_ ^ 1) * kC2Own + lane] = kShiftNone;
             if (wave == 0) {
-                int sc = kShiftNone;
-                if (lane < kC2Own) {
-#pragma unroll
-                    for (int x = 0; x <= kC2RedN; ++x) sc = max(sc, shw_s[x * kC2Own + lane]);
-                    shc_s[B_ * kC2Own + lane] = sc;
-                }
-                const int sg = wave_max_dpp(fok ? sc : kShiftNone);
+                // largest shift of the own columns: the reference of the P-step's partial sums
+                const int sg = wave_max_dpp(fok ? shc_s[B_ * kC2Own + lane] : kShiftNone);
                 if (lane == 0) ctl_s[2 + B_] = sg;
             }
-            c2_barrier();
             const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
             // (a column this lane does not have: a huge shift makes its E zero)
             const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
@@ -876,7 +883,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             }
             if (wave == 0) EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)shc_s[B_ * kC2Own + min(lane, kC2Own - 1)]));
             c2_pin(EB[B_]);
-            sigP[B_] = ctl_s[2 + B_];
             if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); }
         };
         auto meet = [&]() __attribute__((always_inline)) {
@@ -893,7 +899,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         issueP(std::integral_constant<int, 0>(), 0);
         prep(std::integral_constant<int, 0>(), [] {});
 
-        int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
             constexpr int B_ = decltype(BUF)::value;
             const int iF = 2 * p, iP = 2 * p + 1;
@@ -913,35 +918,43 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             {
                 const int tF = L - 1 - iF;
                 const int S = ctl_s[0];
-                float bv[kClNC];
+                float bv[kC2NC];
 #pragma unroll
-                for (int j = 0; j < kClNC; ++j) bv[j] = full_s[lane + 64 * j];
+                for (int j = 0; j < kC2NC; ++j) bv[j] = full_s[lane + 64 * j];
+                // straggler element of this lane times its column's value; it joins the sum of its row
+                const float bS = full_s[min(kC2PC + sI, 319)];
+                const float sprod = ESb[B_] * bS;
+                float facS = 0.f;
 #pragma unroll
                 for (int ri = 0; ri < kC2RW; ++ri) {
-                    const int rloc = min(wave + ri * kC2Waves, g.nr - 1);
-                    const float brow = full_s[g.r0 + rloc];
-                    // the empty label (column 0) returns to the row's own state
-                    float acc = EFb[B_][ri][0] * (lane == 0 ? brow : bv[0]);
+                    if (ri < nrw) {
+                        const int rloc = wave + ri * kC2Waves;
+                        const float brow = full_s[g.r0 + rloc];
+                        // the empty label (column 0) returns to the row's own state
+                        float acc = EFb[B_][ri][0] * (lane == 0 ? brow : bv[0]);
 #pragma unroll
-                    for (int j = 1; j < kClNC; ++j) acc = fmaf(EFb[B_][ri][j], bv[j], acc);
-                    const float tot = wave_sum_dpp(acc);
-                    if (lane == 0 && ri < nrw) {
-                        red_s[rloc] = tot;
-                        shr_s[rloc] = srF[B_][ri];
-                    }
-                    if (GAMMA && iF >= ph1 && ri < nrw) {
-                        const float arow = __shfl(aF[B_], ri, 64);
-                        const float fac = a.scale * arow *
-                                          fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
-                        const unsigned gso = (unsigned)tF * frb + roff(ri);
+                        for (int j = 1; j < kC2NC; ++j) acc = fmaf(EFb[B_][ri][j], bv[j], acc);
+                        if (nstF > 0) acc += rS == ri ? sprod : 0.f;
+                        const float tot = wave_sum_dpp(acc);
+                        if (lane == 0) {
+                            red_s[rloc] = tot;
+                            shr_s[rloc] = srF[B_][ri];
+                        }
+                        if (GAMMA && iF >= ph1) {
+                            const float arow = __shfl(aF[B_], ri, 64);
+                            const float fac = a.scale * arow *
+                                              fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
+                            if (rS == ri) facS = fac;
+                            const unsigned gso = (unsigned)tF * frb + roff(ri);
 #pragma unroll
-                        for (int j = 0; j < kClNC; ++j)
-                            {
+                            for (int j = 0; j < kC2NC; ++j) {
                                 const float bb = (j == 0 && lane == 0) ? brow : bv[j];
                                 buf_store(EFb[B_][ri][j] * bb * fac, grs, coffj(j), gso);
                             }
+                        }
                     }
                 }
+                if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
                 c2_barrier();
                 if (wave == 0) {
                     const bool ok = lane < g.nr;
@@ -952,7 +965,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (lane < kC2Own) {
                         own_s[lane] = own;
                         // for the P-step: own states times 2^(shift of their column - largest shift)
-                        bt_s[lane] = c2_scale(own, shc_s[B_ * kC2Own + lane] - sigP[B_]);
+                        bt_s[lane] = c2_scale(own, shc_s[B_ * kC2Own + lane] - ctl_s[2 + B_]);
                     }
                     const int ek = (ms == kShiftNone) ? S : S + ms;
                     if (lane == 0) ctl_s[1] = ek;
@@ -980,9 +993,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const unsigned tag = gstep + 1;
                 u64* xs = xbase + (size_t)(gstep & 1) * kClMaxK * kC2XS;
                 const int ek = ctl_s[1];
-                const int sg = sigP[B_];
+                const int sg = ctl_s[2 + B_];
                 const bool exch = !(GAMMA && iP == L - 1);
-                C2_MARK(a, p, 6);
                 // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state):
                 // every lane its two columns of its eleven rows, then thread <-> row over the lanes' parts
                 {
@@ -1002,7 +1014,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (tid < 320) afull_s[tid] = rowok ? c2_scale(aP[B_], sak - samax) : 0.f;
                 }
                 c2_barrier();
-                C2_MARK(a, p, 7);
                 if (rowok && exch) {
                     const float4* rp4 = (const float4*)&red2_s[tid * kC2R2S];
                     const float4 x0 = rp4[0], x1 = rp4[1], x2 = rp4[2], x3 = rp4[3];
