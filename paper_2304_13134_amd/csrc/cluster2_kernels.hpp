@@ -29,11 +29,17 @@
 // steps that read "own columns" the workgroup reads column 0 for its own rows
 // separately.
 //
-// Arithmetic as in cluster_kernels.hpp: E = 2^(w log2 e - s) with integer shifts s
-// from the data (per column or per row), evaluated while the exchange of the
-// previous pair is in flight.  Exchange words are [value:32 | tag:32], published
-// with plain stores into the XCD's L2 and gathered with agent-scope loads, 8 + 8
-// per thread in flight; all waits are bounded (status 5 instead of a hang).
+// Arithmetic as in cluster_kernels.hpp: E = 2^(w log2 e - s) with integer shifts s from the data (per
+// own column, or per row), evaluated for the NEXT pair while the exchange of the current one is in
+// flight.  Exchange words are [value:32 | tag:16 | exponent:16], published with plain stores into the
+// XCD's L2 and gathered with agent-scope loads (K per thread, the first look issued halfway through the
+// exp pass); all waits are bounded (status 5 instead of a hang).
+//
+// Access patterns.  "Own rows x all columns" (alpha P-step, beta F-step) is read row-contiguous.  "All
+// rows x own columns" (alpha F-step, beta P-step) is read three rows per instruction, 17 lanes x 8 bytes
+// per row.  Masks are not branches: a lane that must not store gets a buffer offset beyond the
+// descriptor (dropped by the hardware's range check), and loads beyond the matrix fetch a copy of the
+// last row or column, which meets a zero of the state vector in every sum.
 #pragma once
 #include "cluster_kernels.hpp"
 
@@ -44,14 +50,13 @@ constexpr int kC2Waves = 8;
 constexpr int kC2NQ = 33;      // rows per wave when a workgroup reads all rows: 8 * 33 >= 264
 constexpr int kC2FG = 3;       // alpha F-step: row groups per wave (17 lanes each, two columns per lane)
 constexpr int kC2FJ = 11;      // alpha F-step: rows per lane, kC2FG * kC2FJ = kC2NQ
-constexpr int kC2Hdr = 264;    // exchange row: C values, the producer's exponent at [kC2Hdr]
+constexpr int kC2Hdr = 264;    // largest number of states on this path (words of value per producer and slot)
 constexpr int kC2XS = 272;     // words per producer and slot
 constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
 constexpr int kC2NC = 4;       // ... in chunks of 64 columns; columns beyond 256 by one more instruction (see beta F-step)
-constexpr int kC2RT = 33;      // own rows (alpha) or own columns (beta) of a workgroup in the P-step
-constexpr int kC2PH = 17;      // ... of which a thread takes one half: [0, 17) or [17, 33)
-constexpr int kC2PC = 256;     // columns (alpha) or rows (beta) that have a thread per half; the few beyond
-                               // ("stragglers", at most 8) are taken by one wave each, lane <-> own row / column
+constexpr int kC2PH = 17;      // alpha P-step: a thread takes one half of the (at most 33) own rows: [0, 17) or [17, 33)
+constexpr int kC2PC = 256;     // columns that have a thread per half (alpha P-step) or a lane per chunk (beta F-step);
+                               // the few beyond ("stragglers", at most 8) are taken lane-wise by single instructions
 constexpr int kC2Own = 40;     // LDS slots for own states
 // A per-lane buffer offset beyond every descriptor's size: the hardware's range check drops the lane's
 // store and returns zero for its load.  Replaces branches around accesses whose mask differs per lane.
@@ -62,8 +67,7 @@ constexpr int kC2Full = 0;                          // [320] whole state vector
 constexpr int kC2OwnS = kC2Full + 320;              // [40]  own states
 constexpr int kC2RedN = kC2Waves * kC2FG;           // partial sums per own column (alpha F-step)
 constexpr int kC2Red = kC2OwnS + kC2Own;            // [24][40] partials per wave and row group
-constexpr int kC2Shw = kC2Red + kC2RedN * kC2Own;   // [25][40] shifts per wave and row group, empty label last (int)
-constexpr int kC2Shc = kC2Shw + (kC2RedN + 1) * kC2Own;   // [2][40] shift per own column, per buffer (int)
+constexpr int kC2Shc = kC2Red + kC2RedN * kC2Own;   // [2][40] shift per own column, per buffer (int, atomic maxima)
 constexpr int kC2Bl = kC2Shc + 2 * kC2Own;          // [40] empty-label terms
 constexpr int kC2Pacc = kC2Bl + kC2Own;             // [320] partial sums of the second half
 constexpr int kC2Bo = kC2Pacc + 320;                // [40] other side's own-state values (marginals)
@@ -77,6 +81,8 @@ constexpr int kC2Afull = kC2Bt + kC2Own;            // [320] beta P-step: other 
 constexpr int kC2R2S = 20;                          // row pitch of the per-lane partials
 constexpr int kC2Red2 = kC2Afull + 320;             // [264][20] beta P-step: partial sums per row and lane
 constexpr int kC2Lds = kC2Red2 + kC2Waves * kC2NQ * kC2R2S;
+static_assert(kC2Red2 % 4 == 0 && kC2R2S % 4 == 0, "16-byte reads of the per-row partials");
+static_assert(kC2Red % 2 == 0 && kC2Shc % 2 == 0 && kC2Bt % 2 == 0 && kC2Own % 2 == 0, "8-byte LDS accesses");
 
 #ifdef LAST_TRACE
 #define C2_MARK(a, p, k)                                                                    \
@@ -224,7 +230,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
     float* full_s = smem + kC2Full;
     float* own_s = smem + kC2OwnS;
     float* red_s = smem + kC2Red;
-    int* shw_s = (int*)(smem + kC2Shw);
     int* shc_s = (int*)(smem + kC2Shc);
     float* bl_s = smem + kC2Bl;
     float* pacc_s = smem + kC2Pacc;
@@ -647,13 +652,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
-// one half of a row's own columns: 17 consecutive floats, read or written in 16-byte pieces (the rows of
-// the weight tensor are only 4-byte aligned; the compiler picks the widest access the target allows)
-struct C2Row {
-    float v[kC2PH];
-};
-typedef float c2_f4 __attribute__((ext_vector_type(4), aligned(4)));
-
 template <bool GAMMA>
 __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
@@ -662,7 +660,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     float* own_s = smem + kC2OwnS;
     float* red_s = smem + kC2RowF;            // [40] row sums of the F-step
     int* shr_s = (int*)(smem + kC2RowS);      // [40] their shifts
-    int* shw_s = (int*)(smem + kC2Shw);
     int* shc_s = (int*)(smem + kC2Shc);
     float* bl_s = smem + kC2Bl;
     float* bt_s = smem + kC2Bt;
