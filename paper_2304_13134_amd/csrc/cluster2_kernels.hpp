@@ -320,7 +320,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 
         float EF0[2][kC2FJ], EF1[2][kC2FJ], EP[2][kC2PH];
         float EB[2] = {0.f, 0.f}, ES[2] = {0.f, 0.f}, bSt[2] = {0.f, 0.f};
-        int shP[2] = {0, 0}, sigP[2] = {0, 0}, ssP[2] = {kShiftNone, kShiftNone};
+        float EBP[2] = {0.f, 0.f};                  // wave 0: empty-label weight of the own row of this lane, P frame
+        int shP[2] = {0, 0}, sigP[2] = {0, 0}, ssP[2] = {kShiftNone, kShiftNone}, sbP0[2] = {kShiftNone, kShiftNone};
         // other side's vector for the marginals
         float bF0[2] = {0.f, 0.f}, bF1[2] = {0.f, 0.f}, bFb[2] = {0.f, 0.f}, bPv[2] = {0.f, 0.f}, boP[2] = {0.f, 0.f};
         int sbF[2] = {0, 0}, sbP[2] = {0, 0};
@@ -376,6 +377,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 if (r >= r0_ && r < r1_)
                     EP[B_][r] = buf_load(wrs, coffPm, foP + rbaseP + (unsigned)min(rP0 + r, g.nr - 1) * pitch);
             if (r1_ >= kC2PH && hasS) ES[B_] = buf_load(wrs, coffS, foP + rbaseP);
+            if (r1_ >= kC2PH && wave == 0) EBP[B_] = buf_load(wrs, fok ? rowB : kC2Off, foP);     // w[q][0], own rows
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
@@ -410,6 +412,14 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 ES[B_] = fast_exp2(fmaf(e, kLog2e, -(float)ssp));
                 c2_pin(ES[B_]);
                 wm = max(wm, ssp);
+            }
+            if (wave == 0) {
+                // empty-label arcs of the own rows: lane <-> row, each with its own shift
+                const int sb0 = shift_for(fok ? EBP[B_] : LAST_NEG_INF);
+                EBP[B_] = fok ? fast_exp2(fmaf(EBP[B_], kLog2e, -(float)sb0)) : 0.f;
+                c2_pin(EBP[B_]);
+                sbP0[B_] = sb0;
+                wm = max(wm, wave_max_dpp(sb0));
             }
             if (lane == 0) atomicMax(&ctl_s[2 + B_], wm);
             c2_barrier();
@@ -571,11 +581,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 const int sp = shP[B_], sg = sigP[B_], ssp = ssP[B_];
                 const float val = (sp == kShiftNone) ? 0.f : c2_scale(acc0 + acc1, sp - sg);
                 issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 9, kC2PH);
-                if (cP == 0) {
-#pragma unroll
-                    for (int r = 0; r < kC2PH; ++r)
-                        bl_s[rP0 + r] = (sp == kShiftNone) ? 0.f : c2_scale(own_s[rP0 + r] * EP[B_][r], sp - sg);
-                }
+                if (wave == 0 && lane < kC2Own)
+                    bl_s[lane] = (sbP0[B_] == kShiftNone) ? 0.f : c2_scale(own_s[lane] * EBP[B_], sbP0[B_] - sg);
                 if (hP == 1) pacc_s[cP] = val;                 // second half of the own rows
                 if (hasS) {
                     const float sv = wave_sum_dpp(lane < g.nr ? own_s[lane] * ES[B_] : 0.f);
