@@ -9,6 +9,7 @@
 #include "numerator_kernels.hpp"
 #include "cluster_kernels.hpp"
 #include "cluster2_kernels.hpp"
+#include "cluster2v_kernels.hpp"
 #include "fused_kernels.hpp"
 #include <algorithm>
 
@@ -108,13 +109,15 @@ PosteriorWs carve_posteriors(Carver& cv, const Shape& s)
 struct PathWs {
     int* bp;
     int* final_state;
+    u64* xv;             // exchange buffer of the clustered tropical kernel (xwords > 0)
 };
 
-PathWs carve_path(Carver& cv, const Shape& s)
+PathWs carve_path(Carver& cv, const Shape& s, size_t xwords)
 {
     PathWs p;
     p.bp = cv.take<int>((size_t)s.B * (s.T > 0 ? s.T : 1) * s.C);
     p.final_state = cv.take<int>((size_t)s.B);
+    p.xv = xwords ? cv.take<u64>(xwords) : nullptr;
     return p;
 }
 
@@ -412,6 +415,50 @@ bool launch_bigram_viterbi(const Shape& s, const float* w, const int* lengths, i
     return true;
 }
 
+// geometry of the clustered tropical kernel (cluster2v_kernels.hpp): K workgroups per item
+struct ViterbiPlan {
+    bool ok;
+    int K, RPW, ncl, grid;
+    size_t xwords;
+};
+
+ViterbiPlan viterbi_plan(const Shape& s, int kind)
+{
+    ViterbiPlan p{};
+    const char* force = std::getenv("LAST_FORCE_SOLO");
+    if (force && force[0] == '1') return p;
+    const char* off = std::getenv("LAST_CLUSTER_VITERBI");
+    if (off && off[0] == '0') return p;
+    if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kC2Hdr || s.T < 1) return p;
+    if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;      // one 32-bit buffer descriptor per item
+    if ((size_t)s.C * s.C >= (size_t)kVNone) return p;                    // 17-bit arc indices in the exchange
+    p.K = (s.C + 32) / 33;
+    if (p.K > kClMaxK) return p;
+    p.RPW = (s.C + p.K - 1) / p.K;
+    if (s.C - (p.K - 1) * p.RPW < 1) return p;
+    const int max_ncl = 32 / p.K;               // one workgroup per compute unit: 32 per XCD
+    if (max_ncl < 1) return p;
+    const int want = (s.B + 7) / 8;
+    p.ncl = want < max_ncl ? want : max_ncl;
+    p.grid = 8 * p.ncl * p.K;
+    p.xwords = (size_t)8 * p.ncl * 2 * kClMaxK * kC2XS;
+    p.ok = true;
+    return p;
+}
+
+void launch_cluster_viterbi(const Shape& s, const ViterbiPlan& p, u64* xv, const float* w, const int* lengths,
+                            int* bp, int* final_state, float* score, int* item_status, hipStream_t st)
+{
+    hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, xv, p.xwords);
+    ClusterVArgs a;
+    a.w = w; a.len = lengths; a.bp = bp; a.final_state = final_state; a.score = score;
+    a.item_status = item_status; a.xa = xv;
+    a.B = s.B; a.T = s.T; a.C = s.C; a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl;
+    a.spin_limit = 1 << 20;
+    if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+    else hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+}
+
 last_status_t check_ws(void* ws, size_t have, size_t need)
 {
     if (need == 0) return LAST_OK;
@@ -481,10 +528,12 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
         return cv.used;
     }
     const ClusterPlan plan = cluster_plan(s, weights->kind);
+    const ViterbiPlan vplan = viterbi_plan(s, weights->kind);
     switch (op) {
     case LAST_OP_SHORTEST_DISTANCE:
         if (plan.ok) carve_cluster(cv, s, plan);
         else cv.take<double>(1);
+        if (vplan.ok) cv.take<u64>(vplan.xwords);        // tropical semiring: exchange buffer
         break;
     case LAST_OP_ARC_POSTERIORS:
         if (plan.ok) carve_cluster(cv, s, plan);
@@ -495,7 +544,7 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
         carve_num(cv, s, Umax);
         break;
     case LAST_OP_SHORTEST_PATH:
-        carve_path(cv, s);
+        carve_path(cv, s, vplan.ok ? vplan.xwords : 0);
         break;
     default:
         return 0;
@@ -537,6 +586,12 @@ last_status_t last_shortest_distance(const last_weights_t* weights, const int32_
         hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
                            weights->w, lengths, c, s.T, l.CPAD, l.R,
                            (float*)nullptr, (double*)nullptr, (double*)nullptr, dist, item_status);
+    } else if (const ViterbiPlan vp = viterbi_plan(s, weights->kind); vp.ok) {
+        Carver cv(ws);
+        if (plan.ok) carve_cluster(cv, s, plan);
+        else cv.take<double>(1);
+        u64* xv = cv.take<u64>(vp.xwords);
+        launch_cluster_viterbi(s, vp, xv, weights->w, lengths, nullptr, nullptr, dist, item_status, st);
     } else {
         if (l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
         if (!launch_bigram_viterbi(s, weights->w, lengths, nullptr, nullptr, dist, item_status, st))
@@ -662,11 +717,14 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
     if (rc != LAST_OK) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
     const SoloLayout l = solo_layout(s);
-    if (l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    const ViterbiPlan vp = viterbi_plan(s, weights->kind);
+    if (!vp.ok && l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
     const Ctx c = make_ctx(s);
     Carver cv(ws);
-    PathWs p = carve_path(cv, s);
-    if (!launch_bigram_viterbi(s, weights->w, lengths, p.bp, p.final_state, score, item_status, st))
+    PathWs p = carve_path(cv, s, vp.ok ? vp.xwords : 0);
+    if (vp.ok)
+        launch_cluster_viterbi(s, vp, p.xv, weights->w, lengths, p.bp, p.final_state, score, item_status, st);
+    else if (!launch_bigram_viterbi(s, weights->w, lengths, p.bp, p.final_state, score, item_status, st))
         hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,
                            c, s.T, l.CPAD, l.R, p.bp, p.final_state, score, item_status);
     hipLaunchKernelGGL(backtrace_kernel, dim3(s.B), dim3(256), 0, st, (const int*)p.bp, lengths,

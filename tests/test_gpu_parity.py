@@ -107,6 +107,7 @@ def test_state_counts_around_256_and_every_pair_parity():
         cfg = workloads.dense(B=6, T=9, V=V, order=1, sigma=2.0, seed=300 + V, len_lo=1, len_hi=9)
         cfg["lengths"] = np.array([1, 2, 3, 4, 8, 9], dtype=np.int32)
         check_posteriors(cfg)
+        check_path(cfg)
 
 
 def test_first_generation_clustered_kernel(monkeypatch):
@@ -117,6 +118,15 @@ def test_first_generation_clustered_kernel(monkeypatch):
     for V in (65, 130, 263):
         cfg = workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9)
         check_posteriors(cfg)
+
+
+def test_one_workgroup_shortest_path_kernels(monkeypatch):
+    # LAST_CLUSTER_VITERBI=0 selects the kernels with one workgroup per item; they stay covered
+    monkeypatch.setenv("LAST_CLUSTER_VITERBI", "0")
+    announce("one-workgroup shortest path: B=3 T=40 V=256, and ragged sizes")
+    check_path(workloads.config(2, B=3, T=40))
+    for V in (5, 130, 200, 263):
+        check_path(workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9))
 
 
 def test_edge_lengths_and_status():
