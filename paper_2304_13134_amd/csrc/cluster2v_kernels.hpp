@@ -63,6 +63,15 @@ __device__ __forceinline__ u64 v2_pack(float v, unsigned tag, int flat)
     return (u64)__float_as_uint(v) | ((u64)(((tag & 0x7FFFu) << 17) | ((unsigned)flat & 0x1FFFFu)) << 32);
 }
 
+// The same inside one thread's scan, whose candidates come in increasing arc order: a tie keeps the
+// earlier, lower arc, and a candidate of -inf never beats the initial -inf.
+__device__ __forceinline__ void v2_scan(float v, int flat, float& best, int& bflat)
+{
+    const bool up = v > best;
+    best = up ? v : best;
+    bflat = up ? flat : bflat;
+}
+
 // best (score, arc) of a wave, in every lane
 __device__ __forceinline__ void v2_wave_best(float& v, int& f)
 {
@@ -232,8 +241,8 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                 for (int j = 0; j < kC2FJ; ++j) {
                     const int q = qF0 + kC2FG * j;
                     const float aq = full_s[min(q, 319)];            // -inf beyond the last state
-                    v2_acc(__fadd_rn(aq, EF0[B_][j]), q * V1 + y0, b0, f0);
-                    v2_acc(__fadd_rn(aq, EF1[B_][j]), q * V1 + y0 + 1, b1, f1);
+                    v2_scan(__fadd_rn(aq, EF0[B_][j]), q * V1 + y0, b0, f0);         // (q increases with j)
+                    v2_scan(__fadd_rn(aq, EF1[B_][j]), q * V1 + y0 + 1, b1, f1);
                 }
                 if (!v0ok) { b0 = LAST_NEG_INF; f0 = kVNone; }
                 if (!v1ok) { b1 = LAST_NEG_INF; f1 = kVNone; }
@@ -269,7 +278,7 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                 int bfv = kVNone;
 #pragma unroll
                 for (int r = 0; r < kC2PH; ++r)      // (rows beyond the own ones have score -inf)
-                    v2_acc(__fadd_rn(own_s[rP0 + r], EP[B_][r]), (r0 + rP0 + r) * V1 + cP, bv, bfv);
+                    v2_scan(__fadd_rn(own_s[rP0 + r], EP[B_][r]), (r0 + rP0 + r) * V1 + cP, bv, bfv);
                 if (!colok || cP == 0) { bv = LAST_NEG_INF; bfv = kVNone; }     // column 0 is the empty label
                 if (wave == 0 && lane < kC2Own) {
                     // the empty label keeps the state: candidates of the own states, lane <-> state
