@@ -510,6 +510,7 @@ int32_t last_kernel_variant(const last_weights_t* weights, const last_context_t*
     }
     if (op == LAST_OP_SHORTEST_DISTANCE || op == LAST_OP_ARC_POSTERIORS)
         return cluster_plan(s, weights->kind).ok ? 1 : 0;
+    if (op == LAST_OP_SHORTEST_PATH) return viterbi_plan(s, weights->kind).ok ? 1 : 0;
     return 0;
 }
 
