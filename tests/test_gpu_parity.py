@@ -120,6 +120,14 @@ def test_first_generation_clustered_kernel(monkeypatch):
         check_posteriors(cfg)
 
 
+def test_more_items_than_clusters():
+    # 37 items on 16 clusters: every cluster walks several items one after the other, with ragged lengths
+    announce("clustered path: B=37 T=6 V=256")
+    cfg = workloads.dense(B=37, T=6, V=256, order=1, sigma=2.0, seed=3737, len_lo=0, len_hi=6)
+    check_posteriors(cfg)
+    check_path(cfg)
+
+
 def test_one_workgroup_shortest_path_kernels(monkeypatch):
     # LAST_CLUSTER_VITERBI=0 selects the kernels with one workgroup per item; they stay covered
     monkeypatch.setenv("LAST_CLUSTER_VITERBI", "0")
