@@ -540,9 +540,17 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     float v = 0.f;
                     const int shFl = shc_s[B_ * kC2Own + min(lane, kC2Own - 1)];
                     if (fok) {
+                        // all partial sums are requested before the first is used (left to itself the
+                        // compiler waits for every LDS read in turn to save registers: 12 round trips)
+                        float pr[kC2RedN];
 #pragma unroll
-                        for (int x = 0; x < kC2RedN; ++x) v += red_s[x * kC2Own + lane];
-                        v = fmaf(full_s[yF], EB[B_], v);
+                        for (int x = 0; x < kC2RedN; ++x) pr[x] = red_s[x * kC2Own + lane];
+                        const float ay = full_s[yF];
+                        __builtin_amdgcn_sched_group_barrier(0x100, kC2RedN + 1, 0);    // the LDS reads
+                        __builtin_amdgcn_sched_group_barrier(0x002, kC2RedN + 1, 0);    // then the additions
+#pragma unroll
+                        for (int x = 0; x < kC2RedN; ++x) v += pr[x];
+                        v = fmaf(ay, EB[B_], v);
                     }
                     const int sc = (fok && v > 0.f) ? shFl + float_exponent(v) : kShiftNone;
                     const int ms = wave_max_dpp(sc);
