@@ -108,6 +108,17 @@ __device__ __forceinline__ void c2_pin(T& v)
     asm volatile("" : "+v"(v));
 }
 
+// The compiler follows loads without regard to the conditions they sit under: a load under a
+// condition whose uses sit under the same condition still counts as possibly pending at every later
+// use, and costs a wait that also covers whatever was issued in between.  Loads of this kernel are
+// therefore issued on every path (a lane or wave that needs nothing gets the out-of-range offset), and
+// where a path does not use a loaded value it "touches" it: a comparison that is never true, whose
+// result ends in a flag nobody reads.
+__device__ __forceinline__ int c2_touch(float v)
+{
+    return v > 3.3e38f ? 1 : 0;
+}
+
 // Wait for every vector memory load in flight (vmcnt(0); the other counters untouched).  Used on the
 // rare path that reloads prefetched values: the compiler merges the pending state of that path into
 // the common one, and would otherwise make the common path wait for loads it has only just issued.
@@ -349,7 +360,17 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             // whose exponent the column-0 thread uses for the empty-label arcs)
             // (only loads here: arithmetic on the loaded values would wait for every load in flight)
             boP[B_] = buf_load(brs, yoff, (unsigned)(tP + 1) * pitch);       // wave 0: own state of this lane
-            if (nst > 0) bSt[B_] = buf_load(brs, soffS, (unsigned)(tP + 1) * pitch);   // lanes 0..7: straggler columns
+            bSt[B_] = buf_load(brs, nst > 0 ? soffS : kC2Off, (unsigned)(tP + 1) * pitch);   // lanes 0..7: straggler columns
+        };
+        // after a reload on the rare path: read every reloaded value once, so that none of them counts as
+        // pending on the common path (see c2_touch)
+        auto settle = [&]() __attribute__((always_inline)) {
+            int t = 0;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+                t |= c2_touch(bF0[x]) | c2_touch(bF1[x]) | c2_touch(bFb[x]) | c2_touch(bPv[x]) | c2_touch(boP[x]) |
+                     c2_touch(bSt[x]) | (sbF[x] == 0x7fffffff) | (sbP[x] == 0x7fffffff);
+            if (t) ctl_s[9] = 1;          // (never; nobody reads it)
         };
         // The loads of a pair are issued in four pieces spread over the previous pair: issued in one
         // go, the whole chip would pull at the HBM limit for a moment and every wave would sit in its
@@ -366,7 +387,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     EF0[B_][j] = x.x;
                     EF1[B_][j] = x.y;
                 }
-            if (j1 >= kC2FJ && wave == 0 && lane < kC2Own) EB[B_] = buf_load(wrs, rowB, foF);
+            if (j1 >= kC2FJ) EB[B_] = buf_load(wrs, wave == 0 && fok ? rowB : kC2Off, foF);
             if (GAMMA && j0 == 0) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p, int r0_, int r1_) __attribute__((always_inline)) {
@@ -376,8 +397,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             for (int r = 0; r < kC2PH; ++r)
                 if (r >= r0_ && r < r1_)
                     EP[B_][r] = buf_load(wrs, coffPm, foP + rbaseP + (unsigned)min(rP0 + r, g.nr - 1) * pitch);
-            if (r1_ >= kC2PH && hasS) ES[B_] = buf_load(wrs, coffS, foP + rbaseP);
-            if (r1_ >= kC2PH && wave == 0) EBP[B_] = buf_load(wrs, fok ? rowB : kC2Off, foP);     // w[q][0], own rows
+            if (r1_ >= kC2PH) ES[B_] = buf_load(wrs, hasS ? coffS : kC2Off, foP + rbaseP);
+            if (r1_ >= kC2PH) EBP[B_] = buf_load(wrs, wave == 0 && fok ? rowB : kC2Off, foP);     // w[q][0], own rows
         };
         // exp pass of both frames of a pair (contains workgroup barriers)
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
@@ -394,9 +415,12 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 atomicMax(&shc_s[B_ * kC2Own + 2 * ci], shift_for(v0ok ? m0 : LAST_NEG_INF));
                 atomicMax(&shc_s[B_ * kC2Own + 2 * ci + 1], shift_for(v1ok ? m1 : LAST_NEG_INF));
             }
+            int touched = 0;
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
                 atomicMax(&shc_s[B_ * kC2Own + lane], shift_for(EB[B_]));
+            } else {
+                touched |= c2_touch(EB[B_]);
             }
             // P frame: one shift per column and thread, the workgroup's largest as reference
             float mp = LAST_NEG_INF;
@@ -410,17 +434,22 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 const float e = lane < g.nr ? ES[B_] : LAST_NEG_INF;
                 ssp = shift_for(wave_max_dpp(e));
                 ES[B_] = fast_exp2(fmaf(e, kLog2e, -(float)ssp));
-                c2_pin(ES[B_]);
                 wm = max(wm, ssp);
+            } else {
+                touched |= c2_touch(ES[B_]);
             }
+            c2_pin(ES[B_]);
             if (wave == 0) {
                 // empty-label arcs of the own rows: lane <-> row, each with its own shift
                 const int sb0 = shift_for(fok ? EBP[B_] : LAST_NEG_INF);
                 EBP[B_] = fok ? fast_exp2(fmaf(EBP[B_], kLog2e, -(float)sb0)) : 0.f;
-                c2_pin(EBP[B_]);
                 sbP0[B_] = sb0;
                 wm = max(wm, wave_max_dpp(sb0));
+            } else {
+                touched |= c2_touch(EBP[B_]);
             }
+            c2_pin(EBP[B_]);
+            if (touched) ctl_s[9] = 1;        // (never; nobody reads it)
             if (lane == 0) atomicMax(&ctl_s[2 + B_], wm);
             c2_barrier();
             // every wave is past the pair that is ending: its cells are cleared for the pass after this one
@@ -486,6 +515,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     other(std::integral_constant<int, B_>(), p);
                     other(std::integral_constant<int, B_ ^ 1>(), p + 1);
                     c2_wait_loads();
+                    settle();
                 }
             }
             {
@@ -575,6 +605,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     other(std::integral_constant<int, B_>(), p);
                     other(std::integral_constant<int, B_ ^ 1>(), p + 1);
                     c2_wait_loads();
+                    settle();
                 }
             }
             {
@@ -805,16 +836,26 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             aP[B_] = buf_load(ars, (unsigned)(qT * (int)sizeof(float)), (unsigned)tP * pitch);
             saP[B_] = __builtin_bit_cast(int, buf_load(sars, koff, (unsigned)tP * (unsigned)(kClMaxK * sizeof(int))));
         };
+        // after a reload on the rare path: read every reloaded value once, so that none of them counts as
+        // pending on the common path (see c2_touch)
+        auto settle = [&]() __attribute__((always_inline)) {
+            int t = 0;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+                t |= c2_touch(aF[x]) | c2_touch(aP[x]) | (saF[x] == 0x7fffffff) | (saP[x] == 0x7fffffff);
+            if (t) ctl_s[9] = 1;          // (never; nobody reads it)
+        };
         auto issueF = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             const unsigned foF = (unsigned)frameF(p) * frb;
 #pragma unroll
-            for (int ri = 0; ri < kC2RW; ++ri)
-                if (ri < nrw) {
+            for (int ri = 0; ri < kC2RW; ++ri) {
+                // (a wave without a row ri loads nothing: every lane out of range)
 #pragma unroll
-                    for (int j = 0; j < kC2NC; ++j) EFb[B_][ri][j] = buf_load(wrs, coffl(j), foF + roff(ri));
-                }
-            if (nstF > 0) ESb[B_] = buf_load(wrs, offSt, foF);
+                for (int j = 0; j < kC2NC; ++j)
+                    EFb[B_][ri][j] = buf_load(wrs, ri < nrw ? coffl(j) : kC2Off, foF + roff(ri));
+            }
+            ESb[B_] = buf_load(wrs, offSt, foF);
             if (GAMMA) other(BUF, p);
         };
         auto issueP = [&](auto BUF, int p) __attribute__((always_inline)) {
@@ -828,12 +869,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 EQ0[B_][j] = x.x;
                 EQ1[B_][j] = x.y;
             }
-            if (wave == 0 && lane < kC2Own) EB[B_] = buf_load(wrs, rowB, foP);      // w[q][0] of the own states
+            EB[B_] = buf_load(wrs, wave == 0 && fok ? rowB : kC2Off, foP);           // w[q][0] of the own states
         };
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             // F frame: one shift per own row (wave-uniform)
             float fsS = 3.0e38f;       // shift of the row of this lane's straggler element
+            int touched = 0;
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri) {
                 if (ri < nrw) {
@@ -846,16 +888,17 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     const float fs = (float)s;
                     if (rS == ri) fsS = fs;
 #pragma unroll
-                    for (int j = 0; j < kC2NC; ++j) { EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs)); c2_pin(EFb[B_][ri][j]); }
+                    for (int j = 0; j < kC2NC; ++j) EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
                 } else {
                     srF[B_][ri] = kShiftNone;
+#pragma unroll
+                    for (int j = 0; j < kC2NC; ++j) touched |= c2_touch(EFb[B_][ri][j]);
                 }
+#pragma unroll
+                for (int j = 0; j < kC2NC; ++j) c2_pin(EFb[B_][ri][j]);
             }
-            if (nstF > 0) {
-                ESb[B_] = validS ? fast_exp2(fmaf(ESb[B_], kLog2e, -fsS)) : 0.f;
-                c2_pin(ESb[B_]);
-            }
-            C2_MARK(a, p, 6);
+            ESb[B_] = validS ? fast_exp2(fmaf(ESb[B_], kLog2e, -fsS)) : 0.f;
+            c2_pin(ESb[B_]);
             halfway();
             // P frame: one shift per own column, common to all waves and row groups; the empty-label weight
             // of an own state q shares the shift of the column of q, whose value it multiplies
@@ -873,9 +916,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
                 atomicMax(&shc_s[B_ * kC2Own + lane], shift_for(EB[B_]));
+            } else {
+                touched |= c2_touch(EB[B_]);
             }
+            if (touched) ctl_s[9] = 1;        // (never; nobody reads it)
             c2_barrier();
-            C2_MARK(a, p, 7);
             // every wave is past the pair that is ending: its cells are cleared for the pass after this one
             if (wave == 1 && lane < kC2Own) shc_s[(B_ ^ 1) * kC2Own + lane] = kShiftNone;
             if (wave == 0) {
@@ -925,6 +970,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     other(std::integral_constant<int, B_>(), p);
                     other(std::integral_constant<int, B_ ^ 1>(), p + 1);
                     c2_wait_loads();
+                    settle();
                 }
             }
             {
@@ -967,7 +1013,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     }
                 }
                 if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
+                C2_MARK(a, p, 6);
                 c2_barrier();
+                C2_MARK(a, p, 7);
                 if (wave == 0) {
                     const bool ok = lane < g.nr;
                     const float v = ok ? red_s[lane] : 0.f;
@@ -998,6 +1046,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     other(std::integral_constant<int, B_>(), p);
                     other(std::integral_constant<int, B_ ^ 1>(), p + 1);
                     c2_wait_loads();
+                    settle();
                 }
             }
             {
