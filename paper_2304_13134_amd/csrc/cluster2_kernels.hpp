@@ -149,14 +149,14 @@ struct C2Look {
     u64 wv[kClMaxK];
 };
 
+// (Threads beyond the last state read the last state's words and discard the result: loads and their
+// uses sit on every path, see c2_touch.)
 __device__ __forceinline__ void c2_gather_look(const u64* xs, int K, int C, C2Look& lk)
 {
-    const int tid = threadIdx.x;
-    if (tid < C) {
+    const int q = min((int)threadIdx.x, C - 1);
 #pragma unroll
-        for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
-    }
+    for (int kk = 0; kk < kClMaxK; ++kk)
+        if (kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + q);
 }
 
 // Every thread calls; ends with a workgroup barrier.
@@ -167,7 +167,7 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
     const int S0 = ctl_s[0];           // exponent the producers' exponents are relative to
     float v = 0.f;
     int hr = 0;
-    if (tid < C) {
+    {
         int n = 0;
         for (;;) {
             bool ok = true;
@@ -188,6 +188,7 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
             if (kk < K)
                 v += c2_scale(__uint_as_float((unsigned)lk.wv[kk]), (int)(short)(unsigned short)(lk.wv[kk] >> 32) - href);
         hr = href;
+        if (tid >= C) v = 0.f;
     }
     // renormalise by the largest magnitude actually present, so that mantissas do not drift
     const int mu = wave_max_dpp(v > 0.f ? float_exponent(v) : -(1 << 20));
