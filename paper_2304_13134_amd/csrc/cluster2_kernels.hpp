@@ -536,8 +536,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     *(float2*)&red_s[slotF] = pw;
                 }
                 C2_MARK(a, p, 6);
-                // next pair's F frame: issued behind the sums, which would otherwise wait for these loads
-                issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, kC2FJ);
                 if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
                     const int sbk = __builtin_amdgcn_readlane(sbF[B_], g.k);
@@ -567,6 +565,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 }
                 c2_barrier();
                 C2_MARK(a, p, 7);
+                // next pair's F frame: waves 1..7 request theirs while wave 0 adds up the columns; wave 0
+                // requests its own afterwards (alone on the address path, that is quick)
+                if (wave != 0) issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, kC2FJ);
                 if (wave == 0) {
                     float v = 0.f;
                     const int shFl = shc_s[B_ * kC2Own + min(lane, kC2Own - 1)];
@@ -593,6 +594,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         if (fok) ah[(size_t)(tF + 1) * C + g.r0 + lane] = own;
                         if (lane == 0) Sa[(size_t)(tF + 1) * kClMaxK + g.k] = ek;
                     }
+                    issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, kC2FJ);
                 }
                 c2_barrier();
             }
