@@ -761,13 +761,13 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             else if (pw) bs_s[tid - 127] = word_value(x);
             const float P = (float)(offs[t + 1] - offs[t]);
             if (__syncthreads_or(dead)) any_dead = 1;
-            // fragments of W for the dpre contraction: requested now, used after the row pass
-            bf16x8 wt[kFuKT][3];
+            // fragments of W for the dpre contraction: the first column tile is requested now and used after
+            // the row pass, every further one while its predecessor is being used (all of them at once cost
+            // 48 registers, which this kernel then spills)
+            bf16x8 wt[2][3];
 #pragma unroll
-            for (int kt = 0; kt < kFuKT; ++kt)
-#pragma unroll
-                for (int ys = 0; ys < 3; ++ys)
-                    wt[kt][ys] = a.Wt[((size_t)min(kFuKT * wave + kt, H / 16 - 1) * 3 + ys) * 64 + lane];
+            for (int ys = 0; ys < 3; ++ys)
+                wt[0][ys] = a.Wt[((size_t)min(kFuKT * wave, H / 16 - 1) * 3 + ys) * 64 + lane];
             fused_rows<false>(w_s, bl, bn_s, bs_s, aw_s, P, V, R, b == 1, bl_new, gh_s, gl_s);
             lds_barrier();
             if (tid < R && (tid > 0 || b == 1)) bws[(size_t)t * a.C + fused_state(V, b, tid)] = bl_new[tid];
@@ -776,6 +776,11 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
             for (int kt = 0; kt < kFuKT; ++kt) {
                 const int k0 = 16 * (kFuKT * wave + kt);
+                if (kt + 1 < kFuKT) {
+#pragma unroll
+                    for (int ys = 0; ys < 3; ++ys)
+                        wt[(kt + 1) & 1][ys] = a.Wt[((size_t)min(kFuKT * wave + kt + 1, H / 16 - 1) * 3 + ys) * 64 + lane];
+                }
                 if (k0 < H) {
                     float colsum = 0.f;
 #pragma unroll
@@ -787,8 +792,8 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                                 const int off = (16 * mt + (lane & 15)) * kFuGS + 32 * ys + 8 * (lane >> 4);
                                 const bf16x8 ah = *(const bf16x8*)&gh_s[off];
                                 const bf16x8 al = *(const bf16x8*)&gl_s[off];
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[kt][ys], acc, 0, 0, 0);
-                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[kt][ys], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wt[kt & 1][ys], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wt[kt & 1][ys], acc, 0, 0, 0);
                             }
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
