@@ -234,6 +234,32 @@ __device__ __forceinline__ void buf_store2(float x, float y, buf_t r, unsigned v
     __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, f), r, (int)voff, (int)soff, 0);
 }
 
+// Lane -> pair of neighbouring own columns for the "all rows x own columns" frames.  Every lane with
+// columns stores 8 bytes per row: the pairs start behind the column that takes no label arcs (column 0 of
+// the first workgroup), and an odd number of columns ends in a pair that overlaps its predecessor by one
+// column (dup0: stored twice with the same value, counted once).  Only a workgroup with a single label
+// column has a lane with one column (single).
+struct C2Pair {
+    int c0;            // first own column of the lane (second: c0 + 1)
+    bool act, dup0, single;
+};
+__device__ __forceinline__ C2Pair c2_pair(int ci, bool in_group, int r0, int nr)
+{
+    C2Pair p;
+    const int cbase = r0 == 0 ? 1 : 0;
+    const int ncols = max(nr - cbase, 0);
+    const int np = (ncols + 1) / 2;
+    p.act = in_group && ci < np;
+    p.c0 = cbase + 2 * min(ci, max(np - 1, 0));
+    p.dup0 = false;
+    p.single = false;
+    if (p.c0 + 1 >= nr) {
+        if (ncols >= 2) { p.c0 = nr - 2; p.dup0 = true; }
+        else p.single = true;
+    }
+    return p;
+}
+
 // ------------------------------------------------------------------ alpha role
 template <bool GAMMA>
 __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
@@ -266,12 +292,15 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
     // third row, and a lane takes two neighbouring own columns (8-byte accesses): row 33 wave + 3 j + gq,
     // columns r0 + 2 ci, r0 + 2 ci + 1.  Lanes 51..63 idle.  The sums over rows end in wave 0, lane <-> own column.
     const int gq = lane / 17, ci = lane - 17 * gq;
-    const bool lact = lane < 17 * kC2FG && 2 * ci < g.nr;
-    const bool v0ok = lact && g.r0 + 2 * ci != 0;      // state 0 receives no label arcs
-    const bool v1ok = lact && 2 * ci + 1 < g.nr;
+    const C2Pair pr = c2_pair(ci, lane < 17 * kC2FG, g.r0, g.nr);    // (state 0 receives no label arcs)
+    const bool lact = pr.act;
+    const int c0 = pr.c0;
+    const bool v0ok = lact && !pr.dup0;                 // columns this lane adds up: the overlap only once
+    const bool v1ok = lact && !pr.single;
+    const bool need1 = g.nr - (g.r0 == 0 ? 1 : 0) == 1;  // (whole workgroup) one label column: 4-byte stores
     const int qF0 = kC2NQ * wave + gq;                  // first row of this lane
     const int jlim = lact ? (C - qF0 + kC2FG - 1) / kC2FG : 0;   // rows j < jlim exist
-    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + 2 * ci;
+    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + c0;
     const bool fok = lane < g.nr;                       // wave 0: lane <-> own column
     const int yF = min(g.r0 + lane, C - 1);
 
@@ -300,7 +329,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         const unsigned coffS = lane < g.nr ? (unsigned)lane * pitch + (unsigned)(cS * (int)sizeof(float)) : kC2Off;
         const unsigned soffS = (unsigned)(min(kC2PC + (lane & 7), C - 1) * (int)sizeof(float));
         const unsigned rbaseP = (unsigned)g.r0 * pitch;
-        const unsigned colF = (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned colF = (unsigned)((g.r0 + c0) * (int)sizeof(float));
         const unsigned coffF = (unsigned)gq * pitch + colF;
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
@@ -312,8 +341,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         // columns of its own repeats the address of a lane that has some (no traffic of its own); its
         // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
         // see through, so that the offsets are made where they are used instead of being kept.)
-        const int gqa = min(gq, kC2FG - 1), cia = min(gq < kC2FG ? ci : 16, max(g.nr - 1, 0) / 2);
-        const unsigned cola = (unsigned)((g.r0 + 2 * cia) * (int)sizeof(float));
+        const int gqa = min(gq, kC2FG - 1);
+        const unsigned cola = colF;          // (c2_pair gives a lane without columns the last pair's)
         const unsigned offA0 = (unsigned)(kC2NQ * wave + gqa) * pitch + cola;
         const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
         const int jla = max((C - (kC2NQ * wave + gqa) + kC2FG - 1) / kC2FG, 0);
@@ -413,8 +442,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             }
             // (maxima of integers through LDS atomics: the order does not matter, one barrier is enough)
             if (lane < 17 * kC2FG) {
-                atomicMax(&shc_s[B_ * kC2Own + 2 * ci], shift_for(v0ok ? m0 : LAST_NEG_INF));
-                atomicMax(&shc_s[B_ * kC2Own + 2 * ci + 1], shift_for(v1ok ? m1 : LAST_NEG_INF));
+                if (v0ok) atomicMax(&shc_s[B_ * kC2Own + c0], shift_for(m0));
+                if (v1ok) atomicMax(&shc_s[B_ * kC2Own + c0 + 1], shift_for(m1));
             }
             int touched = 0;
             if (wave == 0 && lane < kC2Own) {
@@ -461,9 +490,11 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             const float fsp = sp == kShiftNone ? 3.0e38f : (float)sp;
 #pragma unroll
             for (int r = 0; r < kC2PH; ++r) { EP[B_][r] = fast_exp2(fmaf(EP[B_][r], kLog2e, -fsp)); c2_pin(EP[B_][r]); }
-            const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
-            // (a column this lane does not have: a huge shift makes its E zero)
-            const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
+            int2 sc2;
+            sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
+            // (a column this lane does not have: a huge shift makes its E zero; the overlapping column keeps
+            // its E, which the marginals need)
+            const float fs0 = lact && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
             const float fs1 = v1ok && sc2.y != kShiftNone ? (float)sc2.y : 3.0e38f;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
@@ -530,23 +561,21 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     ps0 = fmaf(aq[j], EF0[B_][j], ps0);
                     ps1 = fmaf(aq[j], EF1[B_][j], ps1);
                 }
-                if (lane < 17 * kC2FG) {
-                    float2 pw;
-                    pw.x = ps0; pw.y = ps1;
-                    *(float2*)&red_s[slotF] = pw;
-                }
+                if (v0ok) red_s[slotF] = ps0;
+                if (v1ok) red_s[slotF + 1] = ps1;
                 C2_MARK(a, p, 6);
                 if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
                     const int sbk = __builtin_amdgcn_readlane(sbF[B_], g.k);
                     {
-                        // lanes with both columns store 8 bytes; the few with one (the odd last column, the
-                        // column next to the start state) store it with a second instruction
-                        const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
+                        // every lane with columns stores 8 bytes (see c2_pair); 4-byte stores only in a workgroup
+                        // with a single label column
+                        int2 sc2;
+                        sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
                         const float fc0 = a.scale * bF0[B_] * fast_exp2((float)((double)(sbk + S + sc2.x) - D2));
                         const float fc1 = a.scale * bF1[B_] * fast_exp2((float)((double)(sbk + S + sc2.y) - D2));
-                        const unsigned off2 = (v0ok && v1ok) ? coffF : kC2Off;
-                        const unsigned off1 = (v0ok == v1ok) ? kC2Off : (v0ok ? coffF : coffF + 4u);
+                        const unsigned off2 = (lact && !pr.single) ? coffF : kC2Off;
+                        const unsigned off1 = (lact && pr.single) ? coffF : kC2Off;
                         int jl = jlim;
                         c2_pin(jl);
 #pragma unroll
@@ -554,7 +583,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                             const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
                             const float g0 = aq[j] * EF0[B_][j] * fc0, g1 = aq[j] * EF1[B_][j] * fc1;
                             buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
-                            buf_store(v0ok ? g0 : g1, grs, j < jl ? off1 : kC2Off, so);
+                            if (need1) buf_store(g0, grs, j < jl ? off1 : kC2Off, so);
                             __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                         }
                     }
@@ -731,12 +760,15 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     // columns (8-byte accesses).  One shift per own column; the lanes' partial sums of a row meet in LDS,
     // where thread <-> row qT adds them up and publishes.
     const int gq = lane / 17, ci = lane - 17 * gq;
-    const bool lact = lane < 17 * kC2FG && 2 * ci < g.nr;
-    const bool v0ok = lact && g.r0 + 2 * ci != 0;      // column 0 is the empty label
-    const bool v1ok = lact && 2 * ci + 1 < g.nr;
+    const C2Pair pr = c2_pair(ci, lane < 17 * kC2FG, g.r0, g.nr);    // (column 0 is the empty label)
+    const bool lact = pr.act;
+    const int c0 = pr.c0;
+    const bool v0ok = lact && !pr.dup0;                 // columns this lane adds up: the overlap only once
+    const bool v1ok = lact && !pr.single;
+    const bool need1 = g.nr - (g.r0 == 0 ? 1 : 0) == 1;  // (whole workgroup) one label column: 4-byte stores
     const int qF0 = kC2NQ * wave + gq;                  // first row of this lane
     const int jlim = lact ? (C - qF0 + kC2FG - 1) / kC2FG : 0;   // rows j < jlim exist
-    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + 2 * ci;
+    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + c0;
     const bool fok = lane < g.nr;                       // wave 0: lane <-> own state (empty-label arcs)
     const int yF = min(g.r0 + lane, C - 1);
     const int qT = min(tid, C - 1);
@@ -784,7 +816,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned aoffF = (unsigned)((g.r0 + max(min(wave + min(lane, kC2RW - 1) * kC2Waves, g.nr - 1), 0)) * (int)sizeof(float));
         const unsigned offSt = validS ? (unsigned)(g.r0 + wave + rS * kC2Waves) * pitch + (unsigned)((kC2PC + sI) * (int)sizeof(float))
                                       : kC2Off;
-        const unsigned colF = (unsigned)((g.r0 + 2 * ci) * (int)sizeof(float));
+        const unsigned colF = (unsigned)((g.r0 + c0) * (int)sizeof(float));
         const unsigned coffF = (unsigned)gq * pitch + colF;
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
@@ -795,8 +827,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         // columns of its own repeats the address of a lane that has some (no traffic of its own); its
         // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
         // see through, so that the offsets are made where they are used instead of being kept.)
-        const int gqa = min(gq, kC2FG - 1), cia = min(gq < kC2FG ? ci : 16, max(g.nr - 1, 0) / 2);
-        const unsigned cola = (unsigned)((g.r0 + 2 * cia) * (int)sizeof(float));
+        const int gqa = min(gq, kC2FG - 1);
+        const unsigned cola = colF;          // (c2_pair gives a lane without columns the last pair's)
         const unsigned offA0 = (unsigned)(kC2NQ * wave + gqa) * pitch + cola;
         const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
         const int jla = max((C - (kC2NQ * wave + gqa) + kC2FG - 1) / kC2FG, 0);
@@ -913,8 +945,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             }
             // (maxima of integers through LDS atomics: the order does not matter, one barrier is enough)
             if (lane < 17 * kC2FG) {
-                atomicMax(&shc_s[B_ * kC2Own + 2 * ci], shift_for(v0ok ? m0 : LAST_NEG_INF));
-                atomicMax(&shc_s[B_ * kC2Own + 2 * ci + 1], shift_for(v1ok ? m1 : LAST_NEG_INF));
+                if (v0ok) atomicMax(&shc_s[B_ * kC2Own + c0], shift_for(m0));
+                if (v1ok) atomicMax(&shc_s[B_ * kC2Own + c0 + 1], shift_for(m1));
             }
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
@@ -931,9 +963,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const int sg = wave_max_dpp(fok ? shc_s[B_ * kC2Own + lane] : kShiftNone);
                 if (lane == 0) ctl_s[2 + B_] = sg;
             }
-            const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
-            // (a column this lane does not have: a huge shift makes its E zero)
-            const float fs0 = v0ok && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
+            int2 sc2;
+            sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
+            // (a column this lane does not have: a huge shift makes its E zero; the overlapping column keeps
+            // its E, which the marginals need)
+            const float fs0 = lact && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
             const float fs1 = v1ok && sc2.y != kShiftNone ? (float)sc2.y : 3.0e38f;
 #pragma unroll
             for (int j = 0; j < kC2FJ; ++j) {
@@ -1016,9 +1050,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     }
                 }
                 if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
-                C2_MARK(a, p, 6);
                 c2_barrier();
-                C2_MARK(a, p, 7);
                 if (wave == 0) {
                     const bool ok = lane < g.nr;
                     const float v = ok ? red_s[lane] : 0.f;
@@ -1062,7 +1094,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state):
                 // every lane its two columns of its eleven rows, then thread <-> row over the lanes' parts
                 {
-                    const float2 bt = *(const float2*)&bt_s[2 * ci];
+                    float2 bt;
+                    bt.x = v0ok ? bt_s[c0] : 0.f;          // (the overlapping column is counted by its other lane)
+                    bt.y = v1ok ? bt_s[c0 + 1] : 0.f;
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) {
                         const float pj = fmaf(EQ0[B_][j], bt.x, EQ1[B_][j] * bt.y);
@@ -1087,25 +1121,28 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (rowown) pub += bl_s[tid - g.r0];
                     xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
+                C2_MARK(a, p, 6);
                 if (GAMMA && iP >= ph1) {
                     // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
                     const unsigned gso = (unsigned)tP * frb;
-                    const int2 sc2 = *(const int2*)&shc_s[B_ * kC2Own + 2 * ci];
-                    const float f0 = a.scale * own_s[2 * ci] * fast_exp2((float)((double)(sc2.x + ek + samax) - D2));
-                    const float f1 = a.scale * own_s[2 * ci + 1] * fast_exp2((float)((double)(sc2.y + ek + samax) - D2));
-                    const unsigned off2 = (v0ok && v1ok) ? coffF : kC2Off;
-                    const unsigned off1 = (v0ok == v1ok) ? kC2Off : (v0ok ? coffF : coffF + 4u);
+                    int2 sc2;
+                    sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
+                    const float f0 = a.scale * own_s[c0] * fast_exp2((float)((double)(sc2.x + ek + samax) - D2));
+                    const float f1 = a.scale * own_s[c0 + 1] * fast_exp2((float)((double)(sc2.y + ek + samax) - D2));
+                    const unsigned off2 = (lact && !pr.single) ? coffF : kC2Off;
+                    const unsigned off1 = (lact && pr.single) ? coffF : kC2Off;
                     int jl = jlim;
                     c2_pin(jl);
                     float aq[kC2FJ];
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) aq[j] = afull_s[min(qF0 + kC2FG * j, 319)];
+                    C2_MARK(a, p, 7);
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) {
                         const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
                         const float g0 = aq[j] * EQ0[B_][j] * f0, g1 = aq[j] * EQ1[B_][j] * f1;
                         buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
-                        buf_store(v0ok ? g0 : g1, grs, j < jl ? off1 : kC2Off, so);
+                        if (need1) buf_store(g0, grs, j < jl ? off1 : kC2Off, so);
                         __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                     }
                     if (wave == 0 && fok) {
