@@ -53,9 +53,9 @@ constexpr int kC2FJ = 11;      // alpha F-step: rows per lane, kC2FG * kC2FJ = k
 constexpr int kC2Hdr = 264;    // largest number of states on this path (words of value per producer and slot)
 constexpr int kC2XS = 272;     // words per producer and slot
 constexpr int kC2RW = 5;       // rows per wave when a workgroup reads its own rows wave by wave: 8 * 5 >= 33
-constexpr int kC2NC = 4;       // ... in chunks of 64 columns; columns beyond 256 by one more instruction (see beta F-step)
+constexpr int kC2NC = 4;       // ... a lane takes four neighbouring columns; columns beyond 256 by one more instruction (see beta F-step)
 constexpr int kC2PH = 17;      // alpha P-step: a thread takes one half of the (at most 33) own rows: [0, 17) or [17, 33)
-constexpr int kC2PC = 256;     // columns that have a thread per half (alpha P-step) or a lane per chunk (beta F-step);
+constexpr int kC2PC = 256;     // columns that have a thread per half (alpha P-step) or a lane per four (beta F-step);
                                // the few beyond ("stragglers", at most 8) are taken lane-wise by single instructions
 constexpr int kC2Own = 40;     // LDS slots for own states
 // A per-lane buffer offset beyond every descriptor's size: the hardware's range check drops the lane's
@@ -233,6 +233,17 @@ __device__ __forceinline__ void buf_store2(float x, float y, buf_t r, unsigned v
     f.x = x; f.y = y;
     __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, f), r, (int)voff, (int)soff, 0);
 }
+
+// 16-byte buffer accesses (four neighbouring floats, 4-byte aligned)
+__device__ __forceinline__ float4 buf_load4(buf_t r, unsigned voff, unsigned soff)
+{
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+    static_assert(sizeof(v) == sizeof(float4), "16-byte buffer load");
+    return __builtin_bit_cast(float4, v);
+}
+// (No 16-byte buffer stores: with a scalar offset the compiler leaves no wait state between such a store
+// and the next instruction that overwrites its data registers, and on this chip lanes of the store were
+// then seen to pick up the new contents.  Stores are 8 bytes at most.)
 
 // Lane -> pair of neighbouring own columns for the "all rows x own columns" frames.  Every lane with
 // columns stores 8 bytes per row: the pairs start behind the column that takes no label arcs (column 0 of
@@ -748,13 +759,19 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int C = a.C, K = a.K, RPW = a.RPW;
-    // F-step: wave <-> own rows wave, wave + 8, ..., lanes <-> columns 0..255 in four chunks; the columns
-    // beyond (at most 8) of all rows of the wave by one more instruction: lane <-> (row lane & 7, column 256 + (lane >> 3))
+    // F-step: wave <-> own rows wave, wave + 8, ..., lane <-> four neighbouring columns cb4 .. cb4 + 3 of the
+    // first 256 (one 16-byte access per row); the columns beyond (at most 8) of all rows of the wave by one
+    // more instruction: lane <-> (row lane & 7, column 256 + (lane >> 3)).  Where the row ends inside or before
+    // a lane's four columns the lane takes the last four of the row instead: what it has in common with its
+    // predecessors enters no sum (their entry of the state vector is replaced by zero) and is stored twice
+    // with the same value, or not at all by a lane that lies wholly beyond the row.
     int nrw = (g.nr - wave + kC2Waves - 1) / kC2Waves;
     if (nrw < 0) nrw = 0;
     const int nstF = max(C - kC2PC, 0);
     const int rS = lane & 7, sI = lane >> 3;
     const bool validS = rS < nrw && rS < kC2RW && sI < nstF;
+    const int cb4 = min(4 * lane, min(C, kC2PC) - 4);      // (C >= 4 on this path)
+    const bool st4 = 4 * lane < min(C, kC2PC);             // the lane has a column nobody else has
     // P-step (all rows x own columns), the mirror image of the other role's F-step: wave <-> rows
     // [33 wave, 33 wave + 33), three groups of 17 lanes take every third row, a lane two neighbouring own
     // columns (8-byte accesses).  One shift per own column; the lanes' partial sums of a row meet in LDS,
@@ -794,16 +811,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         u64* xbase = a.xb + (size_t)g.cg * 2 * kClMaxK * kC2XS;
         const buf_t wrs = make_buf(wi, (unsigned)a.T * frb);
         const buf_t grs = make_buf(GAMMA ? (const float*)gi : wi, GAMMA ? (unsigned)a.T * frb : 0u);
-        // columns lane, lane + 64, ...: one register; a column beyond the row is neither read nor written
-        const unsigned coff0 = (unsigned)(lane * (int)sizeof(float));
-        auto coffj = [&](int j) __attribute__((always_inline)) {
-            return lane + 64 * j < C ? coff0 + 256u * (unsigned)j : kC2Off;
-        };
-        // loads: a column beyond the row is replaced by the last one, which leaves the row's maximum alone
-        // and meets a zero of the state vector in the sum, so the exp pass needs no mask
-        auto coffl = [&](int j) __attribute__((always_inline)) {
-            return (unsigned)(min(lane + 64 * j, C - 1) * (int)sizeof(float));
-        };
+        const unsigned coff4 = (unsigned)(cb4 * (int)sizeof(float));
+        const unsigned coff4s = st4 ? coff4 : kC2Off;
         auto roff = [&](int ri) __attribute__((always_inline)) {              // scalar
             return (unsigned)(g.r0 + min(wave + ri * kC2Waves, g.nr - 1)) * pitch;
         };
@@ -886,9 +895,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri) {
                 // (a wave without a row ri loads nothing: every lane out of range)
-#pragma unroll
-                for (int j = 0; j < kC2NC; ++j)
-                    EFb[B_][ri][j] = buf_load(wrs, ri < nrw ? coffl(j) : kC2Off, foF + roff(ri));
+                const float4 x = buf_load4(wrs, ri < nrw ? coff4 : kC2Off, foF + roff(ri));
+                EFb[B_][ri][0] = x.x; EFb[B_][ri][1] = x.y; EFb[B_][ri][2] = x.z; EFb[B_][ri][3] = x.w;
             }
             ESb[B_] = buf_load(wrs, offSt, foF);
             if (GAMMA) other(BUF, p);
@@ -908,29 +916,32 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         };
         auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            // F frame: one shift per own row (wave-uniform)
+            // F frame: one shift per own row (wave-uniform).  All five rows at once, without branches, so
+            // that their cross-lane reductions overlap: a row the wave does not have holds the zeros of its
+            // out-of-range loads, and what is made of them is used nowhere.
             float fsS = 3.0e38f;       // shift of the row of this lane's straggler element
             int touched = 0;
+            float mxr[kC2RW];
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri) {
-                if (ri < nrw) {
-                    float mx = (validS && rS == ri) ? ESb[B_] : LAST_NEG_INF;
+                float mx = (validS && rS == ri) ? ESb[B_] : LAST_NEG_INF;
 #pragma unroll
-                    for (int j = 0; j < kC2NC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
-                    mx = wave_max_dpp(mx);
-                    const int s = shift_for(mx);
-                    srF[B_][ri] = s;
-                    const float fs = (float)s;
-                    if (rS == ri) fsS = fs;
+                for (int j = 0; j < kC2NC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
+                mxr[ri] = mx;
+            }
 #pragma unroll
-                    for (int j = 0; j < kC2NC; ++j) EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
-                } else {
-                    srF[B_][ri] = kShiftNone;
+            for (int ri = 0; ri < kC2RW; ++ri) mxr[ri] = wave_max_dpp(mxr[ri]);
 #pragma unroll
-                    for (int j = 0; j < kC2NC; ++j) touched |= c2_touch(EFb[B_][ri][j]);
+            for (int ri = 0; ri < kC2RW; ++ri) {
+                const int s = shift_for(mxr[ri]);
+                srF[B_][ri] = ri < nrw ? s : kShiftNone;
+                const float fs = (float)s;
+                if (rS == ri) fsS = fs;
+#pragma unroll
+                for (int j = 0; j < kC2NC; ++j) {
+                    EFb[B_][ri][j] = fast_exp2(fmaf(EFb[B_][ri][j], kLog2e, -fs));
+                    c2_pin(EFb[B_][ri][j]);
                 }
-#pragma unroll
-                for (int j = 0; j < kC2NC; ++j) c2_pin(EFb[B_][ri][j]);
             }
             ESb[B_] = validS ? fast_exp2(fmaf(ESb[B_], kLog2e, -fsS)) : 0.f;
             c2_pin(ESb[B_]);
@@ -1013,43 +1024,57 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             {
                 const int tF = L - 1 - iF;
                 const int S = ctl_s[0];
-                float bv[kC2NC];
+                // bg: the columns' values; bv: the same with zero for columns that belong to a lane before
+                float bg[kC2NC], bv[kC2NC];
 #pragma unroll
-                for (int j = 0; j < kC2NC; ++j) bv[j] = full_s[lane + 64 * j];
+                for (int j = 0; j < kC2NC; ++j) {
+                    bg[j] = full_s[cb4 + j];
+                    bv[j] = cb4 + j >= 4 * lane ? bg[j] : 0.f;
+                }
                 // straggler element of this lane times its column's value; it joins the sum of its row
                 const float bS = full_s[min(kC2PC + sI, 319)];
                 const float sprod = ESb[B_] * bS;
                 float facS = 0.f;
+                C2_MARK(a, p, 6);
+                // all five rows at once, without branches: the cross-lane sums overlap (a row the wave does
+                // not have gives a sum that is not written)
+                float brow[kC2RW], tot[kC2RW];
+#pragma unroll
+                for (int ri = 0; ri < kC2RW; ++ri) brow[ri] = full_s[g.r0 + max(min(wave + ri * kC2Waves, g.nr - 1), 0)];
 #pragma unroll
                 for (int ri = 0; ri < kC2RW; ++ri) {
-                    if (ri < nrw) {
-                        const int rloc = wave + ri * kC2Waves;
-                        const float brow = full_s[g.r0 + rloc];
-                        // the empty label (column 0) returns to the row's own state
-                        float acc = EFb[B_][ri][0] * (lane == 0 ? brow : bv[0]);
+                    // the empty label (column 0) returns to the row's own state
+                    float acc = EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bv[0]);
 #pragma unroll
-                        for (int j = 1; j < kC2NC; ++j) acc = fmaf(EFb[B_][ri][j], bv[j], acc);
-                        if (nstF > 0) acc += rS == ri ? sprod : 0.f;
-                        const float tot = wave_sum_dpp(acc);
-                        if (lane == 0) {
-                            red_s[rloc] = tot;
-                            shr_s[rloc] = srF[B_][ri];
-                        }
-                        if (GAMMA && iF >= ph1) {
-                            const float arow = __shfl(aF[B_], ri, 64);
-                            const float fac = a.scale * arow *
-                                              fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
-                            if (rS == ri) facS = fac;
-                            const unsigned gso = (unsigned)tF * frb + roff(ri);
+                    for (int j = 1; j < kC2NC; ++j) acc = fmaf(EFb[B_][ri][j], bv[j], acc);
+                    if (nstF > 0) acc += rS == ri ? sprod : 0.f;
+                    tot[ri] = acc;
+                }
 #pragma unroll
-                            for (int j = 0; j < kC2NC; ++j) {
-                                const float bb = (j == 0 && lane == 0) ? brow : bv[j];
-                                buf_store(EFb[B_][ri][j] * bb * fac, grs, coffj(j), gso);
-                            }
-                        }
+                for (int ri = 0; ri < kC2RW; ++ri) tot[ri] = wave_sum_dpp(tot[ri]);
+#pragma unroll
+                for (int ri = 0; ri < kC2RW; ++ri) {
+                    const int rloc = wave + ri * kC2Waves;
+                    if (lane == 0 && ri < nrw) {
+                        red_s[rloc] = tot[ri];
+                        shr_s[rloc] = srF[B_][ri];
+                    }
+                }
+                if (GAMMA && iF >= ph1) {
+#pragma unroll
+                    for (int ri = 0; ri < kC2RW; ++ri) {
+                        const float arow = __shfl(aF[B_], ri, 64);
+                        const float fac = a.scale * arow *
+                                          fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
+                        if (rS == ri) facS = fac;
+                        const unsigned gso = (unsigned)tF * frb + roff(ri);
+                        const unsigned so4 = ri < nrw ? coff4s : kC2Off;
+                        buf_store2(EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bg[0]) * fac, EFb[B_][ri][1] * bg[1] * fac, grs, so4, gso);
+                        buf_store2(EFb[B_][ri][2] * bg[2] * fac, EFb[B_][ri][3] * bg[3] * fac, grs, so4 + 8u, gso);
                     }
                 }
                 if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
+                C2_MARK(a, p, 7);
                 c2_barrier();
                 if (wave == 0) {
                     const bool ok = lane < g.nr;
@@ -1121,7 +1146,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (rowown) pub += bl_s[tid - g.r0];
                     xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
-                C2_MARK(a, p, 6);
                 if (GAMMA && iP >= ph1) {
                     // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
                     const unsigned gso = (unsigned)tP * frb;
@@ -1136,7 +1160,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     float aq[kC2FJ];
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) aq[j] = afull_s[min(qF0 + kC2FG * j, 319)];
-                    C2_MARK(a, p, 7);
 #pragma unroll
                     for (int j = 0; j < kC2FJ; ++j) {
                         const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
