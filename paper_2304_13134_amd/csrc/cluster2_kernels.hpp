@@ -1076,7 +1076,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
                 C2_MARK(a, p, 7);
                 c2_barrier();
-                if (wave == 0) {
+                {
+                    // Every wave by itself, lane <-> own state: the same values from the same inputs, written
+                    // to the same cells; a wave reads them only after its own writes, so no second barrier.
                     const bool ok = lane < g.nr;
                     const float v = ok ? red_s[lane] : 0.f;
                     const int sc = (ok && v > 0.f) ? shr_s[lane] + float_exponent(v) : kShiftNone;
@@ -1089,12 +1091,11 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     }
                     const int ek = (ms == kShiftNone) ? S : S + ms;
                     if (lane == 0) ctl_s[1] = ek;
-                    if (tF >= mid) {
+                    if (wave == 0 && tF >= mid) {
                         if (ok) bh[(size_t)tF * C + g.r0 + lane] = own;
                         if (lane == 0) Sb[(size_t)tF * kClMaxK + g.k] = ek;
                     }
                 }
-                c2_barrier();
             }
             if (iP >= n) return false;
             C2_MARK(a, p, 2);
