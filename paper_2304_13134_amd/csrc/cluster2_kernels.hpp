@@ -58,6 +58,9 @@ constexpr int kC2PH = 17;      // alpha P-step: a thread takes one half of the (
 constexpr int kC2PC = 256;     // columns that have a thread per half (alpha P-step) or a lane per four (beta F-step);
                                // the few beyond ("stragglers", at most 8) are taken lane-wise by single instructions
 constexpr int kC2Own = 40;     // LDS slots for own states
+constexpr int kC2QL = 9;       // beta P-step: lanes per row, four neighbouring own columns each (16-byte loads)
+constexpr int kC2QG = 7;       // ... rows per instruction (63 lanes)
+constexpr int kC2QJ = 5;       // ... instructions per lane: row slots kC2QG * j + group, 35 >= kC2NQ
 // A per-lane buffer offset beyond every descriptor's size: the hardware's range check drops the lane's
 // store and returns zero for its load.  Replaces branches around accesses whose mask differs per lane.
 constexpr unsigned kC2Off = 0xFFFFFF00u;
@@ -78,8 +81,8 @@ constexpr int kC2RowF = kC2Strag + 8;               // [40] beta F-step: row sum
 constexpr int kC2RowS = kC2RowF + kC2Own;           // [40] beta F-step: row shifts (int)
 constexpr int kC2Bt = kC2RowS + kC2Own;             // [40] beta P-step: own states times their columns' shifts
 constexpr int kC2Afull = kC2Bt + kC2Own;            // [320] beta P-step: other side's vector (marginals)
-constexpr int kC2R2S = 20;                          // row pitch of the per-lane partials
-constexpr int kC2Red2 = kC2Afull + 320;             // [264][20] beta P-step: partial sums per row and lane
+constexpr int kC2R2S = 12;                          // row pitch of the per-lane partials (9 used, the rest stays zero)
+constexpr int kC2Red2 = kC2Afull + 320;             // [264][12] beta P-step: partial sums per row and lane
 constexpr int kC2Lds = kC2Red2 + kC2Waves * kC2NQ * kC2R2S;
 static_assert(kC2Red2 % 4 == 0 && kC2R2S % 4 == 0, "16-byte reads of the per-row partials");
 static_assert(kC2Red % 2 == 0 && kC2Shc % 2 == 0 && kC2Bt % 2 == 0 && kC2Own % 2 == 0, "8-byte LDS accesses");
@@ -269,6 +272,28 @@ __device__ __forceinline__ C2Pair c2_pair(int ci, bool in_group, int r0, int nr)
         else p.single = true;
     }
     return p;
+}
+
+// Lane -> four neighbouring own columns (beta P-step).  The quads start behind the column that takes no
+// label arcs; the last quad is moved back so that it ends with the last own column, and the ndup columns
+// it then has in common with its predecessor are stored twice with the same value and counted once.
+// (The workgroup has at least four such columns.)
+struct C2Quad {
+    int c0;            // first own column of the lane
+    int ndup;          // leading columns that belong to the lane before
+    bool act;
+};
+__device__ __forceinline__ C2Quad c2_quad(int ci, bool in_group, int r0, int nr)
+{
+    C2Quad q;
+    const int cbase = r0 == 0 ? 1 : 0;
+    const int ncols = max(nr - cbase, 4);
+    const int nq = (ncols + 3) / 4;
+    q.act = in_group && ci < nq;
+    const int want = cbase + 4 * min(ci, nq - 1);
+    q.c0 = max(min(want, nr - 4), 0);
+    q.ndup = want - q.c0;
+    return q;
 }
 
 // ------------------------------------------------------------------ alpha role
@@ -772,20 +797,21 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     const bool validS = rS < nrw && rS < kC2RW && sI < nstF;
     const int cb4 = min(4 * lane, min(C, kC2PC) - 4);      // (C >= 4 on this path)
     const bool st4 = 4 * lane < min(C, kC2PC);             // the lane has a column nobody else has
-    // P-step (all rows x own columns), the mirror image of the other role's F-step: wave <-> rows
-    // [33 wave, 33 wave + 33), three groups of 17 lanes take every third row, a lane two neighbouring own
-    // columns (8-byte accesses).  One shift per own column; the lanes' partial sums of a row meet in LDS,
-    // where thread <-> row qT adds them up and publishes.
-    const int gq = lane / 17, ci = lane - 17 * gq;
-    const C2Pair pr = c2_pair(ci, lane < 17 * kC2FG, g.r0, g.nr);    // (column 0 is the empty label)
-    const bool lact = pr.act;
-    const int c0 = pr.c0;
-    const bool v0ok = lact && !pr.dup0;                 // columns this lane adds up: the overlap only once
-    const bool v1ok = lact && !pr.single;
-    const bool need1 = g.nr - (g.r0 == 0 ? 1 : 0) == 1;  // (whole workgroup) one label column: 4-byte stores
+    // P-step (all rows x own columns): wave <-> rows [33 wave, 33 wave + 33); seven groups of nine lanes take
+    // every seventh row (row slot 7 j + group, j < 5; slots 33 and 34 are unused), a lane four neighbouring
+    // own columns (16-byte loads, 8-byte stores).  One shift per own column; the lanes' partial sums of a row
+    // meet in LDS, where thread <-> row qT adds them up and publishes.
+    const int gq = min(lane / kC2QL, kC2QG - 1), ci = lane - kC2QL * (lane / kC2QL);
+    const C2Quad qd = c2_quad(ci, lane < kC2QL * kC2QG, g.r0, g.nr);    // (column 0 is the empty label)
+    const bool lact = qd.act;
+    const int c0 = qd.c0;
+    bool vok[4];                                        // columns this lane adds up: the overlap only once
+#pragma unroll
+    for (int k = 0; k < 4; ++k) vok[k] = lact && k >= qd.ndup;
     const int qF0 = kC2NQ * wave + gq;                  // first row of this lane
-    const int jlim = lact ? (C - qF0 + kC2FG - 1) / kC2FG : 0;   // rows j < jlim exist
-    const int slotF = (wave * kC2FG + min(gq, kC2FG - 1)) * kC2Own + c0;
+    // rows j < jlim exist: inside the wave's 33 and inside the matrix
+    const int jlim = lact ? max(min((kC2NQ - gq + kC2QG - 1) / kC2QG, (C - qF0 + kC2QG - 1) / kC2QG), 0) : 0;
+    const bool slot4 = lane < kC2QL * kC2QG && gq < kC2NQ - kC2QG * (kC2QJ - 1);   // the lane's fifth row slot is one of the wave's
     const bool fok = lane < g.nr;                       // wave 0: lane <-> own state (empty-label arcs)
     const int yF = min(g.r0 + lane, C - 1);
     const int qT = min(tid, C - 1);
@@ -836,13 +862,12 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         // columns of its own repeats the address of a lane that has some (no traffic of its own); its
         // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
         // see through, so that the offsets are made where they are used instead of being kept.)
-        const int gqa = min(gq, kC2FG - 1);
-        const unsigned cola = colF;          // (c2_pair gives a lane without columns the last pair's)
-        const unsigned offA0 = (unsigned)(kC2NQ * wave + gqa) * pitch + cola;
+        const unsigned cola = colF;          // (c2_quad gives a lane without columns the last quad's)
+        const unsigned offA0 = (unsigned)qF0 * pitch + cola;
         const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
-        const int jla = max((C - (kC2NQ * wave + gqa) + kC2FG - 1) / kC2FG, 0);
+        const int jla = max(min((kC2NQ - gq + kC2QG - 1) / kC2QG, (C - qF0 + kC2QG - 1) / kC2QG), 0);
         auto rowcol = [&](int j, int jl) __attribute__((always_inline)) {
-            return j < jl ? offA0 + (unsigned)(kC2FG * j) * pitch : offAL;
+            return j < jl ? offA0 + (unsigned)(kC2QG * j) * pitch : offAL;
         };
         // b_L = 1 for every state, exponent 0
         for (int q = tid; q < 320; q += kC2Threads) full_s[q] = q < C ? 1.f : 0.f;
@@ -850,12 +875,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         if (tid < 32) ctl_s[tid] = 0;
         if (tid < 2 * kC2Own) shc_s[tid] = kShiftNone;
         if (tid < kC2Own) { bt_s[tid] = 0.f; bl_s[tid] = 0.f; }
+        for (int q = tid; q < kC2Waves * kC2NQ * kC2R2S; q += kC2Threads) red2_s[q] = 0.f;    // (cells beyond the ninth of a row stay zero)
         if (tid < g.nr) bh[(size_t)L * C + g.r0 + tid] = 1.f;
         if (tid == 0) Sb[(size_t)L * kClMaxK + g.k] = 0;
         __syncthreads();
 
         float EFb[2][kC2RW][kC2NC], ESb[2] = {0.f, 0.f};
-        float EQ0[2][kC2FJ], EQ1[2][kC2FJ];
+        float EQ[2][kC2QJ][4];
         float EB[2] = {0.f, 0.f};
         int srF[2][kC2RW];
         float aF[2] = {0.f, 0.f}, aP[2] = {0.f, 0.f};      // other side's vector for the marginals
@@ -907,10 +933,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             int jl = jla;
             c2_pin(jl);
 #pragma unroll
-            for (int j = 0; j < kC2FJ; ++j) {
-                const float2 x = buf_load2(wrs, rowcol(j, jl), foP);
-                EQ0[B_][j] = x.x;
-                EQ1[B_][j] = x.y;
+            for (int j = 0; j < kC2QJ; ++j) {
+                const float4 x = buf_load4(wrs, rowcol(j, jl), foP);
+                EQ[B_][j][0] = x.x; EQ[B_][j][1] = x.y; EQ[B_][j][2] = x.z; EQ[B_][j][3] = x.w;
             }
             EB[B_] = buf_load(wrs, wave == 0 && fok ? rowB : kC2Off, foP);           // w[q][0] of the own states
         };
@@ -948,17 +973,15 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             halfway();
             // P frame: one shift per own column, common to all waves and row groups; the empty-label weight
             // of an own state q shares the shift of the column of q, whose value it multiplies
-            float m0 = LAST_NEG_INF, m1 = LAST_NEG_INF;
+            float mq[4] = {LAST_NEG_INF, LAST_NEG_INF, LAST_NEG_INF, LAST_NEG_INF};
 #pragma unroll
-            for (int j = 0; j < kC2FJ; ++j) {
-                m0 = fmaxf(m0, EQ0[B_][j]);
-                m1 = fmaxf(m1, EQ1[B_][j]);
-            }
+            for (int j = 0; j < kC2QJ; ++j)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) mq[k] = fmaxf(mq[k], EQ[B_][j][k]);
             // (maxima of integers through LDS atomics: the order does not matter, one barrier is enough)
-            if (lane < 17 * kC2FG) {
-                if (v0ok) atomicMax(&shc_s[B_ * kC2Own + c0], shift_for(m0));
-                if (v1ok) atomicMax(&shc_s[B_ * kC2Own + c0 + 1], shift_for(m1));
-            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (vok[k]) atomicMax(&shc_s[B_ * kC2Own + c0 + k], shift_for(mq[k]));
             if (wave == 0 && lane < kC2Own) {
                 if (!fok) EB[B_] = LAST_NEG_INF;
                 atomicMax(&shc_s[B_ * kC2Own + lane], shift_for(EB[B_]));
@@ -974,18 +997,21 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const int sg = wave_max_dpp(fok ? shc_s[B_ * kC2Own + lane] : kShiftNone);
                 if (lane == 0) ctl_s[2 + B_] = sg;
             }
-            int2 sc2;
-            sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
-            // (a column this lane does not have: a huge shift makes its E zero; the overlapping column keeps
-            // its E, which the marginals need)
-            const float fs0 = lact && sc2.x != kShiftNone ? (float)sc2.x : 3.0e38f;
-            const float fs1 = v1ok && sc2.y != kShiftNone ? (float)sc2.y : 3.0e38f;
+            // (a lane without columns: a huge shift makes its E zero; the overlapping columns keep their E,
+            // which the marginals need)
+            float fsq[4];
 #pragma unroll
-            for (int j = 0; j < kC2FJ; ++j) {
-                EQ0[B_][j] = fast_exp2(fmaf(EQ0[B_][j], kLog2e, -fs0));
-                EQ1[B_][j] = fast_exp2(fmaf(EQ1[B_][j], kLog2e, -fs1));
-                c2_pin(EQ0[B_][j]); c2_pin(EQ1[B_][j]);
+            for (int k = 0; k < 4; ++k) {
+                const int sc = shc_s[B_ * kC2Own + c0 + k];
+                fsq[k] = lact && sc != kShiftNone ? (float)sc : 3.0e38f;
             }
+#pragma unroll
+            for (int j = 0; j < kC2QJ; ++j)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    EQ[B_][j][k] = fast_exp2(fmaf(EQ[B_][j][k], kLog2e, -fsq[k]));
+                    c2_pin(EQ[B_][j][k]);
+                }
             if (wave == 0) EB[B_] = fast_exp2(fmaf(EB[B_], kLog2e, -(float)shc_s[B_ * kC2Own + min(lane, kC2Own - 1)]));
             c2_pin(EB[B_]);
             if (GAMMA) { c2_pin(aF[B_]); c2_pin(aP[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]); }
@@ -1120,13 +1146,15 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 // b'[q] = sum over the own label columns of M[q][y] b[y]  (+ M[q][0] b[q] for an own state):
                 // every lane its two columns of its eleven rows, then thread <-> row over the lanes' parts
                 {
-                    float2 bt;
-                    bt.x = v0ok ? bt_s[c0] : 0.f;          // (the overlapping column is counted by its other lane)
-                    bt.y = v1ok ? bt_s[c0 + 1] : 0.f;
+                    float bt[4];                    // (an overlapping column is counted by its other lane)
 #pragma unroll
-                    for (int j = 0; j < kC2FJ; ++j) {
-                        const float pj = fmaf(EQ0[B_][j], bt.x, EQ1[B_][j] * bt.y);
-                        if (lane < 17 * kC2FG) red2_s[(qF0 + kC2FG * j) * kC2R2S + ci] = pj;
+                    for (int k = 0; k < 4; ++k) bt[k] = vok[k] ? bt_s[c0 + k] : 0.f;
+#pragma unroll
+                    for (int j = 0; j < kC2QJ; ++j) {
+                        float pj = EQ[B_][j][0] * bt[0];
+#pragma unroll
+                        for (int k = 1; k < 4; ++k) pj = fmaf(EQ[B_][j][k], bt[k], pj);
+                        if (j < kC2QJ - 1 ? lane < kC2QL * kC2QG : slot4) red2_s[(qF0 + kC2QG * j) * kC2R2S + ci] = pj;
                     }
                     if (wave == 0 && lane < kC2Own) bl_s[lane] = EB[B_] * bt_s[lane];
                 }
@@ -1140,33 +1168,31 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 c2_barrier();
                 if (rowok && exch) {
                     const float4* rp4 = (const float4*)&red2_s[tid * kC2R2S];
-                    const float4 x0 = rp4[0], x1 = rp4[1], x2 = rp4[2], x3 = rp4[3];
-                    float pub = ((x0.x + x0.y) + (x0.z + x0.w)) + ((x1.x + x1.y) + (x1.z + x1.w)) +
-                                ((x2.x + x2.y) + (x2.z + x2.w)) + ((x3.x + x3.y) + (x3.z + x3.w)) +
-                                red2_s[tid * kC2R2S + 16];
+                    const float4 x0 = rp4[0], x1 = rp4[1], x2 = rp4[2];
+                    float pub = ((x0.x + x0.y) + (x0.z + x0.w)) + ((x1.x + x1.y) + (x1.z + x1.w)) + ((x2.x + x2.y) + (x2.z + x2.w));
                     if (rowown) pub += bl_s[tid - g.r0];
                     xpublish(xs + (size_t)g.k * kC2XS + tid, c2_pack(pub, tag, (sg == kShiftNone ? ek : ek + sg) - ctl_s[0]));
                 }
                 if (GAMMA && iP >= ph1) {
                     // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z
                     const unsigned gso = (unsigned)tP * frb;
-                    int2 sc2;
-                    sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
-                    const float f0 = a.scale * own_s[c0] * fast_exp2((float)((double)(sc2.x + ek + samax) - D2));
-                    const float f1 = a.scale * own_s[c0 + 1] * fast_exp2((float)((double)(sc2.y + ek + samax) - D2));
-                    const unsigned off2 = (lact && !pr.single) ? coffF : kC2Off;
-                    const unsigned off1 = (lact && pr.single) ? coffF : kC2Off;
+                    float fq[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        fq[k] = a.scale * own_s[c0 + k] *
+                                fast_exp2((float)((double)(shc_s[B_ * kC2Own + c0 + k] + ek + samax) - D2));
+                    const unsigned offq = lact ? coffF : kC2Off;
                     int jl = jlim;
                     c2_pin(jl);
-                    float aq[kC2FJ];
+                    float aq[kC2QJ];
 #pragma unroll
-                    for (int j = 0; j < kC2FJ; ++j) aq[j] = afull_s[min(qF0 + kC2FG * j, 319)];
+                    for (int j = 0; j < kC2QJ; ++j) aq[j] = afull_s[min(qF0 + kC2QG * j, 319)];
 #pragma unroll
-                    for (int j = 0; j < kC2FJ; ++j) {
-                        const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
-                        const float g0 = aq[j] * EQ0[B_][j] * f0, g1 = aq[j] * EQ1[B_][j] * f1;
-                        buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
-                        if (need1) buf_store(g0, grs, j < jl ? off1 : kC2Off, so);
+                    for (int j = 0; j < kC2QJ; ++j) {
+                        const unsigned so = gso + rowF0 + (unsigned)(kC2QG * j) * pitch;
+                        const unsigned oj = j < jl ? offq : kC2Off;
+                        buf_store2(aq[j] * EQ[B_][j][0] * fq[0], aq[j] * EQ[B_][j][1] * fq[1], grs, oj, so);
+                        buf_store2(aq[j] * EQ[B_][j][2] * fq[2], aq[j] * EQ[B_][j][3] * fq[3], grs, oj + 8u, so);
                         __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                     }
                     if (wave == 0 && fok) {

@@ -170,7 +170,7 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     p.ok = true;
     // the second-generation kernel (one exchange per two frames) unless LAST_CLUSTER_V2=0 asks for the first
     const char* v2 = std::getenv("LAST_CLUSTER_V2");
-    p.v2 = !(v2 && v2[0] == '0') && s.C <= kC2Hdr && s.C >= 4;   // (16-byte row accesses: four columns at least)
+    p.v2 = !(v2 && v2[0] == '0') && s.C <= kC2Hdr && s.C >= 5;   // (16-byte accesses: four label columns at least)
     return p;
 }
 
