@@ -92,7 +92,8 @@ def test_config2_reduced_spans_several_tiles():
 
 
 def test_ragged_vocabulary_sizes():
-    for V in (1, 2, 63, 64, 65, 130):
+    # (3 and 4: the smallest label sets on either side of the clustered kernel's four-column accesses)
+    for V in (1, 2, 3, 4, 5, 8, 32, 33, 34, 63, 64, 65, 130):
         announce("ragged V", V)
         cfg = workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9)
         check_posteriors(cfg)
