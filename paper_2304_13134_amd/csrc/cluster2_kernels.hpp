@@ -36,8 +36,8 @@
 // exp pass); all waits are bounded (status 5 instead of a hang).
 //
 // Access patterns.  "Own rows x all columns" (alpha P-step, beta F-step) is read row-contiguous.  "All
-// rows x own columns" (alpha F-step, beta P-step) is read three rows per instruction, 17 lanes x 8 bytes
-// per row.  Masks are not branches: a lane that must not store gets a buffer offset beyond the
+// rows x own columns" is read three rows per instruction, 17 lanes x 8 bytes per row (alpha F-step), or
+// seven rows per instruction, 9 lanes x 16 bytes per row (beta P-step).  Masks are not branches: a lane that must not store gets a buffer offset beyond the
 // descriptor (dropped by the hardware's range check), and loads beyond the matrix fetch a copy of the
 // last row or column, which meets a zero of the state vector in every sum.
 #pragma once
