@@ -162,9 +162,11 @@ __device__ __forceinline__ void c2_gather_look(const u64* xs, int K, int C, C2Lo
         if (kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + q);
 }
 
-// Every thread calls; ends with a workgroup barrier.
+// Every thread calls; ends with a workgroup barrier.  `after_poll` runs once all words are there, before
+// they are added up: the place for memory requests that should not stand between the polls and their data.
+template <typename AfterPoll>
 __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
-                                          int* ctl_s, int limit, int& dead, C2Look& lk)
+                                          int* ctl_s, int limit, int& dead, C2Look& lk, AfterPoll&& after_poll)
 {
     const int tid = threadIdx.x;
     const int S0 = ctl_s[0];           // exponent the producers' exponents are relative to
@@ -182,6 +184,7 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
             __builtin_amdgcn_s_sleep(1);
             c2_gather_look(xs, K, C, lk);
         }
+        after_poll();
         int href = -(1 << 30);
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
@@ -742,7 +745,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
                 C2_MARK(a, p, 4);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk);
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk, [] {});
                     C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP + 1 <= mid) {
@@ -1029,13 +1032,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         issueF(std::integral_constant<int, 0>(), 0);
         issueP(std::integral_constant<int, 0>(), 0);
         prep(std::integral_constant<int, 0>(), [] {});
+        issueF(std::integral_constant<int, 1>(), 1);
 
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
             constexpr int B_ = decltype(BUF)::value;
             const int iF = 2 * p, iP = 2 * p + 1;
             if (iF >= n) return false;
             C2_MARK(a, p, 0);
-            issueF(std::integral_constant<int, B_ ^ 1>(), p + 1);
             C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
             if (iF == ph1 && !met) {
@@ -1208,8 +1211,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 C2Look lk;
                 prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
                 C2_MARK(a, p, 4);
+                // The F frame of the pair after the next goes into the registers this pair's F-step has
+                // finished with; requested once the exchanged words are there, the requests pass the address
+                // path while the words are added up.
+                if (!exch) issueF(std::integral_constant<int, B_>(), p + 2);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk);
+                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk,
+                              [&]() __attribute__((always_inline)) { issueF(std::integral_constant<int, B_>(), p + 2); });
                     C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP >= mid) {
