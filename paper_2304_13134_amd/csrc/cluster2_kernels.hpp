@@ -1032,6 +1032,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         issueF(std::integral_constant<int, 0>(), 0);
         issueP(std::integral_constant<int, 0>(), 0);
         prep(std::integral_constant<int, 0>(), [] {});
+        issueP(std::integral_constant<int, 1>(), 1);
         issueF(std::integral_constant<int, 1>(), 1);
 
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
@@ -1128,7 +1129,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             }
             if (iP >= n) return false;
             C2_MARK(a, p, 2);
-            issueP(std::integral_constant<int, B_ ^ 1>(), p + 1);
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) {
                 meet();
@@ -1206,6 +1206,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     }
                 }
                 C2_MARK(a, p, 3);
+                // the P frame of the pair after the next, into the registers this P-step has finished with
+                issueP(std::integral_constant<int, B_>(), p + 2);
                 // first look at the exchange halfway through the exp pass: early enough for the round trip to
                 // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
                 C2Look lk;
