@@ -1207,11 +1207,14 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 }
                 C2_MARK(a, p, 3);
                 // the P frame of the pair after the next, into the registers this P-step has finished with
-                issueP(std::integral_constant<int, B_>(), p + 2);
+                if (wave < 4) issueP(std::integral_constant<int, B_>(), p + 2);
                 // first look at the exchange halfway through the exp pass: early enough for the round trip to
                 // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
                 C2Look lk;
-                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
+                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) {
+                    if (wave >= 4) issueP(std::integral_constant<int, B_>(), p + 2);
+                    if (exch) c2_gather_look(xs, K, C, lk);
+                });
                 C2_MARK(a, p, 4);
                 // The F frame of the pair after the next goes into the registers this pair's F-step has
                 // finished with; requested once the exchanged words are there, the requests pass the address
