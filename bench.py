@@ -32,7 +32,7 @@ BYTES_PER_ARC = 12.0           # forward reads w (4), backward reads w (4) and w
 # HBM traffic per forward+backward launch measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/cluster2_kernel_B16_T500_V256.md: 4.344 GB fetched + 2.260 GB written.
-MEASURED_TRAFFIC_BYTES = 6.606e9
+MEASURED_TRAFFIC_BYTES = 6.582e9
 
 
 def time_region(fn, steps, warmup):
