@@ -44,7 +44,14 @@
  *   3 reference length outside [0,Umax]; 4 infeasible (reference longer than
  *   the number of frames: numerator = -inf, its marginals are 0);
  *   5 the cooperating workgroups of an item timed out waiting for each other
- *   (results of that item are undefined; never expected in normal operation).
+ *   (results of that item are undefined; never expected in normal operation);
+ *   6 the weights of the item span more dynamic range than the bandwidth path
+ *   for dense bigram lattices guarantees for marginals (it keeps state vectors
+ *   in scaled float32: entries more than 2^126 below the largest of a frame
+ *   are zero there).  dist is still exact; marginals of arcs that leave such
+ *   states may be lost.  Not raised for weights within about +-50; setting the
+ *   environment variable LAST_FORCE_SOLO=1 selects the log-domain kernels,
+ *   which have no such limit.
  * Items with status 1..3 get dist = NaN and zero gradients.
  * Frames t >= len[b] do not exist for item b: their weights are never read
  * into a result, their marginals are 0 and their path entries are -1.

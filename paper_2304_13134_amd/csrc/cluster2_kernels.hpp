@@ -135,6 +135,21 @@ __device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e, zero s
     return (v == 0.f) ? 0.f : __builtin_ldexpf(v, max(e, -300));
 }
 
+// 2^(e - D) for the marginals.  e adds up the exponents of three maxima (state vector, weights, state
+// vector) that need not be reached by the same arc.  The three factors it scales are held relative to
+// those maxima in float32, so whatever lies more than 2^126 below its maximum has already become zero:
+// harmless in every sum, but an arc can make up for a small state value by a large weight, and its marginal
+// is then lost.  With e - D <= kC2RangeBits such a lost marginal is below 2^(kC2RangeBits - 126); beyond,
+// the item is flagged (status kItemRange) and the factor is capped so that it stays finite (an infinite
+// factor next to an underflowed product would give NaN).
+constexpr float kC2RangeBits = 80.f;
+__device__ __forceinline__ float c2_marginal_scale(int e, double D2, int* ctl_s)
+{
+    const float x = (float)((double)e - D2);
+    if (x > kC2RangeBits) ctl_s[11] = 1;
+    return fast_exp2(fminf(x, 126.f));
+}
+
 // Exchange word of this kernel: [value:32 | tag:16 | exponent:16].  The exponent is the producer's,
 // relative to the exponent of the vector both sides already share (the one the pair started from), so
 // that it fits 16 bits whatever the length of the sequence; it is the same in all words of a producer.
@@ -611,8 +626,8 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         // with a single label column
                         int2 sc2;
                         sc2.x = shc_s[B_ * kC2Own + c0]; sc2.y = shc_s[B_ * kC2Own + c0 + 1];
-                        const float fc0 = a.scale * bF0[B_] * fast_exp2((float)((double)(sbk + S + sc2.x) - D2));
-                        const float fc1 = a.scale * bF1[B_] * fast_exp2((float)((double)(sbk + S + sc2.y) - D2));
+                        const float fc0 = a.scale * bF0[B_] * c2_marginal_scale(sbk + S + sc2.x, D2, ctl_s);
+                        const float fc1 = a.scale * bF1[B_] * c2_marginal_scale(sbk + S + sc2.y, D2, ctl_s);
                         const unsigned off2 = (lact && !pr.single) ? coffF : kC2Off;
                         const unsigned off1 = (lact && pr.single) ? coffF : kC2Off;
                         int jl = jlim;
@@ -627,7 +642,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         }
                     }
                     if (wave == 0 && fok) {
-                        const float fcb = a.scale * bFb[B_] * fast_exp2((float)((double)(sbk + S + shc_s[B_ * kC2Own + lane]) - D2));
+                        const float fcb = a.scale * bFb[B_] * c2_marginal_scale(sbk + S + shc_s[B_ * kC2Own + lane], D2, ctl_s);
                         buf_store(full_s[yF] * EB[B_] * fcb, grs, rowB, gso);
                     }
                 }
@@ -717,8 +732,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     const int sbk = __shfl(sbP[B_], kP, 64);       // every lane takes part
                     const unsigned gso = (unsigned)tP * frb + rbaseP;
                     {
-                        const float kx = (float)((double)(sbk + sp + ek) - D2);
-                        const float fy = (sp == kShiftNone) ? 0.f : a.scale * fast_exp2(kx) * (cP == 0 ? 1.f : bPv[B_]);
+                        const float fy = (sp == kShiftNone) ? 0.f : a.scale * c2_marginal_scale(sbk + sp + ek, D2, ctl_s) * (cP == 0 ? 1.f : bPv[B_]);
                         // the empty label (column 0) returns to the row's own state: its thread reads the
                         // products instead of the own states; all reads first, then the stores
                         const float* osrc = (cP == 0 ? bo_s : own_s) + rP0;
@@ -734,7 +748,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         const int sbkS = __builtin_amdgcn_readlane(sbP[B_], cS / RPW);
                         const float bS = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bSt[B_]), sS));
                         const float fyS = (ssp == kShiftNone) ? 0.f
-                                          : a.scale * bS * fast_exp2((float)((double)(sbkS + ssp + ek) - D2));
+                                          : a.scale * bS * c2_marginal_scale(sbkS + ssp + ek, D2, ctl_s);
                         buf_store(own_s[min(lane, kC2Own - 1)] * ES[B_] * fyS, grs, coffS, gso);
                     }
                 }
@@ -763,6 +777,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         }
         __syncthreads();
         if (!met) meet();
+        if (tid == 0 && ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
         if (g.k == 0 && tid == 0 && (ctl_s[8] || dead) && a.item_status && !bad) a.item_status[b] = kItemTimeout;
         __syncthreads();
     }
@@ -1095,7 +1110,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     for (int ri = 0; ri < kC2RW; ++ri) {
                         const float arow = __shfl(aF[B_], ri, 64);
                         const float fac = a.scale * arow *
-                                          fast_exp2((float)((double)(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S) - D2));
+                                          c2_marginal_scale(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S, D2, ctl_s);
                         if (rS == ri) facS = fac;
                         const unsigned gso = (unsigned)tF * frb + roff(ri);
                         const unsigned so4 = ri < nrw ? coff4s : kC2Off;
@@ -1183,7 +1198,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
                         fq[k] = a.scale * own_s[c0 + k] *
-                                fast_exp2((float)((double)(shc_s[B_ * kC2Own + c0 + k] + ek + samax) - D2));
+                                c2_marginal_scale(shc_s[B_ * kC2Own + c0 + k] + ek + samax, D2, ctl_s);
                     const unsigned offq = lact ? coffF : kC2Off;
                     int jl = jlim;
                     c2_pin(jl);
@@ -1201,7 +1216,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (wave == 0 && fok) {
                         // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
                         const float fb = a.scale * own_s[lane] *
-                                         fast_exp2((float)((double)(shc_s[B_ * kC2Own + lane] + ek + samax) - D2));
+                                         c2_marginal_scale(shc_s[B_ * kC2Own + lane] + ek + samax, D2, ctl_s);
                         buf_store(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
                     }
                 }
@@ -1240,6 +1255,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         }
         __syncthreads();
         if (!met) meet();
+        if (tid == 0 && ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
         __syncthreads();
     }
 }

@@ -113,6 +113,6 @@ __device__ __forceinline__ float block_sum(float v, float* red)
 
 // per-item status codes written to item_status (see last.h)
 enum : int { kItemOk = 0, kItemBadLength = 1, kItemBadLabel = 2, kItemBadRefLength = 3,
-             kItemInfeasible = 4, kItemTimeout = 5 };
+             kItemInfeasible = 4, kItemTimeout = 5, kItemRange = 6 };
 
 }  // namespace last

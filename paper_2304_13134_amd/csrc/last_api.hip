@@ -153,7 +153,7 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     ClusterPlan p{};
     const char* force = std::getenv("LAST_FORCE_SOLO");
     if (force && force[0] == '1') return p;
-    if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.T < 1) return p;
+    if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.C < 5 || s.T < 1) return p;   // (tiny label sets: one workgroup per item)
     // one item must fit a 32-bit buffer descriptor
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;
     p.K = (s.C + 32) / 33;                   // at most 33 rows per workgroup

@@ -138,6 +138,46 @@ def test_one_workgroup_shortest_path_kernels(monkeypatch):
         check_path(workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9))
 
 
+def forbid_arcs(cfg, seed):
+    """A third of the arcs, every arc out of state 5 and label 7 at frame 3 get weight -1e4."""
+    rng = np.random.default_rng(seed)
+    w = cfg["w"]
+    w[rng.random(w.shape) < 0.3] = -1.0e4
+    w[:, :, 5, :] = -1.0e4
+    w[:, 3, :, 7] = -1.0e4
+    return cfg
+
+
+def test_wide_dynamic_range_is_exact_or_flagged(monkeypatch):
+    # weights of up to about +-50 with forbidden arcs: exact on the bandwidth path, status 0
+    announce("wide range: sigma 12 with forbidden arcs")
+    cfg = forbid_arcs(workloads.dense(B=3, T=14, V=256, order=1, sigma=12.0, seed=1200, len_lo=11, len_hi=14), 5)
+    check_posteriors(cfg)
+    check_path(cfg)
+    # far beyond what scaled float32 state vectors hold (weights of +-180): the distance is still right and
+    # every item says that its marginals may not be (status 6), without NaN
+    announce("wide range: sigma 40")
+    cfg = forbid_arcs(workloads.dense(B=2, T=11, V=130, order=1, sigma=40.0, seed=4130, len_lo=8, len_hi=11), 5)
+    D, gamma, status = run_posteriors(cfg)
+    _, D_o = oracle.forward(cfg["w"], cfg["lengths"], 1)
+    gamma_o = oracle.posteriors(cfg["w"], cfg["lengths"], 1)
+    assert_dist_close(D, D_o)
+    assert not np.any(np.isnan(gamma))
+    for b in range(cfg["B"]):
+        assert status[b] in (0, 6)
+        if status[b] == 0:
+            assert np.max(np.abs(gamma[b] - gamma_o[b])) <= TOL_POST_ABS
+    check_path(cfg)
+    # the log-domain kernels take the same input without a flag; float32 weights of this size resolve
+    # 2^-16, so the marginals agree to a few 1e-5 only
+    announce("wide range: sigma 40, one workgroup per item")
+    monkeypatch.setenv("LAST_FORCE_SOLO", "1")
+    D, gamma, status = run_posteriors(cfg)
+    assert np.all(status == 0)
+    assert_dist_close(D, D_o)
+    assert np.max(np.abs(gamma - gamma_o)) <= 5.0e-5
+
+
 def test_edge_lengths_and_status():
     announce("edge lengths: 0, 1, T, invalid")
     cfg = workloads.dense(B=5, T=6, V=5, order=1, seed=5)
