@@ -874,12 +874,12 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         const unsigned rowF0 = (unsigned)(kC2NQ * wave) * pitch;     // scalar: first row of this wave
         const unsigned rowB = (unsigned)yF * pitch;                  // row of the own state (empty-label weight)
 
-        // Offset of this lane's element pair in row j of its rows.  A row beyond the matrix is replaced by
-        // the last row: what is loaded there is finite, takes part in no maximum that matters and meets a
-        // zero of the state vector in every sum, so the exp pass needs no mask per element.  A lane without
-        // columns of its own repeats the address of a lane that has some (no traffic of its own); its
-        // elements are zeroed by its shift.  (jl: the number of rows, through a register the compiler cannot
-        // see through, so that the offsets are made where they are used instead of being kept.)
+        // Offset of this lane's four elements in row slot j.  A slot beyond the wave's rows or beyond the
+        // matrix is replaced by the last row: what is loaded there is finite, takes part in no maximum that
+        // matters, and is neither added up nor stored.  A lane without columns of its own repeats the address
+        // of a lane that has some (no traffic of its own); its elements are zeroed by its shift.  (jl: the
+        // number of slots, through a register the compiler cannot see through, so that the offsets are made
+        // where they are used instead of being kept.)
         const unsigned cola = colF;          // (c2_quad gives a lane without columns the last quad's)
         const unsigned offA0 = (unsigned)qF0 * pitch + cola;
         const unsigned offAL = (unsigned)(C - 1) * pitch + cola;
