@@ -262,6 +262,27 @@ __device__ __forceinline__ float4 buf_load4(buf_t r, unsigned voff, unsigned sof
     static_assert(sizeof(v) == sizeof(float4), "16-byte buffer load");
     return __builtin_bit_cast(float4, v);
 }
+// Writing marginals: overwrite, or (ACC) add to what the gradient tensor holds.  A lane with the out-of-range
+// offset reads zero and its store is dropped.  Overwriting, the columns that two lanes have in common (see
+// c2_pair, c2_quad) are simply written twice with the same value; adding, each element is added by the one
+// lane that counts it (ok0, ok1), four bytes at a time.
+template <bool ACC>
+__device__ __forceinline__ void c2_put(float x, buf_t r, unsigned voff, unsigned soff)
+{
+    if constexpr (ACC) x += buf_load(r, voff, soff);
+    buf_store(x, r, voff, soff);
+}
+template <bool ACC>
+__device__ __forceinline__ void c2_put2(float x, float y, buf_t r, unsigned voff, unsigned soff, bool ok0, bool ok1)
+{
+    if constexpr (ACC) {
+        c2_put<true>(x, r, ok0 ? voff : kC2Off, soff);
+        c2_put<true>(y, r, ok1 ? voff + 4u : kC2Off, soff);
+    } else {
+        buf_store2(x, y, r, voff, soff);
+    }
+}
+
 // (No 16-byte buffer stores: with a scalar offset the compiler leaves no wait state between such a store
 // and the next instruction that overwrites its data registers, and on this chip lanes of the store were
 // then seen to pick up the new contents.  Stores are 8 bytes at most.)
@@ -315,7 +336,7 @@ __device__ __forceinline__ C2Quad c2_quad(int ci, bool in_group, int r0, int nr)
 }
 
 // ------------------------------------------------------------------ alpha role
-template <bool GAMMA>
+template <bool GAMMA, bool ACC>
 __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                             unsigned& gstep, unsigned& ptag)
 {
@@ -636,14 +657,14 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         for (int j = 0; j < kC2FJ; ++j) {
                             const unsigned so = gso + rowF0 + (unsigned)(kC2FG * j) * pitch;
                             const float g0 = aq[j] * EF0[B_][j] * fc0, g1 = aq[j] * EF1[B_][j] * fc1;
-                            buf_store2(g0, g1, grs, j < jl ? off2 : kC2Off, so);
-                            if (need1) buf_store(g0, grs, j < jl ? off1 : kC2Off, so);
+                            c2_put2<ACC>(g0, g1, grs, j < jl ? off2 : kC2Off, so, v0ok, v1ok);
+                            if (need1) c2_put<ACC>(g0, grs, j < jl ? off1 : kC2Off, so);
                             __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                         }
                     }
                     if (wave == 0 && fok) {
                         const float fcb = a.scale * bFb[B_] * c2_marginal_scale(sbk + S + shc_s[B_ * kC2Own + lane], D2, ctl_s);
-                        buf_store(full_s[yF] * EB[B_] * fcb, grs, rowB, gso);
+                        c2_put<ACC>(full_s[yF] * EB[B_] * fcb, grs, rowB, gso);
                     }
                 }
                 c2_barrier();
@@ -741,7 +762,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         for (int r = 0; r < kC2PH; ++r) ov[r] = osrc[r];
 #pragma unroll
                         for (int r = 0; r < kC2PH; ++r)
-                            buf_store(ov[r] * EP[B_][r] * fy, grs, rP0 + r < g.nr ? coffPm : kC2Off,
+                            c2_put<ACC>(ov[r] * EP[B_][r] * fy, grs, rP0 + r < g.nr ? coffPm : kC2Off,
                                       gso + (unsigned)(rP0 + r) * pitch);
                     }
                     if (hasS) {
@@ -749,7 +770,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         const float bS = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bSt[B_]), sS));
                         const float fyS = (ssp == kShiftNone) ? 0.f
                                           : a.scale * bS * c2_marginal_scale(sbkS + ssp + ek, D2, ctl_s);
-                        buf_store(own_s[min(lane, kC2Own - 1)] * ES[B_] * fyS, grs, coffS, gso);
+                        c2_put<ACC>(own_s[min(lane, kC2Own - 1)] * ES[B_] * fyS, grs, coffS, gso);
                     }
                 }
                 C2_MARK(a, p, 3);
@@ -784,7 +805,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
-template <bool GAMMA>
+template <bool GAMMA, bool ACC>
 __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
@@ -1114,11 +1135,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                         if (rS == ri) facS = fac;
                         const unsigned gso = (unsigned)tF * frb + roff(ri);
                         const unsigned so4 = ri < nrw ? coff4s : kC2Off;
-                        buf_store2(EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bg[0]) * fac, EFb[B_][ri][1] * bg[1] * fac, grs, so4, gso);
-                        buf_store2(EFb[B_][ri][2] * bg[2] * fac, EFb[B_][ri][3] * bg[3] * fac, grs, so4 + 8u, gso);
+                        c2_put2<ACC>(EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bg[0]) * fac, EFb[B_][ri][1] * bg[1] * fac, grs, so4, gso,
+                                     cb4 >= 4 * lane, cb4 + 1 >= 4 * lane);
+                        c2_put2<ACC>(EFb[B_][ri][2] * bg[2] * fac, EFb[B_][ri][3] * bg[3] * fac, grs, so4 + 8u, gso,
+                                     cb4 + 2 >= 4 * lane, cb4 + 3 >= 4 * lane);
                     }
                 }
-                if (GAMMA && iF >= ph1 && nstF > 0) buf_store(sprod * facS, grs, offSt, (unsigned)tF * frb);
+                if (GAMMA && iF >= ph1 && nstF > 0) c2_put<ACC>(sprod * facS, grs, offSt, (unsigned)tF * frb);
                 C2_MARK(a, p, 7);
                 c2_barrier();
                 {
@@ -1209,15 +1232,15 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     for (int j = 0; j < kC2QJ; ++j) {
                         const unsigned so = gso + rowF0 + (unsigned)(kC2QG * j) * pitch;
                         const unsigned oj = j < jl ? offq : kC2Off;
-                        buf_store2(aq[j] * EQ[B_][j][0] * fq[0], aq[j] * EQ[B_][j][1] * fq[1], grs, oj, so);
-                        buf_store2(aq[j] * EQ[B_][j][2] * fq[2], aq[j] * EQ[B_][j][3] * fq[3], grs, oj + 8u, so);
+                        c2_put2<ACC>(aq[j] * EQ[B_][j][0] * fq[0], aq[j] * EQ[B_][j][1] * fq[1], grs, oj, so, vok[0], vok[1]);
+                        c2_put2<ACC>(aq[j] * EQ[B_][j][2] * fq[2], aq[j] * EQ[B_][j][3] * fq[3], grs, oj + 8u, so, vok[2], vok[3]);
                         __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                     }
                     if (wave == 0 && fok) {
                         // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
                         const float fb = a.scale * own_s[lane] *
                                          c2_marginal_scale(shc_s[B_ * kC2Own + lane] + ek + samax, D2, ctl_s);
-                        buf_store(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
+                        c2_put<ACC>(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
                     }
                 }
                 C2_MARK(a, p, 3);
@@ -1260,7 +1283,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     }
 }
 
-template <bool GAMMA>
+template <bool GAMMA, bool ACC = false>
 __global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
 {
     __shared__ __align__(16) float smem[kC2Lds];
@@ -1276,9 +1299,9 @@ __global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
     if (g.nr < 0) g.nr = 0;
     if (g.r0 > a.C) g.r0 = a.C;
     unsigned gstep = 0, ptag = 0;
-    if (GAMMA) cluster_zero_padding(a, g);
-    if (g.role == 0) alpha2_role<GAMMA>(a, g, smem, gstep, ptag);
-    else beta2_role<GAMMA>(a, g, smem, gstep, ptag);
+    if (GAMMA && !ACC) cluster_zero_padding(a, g);      // (adding leaves frames beyond the length alone)
+    if (g.role == 0) alpha2_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
+    else beta2_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
 }
 
 }  // namespace last

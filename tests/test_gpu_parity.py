@@ -201,13 +201,20 @@ def test_edge_lengths_and_status():
 
 def test_scale_and_accumulate():
     announce("scale / accumulate semantics of the gradient output")
-    cfg = workloads.dense(B=2, T=7, V=6, order=1, seed=9)
-    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
-    _, g1 = lb.last_arc_posteriors(w, lengths)
-    base = torch.full_like(w, 0.5)
-    lb.last_arc_posteriors(w, lengths, dw=base, scale=-2.0, accumulate=True)
-    torch.cuda.synchronize()
-    assert torch.max(torch.abs(base - (0.5 - 2.0 * g1))).item() < 1e-6
+    # (6: one workgroup per direction; 130, 256: several workgroups whose lanes share columns at the
+    # edges of their blocks, which adding must count once)
+    for V, T in ((6, 7), (130, 9), (256, 10)):
+        cfg = workloads.dense(B=2, T=T, V=V, order=1, seed=9 + V, len_lo=T - 2, len_hi=T)
+        w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+        _, g1 = lb.last_arc_posteriors(w, lengths)
+        base = torch.full_like(w, 0.5)
+        lb.last_arc_posteriors(w, lengths, dw=base, scale=-2.0, accumulate=True)
+        torch.cuda.synchronize()
+        want = 0.5 - 2.0 * g1
+        # frames beyond an item's length are left as they were
+        for b in range(cfg["B"]):
+            want[b, int(cfg["lengths"][b]):] = 0.5
+        assert torch.max(torch.abs(base - want)).item() < 1e-6
 
 
 def test_viterbi_ties_follow_the_lowest_flat_index():
