@@ -149,6 +149,14 @@ __device__ __forceinline__ float c2_marginal_scale(int e, double D2, int* ctl_s)
     if (x > kC2RangeBits) ctl_s[11] = 1;
     return fast_exp2(fminf(x, 126.f));
 }
+// (the same with the largest exponent kept in a register of the caller, looked at when the item ends:
+// cheaper where the caller has the register to spare)
+__device__ __forceinline__ float c2_marginal_scale(int e, double D2, float& xmax)
+{
+    const float x = (float)((double)e - D2);
+    xmax = fmaxf(xmax, x);
+    return fast_exp2(fminf(x, 126.f));
+}
 
 // Exchange word of this kernel: [value:32 | tag:16 | exponent:16].  The exponent is the producer's,
 // relative to the exponent of the vector both sides already share (the one the pair started from), so
@@ -929,6 +937,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         int dead = 0;
         bool met = false;
         int p = 0;                // pair counter
+        float xwide = -3.0e38f;   // largest exponent of a marginal scale relative to D
 
         // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
         auto frameF = [&](int p) { return max(L - 1 - min(2 * p, nlast), 0); };
@@ -1131,7 +1140,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     for (int ri = 0; ri < kC2RW; ++ri) {
                         const float arow = __shfl(aF[B_], ri, 64);
                         const float fac = a.scale * arow *
-                                          c2_marginal_scale(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S, D2, ctl_s);
+                                          c2_marginal_scale(__builtin_amdgcn_readlane(saF[B_], g.k) + srF[B_][ri] + S, D2, xwide);
                         if (rS == ri) facS = fac;
                         const unsigned gso = (unsigned)tF * frb + roff(ri);
                         const unsigned so4 = ri < nrw ? coff4s : kC2Off;
@@ -1221,7 +1230,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
                         fq[k] = a.scale * own_s[c0 + k] *
-                                c2_marginal_scale(shc_s[B_ * kC2Own + c0 + k] + ek + samax, D2, ctl_s);
+                                c2_marginal_scale(shc_s[B_ * kC2Own + c0 + k] + ek + samax, D2, xwide);
                     const unsigned offq = lact ? coffF : kC2Off;
                     int jl = jlim;
                     c2_pin(jl);
@@ -1239,7 +1248,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (wave == 0 && fok) {
                         // empty-label arc of the own state q: a_t[q] M[q][0] b_{t+1}[q]
                         const float fb = a.scale * own_s[lane] *
-                                         c2_marginal_scale(shc_s[B_ * kC2Own + lane] + ek + samax, D2, ctl_s);
+                                         c2_marginal_scale(shc_s[B_ * kC2Own + lane] + ek + samax, D2, xwide);
                         c2_put<ACC>(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
                     }
                 }
@@ -1278,6 +1287,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         }
         __syncthreads();
         if (!met) meet();
+        if (xwide > kC2RangeBits) ctl_s[11] = 1;
+        __syncthreads();
         if (tid == 0 && ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
         __syncthreads();
     }
