@@ -130,9 +130,9 @@ __device__ __forceinline__ void c2_wait_loads()
     __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-__device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e, zero stays zero
+__device__ __forceinline__ float c2_scale(float v, int e)     // v * 2^e (zero stays zero whatever e is)
 {
-    return (v == 0.f) ? 0.f : __builtin_ldexpf(v, max(e, -300));
+    return __builtin_ldexpf(v, max(e, -300));
 }
 
 // 2^(e - D) for the marginals.  e adds up the exponents of three maxima (state vector, weights, state
