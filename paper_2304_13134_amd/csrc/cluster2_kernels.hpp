@@ -198,10 +198,13 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
     {
         int n = 0;
         for (;;) {
-            bool ok = true;
+            // all K tags right: no bit differs in the upper halves of the words' high parts
+            const unsigned tagw = (tag & 0xFFFFu) << 16;
+            unsigned diff = 0;
 #pragma unroll
             for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) ok = ok && (unsigned)(lk.wv[kk] >> 48) == (tag & 0xFFFFu);
+                if (kk < K) diff |= (unsigned)(lk.wv[kk] >> 32) ^ tagw;
+            const bool ok = (diff >> 16) == 0;
             if (ok || dead) break;
             if (++n > limit) { dead = 1; break; }
             __builtin_amdgcn_s_sleep(1);
@@ -215,7 +218,8 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
             if (kk < K)
-                v += c2_scale(__uint_as_float((unsigned)lk.wv[kk]), (int)(short)(unsigned short)(lk.wv[kk] >> 32) - href);
+                v += __builtin_ldexpf(__uint_as_float((unsigned)lk.wv[kk]),
+                                      (int)(short)(unsigned short)(lk.wv[kk] >> 32) - href);      // (16-bit exponents: in [-65535, 0])
         hr = href;
         if (tid >= C) v = 0.f;
     }
