@@ -177,19 +177,21 @@ struct C2Look {
 
 // (Threads beyond the last state read the last state's words and discard the result: loads and their
 // uses sit on every path, see c2_touch.)
+// FULL: K is the largest number of producers (the common case at 257 states): no test per word.
+template <bool FULL>
 __device__ __forceinline__ void c2_gather_look(const u64* xs, int K, int C, C2Look& lk)
 {
     const int q = min((int)threadIdx.x, C - 1);
 #pragma unroll
     for (int kk = 0; kk < kClMaxK; ++kk)
-        if (kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + q);
+        if (FULL || kk < K) lk.wv[kk] = xload(xs + (size_t)kk * kC2XS + q);
 }
 
 // Every thread calls; ends with a workgroup barrier.  `after_poll` runs once all words are there, before
 // they are added up: the place for memory requests that should not stand between the polls and their data.
-template <typename AfterPoll>
+template <bool FULL, typename AfterPoll>
 __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
-                                          int* ctl_s, int limit, int& dead, C2Look& lk, AfterPoll&& after_poll)
+                                            int* ctl_s, int limit, int& dead, C2Look& lk, AfterPoll&& after_poll)
 {
     const int tid = threadIdx.x;
     const int S0 = ctl_s[0];           // exponent the producers' exponents are relative to
@@ -203,21 +205,21 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
             unsigned diff = 0;
 #pragma unroll
             for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) diff |= (unsigned)(lk.wv[kk] >> 32) ^ tagw;
+                if (FULL || kk < K) diff |= (unsigned)(lk.wv[kk] >> 32) ^ tagw;
             const bool ok = (diff >> 16) == 0;
             if (ok || dead) break;
             if (++n > limit) { dead = 1; break; }
             __builtin_amdgcn_s_sleep(1);
-            c2_gather_look(xs, K, C, lk);
+            c2_gather_look<FULL>(xs, K, C, lk);
         }
         after_poll();
         int href = -(1 << 30);
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K) href = max(href, (int)(short)(unsigned short)(lk.wv[kk] >> 32));
+            if (FULL || kk < K) href = max(href, (int)(short)(unsigned short)(lk.wv[kk] >> 32));
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K)
+            if (FULL || kk < K)
                 v += __builtin_ldexpf(__uint_as_float((unsigned)lk.wv[kk]),
                                       (int)(short)(unsigned short)(lk.wv[kk] >> 32) - href);      // (16-bit exponents: in [-65535, 0])
         hr = href;
@@ -236,7 +238,6 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
     if (tid == 0) ctl_s[0] = S0 + hr + mx;
     c2_barrier();
 }
-
 // D = log2 sum_q a_mid[q] b_mid[q] with one exponent per block of RPW states on either side
 __device__ __forceinline__ double c2_meeting(const float* ah, const float* bh, const int* Sa, const int* Sb,
                                              int C, int RPW, int K, float* red)
@@ -348,7 +349,7 @@ __device__ __forceinline__ C2Quad c2_quad(int ci, bool in_group, int r0, int nr)
 }
 
 // ------------------------------------------------------------------ alpha role
-template <bool GAMMA, bool ACC>
+template <bool GAMMA, bool ACC, bool FULL>
 __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                             unsigned& gstep, unsigned& ptag)
 {
@@ -789,10 +790,10 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 // first look at the exchange halfway through the exp pass: early enough for the round trip to
                 // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
                 C2Look lk;
-                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look(xs, K, C, lk); });
+                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look<FULL>(xs, K, C, lk); });
                 C2_MARK(a, p, 4);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk, [] {});
+                    c2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk, [] {});
                     C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP + 1 <= mid) {
@@ -817,7 +818,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
-template <bool GAMMA, bool ACC>
+template <bool GAMMA, bool ACC, bool FULL>
 __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGeom& g, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
@@ -1264,7 +1265,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 C2Look lk;
                 prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) {
                     if (wave >= 4) issueP(std::integral_constant<int, B_>(), p + 2);
-                    if (exch) c2_gather_look(xs, K, C, lk);
+                    if (exch) c2_gather_look<FULL>(xs, K, C, lk);
                 });
                 C2_MARK(a, p, 4);
                 // The F frame of the pair after the next goes into the registers this pair's F-step has
@@ -1272,7 +1273,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 // path while the words are added up.
                 if (!exch) issueF(std::integral_constant<int, B_>(), p + 2);
                 if (exch) {
-                    c2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk,
+                    c2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) { issueF(std::integral_constant<int, B_>(), p + 2); });
                     C2_MARK(a, p, 5);
                     gstep += 1;
@@ -1298,7 +1299,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     }
 }
 
-template <bool GAMMA, bool ACC = false>
+// FULL: a.K == kClMaxK, known when the kernel is chosen (no test per exchanged word)
+template <bool GAMMA, bool ACC = false, bool FULL = false>
 __global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
 {
     __shared__ __align__(16) float smem[kC2Lds];
@@ -1315,8 +1317,8 @@ __global__ __launch_bounds__(kC2Threads) void cluster2_kernel(ClusterArgs a)
     if (g.r0 > a.C) g.r0 = a.C;
     unsigned gstep = 0, ptag = 0;
     if (GAMMA && !ACC) cluster_zero_padding(a, g);      // (adding leaves frames beyond the length alone)
-    if (g.role == 0) alpha2_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
-    else beta2_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
+    if (g.role == 0) alpha2_role<GAMMA, ACC, FULL>(a, g, smem, gstep, ptag);
+    else beta2_role<GAMMA, ACC, FULL>(a, g, smem, gstep, ptag);
 }
 
 }  // namespace last

@@ -222,9 +222,11 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     if (const char* e = std::getenv("LAST_AUX_DELAY")) a.aux_delay = std::atoi(e);
     if (p.v2) {
         if (GAMMA && accumulate)
-            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, GAMMA>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, GAMMA, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+        else if (p.K == kClMaxK)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, false, true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
         else
-            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, false, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
         return;
     }
     auto go = [&](auto KC) {
