@@ -32,7 +32,7 @@ BYTES_PER_ARC = 12.0           # forward reads w (4), backward reads w (4) and w
 # HBM traffic per forward+backward launch measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/cluster2_kernel_B16_T500_V256.md: 4.344 GB fetched + 2.260 GB written.
-MEASURED_TRAFFIC_BYTES = 6.579e9
+MEASURED_TRAFFIC_BYTES = 6.581e9
 
 
 def time_region(fn, steps, warmup):
@@ -165,7 +165,7 @@ def main():
                    "B": cfg["B"], "T": cfg["T"], "V": cfg["V"], "C": cfg["C"], "arcs": arcs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES if full else None,
-                     "kernel": "cluster2_kernel<true, false> (+ the 5 us tag-clear kernel of the same call)",
+                     "kernel": "cluster2_kernel<true, false, true> (+ the 5 us tag-clear kernel of the same call)",
                      "algorithmic_bytes_per_launch": BYTES_PER_ARC * arcs},
         "extra": extra,
     }
