@@ -225,15 +225,16 @@ __device__ __forceinline__ void c2_gather(const u64* xs, int K, int C, unsigned 
         hr = href;
         if (tid >= C) v = 0.f;
     }
-    // renormalise by the largest magnitude actually present, so that mantissas do not drift
-    const int mu = wave_max_dpp(v > 0.f ? float_exponent(v) : -(1 << 20));
-    if ((tid & 63) == 0) ctl_s[24 + (tid >> 6)] = mu;
+    // renormalise by the largest magnitude actually present, so that mantissas do not drift.  The values
+    // are sums of products of non-negative numbers: their bit patterns order like integers, and the
+    // exponent is taken once, from the largest.
+    const int mub = wave_max_dpp(__float_as_int(v));
+    if ((tid & 63) == 0) ctl_s[24 + (tid >> 6)] = mub;
     if (dead) ctl_s[8] = 1;
     c2_barrier();
-    int mx = -(1 << 20);
-#pragma unroll
-    for (int w2 = 0; w2 < kC2Waves; ++w2) mx = max(mx, ctl_s[24 + w2]);
-    if (mx == -(1 << 20)) mx = 0;
+    const int4 m0 = *(const int4*)&ctl_s[24], m1 = *(const int4*)&ctl_s[28];
+    const int mxb = max(max(max(m0.x, m0.y), max(m0.z, m0.w)), max(max(m1.x, m1.y), max(m1.z, m1.w)));
+    const int mx = mxb > 0 ? float_exponent(__int_as_float(mxb)) : 0;
     if (tid < C) full_s[tid] = c2_scale(v, -mx);
     if (tid == 0) ctl_s[0] = S0 + hr + mx;
     c2_barrier();
