@@ -85,6 +85,8 @@ __device__ __forceinline__ void v2_wave_best(float& v, int& f)
 
 // Gather one exchange slot: best of the K published candidates per state.  Every thread calls;
 // ends with a workgroup barrier.  Returns the winning arc of state tid (kVNone if none).
+// FULL: K is the largest number of producers, known when the kernel is chosen (no test per word).
+template <bool FULL>
 __device__ __forceinline__ int v2_gather(const u64* xs, int K, int C, unsigned tag, float* full_s,
                                          int* ctl_s, int limit, int& dead)
 {
@@ -94,13 +96,16 @@ __device__ __forceinline__ int v2_gather(const u64* xs, int K, int C, unsigned t
         u64 wv[kClMaxK];
         int n = 0;
         for (;;) {
-            bool ok = true;
 #pragma unroll
             for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
+                if (FULL || kk < K) wv[kk] = xload(xs + (size_t)kk * kC2XS + tid);
+            // all K tags right: no bit differs in the tag fields (the upper 15 bits of the words)
+            const unsigned tagw = (tag & 0x7FFFu) << 17;
+            unsigned diff = 0;
 #pragma unroll
             for (int kk = 0; kk < kClMaxK; ++kk)
-                if (kk < K) ok = ok && (unsigned)(wv[kk] >> 49) == (tag & 0x7FFFu);
+                if (FULL || kk < K) diff |= (unsigned)(wv[kk] >> 32) ^ tagw;
+            const bool ok = (diff >> 17) == 0;
             if (ok || dead) break;
             if (++n > limit) { dead = 1; break; }
             __builtin_amdgcn_s_sleep(1);
@@ -108,7 +113,7 @@ __device__ __forceinline__ int v2_gather(const u64* xs, int K, int C, unsigned t
         float best = LAST_NEG_INF;
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (kk < K) v2_acc(__uint_as_float((unsigned)wv[kk]), (int)((wv[kk] >> 32) & 0x1FFFFu), best, bf);
+            if (FULL || kk < K) v2_acc(__uint_as_float((unsigned)wv[kk]), (int)((wv[kk] >> 32) & 0x1FFFFu), best, bf);
         full_s[tid] = dead ? LAST_NEG_INF : best;
     }
     if (dead) ctl_s[8] = 1;
@@ -116,7 +121,7 @@ __device__ __forceinline__ int v2_gather(const u64* xs, int K, int C, unsigned t
     return bf;
 }
 
-template <bool BP>
+template <bool BP, bool FULL = false>
 __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
 {
     __shared__ __align__(16) float smem[kV2Lds];
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                     if (tid >= r0 && tid < r0 + nr) v2_acc(blv_s[tid - r0], bli_s[tid - r0], pv, pf);
                     xpublish(xs + (size_t)k * kC2XS + tid, v2_pack(pv, tag, pf));
                 }
-                const int bf = v2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+                const int bf = v2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
                 gstep += 1;
                 if (BP && tid >= r0 && tid < r0 + nr) bpi[(size_t)tP * C + tid] = bf == kVNone ? -1 : bf;
             }
@@ -328,7 +333,7 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                 const bool own = tid >= r0 && tid < r0 + nr;
                 xpublish(xs + (size_t)k * kC2XS + tid, v2_pack(own ? own_s[tid - r0] : LAST_NEG_INF, tag, kVNone));
             }
-            v2_gather(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
+            v2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead);
             gstep += 1;
         }
         // best final state, lowest index among equals (every workgroup has the whole vector; the first writes)

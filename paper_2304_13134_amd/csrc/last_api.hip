@@ -460,8 +460,11 @@ void launch_cluster_viterbi(const Shape& s, const ViterbiPlan& p, u64* xv, const
     a.item_status = item_status; a.xa = xv;
     a.B = s.B; a.T = s.T; a.C = s.C; a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl;
     a.spin_limit = 1 << 20;
-    if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
-    else hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+    const bool full = p.K == kClMaxK;      // (the instantiation without a test per exchanged word)
+    if (bp && full) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+    else if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+    else if (full) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<false, true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
+    else hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<false, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
 }
 
 last_status_t check_ws(void* ws, size_t have, size_t need)
