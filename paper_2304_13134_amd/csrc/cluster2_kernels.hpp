@@ -797,9 +797,9 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     c2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk, [] {});
                     C2_MARK(a, p, 5);
                     gstep += 1;
-                    if (tP + 1 <= mid) {
-                        if (tid < g.nr) ah[(size_t)(tP + 1) * C + g.r0 + tid] = full_s[g.r0 + tid];
-                        if (tid == 0) Sa[(size_t)(tP + 1) * kClMaxK + g.k] = ctl_s[0];
+                    if (tP + 1 <= mid && wave == 6) {      // (a wave with no other special duty)
+                        if (lane < g.nr) ah[(size_t)(tP + 1) * C + g.r0 + lane] = full_s[g.r0 + lane];
+                        if (lane == 0) Sa[(size_t)(tP + 1) * kClMaxK + g.k] = ctl_s[0];
                     }
                 }
             }
@@ -1278,9 +1278,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                               [&]() __attribute__((always_inline)) { issueF(std::integral_constant<int, B_>(), p + 2); });
                     C2_MARK(a, p, 5);
                     gstep += 1;
-                    if (tP >= mid) {
-                        if (tid < g.nr) bh[(size_t)tP * C + g.r0 + tid] = full_s[g.r0 + tid];
-                        if (tid == 0) Sb[(size_t)tP * kClMaxK + g.k] = ctl_s[0];
+                    if (tP >= mid && wave == 6) {          // (a wave with no other special duty)
+                        if (lane < g.nr) bh[(size_t)tP * C + g.r0 + lane] = full_s[g.r0 + lane];
+                        if (lane == 0) Sb[(size_t)tP * kClMaxK + g.k] = ctl_s[0];
                     }
                 }
             }
