@@ -158,6 +158,31 @@ __device__ __forceinline__ float c2_marginal_scale(int e, double D2, float& xmax
     return fast_exp2(fminf(x, 126.f));
 }
 
+// Largest float of a wave for several independent values at once: floats are mapped to integers of the
+// same order, and the steps take the smallest integer where a lane has no source, which lets the
+// compiler fold each step into one v_max_i32 with a DPP operand.  (One chain alone is not faster this
+// way, its steps wait on each other; several interleaved chains are.)
+__device__ __forceinline__ int c2_fkey(float x)
+{
+    const int b = __float_as_int(x);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float c2_fkey_inv(int k)
+{
+    return __int_as_float(k ^ ((k >> 31) & 0x7fffffff));
+}
+__device__ __forceinline__ int c2_wave_max_key(int v)
+{
+    constexpr int kMin = -2147483647 - 1;
+    v = max(v, dpp_i<0x111>(kMin, v));
+    v = max(v, dpp_i<0x112>(kMin, v));
+    v = max(v, dpp_i<0x114>(kMin, v));
+    v = max(v, dpp_i<0x118>(kMin, v));
+    v = max(v, dpp_i<0x142, 0xa>(kMin, v));
+    v = max(v, dpp_i<0x143, 0xc>(kMin, v));
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
 // Exchange word of this kernel: [value:32 | tag:16 | exponent:16].  The exponent is the producer's,
 // relative to the exponent of the vector both sides already share (the one the pair started from), so
 // that it fits 16 bits whatever the length of the sequence; it is the same in all words of a producer.
@@ -1008,8 +1033,13 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 for (int j = 0; j < kC2NC; ++j) mx = fmaxf(mx, EFb[B_][ri][j]);
                 mxr[ri] = mx;
             }
+            int kr[kC2RW];
 #pragma unroll
-            for (int ri = 0; ri < kC2RW; ++ri) mxr[ri] = wave_max_dpp(mxr[ri]);
+            for (int ri = 0; ri < kC2RW; ++ri) kr[ri] = c2_fkey(mxr[ri]);
+#pragma unroll
+            for (int ri = 0; ri < kC2RW; ++ri) kr[ri] = c2_wave_max_key(kr[ri]);
+#pragma unroll
+            for (int ri = 0; ri < kC2RW; ++ri) mxr[ri] = c2_fkey_inv(kr[ri]);
 #pragma unroll
             for (int ri = 0; ri < kC2RW; ++ri) {
                 const int s = shift_for(mxr[ri]);
