@@ -176,6 +176,23 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
                                  int32_t* item_status,
                                  void* ws, size_t ws_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): last_shortest_distance
+ * without the workspace arguments.  The scratch memory is a static device array
+ * of LAST_STATIC_SCRATCH_BYTES inside the library; each GPU the library runs on
+ * holds its own copy until the process ends.  The call allocates and frees
+ * nothing.  Shapes whose last_workspace_bytes(..., LAST_OP_SHORTEST_DISTANCE, 0)
+ * exceeds LAST_STATIC_SCRATCH_BYTES are rejected with LAST_ERR_WORKSPACE (nothing
+ * is enqueued).  All calls on one GPU share that GPU's array: calls that overlap
+ * in time on one GPU (two streams, two threads) race on it and must be serialised
+ * by the caller; calls in sequence on one stream are fine (whatever must start
+ * from zero is cleared by the call itself).  Everything else as
+ * last_shortest_distance. */
+#define LAST_STATIC_SCRATCH_BYTES (32u << 20)
+last_status_t last_shortest_distance_static(const last_weights_t* weights, const int32_t* lengths,
+                                            const last_context_t* context, last_semiring_t semiring,
+                                            float* dist, int32_t* item_status, void* hip_stream);
+
 const char* last_status_string(last_status_t status);
 
 /* Text of the HIP error behind the most recent LAST_ERR_HIP (diagnostics). */

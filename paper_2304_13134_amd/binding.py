@@ -22,7 +22,9 @@ WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
 
 EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
            "last_intersect_reference", "last_shortest_path", "last_status_string",
-           "last_version", "last_kernel_variant", "last_hip_error_string"]
+           "last_version", "last_kernel_variant", "last_hip_error_string",
+           "last_shortest_distance_static"]
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class LastContext(ctypes.Structure):
@@ -66,6 +68,9 @@ def load_library():
     lib.last_shortest_distance.restype = i32
     lib.last_shortest_distance.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                            i32, vp, vp, vp, sz, vp]
+    lib.last_shortest_distance_static.restype = i32
+    lib.last_shortest_distance_static.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                                  i32, vp, vp, vp]
     lib.last_arc_posteriors.restype = i32
     lib.last_arc_posteriors.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                         vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
@@ -187,6 +192,19 @@ def last_shortest_distance(w, lengths, order=1, semiring="log", item_status=None
     sr = LAST_LOG if semiring == "log" else LAST_TROPICAL
     _check(lib.last_shortest_distance(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), sr,
                                       _ptr(dist), _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
+    return dist
+
+
+def last_shortest_distance_static(w, lengths, dist, order=1, semiring="log", item_status=None):
+    """last_shortest_distance into the caller's `dist` [B] with the library's static scratch array:
+    nothing is allocated, here or in the library."""
+    lib = load_library()
+    wt, cx, device, B = _weights_and_context(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    _dev_tensor(dist, torch.float32, "dist")
+    sr = LAST_LOG if semiring == "log" else LAST_TROPICAL
+    _check(lib.last_shortest_distance_static(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), sr,
+                                             _ptr(dist), _ptr(item_status), _stream()))
     return dist
 
 

@@ -14,6 +14,7 @@
 #include <algorithm>
 
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 using namespace last;
@@ -739,6 +740,61 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
     hipLaunchKernelGGL(backtrace_kernel, dim3(s.B), dim3(256), 0, st, (const int*)p.bp, lengths,
                        (const int*)p.final_state, s.C, s.V1, s.T, labels, states);
     return hip_status();
+}
+
+// ---- the entry point for callers that cannot allocate --------------------------------------
+// Its scratch memory is a file-scope device array: every GPU the library runs on holds one copy
+// of it, at its own address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels are given the address that call returned.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[LAST_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// address of the current device's copy of `scratch` (looked up once per device)
+last_status_t static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxDevices) return LAST_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { g_last_hip_error = e; return LAST_ERR_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LAST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+last_status_t last_shortest_distance_static(const last_weights_t* weights, const int32_t* lengths,
+                                            const last_context_t* context, last_semiring_t semiring,
+                                            float* dist, int32_t* item_status, void* hip_stream)
+{
+    Shape s;
+    last_status_t rc = check_common(weights, context, &s);
+    if (rc != LAST_OK) return rc;
+    if (!lengths || !dist) return LAST_ERR_NULL;
+    if (semiring != LAST_LOG && semiring != LAST_TROPICAL) return LAST_ERR_SEMIRING;
+    const size_t need = last_workspace_bytes(weights, context, LAST_OP_SHORTEST_DISTANCE, 0);
+    if (need == 0) return LAST_ERR_UNSUPPORTED;
+    if (need > (size_t)LAST_STATIC_SCRATCH_BYTES) return LAST_ERR_WORKSPACE;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != LAST_OK) return rc;
+    return last_shortest_distance(weights, lengths, context, semiring, dist, item_status, ws,
+                                  (size_t)LAST_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 }  // extern "C"
