@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain device copies of the weight tensor (known size) so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--generation", type=int, default=0,
+                    help="cooperating-workgroup kernel generation (0 = the library's choice)")
     ap.add_argument("--B", type=int, default=16)
     ap.add_argument("--T", type=int, default=500)
     ap.add_argument("--V", type=int, default=256)
@@ -95,6 +97,8 @@ def main():
     from paper_2304_13134_amd import workloads
 
     lb.load_library()                      # fails loudly if the HIP library is missing
+    if args.generation:
+        lb.set_option(lb.OPT_CLUSTER_GENERATION, args.generation)
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
 

@@ -193,6 +193,28 @@ last_status_t last_shortest_distance_static(const last_weights_t* weights, const
                                             const last_context_t* context, last_semiring_t semiring,
                                             float* dist, int32_t* item_status, void* hip_stream);
 
+/* Process-wide settings, for cross-checks and tests; they take effect on the next call.
+ *   LAST_OPT_FORCE_SOLO (0/1, default 0): 1 = always the one-workgroup-per-item kernels (log domain,
+ *     no limit on the dynamic range of the weights).
+ *   LAST_OPT_CLUSTER_GENERATION (0..3, default 0): which cooperating-workgroup forward-backward kernel
+ *     dense bigram lattices take; 0 = the newest that supports the shape, 3 = sixteen workgroups per
+ *     direction and item (256 labels only), 2 = eight (5..264 states), 1 = the oldest (one exchange per
+ *     frame).  A generation that does not support the shape falls back to the next older one.
+ *   LAST_OPT_CLUSTER_VITERBI (0/1, default 1): 0 = shortest path with one workgroup per item.
+ *   LAST_OPT_SPIN_LIMIT (>= 1, default 2^20): polls a cooperating workgroup makes before it gives up
+ *     waiting for the others (the item then gets status 5 and dist = NaN; every kernel still ends).
+ * last_set_option returns LAST_ERR_UNSUPPORTED for an unknown option or value; last_get_option
+ * returns -1 for an unknown option. */
+typedef enum {
+    LAST_OPT_FORCE_SOLO = 0,
+    LAST_OPT_CLUSTER_GENERATION = 1,
+    LAST_OPT_CLUSTER_VITERBI = 2,
+    LAST_OPT_SPIN_LIMIT = 3,
+    LAST_OPT_COUNT_ = 4
+} last_option_t;
+last_status_t last_set_option(int32_t option, int32_t value);
+int32_t last_get_option(int32_t option);
+
 const char* last_status_string(last_status_t status);
 
 /* Text of the HIP error behind the most recent LAST_ERR_HIP (diagnostics). */

@@ -23,7 +23,8 @@ WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
 EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
            "last_intersect_reference", "last_shortest_path", "last_status_string",
            "last_version", "last_kernel_variant", "last_hip_error_string",
-           "last_shortest_distance_static"]
+           "last_shortest_distance_static", "last_set_option", "last_get_option"]
+OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 32 << 20
 
 
@@ -84,6 +85,10 @@ def load_library():
     lib.last_status_string.argtypes = [i32]
     lib.last_version.restype = i32
     lib.last_hip_error_string.restype = ctypes.c_char_p
+    lib.last_set_option.restype = i32
+    lib.last_set_option.argtypes = [i32, i32]
+    lib.last_get_option.restype = i32
+    lib.last_get_option.argtypes = [i32]
     lib.last_kernel_variant.restype = i32
     lib.last_kernel_variant.argtypes = [ctypes.POINTER(LastWeights), ctypes.POINTER(LastContext), i32]
     _lib = lib
@@ -96,6 +101,14 @@ def _check(code):
         if code == 7:
             text += ": " + load_library().last_hip_error_string().decode()
         raise LastError(code, text)
+
+
+def set_option(option, value):
+    """Process-wide setting of the library (see last_set_option in include/last.h); returns the old value."""
+    lib = load_library()
+    old = int(lib.last_get_option(option))
+    _check(lib.last_set_option(option, value))
+    return old
 
 
 def _ptr(t):

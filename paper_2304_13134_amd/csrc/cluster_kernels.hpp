@@ -96,6 +96,7 @@ struct ClusterArgs {
                    //                        column = producer half-workgroup
     u64* xb;       // [ncl_total][2][XSB]   beta values
     u64* ph;       // [ncl_total][32]       phase flags
+    u64* fin;      // [B][2]                third generation: workgroups through with an item, time-out mark
     int B, T, C;
     int K, RPW, ncl;   // workgroups per role, rows per workgroup, clusters per XCD
     int XS, XSB;

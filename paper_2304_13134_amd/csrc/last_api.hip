@@ -10,9 +10,11 @@
 #include "cluster_kernels.hpp"
 #include "cluster2_kernels.hpp"
 #include "cluster2v_kernels.hpp"
+#include "cluster3_kernels.hpp"
 #include "fused_kernels.hpp"
 #include <algorithm>
 
+#include <atomic>
 #include <cstdlib>
 #include <mutex>
 #include <type_traits>
@@ -20,6 +22,10 @@
 using namespace last;
 
 namespace {
+
+// process-wide settings (last_set_option)
+std::atomic<int> g_opt[LAST_OPT_COUNT_] = {{0}, {0}, {1}, {1 << 20}};
+inline int opt(int o) { return g_opt[o].load(std::memory_order_relaxed); }
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
@@ -145,18 +151,32 @@ NumWs carve_num(Carver& cv, const Shape& s, int Umax)
 // geometry of the clustered bigram path (see cluster_kernels.hpp)
 struct ClusterPlan {
     bool ok;
-    bool v2;             // one exchange per two frames (cluster2_kernels.hpp)
+    int gen;             // 2: one exchange per two frames, eight workgroups of eight waves per role
+                         // (cluster2_kernels.hpp); 3: sixteen workgroups of four waves per role, two per
+                         // compute unit (cluster3_kernels.hpp, 256 labels); 1: one exchange per frame
     int K, RPW, ncl, XS, XSB, grid;
 };
 
 ClusterPlan cluster_plan(const Shape& s, int kind)
 {
     ClusterPlan p{};
-    const char* force = std::getenv("LAST_FORCE_SOLO");
-    if (force && force[0] == '1') return p;
+    if (opt(LAST_OPT_FORCE_SOLO)) return p;
     if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.C < 5 || s.T < 1) return p;   // (tiny label sets: one workgroup per item)
     // one item must fit a 32-bit buffer descriptor
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;
+    const int want_gen = opt(LAST_OPT_CLUSTER_GENERATION);      // 0: the newest that takes the shape
+    if (want_gen == 3 && s.C == kC3C) {      // (opt-in while it is slower than the second generation)
+        p.gen = 3;
+        p.K = kC3K;
+        p.RPW = 16;
+        const int want3 = (s.B + 7) / 8;
+        p.ncl = want3 < 2 ? want3 : 2;       // two workgroups per compute unit: 64 per XCD, 32 per item
+        p.XS = kC3XS;
+        p.XSB = 0;
+        p.grid = 8 * p.ncl * 2 * p.K;
+        p.ok = true;
+        return p;
+    }
     p.K = (s.C + 32) / 33;                   // at most 33 rows per workgroup
     if (p.K > kClMaxK) return p;
     p.RPW = (s.C + p.K - 1) / p.K;
@@ -169,9 +189,8 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     p.XSB = kClMaxC;                         // 11 waves x 24 words
     p.grid = 8 * p.ncl * 2 * p.K;
     p.ok = true;
-    // the second-generation kernel (one exchange per two frames) unless LAST_CLUSTER_V2=0 asks for the first
-    const char* v2 = std::getenv("LAST_CLUSTER_V2");
-    p.v2 = !(v2 && v2[0] == '0') && s.C <= kC2Hdr && s.C >= 5;   // (16-byte accesses: four label columns at least)
+    // the second generation (one exchange per two frames) unless the first is asked for
+    p.gen = (want_gen != 1 && s.C <= kC2Hdr && s.C >= 5) ? 2 : 1;   // (16-byte accesses: four label columns at least)
     return p;
 }
 
@@ -183,6 +202,7 @@ struct ClusterWs {
     u64* xa;
     u64* xb;
     u64* ph;
+    u64* fin;
     size_t xwords;
 };
 
@@ -192,16 +212,20 @@ ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
     const size_t st = (size_t)s.B * (s.T + 1);
     c.ahat = cv.take<float>(st * s.C);
     c.bhat = cv.take<float>(st * s.C);
-    c.Sa = cv.take<int>(st * kClMaxK);      // one exponent per block of states (second-generation kernel)
-    c.Sb = cv.take<int>(st * kClMaxK);
+    const size_t nblk = p.gen == 3 ? kC3K : kClMaxK;      // one exponent per block of states
+    c.Sa = cv.take<int>(st * nblk);
+    c.Sb = cv.take<int>(st * nblk);
     const size_t ncl = (size_t)8 * p.ncl;
-    const size_t per_role = std::max((size_t)2 * p.XS * kClXK, (size_t)2 * kClMaxK * kC2XS);
+    const size_t per_role = p.gen == 3 ? (size_t)2 * kC3K * kC3XS
+                                       : std::max((size_t)2 * p.XS * kClXK, (size_t)2 * kClMaxK * kC2XS);
     const size_t nxa = ncl * per_role, nxb = std::max(ncl * 2 * p.XSB, ncl * per_role), nph = ncl * 32;
+    const size_t nfin = (size_t)2 * s.B;
     // one contiguous block so that a single launch clears all tags
-    c.xa = cv.take<u64>(nxa + nxb + nph);
+    c.xa = cv.take<u64>(nxa + nxb + nph + nfin);
     c.xb = c.xa ? c.xa + nxa : nullptr;
     c.ph = c.xb ? c.xb + nxb : nullptr;
-    c.xwords = nxa + nxb + nph;
+    c.fin = c.ph ? c.ph + nph : nullptr;
+    c.xwords = nxa + nxb + nph + nfin;
     return c;
 }
 
@@ -214,14 +238,20 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     ClusterArgs a;
     a.w = w; a.len = lengths; a.dw = dw; a.dist = dist; a.item_status = item_status;
     a.ahat = c.ahat; a.bhat = c.bhat; a.Sa = c.Sa; a.Sb = c.Sb;
-    a.xa = c.xa; a.xb = c.xb; a.ph = c.ph;
+    a.xa = c.xa; a.xb = c.xb; a.ph = c.ph; a.fin = c.fin;
     a.B = s.B; a.T = s.T; a.C = s.C;
     a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
     a.scale = scale; a.accumulate = accumulate;
-    a.spin_limit = 1 << 20;
+    a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     a.aux_delay = 4;
-    if (const char* e = std::getenv("LAST_AUX_DELAY")) a.aux_delay = std::atoi(e);
-    if (p.v2) {
+    if (p.gen == 3) {
+        if (GAMMA && accumulate)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, GAMMA>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, false>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+        return;
+    }
+    if (p.gen == 2) {
         if (GAMMA && accumulate)
             hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2_kernel<GAMMA, GAMMA, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
         else if (p.K == kClMaxK)
@@ -362,7 +392,7 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
     a.alpha_ws = keep_alpha ? f.alpha : nullptr; a.offs = f.offs; a.part = f.part; a.Aend = f.Aend;
     a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = wt->hidden; a.C = s.C;
-    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20;
+    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     fused_dispatch(p.MT, [&](auto MT) {
         hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_forward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
                            dim3(kFuThreads), p.lds, st, a);
@@ -391,7 +421,7 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
     a.df = out->df; a.de = out->de; a.dW = out->dW; a.scale = out->scale;
     a.item_status = item_status; a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = H; a.C = s.C;
-    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = 1 << 20; a.nch = p.nch; a.TC = p.TC;
+    a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = opt(LAST_OPT_SPIN_LIMIT); a.nch = p.nch; a.TC = p.TC;
     fused_dispatch(p.MT, [&](auto MT) {
         hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_backward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
                            dim3(kFuThreads), p.lds_bwd, st, a);
@@ -405,7 +435,7 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
 bool launch_bigram_viterbi(const Shape& s, const float* w, const int* lengths, int* bp, int* final_state,
                            float* score, int* item_status, hipStream_t st)
 {
-    if (s.order != 1 || s.C < 129 || s.C > kClMaxC || getenv("LAST_FORCE_SOLO")) return false;
+    if (s.order != 1 || s.C < 129 || s.C > kClMaxC || opt(LAST_OPT_FORCE_SOLO)) return false;
     if ((size_t)s.T * s.C * s.C * 4 >= ((size_t)1 << 31)) return false;   // one buffer descriptor per item
     if (s.C <= 256) {
         const int CPAD = 256;
@@ -431,10 +461,7 @@ struct ViterbiPlan {
 ViterbiPlan viterbi_plan(const Shape& s, int kind)
 {
     ViterbiPlan p{};
-    const char* force = std::getenv("LAST_FORCE_SOLO");
-    if (force && force[0] == '1') return p;
-    const char* off = std::getenv("LAST_CLUSTER_VITERBI");
-    if (off && off[0] == '0') return p;
+    if (opt(LAST_OPT_FORCE_SOLO) || !opt(LAST_OPT_CLUSTER_VITERBI)) return p;
     if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kC2Hdr || s.T < 1) return p;
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;      // one 32-bit buffer descriptor per item
     if ((size_t)s.C * s.C >= (size_t)kVNone) return p;                    // 17-bit arc indices in the exchange
@@ -460,7 +487,7 @@ void launch_cluster_viterbi(const Shape& s, const ViterbiPlan& p, u64* xv, const
     a.w = w; a.len = lengths; a.bp = bp; a.final_state = final_state; a.score = score;
     a.item_status = item_status; a.xa = xv;
     a.B = s.B; a.T = s.T; a.C = s.C; a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl;
-    a.spin_limit = 1 << 20;
+    a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     const bool full = p.K == kClMaxK;      // (the instantiation without a test per exchanged word)
     if (bp && full) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
     else if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
@@ -489,7 +516,21 @@ void dispatch_group(int V1, F&& f)
 
 extern "C" {
 
-int32_t last_version(void) { return 1; }
+int32_t last_version(void) { return 2; }
+
+last_status_t last_set_option(int32_t option, int32_t value)
+{
+    if (option < 0 || option >= LAST_OPT_COUNT_) return LAST_ERR_UNSUPPORTED;
+    if (option == LAST_OPT_CLUSTER_GENERATION && (value < 0 || value > 3)) return LAST_ERR_UNSUPPORTED;
+    if (option == LAST_OPT_SPIN_LIMIT && value < 1) return LAST_ERR_UNSUPPORTED;
+    g_opt[option].store(value, std::memory_order_relaxed);
+    return LAST_OK;
+}
+
+int32_t last_get_option(int32_t option)
+{
+    return option < 0 || option >= LAST_OPT_COUNT_ ? -1 : opt(option);
+}
 
 const char* last_hip_error_string(void) { return hipGetErrorString(g_last_hip_error); }
 

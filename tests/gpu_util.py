@@ -1,5 +1,7 @@
 """Helpers shared by the GPU parity tests (tolerances from the benchmark spec:
 indices bit-exact, log-partition 1e-5 relative, posteriors 1e-5 absolute)."""
+import contextlib
+
 import numpy as np
 import torch
 
@@ -26,3 +28,14 @@ def assert_dist_close(got, want, what="D"):
     assert np.array_equal(got[~fin], want[~fin]) or np.all(np.isnan(want[~fin]) == np.isnan(got[~fin]))
     err = np.abs(got[fin] - want[fin]) / np.maximum(1.0, np.abs(want[fin]))
     assert err.size == 0 or err.max() <= TOL_D_REL, (what, err.max(), got, want)
+
+
+@contextlib.contextmanager
+def library_option(option, value):
+    """Set a process-wide option of the library for the duration of a with-block."""
+    from paper_2304_13134_amd import binding as lb
+    old = lb.set_option(option, value)
+    try:
+        yield
+    finally:
+        lb.set_option(option, old)

@@ -8,7 +8,7 @@ import oracle
 from oracle import brute_force as bf
 from paper_2304_13134_amd import binding as lb
 from paper_2304_13134_amd import workloads
-from gpu_util import TOL_POST_ABS, announce, assert_dist_close, dev
+from gpu_util import TOL_POST_ABS, announce, assert_dist_close, dev, library_option
 
 pytestmark = pytest.mark.gpu
 
@@ -111,14 +111,26 @@ def test_state_counts_around_256_and_every_pair_parity():
         check_path(cfg)
 
 
-def test_first_generation_clustered_kernel(monkeypatch):
-    # LAST_CLUSTER_V2=0 selects the kernel with one exchange per frame; it stays covered
-    monkeypatch.setenv("LAST_CLUSTER_V2", "0")
-    announce("first-generation clustered kernel: B=3 T=40 V=256")
-    check_posteriors(workloads.config(2, B=3, T=40))
-    for V in (65, 130, 263):
-        cfg = workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9)
+def test_first_generation_clustered_kernel():
+    # the kernel with one exchange per frame stays covered
+    with library_option(lb.OPT_CLUSTER_GENERATION, 1):
+        announce("first-generation clustered kernel: B=3 T=40 V=256")
+        check_posteriors(workloads.config(2, B=3, T=40))
+        for V in (65, 130, 263):
+            cfg = workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9)
+            check_posteriors(cfg)
+
+
+@pytest.mark.parametrize("generation", [2, 3])
+def test_clustered_kernel_generations_at_256_labels(generation):
+    # both kernels that take 256 labels (eight / sixteen workgroups per direction and item) stay covered
+    with library_option(lb.OPT_CLUSTER_GENERATION, generation):
+        announce("clustered kernel generation", generation, ": B=3 T=40 V=256, every pair parity, B=37")
+        check_posteriors(workloads.config(2, B=3, T=40))
+        cfg = workloads.dense(B=6, T=9, V=256, order=1, sigma=2.0, seed=556, len_lo=1, len_hi=9)
+        cfg["lengths"] = np.array([1, 2, 3, 4, 8, 9], dtype=np.int32)
         check_posteriors(cfg)
+        check_posteriors(workloads.dense(B=37, T=6, V=256, order=1, sigma=2.0, seed=3737, len_lo=0, len_hi=6))
 
 
 def test_more_items_than_clusters():
@@ -129,13 +141,13 @@ def test_more_items_than_clusters():
     check_path(cfg)
 
 
-def test_one_workgroup_shortest_path_kernels(monkeypatch):
-    # LAST_CLUSTER_VITERBI=0 selects the kernels with one workgroup per item; they stay covered
-    monkeypatch.setenv("LAST_CLUSTER_VITERBI", "0")
-    announce("one-workgroup shortest path: B=3 T=40 V=256, and ragged sizes")
-    check_path(workloads.config(2, B=3, T=40))
-    for V in (5, 130, 200, 263):
-        check_path(workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9))
+def test_one_workgroup_shortest_path_kernels():
+    # the shortest-path kernels with one workgroup per item stay covered
+    with library_option(lb.OPT_CLUSTER_VITERBI, 0):
+        announce("one-workgroup shortest path: B=3 T=40 V=256, and ragged sizes")
+        check_path(workloads.config(2, B=3, T=40))
+        for V in (5, 130, 200, 263):
+            check_path(workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9))
 
 
 def forbid_arcs(cfg, seed):
@@ -148,7 +160,7 @@ def forbid_arcs(cfg, seed):
     return cfg
 
 
-def test_wide_dynamic_range_is_exact_or_flagged(monkeypatch):
+def test_wide_dynamic_range_is_exact_or_flagged():
     # weights of up to about +-50 with forbidden arcs: exact on the bandwidth path, status 0
     announce("wide range: sigma 12 with forbidden arcs")
     cfg = forbid_arcs(workloads.dense(B=3, T=14, V=256, order=1, sigma=12.0, seed=1200, len_lo=11, len_hi=14), 5)
@@ -171,8 +183,8 @@ def test_wide_dynamic_range_is_exact_or_flagged(monkeypatch):
     # the log-domain kernels take the same input without a flag; float32 weights of this size resolve
     # 2^-16, so the marginals agree to a few 1e-5 only
     announce("wide range: sigma 40, one workgroup per item")
-    monkeypatch.setenv("LAST_FORCE_SOLO", "1")
-    D, gamma, status = run_posteriors(cfg)
+    with library_option(lb.OPT_FORCE_SOLO, 1):
+        D, gamma, status = run_posteriors(cfg)
     assert np.all(status == 0)
     assert_dist_close(D, D_o)
     assert np.max(np.abs(gamma - gamma_o)) <= 5.0e-5
