@@ -322,9 +322,25 @@ __device__ __forceinline__ void c2_put2(float x, float y, buf_t r, unsigned voff
     }
 }
 
-// (No 16-byte buffer stores: with a scalar offset the compiler leaves no wait state between such a store
-// and the next instruction that overwrites its data registers, and on this chip lanes of the store were
-// then seen to pick up the new contents.  Stores are 8 bytes at most.)
+// 16-byte stores.  With a scalar offset the compiler leaves no wait state between such a store and the next
+// instruction that overwrites its data registers, and on this chip lanes of the store were then seen to
+// pick up the new contents: the store sits in an asm statement together with its wait states.  It pays:
+// the address path takes a vector memory instruction lane by lane, whatever its width, so four floats per
+// lane cost what two do.  (Adding to the gradient tensor stays at load - add - store of eight bytes.)
+typedef float c2_v4f __attribute__((ext_vector_type(4)));
+template <bool ACC>
+__device__ __forceinline__ void c2_put4(float x0, float x1, float x2, float x3, buf_t r, unsigned voff, unsigned soff,
+                                        bool ok0, bool ok1, bool ok2, bool ok3)
+{
+    if constexpr (ACC) {
+        c2_put2<true>(x0, x1, r, voff, soff, ok0, ok1);
+        c2_put2<true>(x2, x3, r, voff + 8u, soff, ok2, ok3);
+    } else {
+        c2_v4f d;
+        d.x = x0; d.y = x1; d.z = x2; d.w = x3;
+        asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen\n\ts_nop 2" :: "v"(d), "v"(voff), "s"(r), "s"(soff));
+    }
+}
 
 // Lane -> pair of neighbouring own columns for the "all rows x own columns" frames.  Every lane with
 // columns stores 8 bytes per row: the pairs start behind the column that takes no label arcs (column 0 of
@@ -877,7 +893,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
     const bool st4 = 4 * lane < min(C, kC2PC);             // the lane has a column nobody else has
     // P-step (all rows x own columns): wave <-> rows [33 wave, 33 wave + 33); seven groups of nine lanes take
     // every seventh row (row slot 7 j + group, j < 5; slots 33 and 34 are unused), a lane four neighbouring
-    // own columns (16-byte loads, 8-byte stores).  One shift per own column; the lanes' partial sums of a row
+    // own columns (16-byte loads and stores).  One shift per own column; the lanes' partial sums of a row
     // meet in LDS, where thread <-> row qT adds them up and publishes.
     const int gq = min(lane / kC2QL, kC2QG - 1), ci = lane - kC2QL * (lane / kC2QL);
     const C2Quad qd = c2_quad(ci, lane < kC2QL * kC2QG, g.r0, g.nr);    // (column 0 is the empty label)
@@ -1180,10 +1196,9 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                         if (rS == ri) facS = fac;
                         const unsigned gso = (unsigned)tF * frb + roff(ri);
                         const unsigned so4 = ri < nrw ? coff4s : kC2Off;
-                        c2_put2<ACC>(EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bg[0]) * fac, EFb[B_][ri][1] * bg[1] * fac, grs, so4, gso,
-                                     cb4 >= 4 * lane, cb4 + 1 >= 4 * lane);
-                        c2_put2<ACC>(EFb[B_][ri][2] * bg[2] * fac, EFb[B_][ri][3] * bg[3] * fac, grs, so4 + 8u, gso,
-                                     cb4 + 2 >= 4 * lane, cb4 + 3 >= 4 * lane);
+                        c2_put4<ACC>(EFb[B_][ri][0] * (lane == 0 ? brow[ri] : bg[0]) * fac, EFb[B_][ri][1] * bg[1] * fac,
+                                     EFb[B_][ri][2] * bg[2] * fac, EFb[B_][ri][3] * bg[3] * fac, grs, so4, gso,
+                                     cb4 >= 4 * lane, cb4 + 1 >= 4 * lane, cb4 + 2 >= 4 * lane, cb4 + 3 >= 4 * lane);
                     }
                 }
                 if (GAMMA && iF >= ph1 && nstF > 0) c2_put<ACC>(sprod * facS, grs, offSt, (unsigned)tF * frb);
@@ -1277,8 +1292,8 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     for (int j = 0; j < kC2QJ; ++j) {
                         const unsigned so = gso + rowF0 + (unsigned)(kC2QG * j) * pitch;
                         const unsigned oj = j < jl ? offq : kC2Off;
-                        c2_put2<ACC>(aq[j] * EQ[B_][j][0] * fq[0], aq[j] * EQ[B_][j][1] * fq[1], grs, oj, so, vok[0], vok[1]);
-                        c2_put2<ACC>(aq[j] * EQ[B_][j][2] * fq[2], aq[j] * EQ[B_][j][3] * fq[3], grs, oj + 8u, so, vok[2], vok[3]);
+                        c2_put4<ACC>(aq[j] * EQ[B_][j][0] * fq[0], aq[j] * EQ[B_][j][1] * fq[1], aq[j] * EQ[B_][j][2] * fq[2],
+                                     aq[j] * EQ[B_][j][3] * fq[3], grs, oj, so, vok[0], vok[1], vok[2], vok[3]);
                         __builtin_amdgcn_sched_barrier(0);     // one row at a time: registers
                     }
                     if (wave == 0 && fok) {

@@ -1,59 +1,69 @@
 // Third generation of the clustered forward-backward for the full 1-gram context dependency with
-// exactly 256 labels (C = 257 states; arXiv 2304.13134, Eq. 2 / Eq. 1, Sections 4.1, 4.2.2):
-// sixteen workgroups of four waves per role and item, TWO workgroups per compute unit.
+// exactly 256 labels (C = 257 states; arXiv 2304.13134, Eq. 2 / Eq. 1, Sections 4.1, 4.2.2).
 //
-// The recursion is the one of cluster2_kernels.hpp: an item is walked from both ends at once (K "alpha"
-// workgroups upwards, K "beta" workgroups downwards, meeting in the middle, marginals in the second half),
-// frames are taken in pairs with ONE exchange per pair (F-step: whole vector -> own states, no
-// communication; P-step: own states -> partial sums for all states, published and gathered), arithmetic
-// is in the scaled linear domain E = 2^(w log2 e - s).  What changes is the shape of the work:
-//   * K = 16 workgroups of 256 threads per role, 256 registers per lane: two workgroups share a compute
-//     unit.  They belong to different recursions (or different slices of one), so while one of them sits
-//     in a barrier, waits for its exchange or for memory, the other one computes: the overlap that one
-//     workgroup in lock-step cannot have comes from the hardware's wave scheduler.
-//   * Ownership: workgroup k owns the 16 label states [1 + 16 k, 17 + 16 k); the start state 0, which
-//     receives no label arcs, rides along as a 17th state of workgroup 0.  With 256 label states every
-//     access is regular: a row of a frame is its empty-label weight followed by 256 label weights, which
-//     one wave reads with one 16-byte load per lane ("own rows x all columns": alpha P-step, beta F-step);
-//     "all rows x own columns" is read 16 rows per instruction, four lanes x 16 bytes per row (alpha
-//     F-step, beta P-step).  The start state's row (or, in the other pattern, workgroup 0's 17th row) is a
-//     fifth, mostly masked, instruction per frame.
-//   * One shift s per WAVE and frame (largest weight of the wave's share), applied when the waves'
-//     partial sums meet: no maxima through LDS, no barrier in the exp pass.  The empty-label weights of
-//     the own states have a shift of their own, the same in every wave.
-//   * Exchange words as before, [value:32 | tag:16 | exponent:16], but gathered two words per 16-byte load:
-//     a lane pair shares two neighbouring states and splits the sixteen producers; the halves meet through
-//     one DPP swap.  The start state's sixteen words sit on sixteen lanes and are added up by a DPP scan.
-//     The order of every addition is fixed, so the gathered vector is bit-identical in all workgroups.
+// The recursion is the one of cluster2_kernels.hpp: an item is walked from both ends at once (K = 8 "alpha"
+// workgroups upwards, K "beta" workgroups downwards, eight waves each, one workgroup per compute unit,
+// meeting in the middle, marginals in the second half), frames are taken in pairs with ONE exchange per
+// pair (F-step: whole vector -> own states, no communication; P-step: own states -> partial sums for all
+// states, published and gathered), arithmetic is in the scaled linear domain E = 2^(w log2 e - s).  What
+// changes is how the work is cut, with two things measured on this chip in mind: the address path of a
+// compute unit takes a vector memory instruction lane by lane (about 0.4 clocks per lane plus 8 per
+// instruction, whatever the width), so every access is 16 bytes per lane and no lane loads what another one
+// has; and with two waves per SIMD the vector ALUs are the other bound, so nothing is computed twice.
+//   * Ownership goes down to the wave: wave w of workgroup k ("sub-owner" u = 8 k + w) owns the four label
+//     states 1 + 4 u .. 4 + 4 u; the start state 0, which receives no label arcs, is a fifth state of
+//     sub-owner 0.  A wave needs the other waves of its workgroup only where sums over rows or columns
+//     cross waves.  With 256 label states every access is regular: a row of a frame is its empty-label
+//     weight followed by 256 label weights.
+//       "row pattern" (alpha P-step, beta F-step): the wave's own four rows, one 16-byte load per lane and
+//           row; sub-owner 0 reads the start state's row as a fifth one;
+//       "column pattern" (alpha F-step, beta P-step): all 256 label rows x the workgroup's 32 columns,
+//           eight rows per instruction (eight lanes x 16 bytes per row), 32 rows per wave;
+//       "odd elements": one 4-byte load per wave and frame fetches the empty-label weights of the own
+//           states (lanes 0..3, and lane 4 the start state's) and, in the column pattern, the start state's
+//           label weights into the wave's own columns (lanes 8..11).
+//     17 weights per lane and frame.
+//   * One shift s per wave and frame (largest weight of the wave's share), carried along with the wave's
+//     partial sums and applied where they meet: no maxima through LDS, no barrier in the exp pass.
+//   * Stored state vectors are (value, exponent) pairs, [B][T+1][C][2]: whoever reads a state of the other
+//     side gets its exponent with the same load (own states have one exponent per sub-owner).
+//   * Exchange words as before, [value:32 | tag:16 | exponent:16], gathered two words per 16-byte load: the
+//     four lanes of a quad share two neighbouring states and split the eight producers; their parts meet
+//     through two DPP swaps.  The start state's eight words sit on eight lanes and are added up by a DPP
+//     scan.  The order of every addition is fixed, so the gathered vector is bit-identical in all workgroups.
+//   * Memory requests are spread over the pair instead of being issued in one burst (a wave whose request
+//     finds the address path busy stands still): the frames of the pair after the next are requested piece
+//     by piece between the pieces of the exp pass and inside the gather, the look at the exchange before
+//     them, because a wave's loads return in order.  Marginals leave as 16-byte stores.
 //
-// Per pair and workgroup (alpha; beta mirrors it): F-step sums -> barrier -> own states (every wave by
-// itself) -> P-step sums -> barrier -> publish -> marginals of the pair (second half of the item) -> exp
-// pass of the NEXT pair, with the first look at the exchange and the requests for the pair after the next
-// in its middle -> gather (two barriers).  Requests run one pair ahead of the exp pass that consumes them;
-// the look is issued before them, because a wave's loads return in order.
+// Per pair and workgroup (alpha; beta mirrors it): F-step sums -> barrier -> own states -> P-step sums ->
+// barrier -> publish -> marginals of the pair (second half of the item) -> exp pass of the NEXT pair ->
+// gather (two barriers).
 #pragma once
 #include "cluster2_kernels.hpp"
 
 namespace last {
 
-constexpr int kC3Threads = 256;
-constexpr int kC3Waves = 4;
-constexpr int kC3K = 16;        // workgroups per role and item
+constexpr int kC3Waves = 8;
+constexpr int kC3Threads = 64 * kC3Waves;
+constexpr int kC3K = 8;         // workgroups per role and item
 constexpr int kC3C = 257;       // states: the start state and 256 label states
 constexpr int kC3XS = 272;      // exchange words per producer and slot (257 used; even: word pairs are 16-byte aligned)
-constexpr int kC3RS = 20;       // LDS pitch of a column's sixteen partial sums (conflict-free 16-byte reads)
+constexpr int kC3RS = 12;       // LDS pitch of a column's eight partial sums (16-byte reads)
 constexpr unsigned kC3Sc1 = 16; // cache policy of the exchange loads: agent scope, served by the XCD's L2
+constexpr unsigned kC3SP = kC3C * 8u;   // bytes of a stored state vector: (value, exponent) pairs
 
 // LDS map (floats / ints)
 constexpr int kC3Full = 0;                      // [272] whole state vector: label state y at y - 1, the start state at 256
-constexpr int kC3Red = kC3Full + 272;           // [16][20] alpha F-step: partial sums per own column; [272] beta P-step: row sums
-constexpr int kC3Pacc = kC3Red + 16 * kC3RS;    // [4][256] alpha P-step: partial sums per wave and column
-constexpr int kC3Bl = kC3Pacc + 4 * 256;        // [32] empty-label terms of the own states
-constexpr int kC3OwnS = kC3Bl + 32;             // [32] own states (beta)
-constexpr int kC3Row = kC3OwnS + 32;            // [32] beta F-step: row sums, [32] their shifts
-constexpr int kC3Ctl = kC3Row + 64;             // [32] ints: [0] exponent of full_s, [4..7] F shifts, [8] timeout,
-                                                //            [11] range, [12..15] P shifts, [24..27] gather maxima
-constexpr int kC3RedB = kC3Ctl + 32;            // [32] block reductions
+constexpr int kC3Red = kC3Full + 272;           // [32][12] alpha F-step: the waves' sums per own column; [272] beta P-step: row sums
+constexpr int kC3Pacc = kC3Red + 32 * kC3RS;    // [8][256] alpha P-step: partial sums per wave and column
+constexpr int kC3Bl = kC3Pacc + 8 * 256;        // [8][8] terms of the own states' empty-label arcs (per wave: 4 states, the start state)
+constexpr int kC3OwnS = kC3Bl + 64;             // [36] beta: own states, [4 w + j], the start state at 32
+constexpr int kC3Ctl = kC3OwnS + 40;            // [64] ints: [0] exponent of full_s, [1] timeout, [2] range, per wave: [8..15] F shift
+                                                //            (alpha) / exponent of the own states (beta), [16..23] exponent of the
+                                                //            P-step sums, [24..31] of the odd P-step terms (beta), [32..39] beta: the
+                                                //            waves' parts of the start state's sum, [40..47] gather maxima
+constexpr int kC3RedB = kC3Ctl + 64;            // [32] block reductions
 constexpr int kC3Lds = kC3RedB + 32;
 static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl % 4 == 0, "16-byte LDS accesses");
 
@@ -76,6 +86,11 @@ static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl 
 #define C3_NOTE(a, p, k, v) do { } while (0)
 #endif
 
+__device__ __forceinline__ uint4 c3_ld4(buf_t r, unsigned voff, unsigned soff)
+{
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+    return __builtin_bit_cast(uint4, v);
+}
 __device__ __forceinline__ uint4 c3_xload4(buf_t r, unsigned voff, unsigned soff)
 {
     const auto v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, (int)kC3Sc1);
@@ -86,36 +101,93 @@ __device__ __forceinline__ uint2 c3_xload2(buf_t r, unsigned voff, unsigned soff
     const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, (int)kC3Sc1);
     return __builtin_bit_cast(uint2, v);
 }
+__device__ __forceinline__ void c3_xstore(u64 w, buf_t r, unsigned voff, unsigned soff)
+{
+    typedef decltype(__builtin_amdgcn_raw_buffer_load_b64(r, 0, 0, 0)) b64_t;
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, w), r, (int)voff, (int)soff, 0);
+}
+// (value, exponent) pair of a stored state vector
+__device__ __forceinline__ void c3_load_pair(buf_t r, unsigned voff, unsigned soff, float& v, int& e)
+{
+    const uint2 x = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0));
+    v = __uint_as_float(x.x);
+    e = (int)x.y;
+}
+__device__ __forceinline__ void c3_store_pair(float v, int e, buf_t r, unsigned voff, unsigned soff)
+{
+    uint2 x;
+    x.x = __float_as_uint(v);
+    x.y = (unsigned)e;
+    typedef decltype(__builtin_amdgcn_raw_buffer_load_b64(r, 0, 0, 0)) b64_t;
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, x), r, (int)voff, (int)soff, 0);
+}
 
+// largest of three floats in one instruction (fmaxf alone costs a second instruction per operand that
+// comes from memory: the compiler quiets signalling NaNs first)
+__device__ __forceinline__ float c3_max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+// largest int of a wave, wave-uniform
+__device__ __forceinline__ int c3_wave_max(int v)
+{
+    return c2_wave_max_key(v);
+}
+
+// D split into an integer and a fraction, so that the scale of a marginal needs no double arithmetic
+struct C3D {
+    int i;
+    float f;
+};
+__device__ __forceinline__ C3D c3_split(double D2)
+{
+    C3D d;
+    if (D2 > -1.0e9 && D2 < 1.0e9) {
+        const double fl = __builtin_floor(D2);
+        d.i = (int)fl;
+        d.f = (float)(D2 - fl);
+    } else {               // (no path through the item: every marginal is a product with a zero)
+        d.i = 0;
+        d.f = 0.f;
+    }
+    return d;
+}
 // 2^(e - D) for a marginal, capped so that it stays finite; the largest exponent seen is kept for the
 // range flag (see c2_marginal_scale)
-__device__ __forceinline__ float c3_mscale(int e, double D2, float& xmax)
+__device__ __forceinline__ float c3_mscale(int e, const C3D& D, float& xmax)
 {
-    const float x = (float)((double)e - D2);
+    const float x = (float)(e - D.i) - D.f;
     xmax = fmaxf(xmax, x);
     return fast_exp2(fminf(x, 126.f));
 }
 
-__device__ __forceinline__ float c3_max4(const float (&x)[4])
-{
-    return fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-}
-
-// One exchange slot as a thread sees it: two neighbouring label states from eight producers (the lane
-// pair's other lane has the other eight) and one of the sixteen words of the start state.
+// One exchange slot as a thread sees it: two neighbouring label states from two of the eight producers
+// (the other lanes of its quad have the other six) and one of the eight words of the start state.
 struct C3Look {
-    uint4 q[8];
+    uint4 q[2];
     uint2 z;
 };
 
 __device__ __forceinline__ void c3_look(buf_t xrs, unsigned slot_off, unsigned voffq, unsigned voffz, C3Look& lk)
 {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) lk.q[j] = c3_xload4(xrs, voffq, slot_off + (unsigned)(j * kC3XS * 8));
+    lk.q[0] = c3_xload4(xrs, voffq, slot_off);
+    lk.q[1] = c3_xload4(xrs, voffq, slot_off + (unsigned)(kC3XS * 8));
     lk.z = c3_xload2(xrs, voffz, slot_off);
 }
 
-// Gathering one exchange slot: the sixteen partial values of every state, added up in a fixed order
+// sum over the wave's four rows of sixteen lanes, lane by lane (every lane gets the total of the four lanes
+// that sit at its place in their rows)
+__device__ __forceinline__ float c3_rows_sum(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
+// Gathering one exchange slot: the eight partial values of every state, added up in a fixed order
 // relative to the largest producer exponent; the vector ends in full_s, renormalised by the largest
 // magnitude present, its exponent in ctl_s[0].  Every thread calls; ends with a workgroup barrier.
 // `after_poll` runs once all words are there, before they are added up.
@@ -130,9 +202,7 @@ __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned
     const unsigned tagw = (tag & 0xFFFFu) << 16;
     int n = 0;
     for (;;) {
-        unsigned diff = lk.z.y ^ tagw;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) diff |= (lk.q[j].y ^ tagw) | (lk.q[j].w ^ tagw);
+        const unsigned diff = (lk.z.y ^ tagw) | (lk.q[0].y ^ tagw) | (lk.q[0].w ^ tagw) | (lk.q[1].y ^ tagw) | (lk.q[1].w ^ tagw);
         if ((diff >> 16) == 0 || dead) break;
         if (++n > limit) { dead = 1; break; }
         __builtin_amdgcn_s_sleep(1);
@@ -140,62 +210,69 @@ __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned
     }
     if (relooks) *relooks = n;
     after_poll();
-    int e[8];
-    int hm = -(1 << 30);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        e[j] = (int)(short)(unsigned short)lk.q[j].y;
-        hm = max(hm, e[j]);
+    const int e0 = (int)(short)(unsigned short)lk.q[0].y, e1 = (int)(short)(unsigned short)lk.q[1].y;
+    int hm = max(e0, e1);
+    // (16-bit exponents: differences in [-65535, 0])
+    float vlo = __builtin_ldexpf(__uint_as_float(lk.q[0].x), e0 - hm) + __builtin_ldexpf(__uint_as_float(lk.q[1].x), e1 - hm);
+    float vhi = __builtin_ldexpf(__uint_as_float(lk.q[0].z), e0 - hm) + __builtin_ldexpf(__uint_as_float(lk.q[1].z), e1 - hm);
+    // the other six producers of the same two states: the other lanes of the quad, in two steps (float
+    // addition commutes, so all four lanes end up with the same bits)
+    {
+        const int ho = dpp_i<0xB1>(hm, hm);
+        const float olo = dpp_f<0xB1>(vlo, vlo), ohi = dpp_f<0xB1>(vhi, vhi);
+        const int hr = max(hm, ho);
+        vlo = __builtin_ldexpf(vlo, hm - hr) + __builtin_ldexpf(olo, ho - hr);
+        vhi = __builtin_ldexpf(vhi, hm - hr) + __builtin_ldexpf(ohi, ho - hr);
+        hm = hr;
     }
-    float vlo = 0.f, vhi = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        vlo += __builtin_ldexpf(__uint_as_float(lk.q[j].x), e[j] - hm);      // (16-bit exponents: differences in [-65535, 0])
-        vhi += __builtin_ldexpf(__uint_as_float(lk.q[j].z), e[j] - hm);
+    {
+        const int ho = dpp_i<0x4E>(hm, hm);
+        const float olo = dpp_f<0x4E>(vlo, vlo), ohi = dpp_f<0x4E>(vhi, vhi);
+        const int hr = max(hm, ho);
+        vlo = __builtin_ldexpf(vlo, hm - hr) + __builtin_ldexpf(olo, ho - hr);
+        vhi = __builtin_ldexpf(vhi, hm - hr) + __builtin_ldexpf(ohi, ho - hr);
+        hm = hr;
     }
-    // the other eight producers of the same two states: the neighbouring lane (float addition commutes,
-    // so both lanes of a pair end up with the same bits)
-    const int ho = dpp_i<0xB1>(hm, hm);
-    const float olo = dpp_f<0xB1>(vlo, vlo), ohi = dpp_f<0xB1>(vhi, vhi);
-    const int href = max(hm, ho);
-    vlo = __builtin_ldexpf(vlo, hm - href) + __builtin_ldexpf(olo, ho - href);
-    vhi = __builtin_ldexpf(vhi, hm - href) + __builtin_ldexpf(ohi, ho - href);
-    // the start state: lane l of every row of sixteen holds producer l's word; a scan leaves the sum in lane 15
+    const int href = hm;          // largest of the eight producers' exponents: the same in every lane
+    // the start state: lane l of every group of eight holds producer l's word; a scan leaves the sum in lane 7
     float vz = __builtin_ldexpf(__uint_as_float(lk.z.x), (int)(short)(unsigned short)lk.z.y - href);
     vz += dpp_f<0x111>(0.f, vz);
     vz += dpp_f<0x112>(0.f, vz);
     vz += dpp_f<0x114>(0.f, vz);
-    vz += dpp_f<0x118>(0.f, vz);
-    const float v0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vz), 15));
+    const float v0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vz), 7));
     // renormalise by the largest magnitude actually present (non-negative floats order like integers)
-    int mub = wave_max_dpp(max(__float_as_int(vlo), __float_as_int(vhi)));
+    int mub = c3_wave_max(max(__float_as_int(vlo), __float_as_int(vhi)));
     mub = max(mub, __float_as_int(v0));
-    if (lane == 0) ctl_s[24 + wave] = mub;
-    if (dead) ctl_s[8] = 1;
+    if (lane == 0) ctl_s[40 + wave] = mub;
+    if (dead) ctl_s[1] = 1;
     c2_barrier();
-    const int4 m0 = *(const int4*)&ctl_s[24];
-    const int mxb = max(max(m0.x, m0.y), max(m0.z, m0.w));
+    const int4 m0 = *(const int4*)&ctl_s[40], m1 = *(const int4*)&ctl_s[44];
+    const int mxb = max(max(max(m0.x, m0.y), max(m0.z, m0.w)), max(max(m1.x, m1.y), max(m1.z, m1.w)));
     const int mx = mxb > 0 ? float_exponent(__int_as_float(mxb)) : 0;
-    full_s[tid] = c2_scale((tid & 1) ? vhi : vlo, -mx);
+    // lanes 0 and 1 of a quad write its two states
+    if ((tid & 2) == 0) full_s[2 * (tid >> 2) + (tid & 1)] = __builtin_ldexpf((tid & 1) ? vhi : vlo, -mx);
     if (tid == 0) {
-        full_s[256] = c2_scale(v0, -mx);
+        full_s[256] = __builtin_ldexpf(v0, -mx);
         ctl_s[0] = S0 + href + mx;
     }
     c2_barrier();
 }
 
-// D = log2 sum_q a_mid[q] b_mid[q] with one exponent per block of states on either side
-// (block of the start state: 0; of label state q: (q - 1) / 16)
-__device__ __forceinline__ double c3_meeting(const float* ah, const float* bh, const int* Sa, const int* Sb, float* red)
+// D = log2 sum_q a_mid[q] b_mid[q]; both vectors are stored as (value, exponent) pairs
+__device__ __forceinline__ double c3_meeting(const uint2* ah, const uint2* bh, float* red)
 {
-    int xmax = -(1 << 30);
-    for (int k = 0; k < kC3K; ++k) xmax = max(xmax, Sa[k] + Sb[k]);
-    float part = 0.f;
-    for (int q = threadIdx.x; q < kC3C; q += blockDim.x) {
-        const int k = q == 0 ? 0 : (q - 1) >> 4;
-        part += c2_scale(ah[q] * bh[q], Sa[k] + Sb[k] - xmax);
+    const int q = threadIdx.x;
+    float pv = 0.f;
+    int pe = 0;
+    if (q < kC3C) {
+        const uint2 x = ah[q], y = bh[q];
+        pv = __uint_as_float(x.x) * __uint_as_float(y.x);
+        pe = (int)x.y + (int)y.y;
     }
-    const float tot = block_sum(part, red);
+    const float xm = block_max(pv > 0.f ? (float)pe : -3.0e38f, red);
+    if (!(xm > -1.0e38f)) return -(double)__builtin_huge_valf();
+    const int xmax = (int)xm;
+    const float tot = block_sum(pv > 0.f ? __builtin_ldexpf(pv, pe - xmax) : 0.f, red);
     return (double)xmax + (double)__log2f(tot);
 }
 
@@ -218,18 +295,18 @@ __device__ __forceinline__ void c3_finish_item(const ClusterArgs& a, int b, bool
     }
 }
 
-// Geometry shared by both roles.  "Row pattern": a wave takes four rows of the workgroup's sixteen (and
-// wave 0 of workgroup 0 the start state's row), a lane four neighbouring label columns of each.  "Column
-// pattern": a wave takes 64 of the 256 label states' rows (and wave 0 the start state's), sixteen per
-// instruction, a lane four of the workgroup's sixteen columns.
+// Geometry shared by both roles (see the patterns at the top of the file).
 struct C3Geom {
-    int lane, wave, k;
-    int rg, ci;            // column pattern: row inside the instruction, quad of own columns
-    bool xC, xR;           // the lane (column pattern) / the wave (row pattern) has the extra row
-    bool olane;            // lane <-> own state: 0..15 the label states, 16 the start state (workgroup 0)
-    int ostate, oidx;      // that state and its place in full_s
-    unsigned voffC, voffCx, voffR, voffRx, voffB;
-    unsigned rowC0, rowR0; // scalar: first row of the wave in either pattern
+    int lane, wave, k, u;
+    int rg, ci;            // column pattern: row inside the instruction (0..7), quad of own columns (0..7)
+    bool xR;               // sub-owner 0: the wave also owns the start state
+    bool mvR, mvC;         // the lane has an odd element (row / column pattern)
+    int midx;              // place in full_s of the state the lane's odd element starts from
+    unsigned voffC, voffR; // lane offsets of the 16-byte accesses
+    unsigned voffMr, voffMc;         // ... of the odd elements
+    unsigned voffS;                  // ... of the own states in a stored state vector (lanes 0..3, 4)
+    unsigned voffOc;                 // ... of the states the odd elements of the column pattern lead to
+    unsigned rowC0, rowR0;           // scalar: first row of the wave in either pattern
 };
 __device__ __forceinline__ C3Geom c3_geom(int k)
 {
@@ -238,85 +315,127 @@ __device__ __forceinline__ C3Geom c3_geom(int k)
     g.lane = threadIdx.x & 63;
     g.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     g.k = k;
-    g.rg = g.lane >> 2;
-    g.ci = g.lane & 3;
-    g.xC = g.wave == 0 && g.rg == 0;
-    g.xR = k == 0 && g.wave == 0;
-    g.olane = g.lane < 16 || (g.lane == 16 && k == 0);
-    g.ostate = g.lane < 16 ? 1 + 16 * k + g.lane : 0;
-    g.oidx = g.lane < 16 ? 16 * k + g.lane : 256;
-    g.voffC = (unsigned)(1 + g.rg) * pitch + (unsigned)(1 + 16 * k + 4 * g.ci) * 4u;
-    g.voffCx = g.xC ? (unsigned)(1 + 16 * k + 4 * g.ci) * 4u : kC2Off;
+    g.u = kC3Waves * k + g.wave;
+    g.rg = g.lane >> 3;
+    g.ci = g.lane & 7;
+    g.xR = g.u == 0;
+    const bool l4 = g.lane == 4 && g.xR, lo = g.lane < 4, l8 = g.lane >= 8 && g.lane < 12;
+    g.mvR = lo || l4;
+    g.mvC = lo || l4 || l8;
+    g.midx = lo ? 4 * g.u + g.lane : 256;
+    g.voffC = (unsigned)(1 + g.rg) * pitch + (unsigned)(1 + 32 * k + 4 * g.ci) * 4u;
     g.voffR = (unsigned)(1 + 4 * g.lane) * 4u;
-    g.voffRx = g.xR ? g.voffR : kC2Off;
-    g.voffB = g.olane ? (unsigned)g.ostate * pitch : kC2Off;
-    g.rowC0 = (unsigned)(64 * g.wave) * pitch;
-    g.rowR0 = (unsigned)(1 + 16 * k + 4 * g.wave) * pitch;
+    g.voffMr = lo ? (unsigned)(1 + 4 * g.u + g.lane) * pitch : (l4 ? 0u : kC2Off);
+    g.voffMc = l8 ? (unsigned)(1 + 4 * g.u + g.lane - 8) * 4u : g.voffMr;
+    g.voffS = lo ? (unsigned)(1 + 4 * g.u + g.lane) * 8u : (l4 ? 0u : kC2Off);
+    g.voffOc = l8 ? (unsigned)(1 + 4 * g.u + g.lane - 8) * 8u : g.voffS;
+    g.rowC0 = (unsigned)(32 * g.wave) * pitch;
+    g.rowR0 = (unsigned)(1 + 4 * g.u) * pitch;
     return g;
 }
 
-// A frame's share of one lane: five slots of four neighbouring weights, and an empty-label weight.
+// A frame's share of one lane: four slots of four neighbouring weights, the odd element, and (sub-owner 0,
+// row pattern) the start state's row.
 struct C3Frame {
-    float e[5][4];
-    float b;
+    float e[4][4];
+    float x[4];
+    float m;
 };
-__device__ __forceinline__ void c3_load_cols(C3Frame& f, buf_t wrs, const C3Geom& g, unsigned fo)
+__device__ __forceinline__ void c3_set4(float (&d)[4], const float4& v)
+{
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+}
+// loads of one frame, slot by slot (so that the requests can be spread over other work); slot 4 = the odd element
+// (and, row pattern, the start state's row: sub-owner 0 only)
+__device__ __forceinline__ void c3_load_cols_slot(C3Frame& f, int j, buf_t wrs, const C3Geom& g, unsigned fo)
 {
     constexpr unsigned pitch = kC3C * 4u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float4 x = buf_load4(wrs, g.voffC, fo + g.rowC0 + (unsigned)(16 * j) * pitch);
-        f.e[j][0] = x.x; f.e[j][1] = x.y; f.e[j][2] = x.z; f.e[j][3] = x.w;
+    if (j < 4) c3_set4(f.e[j], buf_load4(wrs, g.voffC, fo + g.rowC0 + (unsigned)(8 * j) * pitch));
+    else f.m = buf_load(wrs, g.voffMc, fo);
+}
+__device__ __forceinline__ void c3_load_rows_slot(C3Frame& f, int j, buf_t wrs, const C3Geom& g, unsigned fo)
+{
+    constexpr unsigned pitch = kC3C * 4u;
+    if (j < 4) {
+        c3_set4(f.e[j], buf_load4(wrs, g.voffR, fo + g.rowR0 + (unsigned)j * pitch));
+    } else {
+        f.m = buf_load(wrs, g.voffMr, fo);
+        if (g.xR) c3_set4(f.x, buf_load4(wrs, g.voffR, fo));
     }
-    const float4 x = buf_load4(wrs, g.voffCx, fo);
-    f.e[4][0] = x.x; f.e[4][1] = x.y; f.e[4][2] = x.z; f.e[4][3] = x.w;
-    f.b = buf_load(wrs, g.voffB, fo);
+}
+__device__ __forceinline__ void c3_load_cols(C3Frame& f, buf_t wrs, const C3Geom& g, unsigned fo)
+{
+#pragma unroll
+    for (int j = 0; j < 5; ++j) c3_load_cols_slot(f, j, wrs, g, fo);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f.x[c] = 0.f;         // (unused in this pattern)
 }
 __device__ __forceinline__ void c3_load_rows(C3Frame& f, buf_t wrs, const C3Geom& g, unsigned fo)
 {
-    constexpr unsigned pitch = kC3C * 4u;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f.x[c] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) c3_load_rows_slot(f, j, wrs, g, fo);
+}
+// exp pass of one frame: E = 2^(w log2 e - s), s = the wave's shift.  mvalid: the lane has an odd element;
+// extra: the wave has the start state's row.
+template <typename Between>
+__device__ __forceinline__ int c3_exp_frame(C3Frame& f, bool mvalid, bool extra, Between&& between)
+{
+    float m = c3_max3(f.e[0][0], f.e[0][1], f.e[0][2]);
+    m = c3_max3(m, f.e[0][3], f.e[1][0]);
+    m = c3_max3(m, f.e[1][1], f.e[1][2]);
+    m = c3_max3(m, f.e[1][3], f.e[2][0]);
+    m = c3_max3(m, f.e[2][1], f.e[2][2]);
+    m = c3_max3(m, f.e[2][3], f.e[3][0]);
+    m = c3_max3(m, f.e[3][1], f.e[3][2]);
+    m = c3_max3(m, f.e[3][3], mvalid ? f.m : LAST_NEG_INF);
+    if (extra) {
+        m = c3_max3(m, f.x[0], f.x[1]);
+        m = c3_max3(m, f.x[2], f.x[3]);
+    }
+    // integer s >= m log2 e, within [kShiftNone, 30000]; -inf (no arc at all) gives kShiftNone
+    const int sl = (int)__builtin_amdgcn_fmed3f(__builtin_ceilf(m * kLog2e), (float)kShiftNone, 30000.f);
+    const int s = c3_wave_max(sl);
+    const float nfs = -(float)s;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float4 x = buf_load4(wrs, g.voffR, fo + g.rowR0 + (unsigned)j * pitch);
-        f.e[j][0] = x.x; f.e[j][1] = x.y; f.e[j][2] = x.z; f.e[j][3] = x.w;
-    }
-    const float4 x = buf_load4(wrs, g.voffRx, fo);
-    f.e[4][0] = x.x; f.e[4][1] = x.y; f.e[4][2] = x.z; f.e[4][3] = x.w;
-    f.b = buf_load(wrs, g.voffB, fo);
-}
-// exp pass of one frame: E = 2^(w log2 e - s), s the wave's shift (sw), and sb the shift of the own states'
-// empty-label weights (the same in every wave).  `extra`: the lane holds the fifth slot.
-__device__ __forceinline__ void c3_exp_frame(C3Frame& f, bool extra, bool olane, int& sw, int& sb)
-{
-    float m = fmaxf(fmaxf(c3_max4(f.e[0]), c3_max4(f.e[1])), fmaxf(c3_max4(f.e[2]), c3_max4(f.e[3])));
-    m = extra ? fmaxf(m, c3_max4(f.e[4])) : m;
-    const int s = shift_for(wave_max_dpp(m));
-    const float fs = (float)s;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            f.e[j][c] = fast_exp2(fmaf(f.e[j][c], kLog2e, -fs));
+            f.e[j][c] = fast_exp2(fmaf(f.e[j][c], kLog2e, nfs));
             c2_pin(f.e[j][c]);
         }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        f.e[4][c] = extra ? fast_exp2(fmaf(f.e[4][c], kLog2e, -fs)) : 0.f;
-        c2_pin(f.e[4][c]);
+        between(j);
     }
-    const int s2 = shift_for(wave_max_dpp(olane ? f.b : LAST_NEG_INF));
-    f.b = olane ? fast_exp2(fmaf(f.b, kLog2e, -(float)s2)) : 0.f;
-    c2_pin(f.b);
-    sw = s;
-    sb = s2;
+    if (extra) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            f.x[c] = fast_exp2(fmaf(f.x[c], kLog2e, nfs));
+            c2_pin(f.x[c]);
+        }
+    }
+    f.m = mvalid ? fast_exp2(fmaf(f.m, kLog2e, nfs)) : 0.f;
+    c2_pin(f.m);
+    return s;
 }
 
-// four marginals of one row slot: two 8-byte stores
+// Four marginals of one row slot: one 16-byte store (the address path takes a vector memory instruction
+// lane by lane, whatever its width).  The store sits in an asm statement together with the wait states
+// that must pass before its data registers are written again: with a scalar offset the compiler leaves
+// none, and on this chip lanes of such a store were seen to pick up the new contents.  (Adding to the
+// gradient tensor: load - add - store, eight bytes at a time.)
+typedef float c3_v4f __attribute__((ext_vector_type(4)));
 template <bool ACC>
 __device__ __forceinline__ void c3_put4(const float (&x)[4], buf_t grs, unsigned voff, unsigned soff)
 {
-    c2_put2<ACC>(x[0], x[1], grs, voff, soff, true, true);
-    c2_put2<ACC>(x[2], x[3], grs, voff + 8u, soff, true, true);
+    if constexpr (ACC) {
+        c2_put2<true>(x[0], x[1], grs, voff, soff, true, true);
+        c2_put2<true>(x[2], x[3], grs, voff + 8u, soff, true, true);
+    } else {
+        c3_v4f d;
+        d.x = x[0]; d.y = x[1]; d.z = x[2]; d.w = x[3];
+        asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen\n\ts_nop 2" :: "v"(d), "v"(voff), "s"(grs), "s"(soff));
+    }
 }
 
 // ------------------------------------------------------------------ alpha role
@@ -335,8 +454,15 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
     const int tid = threadIdx.x;
     const C3Geom g = c3_geom(cg.k);
     const int lane = g.lane, wave = g.wave, k = g.k;
-    const unsigned voffq = (unsigned)((8 * (tid & 1)) * kC3XS + 2 * (tid >> 1)) * 8u;
-    const unsigned voffz = (unsigned)((lane & 15) * kC3XS + 256) * 8u;
+    // gather: quad <-> two neighbouring states, its lanes <-> two producers each
+    const unsigned voffq = (unsigned)((2 * (tid & 3)) * kC3XS + 2 * (tid >> 2)) * 8u;
+    const unsigned voffz = (unsigned)((lane & 7) * kC3XS + 256) * 8u;
+    // publish: threads 0..255 <-> label states; the thread of an own state adds the state's empty-label term
+    const unsigned voffpub = tid < 256 ? (unsigned)(k * kC3XS + tid) * 8u : kC2Off;
+    const int pcol = tid & 255;
+    const bool pubown = (pcol >> 5) == k;
+    const int pubw = (pcol & 31) >> 2;               // the wave that owns the state
+    const int pubbl = 8 * pubw + (pcol & 3);
 
     for (int b = cg.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -346,54 +472,59 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         const int n = GAMMA ? L : mid;
         const int nlast = max(n - 1, 0);
         const size_t fr = (size_t)C * C;
-        float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
-        const float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
-        int* Sa = a.Sa + (size_t)b * (a.T + 1) * kC3K;
-        const int* Sb = a.Sb + (size_t)b * (a.T + 1) * kC3K;
-        u64* xbase = a.xa + (size_t)cg.cg * 2 * kC3K * kC3XS;
+        float* ah = a.ahat + (size_t)b * (a.T + 1) * C * 2;
+        const float* bh = a.bhat + (size_t)b * (a.T + 1) * C * 2;
         const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
         const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
-        const buf_t brs = make_buf(bh, (unsigned)(a.T + 1) * pitch);
-        const buf_t sbrs = make_buf(Sb, (unsigned)(a.T + 1) * (unsigned)(kC3K * sizeof(int)));
-        const buf_t xrs = make_buf(xbase, (unsigned)(2 * kC3K * kC3XS * sizeof(u64)));
+        const buf_t srs = make_buf(ah, (unsigned)(a.T + 1) * kC3SP);        // own side's stored vectors
+        const buf_t ors = make_buf(bh, (unsigned)(a.T + 1) * kC3SP);        // other side's
+        const buf_t xrs = make_buf(a.xa + (size_t)cg.cg * 2 * kC3K * kC3XS, (unsigned)(2 * kC3K * kC3XS * sizeof(u64)));
 
         // a_0 = unit vector at the start state, exponent 0
-        for (int q = tid; q < 272; q += kC3Threads) full_s[q] = q == 256 ? 1.f : 0.f;
-        if (tid < 32) { ctl_s[tid] = 0; bl_s[tid] = 0.f; }
-        if (wave == 0 && g.olane) ah[g.ostate] = g.ostate == 0 ? 1.f : 0.f;
-        if (tid == 0) Sa[k] = 0;
+        if (tid < 272) full_s[tid] = tid == 256 ? 1.f : 0.f;
+        if (tid < 64) { ctl_s[tid] = 0; bl_s[tid] = 0.f; }
+        c3_store_pair(lane == 4 ? 1.f : 0.f, 0, srs, g.voffS, 0u);
         __syncthreads();
 
         C3Frame EF[2], EP[2];
-        int sF[2] = {0, 0}, sP[2] = {0, 0}, sFb[2] = {0, 0}, sPb[2] = {0, 0};
-        // the other side's vectors for the marginals
-        float bF4[2][4], bP4[2][4], bFo[2] = {0.f, 0.f}, bPo[2] = {0.f, 0.f};
-        int sbF[2] = {0, 0}, sbP[2] = {0, 0}, sbPl[2] = {0, 0};
+        int sF[2] = {0, 0}, sP[2] = {0, 0};
+        // the other side's vectors for the marginals: values and exponents
+        float bF4[2][4], bP4[2][4], bFm[2] = {0.f, 0.f}, bPm[2] = {0.f, 0.f};
+        int eF4[2] = {0, 0}, eP4[2] = {0, 0}, eFm[2] = {0, 0}, ePm[2] = {0, 0};
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int c = 0; c < 4; ++c) { bF4[x][c] = 0.f; bP4[x][c] = 0.f; }
-        double D2 = 0.0;
+        C3D D{0, 0.f};
         float xwide = -3.0e38f;
         int dead = 0;
         bool met = false;
 
-        // state vectors of the other side for the marginals of pair p (rows t + 1 of its two frames);
-        // fetched with the pair's frames, and again right after the meeting for the pairs in flight
-        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
+        // state vectors of the other side for the marginals of pair p (rows t + 1 of its two frames), in four
+        // pieces; fetched once the two sides have met, and right after the meeting for the pairs in flight
+        auto other_piece = [&](auto BUF, int p, int piece) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            const unsigned tF1 = (unsigned)(min(2 * p, nlast) + 1), tP1 = (unsigned)(min(2 * p + 1, nlast) + 1);
-            const float4 x = buf_load4(brs, (unsigned)(1 + 16 * k + 4 * g.ci) * 4u, tF1 * pitch);
-            bF4[B_][0] = x.x; bF4[B_][1] = x.y; bF4[B_][2] = x.z; bF4[B_][3] = x.w;
-            bFo[B_] = buf_load(brs, (unsigned)g.ostate * 4u, tF1 * pitch);
-            // block exponents: one per lane, picked where they are used (a wave-uniform address would make
-            // these scalar loads, and every workgroup barrier waits for those)
-            sbF[B_] = __builtin_bit_cast(int, buf_load(sbrs, (unsigned)(lane & 15) * 4u, tF1 * (unsigned)(kC3K * sizeof(int))));
-            const float4 y = buf_load4(brs, g.voffR, tP1 * pitch);
-            bP4[B_][0] = y.x; bP4[B_][1] = y.y; bP4[B_][2] = y.z; bP4[B_][3] = y.w;
-            bPo[B_] = buf_load(brs, (unsigned)g.ostate * 4u, tP1 * pitch);
-            sbP[B_] = __builtin_bit_cast(int, buf_load(sbrs, (unsigned)(lane & 15) * 4u, tP1 * (unsigned)(kC3K * sizeof(int))));
-            sbPl[B_] = __builtin_bit_cast(int, buf_load(sbrs, (unsigned)(lane >> 2) * 4u, tP1 * (unsigned)(kC3K * sizeof(int))));
+            const unsigned tF1 = (unsigned)(min(2 * p, nlast) + 1) * kC3SP, tP1 = (unsigned)(min(2 * p + 1, nlast) + 1) * kC3SP;
+            const unsigned vF = (unsigned)(1 + 32 * k + 4 * g.ci) * 8u, vP = (unsigned)(1 + 4 * lane) * 8u;
+            if (piece == 0) {
+                const uint4 x0 = c3_ld4(ors, vF, tF1), x1 = c3_ld4(ors, vF + 16u, tF1);
+                bF4[B_][0] = __uint_as_float(x0.x); bF4[B_][1] = __uint_as_float(x0.z);
+                bF4[B_][2] = __uint_as_float(x1.x); bF4[B_][3] = __uint_as_float(x1.z);
+                eF4[B_] = (int)x0.y;                 // (the four states have one sub-owner: one exponent)
+            } else if (piece == 1) {
+                c3_load_pair(ors, g.voffOc, tF1, bFm[B_], eFm[B_]);
+            } else if (piece == 2) {
+                const uint4 y0 = c3_ld4(ors, vP, tP1), y1 = c3_ld4(ors, vP + 16u, tP1);
+                bP4[B_][0] = __uint_as_float(y0.x); bP4[B_][1] = __uint_as_float(y0.z);
+                bP4[B_][2] = __uint_as_float(y1.x); bP4[B_][3] = __uint_as_float(y1.z);
+                eP4[B_] = (int)y0.y;
+            } else {
+                c3_load_pair(ors, g.voffS, tP1, bPm[B_], ePm[B_]);
+            }
+        };
+        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
+#pragma unroll
+            for (int piece = 0; piece < 4; ++piece) other_piece(BUF, p, piece);
         };
         auto settle = [&]() __attribute__((always_inline)) {
             int t = 0;
@@ -401,33 +532,34 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             for (int x = 0; x < 2; ++x) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) t |= c2_touch(bF4[x][c]) | c2_touch(bP4[x][c]);
-                t |= c2_touch(bFo[x]) | c2_touch(bPo[x]) | (sbF[x] == 0x7fffffff) | (sbP[x] == 0x7fffffff) | (sbPl[x] == 0x7fffffff);
+                t |= c2_touch(bFm[x]) | c2_touch(bPm[x]) | (eF4[x] == 0x7fffffff) | (eP4[x] == 0x7fffffff)
+                     | (eFm[x] == 0x7fffffff) | (ePm[x] == 0x7fffffff);
             }
-            if (t) ctl_s[9] = 1;          // (never; nobody reads it)
+            if (t) ctl_s[3] = 1;          // (never; nobody reads it)
         };
         auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             c3_load_cols(EF[B_], wrs, g, (unsigned)min(2 * p, nlast) * frb);
             c3_load_rows(EP[B_], wrs, g, (unsigned)min(2 * p + 1, nlast) * frb);
-            if (GAMMA) other(BUF, p);
         };
-        auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
+        // exp pass of a pair's two frames; the callbacks place memory requests between its pieces
+        auto prep = [&](auto BUF, auto&& duringF, auto&& middle, auto&& duringP) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            c3_exp_frame(EF[B_], g.xC, g.olane, sF[B_], sFb[B_]);
-            halfway();
-            c3_exp_frame(EP[B_], g.xR, g.olane, sP[B_], sPb[B_]);
+            sF[B_] = c3_exp_frame(EF[B_], g.mvC, false, duringF);
+            middle();
+            sP[B_] = c3_exp_frame(EP[B_], g.mvR, g.xR, duringP);
             if (GAMMA) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) { c2_pin(bF4[B_][c]); c2_pin(bP4[B_][c]); }
-                c2_pin(bFo[B_]); c2_pin(bPo[B_]); c2_pin(sbF[B_]); c2_pin(sbP[B_]); c2_pin(sbPl[B_]);
+                c2_pin(bFm[B_]); c2_pin(bPm[B_]); c2_pin(eF4[B_]); c2_pin(eP4[B_]); c2_pin(eFm[B_]); c2_pin(ePm[B_]);
             }
         };
         auto meet = [&]() __attribute__((always_inline)) {
-            if (dead) ctl_s[8] = 1;
-            cluster_sync(a, cg, ptag, &ctl_s[8]);
+            if (dead) ctl_s[1] = 1;
+            cluster_sync(a, cg, ptag, &ctl_s[1]);
             ptag += 1;
-            D2 = c3_meeting(ah + (size_t)mid * C, bh + (size_t)mid * C, Sa + (size_t)mid * kC3K,
-                            Sb + (size_t)mid * kC3K, redb);
+            const double D2 = c3_meeting((const uint2*)ah + (size_t)mid * C, (const uint2*)bh + (size_t)mid * C, redb);
+            D = c3_split(D2);
             if (k == 0 && tid == 0) {
                 a.dist[b] = bad ? __builtin_nanf("") : (float)(D2 * 0.6931471805599453);
                 if (a.item_status) a.item_status[b] = bad ? kItemBadLength : kItemOk;
@@ -438,7 +570,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
 
         issue(std::integral_constant<int, 0>(), 0);
         issue(std::integral_constant<int, 1>(), 1);
-        prep(std::integral_constant<int, 0>(), [] {});
+        prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
@@ -457,65 +589,65 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             if (tF == mid && !met) { meet(); after_meeting(); }
             C3_MARK(a, p, 0);
             const int S = ctl_s[0];
-            float own;
-            int ek;
+            float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
+            int ek;           // their exponent
             {
-                float aq[5];
+                float aq[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) aq[j] = full_s[64 * wave + 16 * j + g.rg];
-                aq[4] = g.xC ? full_s[256] : 0.f;
+                for (int j = 0; j < 4; ++j) aq[j] = full_s[32 * wave + 8 * j + g.rg];
+                const float am = full_s[g.midx];
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int j = 0; j < 5; ++j)
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[c] = fmaf(aq[j], EF[B_].e[j][c], acc[c]);
-                // the four rows of a group of sixteen lanes
+                // the eight rows of an instruction: the two of a group of sixteen lanes, then the wave's four groups
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    acc[c] += dpp_f<0x114>(0.f, acc[c]);
                     acc[c] += dpp_f<0x118>(0.f, acc[c]);
+                    acc[c] = c3_rows_sum(acc[c]);
                 }
-                if ((lane & 15) >= 12) {
+                if (lane >= 8 && lane < 16) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) red_s[(4 * g.ci + c) * kC3RS + 4 * wave + (lane >> 4)] = acc[c];
+                    for (int c = 0; c < 4; ++c) red_s[(4 * g.ci + c) * kC3RS + wave] = acc[c];
                 }
-                if (lane == 0) ctl_s[4 + wave] = sF[B_];
+                if (lane == 0) ctl_s[8 + wave] = sF[B_];
+                // odd elements: the empty-label arc of an own state (lanes 0..4) and the start state's label arc
+                // into it (lanes 8..11, moved to lanes 0..3)
+                float mt = am * EF[B_].m;
+                mt += dpp_f<0x108>(0.f, mt);
                 if (GAMMA && tF >= mid) {
-                    const int sbk = __builtin_amdgcn_readlane(sbF[B_], k);
-                    const float fcs = a.scale * c3_mscale(S + sF[B_] + sbk, D2, xwide);
                     const unsigned gso = (unsigned)tF * frb;
+                    const float fcs = a.scale * c3_mscale(S + sF[B_] + eF4[B_], D, xwide);
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) {
+                    for (int j = 0; j < 4; ++j) {
                         float x[4];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) x[c] = aq[j] * EF[B_].e[j][c] * (bF4[B_][c] * fcs);
-                        c3_put4<ACC>(x, grs, j < 4 ? g.voffC : g.voffCx, j < 4 ? gso + g.rowC0 + (unsigned)(16 * j) * pitch : gso);
+                        c3_put4<ACC>(x, grs, g.voffC, gso + g.rowC0 + (unsigned)(8 * j) * pitch);
                     }
-                    if (wave == 0) {
-                        const float fb = a.scale * bFo[B_] * c3_mscale(S + sFb[B_] + sbk, D2, xwide);
-                        c2_put<ACC>(full_s[g.oidx] * EF[B_].b * fb, grs, g.voffB, gso);
-                    }
+                    const float fm = a.scale * bFm[B_] * c3_mscale(S + sF[B_] + eFm[B_], D, xwide);
+                    c2_put<ACC>(am * EF[B_].m * fm, grs, g.voffMc, gso);
                 }
                 C3_MARK(a, p, 1);
                 c2_barrier();
                 C3_MARK(a, p, 2);
-                // own states: every wave by itself (the same values from the same inputs)
-                const int4 sh = *(const int4*)&ctl_s[4];
-                const int smax = max(max(max(sh.x, sh.y), max(sh.z, sh.w)), sFb[B_]);
-                const float4* rp = (const float4*)&red_s[(lane & 15) * kC3RS];
-                const float4 p0 = rp[0], p1 = rp[1], p2 = rp[2], p3 = rp[3];
-                float v = c2_scale((p0.x + p0.y) + (p0.z + p0.w), sh.x - smax) + c2_scale((p1.x + p1.y) + (p1.z + p1.w), sh.y - smax)
-                          + c2_scale((p2.x + p2.y) + (p2.z + p2.w), sh.z - smax) + c2_scale((p3.x + p3.y) + (p3.z + p3.w), sh.w - smax);
-                v = lane < 16 ? v : 0.f;
-                v = fmaf(full_s[g.oidx], c2_scale(EF[B_].b, sFb[B_] - smax), v);
-                const int te = v > 0.f ? float_exponent(v) : kShiftNone;
-                const int ms = wave_max_dpp(te);
-                own = v > 0.f ? c2_scale(v, -ms) : 0.f;
+                // own states: lane j < 4 adds up the eight waves' sums of column 4 wave + j
+                const int4 sh0 = *(const int4*)&ctl_s[8], sh1 = *(const int4*)&ctl_s[12];
+                const int smax = max(max(max(sh0.x, sh0.y), max(sh0.z, sh0.w)), max(max(sh1.x, sh1.y), max(sh1.z, sh1.w)));
+                const float4* rp = (const float4*)&red_s[(4 * wave + (lane & 3)) * kC3RS];
+                const float4 p0 = rp[0], p1 = rp[1];
+                float v = ((__builtin_ldexpf(p0.x, sh0.x - smax) + __builtin_ldexpf(p0.y, sh0.y - smax))
+                           + (__builtin_ldexpf(p0.z, sh0.z - smax) + __builtin_ldexpf(p0.w, sh0.w - smax)))
+                          + ((__builtin_ldexpf(p1.x, sh1.x - smax) + __builtin_ldexpf(p1.y, sh1.y - smax))
+                             + (__builtin_ldexpf(p1.z, sh1.z - smax) + __builtin_ldexpf(p1.w, sh1.w - smax)));
+                v = lane < 4 ? v : 0.f;
+                v += __builtin_ldexpf(mt, sF[B_] - smax);
+                v = g.mvR ? v : 0.f;
+                const int ms = c3_wave_max(v > 0.f ? float_exponent(v) : kShiftNone);
+                own = __builtin_ldexpf(v, -ms);
                 ek = ms == kShiftNone ? S : S + smax + ms;
-                if (tF + 1 <= mid && wave == 0) {
-                    if (g.olane) ah[(size_t)(tF + 1) * C + g.ostate] = own;
-                    if (lane == 0) Sa[(size_t)(tF + 1) * kC3K + k] = ek;
-                }
+                if (tF + 1 <= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)(tF + 1) * kC3SP);
             }
             if (tP >= n) return false;
             C3_MARK(a, p, 3);
@@ -524,75 +656,99 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             {
                 const unsigned tag = gstep + 1;
                 const unsigned slot_off = (gstep & 1) * (unsigned)(kC3K * kC3XS * sizeof(u64));
-                u64* xs = xbase + (size_t)(gstep & 1) * kC3K * kC3XS;
-                float o[5];
+                float o[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    o[j] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(own), 4 * wave + j));
-                o[4] = g.xR ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(own), 16)) : 0.f;
+                    o[j] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(own), j));
+                const float o0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(own), 4));
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int j = 0; j < 5; ++j)
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[c] = fmaf(o[j], EP[B_].e[j][c], acc[c]);
+                if (g.xR) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[c] = fmaf(o0, EP[B_].x[c], acc[c]);
+                }
                 float4 av;
                 av.x = acc[0]; av.y = acc[1]; av.z = acc[2]; av.w = acc[3];
                 *(float4*)&pacc_s[wave * 256 + 4 * lane] = av;
-                if (lane == 0) ctl_s[12 + wave] = sP[B_];
-                if (wave == 0 && lane < 32) bl_s[lane] = own * EP[B_].b;
+                const int tw = ek + sP[B_];                 // exponent of this wave's sums
+                if (lane == 0) ctl_s[16 + wave] = tw;
+                if (lane < 8) bl_s[8 * wave + lane] = own * EP[B_].m;      // empty-label arcs of the own states
                 C3_MARK(a, p, 4);
                 c2_barrier();
                 C3_MARK(a, p, 5);
-                const int4 sp = *(const int4*)&ctl_s[12];
-                const int spmax = max(max(max(sp.x, sp.y), max(sp.z, sp.w)), sPb[B_]);
-                float val = c2_scale(pacc_s[tid], sp.x - spmax) + c2_scale(pacc_s[256 + tid], sp.y - spmax)
-                            + c2_scale(pacc_s[512 + tid], sp.z - spmax) + c2_scale(pacc_s[768 + tid], sp.w - spmax);
-                if ((tid >> 4) == k) val += c2_scale(bl_s[tid & 15], sPb[B_] - spmax);
-                const int rel = (spmax == kShiftNone ? ek : ek + spmax) - S;
                 const bool exch = !(GAMMA && tP == L - 1);
-                if (exch) {
-                    xpublish(xs + (size_t)k * kC3XS + tid, c2_pack(val, tag, rel));
+                if (exch && tid < 256) {
+                    const int4 tw0 = *(const int4*)&ctl_s[16], tw1 = *(const int4*)&ctl_s[20];
+                    const int tmax = max(max(max(tw0.x, tw0.y), max(tw0.z, tw0.w)), max(max(tw1.x, tw1.y), max(tw1.z, tw1.w)));
+                    float val = ((__builtin_ldexpf(pacc_s[tid], tw0.x - tmax) + __builtin_ldexpf(pacc_s[256 + tid], tw0.y - tmax))
+                                 + (__builtin_ldexpf(pacc_s[512 + tid], tw0.z - tmax) + __builtin_ldexpf(pacc_s[768 + tid], tw0.w - tmax)))
+                                + ((__builtin_ldexpf(pacc_s[1024 + tid], tw1.x - tmax) + __builtin_ldexpf(pacc_s[1280 + tid], tw1.y - tmax))
+                                   + (__builtin_ldexpf(pacc_s[1536 + tid], tw1.z - tmax) + __builtin_ldexpf(pacc_s[1792 + tid], tw1.w - tmax)));
+                    if (pubown) val += __builtin_ldexpf(bl_s[pubbl], ctl_s[16 + pubw] - tmax);
+                    const int rel = tmax - S;
+                    c3_xstore(c2_pack(val, tag, rel), xrs, voffpub, slot_off);
                     // the start state moves on by its empty-label arc only: workgroup 0 has it, the others add zero
                     if (tid == 0)
-                        xpublish(xs + (size_t)k * kC3XS + 256, c2_pack(k == 0 ? c2_scale(bl_s[16], sPb[B_] - spmax) : 0.f, tag, rel));
+                        c3_xstore(c2_pack(k == 0 ? __builtin_ldexpf(bl_s[4], tw0.x - tmax) : 0.f, tag, rel), xrs,
+                                  (unsigned)(k * kC3XS + 256) * 8u, slot_off);
                 }
                 if (GAMMA && tP >= mid) {
-                    const int sbk = __builtin_amdgcn_readlane(sbP[B_], k);
-                    const float fys = a.scale * c3_mscale(ek + sP[B_] + sbPl[B_], D2, xwide);
                     const unsigned gso = (unsigned)tP * frb;
+                    const float fys = a.scale * c3_mscale(tw + eP4[B_], D, xwide);
+                    float fy[4];
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) {
+                    for (int c = 0; c < 4; ++c) fy[c] = bP4[B_][c] * fys;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
                         float x[4];
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) x[c] = o[j] * EP[B_].e[j][c] * (bP4[B_][c] * fys);
-                        c3_put4<ACC>(x, grs, j < 4 ? g.voffR : g.voffRx, j < 4 ? gso + g.rowR0 + (unsigned)j * pitch : gso);
+                        for (int c = 0; c < 4; ++c) x[c] = o[j] * EP[B_].e[j][c] * fy[c];
+                        c3_put4<ACC>(x, grs, g.voffR, gso + g.rowR0 + (unsigned)j * pitch);
                     }
-                    if (wave == 0) {
-                        const float fb = a.scale * bPo[B_] * c3_mscale(ek + sPb[B_] + sbk, D2, xwide);
-                        c2_put<ACC>(own * EP[B_].b * fb, grs, g.voffB, gso);
+                    if (g.xR) {
+                        float x[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) x[c] = o0 * EP[B_].x[c] * fy[c];
+                        c3_put4<ACC>(x, grs, g.voffR, gso);
                     }
+                    const float fm = a.scale * bPm[B_] * c3_mscale(tw + ePm[B_], D, xwide);
+                    c2_put<ACC>(own * EP[B_].m * fm, grs, g.voffMr, gso);
                 }
-                // exp pass of the next pair; in its middle the first look at the exchange and, behind it (a
-                // wave's loads return in order), the requests for the pair after the next, into the registers
-                // this pair has finished with
+                // exp pass of the next pair, with the requests for the pair after the next (into the registers
+                // this pair has finished with) between its pieces; the look at the exchange comes before the
+                // frames' requests, because a wave's loads return in order
                 C3_MARK(a, p, 6);
                 C3Look lk;
-                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) {
-                    if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
-                    issue(std::integral_constant<int, B_>(), p + 2);
-                });
+                const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb, foP2 = (unsigned)min(2 * p + 5, nlast) * frb;
+                prep(std::integral_constant<int, B_ ^ 1>(),
+                     [&](int j) __attribute__((always_inline)) {
+                         if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
+                     },
+                     [&]() __attribute__((always_inline)) {
+                         C3_MARK(a, p, 11);
+                         if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
+                         C3_MARK(a, p, 12);
+                     },
+                     [&](int j) __attribute__((always_inline)) {
+                         c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
+                         if (j == 3) c3_load_cols_slot(EF[B_], 4, wrs, g, foF2);
+                     });
                 C3_MARK(a, p, 7);
                 if (exch) {
                     int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
-                              [&]() __attribute__((always_inline)) { C3_MARK(a, p, 8); }, &relooks);
+                              [&]() __attribute__((always_inline)) {
+                                  C3_MARK(a, p, 8);
+#pragma unroll
+                                  for (int j = 0; j < 5; ++j) c3_load_rows_slot(EP[B_], j, wrs, g, foP2);
+                              }, &relooks);
                     C3_MARK(a, p, 9);
                     C3_NOTE(a, p, 10, relooks);
                     gstep += 1;
-                    if (tP + 1 <= mid && wave == 1) {
-                        if (g.olane) ah[(size_t)(tP + 1) * C + g.ostate] = full_s[g.oidx];
-                        if (lane == 0) Sa[(size_t)(tP + 1) * kC3K + k] = ctl_s[0];
-                    }
+                    if (tP + 1 <= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)(tP + 1) * kC3SP);
                 }
             }
             ++p;
@@ -604,12 +760,12 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         }
         __syncthreads();
         if (!met) meet();
-        if (xwide > kC2RangeBits) ctl_s[11] = 1;
-        if (dead) ctl_s[8] = 1;
+        if (xwide > kC2RangeBits) ctl_s[2] = 1;
+        if (dead) ctl_s[1] = 1;
         __syncthreads();
         if (tid == 0) {
-            if (ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
-            c3_finish_item(a, b, ctl_s[8] != 0, bad);
+            if (ctl_s[2] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
+            c3_finish_item(a, b, ctl_s[1] != 0, bad);
         }
         __syncthreads();
     }
@@ -623,18 +779,25 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
     constexpr int C = kC3C;
     constexpr unsigned pitch = C * 4u, frb = (unsigned)C * C * 4u;
     float* full_s = smem + kC3Full;
-    float* rowp_s = smem + kC3Red;            // [272] P-step: row sums (label state y at y - 1, the start state at 256)
+    float* rowp_s = smem + kC3Red;            // [272] P-step: row sums (label state y at y - 1)
     float* bl_s = smem + kC3Bl;
     float* own_s = smem + kC3OwnS;
-    float* row_s = smem + kC3Row;             // [32] F-step: row sums
-    int* rsh_s = (int*)(smem + kC3Row + 32);  // [32] their shifts
     int* ctl_s = (int*)(smem + kC3Ctl);
+    float* z_s = smem + kC3Ctl + 32;          // [8] the waves' parts of the start state's sum
     float* redb = smem + kC3RedB;
     const int tid = threadIdx.x;
     const C3Geom g = c3_geom(cg.k);
     const int lane = g.lane, wave = g.wave, k = g.k;
-    const unsigned voffq = (unsigned)((8 * (tid & 1)) * kC3XS + 2 * (tid >> 1)) * 8u;
-    const unsigned voffz = (unsigned)((lane & 15) * kC3XS + 256) * 8u;
+    const unsigned voffq = (unsigned)((2 * (tid & 3)) * kC3XS + 2 * (tid >> 2)) * 8u;
+    const unsigned voffz = (unsigned)((lane & 7) * kC3XS + 256) * 8u;
+    const unsigned voffpub = tid < 256 ? (unsigned)(k * kC3XS + tid) * 8u : kC2Off;
+    const int pcol = tid & 255;
+    const bool pubown = (pcol >> 5) == k;
+    const int pubw = (pcol & 31) >> 2;
+    const int pubbl = 8 * pubw + (pcol & 3);
+    const int prow = pcol >> 5;               // the wave that has summed the row of label state pcol + 1
+    // odd elements of the column pattern lead to the own states (lanes 0..3, 8..11) or the start state (lane 4)
+    const int oidx = (lane & 7) < 4 ? 4 * wave + (lane & 3) : 32;
 
     for (int b = cg.cg; b < a.B; b += 8 * a.ncl) {
         int L = a.len[b];
@@ -645,34 +808,31 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         const int ph1 = L - mid;                      // step at which the state index reaches mid
         const int nlast = max(n - 1, 0);
         const size_t fr = (size_t)C * C;
-        const float* ah = a.ahat + (size_t)b * (a.T + 1) * C;
-        float* bh = a.bhat + (size_t)b * (a.T + 1) * C;
-        const int* Sa = a.Sa + (size_t)b * (a.T + 1) * kC3K;
-        int* Sb = a.Sb + (size_t)b * (a.T + 1) * kC3K;
-        u64* xbase = a.xb + (size_t)cg.cg * 2 * kC3K * kC3XS;
+        const float* ah = a.ahat + (size_t)b * (a.T + 1) * C * 2;
+        float* bh = a.bhat + (size_t)b * (a.T + 1) * C * 2;
         const buf_t wrs = make_buf(a.w + (size_t)b * a.T * fr, (unsigned)a.T * frb);
         const buf_t grs = make_buf(GAMMA ? a.dw + (size_t)b * a.T * fr : a.w, GAMMA ? (unsigned)a.T * frb : 0u);
-        const buf_t ars = make_buf(ah, (unsigned)(a.T + 1) * pitch);
-        const buf_t sars = make_buf(Sa, (unsigned)(a.T + 1) * (unsigned)(kC3K * sizeof(int)));
-        const buf_t xrs = make_buf(xbase, (unsigned)(2 * kC3K * kC3XS * sizeof(u64)));
+        const buf_t srs = make_buf(bh, (unsigned)(a.T + 1) * kC3SP);
+        const buf_t ors = make_buf(ah, (unsigned)(a.T + 1) * kC3SP);
+        const buf_t xrs = make_buf(a.xb + (size_t)cg.cg * 2 * kC3K * kC3XS, (unsigned)(2 * kC3K * kC3XS * sizeof(u64)));
 
         // b_L = 1 for every state, exponent 0
-        for (int q = tid; q < 272; q += kC3Threads) full_s[q] = q < C ? 1.f : 0.f;
-        if (tid < 32) { ctl_s[tid] = 0; bl_s[tid] = 0.f; own_s[tid] = 0.f; row_s[tid] = 0.f; rsh_s[tid] = kShiftNone; }
-        if (wave == 0 && g.olane) bh[(size_t)L * C + g.ostate] = 1.f;
-        if (tid == 0) Sb[(size_t)L * kC3K + k] = 0;
+        if (tid < 272) full_s[tid] = tid < C ? 1.f : 0.f;
+        if (tid < 64) { ctl_s[tid] = 0; bl_s[tid] = 0.f; }
+        if (tid < 40) own_s[tid] = 0.f;
+        c3_store_pair(1.f, 0, srs, g.voffS, (unsigned)L * kC3SP);
         __syncthreads();
 
         C3Frame EF[2], EP[2];
-        int sF[2] = {0, 0}, sP[2] = {0, 0}, sFb[2] = {0, 0}, sPb[2] = {0, 0};
-        // the other side's vectors for the marginals
-        float aFo[2] = {0.f, 0.f}, aPo[2] = {0.f, 0.f}, aP[2][5];
-        int saF[2] = {0, 0}, saP[2] = {0, 0};
+        int sF[2] = {0, 0}, sP[2] = {0, 0};
+        // the other side's vectors for the marginals: values and exponents
+        float aFm[2] = {0.f, 0.f}, aPm[2] = {0.f, 0.f}, aP[2][4];
+        int eFm[2] = {0, 0}, ePm[2] = {0, 0}, eP[2][4];
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
-            for (int j = 0; j < 5; ++j) aP[x][j] = 0.f;
-        double D2 = 0.0;
+            for (int j = 0; j < 4; ++j) { aP[x][j] = 0.f; eP[x][j] = 0; }
+        C3D D{0, 0.f};
         float xwide = -3.0e38f;
         int dead = 0;
         bool met = false;
@@ -680,58 +840,65 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         // step index i -> frame L - 1 - i; pair p = steps 2p (F) and 2p + 1 (P)
         auto frameF = [&](int p) { return max(L - 1 - min(2 * p, nlast), 0); };
         auto frameP = [&](int p) { return max(L - 1 - min(2 * p + 1, nlast), 0); };
-        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
+        auto other_piece = [&](auto BUF, int p, int piece) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            const unsigned tF = (unsigned)frameF(p), tP = (unsigned)frameP(p);
-            aFo[B_] = buf_load(ars, (unsigned)g.ostate * 4u, tF * pitch);
-            saF[B_] = __builtin_bit_cast(int, buf_load(sars, (unsigned)(lane & 15) * 4u, tF * (unsigned)(kC3K * sizeof(int))));
+            const unsigned tF = (unsigned)frameF(p) * kC3SP, tP = (unsigned)frameP(p) * kC3SP;
+            const unsigned vr = (unsigned)(1 + g.rg) * 8u, r0 = tP + (unsigned)(32 * wave) * 8u;
+            if (piece == 0) {
+                c3_load_pair(ors, g.voffS, tF, aFm[B_], eFm[B_]);
+                // odd elements of the P frame: the own states' empty-label arcs (lanes 0..3, the start state's on
+                // lane 4) and the start state's label arcs (lanes 8..11) leave from these states
+                c3_load_pair(ors, lane >= 8 && lane < 12 ? 0u : g.voffS, tP, aPm[B_], ePm[B_]);
+            } else if (piece == 1) {
+                c3_load_pair(ors, vr, r0, aP[B_][0], eP[B_][0]);
+                c3_load_pair(ors, vr, r0 + 64u, aP[B_][1], eP[B_][1]);
+            } else if (piece == 2) {
+                c3_load_pair(ors, vr, r0 + 128u, aP[B_][2], eP[B_][2]);
+                c3_load_pair(ors, vr, r0 + 192u, aP[B_][3], eP[B_][3]);
+            }
+        };
+        auto other = [&](auto BUF, int p) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                aP[B_][j] = buf_load(ars, (unsigned)(1 + 64 * wave + 16 * j + g.rg) * 4u, tP * pitch);
-            aP[B_][4] = buf_load(ars, g.xC ? 0u : kC2Off, tP * pitch);
-            aPo[B_] = buf_load(ars, (unsigned)g.ostate * 4u, tP * pitch);
-            saP[B_] = __builtin_bit_cast(int, buf_load(sars, (unsigned)(lane & 15) * 4u, tP * (unsigned)(kC3K * sizeof(int))));
+            for (int piece = 0; piece < 3; ++piece) other_piece(BUF, p, piece);
         };
         auto settle = [&]() __attribute__((always_inline)) {
             int t = 0;
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
 #pragma unroll
-                for (int j = 0; j < 5; ++j) t |= c2_touch(aP[x][j]);
-                t |= c2_touch(aFo[x]) | c2_touch(aPo[x]) | (saF[x] == 0x7fffffff) | (saP[x] == 0x7fffffff);
+                for (int j = 0; j < 4; ++j) t |= c2_touch(aP[x][j]) | (eP[x][j] == 0x7fffffff);
+                t |= c2_touch(aFm[x]) | c2_touch(aPm[x]) | (eFm[x] == 0x7fffffff) | (ePm[x] == 0x7fffffff);
             }
-            if (t) ctl_s[9] = 1;          // (never; nobody reads it)
+            if (t) ctl_s[3] = 1;          // (never; nobody reads it)
         };
         auto issue = [&](auto BUF, int p) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
             c3_load_rows(EF[B_], wrs, g, (unsigned)frameF(p) * frb);
             c3_load_cols(EP[B_], wrs, g, (unsigned)frameP(p) * frb);
-            if (GAMMA) other(BUF, p);
         };
-        auto prep = [&](auto BUF, auto&& halfway) __attribute__((always_inline)) {
+        auto prep = [&](auto BUF, auto&& duringF, auto&& middle, auto&& duringP) __attribute__((always_inline)) {
             constexpr int B_ = decltype(BUF)::value;
-            c3_exp_frame(EF[B_], g.xR, g.olane, sF[B_], sFb[B_]);
-            halfway();
-            c3_exp_frame(EP[B_], g.xC, g.olane, sP[B_], sPb[B_]);
+            sF[B_] = c3_exp_frame(EF[B_], g.mvR, g.xR, duringF);
+            middle();
+            sP[B_] = c3_exp_frame(EP[B_], g.mvC, false, duringP);
             if (GAMMA) {
 #pragma unroll
-                for (int j = 0; j < 5; ++j) c2_pin(aP[B_][j]);
-                c2_pin(aFo[B_]); c2_pin(aPo[B_]); c2_pin(saF[B_]); c2_pin(saP[B_]);
+                for (int j = 0; j < 4; ++j) { c2_pin(aP[B_][j]); c2_pin(eP[B_][j]); }
+                c2_pin(aFm[B_]); c2_pin(aPm[B_]); c2_pin(eFm[B_]); c2_pin(ePm[B_]);
             }
         };
         auto meet = [&]() __attribute__((always_inline)) {
-            if (dead) ctl_s[8] = 1;
-            cluster_sync(a, cg, ptag, &ctl_s[8]);
+            if (dead) ctl_s[1] = 1;
+            cluster_sync(a, cg, ptag, &ctl_s[1]);
             ptag += 1;
-            D2 = c3_meeting(ah + (size_t)mid * C, bh + (size_t)mid * C, Sa + (size_t)mid * kC3K,
-                            Sb + (size_t)mid * kC3K, redb);
+            D = c3_split(c3_meeting((const uint2*)ah + (size_t)mid * C, (const uint2*)bh + (size_t)mid * C, redb));
             met = true;
             __syncthreads();
         };
 
         issue(std::integral_constant<int, 0>(), 0);
         issue(std::integral_constant<int, 1>(), 1);
-        prep(std::integral_constant<int, 0>(), [] {});
+        prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
@@ -750,63 +917,67 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
             if (iF == ph1 && !met) { meet(); after_meeting(); }
             C3_MARK(a, p, 0);
             const int S = ctl_s[0];
-            float own;
-            int ek;
+            float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
+            int ek;           // their exponent
             {
                 const int tF = L - 1 - iF;
                 const float4 bq4 = *(const float4*)&full_s[4 * lane];
                 const float bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
+                const float bm = full_s[g.midx];
                 float rs[5];
 #pragma unroll
-                for (int j = 0; j < 5; ++j) {
+                for (int j = 0; j < 4; ++j) {
                     float t = EF[B_].e[j][0] * bq[0];
 #pragma unroll
                     for (int c = 1; c < 4; ++c) t = fmaf(EF[B_].e[j][c], bq[c], t);
                     rs[j] = t;
                 }
-                // (five independent chains: their cross-lane steps overlap)
+                rs[4] = 0.f;
+                if (g.xR) {
+                    float t = EF[B_].x[0] * bq[0];
 #pragma unroll
-                for (int j = 0; j < 5; ++j) rs[j] = wave_sum_dpp(rs[j]);
-                if (lane == 0) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) { row_s[4 * wave + j] = rs[j]; rsh_s[4 * wave + j] = sF[B_]; }
-                    if (g.xR) { row_s[16] = rs[4]; rsh_s[16] = sF[B_]; }
+                    for (int c = 1; c < 4; ++c) t = fmaf(EF[B_].x[c], bq[c], t);
+                    rs[4] = t;
                 }
-                if (GAMMA && iF >= ph1) {
-                    const int sak = __builtin_amdgcn_readlane(saF[B_], k);
-                    const float frs = a.scale * c3_mscale(sak + S + sF[B_], D2, xwide);
-                    const unsigned gso = (unsigned)tF * frb;
+                // (independent chains: their cross-lane steps overlap)
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) {
-                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFo[B_]), j < 4 ? 4 * wave + j : 16)) * frs;
+                for (int j = 0; j < 4; ++j) rs[j] = wave_sum_dpp(rs[j]);
+                if (g.xR) rs[4] = wave_sum_dpp(rs[4]);
+                if (GAMMA && iF >= ph1) {
+                    const unsigned gso = (unsigned)tF * frb;
+                    const float frs = a.scale * c3_mscale(__builtin_amdgcn_readlane(eFm[B_], 0) + S + sF[B_], D, xwide);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), j)) * frs;
                         float x[4];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) x[c] = EF[B_].e[j][c] * bq[c] * fr_;
-                        c3_put4<ACC>(x, grs, j < 4 ? g.voffR : g.voffRx, j < 4 ? gso + g.rowR0 + (unsigned)j * pitch : gso);
+                        c3_put4<ACC>(x, grs, g.voffR, gso + g.rowR0 + (unsigned)j * pitch);
                     }
-                    if (wave == 0) {
-                        const float fb = a.scale * aFo[B_] * c3_mscale(sak + S + sFb[B_], D2, xwide);
-                        c2_put<ACC>(full_s[g.oidx] * EF[B_].b * fb, grs, g.voffB, gso);
+                    if (g.xR) {
+                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), 4)) * frs;
+                        float x[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) x[c] = EF[B_].x[c] * bq[c] * fr_;
+                        c3_put4<ACC>(x, grs, g.voffR, gso);
                     }
+                    const float fm = a.scale * aFm[B_] * c3_mscale(eFm[B_] + S + sF[B_], D, xwide);
+                    c2_put<ACC>(bm * EF[B_].m * fm, grs, g.voffMr, gso);
                 }
+                // own states: row sum plus the empty-label arc, lane j <-> own state j (lane 4: the start state)
+                float v = lane == 0 ? rs[0] : lane == 1 ? rs[1] : lane == 2 ? rs[2] : lane == 3 ? rs[3] : rs[4];
+                v = fmaf(bm, EF[B_].m, v);
+                v = g.mvR ? v : 0.f;
+                const int ms = c3_wave_max(v > 0.f ? float_exponent(v) : kShiftNone);
+                own = __builtin_ldexpf(v, -ms);
+                ek = ms == kShiftNone ? S : S + sF[B_] + ms;
+                if (lane < 4) own_s[4 * wave + lane] = own;
+                if (lane == 4 && g.xR) own_s[32] = own;
+                if (lane == 0) ctl_s[8 + wave] = ek;
+                if (tF >= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)tF * kC3SP);
                 C3_MARK(a, p, 1);
                 c2_barrier();
                 C3_MARK(a, p, 2);
-                // own states: every wave by itself (the same values from the same inputs, written to the same cells)
-                const bool ok = g.olane;
-                const float rv = ok ? row_s[min(lane, 31)] : 0.f;
-                const int rsh = ok ? rsh_s[min(lane, 31)] : kShiftNone;
-                const int m = max(rsh, sFb[B_]);
-                const float v = fmaf(full_s[g.oidx], c2_scale(EF[B_].b, sFb[B_] - m), c2_scale(rv, rsh - m));
-                const int te = v > 0.f ? m + float_exponent(v) : kShiftNone;
-                const int ms = wave_max_dpp(te);
-                own = v > 0.f ? c2_scale(v, m - ms) : 0.f;
-                ek = ms == kShiftNone ? S : S + ms;
-                if (lane < 32) own_s[lane] = own;
-                if (wave == 0 && tF >= mid) {
-                    if (g.olane) bh[(size_t)tF * C + g.ostate] = own;
-                    if (lane == 0) Sb[(size_t)tF * kC3K + k] = ek;
-                }
             }
             if (iP >= n) return false;
             C3_MARK(a, p, 3);
@@ -816,83 +987,110 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 const int tP = L - 1 - iP;
                 const unsigned tag = gstep + 1;
                 const unsigned slot_off = (gstep & 1) * (unsigned)(kC3K * kC3XS * sizeof(u64));
-                u64* xs = xbase + (size_t)(gstep & 1) * kC3K * kC3XS;
+                // the lane's four columns are the own states of wave ci: bring them to the largest of the waves' exponents
+                const int4 ek0 = *(const int4*)&ctl_s[8], ek1 = *(const int4*)&ctl_s[12];
+                const int ekmax = max(max(max(ek0.x, ek0.y), max(ek0.z, ek0.w)), max(max(ek1.x, ek1.y), max(ek1.z, ek1.w)));
+                const int ekc = ctl_s[8 + g.ci];
                 const float4 ov4 = *(const float4*)&own_s[4 * g.ci];
-                const float ov[4] = {ov4.x, ov4.y, ov4.z, ov4.w};
-                float t[5];
+                float ov[4] = {ov4.x, ov4.y, ov4.z, ov4.w};
 #pragma unroll
-                for (int j = 0; j < 5; ++j) {
+                for (int c = 0; c < 4; ++c) ov[c] = __builtin_ldexpf(ov[c], ekc - ekmax);
+                float t[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
                     float s = EP[B_].e[j][0] * ov[0];
 #pragma unroll
                     for (int c = 1; c < 4; ++c) s = fmaf(EP[B_].e[j][c], ov[c], s);
                     t[j] = s;
                 }
-                // the four lanes of a row
+                // the eight lanes of a row: the four of a quad, then the row's two quads (the total ends in the
+                // upper quad's lanes)
 #pragma unroll
-                for (int j = 0; j < 5; ++j) {
+                for (int j = 0; j < 4; ++j) {
                     t[j] += dpp_f<0xB1>(0.f, t[j]);
                     t[j] += dpp_f<0x4E>(0.f, t[j]);
+                    t[j] += dpp_f<0x114>(0.f, t[j]);
                 }
-                if (g.ci == 0) {
+                if (g.ci == 4) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) rowp_s[64 * wave + 16 * j + g.rg] = t[j];
-                    if (g.xC) rowp_s[256] = t[4];
+                    for (int j = 0; j < 4; ++j) rowp_s[32 * wave + 8 * j + g.rg] = t[j];
                 }
-                if (lane == 0) ctl_s[12 + wave] = sP[B_];
-                if (wave == 0 && lane < 32) bl_s[lane] = own * EP[B_].b;
+                // odd elements: the own states' empty-label arcs (lanes 0..4) and the start state's label arcs into the
+                // own states (lanes 8..11, added up over the four); their exponent is the wave's own
+                const float mo = own_s[oidx] * EP[B_].m;
+                float zt = mo;
+                zt += dpp_f<0xB1>(0.f, zt);
+                zt += dpp_f<0x4E>(0.f, zt);
+                const int tw = ekmax + sP[B_], tb = ek + sP[B_];
+                if (lane < 8) bl_s[8 * wave + lane] = mo;
+                if (lane == 8) z_s[wave] = zt;
+                if (lane == 0) { ctl_s[16 + wave] = tw; ctl_s[24 + wave] = tb; }
                 C3_MARK(a, p, 4);
                 c2_barrier();
                 C3_MARK(a, p, 5);
-                const int4 sp = *(const int4*)&ctl_s[12];
-                const int spmax = max(max(max(sp.x, sp.y), max(sp.z, sp.w)), sPb[B_]);
-                // thread <-> label state tid + 1, whose row this thread's own wave has summed
-                float val = c2_scale(rowp_s[tid], sP[B_] - spmax);
-                if ((tid >> 4) == k) val += c2_scale(bl_s[tid & 15], sPb[B_] - spmax);
-                const int rel = (spmax == kShiftNone ? ek : ek + spmax) - S;
                 const bool exch = !(GAMMA && iP == L - 1);
-                if (exch) {
-                    xpublish(xs + (size_t)k * kC3XS + tid, c2_pack(val, tag, rel));
+                if (exch && tid < 256) {
+                    const int4 tw0 = *(const int4*)&ctl_s[16], tw1 = *(const int4*)&ctl_s[20];
+                    const int4 tb0 = *(const int4*)&ctl_s[24], tb1 = *(const int4*)&ctl_s[28];
+                    const int tmax = max(max(max(max(tw0.x, tw0.y), max(tw0.z, tw0.w)), max(max(tw1.x, tw1.y), max(tw1.z, tw1.w))),
+                                         max(max(max(tb0.x, tb0.y), max(tb0.z, tb0.w)), max(max(tb1.x, tb1.y), max(tb1.z, tb1.w))));
+                    // thread <-> label state tid + 1
+                    float val = __builtin_ldexpf(rowp_s[tid], ctl_s[16 + prow] - tmax);
+                    if (pubown) val += __builtin_ldexpf(bl_s[pubbl], ctl_s[24 + pubw] - tmax);
+                    const int rel = tmax - S;
+                    c3_xstore(c2_pack(val, tag, rel), xrs, voffpub, slot_off);
                     if (tid == 0) {
-                        float v0 = c2_scale(rowp_s[256], sp.x - spmax);
-                        if (k == 0) v0 += c2_scale(bl_s[16], sPb[B_] - spmax);
-                        xpublish(xs + (size_t)k * kC3XS + 256, c2_pack(v0, tag, rel));
+                        float v0 = ((__builtin_ldexpf(z_s[0], tb0.x - tmax) + __builtin_ldexpf(z_s[1], tb0.y - tmax))
+                                    + (__builtin_ldexpf(z_s[2], tb0.z - tmax) + __builtin_ldexpf(z_s[3], tb0.w - tmax)))
+                                   + ((__builtin_ldexpf(z_s[4], tb1.x - tmax) + __builtin_ldexpf(z_s[5], tb1.y - tmax))
+                                      + (__builtin_ldexpf(z_s[6], tb1.z - tmax) + __builtin_ldexpf(z_s[7], tb1.w - tmax)));
+                        if (k == 0) v0 += __builtin_ldexpf(bl_s[4], tb0.x - tmax);
+                        c3_xstore(c2_pack(v0, tag, rel), xrs, (unsigned)(k * kC3XS + 256) * 8u, slot_off);
                     }
                 }
                 if (GAMMA && iP >= ph1) {
                     // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z, b_{t+1} = the own states of the F-step
                     const unsigned gso = (unsigned)tP * frb;
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) {
-                        const int saj = __builtin_amdgcn_readlane(saP[B_], j < 4 ? 4 * wave + j : 0);
-                        const float fq = a.scale * aP[B_][j] * c3_mscale(saj + ek + sP[B_], D2, xwide);
+                    for (int j = 0; j < 4; ++j) {
+                        const float fq = a.scale * aP[B_][j] * c3_mscale(eP[B_][j] + tw, D, xwide);
                         float x[4];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) x[c] = fq * EP[B_].e[j][c] * ov[c];
-                        c3_put4<ACC>(x, grs, j < 4 ? g.voffC : g.voffCx, j < 4 ? gso + g.rowC0 + (unsigned)(16 * j) * pitch : gso);
+                        c3_put4<ACC>(x, grs, g.voffC, gso + g.rowC0 + (unsigned)(8 * j) * pitch);
                     }
-                    if (wave == 0) {
-                        const float fb = a.scale * aPo[B_] * c3_mscale(__builtin_amdgcn_readlane(saP[B_], k) + ek + sPb[B_], D2, xwide);
-                        c2_put<ACC>(own * EP[B_].b * fb, grs, g.voffB, gso);
-                    }
+                    const float fm = a.scale * aPm[B_] * c3_mscale(ePm[B_] + tb, D, xwide);
+                    c2_put<ACC>(mo * fm, grs, g.voffMc, gso);
                 }
                 C3_MARK(a, p, 6);
                 C3Look lk;
-                prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) {
-                    if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
-                    issue(std::integral_constant<int, B_>(), p + 2);
-                });
+                const unsigned foF2 = (unsigned)frameF(p + 2) * frb, foP2 = (unsigned)frameP(p + 2) * frb;
+                prep(std::integral_constant<int, B_ ^ 1>(),
+                     [&](int j) __attribute__((always_inline)) {
+                         if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
+                     },
+                     [&]() __attribute__((always_inline)) {
+                         C3_MARK(a, p, 11);
+                         if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
+                         C3_MARK(a, p, 12);
+                     },
+                     [&](int j) __attribute__((always_inline)) {
+                         c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
+                         if (j == 3) c3_load_rows_slot(EF[B_], 4, wrs, g, foF2);
+                     });
                 C3_MARK(a, p, 7);
                 if (exch) {
                     int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
-                              [&]() __attribute__((always_inline)) { C3_MARK(a, p, 8); }, &relooks);
+                              [&]() __attribute__((always_inline)) {
+                                  C3_MARK(a, p, 8);
+#pragma unroll
+                                  for (int j = 0; j < 5; ++j) c3_load_cols_slot(EP[B_], j, wrs, g, foP2);
+                              }, &relooks);
                     C3_MARK(a, p, 9);
                     C3_NOTE(a, p, 10, relooks);
                     gstep += 1;
-                    if (tP >= mid && wave == 1) {
-                        if (g.olane) bh[(size_t)tP * C + g.ostate] = full_s[g.oidx];
-                        if (lane == 0) Sb[(size_t)tP * kC3K + k] = ctl_s[0];
-                    }
+                    if (tP >= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)tP * kC3SP);
                 }
             }
             ++p;
@@ -904,20 +1102,20 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         }
         __syncthreads();
         if (!met) meet();
-        if (xwide > kC2RangeBits) ctl_s[11] = 1;
-        if (dead) ctl_s[8] = 1;
+        if (xwide > kC2RangeBits) ctl_s[2] = 1;
+        if (dead) ctl_s[1] = 1;
         __syncthreads();
         if (tid == 0) {
-            if (ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
-            c3_finish_item(a, b, ctl_s[8] != 0, bad);
+            if (ctl_s[2] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
+            c3_finish_item(a, b, ctl_s[1] != 0, bad);
         }
         __syncthreads();
     }
 }
 
-// Two workgroups per compute unit: at most 256 registers per lane.
+// One workgroup per compute unit, two waves per SIMD: at most 256 registers per lane.
 template <bool GAMMA, bool ACC = false>
-__global__ __launch_bounds__(kC3Threads, 2) void cluster3_kernel(ClusterArgs a)
+__global__ __launch_bounds__(kC3Threads) void cluster3_kernel(ClusterArgs a)
 {
     __shared__ __align__(16) float smem[kC3Lds];
     ClusterGeom g;

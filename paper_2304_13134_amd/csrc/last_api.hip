@@ -151,9 +151,9 @@ NumWs carve_num(Carver& cv, const Shape& s, int Umax)
 // geometry of the clustered bigram path (see cluster_kernels.hpp)
 struct ClusterPlan {
     bool ok;
-    int gen;             // 2: one exchange per two frames, eight workgroups of eight waves per role
-                         // (cluster2_kernels.hpp); 3: sixteen workgroups of four waves per role, two per
-                         // compute unit (cluster3_kernels.hpp, 256 labels); 1: one exchange per frame
+    int gen;             // 2: one exchange per two frames (cluster2_kernels.hpp); 3: the same with the work cut
+                         // down to the wave and 16-byte accesses throughout (cluster3_kernels.hpp, 256 labels
+                         // only); 1: one exchange per frame
     int K, RPW, ncl, XS, XSB, grid;
 };
 
@@ -165,12 +165,12 @@ ClusterPlan cluster_plan(const Shape& s, int kind)
     // one item must fit a 32-bit buffer descriptor
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;
     const int want_gen = opt(LAST_OPT_CLUSTER_GENERATION);      // 0: the newest that takes the shape
-    if (want_gen == 3 && s.C == kC3C) {      // (opt-in while it is slower than the second generation)
+    if ((want_gen == 0 || want_gen == 3) && s.C == kC3C) {
         p.gen = 3;
         p.K = kC3K;
-        p.RPW = 16;
+        p.RPW = 32;
         const int want3 = (s.B + 7) / 8;
-        p.ncl = want3 < 2 ? want3 : 2;       // two workgroups per compute unit: 64 per XCD, 32 per item
+        p.ncl = want3 < 2 ? want3 : 2;       // one workgroup per compute unit: 32 per XCD, 16 per item
         p.XS = kC3XS;
         p.XSB = 0;
         p.grid = 8 * p.ncl * 2 * p.K;
@@ -210,8 +210,9 @@ ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
 {
     ClusterWs c;
     const size_t st = (size_t)s.B * (s.T + 1);
-    c.ahat = cv.take<float>(st * s.C);
-    c.bhat = cv.take<float>(st * s.C);
+    const size_t per_state = p.gen == 3 ? 2 : 1;          // third generation: (value, exponent) pairs
+    c.ahat = cv.take<float>(st * s.C * per_state);
+    c.bhat = cv.take<float>(st * s.C * per_state);
     const size_t nblk = p.gen == 3 ? kC3K : kClMaxK;      // one exponent per block of states
     c.Sa = cv.take<int>(st * nblk);
     c.Sb = cv.take<int>(st * nblk);
