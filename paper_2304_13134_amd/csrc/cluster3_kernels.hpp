@@ -174,7 +174,7 @@ __device__ __forceinline__ void c3_look(buf_t xrs, unsigned slot_off, unsigned v
 {
     lk.q[0] = c3_xload4(xrs, voffq, slot_off);
     lk.q[1] = c3_xload4(xrs, voffq, slot_off + (unsigned)(kC3XS * 8));
-    lk.z = c3_xload2(xrs, voffz, slot_off);
+    lk.z = c3_xload2(xrs, voffz, slot_off);           // (lanes 0..7 of wave 0; out of range elsewhere)
 }
 
 // sum over the wave's four rows of sixteen lanes, lane by lane (every lane gets the total of the four lanes
@@ -202,7 +202,8 @@ __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned
     const unsigned tagw = (tag & 0xFFFFu) << 16;
     int n = 0;
     for (;;) {
-        const unsigned diff = (lk.z.y ^ tagw) | (lk.q[0].y ^ tagw) | (lk.q[0].w ^ tagw) | (lk.q[1].y ^ tagw) | (lk.q[1].w ^ tagw);
+        const unsigned zdiff = tid < 8 ? lk.z.y ^ tagw : 0u;
+        const unsigned diff = zdiff | (lk.q[0].y ^ tagw) | (lk.q[0].w ^ tagw) | (lk.q[1].y ^ tagw) | (lk.q[1].w ^ tagw);
         if ((diff >> 16) == 0 || dead) break;
         if (++n > limit) { dead = 1; break; }
         __builtin_amdgcn_s_sleep(1);
@@ -234,8 +235,8 @@ __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned
         hm = hr;
     }
     const int href = hm;          // largest of the eight producers' exponents: the same in every lane
-    // the start state: lane l of every group of eight holds producer l's word; a scan leaves the sum in lane 7
-    float vz = __builtin_ldexpf(__uint_as_float(lk.z.x), (int)(short)(unsigned short)lk.z.y - href);
+    // the start state (wave 0): lane l < 8 holds producer l's word; a scan leaves the sum in lane 7
+    float vz = tid < 8 ? __builtin_ldexpf(__uint_as_float(lk.z.x), (int)(short)(unsigned short)lk.z.y - href) : 0.f;
     vz += dpp_f<0x111>(0.f, vz);
     vz += dpp_f<0x112>(0.f, vz);
     vz += dpp_f<0x114>(0.f, vz);
@@ -456,7 +457,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
     const int lane = g.lane, wave = g.wave, k = g.k;
     // gather: quad <-> two neighbouring states, its lanes <-> two producers each
     const unsigned voffq = (unsigned)((2 * (tid & 3)) * kC3XS + 2 * (tid >> 2)) * 8u;
-    const unsigned voffz = (unsigned)((lane & 7) * kC3XS + 256) * 8u;
+    const unsigned voffz = tid < 8 ? (unsigned)(tid * kC3XS + 256) * 8u : kC2Off;
     // publish: threads 0..255 <-> label states; the thread of an own state adds the state's empty-label term
     const unsigned voffpub = tid < 256 ? (unsigned)(k * kC3XS + tid) * 8u : kC2Off;
     const int pcol = tid & 255;
@@ -569,7 +570,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         };
 
         issue(std::integral_constant<int, 0>(), 0);
-        issue(std::integral_constant<int, 1>(), 1);
+        c3_load_cols(EF[1], wrs, g, (unsigned)min(2, nlast) * frb);       // (its P frame: requested in pair 0)
         prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
@@ -616,6 +617,11 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // into it (lanes 8..11, moved to lanes 0..3)
                 float mt = am * EF[B_].m;
                 mt += dpp_f<0x108>(0.f, mt);
+                // the P frame of the next pair is requested here and in the P-step, where the address path has
+                // little else to do (into the registers the pair before this one has finished with)
+                const unsigned foP1 = (unsigned)min(2 * p + 3, nlast) * frb;
+                c3_load_rows_slot(EP[B_ ^ 1], 0, wrs, g, foP1);
+                c3_load_rows_slot(EP[B_ ^ 1], 1, wrs, g, foP1);
                 if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
                     const float fcs = a.scale * c3_mscale(S + sF[B_] + eF4[B_], D, xwide);
@@ -676,6 +682,11 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 const int tw = ek + sP[B_];                 // exponent of this wave's sums
                 if (lane == 0) ctl_s[16 + wave] = tw;
                 if (lane < 8) bl_s[8 * wave + lane] = own * EP[B_].m;      // empty-label arcs of the own states
+                {
+                    const unsigned foP1 = (unsigned)min(2 * p + 3, nlast) * frb;
+#pragma unroll
+                    for (int j = 2; j < 5; ++j) c3_load_rows_slot(EP[B_ ^ 1], j, wrs, g, foP1);
+                }
                 C3_MARK(a, p, 4);
                 c2_barrier();
                 C3_MARK(a, p, 5);
@@ -722,7 +733,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // frames' requests, because a wave's loads return in order
                 C3_MARK(a, p, 6);
                 C3Look lk;
-                const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb, foP2 = (unsigned)min(2 * p + 5, nlast) * frb;
+                const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb;
                 prep(std::integral_constant<int, B_ ^ 1>(),
                      [&](int j) __attribute__((always_inline)) {
                          if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
@@ -732,18 +743,19 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
                          C3_MARK(a, p, 12);
                      },
-                     [&](int j) __attribute__((always_inline)) {
-                         c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
-                         if (j == 3) c3_load_cols_slot(EF[B_], 4, wrs, g, foF2);
-                     });
+                     [](int) {});
                 C3_MARK(a, p, 7);
+                if (!exch) {
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
+                }
                 if (exch) {
                     int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
                                   C3_MARK(a, p, 8);
 #pragma unroll
-                                  for (int j = 0; j < 5; ++j) c3_load_rows_slot(EP[B_], j, wrs, g, foP2);
+                                  for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
                               }, &relooks);
                     C3_MARK(a, p, 9);
                     C3_NOTE(a, p, 10, relooks);
@@ -789,7 +801,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
     const C3Geom g = c3_geom(cg.k);
     const int lane = g.lane, wave = g.wave, k = g.k;
     const unsigned voffq = (unsigned)((2 * (tid & 3)) * kC3XS + 2 * (tid >> 2)) * 8u;
-    const unsigned voffz = (unsigned)((lane & 7) * kC3XS + 256) * 8u;
+    const unsigned voffz = tid < 8 ? (unsigned)(tid * kC3XS + 256) * 8u : kC2Off;
     const unsigned voffpub = tid < 256 ? (unsigned)(k * kC3XS + tid) * 8u : kC2Off;
     const int pcol = tid & 255;
     const bool pubown = (pcol >> 5) == k;
@@ -897,7 +909,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         };
 
         issue(std::integral_constant<int, 0>(), 0);
-        issue(std::integral_constant<int, 1>(), 1);
+        c3_load_rows(EF[1], wrs, g, (unsigned)frameF(1) * frb);          // (its P frame: requested in pair 0)
         prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
@@ -943,6 +955,13 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                 for (int j = 0; j < 4; ++j) rs[j] = wave_sum_dpp(rs[j]);
                 if (g.xR) rs[4] = wave_sum_dpp(rs[4]);
+                // the P frame of the next pair is requested here and in the P-step, where the address path has
+                // little else to do (into the registers the pair before this one has finished with)
+                {
+                    const unsigned foP1 = (unsigned)frameP(p + 1) * frb;
+                    c3_load_cols_slot(EP[B_ ^ 1], 0, wrs, g, foP1);
+                    c3_load_cols_slot(EP[B_ ^ 1], 1, wrs, g, foP1);
+                }
                 if (GAMMA && iF >= ph1) {
                     const unsigned gso = (unsigned)tF * frb;
                     const float frs = a.scale * c3_mscale(__builtin_amdgcn_readlane(eFm[B_], 0) + S + sF[B_], D, xwide);
@@ -1025,6 +1044,11 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 if (lane < 8) bl_s[8 * wave + lane] = mo;
                 if (lane == 8) z_s[wave] = zt;
                 if (lane == 0) { ctl_s[16 + wave] = tw; ctl_s[24 + wave] = tb; }
+                {
+                    const unsigned foP1 = (unsigned)frameP(p + 1) * frb;
+#pragma unroll
+                    for (int j = 2; j < 5; ++j) c3_load_cols_slot(EP[B_ ^ 1], j, wrs, g, foP1);
+                }
                 C3_MARK(a, p, 4);
                 c2_barrier();
                 C3_MARK(a, p, 5);
@@ -1064,7 +1088,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 }
                 C3_MARK(a, p, 6);
                 C3Look lk;
-                const unsigned foF2 = (unsigned)frameF(p + 2) * frb, foP2 = (unsigned)frameP(p + 2) * frb;
+                const unsigned foF2 = (unsigned)frameF(p + 2) * frb;
                 prep(std::integral_constant<int, B_ ^ 1>(),
                      [&](int j) __attribute__((always_inline)) {
                          if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
@@ -1074,18 +1098,19 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
                          C3_MARK(a, p, 12);
                      },
-                     [&](int j) __attribute__((always_inline)) {
-                         c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
-                         if (j == 3) c3_load_rows_slot(EF[B_], 4, wrs, g, foF2);
-                     });
+                     [](int) {});
                 C3_MARK(a, p, 7);
+                if (!exch) {
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
+                }
                 if (exch) {
                     int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
                                   C3_MARK(a, p, 8);
 #pragma unroll
-                                  for (int j = 0; j < 5; ++j) c3_load_cols_slot(EP[B_], j, wrs, g, foP2);
+                                  for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
                               }, &relooks);
                     C3_MARK(a, p, 9);
                     C3_NOTE(a, p, 10, relooks);
