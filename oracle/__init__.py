@@ -77,6 +77,20 @@ def next_state(V: int, order: int, q: int, y: int) -> int:
     return int(_load().lo_next_state(int(V), int(order), int(q), int(y)))
 
 
+_table_keepalive = None
+
+
+def set_next_table(table) -> None:
+    """Register a NextStateTable context dependency (Section 3): table [C, V] int32, table[q, y-1] =
+    destination of label y out of state q.  Functions called with order = 0 use it."""
+    global _table_keepalive
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    C, V = table.shape
+    assert table.min() >= 0 and table.max() < C
+    _table_keepalive = table
+    _load().lo_set_next_table(_p(table, ctypes.c_int32), int(C), int(V))
+
+
 def next_state_table(V: int, order: int) -> np.ndarray:
     C = num_states(V, order)
     return np.array([[next_state(V, order, q, y) for y in range(V + 1)] for q in range(C)],
@@ -169,6 +183,33 @@ def numerator(w, lengths, refs, ref_lengths, order=1):
                               _p(pl, ctypes.c_double))
     assert rc == 0
     return dict(N=N, ctx=ctx, a=a, b=bb, pb=pb, pl=pl)
+
+
+def numerator_local(w, lengths, refs, ref_lengths, order=1, grad=True):
+    """Locally normalised (RNN-T-style) log-likelihood of the reference on the intersected lattice
+    (Section 2.1; Table 1, first row): the numerator recursion on w - logsumexp_y w.  Returns the
+    dict of `numerator` plus grad [B,T,C,V+1] = dN/dw."""
+    w, B, T, C, V = _dims(w, order)
+    lengths = _i32(lengths)
+    refs = _i32(refs)
+    ref_lengths = _i32(ref_lengths)
+    Umax = refs.shape[1]
+    U1 = Umax + 1
+    ctx = np.empty((B, U1), dtype=np.int32)
+    a = np.empty((B, T + 1, U1), dtype=np.float64)
+    bb = np.empty((B, T + 1, U1), dtype=np.float64)
+    N = np.empty((B,), dtype=np.float64)
+    pb = np.empty((B, T, U1), dtype=np.float64)
+    pl = np.empty((B, T, U1), dtype=np.float64)
+    g = np.empty((B, T, C, V + 1), dtype=np.float64) if grad else None
+    rc = _load().lo_numerator_local(_p(w, ctypes.c_float), _p(lengths, ctypes.c_int32),
+                                    _p(refs, ctypes.c_int32), _p(ref_lengths, ctypes.c_int32),
+                                    B, T, V, order, Umax, _p(ctx, ctypes.c_int32),
+                                    _p(a, ctypes.c_double), _p(bb, ctypes.c_double),
+                                    _p(N, ctypes.c_double), _p(pb, ctypes.c_double),
+                                    _p(pl, ctypes.c_double), _p(g, ctypes.c_double))
+    assert rc == 0
+    return dict(N=N, ctx=ctx, a=a, b=bb, pb=pb, pl=pl, grad=g)
 
 
 def numerator_posteriors_dense(num, refs, ref_lengths, shape):

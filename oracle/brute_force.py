@@ -57,6 +57,44 @@ def enumerate_paths(w_item: np.ndarray, order: int):
             np.array(scores, dtype=np.float64))
 
 
+def history_table(V: int, order: int):
+    """The full n-gram context dependency of any order as an explicit automaton (Section 3): the
+    states are the label histories of length < order ... = order in order of length, then
+    lexicographically; returns (table [C, V] with table[q, y-1] = state after label y, histories)."""
+    hist = [()]
+    for n in range(1, order + 1):
+        hist += list(itertools.product(range(1, V + 1), repeat=n))
+    index = {h: i for i, h in enumerate(hist)}
+    table = np.zeros((len(hist), V), dtype=np.int32)
+    for h, i in index.items():
+        for y in range(1, V + 1):
+            table[i, y - 1] = index[(h + (y,))[-order:]]
+    return table, hist
+
+
+def enumerate_paths_table(w_item: np.ndarray, table: np.ndarray):
+    """All accepting paths when the context dependency is an explicit automaton: table[q, y-1] is
+    the state after label y in state q, label 0 (empty) keeps the state."""
+    T, C, V1 = w_item.shape
+    w = w_item.astype(np.float64)
+    labels, states, scores = [], [], []
+    for seq in itertools.product(range(V1), repeat=T):
+        q = 0
+        st = [0]
+        s = 0.0
+        for t, y in enumerate(seq):
+            s += w[t, q, y]
+            if y != 0:
+                q = int(table[q, y - 1])
+            st.append(q)
+        labels.append(seq)
+        states.append(st)
+        scores.append(s)
+    return (np.array(labels, dtype=np.int64).reshape(-1, T),
+            np.array(states, dtype=np.int64).reshape(-1, T + 1),
+            np.array(scores, dtype=np.float64))
+
+
 def log_sum(scores: np.ndarray) -> float:
     if scores.size == 0:
         return -np.inf

@@ -46,9 +46,24 @@
 /* order 2: state 0, states (a) -> a, states (a,b) -> 1+V+(a-1)V+(b-1).    */
 /* ---------------------------------------------------------------------- */
 
+/* A context dependency may also be any deterministic automaton that accepts  */
+/* Sigma^*, given by a look-up table ("NextStateTable", Section 3):          */
+/* table[q][y-1] = destination of label y out of state q.  It is registered  */
+/* with lo_set_next_table and selected with order == 0.                      */
+static const int32_t* g_table = NULL;
+static int g_table_C = 0, g_table_V = 0;
+
+void lo_set_next_table(const int32_t* table, int C, int V)
+{
+    g_table = table;
+    g_table_C = C;
+    g_table_V = V;
+}
+
 int lo_num_states(int V, int order)
 {
     if (V < 1) return -1;
+    if (order == 0) return (g_table != NULL && V == g_table_V) ? g_table_C : -1;
     if (order == 1) return 1 + V;
     if (order == 2) return 1 + V + V * V;
     return -1;
@@ -58,6 +73,7 @@ int lo_num_states(int V, int order)
 int lo_next_state(int V, int order, int q, int y)
 {
     if (y == 0) return q;
+    if (order == 0) return g_table[q * V + (y - 1)];
     if (order == 1) return y;
     /* order 2 */
     if (q == 0) return y;                       /* ()    --y--> (y)    */
@@ -329,6 +345,104 @@ int lo_numerator(const float* w, const int32_t* len, const int32_t* refs, const 
                         double nl = Bk[(size_t)(t + 1) * U1 + u + 1];
                         if (nl != NEG_INF)
                             PL[(size_t)t * U1 + u] = exp(av + (double)wt[cx[u] * V1 + r[u]] + nl - N[b]);
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Locally normalised model on the intersected lattice (Section 2.1: a     */
+/* model like RNN-T is the intersection followed by a shortest distance;    */
+/* Table 1, first row).  The weights of the V+1 arcs leaving a state (t,q)  */
+/* are normalised, w'[t][q][y] = w[t][q][y] - log sum_y' exp w[t][q][y'],   */
+/* and the shortest distance of the intersected lattice under w' is the     */
+/* log-likelihood of the reference string; there is no denominator.         */
+/* Same outputs as lo_numerator, plus                                       */
+/*   grad out [B][T][C][V+1] (or NULL): d N / d w, i.e. for every state     */
+/*        (t,u) with context q: its arc marginals on (q,0) and (q,ref[u])   */
+/*        minus (their sum) * softmax(w[t][q])[y] on every y.               */
+/* ---------------------------------------------------------------------- */
+static double local_logw(const float* wt, int V1, int q, int y)
+{
+    double tmp[V1];
+    for (int k = 0; k < V1; ++k) tmp[k] = (double)wt[q * V1 + k];
+    return (double)wt[q * V1 + y] - lse(tmp, V1);
+}
+
+int lo_numerator_local(const float* w, const int32_t* len, const int32_t* refs, const int32_t* ulen,
+                       int B, int T, int V, int order, int Umax,
+                       int32_t* ctx, double* a, double* bb, double* N, double* pb, double* pl,
+                       double* grad)
+{
+    const int C = lo_num_states(V, order);
+    if (C < 0) return 1;
+    const int V1 = V + 1;
+    const int U1 = Umax + 1;
+    const size_t fr = (size_t)C * V1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int L = clamp_len(len[b], T);
+        const int U = ulen[b];
+        const int32_t* r = refs + (size_t)b * Umax;
+        int32_t* cx = ctx + (size_t)b * U1;
+        double* A = a + (size_t)b * (T + 1) * U1;
+        double* Bk = bb + (size_t)b * (T + 1) * U1;
+        double* PB = pb + (size_t)b * T * U1;
+        double* PL = pl + (size_t)b * T * U1;
+        for (size_t i = 0; i < (size_t)(T + 1) * U1; ++i) { A[i] = NEG_INF; Bk[i] = NEG_INF; }
+        for (size_t i = 0; i < (size_t)T * U1; ++i) { PB[i] = 0.0; PL[i] = 0.0; }
+        if (grad) for (size_t i = 0; i < (size_t)T * fr; ++i) grad[(size_t)b * T * fr + i] = 0.0;
+        cx[0] = 0;
+        for (int u = 1; u <= Umax; ++u)
+            cx[u] = (u <= U) ? lo_next_state(V, order, cx[u - 1], r[u - 1]) : -1;
+        A[0] = 0.0;
+        for (int t = 0; t < L; ++t) {
+            const float* wt = w + ((size_t)b * T + t) * fr;
+            for (int u = 0; u <= U; ++u) {
+                double c[2];
+                c[0] = A[(size_t)t * U1 + u] + local_logw(wt, V1, cx[u], 0);
+                c[1] = NEG_INF;
+                if (u >= 1)
+                    c[1] = A[(size_t)t * U1 + u - 1] + local_logw(wt, V1, cx[u - 1], r[u - 1]);
+                A[(size_t)(t + 1) * U1 + u] = lse(c, 2);
+            }
+        }
+        N[b] = A[(size_t)L * U1 + U];
+        Bk[(size_t)L * U1 + U] = 0.0;
+        for (int t = L - 1; t >= 0; --t) {
+            const float* wt = w + ((size_t)b * T + t) * fr;
+            for (int u = 0; u <= U; ++u) {
+                double c[2];
+                c[0] = local_logw(wt, V1, cx[u], 0) + Bk[(size_t)(t + 1) * U1 + u];
+                c[1] = NEG_INF;
+                if (u < U)
+                    c[1] = local_logw(wt, V1, cx[u], r[u]) + Bk[(size_t)(t + 1) * U1 + u + 1];
+                Bk[(size_t)t * U1 + u] = lse(c, 2);
+            }
+        }
+        if (N[b] != NEG_INF) {
+            for (int t = 0; t < L; ++t) {
+                const float* wt = w + ((size_t)b * T + t) * fr;
+                for (int u = 0; u <= U; ++u) {
+                    double av = A[(size_t)t * U1 + u];
+                    if (av == NEG_INF) continue;
+                    double nb = Bk[(size_t)(t + 1) * U1 + u];
+                    if (nb != NEG_INF)
+                        PB[(size_t)t * U1 + u] = exp(av + local_logw(wt, V1, cx[u], 0) + nb - N[b]);
+                    if (u < U) {
+                        double nl = Bk[(size_t)(t + 1) * U1 + u + 1];
+                        if (nl != NEG_INF)
+                            PL[(size_t)t * U1 + u] = exp(av + local_logw(wt, V1, cx[u], r[u]) + nl - N[b]);
+                    }
+                    if (grad) {
+                        double* g = grad + ((size_t)b * T + t) * fr + (size_t)cx[u] * V1;
+                        const double occ = PB[(size_t)t * U1 + u] + PL[(size_t)t * U1 + u];
+                        g[0] += PB[(size_t)t * U1 + u];
+                        if (u < U) g[r[u]] += PL[(size_t)t * U1 + u];
+                        for (int y = 0; y < V1; ++y) g[y] -= occ * exp(local_logw(wt, V1, cx[u], y));
                     }
                 }
             }

@@ -34,10 +34,26 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
-def dense(B, T, V, order=1, sigma=1.0, len_lo=None, len_hi=None, seed=0, pad_nan=False):
-    """Dense weights [B,T,C,V+1] ~ sigma*N(0,1) with per-item lengths."""
+def random_table(C, V, seed=0):
+    """A random deterministic automaton over V labels that accepts every string: table [C, V]
+    int32, table[q, y-1] = state after label y.  Every state is made reachable from state 0."""
     rng = np.random.default_rng(seed)
-    C = num_states(V, order)
+    table = rng.integers(0, C, size=(C, V)).astype(np.int32)
+    used = set()
+    for q in range(1, C):          # a spanning tree of label arcs keeps every state reachable
+        slot = (int(rng.integers(0, q)), int(rng.integers(0, V)))
+        if slot in used:           # state q-1 has given away no arc yet
+            slot = (q - 1, slot[1])
+        used.add(slot)
+        table[slot] = q
+    return table
+
+
+def dense(B, T, V, order=1, sigma=1.0, len_lo=None, len_hi=None, seed=0, pad_nan=False, C=None):
+    """Dense weights [B,T,C,V+1] ~ sigma*N(0,1) with per-item lengths (C given: table contexts)."""
+    rng = np.random.default_rng(seed)
+    if C is None:
+        C = num_states(V, order)
     if len_lo is None:
         lengths = np.full((B,), T, dtype=np.int32)
     else:

@@ -472,3 +472,158 @@ def test_fused_gradients_match_dense_chain_rule_and_finite_differences():
             args_m = dict(f=f, e=e, W=W); args_m[name] = am
             fd = (total_D(**args_p) - total_D(**args_m)) / (2 * h)
             assert abs(fd - g[idx]) < 1e-7, (name, idx, fd, g[idx])
+
+
+# ------------------------------------------- table-driven context dependencies
+def _use_table(table):
+    oracle.set_next_table(table)
+    return 0          # the order value that selects the registered table
+
+
+@pytest.mark.parametrize("V,order,T", [(3, 1, 5), (2, 2, 6)])
+def test_table_of_full_ngram_reproduces_closed_form_orders(V, order, T):
+    """A NextStateTable built from label histories (Section 3) gives the same lattice as the
+    closed-form full n-gram arithmetic of orders 1 and 2."""
+    table, hist = bf.history_table(V, order)
+    assert [bf.history_index(h, V) for h in hist] == list(range(len(hist)))
+    d = workloads.dense(B=2, T=T, V=V, order=order, seed=71, len_lo=T - 2, len_hi=T)
+    o0 = _use_table(table)
+    a0, D0 = oracle.forward(d["w"], d["lengths"], o0)
+    a1, D1 = oracle.forward(d["w"], d["lengths"], order)
+    assert np.array_equal(a0, a1) and np.array_equal(D0, D1)
+    assert np.array_equal(oracle.posteriors(d["w"], d["lengths"], o0),
+                          oracle.posteriors(d["w"], d["lengths"], order))
+    for x, y in zip(oracle.viterbi(d["w"], d["lengths"], o0), oracle.viterbi(d["w"], d["lengths"], order)):
+        assert np.array_equal(x, y)
+    refs = np.array([[1, 2, 1], [2, 2, 1]], dtype=np.int32)
+    n0 = oracle.numerator(d["w"], d["lengths"], refs, [3, 2], o0)
+    n1 = oracle.numerator(d["w"], d["lengths"], refs, [3, 2], order)
+    for k in n0:
+        assert np.array_equal(n0[k], n1[k]), k
+
+
+def _check_table_vs_enumeration(table, w, ref):
+    T = w.shape[1]
+    o0 = _use_table(table)
+    labels, states, scores = bf.enumerate_paths_table(w[0], table)
+    D_bf, g_bf = bf.arc_marginals(labels, states, scores, w[0].shape)
+    _, D = oracle.forward(w, [T], o0)
+    assert abs(D[0] - D_bf) < 1e-10
+    assert np.max(np.abs(oracle.posteriors(w, [T], o0)[0] - g_bf)) < 1e-12
+    lab, st, score = oracle.viterbi(w, [T], o0, precision="f64")
+    bl, bs, bsc = bf.best_path(labels, states, scores)
+    assert abs(score[0] - bsc) < 1e-12
+    assert np.array_equal(lab[0], bl) and np.array_equal(st[0], bs)
+    U = len(ref)
+    refs = np.ones((1, max(U, 1)), dtype=np.int32)
+    refs[0, :U] = ref
+    num = oracle.numerator(w, [T], refs, [U], o0)
+    l, s, sc = bf.restrict_to_reference(labels, states, scores, ref)
+    N_bf, gn_bf = bf.arc_marginals(l, s, sc, w[0].shape)
+    assert abs(num["N"][0] - N_bf) < 1e-10
+    gn = oracle.numerator_posteriors_dense(num, refs, [U], w.shape)
+    assert np.max(np.abs(gn[0] - gn_bf)) < 1e-12
+
+
+def test_order3_table_vs_enumeration():
+    """Full 3-gram context dependency, given as a table over label histories: 1+2+4+8 states."""
+    table, hist = bf.history_table(2, 3)
+    assert table.shape == (15, 2)
+    d = workloads.dense(B=1, T=7, V=2, seed=72, C=15)
+    _check_table_vs_enumeration(table, d["w"], (1, 2, 2, 1, 1))
+
+
+@pytest.mark.parametrize("C,V,T,seed", [(5, 3, 6, 0), (4, 2, 8, 1), (1, 3, 5, 2), (7, 1, 9, 3)])
+def test_random_table_vs_enumeration(C, V, T, seed):
+    """Any deterministic automaton accepting every string is a valid context dependency."""
+    table = workloads.random_table(C, V, seed)
+    d = workloads.dense(B=1, T=T, V=V, seed=73 + seed, C=C)
+    rng = np.random.default_rng(seed)
+    ref = tuple(int(x) for x in rng.integers(1, V + 1, size=min(T - 2, 4)))
+    _check_table_vs_enumeration(table, d["w"], ref)
+
+
+# ------------------------------------------------- locally normalised numerator
+def test_local_numerator_equals_numerator_on_library_log_softmax():
+    """Normalising the arcs leaving each state and running the globally normalised numerator is
+    the same computation (Section 2.1); the library log-softmax stands in for the oracle's."""
+    from scipy.special import log_softmax
+    d = workloads.config(3, B=3, T=14, V=5, Umax=7, u_lo=0, u_hi=7)
+    w = d["w"]
+    wl = log_softmax(w.astype(np.float64), axis=-1)
+    loc = oracle.numerator_local(w, d["lengths"], d["refs"], d["ref_lengths"], 1)
+    # the float32 rounding of the normalised weights is the only difference; bound it
+    num = oracle.numerator(wl.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1)
+    assert np.max(np.abs(loc["N"] - num["N"])) < 14 * 2e-7 * np.abs(wl).max()
+    assert np.max(np.abs(loc["pb"] - num["pb"])) < 1e-5
+    assert np.max(np.abs(loc["pl"] - num["pl"])) < 1e-5
+    assert np.array_equal(loc["ctx"], num["ctx"])
+    # and the denominator of locally normalised weights is log 1
+    _, D = oracle.forward(wl.astype(np.float32), d["lengths"], 1)
+    assert np.max(np.abs(D)) < 1e-5
+
+
+def test_local_numerator_is_a_distribution_over_label_strings():
+    """With locally normalised arcs the likelihoods of all label strings of length <= T sum to 1."""
+    d = workloads.dense(B=1, T=6, V=2, order=2, seed=74)
+    total = []
+    for U in range(0, 7):
+        for ref in itertools.product((1, 2), repeat=U):
+            refs = np.ones((1, 6), dtype=np.int32)
+            refs[0, :U] = ref
+            total.append(oracle.numerator_local(d["w"], d["lengths"], refs, [U], 2, grad=False)["N"][0])
+    assert len(total) == 127
+    assert abs(logsumexp(np.array(total))) < 1e-12
+
+
+def test_local_numerator_closed_forms_and_enumeration():
+    T, V = 11, 4
+    w = np.full((1, T, V + 1, V + 1), 0.375, dtype=np.float32)
+    for U in (0, 1, 5, 11):
+        refs = np.ones((1, T), dtype=np.int32) * 3
+        loc = oracle.numerator_local(w, [T], refs, [U], 1)
+        assert abs(loc["N"][0] - (math.log(comb(T, U, exact=True)) - T * math.log(V + 1))) < 1e-10
+    # one path by hand: U = 0 keeps the start state, every arc is the empty label
+    d = workloads.dense(B=1, T=9, V=3, seed=75)
+    w64 = d["w"].astype(np.float64)
+    loc = oracle.numerator_local(d["w"], d["lengths"], np.ones((1, 2), np.int32), [0], 1)
+    assert abs(loc["N"][0] - np.sum(w64[0, :, 0, 0] - logsumexp(w64[0, :, 0, :], axis=-1))) < 1e-12
+    # infeasible
+    loc = oracle.numerator_local(d["w"], [3], np.ones((1, 4), np.int32), [4], 1)
+    assert loc["N"][0] == -np.inf and np.all(loc["grad"] == 0)
+    # enumeration with path weights normalised arc by arc, on a random table
+    table = workloads.random_table(4, 2, 5)
+    o0 = _use_table(table)
+    d = workloads.dense(B=1, T=7, V=2, seed=76, C=4)
+    wn = d["w"].astype(np.float64) - logsumexp(d["w"].astype(np.float64), axis=-1, keepdims=True)
+    labels, states, scores = bf.enumerate_paths_table(wn[0], table)
+    assert abs(bf.log_sum(scores)) < 1e-12
+    ref = (2, 1, 1)
+    l, s, sc = bf.restrict_to_reference(labels, states, scores, ref)
+    N_bf, g_bf = bf.arc_marginals(l, s, sc, wn[0].shape)
+    loc = oracle.numerator_local(d["w"], [7], np.array([ref], np.int32), [3], o0)
+    assert abs(loc["N"][0] - N_bf) < 1e-10
+    g = oracle.numerator_posteriors_dense(loc, np.array([ref], np.int32), [3], d["w"].shape)
+    assert np.max(np.abs(g[0] - g_bf)) < 1e-12
+    # gradient = arc marginals - (occupancy of the source state) * softmax
+    occ = g_bf.sum(axis=-1, keepdims=True)
+    assert np.max(np.abs(loc["grad"][0] - (g_bf - occ * np.exp(wn[0])))) < 1e-12
+
+
+def test_local_numerator_gradient_finite_differences():
+    d = workloads.config(3, B=1, T=9, V=3, Umax=5, u_lo=4, u_hi=4)
+    w = np.round(d["w"].astype(np.float64) * 32) / 32
+    loc = oracle.numerator_local(w.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1)
+    assert np.max(np.abs(loc["grad"].sum(axis=-1))) < 1e-12
+    rng = np.random.default_rng(7)
+    h = 2.0 ** -10
+    L = int(d["lengths"][0])
+    ctxs = loc["ctx"][0, :5]
+    for _ in range(40):
+        t, q, y = rng.integers(0, L), int(ctxs[rng.integers(0, 5)]), rng.integers(0, 4)
+        wp, wm = w.copy(), w.copy()
+        wp[0, t, q, y] += h
+        wm[0, t, q, y] -= h
+        Np = oracle.numerator_local(wp.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1, grad=False)["N"][0]
+        Nm = oracle.numerator_local(wm.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1, grad=False)["N"][0]
+        assert abs((Np - Nm) / (2 * h) - loc["grad"][0, t, q, y]) < 1e-6
