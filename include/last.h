@@ -10,7 +10,9 @@
  * tropical shortest path with integer backpointers (Sections 2.3, 4.2.3).
  *
  * Lattice (Section 3): context dependency = full n-gram of context size
- * `order` over `vocab` labels; alignment lattice = frame dependent (exactly
+ * `order` (1 or 2) over `vocab` labels, or any deterministic automaton that
+ * accepts every label string, given as a next-state table (order = 0; this is
+ * also how context sizes of 3 and more are expressed); alignment lattice = frame dependent (exactly
  * one arc, a label or the empty label, per frame; Figure 1b); weight function
  * = a dense tensor, or the shared-embedding function evaluated on the fly
  * (Section 4.1) as tanh(f[b][t] + e[q]) @ W.
@@ -20,7 +22,8 @@
  *   context states q in 0..C-1; 0 = empty history;
  *     order 1: state a (1..V) = "last label a";               C = 1 + V
  *     order 2: (a) -> a, (a,b) -> 1 + V + (a-1)V + (b-1);     C = 1 + V + V^2
- *   next(q, y>0): order 1 -> y; order 2: () -> (y), (a) -> (a,y), (a,b) -> (b,y).
+ *   next(q, y>0): order 1 -> y; order 2: () -> (y), (a) -> (a,y), (a,b) -> (b,y);
+ *     order 0: next_table[q*V + (y-1)], the start state is 0.
  *   every state (len[b], q) is final with weight 0.
  *   dense weights: w[b][t][q][y], float32, C-contiguous [B][T][C][V+1].
  *   semirings: higher is better; (+) = log-add-exp (LAST_LOG) or max
@@ -70,7 +73,7 @@ typedef enum {
     LAST_OK = 0,
     LAST_ERR_NULL = 1,        /* a required pointer is NULL                    */
     LAST_ERR_SHAPE = 2,       /* a size is non-positive or too large           */
-    LAST_ERR_CONTEXT = 3,     /* order not in {1,2} or num_states inconsistent */
+    LAST_ERR_CONTEXT = 3,     /* order not in {0,1,2} or num_states inconsistent */
     LAST_ERR_SEMIRING = 4,    /* unknown semiring                              */
     LAST_ERR_WORKSPACE = 5,   /* ws NULL, misaligned or too small              */
     LAST_ERR_UNSUPPORTED = 6, /* combination not implemented                   */
@@ -83,14 +86,23 @@ typedef enum {
     LAST_OP_SHORTEST_DISTANCE = 0,
     LAST_OP_ARC_POSTERIORS = 1,
     LAST_OP_INTERSECT_REFERENCE = 2,
-    LAST_OP_SHORTEST_PATH = 3
+    LAST_OP_SHORTEST_PATH = 3,
+    LAST_OP_LOCAL_LOG_LIKELIHOOD = 4
 } last_op_t;
 
-/* Context dependency: full n-gram (Section 3; Figure 1a is order 1). */
+/* Context dependency (Section 3): the full n-gram one in closed form (Figure 1a
+ * is order 1), or a next-state table.  next_table: dev int32 [C][V], read by
+ * every call that uses the struct, never written; it must stay valid until the
+ * work enqueued by the call has finished.  With a table, the weights must be
+ * dense, every call runs one workgroup per item, C is limited by the 160 KiB of
+ * LDS of a compute unit (about 10000 states for the log semiring, 13000 for the
+ * tropical one; LAST_ERR_UNSUPPORTED beyond), and each call validates the table
+ * on the device (item_status 7). */
 typedef struct {
-    int32_t vocab;      /* V >= 1                                  */
-    int32_t order;      /* context size n: 1 or 2                  */
-    int32_t num_states; /* C, must equal sum_{k<=n} V^k            */
+    int32_t vocab;             /* V >= 1                                              */
+    int32_t order;             /* context size n: 1 or 2; 0 = next_table              */
+    int32_t num_states;        /* C; order 1, 2: must equal sum_{k<=n} V^k            */
+    const int32_t* next_table; /* order 0 only (NULL otherwise)                       */
 } last_context_t;
 
 enum { LAST_WEIGHTS_DENSE = 0, LAST_WEIGHTS_SHARED_EMB = 1 };
@@ -127,7 +139,8 @@ typedef struct {
 } last_grads_t;
 
 /* Scratch bytes `op` needs for these shapes (Umax only matters for
- * LAST_OP_INTERSECT_REFERENCE).  Returns 0 on invalid arguments. */
+ * LAST_OP_INTERSECT_REFERENCE and LAST_OP_LOCAL_LOG_LIKELIHOOD).  Returns 0 on
+ * invalid arguments. */
 size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t* context,
                             int32_t op, int32_t Umax);
 
@@ -164,6 +177,24 @@ last_status_t last_intersect_reference(const last_weights_t* weights, const int3
                                        int32_t Umax, float* numerator,
                                        const last_grads_t* out, int32_t* item_status,
                                        void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Log-likelihood of the reference string under the locally normalised model on
+ * the same lattice (Section 2.1: intersection and shortest distance, with the
+ * weights of the V+1 arcs leaving each state (t,q) normalised,
+ * w'[t][q][y] = w[t][q][y] - log sum_y' exp w[t][q][y']; Table 1, first row).
+ * No denominator lattice is needed.  Arguments as last_intersect_reference;
+ * loglik: dev float32 [B].  out (or NULL): d loglik / d w on the dense tensor,
+ * i.e. the marginals of the intersected lattice on the arcs they ride on minus
+ * (their sum over the arcs leaving the state) * softmax(w[t][q])[y]; rows of
+ * states the reference never visits are 0.  Unlike last_intersect_reference
+ * the result is independent of timing (no floating-point atomics).
+ * Requires 4*(V+1)*4 bytes <= 64 KiB of LDS (V < 4096). */
+last_status_t last_local_log_likelihood(const last_weights_t* weights, const int32_t* lengths,
+                                        const last_context_t* context,
+                                        const int32_t* refs, const int32_t* ref_lengths,
+                                        int32_t Umax, float* loglik,
+                                        const last_grads_t* out, int32_t* item_status,
+                                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Tropical shortest path (Sections 2.1, 2.3, 4.2.3): one float32 add per arc,
  * arg max kept per state as the flat arc index q*(V+1)+y, ties to the lowest

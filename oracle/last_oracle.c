@@ -365,11 +365,17 @@ int lo_numerator(const float* w, const int32_t* len, const int32_t* refs, const 
 /*        (t,u) with context q: its arc marginals on (q,0) and (q,ref[u])   */
 /*        minus (their sum) * softmax(w[t][q])[y] on every y.               */
 /* ---------------------------------------------------------------------- */
-static double local_logw(const float* wt, int V1, int q, int y)
+static double row_lse(const float* wt, int V1, int q)
 {
     double tmp[V1];
     for (int k = 0; k < V1; ++k) tmp[k] = (double)wt[q * V1 + k];
-    return (double)wt[q * V1 + y] - lse(tmp, V1);
+    return lse(tmp, V1);
+}
+
+/* normalised weight of arc (q, y) of the frame whose weights start at wt */
+static double local_logw(const float* wt, int V1, int q, int y)
+{
+    return (double)wt[q * V1 + y] - row_lse(wt, V1, q);
 }
 
 int lo_numerator_local(const float* w, const int32_t* len, const int32_t* refs, const int32_t* ulen,
@@ -442,7 +448,8 @@ int lo_numerator_local(const float* w, const int32_t* len, const int32_t* refs, 
                         const double occ = PB[(size_t)t * U1 + u] + PL[(size_t)t * U1 + u];
                         g[0] += PB[(size_t)t * U1 + u];
                         if (u < U) g[r[u]] += PL[(size_t)t * U1 + u];
-                        for (int y = 0; y < V1; ++y) g[y] -= occ * exp(local_logw(wt, V1, cx[u], y));
+                        const double z = row_lse(wt, V1, cx[u]);
+                        for (int y = 0; y < V1; ++y) g[y] -= occ * exp((double)wt[cx[u] * V1 + y] - z);
                     }
                 }
             }

@@ -18,19 +18,21 @@ LIB_PATH = os.environ.get("LAST_HIP_LIB") or os.path.join(_HERE, "liblast_hip.so
 
 LAST_LOG, LAST_TROPICAL = 0, 1
 OP_SHORTEST_DISTANCE, OP_ARC_POSTERIORS, OP_INTERSECT_REFERENCE, OP_SHORTEST_PATH = 0, 1, 2, 3
+OP_LOCAL_LOG_LIKELIHOOD = 4
 WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
 
 EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
            "last_intersect_reference", "last_shortest_path", "last_status_string",
            "last_version", "last_kernel_variant", "last_hip_error_string",
-           "last_shortest_distance_static", "last_set_option", "last_get_option"]
+           "last_shortest_distance_static", "last_set_option", "last_get_option",
+           "last_local_log_likelihood"]
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class LastContext(ctypes.Structure):
     _fields_ = [("vocab", ctypes.c_int32), ("order", ctypes.c_int32),
-                ("num_states", ctypes.c_int32)]
+                ("num_states", ctypes.c_int32), ("next_table", ctypes.c_void_p)]
 
 
 class LastWeights(ctypes.Structure):
@@ -78,6 +80,8 @@ def load_library():
     lib.last_intersect_reference.restype = i32
     lib.last_intersect_reference.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                              vp, vp, i32, vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
+    lib.last_local_log_likelihood.restype = i32
+    lib.last_local_log_likelihood.argtypes = lib.last_intersect_reference.argtypes
     lib.last_shortest_path.restype = i32
     lib.last_shortest_path.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                        vp, vp, vp, vp, vp, sz, vp]
@@ -129,8 +133,9 @@ _workspaces = {}
 
 
 def workspace(nbytes, device):
-    """A cached device scratch buffer (grown on demand, 256-byte aligned by the allocator)."""
-    key = torch.device(device).index or 0
+    """A cached device scratch buffer (grown on demand, 256-byte aligned by the allocator), one per
+    device and stream: calls enqueued on different streams may overlap and must not share scratch."""
+    key = (torch.device(device).index or 0, torch.cuda.current_stream().cuda_stream)
     buf = _workspaces.get(key)
     if buf is None or buf.numel() < nbytes:
         buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
@@ -139,8 +144,37 @@ def workspace(nbytes, device):
 
 
 def context(V, order):
+    """order: 1 or 2 (full n-gram in closed form), or a device int32 tensor [C, V], the next-state
+    table of any deterministic automaton (table[q, y-1] = state after label y; start state 0)."""
+    if isinstance(order, torch.Tensor):
+        _dev_tensor(order, torch.int32, "next_table")
+        if order.dim() != 2 or order.shape[1] != V:
+            raise ValueError("next_table must be [C, V]")
+        return LastContext(V, 0, order.shape[0], order.data_ptr())
     C = 1 + V if order == 1 else 1 + V + V * V
-    return LastContext(V, order, C)
+    return LastContext(V, order, C, None)
+
+
+# item_status of the most recent call that was not given one (device int32 [B])
+last_item_status = None
+
+
+def _status(item_status, B, device):
+    """Every call gets an item_status array, so that data-dependent failures are never silent."""
+    global last_item_status
+    if item_status is None:
+        item_status = torch.empty(B, dtype=torch.int32, device=device)
+        last_item_status = item_status
+    return _dev_tensor(item_status, torch.int32, "item_status")
+
+
+def check_item_status(item_status=None):
+    """Synchronises and raises if any item of the call reported a problem (see include/last.h)."""
+    st = last_item_status if item_status is None else item_status
+    if st is not None:
+        bad = torch.nonzero(st).flatten().tolist()
+        if bad:
+            raise LastError(100 + int(st[bad[0]]), "item_status %d on items %s" % (int(st[bad[0]]), bad[:8]))
 
 
 def dense_weights(w):
@@ -198,6 +232,7 @@ def last_shortest_distance(w, lengths, order=1, semiring="log", item_status=None
     wt, cx, device, B = _weights_and_context(w, order)
     _dev_tensor(lengths, torch.int32, "lengths")
     dist = torch.empty(B, dtype=torch.float32, device=device)
+    item_status = _status(item_status, B, device)
     nbytes = last_workspace_bytes(wt, cx, OP_SHORTEST_DISTANCE)
     if nbytes == 0:
         raise LastError(6, "combination not supported")
@@ -243,6 +278,7 @@ def last_arc_posteriors(w, lengths, order=1, dw=None, scale=1.0, accumulate=Fals
             dw = torch.empty_like(w)
         _dev_tensor(dw, torch.float32, "dw")
         g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
+    item_status = _status(item_status, B, device)
     nbytes = last_workspace_bytes(wt, cx, OP_ARC_POSTERIORS)
     if nbytes == 0:
         raise LastError(6, "combination not supported")
@@ -253,10 +289,7 @@ def last_arc_posteriors(w, lengths, order=1, dw=None, scale=1.0, accumulate=Fals
     return dist, dw
 
 
-def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, scale=-1.0,
-                             accumulate=True, item_status=None):
-    """numerator [B] float32; if dw is given, scale * (marginals of the
-    intersected lattice) is added to (accumulate) or written over dw."""
+def _intersect(entry, op, w, lengths, refs, ref_lengths, order, dw, scale, accumulate, item_status):
     lib = load_library()
     wt, cx = dense_weights(w), _dense_ctx(w, order)
     _dev_tensor(lengths, torch.int32, "lengths")
@@ -264,16 +297,36 @@ def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, sc
     _dev_tensor(ref_lengths, torch.int32, "ref_lengths")
     Umax = refs.shape[1]
     num = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    item_status = _status(item_status, w.shape[0], w.device)
     g = None
     if dw is not None:
         _dev_tensor(dw, torch.float32, "dw")
         g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
-    ws = workspace(last_workspace_bytes(wt, cx, OP_INTERSECT_REFERENCE, Umax), w.device)
-    _check(lib.last_intersect_reference(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx),
-                                        _ptr(refs), _ptr(ref_lengths), Umax, _ptr(num),
-                                        ctypes.byref(g) if g is not None else None,
-                                        _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
+    nbytes = last_workspace_bytes(wt, cx, op, Umax)
+    if nbytes == 0:
+        raise LastError(6, "combination not supported")
+    ws = workspace(nbytes, w.device)
+    _check(getattr(lib, entry)(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx),
+                               _ptr(refs), _ptr(ref_lengths), Umax, _ptr(num),
+                               ctypes.byref(g) if g is not None else None,
+                               _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
     return num
+
+
+def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, scale=-1.0,
+                             accumulate=True, item_status=None):
+    """numerator [B] float32; if dw is given, scale * (marginals of the
+    intersected lattice) is added to (accumulate) or written over dw."""
+    return _intersect("last_intersect_reference", OP_INTERSECT_REFERENCE, w, lengths, refs, ref_lengths,
+                      order, dw, scale, accumulate, item_status)
+
+
+def last_local_log_likelihood(w, lengths, refs, ref_lengths, order=1, dw=None, scale=1.0,
+                              accumulate=False, item_status=None):
+    """Log-likelihood [B] float32 of the references under the locally normalised model on the same
+    lattice; if dw is given, scale * d loglik / d w is written over (or added to) it."""
+    return _intersect("last_local_log_likelihood", OP_LOCAL_LOG_LIKELIHOOD, w, lengths, refs, ref_lengths,
+                      order, dw, scale, accumulate, item_status)
 
 
 def last_shortest_path(w, lengths, order=1, item_status=None):
@@ -285,7 +338,11 @@ def last_shortest_path(w, lengths, order=1, item_status=None):
     labels = torch.empty((B, T), dtype=torch.int32, device=w.device)
     states = torch.empty((B, T + 1), dtype=torch.int32, device=w.device)
     score = torch.empty(B, dtype=torch.float32, device=w.device)
-    ws = workspace(last_workspace_bytes(wt, cx, OP_SHORTEST_PATH), w.device)
+    item_status = _status(item_status, B, w.device)
+    nbytes = last_workspace_bytes(wt, cx, OP_SHORTEST_PATH)
+    if nbytes == 0:
+        raise LastError(6, "combination not supported")
+    ws = workspace(nbytes, w.device)
     _check(lib.last_shortest_path(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), _ptr(labels),
                                   _ptr(states), _ptr(score), _ptr(item_status), _ptr(ws),
                                   ws.numel(), _stream()))

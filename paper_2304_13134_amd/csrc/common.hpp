@@ -11,18 +11,26 @@ namespace last {
 constexpr int kWave = 64;
 #define LAST_NEG_INF (-__builtin_huge_valf())
 
-// Full n-gram context dependency (Section 3; Figure 1a is order 1).
+// Context dependency (Section 3): the full n-gram one of size 1 or 2 in closed form
+// (Figure 1a is size 1), or any deterministic automaton given as a next-state table.
 struct Ctx {
     int V;      // vocabulary size, labels 1..V, 0 = empty label
-    int order;  // context size n (1 or 2)
+    int order;  // context size n (1 or 2); 0 = next-state table
     int C;      // number of context states
     int V1;     // V + 1 labels per state
+    const int* nx;  // order 0: device table [C][V], nx[q*V + y-1] = state after label y
 };
 
 // destination context state of arc (q, y); the empty label keeps the state
 __device__ __forceinline__ int ctx_next(const Ctx& c, int q, int y)
 {
     if (y == 0) return q;
+    if (c.order == 0) {
+        // clamped: a table with an entry that names no state is reported by the check kernel of the
+        // call (kItemBadTable); meanwhile nothing may index outside the state vectors
+        const unsigned n = (unsigned)c.nx[(size_t)q * c.V + (y - 1)];
+        return (int)(n < (unsigned)c.C ? n : (unsigned)(c.C - 1));
+    }
     if (c.order == 1) return y;
     if (q == 0) return y;
     if (q <= c.V) return 1 + c.V + (q - 1) * c.V + (y - 1);
@@ -113,6 +121,6 @@ __device__ __forceinline__ float block_sum(float v, float* red)
 
 // per-item status codes written to item_status (see last.h)
 enum : int { kItemOk = 0, kItemBadLength = 1, kItemBadLabel = 2, kItemBadRefLength = 3,
-             kItemInfeasible = 4, kItemTimeout = 5, kItemRange = 6 };
+             kItemInfeasible = 4, kItemTimeout = 5, kItemRange = 6, kItemBadTable = 7 };
 
 }  // namespace last

@@ -7,6 +7,7 @@
 #include "common.hpp"
 #include "solo_kernels.hpp"
 #include "numerator_kernels.hpp"
+#include "table_kernels.hpp"
 #include "cluster_kernels.hpp"
 #include "cluster2_kernels.hpp"
 #include "cluster2v_kernels.hpp"
@@ -17,6 +18,8 @@
 #include <atomic>
 #include <cstdlib>
 #include <mutex>
+#include <set>
+#include <utility>
 #include <type_traits>
 
 using namespace last;
@@ -46,16 +49,24 @@ struct Carver {
 
 struct Shape {
     int B, T, V, V1, C, order;
+    const int* nx;       // order 0: device next-state table [C][V]
 };
 
 last_status_t check_common(const last_weights_t* wt, const last_context_t* cx, Shape* s)
 {
     if (!wt || !cx) return LAST_ERR_NULL;
-    if (cx->order != 1 && cx->order != 2) return LAST_ERR_CONTEXT;
+    if (cx->order < 0 || cx->order > 2) return LAST_ERR_CONTEXT;
     if (cx->vocab < 1) return LAST_ERR_CONTEXT;
     const long long V = cx->vocab;
-    const long long C = cx->order == 1 ? 1 + V : 1 + V + V * V;
-    if (C != cx->num_states || C > (1 << 24)) return LAST_ERR_CONTEXT;
+    long long C = cx->order == 1 ? 1 + V : 1 + V + V * V;
+    if (cx->order == 0) {
+        // any deterministic automaton, as a table; the weights stay dense
+        if (!cx->next_table) return LAST_ERR_NULL;
+        if (cx->num_states < 1) return LAST_ERR_CONTEXT;
+        if (wt && wt->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+        C = cx->num_states;
+    }
+    if (C != cx->num_states || C > (1 << 24) || C * (V + 1) > (1ll << 31) - 2) return LAST_ERR_CONTEXT;
     if (wt->B < 1 || wt->T < 0) return LAST_ERR_SHAPE;
     if (wt->B > 65535 || wt->T > (1 << 24)) return LAST_ERR_SHAPE;
     if (wt->kind == LAST_WEIGHTS_DENSE) {
@@ -72,10 +83,11 @@ last_status_t check_common(const last_weights_t* wt, const last_context_t* cx, S
     s->V1 = cx->vocab + 1;
     s->C = (int)C;
     s->order = cx->order;
+    s->nx = cx->order == 0 ? cx->next_table : nullptr;
     return LAST_OK;
 }
 
-Ctx make_ctx(const Shape& s) { return Ctx{s.V, s.order, s.C, s.V1}; }
+Ctx make_ctx(const Shape& s) { return Ctx{s.V, s.order, s.C, s.V1, s.nx}; }
 
 // thread layout of the one-workgroup-per-item forward kernels
 struct SoloLayout {
@@ -93,10 +105,23 @@ SoloLayout solo_layout(const Shape& s)
     l.lds_forward = (size_t)(2 * s.C + 2 * l.R * l.CPAD + 32) * sizeof(float);
     l.lds_viterbi = (size_t)(2 * s.C + 2 * l.R * l.CPAD + 64) * sizeof(float);
     l.lds_backward = (size_t)(2 * s.C + 32) * sizeof(float);
+    if (s.order == 0) {   // arcs by source state (table_kernels.hpp)
+        l.lds_forward = (size_t)s.C * 16 + 32 * sizeof(float);
+        l.lds_viterbi = (size_t)s.C * 12 + 64 * sizeof(float);
+    }
     return l;
 }
 
 constexpr size_t kMaxLds = 64 * 1024;
+
+// In table mode the workspace starts with the flag that the table check of the call sets.
+int* carve_table_flag(Carver& cv, const Shape& s) { return s.order == 0 ? cv.take<int>(64) : nullptr; }
+
+void launch_table_check(const Shape& s, int* flag, hipStream_t st)
+{
+    hipLaunchKernelGGL(table_clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(table_check_kernel, dim3(64), dim3(256), 0, st, s.nx, s.C, s.V, flag);
+}
 
 struct PosteriorWs {
     float* alpha;
@@ -134,12 +159,18 @@ struct NumWs {
     double* bk;
     double* N;
     int* status;
+    int* ctxs;
+    int* link;
+    double* lz;          // locally normalised only
 };
 
-NumWs carve_num(Carver& cv, const Shape& s, int Umax)
+NumWs carve_num(Carver& cv, const Shape& s, int Umax, bool local)
 {
     NumWs p;
     const size_t U1 = (size_t)Umax + 1;
+    p.ctxs = cv.take<int>((size_t)s.B * U1);
+    p.link = cv.take<int>((size_t)s.B * U1 * 2);
+    p.lz = local ? cv.take<double>((size_t)s.B * (s.T > 0 ? s.T : 1) * U1) : nullptr;
     p.wi = cv.take<float2>((size_t)s.B * (s.T > 0 ? s.T : 1) * U1);
     p.a = cv.take<double>((size_t)s.B * (s.T + 1) * U1);
     p.bk = cv.take<double>((size_t)s.B * (s.T + 1) * U1);
@@ -291,6 +322,69 @@ last_status_t hip_status()
     return e == hipSuccess ? LAST_OK : LAST_ERR_HIP;
 }
 
+template <typename F>
+void dispatch_group(int V1, F&& f)
+{
+    if (V1 <= 4) f(std::integral_constant<int, 4>());
+    else if (V1 <= 8) f(std::integral_constant<int, 8>());
+    else if (V1 <= 16) f(std::integral_constant<int, 16>());
+    else if (V1 <= 48) f(std::integral_constant<int, 32>());
+    else f(std::integral_constant<int, 64>());
+}
+
+constexpr size_t kBigLds = 160 * 1024;
+
+// A kernel that wants more than 64 KiB of LDS has to be told so once on every device it runs on.
+last_status_t allow_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({dev, kernel})) return LAST_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    done.insert({dev, kernel});
+    return LAST_OK;
+}
+
+// ---- context dependency given as a table: one workgroup per item, arcs by source state ----
+last_status_t launch_table_forward(const Shape& s, const SoloLayout& l, const float* w, const int* lengths,
+                                   float* alpha, double* offs, double* D, float* dist, int* item_status,
+                                   const int* flag, hipStream_t st)
+{
+    if (l.lds_forward > kBigLds) return LAST_ERR_UNSUPPORTED;
+    const Ctx c = make_ctx(s);
+    last_status_t rc = LAST_OK;
+    dispatch_group(s.V1, [&](auto G) {
+        auto k = table_forward_log<decltype(G)::value>;
+        if (l.lds_forward > kMaxLds) rc = allow_lds((const void*)k, kBigLds);
+        if (rc == LAST_OK)
+            hipLaunchKernelGGL(k, dim3(s.B), dim3(1024), l.lds_forward, st, w, lengths, c, s.T, alpha, offs,
+                               D, dist, item_status, flag);
+    });
+    return rc;
+}
+
+last_status_t launch_table_viterbi(const Shape& s, const SoloLayout& l, const float* w, const int* lengths,
+                                   int* bp, int* final_state, float* score, int* item_status,
+                                   const int* flag, hipStream_t st)
+{
+    if (l.lds_viterbi > kBigLds) return LAST_ERR_UNSUPPORTED;
+    const Ctx c = make_ctx(s);
+    last_status_t rc = LAST_OK;
+    dispatch_group(s.V1, [&](auto G) {
+        auto k = table_viterbi<decltype(G)::value>;
+        if (l.lds_viterbi > kMaxLds) rc = allow_lds((const void*)k, kBigLds);
+        if (rc == LAST_OK)
+            hipLaunchKernelGGL(k, dim3(s.B), dim3(1024), l.lds_viterbi, st, w, lengths, c, s.T, bp,
+                               final_state, score, item_status, flag);
+    });
+    return rc;
+}
+
 // geometry of the fused trigram path (see fused_kernels.hpp)
 constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel also has a little static LDS
 struct FusedPlan {
@@ -371,17 +465,15 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
                                    const last_weights_t* wt, const int* lengths, float* dist,
                                    int* item_status, bool keep_alpha, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
+    {
         const void* kernels[9] = {
             (const void*)fused_forward_kernel<1>, (const void*)fused_forward_kernel<3>, (const void*)fused_forward_kernel<5>,
             (const void*)fused_backward_kernel<1>, (const void*)fused_backward_kernel<3>, (const void*)fused_backward_kernel<5>,
             (const void*)fused_dw_kernel<1>, (const void*)fused_dw_kernel<3>, (const void*)fused_dw_kernel<5>};
         for (const void* k : kernels) {
-            const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedMaxLds);
-            if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+            const last_status_t rc = allow_lds(k, kFusedMaxLds);
+            if (rc != LAST_OK) return rc;
         }
-        attr_set = true;
     }
     hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, f.xb, f.xwords);
     const int npack = std::max(kFuMaxNT * kFuMaxKS * 64, (wt->hidden / 16) * 3 * 64);
@@ -503,21 +595,12 @@ last_status_t check_ws(void* ws, size_t have, size_t need)
     return LAST_OK;
 }
 
-template <typename F>
-void dispatch_group(int V1, F&& f)
-{
-    if (V1 <= 4) f(std::integral_constant<int, 4>());
-    else if (V1 <= 8) f(std::integral_constant<int, 8>());
-    else if (V1 <= 16) f(std::integral_constant<int, 16>());
-    else if (V1 <= 48) f(std::integral_constant<int, 32>());
-    else f(std::integral_constant<int, 64>());
-}
 
 }  // namespace
 
 extern "C" {
 
-int32_t last_version(void) { return 2; }
+int32_t last_version(void) { return 3; }
 
 last_status_t last_set_option(int32_t option, int32_t value)
 {
@@ -579,6 +662,7 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
         else return 0;
         return cv.used;
     }
+    carve_table_flag(cv, s);
     const ClusterPlan plan = cluster_plan(s, weights->kind);
     const ViterbiPlan vplan = viterbi_plan(s, weights->kind);
     switch (op) {
@@ -593,7 +677,11 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
         break;
     case LAST_OP_INTERSECT_REFERENCE:
         if (Umax < 0) return 0;
-        carve_num(cv, s, Umax);
+        carve_num(cv, s, Umax, false);
+        break;
+    case LAST_OP_LOCAL_LOG_LIKELIHOOD:
+        if (Umax < 0) return 0;
+        carve_num(cv, s, Umax, true);
         break;
     case LAST_OP_SHORTEST_PATH:
         carve_path(cv, s, vplan.ok ? vplan.xwords : 0);
@@ -627,6 +715,16 @@ last_status_t last_shortest_distance(const last_weights_t* weights, const int32_
     rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_SHORTEST_DISTANCE, 0));
     if (rc != LAST_OK) return rc;
     const SoloLayout l = solo_layout(s);
+    if (s.order == 0) {
+        if ((semiring == LAST_LOG ? l.lds_forward : l.lds_viterbi) > kBigLds) return LAST_ERR_UNSUPPORTED;
+        Carver cv(ws);
+        int* flag = carve_table_flag(cv, s);
+        launch_table_check(s, flag, st);
+        rc = semiring == LAST_LOG
+                 ? launch_table_forward(s, l, weights->w, lengths, nullptr, nullptr, nullptr, dist, item_status, flag, st)
+                 : launch_table_viterbi(s, l, weights->w, lengths, nullptr, nullptr, dist, item_status, flag, st);
+        return rc != LAST_OK ? rc : hip_status();
+    }
     const Ctx c = make_ctx(s);
     const ClusterPlan plan = cluster_plan(s, weights->kind);
     if (semiring == LAST_LOG && plan.ok) {
@@ -689,30 +787,41 @@ last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* 
         return hip_status();
     }
     const SoloLayout l = solo_layout(s);
-    if (l.lds_forward > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    if (l.lds_forward > (s.order == 0 ? kBigLds : kMaxLds)) return LAST_ERR_UNSUPPORTED;
     const Ctx c = make_ctx(s);
     Carver cv(ws);
+    int* flag = carve_table_flag(cv, s);
     PosteriorWs p = carve_posteriors(cv, s);
-    hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
-                       weights->w, lengths, c, s.T, l.CPAD, l.R, p.alpha, p.offs, p.D, dist,
-                       item_status);
+    if (s.order == 0) {
+        launch_table_check(s, flag, st);
+        rc = launch_table_forward(s, l, weights->w, lengths, p.alpha, p.offs, p.D, dist, item_status, flag, st);
+        if (rc != LAST_OK) return rc;
+    } else {
+        hipLaunchKernelGGL(solo_forward_log, dim3(s.B), dim3(1024), l.lds_forward, st,
+                           weights->w, lengths, c, s.T, l.CPAD, l.R, p.alpha, p.offs, p.D, dist,
+                           item_status);
+    }
     if (s.T > 0) {
         dispatch_group(s.V1, [&](auto G) {
-            hipLaunchKernelGGL(HIP_KERNEL_NAME(solo_backward_log<decltype(G)::value>), dim3(s.B),
-                               dim3(1024), l.lds_backward, st, weights->w, lengths, c, s.T,
-                               (const float*)p.alpha, (const double*)p.offs, (const double*)p.D,
-                               out->dw, out->scale, out->accumulate);
+            auto k = solo_backward_log<decltype(G)::value>;
+            if (l.lds_backward > kMaxLds) rc = allow_lds((const void*)k, kBigLds);
+            if (rc == LAST_OK)
+                hipLaunchKernelGGL(k, dim3(s.B), dim3(1024), l.lds_backward, st, weights->w, lengths, c, s.T,
+                                   (const float*)p.alpha, (const double*)p.offs, (const double*)p.D,
+                                   out->dw, out->scale, out->accumulate);
         });
+        if (rc != LAST_OK) return rc;
     }
     return hip_status();
 }
 
-last_status_t last_intersect_reference(const last_weights_t* weights, const int32_t* lengths,
-                                       const last_context_t* context,
-                                       const int32_t* refs, const int32_t* ref_lengths,
-                                       int32_t Umax, float* numerator,
-                                       const last_grads_t* out, int32_t* item_status,
-                                       void* ws, size_t ws_bytes, void* hip_stream)
+// Shared by the globally normalised numerator and the locally normalised log-likelihood.
+static last_status_t intersect_impl(const last_weights_t* weights, const int32_t* lengths,
+                                    const last_context_t* context,
+                                    const int32_t* refs, const int32_t* ref_lengths,
+                                    int32_t Umax, float* numerator,
+                                    const last_grads_t* out, int32_t* item_status,
+                                    void* ws, size_t ws_bytes, void* hip_stream, bool local)
 {
     Shape s;
     last_status_t rc = check_common(weights, context, &s);
@@ -724,34 +833,76 @@ last_status_t last_intersect_reference(const last_weights_t* weights, const int3
     if (out && !out->dw) return LAST_ERR_NULL;
     const size_t lds = (size_t)2 * (Umax + 2) * sizeof(double);
     if (lds > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    constexpr int kLocalWaves = 4;
+    const size_t lds_scatter = (size_t)kLocalWaves * s.V1 * sizeof(float);
+    if (local && lds_scatter > kMaxLds) return LAST_ERR_UNSUPPORTED;
     rc = check_ws(ws, ws_bytes,
-                  last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax));
+                  last_workspace_bytes(weights, context,
+                                       local ? LAST_OP_LOCAL_LOG_LIKELIHOOD : LAST_OP_INTERSECT_REFERENCE, Umax));
     if (rc != LAST_OK) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
     const Ctx c = make_ctx(s);
     Carver cv(ws);
-    NumWs p = carve_num(cv, s, Umax);
+    int* flag = carve_table_flag(cv, s);
+    NumWs p = carve_num(cv, s, Umax, local);
     const int U1 = Umax + 1;
+    if (flag) launch_table_check(s, flag, st);
     hipLaunchKernelGGL(num_check_kernel, dim3(s.B), dim3(256), 0, st, lengths, refs, ref_lengths,
-                       s.T, s.V, Umax, p.status);
+                       c, s.T, Umax, p.status, p.ctxs, p.link, (const int*)flag);
     const dim3 pgrid((U1 + 127) / 128, s.T > 0 ? s.T : 1, s.B);
-    if (s.T > 0)
-        hipLaunchKernelGGL(num_gather_kernel, pgrid, dim3(128), 0, st, weights->w, lengths, refs,
-                           ref_lengths, (const int*)p.status, c, s.T, Umax, p.wi);
+    const dim3 wgrid((U1 + kLocalWaves - 1) / kLocalWaves, s.T > 0 ? s.T : 1, s.B);   // a wavefront per cell
+    if (s.T > 0) {
+        if (local)
+            hipLaunchKernelGGL(num_gather_local_kernel, wgrid, dim3(kLocalWaves * kWave), 0, st, weights->w,
+                               lengths, refs, ref_lengths, (const int*)p.status, (const int*)p.ctxs, c,
+                               s.T, Umax, p.wi, p.lz);
+        else
+            hipLaunchKernelGGL(num_gather_kernel, pgrid, dim3(128), 0, st, weights->w, lengths, refs,
+                               ref_lengths, (const int*)p.status, (const int*)p.ctxs, c, s.T, Umax, p.wi);
+    }
     hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
-                       (const float2*)p.wi, lengths, ref_lengths, (const int*)p.status, s.T, Umax,
-                       p.a, p.bk, p.N, numerator, item_status);
+                       (const float2*)p.wi, (const double*)p.lz, lengths, ref_lengths,
+                       (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
     if (out && s.T > 0) {
         if (!out->accumulate) {
             const size_t n = (size_t)s.B * s.T * s.C * s.V1;
             hipLaunchKernelGGL(zero_fill_kernel, dim3(2048), dim3(256), 0, st, out->dw, n);
         }
-        hipLaunchKernelGGL(num_scatter_kernel, pgrid, dim3(128), 0, st, (const float2*)p.wi,
-                           lengths, refs, ref_lengths, (const int*)p.status, c, s.T, Umax,
-                           (const double*)p.a, (const double*)p.bk, (const double*)p.N, out->dw,
-                           out->scale);
+        if (local)
+            hipLaunchKernelGGL(num_scatter_local_kernel, wgrid, dim3(kLocalWaves * kWave), lds_scatter, st,
+                               weights->w, (const float2*)p.wi, (const double*)p.lz, lengths, refs,
+                               ref_lengths, (const int*)p.status, (const int*)p.ctxs, (const int*)p.link,
+                               c, s.T, Umax, (const double*)p.a, (const double*)p.bk, (const double*)p.N,
+                               out->dw, out->scale, out->accumulate);
+        else
+            hipLaunchKernelGGL(num_scatter_kernel, pgrid, dim3(128), 0, st, (const float2*)p.wi,
+                               lengths, refs, ref_lengths, (const int*)p.status, (const int*)p.ctxs, c,
+                               s.T, Umax, (const double*)p.a, (const double*)p.bk, (const double*)p.N,
+                               out->dw, out->scale);
     }
     return hip_status();
+}
+
+last_status_t last_intersect_reference(const last_weights_t* weights, const int32_t* lengths,
+                                       const last_context_t* context,
+                                       const int32_t* refs, const int32_t* ref_lengths,
+                                       int32_t Umax, float* numerator,
+                                       const last_grads_t* out, int32_t* item_status,
+                                       void* ws, size_t ws_bytes, void* hip_stream)
+{
+    return intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, numerator, out, item_status,
+                          ws, ws_bytes, hip_stream, false);
+}
+
+last_status_t last_local_log_likelihood(const last_weights_t* weights, const int32_t* lengths,
+                                        const last_context_t* context,
+                                        const int32_t* refs, const int32_t* ref_lengths,
+                                        int32_t Umax, float* loglik,
+                                        const last_grads_t* out, int32_t* item_status,
+                                        void* ws, size_t ws_bytes, void* hip_stream)
+{
+    return intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, loglik, out, item_status,
+                          ws, ws_bytes, hip_stream, true);
 }
 
 last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* lengths,
@@ -770,11 +921,16 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
     hipStream_t st = (hipStream_t)hip_stream;
     const SoloLayout l = solo_layout(s);
     const ViterbiPlan vp = viterbi_plan(s, weights->kind);
-    if (!vp.ok && l.lds_viterbi > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    if (!vp.ok && l.lds_viterbi > (s.order == 0 ? kBigLds : kMaxLds)) return LAST_ERR_UNSUPPORTED;
     const Ctx c = make_ctx(s);
     Carver cv(ws);
+    int* flag = carve_table_flag(cv, s);
     PathWs p = carve_path(cv, s, vp.ok ? vp.xwords : 0);
-    if (vp.ok)
+    if (s.order == 0) {
+        launch_table_check(s, flag, st);
+        rc = launch_table_viterbi(s, l, weights->w, lengths, p.bp, p.final_state, score, item_status, flag, st);
+        if (rc != LAST_OK) return rc;
+    } else if (vp.ok)
         launch_cluster_viterbi(s, vp, p.xv, weights->w, lengths, p.bp, p.final_state, score, item_status, st);
     else if (!launch_bigram_viterbi(s, weights->w, lengths, p.bp, p.final_state, score, item_status, st))
         hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,

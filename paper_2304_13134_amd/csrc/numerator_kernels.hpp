@@ -11,6 +11,11 @@
 //                 one the backward weights, frame-serial, state-parallel;
 //   3. scatter  : arc marginals exp(a + w + b' - N) are added onto the arcs of
 //                 the complete lattice they ride on.
+// The locally normalised variant (Section 2.1: a model like RNN-T is the same
+// intersection followed by a shortest distance, with the arcs leaving each state
+// normalised; Table 1, first row) adds to the gather the log-sum-exp lz of the
+// V+1 arcs leaving (t, ctx(u)), subtracts it in the recursion, and its scatter
+// writes d/dw = marginals - (occupancy of the state) * softmax(row), row by row.
 // Grid values are kept in float64 (they reach several thousand and feed an
 // exponent that must be good to 1e-6); the transcendental part of each
 // log-add-exp has an O(1) argument and is evaluated in float32.
@@ -29,38 +34,76 @@ __device__ __forceinline__ int ref_context(const Ctx& c, const int* __restrict__
 
 __device__ __forceinline__ int clamp_label(int y, int V) { return y < 1 ? 1 : (y > V ? V : y); }
 
-// status [B]: 0 ok, or the item_status code of the first problem found
+// status [B]: 0 ok, or the item_status code of the first problem found.
+// ctxs [B][U1]: context state after the first u reference labels (-1 past U).
+// link [B][U1][2]: [0] = the next u' > u with the same context (-1: none), [1] = 1 when no
+// u' < u has the same context (u heads its chain).  Cells of one chain ride on the same rows
+// of the complete lattice.
 __global__ void num_check_kernel(const int* __restrict__ len, const int* __restrict__ refs,
-                                 const int* __restrict__ ulen, int T, int V, int Umax,
-                                 int* __restrict__ status)
+                                 const int* __restrict__ ulen, Ctx c, int T, int Umax,
+                                 int* __restrict__ status, int* __restrict__ ctxs,
+                                 int* __restrict__ link, const int* __restrict__ badtab)
 {
     __shared__ int bad;
     const int b = blockIdx.x;
+    const int U1 = Umax + 1;
     if (threadIdx.x == 0) bad = 0;
     __syncthreads();
     const int L = len[b], U = ulen[b];
     int code = kItemOk;
-    if (L < 0 || L > T) code = kItemBadLength;
+    if (badtab && badtab[0]) code = kItemBadTable;
+    else if (L < 0 || L > T) code = kItemBadLength;
     else if (U < 0 || U > Umax) code = kItemBadRefLength;
     else {
         for (int u = threadIdx.x; u < U; u += blockDim.x) {
             const int y = refs[(size_t)b * Umax + u];
-            if (y < 1 || y > V) atomicOr(&bad, 1);
+            if (y < 1 || y > c.V) atomicOr(&bad, 1);
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        if (code == kItemOk && bad) code = kItemBadLabel;
-        if (code == kItemOk && U > L) code = kItemInfeasible;
-        status[b] = code;
+    if (code == kItemOk && bad) code = kItemBadLabel;
+    if (code == kItemOk && U > L) code = kItemInfeasible;
+    if (threadIdx.x == 0) status[b] = code;
+    int* cx = ctxs + (size_t)b * U1;
+    if (code != kItemOk && code != kItemInfeasible) {
+        for (int u = threadIdx.x; u < U1; u += blockDim.x) cx[u] = -1;
+        return;
+    }
+    const int* r = refs + (size_t)b * Umax;
+    if (c.order == 0) {
+        // a general automaton has to be walked label by label
+        if (threadIdx.x == 0) {
+            int q = 0;
+            cx[0] = 0;
+            for (int u = 1; u <= U; ++u) { q = ctx_next(c, q, r[u - 1]); cx[u] = q; }
+        }
+        for (int u = U + 1 + threadIdx.x; u < U1; u += blockDim.x) cx[u] = -1;
+    } else {
+        for (int u = threadIdx.x; u < U1; u += blockDim.x) cx[u] = u <= U ? ref_context(c, r, u) : -1;
+    }
+    __syncthreads();
+    int* lk = link + (size_t)b * U1 * 2;
+    for (int u = threadIdx.x; u < U1; u += blockDim.x) {
+        int nxt = -1, head = 1;
+        if (u <= U) {
+            const int q = cx[u];
+            for (int v = u + 1; v <= U; ++v)
+                if (cx[v] == q) { nxt = v; break; }
+            for (int v = u - 1; v >= 0; --v)
+                if (cx[v] == q) { head = 0; break; }
+        } else {
+            head = 0;
+        }
+        lk[2 * u] = nxt;
+        lk[2 * u + 1] = head;
     }
 }
 
 // wi[b][t][u][0] = w[b][t][ctx(u)][0]; wi[b][t][u][1] = w[b][t][ctx(u)][ref[u]] (u < U)
 __global__ void num_gather_kernel(const float* __restrict__ w, const int* __restrict__ len,
                                   const int* __restrict__ refs, const int* __restrict__ ulen,
-                                  const int* __restrict__ status, Ctx c, int T, int Umax,
-                                  float2* __restrict__ wi)
+                                  const int* __restrict__ status, const int* __restrict__ ctxs,
+                                  Ctx c, int T, int Umax, float2* __restrict__ wi)
 {
     const int U1 = Umax + 1;
     const int b = blockIdx.z, t = blockIdx.y;
@@ -69,12 +112,52 @@ __global__ void num_gather_kernel(const float* __restrict__ w, const int* __rest
     const int L = len[b], U = ulen[b];
     if (t >= L || u > U) return;
     const int* r = refs + (size_t)b * Umax;
-    const int q = ref_context(c, r, u);
+    const int q = ctxs[(size_t)b * U1 + u];
     const float* row = w + (((size_t)b * T + t) * c.C + q) * c.V1;
     float2 o;
     o.x = row[0];
     o.y = (u < U) ? row[r[u]] : LAST_NEG_INF;
     wi[((size_t)b * T + t) * U1 + u] = o;
+}
+
+// Locally normalised variant of the gather: one wavefront per cell (t, u) also takes
+// lz[b][t][u] = log sum_y exp w[b][t][ctx(u)][y].  Cells outside the cone that paths from (0,0)
+// to (len, U) can visit get zeros without touching the weights (their forward or backward weight
+// is -inf, whatever the arc weights).
+__global__ __launch_bounds__(256) void num_gather_local_kernel(
+    const float* __restrict__ w, const int* __restrict__ len, const int* __restrict__ refs,
+    const int* __restrict__ ulen, const int* __restrict__ status, const int* __restrict__ ctxs,
+    Ctx c, int T, int Umax, float2* __restrict__ wi, double* __restrict__ lz)
+{
+    const int U1 = Umax + 1;
+    const int b = blockIdx.z, t = blockIdx.y;
+    const int u = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    if (u >= U1 || status[b] != kItemOk) return;
+    const int L = len[b], U = ulen[b];
+    if (t >= L || u > U) return;
+    const size_t cell = ((size_t)b * T + t) * U1 + u;
+    if (u > t || U - u > L - t) {
+        if (lane == 0) { wi[cell] = make_float2(0.f, 0.f); lz[cell] = 0.0; }
+        return;
+    }
+    const int* r = refs + (size_t)b * Umax;
+    const int q = ctxs[(size_t)b * U1 + u];
+    const float* row = w + (((size_t)b * T + t) * c.C + q) * c.V1;
+    float m = LAST_NEG_INF;
+    for (int y = lane; y < c.V1; y += kWave) m = fmaxf(m, row[y]);
+    m = wave_max(m);
+    float s = 0.f;
+    if (m != LAST_NEG_INF)
+        for (int y = lane; y < c.V1; y += kWave) s += expf(row[y] - m);
+    s = wave_sum(s);
+    if (lane == 0) {
+        float2 o;
+        o.x = row[0];
+        o.y = (u < U) ? row[r[u]] : LAST_NEG_INF;
+        wi[cell] = o;
+        lz[cell] = (m == LAST_NEG_INF) ? (double)LAST_NEG_INF : (double)m + log((double)s);
+    }
 }
 
 __device__ __forceinline__ double log_add(double x, double y)
@@ -89,8 +172,8 @@ __device__ __forceinline__ double log_add(double x, double y)
 // grid (B, 2): blockIdx.y = 0 forward weights a[b][t][u], = 1 backward weights bk.
 // Both arrays are [B][T+1][U1] float64; cells outside the reachable cone hold -inf.
 __global__ __launch_bounds__(256) void num_recursion_kernel(
-    const float2* __restrict__ wi, const int* __restrict__ len, const int* __restrict__ ulen,
-    const int* __restrict__ status, int T, int Umax,
+    const float2* __restrict__ wi, const double* __restrict__ lz, const int* __restrict__ len,
+    const int* __restrict__ ulen, const int* __restrict__ status, int T, int Umax,
     double* __restrict__ a, double* __restrict__ bk, double* __restrict__ Nws,
     float* __restrict__ numerator, int* __restrict__ item_status)
 {
@@ -113,6 +196,7 @@ __global__ __launch_bounds__(256) void num_recursion_kernel(
     double* buf1 = sm + U1 + 1;               // one pad cell on the right for bk[u+1]
     const double NI = (double)LAST_NEG_INF;
     const float2* wb = wi + (size_t)b * T * U1;
+    const double* zb = lz ? lz + (size_t)b * T * U1 : nullptr;   // locally normalised: w - lz
     if (fwd) {
         double* A = a + (size_t)b * (T + 1) * U1;
         for (int u = tid; u <= U; u += blockDim.x) {
@@ -125,9 +209,10 @@ __global__ __launch_bounds__(256) void num_recursion_kernel(
         double* nxt = buf1;
         for (int t = 0; t < L; ++t) {
             const float2* wt = wb + (size_t)t * U1;
+            const double* zt = zb ? zb + (size_t)t * U1 : nullptr;
             for (int u = tid; u <= U; u += blockDim.x) {
-                double v = cur[u] + (double)wt[u].x;
-                if (u >= 1) v = log_add(v, cur[u - 1] + (double)wt[u - 1].y);
+                double v = cur[u] + ((double)wt[u].x - (zt ? zt[u] : 0.0));
+                if (u >= 1) v = log_add(v, cur[u - 1] + ((double)wt[u - 1].y - (zt ? zt[u - 1] : 0.0)));
                 nxt[u] = v;
                 A[(size_t)(t + 1) * U1 + u] = v;
             }
@@ -151,10 +236,12 @@ __global__ __launch_bounds__(256) void num_recursion_kernel(
         double* nxt = buf1;
         for (int t = L - 1; t >= 0; --t) {
             const float2* wt = wb + (size_t)t * U1;
+            const double* zt = zb ? zb + (size_t)t * U1 : nullptr;
             for (int u = tid; u <= U; u += blockDim.x) {
                 const float2 ww = wt[u];
-                double v = (double)ww.x + cur[u];
-                if (u < U) v = log_add(v, (double)ww.y + cur[u + 1]);
+                const double z = zt ? zt[u] : 0.0;
+                double v = ((double)ww.x - z) + cur[u];
+                if (u < U) v = log_add(v, ((double)ww.y - z) + cur[u + 1]);
                 nxt[u] = v;
                 Bk[(size_t)t * U1 + u] = v;
             }
@@ -169,7 +256,8 @@ __global__ __launch_bounds__(256) void num_recursion_kernel(
 // arc of the complete lattice, hence atomic adds.
 __global__ void num_scatter_kernel(const float2* __restrict__ wi, const int* __restrict__ len,
                                    const int* __restrict__ refs, const int* __restrict__ ulen,
-                                   const int* __restrict__ status, Ctx c, int T, int Umax,
+                                   const int* __restrict__ status, const int* __restrict__ ctxs,
+                                   Ctx c, int T, int Umax,
                                    const double* __restrict__ a, const double* __restrict__ bk,
                                    const double* __restrict__ Nws, float* __restrict__ dw,
                                    float scale)
@@ -184,7 +272,7 @@ __global__ void num_scatter_kernel(const float2* __restrict__ wi, const int* __r
     const double av = a[((size_t)b * (T + 1) + t) * U1 + u];
     if (av == (double)LAST_NEG_INF || N == (double)LAST_NEG_INF) return;
     const int* r = refs + (size_t)b * Umax;
-    const int q = ref_context(c, r, u);
+    const int q = ctxs[(size_t)b * U1 + u];
     const float2 ww = wi[((size_t)b * T + t) * U1 + u];
     float* row = dw + (((size_t)b * T + t) * c.C + q) * c.V1;
     const double* bn = bk + ((size_t)b * (T + 1) + t + 1) * U1;
@@ -193,6 +281,72 @@ __global__ void num_scatter_kernel(const float2* __restrict__ wi, const int* __r
     if (u < U) {
         const double e1 = av + (double)ww.y + bn[u + 1] - N;
         if (e1 > -100.0) atomicAdd(row + r[u], scale * __expf((float)e1));
+    }
+}
+
+// Gradient of the locally normalised log-likelihood (Section 2.1) with respect to the weights,
+// dw[b][t][q][y] (+)= scale * ( [marginals of the intersected lattice riding on arc (t,q,y)]
+//                              - [their sum over the arcs leaving (t,q)] * softmax(w[b][t][q])[y] ).
+// One wavefront per frame and chain of cells with the same context q (see num_check_kernel):
+// it alone writes row (t,q), so no atomics are needed and the result does not depend on timing.
+// LDS: blockDim.x/64 arrays of V1 floats (the label marginals of the chain).
+__global__ __launch_bounds__(256) void num_scatter_local_kernel(
+    const float* __restrict__ w, const float2* __restrict__ wi, const double* __restrict__ lz,
+    const int* __restrict__ len, const int* __restrict__ refs, const int* __restrict__ ulen,
+    const int* __restrict__ status, const int* __restrict__ ctxs, const int* __restrict__ link,
+    Ctx c, int T, int Umax, const double* __restrict__ a, const double* __restrict__ bk,
+    const double* __restrict__ Nws, float* __restrict__ dw, float scale, int accumulate)
+{
+    extern __shared__ float nsl_lab[];
+    const int U1 = Umax + 1;
+    const int b = blockIdx.z, t = blockIdx.y;
+    const int wv = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    const int u = blockIdx.x * (blockDim.x / kWave) + wv;
+    if (u >= U1 || status[b] != kItemOk) return;
+    const int L = len[b], U = ulen[b];
+    if (t >= L || u > U) return;
+    const int* lk = link + (size_t)b * U1 * 2;
+    if (!lk[2 * u + 1]) return;
+    const double N = Nws[b];
+    if (N == (double)LAST_NEG_INF) return;
+    float* lab = nsl_lab + (size_t)wv * c.V1;
+    const int* r = refs + (size_t)b * Umax;
+    const double* at = a + ((size_t)b * (T + 1) + t) * U1;
+    const double* bn = bk + ((size_t)b * (T + 1) + t + 1) * U1;
+    const size_t cell0 = ((size_t)b * T + t) * U1;
+    // first walk: is any cell of the chain on a path at all?  (cells outside the cone of paths
+    // carry no log-sum-exp; every cell inside it carries the same one, that of row (t,q))
+    int vin = -1;
+    for (int v = u; v >= 0; v = lk[2 * v])
+        if (vin < 0 && at[v] != (double)LAST_NEG_INF && v <= t && U - v <= L - t) vin = v;
+    if (vin < 0) return;
+    const double z = lz[cell0 + vin];
+    for (int y = lane; y < c.V1; y += kWave) lab[y] = 0.f;
+    float occ = 0.f, pbs = 0.f;
+    for (int v = u; v >= 0; v = lk[2 * v]) {
+        const double av = at[v];
+        if (av == (double)LAST_NEG_INF) continue;
+        const float2 ww = wi[cell0 + v];
+        const double e0 = av + ((double)ww.x - z) + bn[v] - N;
+        const float p0 = e0 > -100.0 ? __expf((float)e0) : 0.f;
+        float p1 = 0.f;
+        if (v < U) {
+            const double e1 = av + ((double)ww.y - z) + bn[v + 1] - N;
+            if (e1 > -100.0) p1 = __expf((float)e1);
+            if (lane == 0) lab[r[v]] += p1;    // one lane, chain order: deterministic
+        }
+        occ += p0 + p1;
+        pbs += p0;
+    }
+    const int q = ctxs[(size_t)b * U1 + u];
+    const size_t ro = (((size_t)b * T + t) * c.C + q) * c.V1;
+    const float* row = w + ro;
+    float* grow = dw + ro;
+    __builtin_amdgcn_wave_barrier();
+    for (int y = lane; y < c.V1; y += kWave) {
+        float g = lab[y] - occ * __expf((float)((double)row[y] - z));
+        if (y == 0) g += pbs;
+        if (accumulate) grow[y] += scale * g; else grow[y] = scale * g;
     }
 }
 

@@ -411,7 +411,7 @@ __global__ void backtrace_kernel(const int* __restrict__ bp, const int* __restri
 {
     const int b = blockIdx.x, tid = threadIdx.x;
     int L = len[b];
-    if (L < 0 || L > T) L = -1;
+    if (L < 0 || L > T || final_state[b] < 0) L = -1;   // no path was found for this item: all -1
     for (int t = tid; t < T; t += blockDim.x)
         if (t >= L) labels[(size_t)b * T + t] = -1;
     for (int t = tid; t <= T; t += blockDim.x)

@@ -123,3 +123,30 @@ def test_shared_embedding_plan_is_checked_on_the_host(lib):
                                    dummy, 1 << 30, None) == 1
     assert lib.last_arc_posteriors(ctypes.byref(se), dummy, ctypes.byref(cx), dummy, ctypes.byref(g), None,
                                    dummy, 4096, None) == 5
+
+
+def test_table_context_is_checked_on_the_host(lib):
+    vp = ctypes.c_void_p
+    dummy = vp(0x2000)
+    wt = _wt()
+    tab = lb.LastContext(3, 0, 40, 0x8000)                 # 40 states, any automaton
+    for op in (lb.OP_SHORTEST_DISTANCE, lb.OP_ARC_POSTERIORS, lb.OP_SHORTEST_PATH):
+        assert lb.last_workspace_bytes(wt, tab, op) > 0
+    assert lb.last_workspace_bytes(wt, tab, lb.OP_LOCAL_LOG_LIKELIHOOD, 5) > \
+        lb.last_workspace_bytes(wt, tab, lb.OP_INTERSECT_REFERENCE, 5) > 0
+    assert lb.last_kernel_variant(wt, tab, lb.OP_ARC_POSTERIORS) == 0
+    # a table context without a table, without states, or with on-the-fly weights
+    assert lib.last_shortest_distance(ctypes.byref(wt), dummy, ctypes.byref(lb.LastContext(3, 0, 40, None)), 0,
+                                      dummy, None, dummy, 1 << 20, None) == 1
+    assert lib.last_shortest_distance(ctypes.byref(wt), dummy, ctypes.byref(lb.LastContext(3, 0, 0, 0x8000)), 0,
+                                      dummy, None, dummy, 1 << 20, None) == 3
+    assert lb.last_workspace_bytes(_se(), lb.LastContext(64, 0, 4161, 0x8000), lb.OP_ARC_POSTERIORS) == 0
+    # more states than the LDS of a compute unit holds
+    big = lb.LastContext(3, 0, 20000, 0x8000)
+    assert lib.last_shortest_distance(ctypes.byref(wt), dummy, ctypes.byref(big), 0, dummy, None, dummy,
+                                      1 << 30, None) == 6
+    g = lb.LastGrads(0x3000, None, None, None, 0, 1.0)
+    assert lib.last_arc_posteriors(ctypes.byref(wt), dummy, ctypes.byref(big), dummy, ctypes.byref(g), None,
+                                   dummy, 1 << 30, None) == 6
+    assert lib.last_local_log_likelihood(ctypes.byref(wt), dummy, ctypes.byref(tab), dummy, dummy, -1, dummy,
+                                         None, None, dummy, 1 << 20, None) == 2
