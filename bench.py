@@ -10,8 +10,11 @@ resident in HBM.  value = arcs/s with arcs = sum_b len[b]*C*(V+1).
 
 Also timed (reported under "extra", not part of `value`): the full globally
 normalised loss (forward+backward plus the numerator on the intersected
-lattice and its scatter), the tropical shortest path with backpointers, and
-the shortest distance alone.
+lattice and its scatter), the tropical shortest path with backpointers, the
+shortest distance alone, the locally normalised log-likelihood, the trigram
+lattice with on-the-fly weights, and -- under "ceilings" -- a plain read sweep
+and a plain copy of the same weight tensor, the streaming yardstick of this
+GPU that the forward+backward time is held against.
 
 Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is
 single-GPU by design.
@@ -29,10 +32,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 BYTES_PER_ARC = 12.0           # forward reads w (4), backward reads w (4) and writes gamma (4)
 
-# HBM traffic per forward+backward launch measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
-# profiles/cluster2_kernel_B16_T500_V256.md: 4.344 GB fetched + 2.260 GB written.
-MEASURED_TRAFFIC_BYTES = 6.581e9
+# HBM traffic of one forward+backward launch at B=16, T=500, V=256, from two rocprofv3 --pmc runs of
+# this script (FETCH_SIZE, then WRITE_SIZE, per dispatch), each scaled by what the same counter reads
+# for the plain copy of the weight tensor that --pmc-calibration adds; the runs and their arithmetic
+# are in profiles/cluster3_kernel_B16_T500_V256.md.
+MEASURED_FETCH_BYTES = 4.344e9
+MEASURED_WRITE_BYTES = 2.260e9
+HEADLINE_KERNEL = "cluster3_kernel<true, false> (+ the 3 us tag-clear kernel of the same call)"
 
 
 def time_region(fn, steps, warmup):
@@ -53,20 +59,33 @@ def time_region(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall
 
 
-def cpu_baseline(cfg, arcs):
-    """The float64 oracle, as it stands, on the same workload (forward, backward, marginals)."""
+def cpu_baseline(cfg):
+    """The float64 oracle, as it stands, on the same workload (forward, backward, marginals): all
+    host threads on the whole batch, and one thread on the first four items."""
+    import numpy as np
     import oracle
     oracle.build()
     cores = oracle.max_threads()
-    t0 = time.perf_counter()
-    alpha, D = oracle.forward(cfg["w"], cfg["lengths"], 1)
-    beta = oracle.backward(cfg["w"], cfg["lengths"], 1)
-    gamma = oracle.posteriors(cfg["w"], cfg["lengths"], 1, alpha, beta, D)
-    dt = time.perf_counter() - t0
-    del gamma
-    return {"value": arcs / dt, "unit": "arcs/s", "cores": cores, "kind": "oracle",
+
+    def run(w, lengths):
+        t0 = time.perf_counter()
+        alpha, D = oracle.forward(w, lengths, 1)
+        beta = oracle.backward(w, lengths, 1)
+        gamma = oracle.posteriors(w, lengths, 1, alpha, beta, D)
+        dt = time.perf_counter() - t0
+        del gamma
+        return float(np.sum(lengths.astype(np.int64)) * cfg["C"] * (cfg["V"] + 1)) / dt, dt
+
+    all_rate, all_dt = run(cfg["w"], cfg["lengths"])
+    n1 = min(4, cfg["B"])
+    oracle.set_threads(1)
+    one_rate, one_dt = run(cfg["w"][:n1], cfg["lengths"][:n1])
+    oracle.set_threads(cores)
+    return {"value": all_rate, "unit": "arcs/s", "cores": cores, "kind": "oracle",
             "sample": "the full workload (B=%d, T=%d, V=%d): float64 forward + backward + marginals, "
-                      "OpenMP over batch items, %.2f s" % (cfg["B"], cfg["T"], cfg["V"], dt)}
+                      "OpenMP over batch items, %.2f s" % (cfg["B"], cfg["T"], cfg["V"], all_dt),
+            "single_thread": {"value": one_rate, "unit": "arcs/s", "cores": 1,
+                              "sample": "the first %d items of the same workload, %.2f s" % (n1, one_dt)}}
 
 
 def main():
@@ -81,6 +100,9 @@ def main():
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--generation", type=int, default=0,
                     help="cooperating-workgroup kernel generation (0 = the library's choice)")
+    ap.add_argument("--option", action="append", default=[], metavar="N=VALUE",
+                    help="set process-wide option N of the library (numbers of last_option_t in "
+                         "include/last.h), e.g. 2=0 for the one-workgroup shortest-path kernels")
     ap.add_argument("--B", type=int, default=16)
     ap.add_argument("--T", type=int, default=500)
     ap.add_argument("--V", type=int, default=256)
@@ -99,6 +121,9 @@ def main():
     lb.load_library()                      # fails loudly if the HIP library is missing
     if args.generation:
         lb.set_option(lb.OPT_CLUSTER_GENERATION, args.generation)
+    for kv in args.option:
+        k, v = kv.split("=")
+        lb.set_option(int(k), int(v))
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
 
@@ -113,19 +138,32 @@ def main():
     refs = torch.from_numpy(cfg["refs"]).cuda()
     ulen = torch.from_numpy(cfg["ref_lengths"]).cuda()
     dw = torch.empty_like(w)
+    st = torch.full((cfg["B"],), -1, dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
 
     def step():
-        lb.last_arc_posteriors(w, lengths, order=1, dw=dw)
+        lb.last_arc_posteriors(w, lengths, order=1, dw=dw, item_status=st)
 
     if args.pmc_calibration:
-        for _ in range(3):
-            dw.copy_(w)                 # reads and writes w.numel() * 4 bytes
+        for _ in range(3):              # probe_copy_kernel: reads and writes w.numel() * 4 bytes
+            lb.last_probe_bandwidth(lb.PROBE_COPY, w, dw)
         torch.cuda.synchronize()
 
     ms, wall_ms = time_region(step, args.steps, args.warmup)
+    lb.check_item_status(st)            # a timed-out or out-of-range item would void the number
     value = arcs / (ms * 1e-3)
     achieved = BYTES_PER_ARC * arcs / (ms * 1e-3) / 1e9
+
+    # what this GPU streams when nothing else happens, on the same tensor: one read sweep, one copy
+    wbytes = float(w.numel() * 4)
+    k = max(5, args.steps // 2)
+    read_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_READ, w, dw), k, 2)
+    copy_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_COPY, w, dw), k, 2)
+    ceilings = {"read_sweep_ms": read_ms, "read_sweep_GBs": wbytes / read_ms / 1e6,
+                "copy_ms": copy_ms, "copy_GBs": 2 * wbytes / copy_ms / 1e6,
+                # forward+backward = one read-only pass + one read-and-write pass over the weights
+                "read_plus_copy_ms": read_ms + copy_ms,
+                "frac_of_read_plus_copy": (read_ms + copy_ms) / ms}
 
     extra = {}
     if not args.no_extra:
@@ -136,6 +174,9 @@ def main():
         extra["full_loss_ms"], _ = time_region(loss_step, k, 1)
         extra["shortest_path_ms"], _ = time_region(lambda: lb.last_shortest_path(w, lengths, order=1), k, 1)
         extra["shortest_distance_log_ms"], _ = time_region(lambda: lb.last_shortest_distance(w, lengths, order=1), k, 1)
+        extra["local_log_likelihood_and_gradient_ms"], _ = time_region(
+            lambda: lb.last_local_log_likelihood(w, lengths, refs, ulen, order=1, dw=dw), k, 1)
+        lb.check_item_status()
         # the trigram lattice with on-the-fly weights (B=4, T=1000, V=64, hidden 512)
         c4 = workloads.config(4)
 
@@ -168,14 +209,16 @@ def main():
                                % (cfg["B"], cfg["T"], cfg["V"], cfg["C"]),
                    "B": cfg["B"], "T": cfg["T"], "V": cfg["V"], "C": cfg["C"], "arcs": arcs},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES if full else None,
-                     "kernel": "cluster2_kernel<true, false, true> (+ the 5 us tag-clear kernel of the same call)",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_FETCH_BYTES + MEASURED_WRITE_BYTES if full and not args.generation else None,
+                     "kernel": HEADLINE_KERNEL if full and not args.generation else None,
                      "algorithmic_bytes_per_launch": BYTES_PER_ARC * arcs},
+        "ceilings": ceilings,
         "extra": extra,
     }
     if not args.no_cpu_baseline:
         del dw
-        out["cpu_baseline"] = cpu_baseline(cfg, arcs)
+        out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out), flush=True)
 
 

@@ -246,6 +246,16 @@ typedef enum {
 last_status_t last_set_option(int32_t option, int32_t value);
 int32_t last_get_option(int32_t option);
 
+/* Measurement aid, not part of the method: plain streaming kernels of known
+ * traffic, the yardstick the lattice kernels are held against and the
+ * calibration of HBM byte counters.  LAST_PROBE_READ reads `bytes` bytes at
+ * src (dev) once and writes nothing (dst: dev, at least 16 bytes, left
+ * untouched); LAST_PROBE_COPY copies them to dst (dev, `bytes` bytes, must not
+ * overlap src).  bytes a positive multiple of 16, both pointers 16-byte
+ * aligned (LAST_ERR_SHAPE otherwise). */
+enum { LAST_PROBE_READ = 0, LAST_PROBE_COPY = 1 };
+last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream);
+
 const char* last_status_string(last_status_t status);
 
 /* Text of the HIP error behind the most recent LAST_ERR_HIP (diagnostics). */

@@ -25,7 +25,8 @@ EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posterior
            "last_intersect_reference", "last_shortest_path", "last_status_string",
            "last_version", "last_kernel_variant", "last_hip_error_string",
            "last_shortest_distance_static", "last_set_option", "last_get_option",
-           "last_local_log_likelihood"]
+           "last_local_log_likelihood", "last_probe_bandwidth"]
+PROBE_READ, PROBE_COPY = 0, 1
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -85,6 +86,8 @@ def load_library():
     lib.last_shortest_path.restype = i32
     lib.last_shortest_path.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                        vp, vp, vp, vp, vp, sz, vp]
+    lib.last_probe_bandwidth.restype = i32
+    lib.last_probe_bandwidth.argtypes = [i32, vp, vp, sz, vp]
     lib.last_status_string.restype = ctypes.c_char_p
     lib.last_status_string.argtypes = [i32]
     lib.last_version.restype = i32
@@ -113,6 +116,13 @@ def set_option(option, value):
     old = int(lib.last_get_option(option))
     _check(lib.last_set_option(option, value))
     return old
+
+
+def last_probe_bandwidth(kind, src, dst):
+    """Plain read sweep (PROBE_READ; dst is any device tensor of >= 16 bytes) or copy (PROBE_COPY) of
+    the bytes of `src`: the streaming yardstick of the benchmark."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().last_probe_bandwidth(kind, _ptr(src), _ptr(dst), nbytes, _stream()))
 
 
 def _ptr(t):

@@ -13,6 +13,7 @@
 #include "cluster2v_kernels.hpp"
 #include "cluster3_kernels.hpp"
 #include "fused_kernels.hpp"
+#include "probe_kernels.hpp"
 #include <algorithm>
 
 #include <atomic>
@@ -614,6 +615,25 @@ last_status_t last_set_option(int32_t option, int32_t value)
 int32_t last_get_option(int32_t option)
 {
     return option < 0 || option >= LAST_OPT_COUNT_ ? -1 : opt(option);
+}
+
+last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream)
+{
+    if (!src || !dst) return LAST_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || (uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0)
+        return LAST_ERR_SHAPE;
+    if (kind != LAST_PROBE_READ && kind != LAST_PROBE_COPY) return LAST_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t n4 = bytes / 16;
+    const size_t copy_grid = (n4 + kProbeThreads - 1) / kProbeThreads;
+    if (copy_grid > 0x7fffffffull) return LAST_ERR_SHAPE;
+    if (kind == LAST_PROBE_READ)
+        hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeReadGrid), dim3(kProbeThreads), 0, st,
+                           (const probe_f4*)src, n4, (float*)dst);
+    else
+        hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)copy_grid), dim3(kProbeThreads), 0, st,
+                           (const probe_f4*)src, (probe_f4*)dst, n4);
+    return hip_status();
 }
 
 const char* last_hip_error_string(void) { return hipGetErrorString(g_last_hip_error); }

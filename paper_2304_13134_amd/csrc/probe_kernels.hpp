@@ -1,0 +1,48 @@
+// Plain streaming kernels of known traffic: a read-only sweep and a copy of a
+// buffer.  They are the yardstick the lattice kernels are held against (what
+// this GPU streams when nothing else happens) and the calibration of the HBM
+// byte counters.  Shapes chosen by measurement on MI355X: 16 bytes per lane,
+// every workgroup takes contiguous tiles, non-temporal accesses; the sweep runs
+// 8192 workgroups over tiles of 16 KiB (7.1 TB/s), the copy gives every tile of
+// 4 KiB a workgroup of its own (6.4 TB/s read + written; grid-stride loops over
+// scattered pieces reach 4.3 to 5.4 TB/s).
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace last {
+
+typedef float probe_f4 __attribute__((ext_vector_type(4)));
+constexpr int kProbeThreads = 256;
+constexpr int kProbeReadUnroll = 4;
+constexpr int kProbeReadGrid = 8192;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const probe_f4* __restrict__ p, size_t n4,
+                                                                    float* __restrict__ sink)
+{
+    constexpr size_t tile = (size_t)kProbeThreads * kProbeReadUnroll;
+    const size_t ntiles = (n4 + tile - 1) / tile;
+    probe_f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const size_t base = t * tile + threadIdx.x;
+        probe_f4 v[kProbeReadUnroll];
+#pragma unroll
+        for (int k = 0; k < kProbeReadUnroll; ++k)
+            if (base + (size_t)k * kProbeThreads < n4) v[k] = __builtin_nontemporal_load(&p[base + (size_t)k * kProbeThreads]);
+#pragma unroll
+        for (int k = 0; k < kProbeReadUnroll; ++k)
+            if (base + (size_t)k * kProbeThreads < n4) acc += v[k];
+    }
+    // every load feeds the sum; the sum is stored only for a value no data produces in practice
+    const float s = acc.x + acc.y + acc.z + acc.w;
+    if (s == -1.2345678e-30f) sink[0] = s;
+}
+
+// one workgroup per tile of kProbeThreads * 16 bytes
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const probe_f4* __restrict__ src,
+                                                                    probe_f4* __restrict__ dst, size_t n4)
+{
+    const size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
+}
+
+}  // namespace last
