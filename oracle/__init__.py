@@ -285,3 +285,36 @@ def fused_forward_backward(f, e, W, lengths, order=2, round_h=True, grads=True):
         _p(df, ctypes.c_double), _p(de, ctypes.c_double), _p(dW, ctypes.c_double))
     assert rc == 0
     return dict(D=D, alpha=alpha, df=df, de=de, dW=dW)
+
+
+def fused_numerator(f, e, W, lengths, refs, ref_lengths, order=2, round_h=True, grads=True):
+    """Numerator (Section 2.1) on shared-embedding weights computed on the fly (Section 4.1): only the
+    two arcs leaving every state (t,u) of the intersected lattice are evaluated.  f [B,T,H], e [C,H],
+    W [H,V+1] as bfloat16 bit patterns.  Returns the dict of `numerator` plus df, de, dW (float64):
+    the chain of the intersected lattice's arc marginals through the weight function."""
+    f, e, W = _u16(f), _u16(e), _u16(W)
+    B, T, H = f.shape
+    C = e.shape[0]
+    V = W.shape[1] - 1
+    assert num_states(V, order) == C and e.shape[1] == H and W.shape[0] == H
+    lengths, refs, ref_lengths = _i32(lengths), _i32(refs), _i32(ref_lengths)
+    Umax = refs.shape[1]
+    U1 = Umax + 1
+    ctx = np.empty((B, U1), dtype=np.int32)
+    a = np.empty((B, T + 1, U1), dtype=np.float64)
+    bb = np.empty((B, T + 1, U1), dtype=np.float64)
+    N = np.empty((B,), dtype=np.float64)
+    pb = np.empty((B, T, U1), dtype=np.float64)
+    pl = np.empty((B, T, U1), dtype=np.float64)
+    df = np.empty((B, T, H), dtype=np.float64) if grads else None
+    de = np.empty((C, H), dtype=np.float64) if grads else None
+    dW = np.empty((H, V + 1), dtype=np.float64) if grads else None
+    rc = _load().lo_fused_numerator(_p(f, ctypes.c_uint16), _p(e, ctypes.c_uint16), _p(W, ctypes.c_uint16),
+                                    _p(lengths, ctypes.c_int32), _p(refs, ctypes.c_int32),
+                                    _p(ref_lengths, ctypes.c_int32), B, T, V, order, H, Umax,
+                                    int(bool(round_h)), _p(ctx, ctypes.c_int32), _p(a, ctypes.c_double),
+                                    _p(bb, ctypes.c_double), _p(N, ctypes.c_double), _p(pb, ctypes.c_double),
+                                    _p(pl, ctypes.c_double), _p(df, ctypes.c_double), _p(de, ctypes.c_double),
+                                    _p(dW, ctypes.c_double))
+    assert rc == 0
+    return dict(N=N, ctx=ctx, a=a, b=bb, pb=pb, pl=pl, df=df, de=de, dW=dW)

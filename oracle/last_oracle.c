@@ -674,3 +674,112 @@ int lo_fused_forward_backward(const uint16_t* f, const uint16_t* e, const uint16
     free(Wd); free(wt); free(mx); free(tmp); free(bcur); free(bnew); free(gam); free(h);
     return 0;
 }
+
+/* ---------------------------------------------------------------------- */
+/* Numerator (Section 2.1) with the weights computed on the fly by the      */
+/* shared-embedding weight function (Section 4.1: nothing is materialised). */
+/* Only the two arcs leaving every state (t,u) of the intersected lattice   */
+/* are evaluated:                                                           */
+/*   w0[t][u] = w[t][ctx(u)][0],  w1[t][u] = w[t][ctx(u)][ref[u]],          */
+/* then the same recursion as lo_numerator on the (t,u) grid, and the chain */
+/* of its arc marginals pb, pl through the weight function:                 */
+/*   gw[k]  = pb W[k][0] + pl W[k][ref[u]],  dpre[k] = gw[k] (1 - h[k]^2),  */
+/*   df[b][t] += dpre, de[ctx(u)] += dpre,                                  */
+/*   dW[k][0] += h[k] pb, dW[k][ref[u]] += h[k] pl,                         */
+/* h = the (possibly bfloat16-rounded) hidden vector of (t, ctx(u)).        */
+/* Outputs as lo_numerator; df [B][T][H], de [C][H], dW [H][V+1] or NULL.   */
+/* ---------------------------------------------------------------------- */
+int lo_fused_numerator(const uint16_t* f, const uint16_t* e, const uint16_t* W,
+                       const int32_t* len, const int32_t* refs, const int32_t* ulen,
+                       int B, int T, int V, int order, int H, int Umax, int round_h,
+                       int32_t* ctx, double* a, double* bb, double* N, double* pb, double* pl,
+                       double* df, double* de, double* dW)
+{
+    const int C = lo_num_states(V, order);
+    if (C < 0) return 1;
+    const int V1 = V + 1;
+    const int U1 = Umax + 1;
+    double* Wd = (double*)malloc((size_t)H * V1 * sizeof(double));
+    for (size_t i = 0; i < (size_t)H * V1; ++i) Wd[i] = (double)bf16_to_f32(W[i]);
+    double* h = (double*)malloc((size_t)H * sizeof(double));
+    double* w0 = (double*)malloc((size_t)(T > 0 ? T : 1) * U1 * sizeof(double));
+    double* w1 = (double*)malloc((size_t)(T > 0 ? T : 1) * U1 * sizeof(double));
+    if (df) memset(df, 0, (size_t)B * T * H * sizeof(double));
+    if (de) memset(de, 0, (size_t)C * H * sizeof(double));
+    if (dW) memset(dW, 0, (size_t)H * V1 * sizeof(double));
+    for (int b = 0; b < B; ++b) {
+        const int L = clamp_len(len[b], T);
+        const int U = ulen[b];
+        const int32_t* r = refs + (size_t)b * Umax;
+        int32_t* cx = ctx + (size_t)b * U1;
+        double* A = a + (size_t)b * (T + 1) * U1;
+        double* Bk = bb + (size_t)b * (T + 1) * U1;
+        double* PB = pb + (size_t)b * T * U1;
+        double* PL = pl + (size_t)b * T * U1;
+        for (size_t i = 0; i < (size_t)(T + 1) * U1; ++i) { A[i] = NEG_INF; Bk[i] = NEG_INF; }
+        for (size_t i = 0; i < (size_t)T * U1; ++i) { PB[i] = 0.0; PL[i] = 0.0; }
+        cx[0] = 0;
+        for (int u = 1; u <= Umax; ++u)
+            cx[u] = (u <= U) ? lo_next_state(V, order, cx[u - 1], r[u - 1]) : -1;
+        /* the two arc weights of every state of the intersected lattice */
+        for (int t = 0; t < L; ++t)
+            for (int u = 0; u <= U; ++u) {
+                hidden_row(f + ((size_t)b * T + t) * H, e + (size_t)cx[u] * H, H, round_h, h);
+                double s0 = 0.0, s1 = 0.0;
+                for (int k = 0; k < H; ++k) {
+                    s0 += h[k] * Wd[(size_t)k * V1];
+                    if (u < U) s1 += h[k] * Wd[(size_t)k * V1 + r[u]];
+                }
+                w0[(size_t)t * U1 + u] = s0;
+                w1[(size_t)t * U1 + u] = (u < U) ? s1 : NEG_INF;
+            }
+        A[0] = 0.0;
+        for (int t = 0; t < L; ++t)
+            for (int u = 0; u <= U; ++u) {
+                double c[2];
+                c[0] = A[(size_t)t * U1 + u] + w0[(size_t)t * U1 + u];
+                c[1] = (u >= 1) ? A[(size_t)t * U1 + u - 1] + w1[(size_t)t * U1 + u - 1] : NEG_INF;
+                A[(size_t)(t + 1) * U1 + u] = lse(c, 2);
+            }
+        N[b] = A[(size_t)L * U1 + U];
+        Bk[(size_t)L * U1 + U] = 0.0;
+        for (int t = L - 1; t >= 0; --t)
+            for (int u = 0; u <= U; ++u) {
+                double c[2];
+                c[0] = w0[(size_t)t * U1 + u] + Bk[(size_t)(t + 1) * U1 + u];
+                c[1] = (u < U) ? w1[(size_t)t * U1 + u] + Bk[(size_t)(t + 1) * U1 + u + 1] : NEG_INF;
+                Bk[(size_t)t * U1 + u] = lse(c, 2);
+            }
+        if (N[b] == NEG_INF) continue;
+        for (int t = 0; t < L; ++t)
+            for (int u = 0; u <= U; ++u) {
+                const double av = A[(size_t)t * U1 + u];
+                if (av == NEG_INF) continue;
+                double p0 = 0.0, p1 = 0.0;
+                const double nb = Bk[(size_t)(t + 1) * U1 + u];
+                if (nb != NEG_INF) p0 = exp(av + w0[(size_t)t * U1 + u] + nb - N[b]);
+                if (u < U) {
+                    const double nl = Bk[(size_t)(t + 1) * U1 + u + 1];
+                    if (nl != NEG_INF) p1 = exp(av + w1[(size_t)t * U1 + u] + nl - N[b]);
+                }
+                PB[(size_t)t * U1 + u] = p0;
+                PL[(size_t)t * U1 + u] = p1;
+                if ((df || de || dW) && (p0 != 0.0 || p1 != 0.0)) {
+                    hidden_row(f + ((size_t)b * T + t) * H, e + (size_t)cx[u] * H, H, round_h, h);
+                    for (int k = 0; k < H; ++k) {
+                        double gw = p0 * Wd[(size_t)k * V1];
+                        if (u < U) gw += p1 * Wd[(size_t)k * V1 + r[u]];
+                        const double dpre = gw * (1.0 - h[k] * h[k]);
+                        if (df) df[((size_t)b * T + t) * H + k] += dpre;
+                        if (de) de[(size_t)cx[u] * H + k] += dpre;
+                        if (dW) {
+                            dW[(size_t)k * V1] += h[k] * p0;
+                            if (u < U) dW[(size_t)k * V1 + r[u]] += h[k] * p1;
+                        }
+                    }
+                }
+            }
+    }
+    free(Wd); free(h); free(w0); free(w1);
+    return 0;
+}

@@ -627,3 +627,67 @@ def test_local_numerator_gradient_finite_differences():
         Np = oracle.numerator_local(wp.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1, grad=False)["N"][0]
         Nm = oracle.numerator_local(wm.astype(np.float32), d["lengths"], d["refs"], d["ref_lengths"], 1, grad=False)["N"][0]
         assert abs((Np - Nm) / (2 * h) - loc["grad"][0, t, q, y]) < 1e-6
+
+
+# --------------------------------------- numerator on on-the-fly (shared-embedding) weights
+def test_fused_numerator_vs_enumeration_on_materialised_weights():
+    """Evaluating only the arcs of the intersected lattice gives what the definition gives on the
+    materialised weights: enumeration of all paths, restricted to the reference (Sections 2.1, 4.1)."""
+    s = workloads.shared_emb(B=2, T=6, V=2, order=2, H=16, seed=44, len_lo=5, len_hi=6)
+    refs = np.array([[1, 2, 2, 1], [2, 2, 1, 1]], dtype=np.int32)
+    ulen = np.array([4, 3], dtype=np.int32)
+    for round_h in (True, False):
+        w = oracle.shared_emb_weights(s["f"], s["e"], s["W"], round_h=round_h)       # float64 [B,T,C,V1]
+        out = oracle.fused_numerator(s["f"], s["e"], s["W"], s["lengths"], refs, ulen, 2, round_h=round_h)
+        for b in range(2):
+            L = int(s["lengths"][b])
+            labels, states, scores = bf.enumerate_paths(w[b, :L], 2)
+            l, st, sc = bf.restrict_to_reference(labels, states, scores, refs[b, :ulen[b]])
+            N_bf, g_bf = bf.arc_marginals(l, st, sc, w[b, :L].shape)
+            assert abs(out["N"][b] - N_bf) < 1e-10
+            one = dict(ctx=out["ctx"][b:b + 1], pb=out["pb"][b:b + 1, :L], pl=out["pl"][b:b + 1, :L])
+            g = oracle.numerator_posteriors_dense(one, refs[b:b + 1], ulen[b:b + 1], (1,) + w[b, :L].shape)
+            assert np.max(np.abs(g[0] - g_bf)) < 1e-12
+    # infeasible reference: no path, no gradient
+    out = oracle.fused_numerator(s["f"], s["e"], s["W"], [3, 6], refs, [4, 3], 2)
+    assert out["N"][0] == -np.inf and np.all(out["df"][0] == 0) and np.isfinite(out["N"][1])
+
+
+def test_fused_numerator_gradients_chain_rule_and_finite_differences():
+    s = workloads.shared_emb(B=2, T=5, V=2, order=2, H=6, seed=45)
+    refs = np.array([[2, 1, 1], [1, 2, 2]], dtype=np.int32)
+    ulen = np.array([3, 2], dtype=np.int32)
+    out = oracle.fused_numerator(s["f"], s["e"], s["W"], s["lengths"], refs, ulen, 2, round_h=False)
+    f = workloads.bf16_bits_to_f32(s["f"]).astype(np.float64)
+    e = workloads.bf16_bits_to_f32(s["e"]).astype(np.float64)
+    W = workloads.bf16_bits_to_f32(s["W"]).astype(np.float64)
+    # chain rule written with library contractions on the dense marginals of the intersection
+    w = oracle.shared_emb_weights(s["f"], s["e"], s["W"], round_h=False)
+    g = oracle.numerator_posteriors_dense(out, refs, ulen, w.shape)                 # [B,T,C,V1]
+    h = np.tanh(f[:, :, None, :] + e[None, None, :, :])                              # [B,T,C,H]
+    dpre = np.einsum("btqy,ky->btqk", g, W) * (1.0 - h * h)
+    assert np.max(np.abs(out["df"] - dpre.sum(axis=2))) < 1e-12
+    assert np.max(np.abs(out["de"] - dpre.sum(axis=(0, 1)))) < 1e-12
+    assert np.max(np.abs(out["dW"] - np.einsum("btqk,btqy->ky", h, g))) < 1e-12
+
+    def total_N(f, e, W):
+        tot = 0.0
+        for b in range(2):
+            wb = np.tanh(f[b][:, None, :] + e[None, :, :]) @ W
+            labels, states, scores = bf.enumerate_paths(wb, 2)
+            _, _, sc = bf.restrict_to_reference(labels, states, scores, refs[b, :ulen[b]])
+            tot += bf.log_sum(sc)
+        return tot
+
+    rng = np.random.default_rng(4)
+    hh = 1e-6
+    for name, arr, gr in (("f", f, out["df"]), ("e", e, out["de"]), ("W", W, out["dW"])):
+        for _ in range(6):
+            idx = tuple(rng.integers(0, n) for n in arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += hh
+            am[idx] -= hh
+            args_p = dict(f=f, e=e, W=W); args_p[name] = ap
+            args_m = dict(f=f, e=e, W=W); args_m[name] = am
+            fd = (total_N(**args_p) - total_N(**args_m)) / (2 * hh)
+            assert abs(fd - gr[idx]) < 1e-7, (name, idx, fd, gr[idx])
