@@ -301,21 +301,26 @@ def last_arc_posteriors(w, lengths, order=1, dw=None, scale=1.0, accumulate=Fals
 
 def _intersect(entry, op, w, lengths, refs, ref_lengths, order, dw, scale, accumulate, item_status):
     lib = load_library()
-    wt, cx = dense_weights(w), _dense_ctx(w, order)
+    wt, cx, device, B = _weights_and_context(w, order)
     _dev_tensor(lengths, torch.int32, "lengths")
     _dev_tensor(refs, torch.int32, "refs")
     _dev_tensor(ref_lengths, torch.int32, "ref_lengths")
     Umax = refs.shape[1]
-    num = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
-    item_status = _status(item_status, w.shape[0], w.device)
+    num = torch.empty(B, dtype=torch.float32, device=device)
+    item_status = _status(item_status, B, device)
     g = None
-    if dw is not None:
+    if dw is not None and isinstance(w, SharedEmb):
+        for t, n in zip(dw, ("df", "de", "dW")):
+            _dev_tensor(t, torch.float32, n)
+        g = LastGrads(None, dw[0].data_ptr(), dw[1].data_ptr(), dw[2].data_ptr(),
+                      int(bool(accumulate)), float(scale))
+    elif dw is not None:
         _dev_tensor(dw, torch.float32, "dw")
         g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
     nbytes = last_workspace_bytes(wt, cx, op, Umax)
     if nbytes == 0:
         raise LastError(6, "combination not supported")
-    ws = workspace(nbytes, w.device)
+    ws = workspace(nbytes, device)
     _check(getattr(lib, entry)(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx),
                                _ptr(refs), _ptr(ref_lengths), Umax, _ptr(num),
                                ctypes.byref(g) if g is not None else None,
@@ -326,7 +331,8 @@ def _intersect(entry, op, w, lengths, refs, ref_lengths, order, dw, scale, accum
 def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, scale=-1.0,
                              accumulate=True, item_status=None):
     """numerator [B] float32; if dw is given, scale * (marginals of the
-    intersected lattice) is added to (accumulate) or written over dw."""
+    intersected lattice) is added to (accumulate) or written over dw.  With SharedEmb weights only
+    the arcs of the intersected lattice are evaluated and dw is the triple (df, de, dW)."""
     return _intersect("last_intersect_reference", OP_INTERSECT_REFERENCE, w, lengths, refs, ref_lengths,
                       order, dw, scale, accumulate, item_status)
 

@@ -13,6 +13,7 @@
 #include "cluster2v_kernels.hpp"
 #include "cluster3_kernels.hpp"
 #include "fused_kernels.hpp"
+#include "fused_numerator_kernels.hpp"
 #include "probe_kernels.hpp"
 #include <algorithm>
 
@@ -433,6 +434,14 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     return p;
 }
 
+// shapes the on-the-fly numerator takes: every lane of a wavefront owns H/64 hidden units, in pairs
+bool fused_numerator_ok(const last_weights_t* wt)
+{
+    const int H = wt->hidden;
+    if (H % 128 != 0 || H < 128 || H > 128 * kFnMaxPairs) return false;
+    return (((uintptr_t)wt->f | (uintptr_t)wt->e | (uintptr_t)wt->W) % 16) == 0;
+}
+
 struct FusedWs {
     float* alpha;
     float* beta;
@@ -676,6 +685,13 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
     Carver cv(nullptr);
     if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
         const FusedPlan fp = fused_plan(s, weights);
+        if (op == LAST_OP_INTERSECT_REFERENCE) {
+            // the numerator evaluates single arcs: no limit on the vocabulary, any closed-form context
+            if (Umax < 0 || !fused_numerator_ok(weights)) return 0;
+            carve_num(cv, s, Umax, false);
+            cv.take<float>((size_t)s.V1 * weights->hidden);
+            return cv.used;
+        }
         if (!fp.ok) return 0;
         if (op == LAST_OP_SHORTEST_DISTANCE) carve_fused(cv, s, fp, false);
         else if (op == LAST_OP_ARC_POSTERIORS) carve_fused(cv, s, fp, true);
@@ -849,10 +865,56 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
     if (!lengths || !ref_lengths || !numerator) return LAST_ERR_NULL;
     if (Umax < 0 || Umax > (1 << 20)) return LAST_ERR_SHAPE;
     if (Umax > 0 && !refs) return LAST_ERR_NULL;
-    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
-    if (out && !out->dw) return LAST_ERR_NULL;
     const size_t lds = (size_t)2 * (Umax + 2) * sizeof(double);
     if (lds > kMaxLds) return LAST_ERR_UNSUPPORTED;
+    if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
+        if (local || !fused_numerator_ok(weights)) return LAST_ERR_UNSUPPORTED;
+        if (out && (!out->df || !out->de || !out->dW)) return LAST_ERR_NULL;
+        rc = check_ws(ws, ws_bytes, last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax));
+        if (rc != LAST_OK) return rc;
+        hipStream_t st = (hipStream_t)hip_stream;
+        const Ctx c = make_ctx(s);
+        const int H = weights->hidden, U1 = Umax + 1;
+        Carver cv(ws);
+        NumWs p = carve_num(cv, s, Umax, false);
+        float* Wt = cv.take<float>((size_t)s.V1 * H);
+        const __bf16* f = (const __bf16*)weights->f;
+        const __bf16* e = (const __bf16*)weights->e;
+        hipLaunchKernelGGL(num_check_kernel, dim3(s.B), dim3(256), 0, st, lengths, refs, ref_lengths,
+                           c, s.T, Umax, p.status, p.ctxs, p.link, (const int*)nullptr);
+        hipLaunchKernelGGL(fnum_transpose_w_kernel, dim3((s.V1 * H + 255) / 256), dim3(256), 0, st,
+                           (const __bf16*)weights->W, H, s.V1, Wt);
+        const dim3 block(kFnWaves * kWave);
+        const int ugrid = (U1 + kFnWaves - 1) / kFnWaves;
+        if (s.T > 0)
+            hipLaunchKernelGGL(fnum_gather_kernel, dim3(ugrid, (s.T + kFnStrip - 1) / kFnStrip, s.B), block, 0, st,
+                               f, e, (const float*)Wt, lengths, refs, ref_lengths, (const int*)p.status,
+                               (const int*)p.ctxs, s.T, Umax, H, p.wi);
+        hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
+                           (const float2*)p.wi, (const double*)nullptr, lengths, ref_lengths,
+                           (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
+        if (out) {
+            if (!out->accumulate) {
+                hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, st, out->de, (size_t)s.C * H);
+                hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(256), 0, st, out->dW, (size_t)H * s.V1);
+            }
+            if (s.T > 0) {
+                hipLaunchKernelGGL(fnum_df_kernel, dim3((s.T + kFnWaves - 1) / kFnWaves, s.B), block, 0, st,
+                                   f, e, (const float*)Wt, (const float2*)p.wi, lengths, refs, ref_lengths,
+                                   (const int*)p.status, (const int*)p.ctxs, (const double*)p.a,
+                                   (const double*)p.bk, (const double*)p.N, s.T, Umax, H, out->df,
+                                   out->scale, out->accumulate);
+                hipLaunchKernelGGL(fnum_de_dw_kernel, dim3(ugrid, (s.T + kFnChunk - 1) / kFnChunk, s.B), block, 0,
+                                   st, f, e, (const float*)Wt, (const float2*)p.wi, lengths, refs, ref_lengths,
+                                   (const int*)p.status, (const int*)p.ctxs, (const double*)p.a,
+                                   (const double*)p.bk, (const double*)p.N, s.T, Umax, H, s.V1, out->de,
+                                   out->dW, out->scale);
+            }
+        }
+        return hip_status();
+    }
+    if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+    if (out && !out->dw) return LAST_ERR_NULL;
     constexpr int kLocalWaves = 4;
     const size_t lds_scatter = (size_t)kLocalWaves * s.V1 * sizeof(float);
     if (local && lds_scatter > kMaxLds) return LAST_ERR_UNSUPPORTED;

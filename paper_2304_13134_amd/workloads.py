@@ -74,7 +74,7 @@ def references(rng, B, V, Umax, u_lo, u_hi):
 
 
 def config(k: int, **over):
-    """The five benchmark configurations (0-indexed).  Keyword overrides shrink
+    """The five benchmark configurations (0-indexed) and, as number 5, the paper's Table 2 shape.  Keyword overrides shrink
     a configuration for parity tests while keeping its structure."""
     seed = SEED_BASE + k
     if k == 0:
@@ -105,6 +105,17 @@ def config(k: int, **over):
         p = dict(B=4, T=1000, V=64, order=2, H=512)
         p.update(over)
         return shared_emb(seed=seed, **p)
+    if k == 5:
+        # the shape of the paper's own benchmark (Table 2): 32 labels, context size 2 (1057 states),
+        # 512 hidden units, batch 16, 1024 frames, 256 output labels; inputs as in configuration 4
+        p = dict(B=16, T=1024, V=32, order=2, H=512)
+        U = over.pop("U", 256)
+        p.update(over)
+        d = shared_emb(seed=seed, **p)
+        rng = np.random.default_rng(seed + 1000)
+        d["refs"], d["ref_lengths"] = references(rng, p["B"], p["V"], U, U, U)
+        d["Umax"] = U
+        return d
     raise ValueError("unknown configuration %r" % (k,))
 
 

@@ -131,3 +131,94 @@ def test_fused_full_size_against_stored_oracle_results():
         assert err <= tol, "%s: max abs error %.3g > %.3g (max |ref| %.3g)" % (name, err, tol, mx)
     # frames past the length of an item get no gradient; the total is finite
     assert bool(torch.isfinite(df).all()) and bool(torch.isfinite(de).all())
+
+
+# ------------------------------------------------- numerator on on-the-fly weights
+def run_fused_loss(s, order=2):
+    """Denominator forward-backward, then the numerator accumulated with scale -1: (D, N, grads)."""
+    se = fused_inputs(s)
+    lengths = torch.from_numpy(s["lengths"]).cuda()
+    refs, ulen = torch.from_numpy(s["refs"]).cuda(), torch.from_numpy(s["ref_lengths"]).cuda()
+    B = s["f"].shape[0]
+    st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    dist, grads = lb.last_arc_posteriors(se, lengths, order=order)
+    num = lb.last_intersect_reference(se, lengths, refs, ulen, order=order, dw=grads, scale=-1.0,
+                                      accumulate=True, item_status=st)
+    torch.cuda.synchronize()
+    return dist.cpu().numpy(), num.cpu().numpy(), [g.cpu().numpy() for g in grads], st.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,T,V,H,U,seed", [(2, 9, 3, 128, 4, 11), (3, 20, 6, 256, 9, 12),
+                                             (2, 14, 17, 384, 14, 13), (2, 40, 5, 512, 21, 14)])
+def test_fused_numerator_small(B, T, V, H, U, seed):
+    announce("numerator on on-the-fly weights", B, T, V, H, U)
+    s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed, len_lo=max(U, T - 3), len_hi=T)
+    rng = np.random.default_rng(seed)
+    s["refs"], s["ref_lengths"] = workloads.references(rng, B, V, U, max(0, U - 3), U)
+    se = fused_inputs(s)
+    lengths = torch.from_numpy(s["lengths"]).cuda()
+    refs, ulen = torch.from_numpy(s["refs"]).cuda(), torch.from_numpy(s["ref_lengths"]).cuda()
+    st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    g = [torch.full(t.shape, 7.0, dtype=torch.float32, device="cuda") for t in se]
+    num = lb.last_intersect_reference(se, lengths, refs, ulen, order=2, dw=g, scale=1.0, accumulate=False,
+                                      item_status=st)
+    num2 = lb.last_intersect_reference(se, lengths, refs, ulen, order=2)          # without gradients
+    torch.cuda.synchronize()
+    o = oracle.fused_numerator(s["f"], s["e"], s["W"], s["lengths"], s["refs"], s["ref_lengths"], 2)
+    assert st.cpu().tolist() == [0] * B
+    assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
+    assert torch.equal(num, num2)
+    for name, got, want in zip(("df", "de", "dW"), g, (o["df"], o["de"], o["dW"])):
+        assert_grad_close(name, got.cpu().numpy(), want)
+    # the full loss gradient: denominator marginals minus numerator marginals through the weight function
+    D, N, grads, st2 = run_fused_loss(s)
+    den = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=True)
+    assert np.all(st2 == 0)
+    assert_dist_close(D, den["D"])
+    for name, got, a, b in zip(("df", "de", "dW"), grads, (den["df"], den["de"], den["dW"]),
+                               (o["df"], o["de"], o["dW"])):
+        tol = 2e-4 * (np.max(np.abs(a)) + np.max(np.abs(b))) + 2e-5
+        assert np.max(np.abs(got - (a - b))) <= tol, name
+
+
+def test_fused_numerator_bigram_context_and_edge_cases():
+    announce("numerator on on-the-fly weights: context size 1, wide vocabulary, U=0, U=len, U>len, bad label")
+    s = workloads.shared_emb(B=5, T=12, V=100, order=1, H=128, seed=21)
+    s["lengths"] = np.array([12, 7, 4, 12, 12], np.int32)
+    rng = np.random.default_rng(21)
+    refs, _ = workloads.references(rng, 5, 100, 13, 1, 5)
+    ulen = np.array([0, 7, 5, 3, 14], np.int32)
+    refs[3, 1] = 101
+    se = fused_inputs(s)
+    st = torch.full((5,), -1, dtype=torch.int32, device="cuda")
+    g = [torch.full(t.shape, 3.0, dtype=torch.float32, device="cuda") for t in se]
+    num = lb.last_intersect_reference(se, torch.from_numpy(s["lengths"]).cuda(), torch.from_numpy(refs).cuda(),
+                                      torch.from_numpy(ulen).cuda(), order=1, dw=g, scale=1.0, accumulate=False,
+                                      item_status=st).cpu().numpy()
+    assert st.cpu().tolist() == [0, 0, 4, 2, 3]
+    assert num[2] == -np.inf and np.isnan(num[3]) and np.isnan(num[4])
+    o = oracle.fused_numerator(s["f"][:2], s["e"], s["W"], s["lengths"][:2], refs[:2], ulen[:2], 1)
+    assert_dist_close(num[:2], o["N"])
+    assert_grad_close("df", g[0].cpu().numpy()[:2], o["df"])
+    assert torch.all(g[0][2:] == 0)
+    assert_grad_close("de", g[1].cpu().numpy(), o["de"])
+    assert_grad_close("dW", g[2].cpu().numpy(), o["dW"])
+
+
+def test_fused_numerator_table2_shape_two_items():
+    """The paper's benchmark shape (Table 2: 32 labels, 1057 states, 512 hidden units, 1024 frames,
+    256 output labels) on two items, numerator and its gradients against the oracle."""
+    announce("numerator on on-the-fly weights, Table 2 shape, B=2")
+    s = workloads.config(5, B=2)
+    se = fused_inputs(s)
+    st = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    g = [torch.empty(t.shape, dtype=torch.float32, device="cuda") for t in se]
+    num = lb.last_intersect_reference(se, torch.from_numpy(s["lengths"]).cuda(), torch.from_numpy(s["refs"]).cuda(),
+                                      torch.from_numpy(s["ref_lengths"]).cuda(), order=2, dw=g, scale=1.0,
+                                      accumulate=False, item_status=st)
+    torch.cuda.synchronize()
+    o = oracle.fused_numerator(s["f"], s["e"], s["W"], s["lengths"], s["refs"], s["ref_lengths"], 2)
+    assert st.cpu().tolist() == [0, 0]
+    assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
+    for name, got, want in zip(("df", "de", "dW"), g, (o["df"], o["de"], o["dW"])):
+        assert_grad_close(name, got.cpu().numpy(), want)
