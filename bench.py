@@ -195,6 +195,27 @@ def main():
         # plus the two gradient contractions, 2*H flops per arc each
         extra["fused_trigram_tflops"] = 5 * 2.0 * 512 * arcs4 / (extra["fused_trigram_fwd_bwd_ms"] * 1e-3) / 1e12
         del se, g4
+        # the shape of the paper's own benchmark (Table 2: 32 labels, 1057 states, 512 hidden units,
+        # batch 16, 1024 frames, 256 output labels): one training step of the globally normalised loss =
+        # denominator forward-backward + numerator, gradients to f, e, W.  The paper's Table 3 times
+        # this step on other hardware (context, not a target).
+        c5 = workloads.config(5)
+        se5 = lb.SharedEmb(bf16(c5["f"]), bf16(c5["e"]), bf16(c5["W"]))
+        len5 = torch.from_numpy(c5["lengths"]).cuda()
+        refs5, ulen5 = torch.from_numpy(c5["refs"]).cuda(), torch.from_numpy(c5["ref_lengths"]).cuda()
+        _, g5 = lb.last_arc_posteriors(se5, len5, order=2)
+
+        def table2_step():
+            lb.last_arc_posteriors(se5, len5, order=2, dw=g5)
+            lb.last_intersect_reference(se5, len5, refs5, ulen5, order=2, dw=g5, scale=-1.0, accumulate=True)
+        extra["table2_training_step_ms"], _ = time_region(table2_step, 3, 1)
+        lb.check_item_status()
+        extra["table2_numerator_ms"], _ = time_region(
+            lambda: lb.last_intersect_reference(se5, len5, refs5, ulen5, order=2, dw=g5, scale=-1.0,
+                                                accumulate=True), 3, 1)
+        arcs5 = float(np.sum(c5["lengths"].astype(np.int64)) * c5["C"] * (c5["V"] + 1))
+        extra["table2_arcs_per_s"] = arcs5 / (extra["table2_training_step_ms"] * 1e-3)
+        del se5, g5
         extra["wall_ms_per_step"] = wall_ms
         wt, cx = lb.dense_weights(w), lb.context(cfg["V"], 1)
         extra["kernel_variant"] = lb.last_kernel_variant(wt, cx, lb.OP_ARC_POSTERIORS)

@@ -222,3 +222,29 @@ def test_fused_numerator_table2_shape_two_items():
     assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
     for name, got, want in zip(("df", "de", "dW"), g, (o["df"], o["de"], o["dW"])):
         assert_grad_close(name, got.cpu().numpy(), want)
+
+
+def test_table2_shape_full_loss_against_stored_oracle_results():
+    """One training step at the shape of the paper's benchmark (Table 2), all 16 items: D, N and the
+    gradient of D - N against tests/golden/table2_fused.npz, written by
+    tests/golden/make_table2_fused.py, which calls only the oracle (D, N, dW whole, 4096 seeded
+    samples each of df and de)."""
+    import os
+    announce("Table 2 shape, full loss, B=16 T=1024 V=32 U=256 hidden 512")
+    gold = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "table2_fused.npz"))
+    s = workloads.config(5)
+    D, N, (df, de, dW), st = run_fused_loss(s)
+    assert np.all(st == 0)
+    assert_dist_close(D, gold["D"])
+    assert_dist_close(N, gold["N"], "numerator")
+    assert np.all(N <= D)
+    dfs = df.ravel()[gold["idx_f"]].astype(np.float64)
+    des = de.ravel()[gold["idx_e"]].astype(np.float64)
+    # the gradient is a difference of two terms of these magnitudes, each within the bound above
+    for name, got, want, mx in (("dW", dW.astype(np.float64), gold["dW"], float(np.max(np.abs(gold["dW"])))),
+                                ("df", dfs, gold["df"], float(gold["df_max"])),
+                                ("de", des, gold["de"], float(gold["de_max"]))):
+        tol = 4e-4 * mx + 2e-5
+        err = float(np.max(np.abs(got - want)))
+        assert np.all(np.isfinite(got)), name
+        assert err <= tol, "%s: max abs error %.3g > %.3g (max |ref| %.3g)" % (name, err, tol, mx)
