@@ -851,6 +851,31 @@ last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* 
     return hip_status();
 }
 
+// The (t,u) recursion with one wavefront per item and direction (references of up to 511 labels);
+// false when the shape needs the workgroup kernel.
+static bool launch_num_wave(const Shape& s, int Umax, const NumWs& p, const int* lengths, const int* ref_lengths,
+                            float* numerator, int* item_status, hipStream_t st)
+{
+    const int U1 = Umax + 1;
+    const int cpl = (U1 + kWave - 1) / kWave;
+    if (cpl > 8 || s.T < 1 || (size_t)(s.T + 1) * U1 * 8 >= 0xfffffff0ull) return false;
+    auto go = [&](auto CPL, auto CH) {
+        hipLaunchKernelGGL(HIP_KERNEL_NAME(num_wave_kernel<decltype(CPL)::value, decltype(CH)::value>),
+                           dim3(s.B, 2), dim3(kWave), 0, st, (const float2*)p.wi, lengths, ref_lengths,
+                           (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
+    };
+    using std::integral_constant;
+    // frames per prefetch chunk: a wavefront can keep count of 63 memory operations in flight, and a
+    // frame costs cpl loads and cpl stores
+    if (cpl <= 1) go(integral_constant<int, 1>(), integral_constant<int, 16>());
+    else if (cpl <= 2) go(integral_constant<int, 2>(), integral_constant<int, 8>());
+    else if (cpl <= 3) go(integral_constant<int, 3>(), integral_constant<int, 6>());
+    else if (cpl <= 4) go(integral_constant<int, 4>(), integral_constant<int, 4>());
+    else if (cpl <= 6) go(integral_constant<int, 6>(), integral_constant<int, 3>());
+    else go(integral_constant<int, 8>(), integral_constant<int, 2>());
+    return true;
+}
+
 // Shared by the globally normalised numerator and the locally normalised log-likelihood.
 static last_status_t intersect_impl(const last_weights_t* weights, const int32_t* lengths,
                                     const last_context_t* context,
@@ -890,9 +915,10 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
             hipLaunchKernelGGL(fnum_gather_kernel, dim3(ugrid, (s.T + kFnStrip - 1) / kFnStrip, s.B), block, 0, st,
                                f, e, (const float*)Wt, lengths, refs, ref_lengths, (const int*)p.status,
                                (const int*)p.ctxs, s.T, Umax, H, p.wi);
-        hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
-                           (const float2*)p.wi, (const double*)nullptr, lengths, ref_lengths,
-                           (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
+        if (!launch_num_wave(s, Umax, p, lengths, ref_lengths, numerator, item_status, st))
+            hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
+                               (const float2*)p.wi, (const double*)nullptr, lengths, ref_lengths,
+                               (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
         if (out) {
             if (!out->accumulate) {
                 hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, st, out->de, (size_t)s.C * H);
@@ -942,9 +968,13 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
             hipLaunchKernelGGL(num_gather_kernel, pgrid, dim3(128), 0, st, weights->w, lengths, refs,
                                ref_lengths, (const int*)p.status, (const int*)p.ctxs, c, s.T, Umax, p.wi);
     }
-    hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
-                       (const float2*)p.wi, (const double*)p.lz, lengths, ref_lengths,
-                       (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
+    if (!local && launch_num_wave(s, Umax, p, lengths, ref_lengths, numerator, item_status, st)) {
+        // one wavefront per item and direction has run the recursion
+    } else {
+        hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
+                           (const float2*)p.wi, (const double*)p.lz, lengths, ref_lengths,
+                           (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
+    }
     if (out && s.T > 0) {
         if (!out->accumulate) {
             const size_t n = (size_t)s.B * s.T * s.C * s.V1;

@@ -160,13 +160,16 @@ __global__ __launch_bounds__(256) void num_gather_local_kernel(
     }
 }
 
+// log(exp x + exp y): the large part m in float64, the correction log(1 + exp(lo - m)) in (0, log 2]
+// with the hardware exp2 / log2 (absolute error of a few 1e-8, far below what feeds an exponent
+// that must be good to 1e-6 after a few hundred frames)
 __device__ __forceinline__ double log_add(double x, double y)
 {
     const double m = x > y ? x : y;
     if (m == (double)LAST_NEG_INF) return m;
     const double lo = x > y ? y : x;
     const float d = (float)(lo - m);           // <= 0, -inf allowed
-    return m + (double)log1pf(__expf(d));
+    return m + (double)__logf(1.f + __expf(d));
 }
 
 // grid (B, 2): blockIdx.y = 0 forward weights a[b][t][u], = 1 backward weights bk.
@@ -247,6 +250,160 @@ __global__ __launch_bounds__(256) void num_recursion_kernel(
             }
             __syncthreads();
             double* s = cur; cur = nxt; nxt = s;
+        }
+    }
+}
+
+// The same recursion with one wavefront per item and direction, for references of up to
+// 64 * CPL - 1 labels: lane l keeps the states u = l*CPL .. l*CPL + CPL-1 of the current frame in
+// registers (one lane shuffle per frame hands a value across the lane boundary; no LDS, no
+// workgroup barrier), and it reads the gathered arc weights of its states a chunk of CH frames ahead
+// of the recursion.  (Pulling them straight out of the dense tensor instead was measured slower:
+// every lane then touches two cache lines of its own per frame, and one wavefront cannot keep
+// enough of those in flight.)  Arithmetic as in num_recursion_kernel.
+
+template <int CPL, int CH>
+struct NwBuf {
+    float w0[CH][CPL], w1[CH][CPL];
+};
+
+typedef __amdgpu_buffer_rsrc_t nw_buf_t;
+constexpr unsigned kNwOut = 0xfffffff0u;        // a byte offset no buffer of an item reaches: loads give 0, stores are dropped
+
+__device__ __forceinline__ nw_buf_t nw_rsrc(const void* p, size_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)(unsigned)bytes, 0x00020000);
+}
+__device__ __forceinline__ void nw_store64(double v, nw_buf_t r, unsigned voff, unsigned soff)
+{
+    typedef decltype(__builtin_amdgcn_raw_buffer_load_b64(r, 0, 0, 0)) b64_t;
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(b64_t, v), r, (int)voff, (int)soff, 0);
+}
+// log_add without a branch: -inf + -inf stays -inf
+__device__ __forceinline__ double nw_log_add(double x, double y)
+{
+    const double m = x > y ? x : y;
+    const double lo = x > y ? y : x;
+    const float d = m == (double)LAST_NEG_INF ? 0.f : (float)(lo - m);
+    return m + (double)__logf(1.f + __expf(d));
+}
+
+// the arc weights of CH frames, t = t0 + k*dir clamped into the item (values of frames outside it are unused)
+template <int CPL, int CH>
+__device__ __forceinline__ void nw_load(NwBuf<CPL, CH>& d, nw_buf_t irs, unsigned rowb, int t0, int dir, int L,
+                                        const unsigned (&ou)[CPL])
+{
+#pragma unroll
+    for (int k = 0; k < CH; ++k) {
+        int t = t0 + k * dir;
+        t = t < L ? t : L - 1;
+        t = t < 0 ? 0 : t;
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+            const float2 v = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(irs, (int)ou[i], (int)((unsigned)t * rowb), 0));
+            d.w0[k][i] = v.x;
+            d.w1[k][i] = v.y;
+        }
+    }
+}
+
+// Requires (T+1)*(Umax+1)*8 below 2^32 - 16 (byte offsets inside one item's arrays).
+template <int CPL, int CH>
+__global__ __launch_bounds__(kWave) void num_wave_kernel(
+    const float2* __restrict__ wi, const int* __restrict__ len, const int* __restrict__ ulen,
+    const int* __restrict__ status, int T, int Umax, double* __restrict__ a, double* __restrict__ bk,
+    double* __restrict__ Nws, float* __restrict__ numerator, int* __restrict__ item_status)
+{
+    const int U1 = Umax + 1;
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const bool fwd = blockIdx.y == 0;
+    const int st = status[b];
+    if (st != kItemOk) {
+        if (fwd && lane == 0) {
+            if (item_status) item_status[b] = st;
+            numerator[b] = (st == kItemInfeasible) ? LAST_NEG_INF : __builtin_nanf("");
+            Nws[b] = (double)LAST_NEG_INF;
+        }
+        return;
+    }
+    if (fwd && lane == 0 && item_status) item_status[b] = kItemOk;
+    const int L = len[b], U = ulen[b];
+    const double NI = (double)LAST_NEG_INF;
+    const unsigned rowb = (unsigned)U1 * 8u;
+    const nw_buf_t irs = nw_rsrc(wi + (size_t)b * T * U1, (size_t)T * U1 * 8);
+    // byte offset of each of this lane's states inside a row of the (t,u) arrays; kNwOut past the reference
+    unsigned ou[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+        const int u = lane * CPL + i;
+        ou[i] = u <= U ? (unsigned)u * 8u : kNwOut;
+    }
+    double cur[CPL];
+    NwBuf<CPL, CH> nxt;
+    if (fwd) {
+        const nw_buf_t ars = nw_rsrc(a + (size_t)b * (T + 1) * U1, (size_t)(T + 1) * U1 * 8);
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+            cur[i] = lane * CPL + i == 0 ? 0.0 : NI;
+            nw_store64(cur[i], ars, ou[i], 0);
+        }
+        if (L > 0) nw_load<CPL, CH>(nxt, irs, rowb, 0, 1, L, ou);
+        for (int t0 = 0; t0 < L; t0 += CH) {
+            const NwBuf<CPL, CH> now = nxt;                       // (waits for the chunk, then frees its registers)
+            nw_load<CPL, CH>(nxt, irs, rowb, t0 + CH, 1, L, ou);
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const int t = t0 + k;
+                if (t < L) {
+                    double up[CPL];
+#pragma unroll
+                    for (int i = 0; i < CPL; ++i) up[i] = cur[i] + (double)now.w1[k][i];     // label arc u -> u+1
+                    double left = __shfl_up(up[CPL - 1], 1, kWave);
+                    left = lane == 0 ? NI : left;
+#pragma unroll
+                    for (int i = 0; i < CPL; ++i) {
+                        const double v = nw_log_add(cur[i] + (double)now.w0[k][i], i == 0 ? left : up[i - 1]);
+                        cur[i] = v;
+                        nw_store64(v, ars, ou[i], (unsigned)(t + 1) * rowb);
+                    }
+                }
+            }
+        }
+        // N = the forward weight of (L, U)
+        double nv = NI;
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) nv = lane * CPL + i == U ? cur[i] : nv;
+        if (lane == U / CPL) {
+            Nws[b] = nv;
+            numerator[b] = (float)nv;
+        }
+    } else {
+        const nw_buf_t brs = nw_rsrc(bk + (size_t)b * (T + 1) * U1, (size_t)(T + 1) * U1 * 8);
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+            cur[i] = lane * CPL + i == U ? 0.0 : NI;
+            nw_store64(cur[i], brs, ou[i], (unsigned)L * rowb);
+        }
+        // frames walked downwards: the chunk that ends below frame tend holds frames tend-1, tend-2, ...
+        if (L > 0) nw_load<CPL, CH>(nxt, irs, rowb, L - 1, -1, L, ou);
+        for (int tend = L; tend > 0; tend -= CH) {
+            const NwBuf<CPL, CH> now = nxt;
+            nw_load<CPL, CH>(nxt, irs, rowb, tend - CH - 1, -1, L, ou);
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const int t = tend - 1 - k;
+                if (t >= 0) {
+                    double right = __shfl_down(cur[0], 1, kWave);
+                    right = lane == kWave - 1 ? NI : right;
+#pragma unroll
+                    for (int i = 0; i < CPL; ++i) {
+                        const double nb = i + 1 < CPL ? cur[i + 1] : right;     // still the weight of frame t+1
+                        const double v = nw_log_add((double)now.w0[k][i] + cur[i], (double)now.w1[k][i] + nb);
+                        cur[i] = v;
+                        nw_store64(v, brs, ou[i], (unsigned)t * rowb);
+                    }
+                }
+            }
         }
     }
 }
