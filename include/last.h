@@ -87,7 +87,8 @@ typedef enum {
     LAST_OP_ARC_POSTERIORS = 1,
     LAST_OP_INTERSECT_REFERENCE = 2,
     LAST_OP_SHORTEST_PATH = 3,
-    LAST_OP_LOCAL_LOG_LIKELIHOOD = 4
+    LAST_OP_LOCAL_LOG_LIKELIHOOD = 4,
+    LAST_OP_LOSS = 5
 } last_op_t;
 
 /* Context dependency (Section 3): the full n-gram one in closed form (Figure 1a
@@ -177,6 +178,23 @@ last_status_t last_intersect_reference(const last_weights_t* weights, const int3
                                        int32_t Umax, float* numerator,
                                        const last_grads_t* out, int32_t* item_status,
                                        void* ws, size_t ws_bytes, void* hip_stream);
+
+/* The globally normalised loss in one call (Section 2.1): dist = denominator
+ * (last_arc_posteriors), numerator (last_intersect_reference), and
+ * out (+)= scale * d(dist - numerator)/d(weights), i.e. the arc marginals of the
+ * complete lattice minus those of the intersected lattice (dense: dw; shared_emb:
+ * df, de, dW).  Results as from the two calls in sequence, but the numerator's
+ * recursion runs beside the denominator on a stream of the library's own (one
+ * per device, default priority, created at the first call and kept until the
+ * process ends; forked from and joined to hip_stream with events, so the call
+ * is still asynchronous and ordered like any other work on hip_stream).
+ * Workspace: last_workspace_bytes(..., LAST_OP_LOSS, Umax).  item_status reports
+ * the first problem of either part. */
+last_status_t last_globally_normalized_loss(const last_weights_t* weights, const int32_t* lengths,
+                                           const last_context_t* context,
+                                           const int32_t* refs, const int32_t* ref_lengths, int32_t Umax,
+                                           float* dist, float* numerator, const last_grads_t* out,
+                                           int32_t* item_status, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Log-likelihood of the reference string under the locally normalised model on
  * the same lattice (Section 2.1: intersection and shortest distance, with the

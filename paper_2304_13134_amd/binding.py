@@ -19,13 +19,14 @@ LIB_PATH = os.environ.get("LAST_HIP_LIB") or os.path.join(_HERE, "liblast_hip.so
 LAST_LOG, LAST_TROPICAL = 0, 1
 OP_SHORTEST_DISTANCE, OP_ARC_POSTERIORS, OP_INTERSECT_REFERENCE, OP_SHORTEST_PATH = 0, 1, 2, 3
 OP_LOCAL_LOG_LIKELIHOOD = 4
+OP_LOSS = 5
 WEIGHTS_DENSE, WEIGHTS_SHARED_EMB = 0, 1
 
 EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posteriors",
            "last_intersect_reference", "last_shortest_path", "last_status_string",
            "last_version", "last_kernel_variant", "last_hip_error_string",
            "last_shortest_distance_static", "last_set_option", "last_get_option",
-           "last_local_log_likelihood", "last_probe_bandwidth"]
+           "last_local_log_likelihood", "last_probe_bandwidth", "last_globally_normalized_loss"]
 PROBE_READ, PROBE_COPY = 0, 1
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 32 << 20
@@ -83,6 +84,9 @@ def load_library():
                                              vp, vp, i32, vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
     lib.last_local_log_likelihood.restype = i32
     lib.last_local_log_likelihood.argtypes = lib.last_intersect_reference.argtypes
+    lib.last_globally_normalized_loss.restype = i32
+    lib.last_globally_normalized_loss.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
+                                                  vp, vp, i32, vp, vp, ctypes.POINTER(LastGrads), vp, vp, sz, vp]
     lib.last_shortest_path.restype = i32
     lib.last_shortest_path.argtypes = [ctypes.POINTER(LastWeights), vp, ctypes.POINTER(LastContext),
                                        vp, vp, vp, vp, vp, sz, vp]
@@ -335,6 +339,42 @@ def last_intersect_reference(w, lengths, refs, ref_lengths, order=1, dw=None, sc
     the arcs of the intersected lattice are evaluated and dw is the triple (df, de, dW)."""
     return _intersect("last_intersect_reference", OP_INTERSECT_REFERENCE, w, lengths, refs, ref_lengths,
                       order, dw, scale, accumulate, item_status)
+
+
+def last_globally_normalized_loss(w, lengths, refs, ref_lengths, order=1, dw=None, scale=1.0,
+                                  accumulate=False, item_status=None):
+    """(dist [B], numerator [B], dw): the globally normalised loss dist - numerator of every item and
+    dw (+)= scale * its gradient (dense: a tensor like w; SharedEmb: the triple (df, de, dW)), in one
+    call; the numerator's recursion runs beside the denominator."""
+    lib = load_library()
+    wt, cx, device, B = _weights_and_context(w, order)
+    _dev_tensor(lengths, torch.int32, "lengths")
+    _dev_tensor(refs, torch.int32, "refs")
+    _dev_tensor(ref_lengths, torch.int32, "ref_lengths")
+    Umax = refs.shape[1]
+    dist = torch.empty(B, dtype=torch.float32, device=device)
+    num = torch.empty(B, dtype=torch.float32, device=device)
+    item_status = _status(item_status, B, device)
+    if isinstance(w, SharedEmb):
+        if dw is None:
+            dw = tuple(torch.empty(t.shape, dtype=torch.float32, device=device) for t in w)
+        for t, n in zip(dw, ("df", "de", "dW")):
+            _dev_tensor(t, torch.float32, n)
+        g = LastGrads(None, dw[0].data_ptr(), dw[1].data_ptr(), dw[2].data_ptr(),
+                      int(bool(accumulate)), float(scale))
+    else:
+        if dw is None:
+            dw = torch.empty_like(w)
+        _dev_tensor(dw, torch.float32, "dw")
+        g = LastGrads(dw.data_ptr(), None, None, None, int(bool(accumulate)), float(scale))
+    nbytes = last_workspace_bytes(wt, cx, OP_LOSS, Umax)
+    if nbytes == 0:
+        raise LastError(6, "combination not supported")
+    ws = workspace(nbytes, device)
+    _check(lib.last_globally_normalized_loss(ctypes.byref(wt), _ptr(lengths), ctypes.byref(cx), _ptr(refs),
+                                             _ptr(ref_lengths), Umax, _ptr(dist), _ptr(num), ctypes.byref(g),
+                                             _ptr(item_status), _ptr(ws), ws.numel(), _stream()))
+    return dist, num, dw
 
 
 def last_local_log_likelihood(w, lengths, refs, ref_lengths, order=1, dw=None, scale=1.0,

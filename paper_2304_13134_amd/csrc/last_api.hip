@@ -685,6 +685,11 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
     Carver cv(nullptr);
     if (weights->kind == LAST_WEIGHTS_SHARED_EMB) {
         const FusedPlan fp = fused_plan(s, weights);
+        if (op == LAST_OP_LOSS) {
+            const size_t den = last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0);
+            const size_t num = last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax);
+            return den && num ? den + num : 0;
+        }
         if (op == LAST_OP_INTERSECT_REFERENCE) {
             // the numerator evaluates single arcs: no limit on the vocabulary, any closed-form context
             if (Umax < 0 || !fused_numerator_ok(weights)) return 0;
@@ -719,6 +724,11 @@ size_t last_workspace_bytes(const last_weights_t* weights, const last_context_t*
         if (Umax < 0) return 0;
         carve_num(cv, s, Umax, true);
         break;
+    case LAST_OP_LOSS: {
+        const size_t den = last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0);
+        const size_t num = last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax);
+        return den && num ? den + num : 0;
+    }
     case LAST_OP_SHORTEST_PATH:
         carve_path(cv, s, vplan.ok ? vplan.xwords : 0);
         break;
@@ -877,13 +887,17 @@ static bool launch_num_wave(const Shape& s, int Umax, const NumWs& p, const int*
 }
 
 // Shared by the globally normalised numerator and the locally normalised log-likelihood.
+enum { kNumPrepare = 1, kNumScatter = 2 };   // the two halves of a numerator call: up to the recursion, the gradient
+
 static last_status_t intersect_impl(const last_weights_t* weights, const int32_t* lengths,
                                     const last_context_t* context,
                                     const int32_t* refs, const int32_t* ref_lengths,
                                     int32_t Umax, float* numerator,
                                     const last_grads_t* out, int32_t* item_status,
-                                    void* ws, size_t ws_bytes, void* hip_stream, bool local)
+                                    void* ws, size_t ws_bytes, void* hip_stream, bool local,
+                                    int phases = kNumPrepare | kNumScatter)
 {
+    const bool prepare = phases & kNumPrepare, scatter = phases & kNumScatter;
     Shape s;
     last_status_t rc = check_common(weights, context, &s);
     if (rc != LAST_OK) return rc;
@@ -905,12 +919,13 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
         float* Wt = cv.take<float>((size_t)s.V1 * H);
         const __bf16* f = (const __bf16*)weights->f;
         const __bf16* e = (const __bf16*)weights->e;
+        const dim3 block(kFnWaves * kWave);
+        const int ugrid = (U1 + kFnWaves - 1) / kFnWaves;
+        if (prepare) {
         hipLaunchKernelGGL(num_check_kernel, dim3(s.B), dim3(256), 0, st, lengths, refs, ref_lengths,
                            c, s.T, Umax, p.status, p.ctxs, p.link, (const int*)nullptr);
         hipLaunchKernelGGL(fnum_transpose_w_kernel, dim3((s.V1 * H + 255) / 256), dim3(256), 0, st,
                            (const __bf16*)weights->W, H, s.V1, Wt);
-        const dim3 block(kFnWaves * kWave);
-        const int ugrid = (U1 + kFnWaves - 1) / kFnWaves;
         if (s.T > 0)
             hipLaunchKernelGGL(fnum_gather_kernel, dim3(ugrid, (s.T + kFnStrip - 1) / kFnStrip, s.B), block, 0, st,
                                f, e, (const float*)Wt, lengths, refs, ref_lengths, (const int*)p.status,
@@ -919,7 +934,8 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
             hipLaunchKernelGGL(num_recursion_kernel, dim3(s.B, 2), dim3(256), lds, st,
                                (const float2*)p.wi, (const double*)nullptr, lengths, ref_lengths,
                                (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
-        if (out) {
+        }
+        if (out && scatter) {
             if (!out->accumulate) {
                 hipLaunchKernelGGL(zero_fill_kernel, dim3(256), dim3(256), 0, st, out->de, (size_t)s.C * H);
                 hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(256), 0, st, out->dW, (size_t)H * s.V1);
@@ -954,11 +970,12 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
     int* flag = carve_table_flag(cv, s);
     NumWs p = carve_num(cv, s, Umax, local);
     const int U1 = Umax + 1;
+    const dim3 pgrid((U1 + 127) / 128, s.T > 0 ? s.T : 1, s.B);
+    const dim3 wgrid((U1 + kLocalWaves - 1) / kLocalWaves, s.T > 0 ? s.T : 1, s.B);   // a wavefront per cell
+    if (prepare) {
     if (flag) launch_table_check(s, flag, st);
     hipLaunchKernelGGL(num_check_kernel, dim3(s.B), dim3(256), 0, st, lengths, refs, ref_lengths,
                        c, s.T, Umax, p.status, p.ctxs, p.link, (const int*)flag);
-    const dim3 pgrid((U1 + 127) / 128, s.T > 0 ? s.T : 1, s.B);
-    const dim3 wgrid((U1 + kLocalWaves - 1) / kLocalWaves, s.T > 0 ? s.T : 1, s.B);   // a wavefront per cell
     if (s.T > 0) {
         if (local)
             hipLaunchKernelGGL(num_gather_local_kernel, wgrid, dim3(kLocalWaves * kWave), 0, st, weights->w,
@@ -975,7 +992,8 @@ static last_status_t intersect_impl(const last_weights_t* weights, const int32_t
                            (const float2*)p.wi, (const double*)p.lz, lengths, ref_lengths,
                            (const int*)p.status, s.T, Umax, p.a, p.bk, p.N, numerator, item_status);
     }
-    if (out && s.T > 0) {
+    }
+    if (out && s.T > 0 && scatter) {
         if (!out->accumulate) {
             const size_t n = (size_t)s.B * s.T * s.C * s.V1;
             hipLaunchKernelGGL(zero_fill_kernel, dim3(2048), dim3(256), 0, st, out->dw, n);
@@ -1015,6 +1033,104 @@ last_status_t last_local_log_likelihood(const last_weights_t* weights, const int
 {
     return intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, loglik, out, item_status,
                           ws, ws_bytes, hip_stream, true);
+}
+
+// ---- denominator and numerator in one call ---------------------------------------------------
+// The numerator up to its recursion does not depend on the denominator, so it runs beside it on a
+// stream of the library's own (one per device, default priority, created at first use), forked from
+// and joined to the caller's stream with events; only the numerator's gradient pass waits for the
+// denominator's.  Host calls are serialised by a mutex so that each record/wait pair stays together.
+namespace {
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int kMaxSideDevices = 64;
+SideStream g_side[kMaxSideDevices];
+std::mutex g_side_mu;
+
+last_status_t side_stream(SideStream** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    if (dev < 0 || dev >= kMaxSideDevices) return LAST_ERR_UNSUPPORTED;
+    SideStream& sd = g_side[dev];
+    if (!sd.stream) {
+        e = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.join, hipEventDisableTiming);
+        if (e != hipSuccess) { g_last_hip_error = e; sd = SideStream(); return LAST_ERR_HIP; }
+    }
+    *out = &sd;
+    return LAST_OK;
+}
+
+__global__ void merge_status_kernel(const int* __restrict__ num_status, int* __restrict__ item_status, int B)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B && item_status[b] == kItemOk && num_status[b] != kItemOk) item_status[b] = num_status[b];
+}
+}  // namespace
+
+last_status_t last_globally_normalized_loss(const last_weights_t* weights, const int32_t* lengths,
+                                           const last_context_t* context,
+                                             const int32_t* refs, const int32_t* ref_lengths, int32_t Umax,
+                                             float* dist, float* numerator, const last_grads_t* out,
+                                             int32_t* item_status, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!weights || !context || !out) return LAST_ERR_NULL;
+    const size_t need_den = last_workspace_bytes(weights, context, LAST_OP_ARC_POSTERIORS, 0);
+    const size_t need_num = last_workspace_bytes(weights, context, LAST_OP_INTERSECT_REFERENCE, Umax);
+    if (need_den == 0 || need_num == 0) {
+        Shape s;
+        const last_status_t rc = check_common(weights, context, &s);
+        return rc != LAST_OK ? rc : LAST_ERR_UNSUPPORTED;
+    }
+    last_status_t rc = check_ws(ws, ws_bytes, need_den + need_num);
+    if (rc != LAST_OK) return rc;
+    if (!dist || !numerator) return LAST_ERR_NULL;
+    void* ws_num = (char*)ws + need_den;            // (both sizes are multiples of the alignment)
+    hipStream_t st = (hipStream_t)hip_stream;
+    std::lock_guard<std::mutex> lock(g_side_mu);
+    SideStream* sd = nullptr;
+    rc = side_stream(&sd);
+    if (rc != LAST_OK) return rc;
+    // the numerator's gradient is accumulated with the opposite sign onto the denominator's
+    last_grads_t gnum = *out;
+    gnum.accumulate = 1;
+    gnum.scale = -out->scale;
+    // arguments are checked by a dry pass before anything is enqueued: the numerator call with no phase
+    rc = intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, numerator, &gnum, nullptr,
+                        ws_num, need_num, nullptr, false, 0);
+    if (rc != LAST_OK) return rc;
+    hipError_t e = hipEventRecord(sd->fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(sd->stream, sd->fork, 0);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    rc = intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, numerator, &gnum, nullptr,
+                        ws_num, need_num, sd->stream, false, kNumPrepare);
+    // the fork is always joined, also after an error, so that the caller's stream never loses the side work
+    e = hipEventRecord(sd->join, sd->stream);
+    const last_status_t rc_den = last_arc_posteriors(weights, lengths, context, dist, out, item_status, ws,
+                                                     need_den, hip_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(st, sd->join, 0);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    if (rc != LAST_OK) return rc;
+    if (rc_den != LAST_OK) return rc_den;
+    rc = intersect_impl(weights, lengths, context, refs, ref_lengths, Umax, numerator, &gnum, nullptr,
+                        ws_num, need_num, hip_stream, false, kNumScatter);
+    if (rc != LAST_OK) return rc;
+    if (item_status) {
+        // the numerator's per-item status sits at a fixed place of its workspace
+        Shape s;
+        check_common(weights, context, &s);
+        Carver cv(ws_num);
+        carve_table_flag(cv, s);
+        const NumWs p = carve_num(cv, s, Umax, false);
+        hipLaunchKernelGGL(merge_status_kernel, dim3((s.B + 255) / 256), dim3(256), 0, st,
+                           (const int*)p.status, item_status, s.B);
+    }
+    return hip_status();
 }
 
 last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* lengths,

@@ -248,3 +248,21 @@ def test_table2_shape_full_loss_against_stored_oracle_results():
         err = float(np.max(np.abs(got - want)))
         assert np.all(np.isfinite(got)), name
         assert err <= tol, "%s: max abs error %.3g > %.3g (max |ref| %.3g)" % (name, err, tol, mx)
+
+
+def test_fused_loss_in_one_call():
+    announce("loss in one call on on-the-fly weights")
+    s = workloads.shared_emb(B=3, T=20, V=6, order=2, H=256, seed=31, len_lo=17, len_hi=20)
+    rng = np.random.default_rng(31)
+    s["refs"], s["ref_lengths"] = workloads.references(rng, 3, 6, 9, 4, 9)
+    D, N, grads, st = run_fused_loss(s)
+    se = fused_inputs(s)
+    st1 = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+    d1, n1, g1 = lb.last_globally_normalized_loss(se, torch.from_numpy(s["lengths"]).cuda(),
+                                                  torch.from_numpy(s["refs"]).cuda(),
+                                                  torch.from_numpy(s["ref_lengths"]).cuda(), order=2, item_status=st1)
+    torch.cuda.synchronize()
+    assert st1.cpu().tolist() == [0, 0, 0]
+    assert np.array_equal(d1.cpu().numpy(), D) and np.array_equal(n1.cpu().numpy(), N)
+    for name, a, b in zip(("df", "de", "dW"), g1, grads):
+        assert_grad_close(name, a.cpu().numpy(), b.astype(np.float64))

@@ -392,3 +392,48 @@ def test_config3_full_size_loss_and_gradient(config3_full):
         assert np.max(np.abs(got - want)) <= 2 * TOL_POST_ABS
     sums = dw.sum(dim=(2, 3), dtype=torch.float64).cpu().numpy()
     assert np.max(np.abs(sums)) < 1e-4                 # denominator and numerator marginals cancel
+
+
+# ------------------------------------------------------- loss in one call
+def check_loss_one_call(cfg, order=1, g_order=None):
+    """last_globally_normalized_loss against the two calls in sequence and against the oracle."""
+    g_order = order if g_order is None else g_order
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    refs, ulen = dev(cfg["refs"]), dev(cfg["ref_lengths"])
+    B = cfg["w"].shape[0]
+    st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    dist, num, dw = lb.last_globally_normalized_loss(w, lengths, refs, ulen, order=g_order, item_status=st)
+    d2, dw2 = lb.last_arc_posteriors(w, lengths, order=g_order)
+    n2 = lb.last_intersect_reference(w, lengths, refs, ulen, order=g_order, dw=dw2, scale=-1.0, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dist, d2) and torch.equal(num, n2)
+    assert float((dw - dw2).abs().max()) <= 1e-6          # same kernels; float atomics may land in another order
+    o = oracle.numerator(cfg["w"], cfg["lengths"], cfg["refs"], cfg["ref_lengths"], order)
+    gden = oracle.posteriors(cfg["w"], cfg["lengths"], order)
+    gnum = oracle.numerator_posteriors_dense(o, cfg["refs"], cfg["ref_lengths"], cfg["w"].shape)
+    assert np.max(np.abs(dw.cpu().numpy() - (gden - gnum))) <= 2 * TOL_POST_ABS
+    assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
+    # scale and accumulate; several calls in a row on the same stream
+    acc = torch.full_like(w, 0.25)
+    for _ in range(3):
+        lb.last_globally_normalized_loss(w, lengths, refs, ulen, order=g_order, dw=acc, scale=0.5, accumulate=True)
+    assert np.max(np.abs(acc.cpu().numpy() - (0.25 + 1.5 * (gden - gnum)))) <= 4 * TOL_POST_ABS
+    return st.cpu().numpy()
+
+
+def test_loss_in_one_call():
+    announce("loss in one call: config 3 reduced (clustered denominator), B=4 T=60 V=256")
+    cfg = workloads.config(3, B=4, T=60, V=256, Umax=30, u_lo=5, u_hi=30)
+    assert np.all(check_loss_one_call(cfg) == 0)
+    announce("loss in one call: context size 2, B=2 T=20 V=5")
+    cfg = workloads.config(3, B=2, T=20, V=5, order=2, Umax=12, u_lo=3, u_hi=12)
+    assert np.all(check_loss_one_call(cfg, order=2) == 0)
+    announce("loss in one call: status of either part")
+    cfg = workloads.config(3, B=4, T=10, V=6, Umax=12, u_lo=1, u_hi=5)
+    cfg["lengths"] = np.array([10, 11, 4, 10], np.int32)
+    cfg["ref_lengths"] = np.array([3, 2, 5, 13], np.int32)
+    st = torch.full((4,), -1, dtype=torch.int32, device="cuda")
+    dist, num, dw = lb.last_globally_normalized_loss(dev(cfg["w"]), dev(cfg["lengths"]), dev(cfg["refs"]),
+                                                     dev(cfg["ref_lengths"]), item_status=st)
+    assert st.cpu().tolist() == [0, 1, 4, 3]
+    assert torch.isnan(dist[1]) and float(num[2]) == -np.inf and torch.isnan(num[3])
