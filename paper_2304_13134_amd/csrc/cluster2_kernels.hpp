@@ -854,7 +854,7 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
         __syncthreads();
         if (!met) meet();
         if (tid == 0 && ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
-        if (g.k == 0 && tid == 0 && (ctl_s[8] || dead) && a.item_status && !bad) a.item_status[b] = kItemTimeout;
+        if (tid == 0) cluster_finish_item(a, b, ctl_s[8] != 0 || dead != 0, bad, 2 * a.K);
         __syncthreads();
     }
 }
@@ -1341,6 +1341,7 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
         if (xwide > kC2RangeBits) ctl_s[11] = 1;
         __syncthreads();
         if (tid == 0 && ctl_s[11] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
+        if (tid == 0) cluster_finish_item(a, b, ctl_s[8] != 0 || dead != 0, bad, 2 * a.K);
         __syncthreads();
     }
 }

@@ -30,6 +30,7 @@ struct ClusterVArgs {
     float* score;
     int* item_status;
     u64* xa;
+    u64* fin;            // [B][2], cleared to ~0: workgroups through with the item, time-out mark
     int B, T, C, K, RPW, ncl;
     int spin_limit;
 };
@@ -355,6 +356,24 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                 a.score[b] = (bad || tmo) ? __builtin_nanf("") : best;
                 if (a.final_state) a.final_state[b] = (bad || tmo) ? -1 : bidx;
                 if (a.item_status) a.item_status[b] = bad ? kItemBadLength : (tmo ? kItemTimeout : kItemOk);
+            }
+        }
+        __syncthreads();
+        // a time-out of any workgroup voids the item: the last workgroup through looks at the mark
+        if (tid == 0) {
+            u64* fin = a.fin + (size_t)b * 2;
+            if (ctl_s[8] != 0 || dead) __hip_atomic_store(fin + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence();
+            const u64 old = __hip_atomic_fetch_add(fin, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == (u64)(K - 2)) {
+                __threadfence();
+                if (__hip_atomic_load(fin + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ~0ull && !bad) {
+                    __hip_atomic_store(a.score + b, __builtin_nanf(""), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (a.final_state)
+                        __hip_atomic_store(a.final_state + b, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (a.item_status)
+                        __hip_atomic_store(a.item_status + b, (int)kItemTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
         __syncthreads();

@@ -289,25 +289,6 @@ __device__ __forceinline__ double c3_meeting(const uint2* ah, const uint2* bh, f
     return (double)xmax + (double)__log2f(tot);
 }
 
-// When the last workgroup of an item is through: an item on which any workgroup gave up waiting gets
-// dist = NaN and status 5, whoever wrote dist before.  fin: [B][2] words, cleared to ~0 before the launch:
-// [0] counts the workgroups that are through, [1] is written by a workgroup that timed out.
-__device__ __forceinline__ void c3_finish_item(const ClusterArgs& a, int b, bool timed_out, bool bad)
-{
-    u64* fin = a.fin + (size_t)b * 2;
-    if (timed_out) __hip_atomic_store(fin + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __threadfence();
-    const u64 old = __hip_atomic_fetch_add(fin, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == (u64)(2 * kC3K - 2)) {
-        __threadfence();
-        if (__hip_atomic_load(fin + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ~0ull && !bad) {
-            __hip_atomic_store(a.dist + b, __builtin_nanf(""), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (a.item_status)
-                __hip_atomic_store(a.item_status + b, (int)kItemTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-
 // Geometry shared by both roles (see the patterns at the top of the file).
 struct C3Geom {
     int lane, wave, k, u;
@@ -789,7 +770,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         __syncthreads();
         if (tid == 0) {
             if (ctl_s[2] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
-            c3_finish_item(a, b, ctl_s[1] != 0, bad);
+            cluster_finish_item(a, b, ctl_s[1] != 0, bad, 2 * kC3K);
         }
         __syncthreads();
     }
@@ -1144,7 +1125,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         __syncthreads();
         if (tid == 0) {
             if (ctl_s[2] && a.item_status && !bad) atomicMax(&a.item_status[b], (int)kItemRange);
-            c3_finish_item(a, b, ctl_s[1] != 0, bad);
+            cluster_finish_item(a, b, ctl_s[1] != 0, bad, 2 * kC3K);
         }
         __syncthreads();
     }

@@ -295,6 +295,26 @@ __device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const Cluster
     __threadfence();
 }
 
+// Called by one thread of every workgroup of an item (nwg of them) when it is through with the item.
+// An item on which any workgroup gave up waiting gets dist = NaN and status 5, whoever wrote dist
+// before: the last workgroup through looks at the mark.  fin: [B][2] words, cleared to ~0 before the
+// launch: [0] counts the workgroups that are through, [1] is written by a workgroup that timed out.
+__device__ __forceinline__ void cluster_finish_item(const ClusterArgs& a, int b, bool timed_out, bool bad, int nwg)
+{
+    u64* fin = a.fin + (size_t)b * 2;
+    if (timed_out) __hip_atomic_store(fin + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    const u64 old = __hip_atomic_fetch_add(fin, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == (u64)(nwg - 2)) {
+        __threadfence();
+        if (__hip_atomic_load(fin + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ~0ull && !bad) {
+            __hip_atomic_store(a.dist + b, __builtin_nanf(""), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.item_status)
+                __hip_atomic_store(a.item_status + b, (int)kItemTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // D at the meeting frame: (Sa_mid + Sb_mid) + log2 sum_q ahat_mid[q] bhat_mid[q], in units of ln 2.
 // Called by every thread of the workgroup (contains workgroup barriers).
 __device__ __forceinline__ double meeting_value(const float* ah, const float* bh, const int* Sa,
@@ -573,7 +593,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
         }
         __syncthreads();
-        if (g.k == 0 && tid == 0 && ctl_s[40] && a.item_status && !bad) a.item_status[b] = kItemTimeout;
+        if (tid == 0) cluster_finish_item(a, b, ctl_s[40] != 0, bad, 2 * a.K);
         __syncthreads();
     }
 }
@@ -818,6 +838,8 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
             if (!step(std::integral_constant<int, 2>())) break;
             if constexpr (D > 3) { if (!step(std::integral_constant<int, 3>())) break; }
         }
+        __syncthreads();
+        if (tid == 0) cluster_finish_item(a, b, ctl_s[40] != 0, bad, 2 * a.K);
         __syncthreads();
     }
 }

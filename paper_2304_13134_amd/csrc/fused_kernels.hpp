@@ -485,7 +485,9 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             float s = (mine && mx != LAST_NEG_INF) ? __expf(v - mx) : 0.f;
             s = block_sum(s, red);
             if (tid == 0) {
-                a.part[(size_t)item * V + (b - 1)] = (mx == LAST_NEG_INF) ? LAST_NEG_INF : mx + __logf(s);
+                // a workgroup that gave up waiting marks its part: the item's distance becomes NaN
+                a.part[(size_t)item * V + (b - 1)] = ctl_s[0] ? __builtin_nanf("")
+                                                     : (mx == LAST_NEG_INF) ? LAST_NEG_INF : mx + __logf(s);
                 if (b == 1) {
                     a.Aend[item] = bad ? __builtin_nan("") : A;
                     if (a.item_status) a.item_status[item] = bad ? kItemBadLength : (ctl_s[0] ? kItemTimeout : kItemOk);
@@ -496,20 +498,28 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
 }
 
-// D[item] = offset + log-sum-exp over the workgroups' partial values
+// D[item] = offset + log-sum-exp over the workgroups' partial values; NaN and status 5 when a
+// workgroup of the item timed out (its part is NaN)
 __global__ void fused_finalize_kernel(const float* __restrict__ part, const double* __restrict__ Aend,
-                                      int B, int V, float* __restrict__ dist, double* __restrict__ Dws)
+                                      int B, int V, float* __restrict__ dist, double* __restrict__ Dws,
+                                      int* __restrict__ item_status)
 {
     const int item = blockIdx.x * blockDim.x + threadIdx.x;
     if (item >= B) return;
     const double A = Aend[item];
     float mx = LAST_NEG_INF;
-    for (int j = 0; j < V; ++j) mx = fmaxf(mx, part[(size_t)item * V + j]);
+    bool tmo = false;
+    for (int j = 0; j < V; ++j) {
+        const float p = part[(size_t)item * V + j];
+        tmo = tmo || p != p;
+        mx = fmaxf(mx, p);
+    }
     float s = 0.f;
     for (int j = 0; j < V; ++j) s += expf(part[(size_t)item * V + j] - mx);
-    const double D = (A != A) ? __builtin_nan("") : A + (double)mx + (double)logf(s);
+    const double D = (A != A || tmo) ? __builtin_nan("") : A + (double)mx + (double)logf(s);
     dist[item] = (float)D;
     if (Dws) Dws[item] = D;
+    if (tmo && A == A && item_status) item_status[item] = kItemTimeout;
 }
 
 // ---------------------------------------------------------------------------
@@ -537,6 +547,7 @@ struct FusedBwdArgs {
     float* dW;               // [H][V+1]
     float scale;
     int* item_status;
+    float* dist;             // [B]: set to NaN for an item on which a workgroup gave up waiting
     u64* xb;
     int B, T, V, H, C;
     int ncl, XW;
@@ -813,8 +824,12 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             gstep += 1;
             lds_barrier();
         }
-        if (any_dead && b == 1 && tid == 0 && a.item_status && a.item_status[item] == kItemOk)
-            a.item_status[item] = kItemTimeout;
+        // any workgroup that gave up waiting voids the item (its gradients are wrong): status 5, dist NaN
+        if (any_dead && tid == 0 && a.len[item] >= 0 && a.len[item] <= a.T) {
+            if (a.item_status)
+                __hip_atomic_store(a.item_status + item, (int)kItemTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.dist + item, __builtin_nanf(""), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     // de: rows of different clusters (items) add up
 #pragma unroll

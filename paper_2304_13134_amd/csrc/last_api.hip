@@ -501,12 +501,12 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
                            dim3(kFuThreads), p.lds, st, a);
     });
     hipLaunchKernelGGL(fused_finalize_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st,
-                       (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D);
+                       (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D, item_status);
     return hip_status();
 }
 
 // beta recursion + gradients of the fused path; the forward pass (with alpha kept) has been enqueued
-last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const FusedWs& f,
+last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const FusedWs& f, float* dist,
                                     const last_weights_t* wt, const int* lengths, const last_grads_t* out,
                                     int* item_status, hipStream_t st)
 {
@@ -522,7 +522,7 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
     a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.Wf = f.Wf; a.Wt = f.Wt;
     a.len = lengths; a.alpha_ws = f.alpha; a.offs = f.offs; a.Dws = f.D; a.beta_ws = f.beta;
     a.df = out->df; a.de = out->de; a.dW = out->dW; a.scale = out->scale;
-    a.item_status = item_status; a.xb = f.xb;
+    a.item_status = item_status; a.dist = dist; a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = H; a.C = s.C;
     a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = opt(LAST_OPT_SPIN_LIMIT); a.nch = p.nch; a.TC = p.TC;
     fused_dispatch(p.MT, [&](auto MT) {
@@ -577,7 +577,7 @@ ViterbiPlan viterbi_plan(const Shape& s, int kind)
     const int want = (s.B + 7) / 8;
     p.ncl = want < max_ncl ? want : max_ncl;
     p.grid = 8 * p.ncl * p.K;
-    p.xwords = (size_t)8 * p.ncl * 2 * kClMaxK * kC2XS;
+    p.xwords = (size_t)8 * p.ncl * 2 * kClMaxK * kC2XS + (size_t)2 * s.B;    // exchange slots + per-item end words
     p.ok = true;
     return p;
 }
@@ -588,7 +588,7 @@ void launch_cluster_viterbi(const Shape& s, const ViterbiPlan& p, u64* xv, const
     hipLaunchKernelGGL(cluster_clear_kernel, dim3(64), dim3(256), 0, st, xv, p.xwords);
     ClusterVArgs a;
     a.w = w; a.len = lengths; a.bp = bp; a.final_state = final_state; a.score = score;
-    a.item_status = item_status; a.xa = xv;
+    a.item_status = item_status; a.xa = xv; a.fin = xv + (p.xwords - (size_t)2 * s.B);
     a.B = s.B; a.T = s.T; a.C = s.C; a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl;
     a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     const bool full = p.K == kClMaxK;      // (the instantiation without a test per exchanged word)
@@ -817,7 +817,7 @@ last_status_t last_arc_posteriors(const last_weights_t* weights, const int32_t* 
         const FusedWs fw = carve_fused(cvf, s, fp, true);
         rc = launch_fused_forward(s, fp, fw, weights, lengths, dist, item_status, true, (hipStream_t)hip_stream);
         if (rc != LAST_OK) return rc;
-        return launch_fused_backward(s, fp, fw, weights, lengths, out, item_status, (hipStream_t)hip_stream);
+        return launch_fused_backward(s, fp, fw, dist, weights, lengths, out, item_status, (hipStream_t)hip_stream);
     }
     if (weights->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
     if (!out->dw) return LAST_ERR_NULL;

@@ -266,3 +266,28 @@ def test_fused_loss_in_one_call():
     assert np.array_equal(d1.cpu().numpy(), D) and np.array_equal(n1.cpu().numpy(), N)
     for name, a, b in zip(("df", "de", "dW"), g1, grads):
         assert_grad_close(name, a.cpu().numpy(), b.astype(np.float64))
+
+
+def test_fused_bounded_waits_end_every_kernel_and_are_reported():
+    """Spin limit of one poll on the fused kernels: every kernel ends, items that gave up carry status 5."""
+    from gpu_util import library_option
+    announce("spin limit 1, fused forward-backward")
+    s = workloads.shared_emb(B=3, T=12, V=6, order=2, H=256, seed=77)
+    se, lengths = fused_inputs(s), torch.from_numpy(s["lengths"]).cuda()
+    with library_option(lb.OPT_SPIN_LIMIT, 1):
+        st = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+        dist, grads = lb.last_arc_posteriors(se, lengths, order=2, item_status=st)
+        torch.cuda.synchronize()
+    st = st.cpu().numpy()
+    assert set(st.tolist()) <= {0, 5}
+    o = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=False)
+    for b in range(3):
+        if st[b] == 0:
+            assert abs(float(dist[b]) - o["D"][b]) <= 1e-5 * abs(o["D"][b])
+        else:
+            assert torch.isnan(dist[b])
+    st2 = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+    dist2 = lb.last_shortest_distance(se, lengths, order=2, item_status=st2)
+    torch.cuda.synchronize()
+    assert st2.cpu().tolist() == [0, 0, 0]
+    assert_dist_close(dist2.cpu().numpy(), o["D"])

@@ -437,3 +437,48 @@ def test_loss_in_one_call():
                                                      dev(cfg["ref_lengths"]), item_status=st)
     assert st.cpu().tolist() == [0, 1, 4, 3]
     assert torch.isnan(dist[1]) and float(num[2]) == -np.inf and torch.isnan(num[3])
+
+
+# ------------------------------------------------ bounded waits, driven from the host
+def test_bounded_waits_end_every_kernel_and_are_reported():
+    """With a spin limit of one poll the cooperating workgroups give up waiting for each other almost
+    at once: every kernel must still end, every item must either be right or carry status 5 and NaN,
+    and the next call with the normal limit must be right again."""
+    cfg = workloads.dense(B=6, T=24, V=256, order=1, sigma=2.0, seed=4242, len_lo=20, len_hi=24)
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    _, D_o = oracle.forward(cfg["w"], cfg["lengths"], 1)
+    gamma_o = oracle.posteriors(cfg["w"], cfg["lengths"], 1)
+    l_o, s_o, sc_o = oracle.viterbi(cfg["w"], cfg["lengths"], 1, "f32")
+    seen_timeouts = 0
+    for generation in (3, 2, 1):
+        announce("spin limit 1, clustered forward-backward, generation", generation)
+        with library_option(lb.OPT_CLUSTER_GENERATION, generation), library_option(lb.OPT_SPIN_LIMIT, 1):
+            st = torch.full((6,), -1, dtype=torch.int32, device="cuda")
+            dist, dw = lb.last_arc_posteriors(w, lengths, item_status=st)
+            torch.cuda.synchronize()
+        st, dist, dw = st.cpu().numpy(), dist.cpu().numpy(), dw.cpu().numpy()
+        assert set(st.tolist()) <= {0, 5}
+        for b in range(6):
+            if st[b] == 5:
+                assert np.isnan(dist[b])
+                seen_timeouts += 1
+            else:
+                assert abs(dist[b] - D_o[b]) <= 1e-5 * abs(D_o[b])
+                assert np.max(np.abs(dw[b] - gamma_o[b])) <= TOL_POST_ABS
+    announce("spin limit 1, clustered shortest path")
+    with library_option(lb.OPT_SPIN_LIMIT, 1):
+        st = torch.full((6,), -1, dtype=torch.int32, device="cuda")
+        labels, states, score = lb.last_shortest_path(w, lengths, item_status=st)
+        torch.cuda.synchronize()
+    st = st.cpu().numpy()
+    assert set(st.tolist()) <= {0, 5}
+    for b in range(6):
+        if st[b] == 5:
+            assert torch.isnan(score[b]) and torch.all(labels[b] == -1) and torch.all(states[b] == -1)
+            seen_timeouts += 1
+        else:
+            assert np.array_equal(labels[b].cpu().numpy(), l_o[b]) and float(score[b]) == sc_o[b]
+    assert seen_timeouts > 0, "the bounded-wait path was not exercised"
+    announce("normal spin limit again")
+    check_posteriors(cfg)
+    check_path(cfg)
