@@ -143,14 +143,22 @@ PosteriorWs carve_posteriors(Carver& cv, const Shape& s)
 struct PathWs {
     int* bp;
     int* final_state;
+    int* map;            // backtrace: [B][nseg][C] state at the lower end of a segment, by state at its upper end
+    int* bnd;            // backtrace: [B][nseg+1] states of the path at the segment boundaries
+    int S, nseg;         // frames per segment (about sqrt(T)), number of segments
     u64* xv;             // exchange buffer of the clustered tropical kernel (xwords > 0)
 };
 
 PathWs carve_path(Carver& cv, const Shape& s, size_t xwords)
 {
     PathWs p;
+    p.S = 8;
+    while (p.S * p.S < s.T) ++p.S;
+    p.nseg = s.T > 0 ? (s.T + p.S - 1) / p.S : 1;
     p.bp = cv.take<int>((size_t)s.B * (s.T > 0 ? s.T : 1) * s.C);
     p.final_state = cv.take<int>((size_t)s.B);
+    p.map = cv.take<int>((size_t)s.B * p.nseg * s.C);
+    p.bnd = cv.take<int>((size_t)s.B * (p.nseg + 1));
     p.xv = xwords ? cv.take<u64>(xwords) : nullptr;
     return p;
 }
@@ -1163,8 +1171,14 @@ last_status_t last_shortest_path(const last_weights_t* weights, const int32_t* l
     else if (!launch_bigram_viterbi(s, weights->w, lengths, p.bp, p.final_state, score, item_status, st))
         hipLaunchKernelGGL(solo_viterbi, dim3(s.B), dim3(1024), l.lds_viterbi, st, weights->w, lengths,
                            c, s.T, l.CPAD, l.R, p.bp, p.final_state, score, item_status);
-    hipLaunchKernelGGL(backtrace_kernel, dim3(s.B), dim3(256), 0, st, (const int*)p.bp, lengths,
-                       (const int*)p.final_state, s.C, s.V1, s.T, labels, states);
+    const int cthreads = s.C < 256 ? (s.C + 63) / 64 * 64 : 256;
+    hipLaunchKernelGGL(backtrace_compose_kernel, dim3(p.nseg, s.B), dim3(cthreads), 0, st, (const int*)p.bp,
+                       lengths, s.C, s.V1, s.T, p.S, p.nseg, p.map);
+    hipLaunchKernelGGL(backtrace_boundaries_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st, (const int*)p.map,
+                       lengths, (const int*)p.final_state, s.B, s.C, s.T, p.S, p.nseg, p.bnd);
+    hipLaunchKernelGGL(backtrace_emit_kernel, dim3(p.nseg, s.B), dim3(64), 0, st, (const int*)p.bp, lengths,
+                       (const int*)p.final_state, (const int*)p.bnd, s.C, s.V1, s.T, p.S, p.nseg, labels,
+                       states);
     return hip_status();
 }
 

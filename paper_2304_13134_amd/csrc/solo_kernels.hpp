@@ -403,25 +403,84 @@ __global__ __launch_bounds__(1024) void bigram_viterbi(
     }
 }
 
-// Follow the backpointers from the best final state (the 0/1 arc mask of the
-// tropical gradient, Section 2.3, returned as indices).
-__global__ void backtrace_kernel(const int* __restrict__ bp, const int* __restrict__ len,
-                                 const int* __restrict__ final_state, int C, int V1, int T,
-                                 int* __restrict__ labels, int* __restrict__ states)
+// Follow the backpointers from the best final state (the 0/1 arc mask of the tropical gradient,
+// Section 2.3, returned as indices).  A walk of len dependent loads would take len memory latencies,
+// so the frames are cut into segments of S:
+//   1. compose: for every segment and every state at its upper end, the state at its lower end
+//      (S dependent loads, all segments and states in parallel);
+//   2. boundaries: one thread per item hops from segment to segment (len/S dependent loads);
+//   3. emit: every segment is walked once more from its now known upper state, writing labels
+//      and states; frames past the length get -1.
+// map [B][nseg][C], bnd [B][nseg+1].  An item without a path (invalid length, final state -1) gets
+// -1 everywhere.  States read from bp are clamped into range: whatever the array holds, no access
+// leaves it.
+__device__ __forceinline__ int bt_prev_state(int arc, int V1, int C)
 {
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int q = arc / V1;
+    return q < 0 ? 0 : (q >= C ? C - 1 : q);
+}
+
+__global__ void backtrace_compose_kernel(const int* __restrict__ bp, const int* __restrict__ len, int C, int V1,
+                                         int T, int S, int nseg, int* __restrict__ map)
+{
+    const int s = blockIdx.x, b = blockIdx.y;
+    const int L = len[b];
+    if (L < 0 || L > T) return;
+    const int t0 = s * S;
+    const int t1 = t0 + S < L ? t0 + S : L;          // states at frame t1 -> states at frame t0
+    if (t0 >= L) return;
+    for (int q0 = threadIdx.x; q0 < C; q0 += blockDim.x) {
+        int q = q0;
+        for (int t = t1 - 1; t >= t0; --t) q = bt_prev_state(bp[((size_t)b * T + t) * C + q], V1, C);
+        map[((size_t)b * nseg + s) * C + q0] = q;
+    }
+}
+
+__global__ void backtrace_boundaries_kernel(const int* __restrict__ map, const int* __restrict__ len,
+                                            const int* __restrict__ final_state, int B, int C, int T, int S,
+                                            int nseg, int* __restrict__ bnd)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int L = len[b];
+    int q = final_state[b];
+    if (L < 0 || L > T || q < 0) return;
+    q = q >= C ? C - 1 : q;
+    const int last = L > 0 ? (L - 1) / S : -1;
+    for (int s = last; s >= 0; --s) {
+        bnd[(size_t)b * (nseg + 1) + s + 1] = q;          // state at the upper end of segment s
+        q = map[((size_t)b * nseg + s) * C + q];
+    }
+    bnd[(size_t)b * (nseg + 1)] = q;
+}
+
+__global__ void backtrace_emit_kernel(const int* __restrict__ bp, const int* __restrict__ len,
+                                      const int* __restrict__ final_state, const int* __restrict__ bnd,
+                                      int C, int V1, int T, int S, int nseg,
+                                      int* __restrict__ labels, int* __restrict__ states)
+{
+    const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     int L = len[b];
     if (L < 0 || L > T || final_state[b] < 0) L = -1;   // no path was found for this item: all -1
-    for (int t = tid; t < T; t += blockDim.x)
+    const int t0 = s * S;
+    // padding of this segment's frames (and, by the last segment, of the last state)
+    for (int t = t0 + tid; t < t0 + S && t < T; t += blockDim.x) {
         if (t >= L) labels[(size_t)b * T + t] = -1;
-    for (int t = tid; t <= T; t += blockDim.x)
         if (t > L) states[(size_t)b * (T + 1) + t] = -1;
+    }
+    if (s == nseg - 1 && tid == 0 && T > L) states[(size_t)b * (T + 1) + T] = -1;
     if (tid != 0 || L < 0) return;
-    int q = final_state[b];
-    states[(size_t)b * (T + 1) + L] = q;
-    for (int t = L - 1; t >= 0; --t) {
+    if (L == 0) {
+        if (s == 0) states[(size_t)b * (T + 1)] = bnd[(size_t)b * (nseg + 1)];
+        return;
+    }
+    if (t0 >= L) return;
+    const int t1 = t0 + S < L ? t0 + S : L;
+    int q = bnd[(size_t)b * (nseg + 1) + s + 1];
+    if (t1 == L) states[(size_t)b * (T + 1) + L] = q;
+    for (int t = t1 - 1; t >= t0; --t) {
         const int arc = bp[((size_t)b * T + t) * C + q];
-        q = arc / V1;
+        q = bt_prev_state(arc, V1, C);
         labels[(size_t)b * T + t] = arc - q * V1;
         states[(size_t)b * (T + 1) + t] = q;
     }
