@@ -87,8 +87,9 @@ static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl 
 #endif
 
 // Weight loads use the default cache policy although every weight is read once per pass: with the
-// non-temporal hint the kernel was measured 2.5 % slower (neighbouring workgroups share the cache
-// lines at the ends of their row pieces, and a plain read sweep is what gains from the hint).
+// non-temporal hint on all of them the kernel was measured 2.5 % slower (neighbouring workgroups share
+// the cache lines at the ends of their row pieces), with the hint on the row-contiguous frames only it
+// ran at the same speed; a plain read sweep is what gains from the hint.
 constexpr int kC3WeightPolicy = 0;
 __device__ __forceinline__ float4 c3_wload4(buf_t r, unsigned voff, unsigned soff)
 {

@@ -198,10 +198,31 @@ struct ClusterPlan {
     int K, RPW, ncl, XS, XSB, grid;
 };
 
+// The cooperating-workgroup kernels spin on each other: every workgroup of a launch must be resident
+// at once, one per compute unit, on a chip of eight XCDs of 32 compute units each (a cluster of an
+// item sits on the XCD its workgroup ids select).  Anything else takes the one-workgroup kernels.
+// (Without a device, e.g. when only sizes are asked for on a build machine, the layout is assumed.)
+bool chip_takes_clusters()
+{
+    static std::mutex mu;
+    static int cached[64] = {};            // 0 unknown, 1 yes, 2 no
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return true; }
+    if (dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cached[dev]) {
+        int cus = 0;
+        const hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) (void)hipGetLastError();
+        cached[dev] = (e == hipSuccess && cus >= 256) ? 1 : 2;
+    }
+    return cached[dev] == 1;
+}
+
 ClusterPlan cluster_plan(const Shape& s, int kind)
 {
     ClusterPlan p{};
-    if (opt(LAST_OPT_FORCE_SOLO)) return p;
+    if (opt(LAST_OPT_FORCE_SOLO) || !chip_takes_clusters()) return p;
     if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kClMaxC || s.C < 5 || s.T < 1) return p;   // (tiny label sets: one workgroup per item)
     // one item must fit a 32-bit buffer descriptor
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;
@@ -417,7 +438,7 @@ void fused_dispatch(int MT, F&& f)
 FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
 {
     FusedPlan p{};
-    if (wt->kind != LAST_WEIGHTS_SHARED_EMB || s.order != 2) return p;
+    if (wt->kind != LAST_WEIGHTS_SHARED_EMB || s.order != 2 || !chip_takes_clusters()) return p;
     const int H = wt->hidden;
     if (s.V > 64 || H % kFuKC != 0 || H < kFuKC || H > 512) return p;
     // the kernels fetch f and e with 16-byte loads
@@ -572,7 +593,7 @@ struct ViterbiPlan {
 ViterbiPlan viterbi_plan(const Shape& s, int kind)
 {
     ViterbiPlan p{};
-    if (opt(LAST_OPT_FORCE_SOLO) || !opt(LAST_OPT_CLUSTER_VITERBI)) return p;
+    if (opt(LAST_OPT_FORCE_SOLO) || !opt(LAST_OPT_CLUSTER_VITERBI) || !chip_takes_clusters()) return p;
     if (kind != LAST_WEIGHTS_DENSE || s.order != 1 || s.C > kC2Hdr || s.T < 1) return p;
     if ((double)s.T * s.C * s.C * sizeof(float) >= 4.0e9) return p;      // one 32-bit buffer descriptor per item
     if ((size_t)s.C * s.C >= (size_t)kVNone) return p;                    // 17-bit arc indices in the exchange
