@@ -349,6 +349,35 @@ def test_config2_full_size_sampled_marginals_and_invariants(config3_full):
     assert torch.all(dw[:, 0, 1:, :] == 0)
 
 
+def test_config2_and_3_full_size_every_element(config3_full):
+    """All 5.28e8 arc marginals of config 2 and the whole loss gradient of config 3 against the
+    oracle's dense tensors, item by item (the oracle's forward and backward weights are reused)."""
+    announce("configs 2 and 3 full size: every marginal and every element of the loss gradient")
+    cfg, alpha, beta, D_o = config3_full
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    refs, ulen = dev(cfg["refs"]), dev(cfg["ref_lengths"])
+    dist, dw = lb.last_arc_posteriors(w, lengths)
+    d2, num, gl = lb.last_globally_normalized_loss(w, lengths, refs, ulen)
+    torch.cuda.synchronize()
+    o = oracle.numerator(cfg["w"], cfg["lengths"], cfg["refs"], cfg["ref_lengths"], 1)
+    worst_den = worst_loss = 0.0
+    for b in range(cfg["B"]):
+        sl = slice(b, b + 1)
+        gamma = oracle.posteriors(cfg["w"][sl], cfg["lengths"][sl], 1, alpha[sl], beta[sl], D_o[sl])
+        got = dw[b].cpu().numpy()
+        worst_den = max(worst_den, float(np.max(np.abs(got - gamma[0]))))
+        assert np.all(got[gamma[0] == 0.0] == 0.0)
+        one = dict(ctx=o["ctx"][sl], pb=o["pb"][sl], pl=o["pl"][sl])
+        gnum = oracle.numerator_posteriors_dense(one, cfg["refs"][sl], cfg["ref_lengths"][sl], gamma.shape)
+        worst_loss = max(worst_loss, float(np.max(np.abs(gl[b].cpu().numpy() - (gamma[0] - gnum[0])))))
+        del gamma, gnum, got
+    announce("largest deviation: marginals %.3g, loss gradient %.3g" % (worst_den, worst_loss))
+    assert worst_den <= TOL_POST_ABS
+    assert worst_loss <= 2 * TOL_POST_ABS
+    assert_dist_close(d2.cpu().numpy(), D_o)
+    assert_dist_close(num.cpu().numpy(), o["N"], "numerator")
+
+
 def test_config2_full_size_shortest_path(config3_full):
     announce("config 2 full size: tropical shortest path, bit-exact indices")
     cfg, _, _, _ = config3_full
