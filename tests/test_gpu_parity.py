@@ -511,3 +511,13 @@ def test_bounded_waits_end_every_kernel_and_are_reported():
     announce("normal spin limit again")
     check_posteriors(cfg)
     check_path(cfg)
+
+
+def test_dense_context_size_2_with_more_than_1024_states():
+    # 32 labels, context size 2: 1057 states, more than the 1024 threads of the one-workgroup kernels
+    # (the state loop takes a second sweep); the lattice of the paper's Table 2 with dense weights
+    announce("dense weights, context size 2, V=32 (C=1057), B=2 T<=9")
+    cfg = workloads.config(3, B=2, T=9, V=32, order=2, Umax=6, u_lo=2, u_hi=6, len_lo=6, len_hi=9)
+    check_posteriors(cfg, order=2)
+    check_path(cfg, order=2)
+    assert np.all(check_loss(cfg, order=2) == 0)
