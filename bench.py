@@ -159,11 +159,18 @@ def main():
     k = max(5, args.steps // 2)
     read_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_READ, w, dw), k, 2)
     copy_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_COPY, w, dw), k, 2)
-    ceilings = {"read_sweep_ms": read_ms, "read_sweep_GBs": wbytes / read_ms / 1e6,
+    ceilings = {}
+    if cfg["C"] == 257:
+        # the kernel's two read patterns without its arithmetic (rows per wavefront / column blocks per workgroup)
+        rows_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_READ_ROWS, w, dw), k, 2)
+        cols_ms, _ = time_region(lambda: lb.last_probe_bandwidth(lb.PROBE_READ_COLUMNS, w, dw), k, 2)
+        ceilings.update({"read_rows_pattern_GBs": wbytes / rows_ms / 1e6,
+                         "read_column_blocks_pattern_GBs": wbytes / cols_ms / 1e6})
+    ceilings.update({"read_sweep_ms": read_ms, "read_sweep_GBs": wbytes / read_ms / 1e6,
                 "copy_ms": copy_ms, "copy_GBs": 2 * wbytes / copy_ms / 1e6,
                 # forward+backward = one read-only pass + one read-and-write pass over the weights
                 "read_plus_copy_ms": read_ms + copy_ms,
-                "frac_of_read_plus_copy": (read_ms + copy_ms) / ms}
+                "frac_of_read_plus_copy": (read_ms + copy_ms) / ms})
 
     extra = {}
     if not args.no_extra:

@@ -270,8 +270,14 @@ int32_t last_get_option(int32_t option);
  * src (dev) once and writes nothing (dst: dev, at least 16 bytes, left
  * untouched); LAST_PROBE_COPY copies them to dst (dev, `bytes` bytes, must not
  * overlap src).  bytes a positive multiple of 16, both pointers 16-byte
- * aligned (LAST_ERR_SHAPE otherwise). */
-enum { LAST_PROBE_READ = 0, LAST_PROBE_COPY = 1 };
+ * aligned (LAST_ERR_SHAPE otherwise).  LAST_PROBE_READ_ROWS and
+ * LAST_PROBE_READ_COLUMNS read src, taken as frames of [257][257] float32
+ * (bytes a multiple of 257*257*4), once in the two access patterns of the
+ * bigram forward-backward kernel at 256 labels, with its launch shape and none
+ * of its arithmetic: whole rows per wavefront, or blocks of 32 columns per
+ * workgroup (128-byte pieces at a stride of 1028 bytes); dst as for
+ * LAST_PROBE_READ. */
+enum { LAST_PROBE_READ = 0, LAST_PROBE_COPY = 1, LAST_PROBE_READ_ROWS = 2, LAST_PROBE_READ_COLUMNS = 3 };
 last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream);
 
 const char* last_status_string(last_status_t status);

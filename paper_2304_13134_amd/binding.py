@@ -27,7 +27,7 @@ EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posterior
            "last_version", "last_kernel_variant", "last_hip_error_string",
            "last_shortest_distance_static", "last_set_option", "last_get_option",
            "last_local_log_likelihood", "last_probe_bandwidth", "last_globally_normalized_loss"]
-PROBE_READ, PROBE_COPY = 0, 1
+PROBE_READ, PROBE_COPY, PROBE_READ_ROWS, PROBE_READ_COLUMNS = 0, 1, 2, 3
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 32 << 20
 

@@ -660,8 +660,20 @@ last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, siz
     if (!src || !dst) return LAST_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0 || (uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0)
         return LAST_ERR_SHAPE;
-    if (kind != LAST_PROBE_READ && kind != LAST_PROBE_COPY) return LAST_ERR_UNSUPPORTED;
+    if (kind < LAST_PROBE_READ || kind > LAST_PROBE_READ_COLUMNS) return LAST_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (kind == LAST_PROBE_READ_ROWS || kind == LAST_PROBE_READ_COLUMNS) {
+        const size_t frame = (size_t)257 * 257 * 4;
+        if (bytes % frame != 0 || bytes / frame > 0x7fffffffull) return LAST_ERR_SHAPE;
+        const int nframes = (int)(bytes / frame);
+        if (kind == LAST_PROBE_READ_ROWS)
+            hipLaunchKernelGGL(probe_pattern_kernel<false>, dim3(256), dim3(512), 0, st, (const float*)src, nframes,
+                               (float*)dst);
+        else
+            hipLaunchKernelGGL(probe_pattern_kernel<true>, dim3(256), dim3(512), 0, st, (const float*)src, nframes,
+                               (float*)dst);
+        return hip_status();
+    }
     const size_t n4 = bytes / 16;
     const size_t copy_grid = (n4 + kProbeThreads - 1) / kProbeThreads;
     if (copy_grid > 0x7fffffffull) return LAST_ERR_SHAPE;

@@ -45,4 +45,34 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const probe_f
     if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
+// The two read patterns of the bigram forward-backward kernel at 256 labels, without its arithmetic: the
+// tensor is taken as frames of [257][257] floats; 32 groups of 8 workgroups of 8 waves walk the frames;
+// each lane has four 16-byte loads in flight and every element is read once.
+//   COLUMNS: workgroup k of a group reads columns 32k .. 32k+31 of every row: pieces of 128 bytes at a
+//            stride of 1028 bytes (wave w: rows 32w .. 32w+31, eight rows per instruction);
+//   ROWS   : wave w of workgroup k reads rows 1+4u .. 4+4u, u = 8k + w: 4112 contiguous bytes.
+// (Row 0 / the last row and column are left out: a yardstick, not a checksum.)
+template <bool COLUMNS>
+__global__ __launch_bounds__(512) void probe_pattern_kernel(const float* __restrict__ w, int nframes,
+                                                            float* __restrict__ sink)
+{
+    constexpr int C = 257;
+    const int k = blockIdx.x & 7, group = blockIdx.x >> 3, ngroups = gridDim.x >> 3;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    probe_f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int f = group; f < nframes; f += ngroups) {
+        const float* fr = w + (size_t)f * C * C;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float* p = COLUMNS ? fr + (size_t)(32 * wave + 8 * j + (lane >> 3)) * C + 32 * k + 4 * (lane & 7)
+                                     : fr + (size_t)(1 + 4 * (8 * k + wave) + j) * C + 4 * lane;
+            probe_f4 v;
+            __builtin_memcpy(&v, p, 16);         // (rows are only 4-byte aligned)
+            acc += v;
+        }
+    }
+    const float s = acc.x + acc.y + acc.z + acc.w;
+    if (s == -1.2345678e-30f) sink[0] = s;
+}
+
 }  // namespace last
