@@ -521,3 +521,41 @@ def test_dense_context_size_2_with_more_than_1024_states():
     check_posteriors(cfg, order=2)
     check_path(cfg, order=2)
     assert np.all(check_loss(cfg, order=2) == 0)
+
+
+def test_calls_under_graph_capture_replay_like_eager():
+    """The loss in one call (with its fork to the library's side stream and the join back) and the
+    entry point that allocates nothing, captured into a HIP graph: every replay, with eager work
+    between the replays, gives the eager results bit for bit."""
+    announce("graph capture: loss in one call, static-scratch shortest distance; three replays")
+    cfg = workloads.config(3, B=4, T=60, V=256, Umax=30, u_lo=5, u_hi=30)
+    w, lengths = dev(cfg["w"]), dev(cfg["lengths"])
+    refs, ulen = dev(cfg["refs"]), dev(cfg["ref_lengths"])
+    st = torch.zeros(4, dtype=torch.int32, device="cuda")
+    d0, n0, g0 = lb.last_globally_normalized_loss(w, lengths, refs, ulen, item_status=st)
+    s0 = lb.last_shortest_distance(w, lengths)
+    torch.cuda.synchronize()
+    dw = torch.empty_like(w)
+    sd = torch.empty(4, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on a side stream, as graph capture asks for
+        lb.last_globally_normalized_loss(w, lengths, refs, ulen, dw=dw, item_status=st)
+        lb.last_shortest_distance_static(w, lengths, sd, item_status=st)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        d1, n1, _ = lb.last_globally_normalized_loss(w, lengths, refs, ulen, dw=dw, item_status=st)
+        lb.last_shortest_distance_static(w, lengths, sd, item_status=st)
+    for _ in range(3):
+        dw.fill_(7.0)
+        d1.fill_(0.0)
+        n1.fill_(0.0)
+        sd.fill_(0.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(d1, d0) and torch.equal(n1, n0) and torch.equal(sd, s0)
+        assert float((dw - g0).abs().max()) <= 1e-6       # (float atomics of the numerator's scatter)
+        assert torch.all(st == 0)
+        float(torch.randn(1000, device="cuda").sum())     # eager work between the replays
