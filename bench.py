@@ -173,6 +173,17 @@ def main():
                 "frac_of_read_plus_copy": (read_ms + copy_ms) / ms})
 
     extra = {}
+    # every call timed by itself as well: median and minimum (the headline figure is the mean of the
+    # whole timed region above)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    each = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    extra["ms_per_step_median"] = each[len(each) // 2]
+    extra["ms_per_step_min"] = each[0]
     if not args.no_extra:
         def loss_step():
             lb.last_arc_posteriors(w, lengths, order=1, dw=dw)
@@ -226,6 +237,13 @@ def main():
         arcs5 = float(np.sum(c5["lengths"].astype(np.int64)) * c5["C"] * (c5["V"] + 1))
         extra["table2_arcs_per_s"] = arcs5 / (extra["table2_training_step_ms"] * 1e-3)
         del se5, g5
+        # the small batch denominator (B=8, T<=200, V=32): 7 MB of weights, latency bound; time only
+        c1 = workloads.config(1)
+        w1, len1 = torch.from_numpy(c1["w"]).cuda(), torch.from_numpy(c1["lengths"]).cuda()
+        g1 = torch.empty_like(w1)
+        extra["config1_forward_backward_ms"], _ = time_region(
+            lambda: lb.last_arc_posteriors(w1, len1, order=1, dw=g1), 10, 2)
+        lb.check_item_status()
         extra["wall_ms_per_step"] = wall_ms
         wt, cx = lb.dense_weights(w), lb.context(cfg["V"], 1)
         extra["kernel_variant"] = lb.last_kernel_variant(wt, cx, lb.OP_ARC_POSTERIORS)
@@ -242,6 +260,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_FETCH_BYTES + MEASURED_WRITE_BYTES if full and not args.generation else None,
+                     "counter_GBs": (MEASURED_FETCH_BYTES + MEASURED_WRITE_BYTES) / (ms * 1e-3) / 1e9
+                                    if full and not args.generation else None,
                      "kernel": HEADLINE_KERNEL if full and not args.generation else None,
                      "algorithmic_bytes_per_launch": BYTES_PER_ARC * arcs},
         "ceilings": ceilings,
