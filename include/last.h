@@ -97,7 +97,7 @@ typedef enum {
  * work enqueued by the call has finished.  With a table, the weights must be
  * dense, every call runs one workgroup per item, C is limited by the 160 KiB of
  * LDS of a compute unit (about 10000 states for the log semiring, 13000 for the
- * tropical one; LAST_ERR_UNSUPPORTED beyond), and each call validates the table
+ * tropical one) and C*V by 2^24 (LAST_ERR_UNSUPPORTED beyond), and each call validates the table
  * on the device (item_status 7). */
 typedef struct {
     int32_t vocab;             /* V >= 1                                              */

@@ -66,6 +66,8 @@ last_status_t check_common(const last_weights_t* wt, const last_context_t* cx, S
         if (!cx->next_table) return LAST_ERR_NULL;
         if (cx->num_states < 1) return LAST_ERR_CONTEXT;
         if (wt && wt->kind != LAST_WEIGHTS_DENSE) return LAST_ERR_UNSUPPORTED;
+        // (the fixed-point sums of the table kernels hold at most 2^24 arcs into one state)
+        if ((long long)cx->num_states * V > (1ll << 24)) return LAST_ERR_UNSUPPORTED;
         C = cx->num_states;
     }
     if (C != cx->num_states || C > (1 << 24) || C * (V + 1) > (1ll << 31) - 2) return LAST_ERR_CONTEXT;
