@@ -289,7 +289,7 @@ __device__ __forceinline__ void cluster_sync(const ClusterArgs& a, const Cluster
     const int me = g.role * a.K + g.k;
     const u64 target = (u64)tag + 1;          // flags count items; ~0 = never written
     if (threadIdx.x == 0) xstore(flags + me, target);
-    if (threadIdx.x < 2 * a.K && !*dead_s)
+    if ((int)threadIdx.x < 2 * a.K && !*dead_s)
         if (!poll_flag(flags + threadIdx.x, target, a.spin_limit)) *dead_s = 1;
     __syncthreads();
     __threadfence();

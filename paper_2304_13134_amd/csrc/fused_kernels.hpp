@@ -319,7 +319,7 @@ template <int MT>
 __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
-    const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
+    const int V = a.V, H = a.H, R = V + 2;
     const int NTL = (V + 15) / 16;                                   // label tiles (waves 0..NTL-1)
     __bf16* e_s = (__bf16*)smem_raw;                                  // [R][H]
     __bf16* hid_s = e_s + (size_t)R * H;                              // [2][kFuMaxRows][kFuHS]
