@@ -211,6 +211,12 @@ def main():
             lambda: lb.last_shortest_distance(se, len4, order=2), 3, 1)
         extra["fused_trigram_fwd_bwd_ms"], _ = time_region(
             lambda: lb.last_arc_posteriors(se, len4, order=2, dw=g4), 3, 1)
+        # the forward kernel with the weights of one frame at a time instead of two (the default)
+        frames_default = lb.set_option(lb.OPT_FUSED_FRAMES_PER_TILE, 1)
+        extra["fused_trigram_shortest_distance_ms_one_frame_per_tile"], _ = time_region(
+            lambda: lb.last_shortest_distance(se, len4, order=2), 3, 1)
+        lb.set_option(lb.OPT_FUSED_FRAMES_PER_TILE, frames_default)
+        extra["fused_frames_per_tile"] = frames_default
         arcs4 = float(np.sum(c4["lengths"].astype(np.int64)) * c4["C"] * (c4["V"] + 1))
         extra["fused_trigram_arcs_per_s_fwd_bwd"] = arcs4 / (extra["fused_trigram_fwd_bwd_ms"] * 1e-3)
         # matrix-core work of one forward+backward: the weights three times (forward, beta pass, dW pass)

@@ -252,6 +252,11 @@ last_status_t last_shortest_distance_static(const last_weights_t* weights, const
  *   LAST_OPT_CLUSTER_VITERBI (0/1, default 1): 0 = shortest path with one workgroup per item.
  *   LAST_OPT_SPIN_LIMIT (>= 1, default 2^20): polls a cooperating workgroup makes before it gives up
  *     waiting for the others (the item then gets status 5 and dist = NaN; every kernel still ends).
+ *   LAST_OPT_FUSED_FRAMES_PER_TILE (1 or 2, default 2): frames whose on-the-fly weights the forward
+ *     kernel of the shared_emb path computes at a time (Section 5 discusses evaluating the weight
+ *     function for several frames at once).  2 shares the rows of e and the phase barriers between
+ *     two frames and doubles the hidden tile in LDS; a shape whose tiles then no longer fit uses 1.
+ *     The shortest distance does not depend on it bit for bit.
  * last_set_option returns LAST_ERR_UNSUPPORTED for an unknown option or value; last_get_option
  * returns -1 for an unknown option. */
 typedef enum {
@@ -259,7 +264,8 @@ typedef enum {
     LAST_OPT_CLUSTER_GENERATION = 1,
     LAST_OPT_CLUSTER_VITERBI = 2,
     LAST_OPT_SPIN_LIMIT = 3,
-    LAST_OPT_COUNT_ = 4
+    LAST_OPT_FUSED_FRAMES_PER_TILE = 4,
+    LAST_OPT_COUNT_ = 5
 } last_option_t;
 last_status_t last_set_option(int32_t option, int32_t value);
 int32_t last_get_option(int32_t option);

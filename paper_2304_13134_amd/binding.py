@@ -28,7 +28,7 @@ EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posterior
            "last_shortest_distance_static", "last_set_option", "last_get_option",
            "last_local_log_likelihood", "last_probe_bandwidth", "last_globally_normalized_loss"]
 PROBE_READ, PROBE_COPY, PROBE_READ_ROWS, PROBE_READ_COLUMNS = 0, 1, 2, 3
-OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT = 0, 1, 2, 3
+OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT, OPT_FUSED_FRAMES_PER_TILE = 0, 1, 2, 3, 4
 STATIC_SCRATCH_BYTES = 32 << 20
 
 

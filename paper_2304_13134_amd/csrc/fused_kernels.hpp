@@ -42,7 +42,7 @@ constexpr int kFuMaxKS = 16;        // hidden / 32
 constexpr int kFuKC = 128;          // hidden units per chunk of the hidden tile (forward kernel)
 constexpr int kFuNC = 4;            // chunks (hidden <= 512, a multiple of kFuKC)
 constexpr int kFuHS = kFuKC + 8;    // row stride (bf16) of a hidden-tile chunk in LDS
-constexpr int kFuHB = kFuMaxRows * kFuHS;   // elements per chunk buffer
+constexpr int kFuHB = kFuMaxRows * kFuHS;   // elements per chunk buffer at most (a kernel with MT row tiles: 16 MT rows)
 constexpr int kFuHF = 512 + 8;      // row stride (bf16) of the whole hidden tile (backward kernels)
 constexpr int kFuGS = 104;          // row stride (bf16) of the marginal tiles in LDS; 96 used
 constexpr int kFuKT = 4;            // 16-wide tiles of the hidden dimension per wave (8 waves x 4 x 16 = 512)
@@ -166,21 +166,23 @@ __device__ __forceinline__ void fused_mfma_chunk(const __bf16* hb, floatx4 (&acc
     }
 }
 
-// Hidden tile + contraction of one frame in NC + 1 phases (NC = H / kFuKC).  Phase
+// Hidden tile + contraction of NF consecutive frames in NC + 1 phases (NC = H / kFuKC).  Phase
 // p runs the matrix-core contraction of chunk p-1 and forms the hidden tile
 // tanh(f + e) of chunk p, so the transcendental work of one chunk overlaps the
-// contraction of the previous one; chunks alternate between two LDS buffers.
+// contraction of the previous one; chunks alternate between two LDS buffers.  With NF = 2
+// ("two frames per tile") a row of e is read once for both frames and the phase barriers are
+// shared; the frames have their own hidden tiles and accumulators.
 // Columns of the weight tile: waves 0..NTL-1 hold labels 16 n + 1 .. 16 n + 16
 // (lane l, tile mt, element i -> row 16 mt + 4 (l / 16) + i, label 16 n + l % 16 + 1);
 // waves 4..7 hold partial sums of the empty-label column (lanes with l % 16 == 0).
 // One contraction wave of each kind per SIMD keeps the matrix cores evenly loaded.
-// f_s [H] bf16 (features of the frame), e_s [R][H] bf16, hid_s [2][kFuMaxRows][kFuHS]
+// f_s [NF][H] bf16 (features of the frames), e_s [R][H] bf16, hid_s [2][NF][16 MT][kFuHS]
 // bf16 (constant strides keep the LDS addresses of the contraction immediate).
 // `early` (may be null): an exchange word this thread will need afterwards; a first
 // look at it is issued after phase 1 and returned in `early_word`.
-template <int MT>
+template <int MT, int NF>
 __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __bf16* e_s,
-                                                     __bf16* hid_s, floatx4 (&acc)[MT],
+                                                     __bf16* hid_s, floatx4 (&acc)[NF][MT],
                                                      const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NTL,
                                                      const u64* early, u64& early_word
 #ifdef LAST_TRACE
@@ -203,33 +205,40 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
     const int r_first = wave < 4 ? wave : RL + (wave - 4);
     const int r_end = wave < 4 ? RL : R;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int fr = 0; fr < NF; ++fr)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[fr][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
     for (int p = 0; p <= NC; ++p) {
         if (p == 2 && early) early_word = xload(early);
         FU_PMARK(8 + 3 * p);
         if (p >= 1) {
-            const __bf16* hb = hid_s + ((p - 1) & 1) * kFuHB;
-            if (wave >= 4) {
-                switch (p) {
-                case 1: fused_mfma_chunk<MT, 0, true>(hb, acc, wfrag, wave - 4); break;
-                case 2: fused_mfma_chunk<MT, 1, true>(hb, acc, wfrag, wave - 4); break;
-                case 3: fused_mfma_chunk<MT, 2, true>(hb, acc, wfrag, wave - 4); break;
-                default: fused_mfma_chunk<MT, 3, true>(hb, acc, wfrag, wave - 4); break;
-                }
-            } else if (wave < NTL) {
-                switch (p) {
-                case 1: fused_mfma_chunk<MT, 0, false>(hb, acc, wfrag, 0); break;
-                case 2: fused_mfma_chunk<MT, 1, false>(hb, acc, wfrag, 0); break;
-                case 3: fused_mfma_chunk<MT, 2, false>(hb, acc, wfrag, 0); break;
-                default: fused_mfma_chunk<MT, 3, false>(hb, acc, wfrag, 0); break;
+#pragma unroll
+            for (int fr = 0; fr < NF; ++fr) {
+                const __bf16* hb = hid_s + (((p - 1) & 1) * NF + fr) * (16 * MT * kFuHS);
+                if (wave >= 4) {
+                    switch (p) {
+                    case 1: fused_mfma_chunk<MT, 0, true>(hb, acc[fr], wfrag, wave - 4); break;
+                    case 2: fused_mfma_chunk<MT, 1, true>(hb, acc[fr], wfrag, wave - 4); break;
+                    case 3: fused_mfma_chunk<MT, 2, true>(hb, acc[fr], wfrag, wave - 4); break;
+                    default: fused_mfma_chunk<MT, 3, true>(hb, acc[fr], wfrag, wave - 4); break;
+                    }
+                } else if (wave < NTL) {
+                    switch (p) {
+                    case 1: fused_mfma_chunk<MT, 0, false>(hb, acc[fr], wfrag, 0); break;
+                    case 2: fused_mfma_chunk<MT, 1, false>(hb, acc[fr], wfrag, 0); break;
+                    case 3: fused_mfma_chunk<MT, 2, false>(hb, acc[fr], wfrag, 0); break;
+                    default: fused_mfma_chunk<MT, 3, false>(hb, acc[fr], wfrag, 0); break;
+                    }
                 }
             }
         }
         FU_PMARK(9 + 3 * p);
         if (p < NC) {
-            __bf16* hb = hid_s + (p & 1) * kFuHB + 2 * kp;
-            const unsigned f2 = *(const unsigned*)(f_s + kFuKC * p + 2 * kp);
+            __bf16* hb = hid_s + (p & 1) * NF * (16 * MT * kFuHS) + 2 * kp;
+            unsigned f2[NF];
+#pragma unroll
+            for (int fr = 0; fr < NF; ++fr) f2[fr] = *(const unsigned*)(f_s + (size_t)fr * H + kFuKC * p + 2 * kp);
             const __bf16* ep = e_s + kFuKC * p + 2 * kp;
             for (int r = r_first; r < r_end; r += 12) {
                 // three rows per trip: the LDS reads go out together
@@ -237,9 +246,13 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
                 const unsigned e0 = *(const unsigned*)(ep + (size_t)r * H);
                 const unsigned e1 = *(const unsigned*)(ep + (size_t)(r1 < r_end ? r1 : r) * H);
                 const unsigned e2 = *(const unsigned*)(ep + (size_t)(r2 < r_end ? r2 : r) * H);
-                *(unsigned*)(hb + r * kFuHS) = tanh_pair(f2, e0);
-                if (r1 < r_end) *(unsigned*)(hb + r1 * kFuHS) = tanh_pair(f2, e1);
-                if (r2 < r_end) *(unsigned*)(hb + r2 * kFuHS) = tanh_pair(f2, e2);
+#pragma unroll
+                for (int fr = 0; fr < NF; ++fr) {
+                    __bf16* hf = hb + fr * (16 * MT * kFuHS);
+                    *(unsigned*)(hf + r * kFuHS) = tanh_pair(f2[fr], e0);
+                    if (r1 < r_end) *(unsigned*)(hf + r1 * kFuHS) = tanh_pair(f2[fr], e1);
+                    if (r2 < r_end) *(unsigned*)(hf + r2 * kFuHS) = tanh_pair(f2[fr], e2);
+                }
             }
             FU_PMARK(10 + 3 * p);
             lds_barrier();
@@ -309,32 +322,35 @@ __device__ __forceinline__ void fused_publish_header(const float* al, int R, u64
 
 // Shortest distance in the log semiring with on-the-fly weights (Eq. 2 visited
 // frame by frame, Section 4.1).  Grid: ncl * V workgroups of 512 threads; MT =
-// number of 16-row tiles that cover the V + 2 rows of a workgroup.
+// number of 16-row tiles that cover the V + 2 rows of a workgroup; NF = frames whose
+// weights are computed at a time (1 or 2).
 // Per frame: the waves that hold the weight tile reduce the label arcs of the
 // own rows column by column in registers and publish the V partial values; the
-// weights of the NEXT frame (independent of the recursion) are then computed
-// while those words travel; finally the own states are assembled from what the
+// weights of the NEXT NF frames (independent of the recursion) are then computed
+// while those words travel (NF = 2: after the second frame of a group; the exchange of
+// the first one is waited for); finally the own states are assembled from what the
 // other workgroups sent.
-template <int MT>
+template <int MT, int NF>
 __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     const int V = a.V, H = a.H, R = V + 2;
     const int NTL = (V + 15) / 16;                                   // label tiles (waves 0..NTL-1)
     __bf16* e_s = (__bf16*)smem_raw;                                  // [R][H]
-    __bf16* hid_s = e_s + (size_t)R * H;                              // [2][kFuMaxRows][kFuHS]
-    float* al_s = (float*)(hid_s + 2 * kFuHB);                        // [2][kFuMaxRows] forward weights
+    __bf16* hid_s = e_s + (size_t)R * H;                              // [2][NF][16 MT][kFuHS]
+    static_assert(NF == 1 || NF == 2, "the forward weights of a group's frames sit in two LDS rows");
+    float* al_s = (float*)(hid_s + 2 * NF * (16 * MT * kFuHS));       // [2][kFuMaxRows] forward weights
     float* pb_s = al_s + 2 * kFuMaxRows;                              // [4][kFuMaxRows] partial empty-label weights
     float* sa_s = pb_s + 4 * kFuMaxRows;                              // [8] label arc start -> (b)
     float* red = sa_s + 8;                                            // [32]
     int* ctl_s = (int*)(red + 32);                                    // [8]
-    __bf16* f_s = (__bf16*)(ctl_s + 8);                               // [H] features of the frame being prepared
+    __bf16* f_s = (__bf16*)(ctl_s + 8);                               // [NF][H] features of the frames being prepared
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cl = blockIdx.x / V, b = blockIdx.x % V + 1;
     // zero the pad rows of the hidden tile once; they stay zero
-    for (int i = tid; i < 2 * kFuHB; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < 2 * NF * (16 * MT * kFuHS); i += kFuThreads) hid_s[i] = (__bf16)0.f;
     // rows of e owned by this workgroup
     for (int i = tid; i < R * H; i += kFuThreads) {
         const int r = i / H, k = i - r * H;
@@ -342,7 +358,7 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     bf16x8 wfrag[kFuMaxKS];
     fused_load_wfrag(a.Wf, wfrag);
-    floatx4 acc[MT];
+    floatx4 acc[NF][MT];
     unsigned gstep = 0;
     __syncthreads();
 
@@ -359,123 +375,152 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         if (aws && tid < R && (tid > 0 || b == 1)) aws[fused_state(V, b, tid)] = al_s[tid];
         if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1)] = 0.0;
         double A = 0.0;                       // running offset, identical in every workgroup
+        double A_at[2] = {0.0, 0.0};          // ... after frame s - 1, at [s & 1], for the two newest s
         float P_cur = 0.f, P_prev = 0.f, mu_prev = 0.f;
         int dead = 0;
+        int kept = 0;                         // forward weights of frames 0 .. kept are in the workspace
+        // The forward weights kept for the backward pass leave LDS once per group, right before the weights
+        // of the next group are computed: a look at the exchange waits for every store the wave issued
+        // before it, and there the next look is furthest away.
+        auto keep = [&](int upto) __attribute__((always_inline)) {
+            for (int sfr = kept + 1; sfr <= upto; ++sfr) {
+                if (aws && tid < R && (tid > 0 || b == 1))
+                    aws[(size_t)sfr * a.C + fused_state(V, b, tid)] = al_s[(sfr & 1) * kFuMaxRows + tid];
+                if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1) + sfr] = A_at[sfr & 1];
+            }
+            kept = max(kept, upto);
+        };
         if (L > 0 && wave == 0)
             fused_publish_header(al_s, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
                                  gstep + 1);
-        // frame features travel two frames ahead: register (frame t + 2) -> LDS (frame t + 1)
-        unsigned fnext = (2 * tid < H && L > 0) ? *(const unsigned*)(fi + 2 * tid) : 0u;
-        // iteration t = -1 only computes the weights of frame 0
-        for (int t = (L > 0 ? -1 : 0); t < L; ++t) {
-            const int par = t & 1;
-            const float* al = al_s + par * kFuMaxRows;
-            float* an = al_s + (par ^ 1) * kFuMaxRows;
-            const unsigned tag = gstep + 1;
-            u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
-            FU_MARK(a, t, 0);
+        // frame features travel two groups ahead: register (group g + 2) -> LDS (group g + 1)
+        unsigned fnext[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+            fnext[j] = (2 * tid < H && L > 0) ? *(const unsigned*)(fi + (size_t)(j < L ? j : L - 1) * H + 2 * tid) : 0u;
+        // frames are taken in groups of NF; group -1 only computes the weights of the first NF frames
+        for (int t0 = (L > 0 ? -NF : 0); t0 < L; t0 += NF) {
             if (2 * tid < H) {
-                *(unsigned*)(f_s + 2 * tid) = fnext;
-                fnext = *(const unsigned*)(fi + (size_t)(t + 2 < L ? t + 2 : L - 1) * H + 2 * tid);
-            }
-            // label arcs (b), (a,b) --y--> (b,y): reduced over the own rows, sent to workgroup y
-            if (t >= 0 && wave < NTL) {
-                const int g = lane >> 4, y = 16 * wave + (lane & 15) + 1;
-                float v[MT][4];
-                float m = LAST_NEG_INF;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const floatx4 a4 = *(const floatx4*)&al[16 * mt + 4 * g];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int row = 16 * mt + 4 * g + i;
-                        v[mt][i] = (row >= 1 && row < R) ? a4[i] + acc[mt][i] : LAST_NEG_INF;
-                        m = fmaxf(m, v[mt][i]);
-                    }
+                for (int j = 0; j < NF; ++j) {
+                    const int tn = t0 + 2 * NF + j;
+                    *(unsigned*)(f_s + (size_t)j * H + 2 * tid) = fnext[j];
+                    fnext[j] = *(const unsigned*)(fi + (size_t)(tn < L ? tn : L - 1) * H + 2 * tid);
                 }
-                const float v00 = al[0] + acc[0][0];          // row 0 (lanes with g == 0): start --y--> (y)
-                m = fmaxf(m, __shfl_xor(m, 16));
-                m = fmaxf(m, __shfl_xor(m, 32));
-                const float ms = (m == LAST_NEG_INF) ? 0.f : m;
-                float sum = 0.f;
+            }
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+            for (int j = 0; j < NF; ++j) {
+                const int t = t0 + j;
+                const bool live = t >= 0 && t < L;           // (the same in every thread of the item's workgroups)
+                const int par = t & 1;
+                const float* al = al_s + par * kFuMaxRows;
+                float* an = al_s + (par ^ 1) * kFuMaxRows;
+                const unsigned tag = gstep + 1;
+                u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
+                FU_MARK(a, t, 0);
+                // label arcs (b), (a,b) --y--> (b,y): reduced over the own rows, sent to workgroup y
+                if (live && wave < NTL) {
+                    const int g = lane >> 4, y = 16 * wave + (lane & 15) + 1;
+                    float v[MT][4];
+                    float m = LAST_NEG_INF;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) sum += __expf(v[mt][i] - ms);
-                sum += __shfl_xor(sum, 16);
-                sum += __shfl_xor(sum, 32);
-                const float p = (m != LAST_NEG_INF) ? m + __logf(sum) - P_cur : LAST_NEG_INF;
-                if (g == 0 && y <= V) xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
-                if (g == 0 && y == b) sa_s[0] = v00 - P_cur;
-            } else if (t >= 0 && wave >= 4) {
-                // partial empty-label weights of the own rows
-                if ((lane & 15) == 0) {
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const floatx4 a4 = *(const floatx4*)&al[16 * mt + 4 * g];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = 16 * mt + 4 * g + i;
+                            v[mt][i] = (row >= 1 && row < R) ? a4[i] + acc[j][mt][i] : LAST_NEG_INF;
+                            m = fmaxf(m, v[mt][i]);
+                        }
+                    }
+                    const float v00 = al[0] + acc[j][0][0];       // row 0 (lanes with g == 0): start --y--> (y)
+                    m = fmaxf(m, __shfl_xor(m, 16));
+                    m = fmaxf(m, __shfl_xor(m, 32));
+                    const float ms = (m == LAST_NEG_INF) ? 0.f : m;
+                    float sum = 0.f;
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            pb_s[(wave - 4) * kFuMaxRows + 16 * mt + 4 * (lane >> 4) + i] = acc[mt][i];
+                        for (int i = 0; i < 4; ++i) sum += __expf(v[mt][i] - ms);
+                    sum += __shfl_xor(sum, 16);
+                    sum += __shfl_xor(sum, 32);
+                    const float p = (m != LAST_NEG_INF) ? m + __logf(sum) - P_cur : LAST_NEG_INF;
+                    if (g == 0 && y <= V) xstore(xs + (size_t)(y - 1) * a.XW + (b - 1), pack_word(p, tag));
+                    if (g == 0 && y == b) sa_s[0] = v00 - P_cur;
+                } else if (live && wave >= 4) {
+                    // partial empty-label weights of the own rows
+                    if ((lane & 15) == 0) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                pb_s[(wave - 4) * kFuMaxRows + 16 * mt + 4 * (lane >> 4) + i] = acc[j][mt][i];
+                    }
                 }
-            }
-            FU_MARK(a, t, 1);
-            lds_barrier();
-            FU_MARK(a, t, 2);
-            // weights of the next frame while the partial values travel; the first look at the
-            // incoming words is issued half way and consumed afterwards
-            const u64* pw = nullptr;
-            if (t >= 0) {
-                if (tid >= 1 && tid <= V) pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
-                else if (tid >= 128 && tid < 128 + V) pw = xs + (size_t)V * a.XW + (tid - 128);
-            }
-            u64 x = 0;
+                FU_MARK(a, t, 1);
+                lds_barrier();
+                FU_MARK(a, t, 2);
+                // after the last frame of the group: the weights of the next group while the partial values
+                // travel; the first look at the incoming words is issued half way and consumed afterwards
+                const u64* pw = nullptr;
+                if (live) {
+                    if (tid >= 1 && tid <= V) pw = xs + (size_t)(b - 1) * a.XW + (tid - 1);
+                    else if (tid >= 128 && tid < 128 + V) pw = xs + (size_t)V * a.XW + (tid - 128);
+                }
+                u64 x = 0;
+                if (j == NF - 1) keep(min(t0 + NF - 1, L));
+                if (j == NF - 1 && t0 + NF < L) {
 #ifdef LAST_TRACE
-            if (t + 1 < L) fused_weights_phases<MT>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x,
-                                                    (a.trace && t >= 0 && t < 256) ? a.trace + (size_t)t * 32 : nullptr);
+                    fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x,
+                                                 (a.trace && t >= 0 && t < 256) ? a.trace + (size_t)t * 32 : nullptr);
 #else
-            if (t + 1 < L) fused_weights_phases<MT>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x);
+                    fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x);
 #endif
-            else if (pw) x = xload(pw);
-            if (t < 0) continue;
-            FU_MARK(a, t, 3);
-            // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
-            float hv = LAST_NEG_INF;
-            if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
-            FU_MARK(a, t, 4);
-            // empty-label arc of own row r: alpha[r] + w[r][0]
-            auto blank = [&](int r) {
-                return al[r] + ((pb_s[r] + pb_s[kFuMaxRows + r]) + (pb_s[2 * kFuMaxRows + r] + pb_s[3 * kFuMaxRows + r])) - P_cur;
-            };
-            if (tid >= 1 && tid <= V) {
-                an[1 + tid] = log_add_f(word_value(x), blank(1 + tid));
-            } else if (tid == 0) {
-                an[0] = blank(0);
-                an[1] = log_add_f(sa_s[0], blank(1));
-            } else if (pw) {
-                hv = word_value(x);
+                } else if (pw) {
+                    x = xload(pw);
+                }
+                if (!live) continue;
+                FU_MARK(a, t, 3);
+                // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
+                float hv = LAST_NEG_INF;
+                if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
+                FU_MARK(a, t, 4);
+                // empty-label arc of own row r: alpha[r] + w[r][0]
+                auto blank = [&](int r) {
+                    return al[r] + ((pb_s[r] + pb_s[kFuMaxRows + r]) + (pb_s[2 * kFuMaxRows + r] + pb_s[3 * kFuMaxRows + r])) - P_cur;
+                };
+                if (tid >= 1 && tid <= V) {
+                    an[1 + tid] = log_add_f(word_value(x), blank(1 + tid));
+                } else if (tid == 0) {
+                    an[0] = blank(0);
+                    an[1] = log_add_f(sa_s[0], blank(1));
+                } else if (pw) {
+                    hv = word_value(x);
+                }
+                // the header words all sit in wave 2: their maximum goes through LDS; one barrier
+                // publishes it together with the new forward weights
+                if (wave == 2) {
+                    const float hm = wave_max_dpp(hv);
+                    if (lane == 0) red[0] = hm;
+                }
+                if (dead) ctl_s[0] = 1;
+                FU_MARK(a, t, 5);
+                lds_barrier();
+                const float mu = red[0];
+                FU_MARK(a, t, 6);
+                // offset bookkeeping, identical everywhere
+                const float G = mu - mu_prev + P_prev;
+                const float P_next = mu + 2.f * G - P_cur;
+                A += (double)P_cur;
+                A_at[(t + 1) & 1] = A;
+                mu_prev = mu; P_prev = P_cur; P_cur = P_next;
+                gstep += 1;
+                if (wave == 0 && t + 1 < L)
+                    fused_publish_header(an, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
+                                         gstep + 1);
             }
-            // the header words all sit in wave 2: their maximum goes through LDS; one barrier
-            // publishes it together with the new forward weights
-            if (wave == 2) {
-                const float hm = wave_max_dpp(hv);
-                if (lane == 0) red[0] = hm;
-            }
-            if (dead) ctl_s[0] = 1;
-            FU_MARK(a, t, 5);
-            lds_barrier();
-            const float mu = red[0];
-            FU_MARK(a, t, 6);
-            // offset bookkeeping, identical everywhere
-            const float G = mu - mu_prev + P_prev;
-            const float P_next = mu + 2.f * G - P_cur;
-            A += (double)P_cur;
-            mu_prev = mu; P_prev = P_cur; P_cur = P_next;
-            gstep += 1;
-            if (wave == 0 && t + 1 < L)
-                fused_publish_header(an, R, xbase + (size_t)(gstep & 1) * (V + 1) * a.XW + (size_t)V * a.XW + (b - 1),
-                                     gstep + 1);
-            if (aws && tid < R && (tid > 0 || b == 1)) aws[(size_t)(t + 1) * a.C + fused_state(V, b, tid)] = an[tid];
-            if (a.offs && b == 1 && tid == 0) a.offs[(size_t)item * (a.T + 1) + t + 1] = A;
         }
+        keep(L);
         // all states of the last frame are final: per-workgroup log-sum-exp, combined by fused_finalize
         {
             const float* al = al_s + (L & 1) * kFuMaxRows;

@@ -29,7 +29,7 @@ using namespace last;
 namespace {
 
 // process-wide settings (last_set_option)
-std::atomic<int> g_opt[LAST_OPT_COUNT_] = {{0}, {0}, {1}, {1 << 20}};
+std::atomic<int> g_opt[LAST_OPT_COUNT_] = {{0}, {0}, {1}, {1 << 20}, {2}};
 inline int opt(int o) { return g_opt[o].load(std::memory_order_relaxed); }
 
 constexpr size_t kAlign = 256;
@@ -423,6 +423,7 @@ constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel als
 struct FusedPlan {
     bool ok;
     int ncl, XW, KC, R, Mpad, MT;
+    int NF;              // frames whose weights the forward kernel computes at a time
     size_t lds;          // forward kernel
     size_t lds_bwd;      // backward recursion kernel
     size_t lds_dw;       // dW kernel
@@ -451,9 +452,14 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     p.ncl = 256 / s.V;                        // one workgroup per compute unit
     if (p.ncl > s.B) p.ncl = s.B;
     p.XW = (s.V + 7) / 8 * 8;
-    p.lds = (size_t)p.R * H * 2 + (size_t)2 * kFuHB * 2 + (size_t)(6 * kFuMaxRows + 8 + 32 + 8) * 4 + (size_t)H * 2;
-    const size_t tiles = (size_t)kFuMaxRows * kFuWS * 4 + (size_t)2 * kFuMaxRows * kFuGS * 2;
     p.MT = p.Mpad / 16 <= 1 ? 1 : p.Mpad / 16 <= 3 ? 3 : 5;   // instantiated row-tile counts
+    auto lds_forward = [&](int nf) {
+        return (size_t)p.R * H * 2 + (size_t)2 * nf * 16 * p.MT * kFuHS * 2 + (size_t)(6 * kFuMaxRows + 8 + 32 + 8) * 4
+               + (size_t)nf * H * 2;
+    };
+    p.NF = opt(LAST_OPT_FUSED_FRAMES_PER_TILE) == 2 && lds_forward(2) <= (size_t)kFusedMaxLds ? 2 : 1;
+    p.lds = lds_forward(p.NF);
+    const size_t tiles = (size_t)kFuMaxRows * kFuWS * 4 + (size_t)2 * kFuMaxRows * kFuGS * 2;
     p.lds_bwd = (size_t)kFuMaxRows * kFuHF * 2 + tiles + (size_t)(5 * kFuMaxRows + 8) * 4;
     p.lds_dw = (size_t)(32 * ((16 * p.MT + 31) / 32)) * kFuHF * 2 + tiles + (size_t)(4 * kFuMaxRows) * 4;
     p.nch = 256 / (s.B * s.V);                // fill the chip when the batch is small
@@ -507,8 +513,9 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
                                    int* item_status, bool keep_alpha, hipStream_t st)
 {
     {
-        const void* kernels[9] = {
-            (const void*)fused_forward_kernel<1>, (const void*)fused_forward_kernel<3>, (const void*)fused_forward_kernel<5>,
+        const void* kernels[12] = {
+            (const void*)fused_forward_kernel<1, 1>, (const void*)fused_forward_kernel<3, 1>, (const void*)fused_forward_kernel<5, 1>,
+            (const void*)fused_forward_kernel<1, 2>, (const void*)fused_forward_kernel<3, 2>, (const void*)fused_forward_kernel<5, 2>,
             (const void*)fused_backward_kernel<1>, (const void*)fused_backward_kernel<3>, (const void*)fused_backward_kernel<5>,
             (const void*)fused_dw_kernel<1>, (const void*)fused_dw_kernel<3>, (const void*)fused_dw_kernel<5>};
         for (const void* k : kernels) {
@@ -528,8 +535,12 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = wt->hidden; a.C = s.C;
     a.ncl = p.ncl; a.XW = p.XW; a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     fused_dispatch(p.MT, [&](auto MT) {
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_forward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
-                           dim3(kFuThreads), p.lds, st, a);
+        if (p.NF == 2)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_forward_kernel<decltype(MT)::value, 2>), dim3(p.ncl * s.V),
+                               dim3(kFuThreads), p.lds, st, a);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_forward_kernel<decltype(MT)::value, 1>), dim3(p.ncl * s.V),
+                               dim3(kFuThreads), p.lds, st, a);
     });
     hipLaunchKernelGGL(fused_finalize_kernel, dim3((s.B + 63) / 64), dim3(64), 0, st,
                        (const float*)f.part, (const double*)f.Aend, s.B, s.V, dist, f.D, item_status);
@@ -648,6 +659,7 @@ last_status_t last_set_option(int32_t option, int32_t value)
     if (option < 0 || option >= LAST_OPT_COUNT_) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_CLUSTER_GENERATION && (value < 0 || value > 3)) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_SPIN_LIMIT && value < 1) return LAST_ERR_UNSUPPORTED;
+    if (option == LAST_OPT_FUSED_FRAMES_PER_TILE && value != 1 && value != 2) return LAST_ERR_UNSUPPORTED;
     g_opt[option].store(value, std::memory_order_relaxed);
     return LAST_OK;
 }

@@ -150,3 +150,21 @@ def test_table_context_is_checked_on_the_host(lib):
                                    dummy, 1 << 30, None) == 6
     assert lib.last_local_log_likelihood(ctypes.byref(wt), dummy, ctypes.byref(tab), dummy, dummy, -1, dummy,
                                          None, None, dummy, 1 << 20, None) == 2
+
+
+def test_options_are_validated(lib):
+    """last_set_option refuses unknown options and values and leaves the setting as it was."""
+    for option, good, bad in [(lb.OPT_CLUSTER_GENERATION, (0, 1, 2, 3), (-1, 4)),
+                              (lb.OPT_SPIN_LIMIT, (1, 1 << 20), (0, -5)),
+                              (lb.OPT_FUSED_FRAMES_PER_TILE, (1, 2), (0, 3))]:
+        before = lib.last_get_option(option)
+        for v in bad:
+            assert lib.last_set_option(option, v) != 0
+            assert lib.last_get_option(option) == before
+        for v in good:
+            assert lib.last_set_option(option, v) == 0
+            assert lib.last_get_option(option) == v
+        assert lib.last_set_option(option, before) == 0
+    assert lib.last_set_option(99, 0) != 0
+    assert lib.last_get_option(99) == -1
+    assert lib.last_get_option(lb.OPT_FUSED_FRAMES_PER_TILE) == 2     # the default

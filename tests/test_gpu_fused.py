@@ -47,6 +47,36 @@ def test_fused_shortest_distance_config4_shape_short():
     assert_dist_close(dist.cpu().numpy(), o["D"])
 
 
+@pytest.mark.parametrize("B,T,V,H,lens,seed", [(2, 1, 4, 128, [1, 0], 11), (3, 5, 8, 128, [5, 4, 1], 12),
+                                                (2, 9, 20, 256, [9, 2], 13), (4, 12, 33, 384, [12, 11, 7, 3], 14),
+                                                (2, 7, 64, 512, [7, 6], 15)])
+def test_fused_frames_per_tile(B, T, V, H, lens, seed):
+    """Weights of one or of two frames at a time in the forward kernel (the library's
+    LAST_OPT_FUSED_FRAMES_PER_TILE): both against the oracle, odd and even lengths, a length of one
+    and of zero, full-size tiles; the two settings give the same bits (each frame's weights and the
+    recursion are computed by the same instructions, only their order in time differs)."""
+    from gpu_util import library_option
+    announce("fused forward, frames per tile 1 and 2", B, T, V, H, lens)
+    s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed)
+    s["lengths"] = np.asarray(lens, dtype=np.int32)
+    se, lengths = fused_inputs(s), torch.from_numpy(s["lengths"]).cuda()
+    o = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=True)
+    got = {}
+    for frames in (1, 2):
+        with library_option(lb.OPT_FUSED_FRAMES_PER_TILE, frames):
+            st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+            dist = lb.last_shortest_distance(se, lengths, order=2, item_status=st)
+            dist2, grads = lb.last_arc_posteriors(se, lengths, order=2, item_status=st)
+            torch.cuda.synchronize()
+        assert st.cpu().tolist() == [0] * B
+        assert_dist_close(dist.cpu().numpy(), o["D"])
+        assert torch.equal(dist, dist2)
+        for name, a, b in zip(("df", "de", "dW"), grads, (o["df"], o["de"], o["dW"])):
+            assert_grad_close(name, a.cpu().numpy(), b.astype(np.float64))
+        got[frames] = dist.cpu()
+    assert torch.equal(got[1], got[2])
+
+
 # Gradients of the fused path: the marginals enter two bf16 matrix-core contractions as hi + lo
 # halves (16 significant bits), tanh is evaluated in float32 before the bf16 rounding (a value
 # that lands within ~1e-6 of a rounding boundary may round the other way than the float64
@@ -269,13 +299,14 @@ def test_fused_loss_in_one_call():
         assert_grad_close(name, a.cpu().numpy(), b.astype(np.float64))
 
 
-def test_fused_bounded_waits_end_every_kernel_and_are_reported():
+@pytest.mark.parametrize("frames", [1, 2])
+def test_fused_bounded_waits_end_every_kernel_and_are_reported(frames):
     """Spin limit of one poll on the fused kernels: every kernel ends, items that gave up carry status 5."""
     from gpu_util import library_option
-    announce("spin limit 1, fused forward-backward")
+    announce("spin limit 1, fused forward-backward, frames per tile", frames)
     s = workloads.shared_emb(B=3, T=12, V=6, order=2, H=256, seed=77)
     se, lengths = fused_inputs(s), torch.from_numpy(s["lengths"]).cuda()
-    with library_option(lb.OPT_SPIN_LIMIT, 1):
+    with library_option(lb.OPT_SPIN_LIMIT, 1), library_option(lb.OPT_FUSED_FRAMES_PER_TILE, frames):
         st = torch.full((3,), -1, dtype=torch.int32, device="cuda")
         dist, grads = lb.last_arc_posteriors(se, lengths, order=2, item_status=st)
         torch.cuda.synchronize()
