@@ -286,6 +286,19 @@ int32_t last_get_option(int32_t option);
 enum { LAST_PROBE_READ = 0, LAST_PROBE_COPY = 1, LAST_PROBE_READ_ROWS = 2, LAST_PROBE_READ_COLUMNS = 3 };
 last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream);
 
+/* Check, on the current device, what the cooperating-workgroup kernels rely on (Section 4 of the
+ * paper leaves the mapping to hardware open; this is this library's): a launch of 256 workgroups is
+ * resident all at once, and workgroups i and j run on the same XCD exactly when i = j (mod 8), so
+ * that the workgroups of an item exchange their partial results through one XCD's L2.  Runs a small
+ * probe on `hip_stream` and WAITS for it (the one call here besides last_globally_normalized_loss'
+ * set-up that synchronises; not for use under stream capture).  workspace: device memory, at least
+ * 2048 bytes, 4-byte aligned, contents overwritten.  LAST_OK: the layout holds.
+ * LAST_ERR_UNSUPPORTED: it does not (or the chip has fewer than 256 compute units); from then on
+ * every call on this device takes the one-workgroup-per-item kernels.  Without this call the layout
+ * is assumed on chips of 256 compute units; if it did not hold there, the bounded waits would end
+ * the kernels and the items would carry status 5.  The binding calls it once per device. */
+last_status_t last_verify_placement(void* workspace, size_t workspace_bytes, void* hip_stream);
+
 const char* last_status_string(last_status_t status);
 
 /* Text of the HIP error behind the most recent LAST_ERR_HIP (diagnostics). */

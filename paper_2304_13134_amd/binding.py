@@ -26,7 +26,8 @@ EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posterior
            "last_intersect_reference", "last_shortest_path", "last_status_string",
            "last_version", "last_kernel_variant", "last_hip_error_string",
            "last_shortest_distance_static", "last_set_option", "last_get_option",
-           "last_local_log_likelihood", "last_probe_bandwidth", "last_globally_normalized_loss"]
+           "last_local_log_likelihood", "last_probe_bandwidth", "last_globally_normalized_loss",
+           "last_verify_placement"]
 PROBE_READ, PROBE_COPY, PROBE_READ_ROWS, PROBE_READ_COLUMNS = 0, 1, 2, 3
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT, OPT_FUSED_FRAMES_PER_TILE = 0, 1, 2, 3, 4
 STATIC_SCRATCH_BYTES = 32 << 20
@@ -92,6 +93,8 @@ def load_library():
                                        vp, vp, vp, vp, vp, sz, vp]
     lib.last_probe_bandwidth.restype = i32
     lib.last_probe_bandwidth.argtypes = [i32, vp, vp, sz, vp]
+    lib.last_verify_placement.restype = i32
+    lib.last_verify_placement.argtypes = [vp, sz, vp]
     lib.last_status_string.restype = ctypes.c_char_p
     lib.last_status_string.argtypes = [i32]
     lib.last_version.restype = i32
@@ -144,12 +147,29 @@ def _dev_tensor(t, dtype, name):
 
 
 _workspaces = {}
+_placement = {}      # device index -> True (cooperating workgroups) / False (one workgroup per item)
+
+
+def verify_placement(device=None):
+    """Run the library's placement probe on `device` (default: the current one) and return whether the
+    cooperating-workgroup kernels will be used there; waits for the device."""
+    index = torch.cuda.current_device() if device is None else (torch.device(device).index or 0)
+    with torch.cuda.device(index):
+        buf = torch.empty(2048, dtype=torch.uint8, device="cuda")
+        code = load_library().last_verify_placement(_ptr(buf), buf.numel(), _stream())
+    if code not in (0, 6):          # LAST_OK / LAST_ERR_UNSUPPORTED
+        _check(code)
+    _placement[index] = code == 0
+    return _placement[index]
 
 
 def workspace(nbytes, device):
     """A cached device scratch buffer (grown on demand, 256-byte aligned by the allocator), one per
     device and stream: calls enqueued on different streams may overlap and must not share scratch."""
-    key = (torch.device(device).index or 0, torch.cuda.current_stream().cuda_stream)
+    index = torch.device(device).index or 0
+    if index not in _placement and not torch.cuda.is_current_stream_capturing():
+        verify_placement(index)     # once per device, before the first kernel that relies on it
+    key = (index, torch.cuda.current_stream().cuda_stream)
     buf = _workspaces.get(key)
     if buf is None or buf.numel() < nbytes:
         buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

@@ -204,21 +204,21 @@ struct ClusterPlan {
 // at once, one per compute unit, on a chip of eight XCDs of 32 compute units each (a cluster of an
 // item sits on the XCD its workgroup ids select).  Anything else takes the one-workgroup kernels.
 // (Without a device, e.g. when only sizes are asked for on a build machine, the layout is assumed.)
+std::mutex g_chip_mutex;
+int g_chip_state[64] = {};                 // per device: 0 unknown, 1 takes clusters, 2 does not
 bool chip_takes_clusters()
 {
-    static std::mutex mu;
-    static int cached[64] = {};            // 0 unknown, 1 yes, 2 no
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return true; }
     if (dev < 0 || dev >= 64) return false;
-    std::lock_guard<std::mutex> lock(mu);
-    if (!cached[dev]) {
+    std::lock_guard<std::mutex> lock(g_chip_mutex);
+    if (!g_chip_state[dev]) {
         int cus = 0;
         const hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) (void)hipGetLastError();
-        cached[dev] = (e == hipSuccess && cus >= 256) ? 1 : 2;
+        g_chip_state[dev] = (e == hipSuccess && cus >= 256) ? 1 : 2;
     }
-    return cached[dev] == 1;
+    return g_chip_state[dev] == 1;
 }
 
 ClusterPlan cluster_plan(const Shape& s, int kind)
@@ -667,6 +667,45 @@ last_status_t last_set_option(int32_t option, int32_t value)
 int32_t last_get_option(int32_t option)
 {
     return option < 0 || option >= LAST_OPT_COUNT_ ? -1 : opt(option);
+}
+
+last_status_t last_verify_placement(void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    constexpr int kGrid = 256;
+    if (!workspace) return LAST_ERR_NULL;
+    if (workspace_bytes < (kGrid + 1) * sizeof(unsigned) || (uintptr_t)workspace % 4 != 0) return LAST_ERR_WORKSPACE;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    if (dev < 0 || dev >= 64) return LAST_ERR_UNSUPPORTED;
+    if (!chip_takes_clusters()) return LAST_ERR_UNSUPPORTED;     // (fewer than 256 compute units: already routed)
+    hipStream_t st = (hipStream_t)hip_stream;
+    unsigned* out = (unsigned*)workspace;
+    unsigned* counter = out + kGrid;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(1), dim3(64), 0, st, (float*)counter, (size_t)1);
+    hipLaunchKernelGGL(probe_placement_kernel, dim3(kGrid), dim3(512), 0, st, out, counter, 1 << 16);
+    unsigned host[kGrid];
+    e = hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
+    // workgroups i and j must share an XCD exactly when i = j (mod 8), and all must have been resident at once
+    bool ok = true;
+    int xcd_of[8];
+    for (int i = 0; i < kGrid && ok; ++i) {
+        const int xcd = (int)(host[i] & 15u);
+        if (!(host[i] & 0x100u)) ok = false;
+        if (i < 8) {
+            xcd_of[i] = xcd;
+            for (int j = 0; j < i; ++j) ok = ok && xcd_of[j] != xcd;
+        } else {
+            ok = ok && xcd_of[i & 7] == xcd;
+        }
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_chip_mutex);
+        g_chip_state[dev] = ok ? 1 : 2;
+    }
+    return ok ? LAST_OK : LAST_ERR_UNSUPPORTED;
 }
 
 last_status_t last_probe_bandwidth(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream)

@@ -75,4 +75,23 @@ __global__ __launch_bounds__(512) void probe_pattern_kernel(const float* __restr
     if (s == -1.2345678e-30f) sink[0] = s;
 }
 
+// Where the workgroups of a launch of the cooperating-workgroup shape (one workgroup per compute unit)
+// actually run.  Every workgroup writes the XCD it is on (bits 0..3 of its word) and whether it saw all
+// workgroups of the launch arrive while it was resident (bit 8): out[blockIdx.x].  The wait is bounded,
+// so the kernel ends whatever the placement is.  counter: one word, zero at the start.
+__global__ __launch_bounds__(512) void probe_placement_kernel(unsigned* __restrict__ out, unsigned* counter,
+                                                              int spin_limit)
+{
+    if (threadIdx.x != 0) return;
+    // hardware register 20 (XCC_ID), bits 0..3: the XCD of this compute unit
+    const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool all = false;
+    for (int n = 0; n < spin_limit && !all; ++n) {
+        all = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= gridDim.x;
+        if (!all) __builtin_amdgcn_s_sleep(8);
+    }
+    out[blockIdx.x] = xcc | (all ? 0x100u : 0u);
+}
+
 }  // namespace last

@@ -168,3 +168,9 @@ def test_options_are_validated(lib):
     assert lib.last_set_option(99, 0) != 0
     assert lib.last_get_option(99) == -1
     assert lib.last_get_option(lb.OPT_FUSED_FRAMES_PER_TILE) == 2     # the default
+
+
+def test_placement_probe_checks_its_arguments(lib):
+    assert lib.last_verify_placement(None, 4096, None) == 1              # LAST_ERR_NULL
+    assert lib.last_verify_placement(ctypes.c_void_p(0x1000), 64, None) == 5    # workspace too small
+    assert lib.last_verify_placement(ctypes.c_void_p(0x1002), 4096, None) == 5  # misaligned

@@ -559,3 +559,24 @@ def test_calls_under_graph_capture_replay_like_eager():
         assert float((dw - g0).abs().max()) <= 1e-6       # (float atomics of the numerator's scatter)
         assert torch.all(st == 0)
         float(torch.randn(1000, device="cuda").sum())     # eager work between the replays
+
+
+def test_placement_probe_and_fallback_routing():
+    """The probe of what the cooperating-workgroup kernels rely on (all workgroups resident at once,
+    workgroup i on XCD i mod 8) passes on this chip, the binding has run it, and the library routes by
+    its result: with the one-workgroup kernels forced the same inputs still give the oracle's values."""
+    announce("placement probe")
+    assert lb.verify_placement() is True
+    assert lb._placement[torch.cuda.current_device()] is True
+    cx = lb.context(256, 1)
+    wt = lb.LastWeights(lb.WEIGHTS_DENSE, 16, 500, 0x1000, None, None, None, 0)
+    assert lb.load_library().last_kernel_variant(wt, cx, lb.OP_ARC_POSTERIORS) == 1
+    c = workloads.config(0)
+    w, lengths = dev(c["w"]), dev(c["lengths"])
+    _, want = oracle.forward(c["w"], c["lengths"], 1)
+    dist = lb.last_shortest_distance(w, lengths, order=1)
+    with library_option(lb.OPT_FORCE_SOLO, 1):
+        dist_solo = lb.last_shortest_distance(w, lengths, order=1)
+    torch.cuda.synchronize()
+    assert_dist_close(dist.cpu().numpy(), want)
+    assert_dist_close(dist_solo.cpu().numpy(), want)
