@@ -257,6 +257,11 @@ last_status_t last_shortest_distance_static(const last_weights_t* weights, const
  *     function for several frames at once).  2 shares the rows of e and the phase barriers between
  *     two frames and doubles the hidden tile in LDS; a shape whose tiles then no longer fit uses 1.
  *     The shortest distance does not depend on it bit for bit.
+ *   LAST_OPT_FUSED_KEEP_MARGINALS (0/1, default 1): 1 = the backward pass of the shared_emb path keeps
+ *     the arc marginals of every frame (two bfloat16 halves each) in the workspace for the kernel that
+ *     forms dW, which then does not evaluate the weight function a third time; as long as they take
+ *     at most 8 GiB (B T V (V+2) (V+1 rounded up to 8) 4 bytes), else and with 0 they are recomputed.
+ *     last_workspace_bytes follows the setting: ask again after changing it.
  * last_set_option returns LAST_ERR_UNSUPPORTED for an unknown option or value; last_get_option
  * returns -1 for an unknown option. */
 typedef enum {
@@ -265,7 +270,8 @@ typedef enum {
     LAST_OPT_CLUSTER_VITERBI = 2,
     LAST_OPT_SPIN_LIMIT = 3,
     LAST_OPT_FUSED_FRAMES_PER_TILE = 4,
-    LAST_OPT_COUNT_ = 5
+    LAST_OPT_FUSED_KEEP_MARGINALS = 5,
+    LAST_OPT_COUNT_ = 6
 } last_option_t;
 last_status_t last_set_option(int32_t option, int32_t value);
 int32_t last_get_option(int32_t option);

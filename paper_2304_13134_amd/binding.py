@@ -30,6 +30,7 @@ EXPORTS = ["last_workspace_bytes", "last_shortest_distance", "last_arc_posterior
            "last_verify_placement"]
 PROBE_READ, PROBE_COPY, PROBE_READ_ROWS, PROBE_READ_COLUMNS = 0, 1, 2, 3
 OPT_FORCE_SOLO, OPT_CLUSTER_GENERATION, OPT_CLUSTER_VITERBI, OPT_SPIN_LIMIT, OPT_FUSED_FRAMES_PER_TILE = 0, 1, 2, 3, 4
+OPT_FUSED_KEEP_MARGINALS = 5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 

@@ -587,6 +587,9 @@ struct FusedBwdArgs {
     const double* offs;      // [B][T+1]
     const double* Dws;       // [B] shortest distance
     float* beta_ws;          // [B][T+1][C] backward weights relative to (D - offs)
+    __bf16* gamma_ws;        // null, or [B][T][V][2][V+2][P] the marginals of every frame as two bf16 halves
+                             // (hi plane, lo plane; P = V + 1 rounded up to a multiple of 8), written by the
+                             // backward kernel for the dW kernel
     float* df;               // [B][T][H]
     float* de;               // [C][H]
     float* dW;               // [H][V+1]
@@ -623,23 +626,12 @@ __device__ __forceinline__ void fused_load_e(const __bf16* __restrict__ e, int V
 // Hidden tile over the whole hidden dimension (kept for the gradient
 // contractions) + weights of one frame into w_s.  hid_s [.][kFuHF] bf16, rows
 // >= R stay zero.
-template <int MT>
-__device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const FusedERows& er,
-                                                   __bf16* hid_s, float* w_s, const bf16x8* __restrict__ Wf,
-                                                   int R, int H, int NTL, const u64* early, u64& early_word)
+// hidden tile tanh(f_t + e) of one frame over the whole hidden dimension (no barrier)
+__device__ __forceinline__ void fused_hidden_full(const __bf16* __restrict__ ft, const FusedERows& er,
+                                                  __bf16* hid_s, int R, int H)
 {
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kg = lane, rg = wave;              // same mapping as fused_load_e
-    // contraction waves: 0..NTL-1 -> label tiles, 4 -> the empty-label column.  Their fragments
-    // of W are fetched per frame and chunk (L2), one chunk ahead, so that few of them are live.
-    const bool mm = wave < NTL || wave == 4;
-    const bf16x8* wp = Wf + (size_t)wave * kFuMaxKS * 64 + lane;
-    bf16x8 wcur[kFuKC / 32];
-    if (mm) {
-#pragma unroll
-        for (int ks = 0; ks < kFuKC / 32; ++ks) wcur[ks] = wp[ks * 64];
-    }
+    const int kg = threadIdx.x & 63;
+    const int rg = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // same mapping as fused_load_e
     if (8 * kg < H) {
         const uintx4 f4 = *(const uintx4*)(ft + 8 * kg);
         __bf16* hw = hid_s + rg * kFuHF + 8 * kg;
@@ -660,6 +652,25 @@ __device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft
             }
         }
     }
+}
+
+template <int MT>
+__device__ __forceinline__ void fused_weights_full(const __bf16* __restrict__ ft, const FusedERows& er,
+                                                   __bf16* hid_s, float* w_s, const bf16x8* __restrict__ Wf,
+                                                   int R, int H, int NTL, const u64* early, u64& early_word)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // contraction waves: 0..NTL-1 -> label tiles, 4 -> the empty-label column.  Their fragments
+    // of W are fetched per frame and chunk (L2), one chunk ahead, so that few of them are live.
+    const bool mm = wave < NTL || wave == 4;
+    const bf16x8* wp = Wf + (size_t)wave * kFuMaxKS * 64 + lane;
+    bf16x8 wcur[kFuKC / 32];
+    if (mm) {
+#pragma unroll
+        for (int ks = 0; ks < kFuKC / 32; ++ks) wcur[ks] = wp[ks * 64];
+    }
+    fused_hidden_full(ft, er, hid_s, R, H);
     lds_barrier();
     if (early) early_word = xload(early);        // first look at the exchange word, consumed by the caller
     if (mm) {
@@ -827,6 +838,17 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             fused_rows<false>(w_s, bl, bn_s, bs_s, aw_s, P, V, R, b == 1, bl_new, gh_s, gl_s);
             lds_barrier();
             if (tid < R && (tid > 0 || b == 1)) bws[(size_t)t * a.C + fused_state(V, b, tid)] = bl_new[tid];
+            if (a.gamma_ws) {
+                // the marginals of the frame for the dW kernel, so that it need not evaluate the weights again:
+                // both bf16 planes, rows of P values, 16 bytes at a time
+                const int P8 = (V1 + 7) / 8, per_plane = R * P8;
+                uintx4* gout = (uintx4*)(a.gamma_ws + (((size_t)item * a.T + t) * V + (b - 1)) * 2 * R * 8 * P8);
+                for (int i = tid; i < 2 * per_plane; i += kFuThreads) {
+                    const int plane = i >= per_plane ? 1 : 0, k = i - plane * per_plane;
+                    const int r = k / P8, c8 = k - r * P8;
+                    gout[i] = *(const uintx4*)((plane ? gl_s : gh_s) + r * kFuGS + 8 * c8);
+                }
+            }
             // dpre = (gamma W^T) (1 - h^2): this wave owns hidden units [64 wave, 64 wave + 64)
             float* dft = a.df + ((size_t)item * a.T + t) * H;
 #pragma unroll
@@ -894,6 +916,62 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
 }
 
+// h^T gamma of one frame added to the accumulators of this wave (hidden units [64 wave, 64 wave + 64), all
+// labels): row step by row step, the h^T fragments of the wave's four column tiles are formed once, every
+// gamma fragment ([y][r] layout, two bf16 halves) is read once and meets all four.
+template <int MT>
+__device__ __forceinline__ void fused_dw_accumulate(const __bf16* hid_s, const __bf16* gh_s, const __bf16* gl_s,
+                                                    floatx4 (&acc)[kFuKT][kFuMaxNT], int NT, int H)
+{
+    constexpr int RS = (16 * MT + 31) / 32;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (16 * kFuKT * wave < H) {
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+            bf16x8 hv[kFuKT];
+#pragma unroll
+            for (int kt = 0; kt < kFuKT; ++kt)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    hv[kt][j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * kFuHF + 16 * (kFuKT * wave + kt) + (lane & 15)];
+#pragma unroll
+            for (int yt = 0; yt < kFuMaxNT; ++yt)
+                if (yt < NT) {
+                    const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
+                    const bf16x8 gh = *(const bf16x8*)&gh_s[off];
+                    const bf16x8 gl = *(const bf16x8*)&gl_s[off];
+#pragma unroll
+                    for (int kt = 0; kt < kFuKT; ++kt) {
+                        acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gh, acc[kt][yt], 0, 0, 0);
+                        acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gl, acc[kt][yt], 0, 0, 0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+// the accumulators of a workgroup added to dW (workgroups of other items, labels and frame chunks add theirs)
+__device__ __forceinline__ void fused_dw_flush(const floatx4 (&acc)[kFuKT][kFuMaxNT], float* dW, float scale,
+                                               int NT, int H, int V1)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+#pragma unroll
+    for (int kt = 0; kt < kFuKT; ++kt) {
+        const int k0 = 16 * (kFuKT * wave + kt);
+        if (k0 < H) {
+#pragma unroll
+            for (int yt = 0; yt < kFuMaxNT; ++yt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = k0 + 4 * (lane >> 4) + i, y = 16 * yt + (lane & 15);
+                    if (yt < NT && y < V1) unsafeAtomicAdd(dW + (size_t)k * V1 + y, scale * acc[kt][yt][i]);
+                }
+        }
+    }
+}
+
 // dW = sum over items, frames and states of h^T gamma.  No recursion: grid =
 // B * V * nch workgroups, each owning the rows of one last label b of one item
 // over one chunk of frames; the marginals are rebuilt from the stored forward
@@ -915,8 +993,7 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     float* bs_s = bn_s + kFuMaxRows;
     float* aw_s = bs_s + kFuMaxRows;
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = threadIdx.x;
     const int ch = blockIdx.x % a.nch;
     const int b = (blockIdx.x / a.nch) % V + 1;
     const int item = blockIdx.x / (a.nch * V);
@@ -954,47 +1031,76 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         const float P = (float)(offs[t + 1] - offs[t]);
         fused_rows<true>(w_s, bl_s, bn_s, bs_s, aw_s, P, V, R, b == 1, nullptr, gh_s, gl_s);
         lds_barrier();
-        // row step by row step: the h^T fragments of the wave's four column tiles are formed once,
-        // every gamma fragment is read once and meets all four
-        if (16 * kFuKT * wave < H) {
+        fused_dw_accumulate<MT>(hid_s, gh_s, gl_s, acc, NT, H);
+        lds_barrier();
+    }
+    fused_dw_flush(acc, a.dW, a.scale, NT, H, V1);
+}
+
+// The same sum from the marginals the backward kernel has kept (FusedBwdArgs::gamma_ws): per frame the
+// hidden tile (tanh only, no contraction with W) and the frame's two bf16 planes, fetched with 16-byte
+// loads that are requested before the tanh pass and transposed into LDS after it.
+template <int MT>
+__global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_dw_kept_kernel(FusedBwdArgs a)
+{
+    extern __shared__ unsigned char smem_raw[];
+    const int V = a.V, V1 = V + 1, H = a.H, R = V + 2;
+    const int NT = (V1 + 15) / 16;
+    constexpr int RS = (16 * MT + 31) / 32;
+    constexpr int kRows = 32 * RS;
+    constexpr int kGV = (2 * (64 + 2) * ((64 + 1 + 7) / 8) + kFuThreads - 1) / kFuThreads;   // 16-byte pieces per thread at most (V <= 64)
+    __bf16* hid_s = (__bf16*)smem_raw;                                // [kRows][kFuHF]
+    __bf16* gh_s = hid_s + (size_t)kRows * kFuHF;                     // [kFuMaxRows (y)][kFuGS (r)]
+    __bf16* gl_s = gh_s + (size_t)kFuMaxRows * kFuGS;
+
+    const int tid = threadIdx.x;
+    const int ch = blockIdx.x % a.nch;
+    const int b = (blockIdx.x / a.nch) % V + 1;
+    const int item = blockIdx.x / (a.nch * V);
+    int L = a.len[item];
+    if (L < 0 || L > a.T) L = 0;
+    const int t0 = ch * a.TC, t1 = min(L, t0 + a.TC);
+    if (t0 >= t1) return;
+    for (int i = tid; i < kRows * kFuHF; i += kFuThreads) hid_s[i] = (__bf16)0.f;
+    for (int i = tid; i < 2 * kFuMaxRows * kFuGS; i += kFuThreads) gh_s[i] = (__bf16)0.f;
+    floatx4 acc[kFuKT][kFuMaxNT];
 #pragma unroll
-            for (int rs = 0; rs < RS; ++rs) {
-                bf16x8 hv[kFuKT];
+    for (int kt = 0; kt < kFuKT; ++kt)
 #pragma unroll
-                for (int kt = 0; kt < kFuKT; ++kt)
+        for (int yt = 0; yt < kFuMaxNT; ++yt) acc[kt][yt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+    FusedERows er;
+    fused_load_e(a.e, V, b, R, H, er);
+    const int P8 = (V1 + 7) / 8, per_plane = R * P8;
+    for (int t = t0; t < t1; ++t) {
+        const uintx4* gin = (const uintx4*)(a.gamma_ws + (((size_t)item * a.T + t) * V + (b - 1)) * 2 * R * 8 * P8);
+        uintx4 gv[kGV];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        hv[kt][j] = hid_s[(32 * rs + 8 * (lane >> 4) + j) * kFuHF + 16 * (kFuKT * wave + kt) + (lane & 15)];
+        for (int j = 0; j < kGV; ++j) {
+            const int i = tid + j * kFuThreads;
+            gv[j] = i < 2 * per_plane ? gin[i] : uintx4{0u, 0u, 0u, 0u};
+        }
+        fused_hidden_full(a.f + ((size_t)item * a.T + t) * H, er, hid_s, R, H);
 #pragma unroll
-                for (int yt = 0; yt < kFuMaxNT; ++yt)
-                    if (yt < NT) {
-                        const int off = (16 * yt + (lane & 15)) * kFuGS + 32 * rs + 8 * (lane >> 4);
-                        const bf16x8 gh = *(const bf16x8*)&gh_s[off];
-                        const bf16x8 gl = *(const bf16x8*)&gl_s[off];
+        for (int j = 0; j < kGV; ++j) {
+            const int i = tid + j * kFuThreads;
+            if (i < 2 * per_plane) {
+                const int plane = i >= per_plane ? 1 : 0, k = i - plane * per_plane;
+                const int r = k / P8, c8 = k - r * P8;
+                unsigned short* dst = (unsigned short*)(plane ? gl_s : gh_s) + r;
 #pragma unroll
-                        for (int kt = 0; kt < kFuKT; ++kt) {
-                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gh, acc[kt][yt], 0, 0, 0);
-                            acc[kt][yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hv[kt], gl, acc[kt][yt], 0, 0, 0);
-                        }
-                    }
-                __builtin_amdgcn_sched_barrier(0);
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int y = 8 * c8 + 2 * e2;
+                    if (y <= V) dst[(size_t)y * kFuGS] = (unsigned short)(gv[j][e2] & 0xffffu);
+                    if (y + 1 <= V) dst[(size_t)(y + 1) * kFuGS] = (unsigned short)(gv[j][e2] >> 16);
+                }
             }
         }
         lds_barrier();
+        fused_dw_accumulate<MT>(hid_s, gh_s, gl_s, acc, NT, H);
+        lds_barrier();
     }
-#pragma unroll
-    for (int kt = 0; kt < kFuKT; ++kt) {
-        const int k0 = 16 * (kFuKT * wave + kt);
-        if (k0 < H) {
-#pragma unroll
-            for (int yt = 0; yt < kFuMaxNT; ++yt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int k = k0 + 4 * (lane >> 4) + i, y = 16 * yt + (lane & 15);
-                    if (yt < NT && y < V1) unsafeAtomicAdd(a.dW + (size_t)k * V1 + y, a.scale * acc[kt][yt][i]);
-                }
-        }
-    }
+    fused_dw_flush(acc, a.dW, a.scale, NT, H, V1);
 }
 
 }  // namespace last

@@ -29,7 +29,7 @@ using namespace last;
 namespace {
 
 // process-wide settings (last_set_option)
-std::atomic<int> g_opt[LAST_OPT_COUNT_] = {{0}, {0}, {1}, {1 << 20}, {2}};
+std::atomic<int> g_opt[LAST_OPT_COUNT_] = {{0}, {0}, {1}, {1 << 20}, {2}, {1}};
 inline int opt(int o) { return g_opt[o].load(std::memory_order_relaxed); }
 
 constexpr size_t kAlign = 256;
@@ -420,10 +420,12 @@ last_status_t launch_table_viterbi(const Shape& s, const SoloLayout& l, const fl
 
 // geometry of the fused trigram path (see fused_kernels.hpp)
 constexpr int kFusedMaxLds = 160 * 1024 - 2048;   // dynamic LDS; the kernel also has a little static LDS
+constexpr size_t kFusedKeepBytes = (size_t)8 << 30;   // most that is kept of the marginals between two kernels
 struct FusedPlan {
     bool ok;
     int ncl, XW, KC, R, Mpad, MT;
     int NF;              // frames whose weights the forward kernel computes at a time
+    size_t gamma_elems;  // bf16 values of the marginals the backward kernel keeps for the dW kernel; 0: none kept
     size_t lds;          // forward kernel
     size_t lds_bwd;      // backward recursion kernel
     size_t lds_dw;       // dW kernel
@@ -468,6 +470,10 @@ FusedPlan fused_plan(const Shape& s, const last_weights_t* wt)
     p.TC = (s.T + p.nch - 1) / p.nch;
     p.ok = p.lds <= (size_t)kFusedMaxLds && p.lds_bwd <= (size_t)kFusedMaxLds
            && p.lds_dw <= (size_t)kFusedMaxLds;
+    // marginals kept between the backward and the dW kernel: two bf16 planes of [V + 2][V + 1 rounded up to 8]
+    // per frame and last label, as long as they stay below kFusedKeepBytes
+    const size_t ge = (size_t)s.B * s.T * s.V * 2 * p.R * (size_t)((s.V1 + 7) / 8 * 8);
+    p.gamma_elems = opt(LAST_OPT_FUSED_KEEP_MARGINALS) && ge * 2 <= kFusedKeepBytes ? ge : 0;
     return p;
 }
 
@@ -482,6 +488,7 @@ bool fused_numerator_ok(const last_weights_t* wt)
 struct FusedWs {
     float* alpha;
     float* beta;
+    __bf16* gamma;
     bf16x8* Wf;
     bf16x8* Wt;
     double* offs;
@@ -497,6 +504,7 @@ FusedWs carve_fused(Carver& cv, const Shape& s, const FusedPlan& p, bool keep_al
     FusedWs f;
     f.alpha = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
     f.beta = keep_alpha ? cv.take<float>((size_t)s.B * (s.T + 1) * s.C) : nullptr;
+    f.gamma = keep_alpha && p.gamma_elems ? cv.take<__bf16>(p.gamma_elems) : nullptr;
     f.Wf = cv.take<bf16x8>((size_t)kFuMaxNT * kFuMaxKS * 64);
     f.Wt = keep_alpha ? cv.take<bf16x8>((size_t)32 * 3 * 64) : nullptr;
     f.offs = cv.take<double>((size_t)s.B * (s.T + 1));
@@ -513,11 +521,12 @@ last_status_t launch_fused_forward(const Shape& s, const FusedPlan& p, const Fus
                                    int* item_status, bool keep_alpha, hipStream_t st)
 {
     {
-        const void* kernels[12] = {
+        const void* kernels[15] = {
             (const void*)fused_forward_kernel<1, 1>, (const void*)fused_forward_kernel<3, 1>, (const void*)fused_forward_kernel<5, 1>,
             (const void*)fused_forward_kernel<1, 2>, (const void*)fused_forward_kernel<3, 2>, (const void*)fused_forward_kernel<5, 2>,
             (const void*)fused_backward_kernel<1>, (const void*)fused_backward_kernel<3>, (const void*)fused_backward_kernel<5>,
-            (const void*)fused_dw_kernel<1>, (const void*)fused_dw_kernel<3>, (const void*)fused_dw_kernel<5>};
+            (const void*)fused_dw_kernel<1>, (const void*)fused_dw_kernel<3>, (const void*)fused_dw_kernel<5>,
+            (const void*)fused_dw_kept_kernel<1>, (const void*)fused_dw_kept_kernel<3>, (const void*)fused_dw_kept_kernel<5>};
         for (const void* k : kernels) {
             const last_status_t rc = allow_lds(k, kFusedMaxLds);
             if (rc != LAST_OK) return rc;
@@ -563,6 +572,7 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
     FusedBwdArgs a;
     a.f = (const __bf16*)wt->f; a.e = (const __bf16*)wt->e; a.Wf = f.Wf; a.Wt = f.Wt;
     a.len = lengths; a.alpha_ws = f.alpha; a.offs = f.offs; a.Dws = f.D; a.beta_ws = f.beta;
+    a.gamma_ws = f.gamma;
     a.df = out->df; a.de = out->de; a.dW = out->dW; a.scale = out->scale;
     a.item_status = item_status; a.dist = dist; a.xb = f.xb;
     a.B = s.B; a.T = s.T; a.V = s.V; a.H = H; a.C = s.C;
@@ -570,8 +580,12 @@ last_status_t launch_fused_backward(const Shape& s, const FusedPlan& p, const Fu
     fused_dispatch(p.MT, [&](auto MT) {
         hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_backward_kernel<decltype(MT)::value>), dim3(p.ncl * s.V),
                            dim3(kFuThreads), p.lds_bwd, st, a);
-        hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_dw_kernel<decltype(MT)::value>), dim3(s.B * s.V * p.nch),
-                           dim3(kFuThreads), p.lds_dw, st, a);
+        if (a.gamma_ws)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_dw_kept_kernel<decltype(MT)::value>), dim3(s.B * s.V * p.nch),
+                               dim3(kFuThreads), p.lds_dw, st, a);
+        else
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(fused_dw_kernel<decltype(MT)::value>), dim3(s.B * s.V * p.nch),
+                               dim3(kFuThreads), p.lds_dw, st, a);
     });
     return hip_status();
 }
@@ -660,6 +674,7 @@ last_status_t last_set_option(int32_t option, int32_t value)
     if (option == LAST_OPT_CLUSTER_GENERATION && (value < 0 || value > 3)) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_SPIN_LIMIT && value < 1) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_FUSED_FRAMES_PER_TILE && value != 1 && value != 2) return LAST_ERR_UNSUPPORTED;
+    if (option == LAST_OPT_FUSED_KEEP_MARGINALS && value != 0 && value != 1) return LAST_ERR_UNSUPPORTED;
     g_opt[option].store(value, std::memory_order_relaxed);
     return LAST_OK;
 }

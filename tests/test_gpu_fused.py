@@ -77,6 +77,34 @@ def test_fused_frames_per_tile(B, T, V, H, lens, seed):
     assert torch.equal(got[1], got[2])
 
 
+@pytest.mark.parametrize("keep", [0, 1])
+@pytest.mark.parametrize("B,T,V,H,seed", [(3, 9, 3, 128, 21), (2, 7, 17, 384, 22), (2, 6, 64, 512, 23)])
+def test_fused_gradients_with_and_without_kept_marginals(B, T, V, H, seed, keep):
+    """dW from the marginals the backward kernel kept in the workspace (LAST_OPT_FUSED_KEEP_MARGINALS = 1,
+    the default) and from marginals rebuilt with a third evaluation of the weights (0): both against the
+    oracle; the workspace the library asks for follows the setting."""
+    from gpu_util import library_option
+    announce("fused gradients, kept marginals", keep, B, T, V, H)
+    s = workloads.shared_emb(B=B, T=T, V=V, order=2, H=H, seed=seed, len_lo=max(1, T - 3), len_hi=T)
+    se, lengths = fused_inputs(s), torch.from_numpy(s["lengths"]).cuda()
+    o = oracle.fused_forward_backward(s["f"], s["e"], s["W"], s["lengths"], 2, round_h=True, grads=True)
+    wt = lb.LastWeights(lb.WEIGHTS_SHARED_EMB, B, T, None, se[0].data_ptr(), se[1].data_ptr(), se[2].data_ptr(), H)
+    cx = lb.context(V, 2)
+    with library_option(lb.OPT_FUSED_KEEP_MARGINALS, 0):
+        n0 = lb.last_workspace_bytes(wt, cx, lb.OP_ARC_POSTERIORS)
+    with library_option(lb.OPT_FUSED_KEEP_MARGINALS, 1):
+        n1 = lb.last_workspace_bytes(wt, cx, lb.OP_ARC_POSTERIORS)
+    assert n1 >= n0 + B * T * V * (V + 2) * (V + 1) * 4
+    with library_option(lb.OPT_FUSED_KEEP_MARGINALS, keep):
+        st = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        dist, grads = lb.last_arc_posteriors(se, lengths, order=2, item_status=st)
+        torch.cuda.synchronize()
+    assert st.cpu().tolist() == [0] * B
+    assert_dist_close(dist.cpu().numpy(), o["D"])
+    for name, a, b in zip(("df", "de", "dW"), grads, (o["df"], o["de"], o["dW"])):
+        assert_grad_close(name, a.cpu().numpy(), b.astype(np.float64))
+
+
 # Gradients of the fused path: the marginals enter two bf16 matrix-core contractions as hi + lo
 # halves (16 significant bits), tanh is evaluated in float32 before the bf16 rounding (a value
 # that lands within ~1e-6 of a rounding boundary may round the other way than the float64
