@@ -249,7 +249,9 @@ last_status_t last_shortest_distance_static(const last_weights_t* weights, const
  *     dense bigram lattices take; 0 = the newest that supports the shape, 3 = sixteen workgroups per
  *     direction and item (256 labels only), 2 = eight (5..264 states), 1 = the oldest (one exchange per
  *     frame).  A generation that does not support the shape falls back to the next older one.
- *   LAST_OPT_CLUSTER_VITERBI (0/1, default 1): 0 = shortest path with one workgroup per item.
+ *   LAST_OPT_CLUSTER_VITERBI (0..2, default 1): shortest path of dense bigram lattices: 0 = one workgroup
+ *     per item; 1 = cooperating workgroups, the newest kernel that takes the shape; 2 = cooperating
+ *     workgroups, the older kernel also where the newer one (256 labels only) would run.
  *   LAST_OPT_SPIN_LIMIT (>= 1, default 2^20): polls a cooperating workgroup makes before it gives up
  *     waiting for the others (the item then gets status 5 and dist = NaN; every kernel still ends).
  *   LAST_OPT_FUSED_FRAMES_PER_TILE (1 or 2, default 2): frames whose on-the-fly weights the forward

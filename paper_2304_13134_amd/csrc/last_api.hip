@@ -12,6 +12,7 @@
 #include "cluster2_kernels.hpp"
 #include "cluster2v_kernels.hpp"
 #include "cluster3_kernels.hpp"
+#include "cluster3v_kernels.hpp"
 #include "fused_kernels.hpp"
 #include "fused_numerator_kernels.hpp"
 #include "probe_kernels.hpp"
@@ -613,6 +614,7 @@ bool launch_bigram_viterbi(const Shape& s, const float* w, const int* lengths, i
 // geometry of the clustered tropical kernel (cluster2v_kernels.hpp): K workgroups per item
 struct ViterbiPlan {
     bool ok;
+    int gen;             // 3: cluster3v_kernels.hpp (256 labels), 2: cluster2v_kernels.hpp
     int K, RPW, ncl, grid;
     size_t xwords;
 };
@@ -634,6 +636,8 @@ ViterbiPlan viterbi_plan(const Shape& s, int kind)
     p.ncl = want < max_ncl ? want : max_ncl;
     p.grid = 8 * p.ncl * p.K;
     p.xwords = (size_t)8 * p.ncl * 2 * kClMaxK * kC2XS + (size_t)2 * s.B;    // exchange slots + per-item end words
+    p.gen = (s.C == kV3C && opt(LAST_OPT_CLUSTER_VITERBI) != 2) ? 3 : 2;
+    static_assert(kV3K == kClMaxK && kV3XS == kC2XS, "both kernels use the same exchange area");
     p.ok = true;
     return p;
 }
@@ -647,6 +651,11 @@ void launch_cluster_viterbi(const Shape& s, const ViterbiPlan& p, u64* xv, const
     a.item_status = item_status; a.xa = xv; a.fin = xv + (p.xwords - (size_t)2 * s.B);
     a.B = s.B; a.T = s.T; a.C = s.C; a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl;
     a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
+    if (p.gen == 3) {
+        if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3v_kernel<true>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+        else hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3v_kernel<false>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+        return;
+    }
     const bool full = p.K == kClMaxK;      // (the instantiation without a test per exchanged word)
     if (bp && full) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, true>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
     else if (bp) hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster2v_kernel<true, false>), dim3(p.grid), dim3(kC2Threads), 0, st, a);
@@ -673,6 +682,7 @@ last_status_t last_set_option(int32_t option, int32_t value)
     if (option < 0 || option >= LAST_OPT_COUNT_) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_CLUSTER_GENERATION && (value < 0 || value > 3)) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_SPIN_LIMIT && value < 1) return LAST_ERR_UNSUPPORTED;
+    if (option == LAST_OPT_CLUSTER_VITERBI && (value < 0 || value > 2)) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_FUSED_FRAMES_PER_TILE && value != 1 && value != 2) return LAST_ERR_UNSUPPORTED;
     if (option == LAST_OPT_FUSED_KEEP_MARGINALS && value != 0 && value != 1) return LAST_ERR_UNSUPPORTED;
     g_opt[option].store(value, std::memory_order_relaxed);

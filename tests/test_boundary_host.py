@@ -155,6 +155,7 @@ def test_table_context_is_checked_on_the_host(lib):
 def test_options_are_validated(lib):
     """last_set_option refuses unknown options and values and leaves the setting as it was."""
     for option, good, bad in [(lb.OPT_CLUSTER_GENERATION, (0, 1, 2, 3), (-1, 4)),
+                              (lb.OPT_CLUSTER_VITERBI, (0, 1, 2), (-1, 3)),
                               (lb.OPT_SPIN_LIMIT, (1, 1 << 20), (0, -5)),
                               (lb.OPT_FUSED_FRAMES_PER_TILE, (1, 2), (0, 3)),
                               (lb.OPT_FUSED_KEEP_MARGINALS, (0, 1), (-1, 2))]:

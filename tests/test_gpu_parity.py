@@ -150,6 +150,24 @@ def test_one_workgroup_shortest_path_kernels():
             check_path(workloads.dense(B=2, T=9, V=V, order=1, sigma=1.0, seed=V, len_lo=5, len_hi=9))
 
 
+def test_both_clustered_shortest_path_kernels_at_256_labels():
+    """256 labels take the kernel with the work cut down to the wave (LAST_OPT_CLUSTER_VITERBI = 1, the
+    default); 2 selects the older clustered kernel, which other label counts use anyway.  Both against the
+    oracle: random weights with ragged lengths (a length of 1, of 2, odd and even ones), integer weights
+    with many ties, all-equal weights, forbidden arcs."""
+    rng = np.random.default_rng(11)
+    for mode in (1, 2):
+        with library_option(lb.OPT_CLUSTER_VITERBI, mode):
+            announce("clustered shortest path at 256 labels, kernel", mode)
+            cfg = workloads.config(2, B=9, T=21)
+            cfg["lengths"] = np.array([21, 20, 1, 2, 3, 0, 17, 8, 21], np.int32)
+            check_path(cfg)
+            wc = rng.integers(-1, 2, size=(3, 12, 257, 257)).astype(np.float32)
+            check_path(dict(w=wc, lengths=np.array([12, 7, 11], np.int32), B=3))
+            check_path(dict(w=np.zeros((2, 6, 257, 257), np.float32), lengths=np.array([6, 5], np.int32), B=2))
+            check_path(forbid_arcs(workloads.config(2, B=2, T=10), 5))
+
+
 def forbid_arcs(cfg, seed):
     """A third of the arcs, every arc out of state 5 and label 7 at frame 3 get weight -1e4."""
     rng = np.random.default_rng(seed)
@@ -494,19 +512,20 @@ def test_bounded_waits_end_every_kernel_and_are_reported():
             else:
                 assert abs(dist[b] - D_o[b]) <= 1e-5 * abs(D_o[b])
                 assert np.max(np.abs(dw[b] - gamma_o[b])) <= TOL_POST_ABS
-    announce("spin limit 1, clustered shortest path")
-    with library_option(lb.OPT_SPIN_LIMIT, 1):
-        st = torch.full((6,), -1, dtype=torch.int32, device="cuda")
-        labels, states, score = lb.last_shortest_path(w, lengths, item_status=st)
-        torch.cuda.synchronize()
-    st = st.cpu().numpy()
-    assert set(st.tolist()) <= {0, 5}
-    for b in range(6):
-        if st[b] == 5:
-            assert torch.isnan(score[b]) and torch.all(labels[b] == -1) and torch.all(states[b] == -1)
-            seen_timeouts += 1
-        else:
-            assert np.array_equal(labels[b].cpu().numpy(), l_o[b]) and float(score[b]) == sc_o[b]
+    for mode in (1, 2):
+        announce("spin limit 1, clustered shortest path, kernel", mode)
+        with library_option(lb.OPT_CLUSTER_VITERBI, mode), library_option(lb.OPT_SPIN_LIMIT, 1):
+            st = torch.full((6,), -1, dtype=torch.int32, device="cuda")
+            labels, states, score = lb.last_shortest_path(w, lengths, item_status=st)
+            torch.cuda.synchronize()
+        st = st.cpu().numpy()
+        assert set(st.tolist()) <= {0, 5}
+        for b in range(6):
+            if st[b] == 5:
+                assert torch.isnan(score[b]) and torch.all(labels[b] == -1) and torch.all(states[b] == -1)
+                seen_timeouts += 1
+            else:
+                assert np.array_equal(labels[b].cpu().numpy(), l_o[b]) and float(score[b]) == sc_o[b]
     assert seen_timeouts > 0, "the bounded-wait path was not exercised"
     announce("normal spin limit again")
     check_posteriors(cfg)
