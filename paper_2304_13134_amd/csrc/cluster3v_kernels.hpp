@@ -34,17 +34,6 @@
 
 namespace last {
 
-#ifdef LAST_TRACE
-#define V3_MARK(p, k)                                                                          \
-    do {                                                                                       \
-        if (v3_trace && (p) < 64 && threadIdx.x == 0)                                          \
-            v3_trace[((size_t)blockIdx.x * 64 + (p)) * 16 + (k)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-__device__ unsigned long long* v3_trace = nullptr;
-#else
-#define V3_MARK(p, k) do { } while (0)
-#endif
-
 constexpr int kV3K = 8;                       // workgroups per item
 constexpr int kV3C = kC3C;                    // 257 states
 constexpr int kV3V1 = kC3C;                   // labels including the empty one (full 1-gram context: C = V + 1)
@@ -228,7 +217,6 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
             constexpr int B2_ = (B_ + 2) % 3;
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= L) return false;
-            V3_MARK(p, 0);
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             {
                 float best[4];
@@ -267,9 +255,7 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 if (!(lo || l4 || l8)) { mv = LAST_NEG_INF; mf = kVNone; }
                 const float sv = dpp_f<0x108>(LAST_NEG_INF, mv);      // lanes 0..7 take lanes 8..15
                 const int sf = dpp_i<0x108>(kVNone, mf);
-                V3_MARK(p, 1);
                 c2_barrier();
-                V3_MARK(p, 2);
                 // own states: lane j < 4 combines the eight waves' results of column 4 wave + j
                 float v = LAST_NEG_INF;
                 int f = kVNone;
@@ -291,7 +277,6 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 if (BP && (lane < 4 || l4)) bpi[(size_t)tF * C + (lane < 4 ? 1 + 4 * g.u + lane : 0)] = f == kVNone ? -1 : f;
             }
             if (tP >= L) return false;
-            V3_MARK(p, 3);
             // ---------------- P-step: frame tP, own rows x all columns, best candidate for every label state
             {
                 const unsigned tag = gstep + 1;
@@ -328,9 +313,7 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                     blv_s[8 * wave + lane] = cv;
                     bli_s[8 * wave + lane] = (has && cv > LAST_NEG_INF) ? (lane < 4 ? 1 + 4 * g.u + lane : 0) * V1 : kVNone;
                 }
-                V3_MARK(p, 4);
                 c2_barrier();
-                V3_MARK(p, 5);
                 if (tid < 256) {
                     float pv = pav_s[tid];
                     int pf = pai_s[tid];
@@ -346,15 +329,9 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                                   (unsigned)(k * kV3XS) * 8u, slot_off);
                     }
                 }
-                V3_MARK(p, 6);
                 v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, k,
                           BP ? bpi + (size_t)tP * C : nullptr,
-                          [&]() __attribute__((always_inline)) {
-                              V3_MARK(p, 7);
-                              issue(std::integral_constant<int, B2_>(), p + 2);
-                              V3_MARK(p, 8);
-                          });
-                V3_MARK(p, 9);
+                          [&]() __attribute__((always_inline)) { issue(std::integral_constant<int, B2_>(), p + 2); });
                 gstep += 1;
             }
             ++p;
