@@ -87,15 +87,6 @@ constexpr int kC2Lds = kC2Red2 + kC2Waves * kC2NQ * kC2R2S;
 static_assert(kC2Red2 % 4 == 0 && kC2R2S % 4 == 0, "16-byte reads of the per-row partials");
 static_assert(kC2Red % 2 == 0 && kC2Shc % 2 == 0 && kC2Bt % 2 == 0 && kC2Own % 2 == 0, "8-byte LDS accesses");
 
-#ifdef LAST_TRACE
-#define C2_MARK(a, p, k)                                                                    \
-    do {                                                                                    \
-        if ((a).trace && (p) < 64 && threadIdx.x == 0)                                      \
-            (a).trace[((size_t)blockIdx.x * 64 + (p)) * 8 + (k)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-#else
-#define C2_MARK(a, p, k) do { } while (0)
-#endif
 
 __device__ __forceinline__ void c2_barrier()
 {
@@ -668,8 +659,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
             constexpr int B_ = decltype(BUF)::value;
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= n) return false;
-            C2_MARK(a, p, 0);
-            C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             if (tF == mid && !met) {
                 meet();
@@ -693,7 +682,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 }
                 if (v0ok) red_s[slotF] = ps0;
                 if (v1ok) red_s[slotF + 1] = ps1;
-                C2_MARK(a, p, 6);
                 if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
                     const int sbk = __builtin_amdgcn_readlane(sbF[B_], g.k);
@@ -723,7 +711,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                     }
                 }
                 c2_barrier();
-                C2_MARK(a, p, 7);
                 // next pair's F frame: waves 1..7 request theirs while wave 0 adds up the columns; wave 0
                 // requests its own afterwards (alone on the address path, that is quick)
                 if (wave != 0) issueF(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, kC2FJ);
@@ -758,7 +745,6 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                 c2_barrier();
             }
             if (tP >= n) return false;
-            C2_MARK(a, p, 2);
             issueP(std::integral_constant<int, B_ ^ 1>(), p + 1, 0, 9);
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) {
@@ -828,15 +814,12 @@ __device__ __forceinline__ void alpha2_role(const ClusterArgs& a, const ClusterG
                         c2_put<ACC>(own_s[min(lane, kC2Own - 1)] * ES[B_] * fyS, grs, coffS, gso);
                     }
                 }
-                C2_MARK(a, p, 3);
                 // first look at the exchange halfway through the exp pass: early enough for the round trip to
                 // the L2 cache to end with the pass, late enough for the other workgroups' words to be there
                 C2Look lk;
                 prep(std::integral_constant<int, B_ ^ 1>(), [&]() __attribute__((always_inline)) { if (exch) c2_gather_look<FULL>(xs, K, C, lk); });
-                C2_MARK(a, p, 4);
                 if (exch) {
                     c2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk, [] {});
-                    C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP + 1 <= mid && wave == 6) {      // (a wave with no other special duty)
                         if (lane < g.nr) ah[(size_t)(tP + 1) * C + g.r0 + lane] = full_s[g.r0 + lane];
@@ -1136,8 +1119,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
             constexpr int B_ = decltype(BUF)::value;
             const int iF = 2 * p, iP = 2 * p + 1;
             if (iF >= n) return false;
-            C2_MARK(a, p, 0);
-            C2_MARK(a, p, 1);
             // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
             if (iF == ph1 && !met) {
                 meet();
@@ -1162,7 +1143,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 const float bS = full_s[min(kC2PC + sI, 319)];
                 const float sprod = ESb[B_] * bS;
                 float facS = 0.f;
-                C2_MARK(a, p, 6);
                 // all five rows at once, without branches: the cross-lane sums overlap (a row the wave does
                 // not have gives a sum that is not written)
                 float brow[kC2RW], tot[kC2RW];
@@ -1202,7 +1182,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     }
                 }
                 if (GAMMA && iF >= ph1 && nstF > 0) c2_put<ACC>(sprod * facS, grs, offSt, (unsigned)tF * frb);
-                C2_MARK(a, p, 7);
                 c2_barrier();
                 {
                     // Every wave by itself, lane <-> own state: the same values from the same inputs, written
@@ -1226,7 +1205,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 }
             }
             if (iP >= n) return false;
-            C2_MARK(a, p, 2);
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) {
                 meet();
@@ -1303,7 +1281,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                         c2_put<ACC>(afull_s[yF] * EB[B_] * fb, grs, rowB, gso);
                     }
                 }
-                C2_MARK(a, p, 3);
                 // the P frame of the pair after the next, into the registers this P-step has finished with
                 if (wave < 4) issueP(std::integral_constant<int, B_>(), p + 2);
                 // first look at the exchange halfway through the exp pass: early enough for the round trip to
@@ -1313,7 +1290,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                     if (wave >= 4) issueP(std::integral_constant<int, B_>(), p + 2);
                     if (exch) c2_gather_look<FULL>(xs, K, C, lk);
                 });
-                C2_MARK(a, p, 4);
                 // The F frame of the pair after the next goes into the registers this pair's F-step has
                 // finished with; requested once the exchanged words are there, the requests pass the address
                 // path while the words are added up.
@@ -1321,7 +1297,6 @@ __device__ __forceinline__ void beta2_role(const ClusterArgs& a, const ClusterGe
                 if (exch) {
                     c2_gather<FULL>(xs, K, C, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) { issueF(std::integral_constant<int, B_>(), p + 2); });
-                    C2_MARK(a, p, 5);
                     gstep += 1;
                     if (tP >= mid && wave == 6) {          // (a wave with no other special duty)
                         if (lane < g.nr) bh[(size_t)tP * C + g.r0 + lane] = full_s[g.r0 + lane];

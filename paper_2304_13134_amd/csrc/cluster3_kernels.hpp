@@ -67,24 +67,6 @@ constexpr int kC3RedB = kC3Ctl + 64;            // [32] block reductions
 constexpr int kC3Lds = kC3RedB + 32;
 static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl % 4 == 0, "16-byte LDS accesses");
 
-#ifdef LAST_TRACE
-#define C3_MARK(a, p, k)                                                                     \
-    do {                                                                                     \
-        if ((a).trace && (p) < 64 && threadIdx.x == 0)                                       \
-            (a).trace[((size_t)blockIdx.x * 64 + (p)) * 16 + (k)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-#define C3_NOTE(a, p, k, v)                                                                  \
-    do {                                                                                     \
-        if ((a).trace && (p) < 64 && threadIdx.x == 0)                                       \
-            (a).trace[((size_t)blockIdx.x * 64 + (p)) * 16 + (k)] = (unsigned long long)(v); \
-    } while (0)
-#elif defined(C3_ASM_MARKS)
-#define C3_MARK(a, p, k) asm volatile("; C3SEC " #k)
-#define C3_NOTE(a, p, k, v) do { } while (0)
-#else
-#define C3_MARK(a, p, k) do { } while (0)
-#define C3_NOTE(a, p, k, v) do { } while (0)
-#endif
 
 // Weight loads use the default cache policy although every weight is read once per pass: with the
 // non-temporal hint on all of them the kernel was measured 2.5 % slower (neighbouring workgroups share
@@ -207,7 +189,7 @@ __device__ __forceinline__ float c3_rows_sum(float x)
 template <typename AfterPoll>
 __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned voffq, unsigned voffz, unsigned tag,
                                           float* full_s, int* ctl_s, int limit, int& dead, C3Look& lk,
-                                          AfterPoll&& after_poll, int* relooks = nullptr)
+                                          AfterPoll&& after_poll)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -222,7 +204,6 @@ __device__ __forceinline__ void c3_gather(buf_t xrs, unsigned slot_off, unsigned
         __builtin_amdgcn_s_sleep(1);
         c3_look(xrs, slot_off, voffq, voffz, lk);
     }
-    if (relooks) *relooks = n;
     after_poll();
     const int e0 = (int)(short)(unsigned short)lk.q[0].y, e1 = (int)(short)(unsigned short)lk.q[1].y;
     int hm = max(e0, e1);
@@ -582,7 +563,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             };
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             if (tF == mid && !met) { meet(); after_meeting(); }
-            C3_MARK(a, p, 0);
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
@@ -629,9 +609,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                     const float fm = a.scale * bFm[B_] * c3_mscale(S + sF[B_] + eFm[B_], D, xwide);
                     c2_put<ACC>(am * EF[B_].m * fm, grs, g.voffMc, gso);
                 }
-                C3_MARK(a, p, 1);
                 c2_barrier();
-                C3_MARK(a, p, 2);
                 // own states: lane j < 4 adds up the eight waves' sums of column 4 wave + j
                 const int4 sh0 = *(const int4*)&ctl_s[8], sh1 = *(const int4*)&ctl_s[12];
                 const int smax = max(max(max(sh0.x, sh0.y), max(sh0.z, sh0.w)), max(max(sh1.x, sh1.y), max(sh1.z, sh1.w)));
@@ -650,7 +628,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 if (tF + 1 <= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)(tF + 1) * kC3SP);
             }
             if (tP >= n) return false;
-            C3_MARK(a, p, 3);
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) { meet(); after_meeting(); }
             {
@@ -681,9 +658,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
 #pragma unroll
                     for (int j = 2; j < 5; ++j) c3_load_rows_slot(EP[B_ ^ 1], j, wrs, g, foP1);
                 }
-                C3_MARK(a, p, 4);
                 c2_barrier();
-                C3_MARK(a, p, 5);
                 const bool exch = !(GAMMA && tP == L - 1);
                 if (exch && tid < 256) {
                     const int4 tw0 = *(const int4*)&ctl_s[16], tw1 = *(const int4*)&ctl_s[20];
@@ -725,7 +700,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // exp pass of the next pair, with the requests for the pair after the next (into the registers
                 // this pair has finished with) between its pieces; the look at the exchange comes before the
                 // frames' requests, because a wave's loads return in order
-                C3_MARK(a, p, 6);
                 C3Look lk;
                 const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb;
                 prep(std::integral_constant<int, B_ ^ 1>(),
@@ -733,26 +707,19 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                          if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
                      },
                      [&]() __attribute__((always_inline)) {
-                         C3_MARK(a, p, 11);
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
-                         C3_MARK(a, p, 12);
                      },
                      [](int) {});
-                C3_MARK(a, p, 7);
                 if (!exch) {
 #pragma unroll
                     for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
                 }
                 if (exch) {
-                    int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
-                                  C3_MARK(a, p, 8);
 #pragma unroll
                                   for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
-                              }, &relooks);
-                    C3_MARK(a, p, 9);
-                    C3_NOTE(a, p, 10, relooks);
+                              });
                     gstep += 1;
                     if (tP + 1 <= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)(tP + 1) * kC3SP);
                 }
@@ -921,7 +888,6 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
             };
             // ---------------- F-step: frame tF, own rows x all columns, from the whole vector
             if (iF == ph1 && !met) { meet(); after_meeting(); }
-            C3_MARK(a, p, 0);
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
@@ -988,12 +954,9 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 if (lane == 4 && g.xR) own_s[32] = own;
                 if (lane == 0) ctl_s[8 + wave] = ek;
                 if (tF >= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)tF * kC3SP);
-                C3_MARK(a, p, 1);
                 c2_barrier();
-                C3_MARK(a, p, 2);
             }
             if (iP >= n) return false;
-            C3_MARK(a, p, 3);
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) { meet(); after_meeting(); }
             {
@@ -1043,9 +1006,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                     for (int j = 2; j < 5; ++j) c3_load_cols_slot(EP[B_ ^ 1], j, wrs, g, foP1);
                 }
-                C3_MARK(a, p, 4);
                 c2_barrier();
-                C3_MARK(a, p, 5);
                 const bool exch = !(GAMMA && iP == L - 1);
                 if (exch && tid < 256) {
                     const int4 tw0 = *(const int4*)&ctl_s[16], tw1 = *(const int4*)&ctl_s[20];
@@ -1080,7 +1041,6 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                     const float fm = a.scale * aPm[B_] * c3_mscale(ePm[B_] + tb, D, xwide);
                     c2_put<ACC>(mo * fm, grs, g.voffMc, gso);
                 }
-                C3_MARK(a, p, 6);
                 C3Look lk;
                 const unsigned foF2 = (unsigned)frameF(p + 2) * frb;
                 prep(std::integral_constant<int, B_ ^ 1>(),
@@ -1088,26 +1048,19 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                          if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
                      },
                      [&]() __attribute__((always_inline)) {
-                         C3_MARK(a, p, 11);
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
-                         C3_MARK(a, p, 12);
                      },
                      [](int) {});
-                C3_MARK(a, p, 7);
                 if (!exch) {
 #pragma unroll
                     for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
                 }
                 if (exch) {
-                    int relooks = 0;
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
-                                  C3_MARK(a, p, 8);
 #pragma unroll
                                   for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
-                              }, &relooks);
-                    C3_MARK(a, p, 9);
-                    C3_NOTE(a, p, 10, relooks);
+                              });
                     gstep += 1;
                     if (tP >= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)tP * kC3SP);
                 }

@@ -66,21 +66,10 @@ constexpr int kClMaxK = 8;       // max workgroups per role
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kShiftNone = -30000;
 constexpr int kClXK = 8;         // words per exchange row (alpha): one 64-byte scalar load
+constexpr int kClAuxDelay = 4;   // units of 256 clocks the polling wave waits before its first look (measured best)
 constexpr int kClCH = 24;        // exchange words gathered per wave: three 64-byte scalar loads
 constexpr int kClLds = 2 * kClMaxR * 2 + 2 * 320 + 320 + 64 + 32 + 64;   // floats
 
-// Optional cycle-counter marks for tuning (compiled out unless LAST_TRACE is defined):
-// trace[((workgroup * 2 + is_comm) * 64 + step) * 4 + k] = clock of mark k
-#ifdef LAST_TRACE
-#define LAST_MARK(a, iscomm, step, k)                                                          \
-    do {                                                                                       \
-        if ((a).trace && (step) < 64 && (threadIdx.x & 63) == 0 &&                             \
-            ((iscomm) || threadIdx.x == 0))                                                    \
-            (a).trace[(((size_t)blockIdx.x * 2 + (iscomm)) * 64 + (step)) * 4 + (k)] = clock64(); \
-    } while (0)
-#else
-#define LAST_MARK(a, iscomm, step, k) do { } while (0)
-#endif
 
 struct ClusterArgs {
     const float* w;
@@ -103,10 +92,6 @@ struct ClusterArgs {
     float scale;
     int accumulate;
     int spin_limit;
-    int aux_delay;     // units of 256 clocks the aux wave waits before its first poll
-#ifdef LAST_TRACE
-    unsigned long long* trace;
-#endif
 };
 
 // ---- cross-lane helpers on DPP (the critical path cannot afford LDS permutes)
@@ -465,7 +450,6 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
             }
             if (i >= n) return false;
             const bool exch = i < nex;
-            LAST_MARK(a, aux ? 1 : 0, i, 0);
             if (!aux) {
                 // ---- FMA loop, hand-over between the two halves, publish
                 const int P = ctl_s[par];
@@ -502,7 +486,6 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     pub += ((volatile float*)pacc_s)[c];
                     if (exch && colok && c >= 1) xpublish(xs + (size_t)c * kClXK + g.k, pack_word(pub, tag));
                 }
-                LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= mid && colok) {
                     const float kx = (float)((double)(ctl_s[2 + par] + sbn[par]) - D2);
                     const float fac = a.scale * fast_exp2(kx + (float)sc[S]) * (c == 0 ? 1.f : bcol[par]);
@@ -523,10 +506,8 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     sbn[par] = Sb[i + 3];
                 }
                 issue((S + D - 1) % D, min(i + D - 1, nlast));
-                LAST_MARK(a, 0, i, 2);
                 prep((S + 1) % D);
                 if (GAMMA && i + 1 < n && i + 1 >= mid && colok) bv_s[(par ^ 1) * 320 + c] = bcol[par ^ 1];
-                LAST_MARK(a, 0, i, 3);
             }
             if (exch) {
                 // ---- gather: every wave sums the partial columns of three of the own rows
@@ -537,7 +518,7 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                     // the aux wave has nothing else to do: do not poll before the producers can
                     // have published (a poll served too early costs a whole extra round trip)
                     if (aux)
-                        for (int dly = 0; dly < a.aux_delay; ++dly) __builtin_amdgcn_s_sleep(4);
+                        for (int dly = 0; dly < kClAuxDelay; ++dly) __builtin_amdgcn_s_sleep(4);
                     // rows beyond the owned range are still loaded (inside the buffer) and ignored
                     const void* rowp = xs + (size_t)(g.r0 + min(gr0, g.nr - 1)) * kClXK;
                     // the start state (q = 0) receives no label arcs: its row is never written
@@ -563,7 +544,6 @@ __device__ __forceinline__ void alpha_role(const ClusterArgs& a, const ClusterGe
                             if (j < KT) mu = max(mu, (int)vh[2 * j]);
                     }
                 }
-                if (aux) LAST_MARK(a, 1, i, 1);
                 if (lane == 0) {
                     if (grn > 0) ap_s[(par ^ 1) * kClMaxR + lds_row(gr0)] = s0;
                     if (grn > 1) ap_s[(par ^ 1) * kClMaxR + lds_row(gr0 + 1)] = s1;
@@ -728,7 +708,6 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
             const bool exch = i < nex;
             const unsigned tag = gstep + 1;
             u64* xs = xbase + (size_t)(gstep & 1) * a.XSB;
-            LAST_MARK(a, aux ? 1 : 0, i, 0);
             if (!aux) {
                 float bv[kClNC];
 #pragma unroll
@@ -746,7 +725,6 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     if (exch && lane == 0 && ri < nrw)
                         xpublish(xs + row, pack_word(__builtin_ldexpf(tot, sr[S][ri] - P_cur), tag));
                 }
-                LAST_MARK(a, 0, i, 1);
                 if (GAMMA && i >= ph1) {
                     const float kx = (float)((double)(san[par] + sig) - D2);
                     const unsigned gso = (unsigned)t * frb;
@@ -772,9 +750,7 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     san[par] = Sa[t2];
                 }
                 issue((S + D - 1) % D, min(i + D - 1, nlast));
-                LAST_MARK(a, 0, i, 2);
                 prep((S + 1) % D);
-                LAST_MARK(a, 0, i, 3);
             }
             if (exch) {
                 // ---- gather: every wave fetches 24 of the C state values through the scalar path
@@ -814,7 +790,6 @@ __device__ __forceinline__ void beta_role(const ClusterArgs& a, const ClusterGeo
                     if (lane == 0) ctl_s[(par ^ 1) * 16 + wave] = mu;
                     if (dead && lane == 0) ctl_s[40] = 1;
                 }
-                if (aux) LAST_MARK(a, 1, i, 1);
                 gstep += 1;
             }
             __syncthreads();

@@ -63,20 +63,8 @@ struct FusedArgs {
     int B, T, V, H, C;
     int ncl, XW;
     int spin_limit;
-#ifdef LAST_TRACE
-    unsigned long long* trace;   // [frames][32] cycle marks of workgroup 0 (tuning builds only)
-#endif
 };
 
-#ifdef LAST_TRACE
-#define FU_MARK(a, t, k)                                                                        \
-    do {                                                                                        \
-        if ((a).trace && blockIdx.x == 0 && threadIdx.x == 0 && (t) >= 0 && (t) < 256)          \
-            (a).trace[(size_t)(t) * 32 + (k)] = __builtin_amdgcn_s_memtime();                    \
-    } while (0)
-#else
-#define FU_MARK(a, t, k) do { } while (0)
-#endif
 
 __device__ __forceinline__ float word_value(u64 x) { return __uint_as_float((unsigned)x); }
 
@@ -185,16 +173,8 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
                                                      __bf16* hid_s, floatx4 (&acc)[NF][MT],
                                                      const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NTL,
                                                      const u64* early, u64& early_word
-#ifdef LAST_TRACE
-                                                     , unsigned long long* trace_row
-#endif
                                                      )
 {
-#ifdef LAST_TRACE
-#define FU_PMARK(k) do { if (trace_row && blockIdx.x == 0 && threadIdx.x == 0) trace_row[(k)] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define FU_PMARK(k) do { } while (0)
-#endif
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int NC = H / kFuKC;
@@ -211,7 +191,6 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
 #pragma unroll 1
     for (int p = 0; p <= NC; ++p) {
         if (p == 2 && early) early_word = xload(early);
-        FU_PMARK(8 + 3 * p);
         if (p >= 1) {
 #pragma unroll
             for (int fr = 0; fr < NF; ++fr) {
@@ -233,7 +212,6 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
                 }
             }
         }
-        FU_PMARK(9 + 3 * p);
         if (p < NC) {
             __bf16* hb = hid_s + (p & 1) * NF * (16 * MT * kFuHS) + 2 * kp;
             unsigned f2[NF];
@@ -254,7 +232,6 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
                     if (r2 < r_end) *(unsigned*)(hf + r2 * kFuHS) = tanh_pair(f2[fr], e2);
                 }
             }
-            FU_PMARK(10 + 3 * p);
             lds_barrier();
         }
     }
@@ -417,7 +394,6 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 float* an = al_s + (par ^ 1) * kFuMaxRows;
                 const unsigned tag = gstep + 1;
                 u64* xs = xbase + (size_t)(gstep & 1) * (V + 1) * a.XW;
-                FU_MARK(a, t, 0);
                 // label arcs (b), (a,b) --y--> (b,y): reduced over the own rows, sent to workgroup y
                 if (live && wave < NTL) {
                     const int g = lane >> 4, y = 16 * wave + (lane & 15) + 1;
@@ -457,9 +433,7 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                                 pb_s[(wave - 4) * kFuMaxRows + 16 * mt + 4 * (lane >> 4) + i] = acc[j][mt][i];
                     }
                 }
-                FU_MARK(a, t, 1);
                 lds_barrier();
-                FU_MARK(a, t, 2);
                 // after the last frame of the group: the weights of the next group while the partial values
                 // travel; the first look at the incoming words is issued half way and consumed afterwards
                 const u64* pw = nullptr;
@@ -470,21 +444,14 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 u64 x = 0;
                 if (j == NF - 1) keep(min(t0 + NF - 1, L));
                 if (j == NF - 1 && t0 + NF < L) {
-#ifdef LAST_TRACE
-                    fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x,
-                                                 (a.trace && t >= 0 && t < 256) ? a.trace + (size_t)t * 32 : nullptr);
-#else
                     fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x);
-#endif
                 } else if (pw) {
                     x = xload(pw);
                 }
                 if (!live) continue;
-                FU_MARK(a, t, 3);
                 // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
                 float hv = LAST_NEG_INF;
                 if (pw) x = poll_from(pw, x, tag, a.spin_limit, dead);
-                FU_MARK(a, t, 4);
                 // empty-label arc of own row r: alpha[r] + w[r][0]
                 auto blank = [&](int r) {
                     return al[r] + ((pb_s[r] + pb_s[kFuMaxRows + r]) + (pb_s[2 * kFuMaxRows + r] + pb_s[3 * kFuMaxRows + r])) - P_cur;
@@ -504,10 +471,8 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                     if (lane == 0) red[0] = hm;
                 }
                 if (dead) ctl_s[0] = 1;
-                FU_MARK(a, t, 5);
                 lds_barrier();
                 const float mu = red[0];
-                FU_MARK(a, t, 6);
                 // offset bookkeeping, identical everywhere
                 const float G = mu - mu_prev + P_prev;
                 const float P_next = mu + 2.f * G - P_cur;

@@ -309,7 +309,6 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.K = p.K; a.RPW = p.RPW; a.ncl = p.ncl; a.XS = p.XS; a.XSB = p.XSB;
     a.scale = scale; a.accumulate = accumulate;
     a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
-    a.aux_delay = 4;
     if (p.gen == 3) {
         if (GAMMA && accumulate)
             hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, GAMMA>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
