@@ -166,6 +166,10 @@ def test_both_clustered_shortest_path_kernels_at_256_labels():
             check_path(dict(w=wc, lengths=np.array([12, 7, 11], np.int32), B=3))
             check_path(dict(w=np.zeros((2, 6, 257, 257), np.float32), lengths=np.array([6, 5], np.int32), B=2))
             check_path(forbid_arcs(workloads.config(2, B=2, T=10), 5))
+            # more items than clusters: every cluster walks several items one after the other
+            many = workloads.config(2, B=35, T=6)
+            many["lengths"] = (np.arange(35) % 7).astype(np.int32)
+            check_path(many)
 
 
 def forbid_arcs(cfg, seed):
