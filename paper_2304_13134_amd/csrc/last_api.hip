@@ -674,7 +674,7 @@ last_status_t check_ws(void* ws, size_t have, size_t need)
 
 extern "C" {
 
-int32_t last_version(void) { return 3; }
+int32_t last_version(void) { return 4; }
 
 last_status_t last_set_option(int32_t option, int32_t value)
 {
