@@ -172,8 +172,7 @@ template <int MT, int NF>
 __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __bf16* e_s,
                                                      __bf16* hid_s, floatx4 (&acc)[NF][MT],
                                                      const bf16x8 (&wfrag)[kFuMaxKS], int R, int H, int NTL,
-                                                     const u64* early, u64& early_word
-                                                     )
+                                                     const u64* early, u64& early_word, int p_begin, int p_end)
 {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -184,12 +183,16 @@ __device__ __forceinline__ void fused_weights_phases(const __bf16* f_s, const __
     const int RL = (3 * R) / 8 & ~3;
     const int r_first = wave < 4 ? wave : RL + (wave - 4);
     const int r_end = wave < 4 ? RL : R;
+    // phases p_begin .. p_end of 0 .. NC: phase 0 alone (the hidden tile of the first chunk) leaves the
+    // accumulators alone, so it can run while those of the frames before are still in use
+    if (p_end >= 1) {
 #pragma unroll
-    for (int fr = 0; fr < NF; ++fr)
+        for (int fr = 0; fr < NF; ++fr)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[fr][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int mt = 0; mt < MT; ++mt) acc[fr][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll 1
-    for (int p = 0; p <= NC; ++p) {
+    for (int p = p_begin; p <= p_end; ++p) {
         if (p == 2 && early) early_word = xload(early);
         if (p >= 1) {
 #pragma unroll
@@ -385,6 +388,7 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                     fnext[j] = *(const unsigned*)(fi + (size_t)(tn < L ? tn : L - 1) * H + 2 * tid);
                 }
             }
+            bool pre = false;                                // phase 0 of the next group's weights is done
 #pragma unroll
             for (int j = 0; j < NF; ++j) {
                 const int t = t0 + j;
@@ -444,9 +448,16 @@ __global__ __launch_bounds__(kFuThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 u64 x = 0;
                 if (j == NF - 1) keep(min(t0 + NF - 1, L));
                 if (j == NF - 1 && t0 + NF < L) {
-                    fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x);
-                } else if (pw) {
-                    x = xload(pw);
+                    fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, pw, x, pre ? 1 : 0, H / kFuKC);
+                } else {
+                    // not the last frame of the group: its exchange is waited for in the open; the first
+                    // phase of the next group's weights (tanh only, no accumulator) fills part of the wait
+                    if (NF > 1 && live && j == 0 && t0 + NF < L) {
+                        u64 unused = 0;
+                        fused_weights_phases<MT, NF>(f_s, e_s, hid_s, acc, wfrag, R, H, NTL, nullptr, unused, 0, 0);
+                        pre = true;
+                    }
+                    if (pw) x = xload(pw);
                 }
                 if (!live) continue;
                 // gather: (a,b) receives its label-arc part from workgroup a; headers from everybody
