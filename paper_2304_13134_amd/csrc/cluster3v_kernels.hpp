@@ -53,33 +53,34 @@ constexpr int kV3RedB = kV3Ctl + 32;          // [64] final reduction
 constexpr int kV3Lds = kV3RedB + 64;
 static_assert(kV3RedV % 4 == 0 && kV3RedI % 4 == 0 && kV3PaV % 4 == 0 && kV3PaI % 4 == 0, "16-byte LDS accesses");
 
-// the better of two (score, arc) pairs: higher score, then lower arc; symmetric in its arguments
-__device__ __forceinline__ void v3_comb(float v, int f, float& best, int& bflat)
+// Combining (score, arc) candidates in two sweeps: first the highest score (one max per step), then, among
+// the candidates that have it, the lowest arc (one min per step).  The result is the one of "higher score,
+// then lower arc" applied pair by pair, at a fraction of the instructions.
+//   arc of a candidate for the second sweep: its own if it has the best (finite) score, else none
+__device__ __forceinline__ int v3_keep(float v, int f, float best)
 {
-    const bool up = v > best || (v == best && f < bflat);
-    best = up ? v : best;
-    bflat = up ? f : bflat;
+    return (v == best && v > LAST_NEG_INF) ? f : kVNone;
 }
-// ... with the partner the two lane-swap instructions reach (rows of 16 lanes, halves of the wave)
-__device__ __forceinline__ void v3_swap16(float& v, int& f)
+// maximum / minimum with the partner the two lane-swap instructions reach (rows of 16 lanes, halves of the wave)
+__device__ __forceinline__ float v3_max_swap16(float v)
 {
-    const auto rv = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    const auto rf = __builtin_amdgcn_permlane16_swap((unsigned)f, (unsigned)f, false, false);
-    float b = __uint_as_float(rv[0]);
-    int bf = (int)rf[0];
-    v3_comb(__uint_as_float(rv[1]), (int)rf[1], b, bf);
-    v = b;
-    f = bf;
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-__device__ __forceinline__ void v3_swap32(float& v, int& f)
+__device__ __forceinline__ float v3_max_swap32(float v)
 {
-    const auto rv = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    const auto rf = __builtin_amdgcn_permlane32_swap((unsigned)f, (unsigned)f, false, false);
-    float b = __uint_as_float(rv[0]);
-    int bf = (int)rf[0];
-    v3_comb(__uint_as_float(rv[1]), (int)rf[1], b, bf);
-    v = b;
-    f = bf;
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ int v3_min_swap16(int f)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)f, (unsigned)f, false, false);
+    return min((int)r[0], (int)r[1]);
+}
+__device__ __forceinline__ int v3_min_swap32(int f)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)f, (unsigned)f, false, false);
+    return min((int)r[0], (int)r[1]);
 }
 __device__ __forceinline__ float v3_word_score(unsigned lo) { return __uint_as_float(lo); }
 __device__ __forceinline__ int v3_word_arc(unsigned hi) { return (int)(hi & 0x1FFFFu); }
@@ -115,22 +116,35 @@ __device__ __forceinline__ void v3_gather(buf_t xrs, unsigned slot_off, unsigned
         v3_look(xrs, slot_off, voffq, voffz, lk);
     }
     after_poll();
-    // two producers of the two states of the quad, then the other six through the quad's lanes
-    float vlo = v3_word_score(lk.q[0].x), vhi = v3_word_score(lk.q[0].z);
-    int flo = v3_word_arc(lk.q[0].y), fhi = v3_word_arc(lk.q[0].w);
-    v3_comb(v3_word_score(lk.q[1].x), v3_word_arc(lk.q[1].y), vlo, flo);
-    v3_comb(v3_word_score(lk.q[1].z), v3_word_arc(lk.q[1].w), vhi, fhi);
-    v3_comb(dpp_f<0xB1>(vlo, vlo), dpp_i<0xB1>(flo, flo), vlo, flo);
-    v3_comb(dpp_f<0xB1>(vhi, vhi), dpp_i<0xB1>(fhi, fhi), vhi, fhi);
-    v3_comb(dpp_f<0x4E>(vlo, vlo), dpp_i<0x4E>(flo, flo), vlo, flo);
-    v3_comb(dpp_f<0x4E>(vhi, vhi), dpp_i<0x4E>(fhi, fhi), vhi, fhi);
-    // state 256 (wave 0): lane l < 8 holds producer l's word
-    float vz = tid < 8 ? v3_word_score(lk.z.x) : LAST_NEG_INF;
-    int fz = tid < 8 ? v3_word_arc(lk.z.y) : kVNone;
+    // two producers of the two states of the quad, the other six through the quad's lanes (both swaps are
+    // symmetric: every lane of the quad ends up with the same values)
+    const float a0 = v3_word_score(lk.q[0].x), a1 = v3_word_score(lk.q[1].x);
+    const float b0 = v3_word_score(lk.q[0].z), b1 = v3_word_score(lk.q[1].z);
+    float vlo = fmaxf(a0, a1), vhi = fmaxf(b0, b1);
+    vlo = fmaxf(vlo, dpp_f<0xB1>(vlo, vlo));
+    vhi = fmaxf(vhi, dpp_f<0xB1>(vhi, vhi));
+    vlo = fmaxf(vlo, dpp_f<0x4E>(vlo, vlo));
+    vhi = fmaxf(vhi, dpp_f<0x4E>(vhi, vhi));
+    int flo = min(v3_keep(a0, v3_word_arc(lk.q[0].y), vlo), v3_keep(a1, v3_word_arc(lk.q[1].y), vlo));
+    int fhi = min(v3_keep(b0, v3_word_arc(lk.q[0].w), vhi), v3_keep(b1, v3_word_arc(lk.q[1].w), vhi));
+    flo = min(flo, dpp_i<0xB1>(flo, flo));
+    fhi = min(fhi, dpp_i<0xB1>(fhi, fhi));
+    flo = min(flo, dpp_i<0x4E>(flo, flo));
+    fhi = min(fhi, dpp_i<0x4E>(fhi, fhi));
+    // state 256 (wave 0): lane l < 8 holds producer l's word; lanes 0..3 end up with the result
+    const float wz = tid < 8 ? v3_word_score(lk.z.x) : LAST_NEG_INF;
+    float vz = wz;
+    int fz = kVNone;
     if (tid < 64) {
-        v3_comb(dpp_f<0xB1>(vz, vz), dpp_i<0xB1>(fz, fz), vz, fz);
-        v3_comb(dpp_f<0x4E>(vz, vz), dpp_i<0x4E>(fz, fz), vz, fz);
-        v3_comb(dpp_f<0x104>(LAST_NEG_INF, vz), dpp_i<0x104>(kVNone, fz), vz, fz);     // lanes 0..3 take lanes 4..7
+        vz = fmaxf(vz, dpp_f<0xB1>(vz, vz));
+        vz = fmaxf(vz, dpp_f<0x4E>(vz, vz));
+        vz = fmaxf(vz, dpp_f<0x104>(LAST_NEG_INF, vz));                   // lanes 0..3 take lanes 4..7
+        const float vzall = fmaxf(vz, dpp_f<0x114>(LAST_NEG_INF, vz));    // ... and lanes 4..7 take lanes 0..3
+        fz = tid < 8 ? v3_keep(wz, v3_word_arc(lk.z.y), vzall) : kVNone;
+        fz = min(fz, dpp_i<0xB1>(fz, fz));
+        fz = min(fz, dpp_i<0x4E>(fz, fz));
+        fz = min(fz, dpp_i<0x104>(kVNone, fz));
+        vz = vzall;
     }
     // lanes 0 and 1 of a quad write its two states
     if ((tid & 2) == 0) {
@@ -234,9 +248,16 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 // the eight lanes with these columns: the two of a group of sixteen, then the wave's four groups
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    v3_comb(dpp_f<0x118>(LAST_NEG_INF, best[c]), dpp_i<0x118>(kVNone, arc[c]), best[c], arc[c]);
-                    v3_swap16(best[c], arc[c]);
-                    v3_swap32(best[c], arc[c]);
+                    float m = fmaxf(best[c], dpp_f<0x118>(LAST_NEG_INF, best[c]));      // lanes 8..15 of a row: both halves
+                    m = v3_max_swap16(m);
+                    m = v3_max_swap32(m);
+                    m = fmaxf(m, dpp_f<0x108>(LAST_NEG_INF, m));                        // ... handed to lanes 0..7 too
+                    int f = v3_keep(best[c], arc[c], m);
+                    f = min(f, dpp_i<0x118>(kVNone, f));
+                    f = v3_min_swap16(f);
+                    f = v3_min_swap32(f);
+                    best[c] = m;
+                    arc[c] = f;
                 }
                 if (lane >= 8 && lane < 16) {
 #pragma unroll
@@ -264,13 +285,15 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                     const int4* ri = (const int4*)&redi_s[(4 * wave + lane) * 8];
                     const float4 v0 = rv[0], v1 = rv[1];
                     const int4 i0 = ri[0], i1 = ri[1];
-                    v = v0.x; f = i0.x;
-                    v3_comb(v0.y, i0.y, v, f); v3_comb(v0.z, i0.z, v, f); v3_comb(v0.w, i0.w, v, f);
-                    v3_comb(v1.x, i1.x, v, f); v3_comb(v1.y, i1.y, v, f); v3_comb(v1.z, i1.z, v, f);
-                    v3_comb(v1.w, i1.w, v, f);
-                    v3_comb(sv, sf, v, f);
+                    v = fmaxf(fmaxf(fmaxf(v0.x, v0.y), fmaxf(v0.z, v0.w)), fmaxf(fmaxf(v1.x, v1.y), fmaxf(v1.z, v1.w)));
+                    v = fmaxf(v, fmaxf(sv, mv));
+                    f = min(min(min(v3_keep(v0.x, i0.x, v), v3_keep(v0.y, i0.y, v)), min(v3_keep(v0.z, i0.z, v), v3_keep(v0.w, i0.w, v))),
+                            min(min(v3_keep(v1.x, i1.x, v), v3_keep(v1.y, i1.y, v)), min(v3_keep(v1.z, i1.z, v), v3_keep(v1.w, i1.w, v))));
+                    f = min(f, min(v3_keep(sv, sf, v), v3_keep(mv, mf, v)));
+                } else if (l4) {
+                    v = mv;
+                    f = v3_keep(mv, mf, mv);
                 }
-                if (lane < 4 || l4) v3_comb(mv, mf, v, f);
                 if (!(v > LAST_NEG_INF)) f = kVNone;
                 own = v;
                 if (lane < 8) own_s[8 * wave + lane] = v;
@@ -315,11 +338,15 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 }
                 c2_barrier();
                 if (tid < 256) {
-                    float pv = pav_s[tid];
-                    int pf = pai_s[tid];
+                    float cv[9];
 #pragma unroll
-                    for (int w2 = 1; w2 < 8; ++w2) v3_comb(pav_s[256 * w2 + tid], pai_s[256 * w2 + tid], pv, pf);
-                    if (pubown) v3_comb(blv_s[pubbl], bli_s[pubbl], pv, pf);
+                    for (int w2 = 0; w2 < 8; ++w2) cv[w2] = pav_s[256 * w2 + tid];
+                    cv[8] = pubown ? blv_s[pubbl] : LAST_NEG_INF;
+                    float pv = fmaxf(fmaxf(fmaxf(cv[0], cv[1]), fmaxf(cv[2], cv[3])), fmaxf(fmaxf(cv[4], cv[5]), fmaxf(cv[6], cv[7])));
+                    pv = fmaxf(pv, cv[8]);
+                    int pf = pubown ? v3_keep(cv[8], bli_s[pubbl], pv) : kVNone;
+#pragma unroll
+                    for (int w2 = 0; w2 < 8; ++w2) pf = min(pf, v3_keep(cv[w2], pai_s[256 * w2 + tid], pv));
                     if (!(pv > LAST_NEG_INF)) pf = kVNone;
                     c3_xstore(v2_pack(pv, tag, pf), xrs, voffpub, slot_off);
                     // the start state moves on by its empty-label arc only: workgroup 0 has it
