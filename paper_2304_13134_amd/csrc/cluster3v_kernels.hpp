@@ -238,13 +238,18 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) { best[c] = LAST_NEG_INF; arc[c] = kVNone; }
                 const int y0 = 1 + 32 * k + 4 * g.ci;
+                const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb, foP2 = (unsigned)min(2 * p + 5, nlast) * frb;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {                  // (the row index increases with j)
                     const int q = 1 + 32 * wave + 8 * j + g.rg;
                     const float aq = full_s[q];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v2_scan(__fadd_rn(aq, EF[B_].e[j][c]), q * V1 + y0 + c, best[c], arc[c]);
+                    c3_load_cols_slot(EF[B2_], j, wrs, g, foF2);
+                    c3_load_rows_slot(EP[B2_], j, wrs, g, foP2);
                 }
+                c3_load_cols_slot(EF[B2_], 4, wrs, g, foF2);
+                c3_load_rows_slot(EP[B2_], 4, wrs, g, foP2);
                 // the eight lanes with these columns: the two of a group of sixteen, then the wave's four groups
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
@@ -358,7 +363,7 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 }
                 v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, k,
                           BP ? bpi + (size_t)tP * C : nullptr,
-                          [&]() __attribute__((always_inline)) { issue(std::integral_constant<int, B2_>(), p + 2); });
+                          [] {});
                 gstep += 1;
             }
             ++p;
