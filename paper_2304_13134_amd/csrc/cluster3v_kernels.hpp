@@ -246,10 +246,9 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v2_scan(__fadd_rn(aq, EF[B_].e[j][c]), q * V1 + y0 + c, best[c], arc[c]);
                     c3_load_cols_slot(EF[B2_], j, wrs, g, foF2);
-                    c3_load_rows_slot(EP[B2_], j, wrs, g, foP2);
+                    if (j < 2) c3_load_rows_slot(EP[B2_], j, wrs, g, foP2);
                 }
                 c3_load_cols_slot(EF[B2_], 4, wrs, g, foF2);
-                c3_load_rows_slot(EP[B2_], 4, wrs, g, foP2);
                 // the eight lanes with these columns: the two of a group of sixteen, then the wave's four groups
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
@@ -322,11 +321,13 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v2_scan(__fadd_rn(o0, EP[B_].x[c]), y0 + c, best[c], arc[c]);
                 }
+                const unsigned foP2 = (unsigned)min(2 * p + 5, nlast) * frb;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int q = 1 + 4 * g.u + j;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v2_scan(__fadd_rn(o[j], EP[B_].e[j][c]), q * V1 + y0 + c, best[c], arc[c]);
+                    if (j >= 1) c3_load_rows_slot(EP[B2_], j + 1, wrs, g, foP2);
                 }
                 float4 bv;
                 int4 bi;
