@@ -64,6 +64,14 @@ __device__ __forceinline__ u64 v2_pack(float v, unsigned tag, int flat)
     return (u64)__float_as_uint(v) | ((u64)(((tag & 0x7FFFu) << 17) | ((unsigned)flat & 0x1FFFFu)) << 32);
 }
 
+// Many candidates at once, in two sweeps: the highest score first (one max per candidate), then the lowest
+// arc among the candidates that have it (one min per candidate) -- what v2_acc gives pair by pair, at a
+// third of the instructions and without its chain of dependent selects.
+__device__ __forceinline__ int v2_keep(float v, int flat, float best)
+{
+    return (v == best && v != LAST_NEG_INF) ? flat : kVNone;
+}
+
 // The same inside one thread's scan, whose candidates come in increasing arc order: a tie keeps the
 // earlier, lower arc, and a candidate of -inf never beats the initial -inf.
 __device__ __forceinline__ void v2_scan(float v, int flat, float& best, int& bflat)
@@ -114,7 +122,10 @@ __device__ __forceinline__ int v2_gather(const u64* xs, int K, int C, unsigned t
         float best = LAST_NEG_INF;
 #pragma unroll
         for (int kk = 0; kk < kClMaxK; ++kk)
-            if (FULL || kk < K) v2_acc(__uint_as_float((unsigned)wv[kk]), (int)((wv[kk] >> 32) & 0x1FFFFu), best, bf);
+            if (FULL || kk < K) best = fmaxf(best, __uint_as_float((unsigned)wv[kk]));
+#pragma unroll
+        for (int kk = 0; kk < kClMaxK; ++kk)
+            if (FULL || kk < K) bf = min(bf, v2_keep(__uint_as_float((unsigned)wv[kk]), (int)((wv[kk] >> 32) & 0x1FFFFu), best));
         full_s[tid] = dead ? LAST_NEG_INF : best;
     }
     if (dead) ctl_s[8] = 1;
@@ -264,11 +275,17 @@ __global__ __launch_bounds__(kC2Threads) void cluster2v_kernel(ClusterVArgs a)
                     float best = LAST_NEG_INF;
                     int bf = kVNone;
                     if (fok) {
+                        float rv[kC2RedN];
 #pragma unroll
-                        for (int x2 = 0; x2 < kC2RedN; ++x2)
-                            v2_acc(redv_s[x2 * kC2Own + lane], redi_s[x2 * kC2Own + lane], best, bf);
+                        for (int x2 = 0; x2 < kC2RedN; ++x2) rv[x2] = redv_s[x2 * kC2Own + lane];
                         // the empty label keeps the state
-                        v2_acc(__fadd_rn(full_s[yF], EB[B_]), yF * V1, best, bf);
+                        const float ev = __fadd_rn(full_s[yF], EB[B_]);
+                        best = ev;
+#pragma unroll
+                        for (int x2 = 0; x2 < kC2RedN; ++x2) best = fmaxf(best, rv[x2]);
+                        bf = v2_keep(ev, yF * V1, best);
+#pragma unroll
+                        for (int x2 = 0; x2 < kC2RedN; ++x2) bf = min(bf, v2_keep(rv[x2], redi_s[x2 * kC2Own + lane], best));
                         if (BP) bpi[(size_t)tF * C + r0 + lane] = bf == kVNone ? -1 : bf;
                     }
                     if (lane < kC2Own) own_s[lane] = best;
