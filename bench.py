@@ -38,7 +38,7 @@ BYTES_PER_ARC = 12.0           # forward reads w (4), backward reads w (4) and w
 # are in profiles/cluster3_kernel_B16_T500_V256.md.
 MEASURED_FETCH_BYTES = 4.341e9
 MEASURED_WRITE_BYTES = 2.264e9
-HEADLINE_KERNEL = "cluster3_kernel<true, false> (+ the 3 us tag-clear kernel of the same call)"
+HEADLINE_KERNEL = "cluster3_kernel<true, false, 3> (+ the 3 us tag-clear kernel of the same call)"
 
 
 def time_region(fn, steps, warmup):

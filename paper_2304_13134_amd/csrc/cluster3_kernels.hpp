@@ -415,7 +415,7 @@ __device__ __forceinline__ void c3_put4(const float (&x)[4], buf_t grs, unsigned
 }
 
 // ------------------------------------------------------------------ alpha role
-template <bool GAMMA, bool ACC>
+template <bool GAMMA, bool ACC, int NS>
 __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterGeom& cg, float* smem,
                                             unsigned& gstep, unsigned& ptag)
 {
@@ -462,13 +462,13 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         c3_store_pair(lane == 4 ? 1.f : 0.f, 0, srs, g.voffS, 0u);
         __syncthreads();
 
-        C3Frame EF[2], EP[2];
-        int sF[2] = {0, 0}, sP[2] = {0, 0};
+        C3Frame EF[3], EP[3];
+        int sF[3] = {0, 0, 0}, sP[3] = {0, 0, 0};
         // the other side's vectors for the marginals: values and exponents
-        float bF4[2][4], bP4[2][4], bFm[2] = {0.f, 0.f}, bPm[2] = {0.f, 0.f};
-        int eF4[2] = {0, 0}, eP4[2] = {0, 0}, eFm[2] = {0, 0}, ePm[2] = {0, 0};
+        float bF4[3][4], bP4[3][4], bFm[3] = {0.f, 0.f, 0.f}, bPm[3] = {0.f, 0.f, 0.f};
+        int eF4[3] = {0, 0, 0}, eP4[3] = {0, 0, 0}, eFm[3] = {0, 0, 0}, ePm[3] = {0, 0, 0};
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < 3; ++x)
 #pragma unroll
             for (int c = 0; c < 4; ++c) { bF4[x][c] = 0.f; bP4[x][c] = 0.f; }
         C3D D{0, 0.f};
@@ -505,7 +505,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         auto settle = [&]() __attribute__((always_inline)) {
             int t = 0;
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
+            for (int x = 0; x < 3; ++x) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) t |= c2_touch(bF4[x][c]) | c2_touch(bP4[x][c]);
                 t |= c2_touch(bFm[x]) | c2_touch(bPm[x]) | (eF4[x] == 0x7fffffff) | (eP4[x] == 0x7fffffff)
@@ -545,18 +545,20 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         };
 
         issue(std::integral_constant<int, 0>(), 0);
-        c3_load_cols(EF[1], wrs, g, (unsigned)min(2, nlast) * frb);       // (its P frame: requested in pair 0)
+        if (NS == 3) issue(std::integral_constant<int, 1>(), 1);
+        else c3_load_cols(EF[1], wrs, g, (unsigned)min(2, nlast) * frb);  // (its P frame: requested in pair 0)
         prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
-            constexpr int B_ = decltype(BUF)::value;
+            constexpr int B_ = decltype(BUF)::value, B1_ = (B_ + 1) % NS, B2_ = (B_ + 2) % NS;   // this pair, the next, the one after
+            constexpr int BQ_ = NS == 3 ? B2_ : B1_, dq = NS == 3 ? 2 : 1;                       // the pair whose P frame is requested
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= n) return false;
             auto after_meeting = [&]() __attribute__((always_inline)) {
                 if (GAMMA) {
                     other(std::integral_constant<int, B_>(), p);
-                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    other(std::integral_constant<int, B1_>(), p + 1);
                     c2_wait_loads();
                     settle();
                 }
@@ -591,11 +593,11 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // into it (lanes 8..11, moved to lanes 0..3)
                 float mt = am * EF[B_].m;
                 mt += dpp_f<0x108>(0.f, mt);
-                // the P frame of the next pair is requested here and in the P-step, where the address path has
-                // little else to do (into the registers the pair before this one has finished with)
-                const unsigned foP1 = (unsigned)min(2 * p + 3, nlast) * frb;
-                c3_load_rows_slot(EP[B_ ^ 1], 0, wrs, g, foP1);
-                c3_load_rows_slot(EP[B_ ^ 1], 1, wrs, g, foP1);
+                // the P frame of a later pair is requested here and in the P-step, where the address path has
+                // little else to do (into registers no pair in flight uses)
+                const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
+                c3_load_rows_slot(EP[BQ_], 0, wrs, g, foP2);
+                c3_load_rows_slot(EP[BQ_], 1, wrs, g, foP2);
                 if (GAMMA && tF >= mid) {
                     const unsigned gso = (unsigned)tF * frb;
                     const float fcs = a.scale * c3_mscale(S + sF[B_] + eF4[B_], D, xwide);
@@ -654,9 +656,9 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 if (lane == 0) ctl_s[16 + wave] = tw;
                 if (lane < 8) bl_s[8 * wave + lane] = own * EP[B_].m;      // empty-label arcs of the own states
                 {
-                    const unsigned foP1 = (unsigned)min(2 * p + 3, nlast) * frb;
+                    const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
 #pragma unroll
-                    for (int j = 2; j < 5; ++j) c3_load_rows_slot(EP[B_ ^ 1], j, wrs, g, foP1);
+                    for (int j = 2; j < 5; ++j) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
@@ -702,9 +704,9 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // frames' requests, because a wave's loads return in order
                 C3Look lk;
                 const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb;
-                prep(std::integral_constant<int, B_ ^ 1>(),
+                prep(std::integral_constant<int, B1_>(),
                      [&](int j) __attribute__((always_inline)) {
-                         if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
+                         if (GAMMA && met) other_piece(std::integral_constant<int, B2_>(), p + 2, j);
                      },
                      [&]() __attribute__((always_inline)) {
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
@@ -712,13 +714,13 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                      [](int) {});
                 if (!exch) {
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
+                    for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B2_], j, wrs, g, foF2);
                 }
                 if (exch) {
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
 #pragma unroll
-                                  for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B_], j, wrs, g, foF2);
+                                  for (int j = 0; j < 5; ++j) c3_load_cols_slot(EF[B2_], j, wrs, g, foF2);
                               });
                     gstep += 1;
                     if (tP + 1 <= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)(tP + 1) * kC3SP);
@@ -730,6 +732,9 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
         for (;;) {
             if (!pair(std::integral_constant<int, 0>())) break;
             if (!pair(std::integral_constant<int, 1>())) break;
+            if constexpr (NS == 3) {
+                if (!pair(std::integral_constant<int, 2>())) break;
+            }
         }
         __syncthreads();
         if (!met) meet();
@@ -745,7 +750,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
 }
 
 // ------------------------------------------------------------------- beta role
-template <bool GAMMA, bool ACC>
+template <bool GAMMA, bool ACC, int NS>
 __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGeom& cg, float* smem,
                                            unsigned& gstep, unsigned& ptag)
 {
@@ -796,13 +801,13 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         c3_store_pair(1.f, 0, srs, g.voffS, (unsigned)L * kC3SP);
         __syncthreads();
 
-        C3Frame EF[2], EP[2];
-        int sF[2] = {0, 0}, sP[2] = {0, 0};
+        C3Frame EF[3], EP[3];
+        int sF[3] = {0, 0, 0}, sP[3] = {0, 0, 0};
         // the other side's vectors for the marginals: values and exponents
-        float aFm[2] = {0.f, 0.f}, aPm[2] = {0.f, 0.f}, aP[2][4];
-        int eFm[2] = {0, 0}, ePm[2] = {0, 0}, eP[2][4];
+        float aFm[3] = {0.f, 0.f, 0.f}, aPm[3] = {0.f, 0.f, 0.f}, aP[3][4];
+        int eFm[3] = {0, 0, 0}, ePm[3] = {0, 0, 0}, eP[3][4];
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < 3; ++x)
 #pragma unroll
             for (int j = 0; j < 4; ++j) { aP[x][j] = 0.f; eP[x][j] = 0; }
         C3D D{0, 0.f};
@@ -837,7 +842,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         auto settle = [&]() __attribute__((always_inline)) {
             int t = 0;
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
+            for (int x = 0; x < 3; ++x) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t |= c2_touch(aP[x][j]) | (eP[x][j] == 0x7fffffff);
                 t |= c2_touch(aFm[x]) | c2_touch(aPm[x]) | (eFm[x] == 0x7fffffff) | (ePm[x] == 0x7fffffff);
@@ -870,18 +875,20 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         };
 
         issue(std::integral_constant<int, 0>(), 0);
-        c3_load_rows(EF[1], wrs, g, (unsigned)frameF(1) * frb);          // (its P frame: requested in pair 0)
+        if (NS == 3) issue(std::integral_constant<int, 1>(), 1);
+        else c3_load_rows(EF[1], wrs, g, (unsigned)frameF(1) * frb);      // (its P frame: requested in pair 0)
         prep(std::integral_constant<int, 0>(), [](int) {}, [] {}, [](int) {});
 
         int p = 0;
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
-            constexpr int B_ = decltype(BUF)::value;
+            constexpr int B_ = decltype(BUF)::value, B1_ = (B_ + 1) % NS, B2_ = (B_ + 2) % NS;   // this pair, the next, the one after
+            constexpr int BQ_ = NS == 3 ? B2_ : B1_, dq = NS == 3 ? 2 : 1;                       // the pair whose P frame is requested
             const int iF = 2 * p, iP = 2 * p + 1;
             if (iF >= n) return false;
             auto after_meeting = [&]() __attribute__((always_inline)) {
                 if (GAMMA) {
                     other(std::integral_constant<int, B_>(), p);
-                    other(std::integral_constant<int, B_ ^ 1>(), p + 1);
+                    other(std::integral_constant<int, B1_>(), p + 1);
                     c2_wait_loads();
                     settle();
                 }
@@ -915,12 +922,12 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                 for (int j = 0; j < 4; ++j) rs[j] = wave_sum_dpp(rs[j]);
                 if (g.xR) rs[4] = wave_sum_dpp(rs[4]);
-                // the P frame of the next pair is requested here and in the P-step, where the address path has
-                // little else to do (into the registers the pair before this one has finished with)
+                // the P frame of a later pair is requested here and in the P-step, where the address path has
+                // little else to do (into registers no pair in flight uses)
                 {
-                    const unsigned foP1 = (unsigned)frameP(p + 1) * frb;
-                    c3_load_cols_slot(EP[B_ ^ 1], 0, wrs, g, foP1);
-                    c3_load_cols_slot(EP[B_ ^ 1], 1, wrs, g, foP1);
+                    const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
+                    c3_load_cols_slot(EP[BQ_], 0, wrs, g, foP2);
+                    c3_load_cols_slot(EP[BQ_], 1, wrs, g, foP2);
                 }
                 if (GAMMA && iF >= ph1) {
                     const unsigned gso = (unsigned)tF * frb;
@@ -1002,9 +1009,9 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 if (lane == 8) z_s[wave] = zt;
                 if (lane == 0) { ctl_s[16 + wave] = tw; ctl_s[24 + wave] = tb; }
                 {
-                    const unsigned foP1 = (unsigned)frameP(p + 1) * frb;
+                    const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
 #pragma unroll
-                    for (int j = 2; j < 5; ++j) c3_load_cols_slot(EP[B_ ^ 1], j, wrs, g, foP1);
+                    for (int j = 2; j < 5; ++j) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && iP == L - 1);
@@ -1043,9 +1050,9 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 }
                 C3Look lk;
                 const unsigned foF2 = (unsigned)frameF(p + 2) * frb;
-                prep(std::integral_constant<int, B_ ^ 1>(),
+                prep(std::integral_constant<int, B1_>(),
                      [&](int j) __attribute__((always_inline)) {
-                         if (GAMMA && met) other_piece(std::integral_constant<int, B_>(), p + 2, j);
+                         if (GAMMA && met) other_piece(std::integral_constant<int, B2_>(), p + 2, j);
                      },
                      [&]() __attribute__((always_inline)) {
                          if (exch) c3_look(xrs, slot_off, voffq, voffz, lk);
@@ -1053,13 +1060,13 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                      [](int) {});
                 if (!exch) {
 #pragma unroll
-                    for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
+                    for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B2_], j, wrs, g, foF2);
                 }
                 if (exch) {
                     c3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, lk,
                               [&]() __attribute__((always_inline)) {
 #pragma unroll
-                                  for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B_], j, wrs, g, foF2);
+                                  for (int j = 0; j < 5; ++j) c3_load_rows_slot(EF[B2_], j, wrs, g, foF2);
                               });
                     gstep += 1;
                     if (tP >= mid) c3_store_pair(full_s[g.midx], ctl_s[0], srs, g.voffS, (unsigned)tP * kC3SP);
@@ -1071,6 +1078,9 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
         for (;;) {
             if (!pair(std::integral_constant<int, 0>())) break;
             if (!pair(std::integral_constant<int, 1>())) break;
+            if constexpr (NS == 3) {
+                if (!pair(std::integral_constant<int, 2>())) break;
+            }
         }
         __syncthreads();
         if (!met) meet();
@@ -1086,7 +1096,10 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
 }
 
 // One workgroup per compute unit, two waves per SIMD: at most 256 registers per lane.
-template <bool GAMMA, bool ACC = false>
+// NS: register sets of frames.  2: the P frame of a pair is requested during the pair before it (under 200
+// registers: waves of another kernel fit beside this one); 3: two pairs ahead, like the F frames, so that
+// its exp pass never waits for memory while the marginal stores of the second half crowd it (about 240).
+template <bool GAMMA, bool ACC = false, int NS = 2>
 __global__ __launch_bounds__(kC3Threads) void cluster3_kernel(ClusterArgs a)
 {
     __shared__ __align__(16) float smem[kC3Lds];
@@ -1101,8 +1114,8 @@ __global__ __launch_bounds__(kC3Threads) void cluster3_kernel(ClusterArgs a)
     g.nr = 0;
     unsigned gstep = 0, ptag = 0;
     if (GAMMA && !ACC) cluster_zero_padding(a, g);      // (adding leaves frames beyond the length alone)
-    if (g.role == 0) alpha3_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
-    else beta3_role<GAMMA, ACC>(a, g, smem, gstep, ptag);
+    if (g.role == 0) alpha3_role<GAMMA, ACC, NS>(a, g, smem, gstep, ptag);
+    else beta3_role<GAMMA, ACC, NS>(a, g, smem, gstep, ptag);
 }
 
 }  // namespace last

@@ -56,21 +56,31 @@ static_assert(kV3RedV % 4 == 0 && kV3RedI % 4 == 0 && kV3PaV % 4 == 0 && kV3PaI 
 // Combining (score, arc) candidates in two sweeps: first the highest score (one max per step), then, among
 // the candidates that have it, the lowest arc (one min per step).  The result is the one of "higher score,
 // then lower arc" applied pair by pair, at a fraction of the instructions.
-//   arc of a candidate for the second sweep: its own if it has the best (finite) score, else none
+//   arc of a candidate for the second sweep: its own if it has the best score, else none.  Every candidate
+//   of score -inf carries the arc "none" (a scan never leaves its initial -inf for another -inf, published
+//   words and the odd candidates are made so), which is why equal scores of -inf need no test of their own.
 __device__ __forceinline__ int v3_keep(float v, int f, float best)
 {
-    return (v == best && v > LAST_NEG_INF) ? f : kVNone;
+    return v == best ? f : kVNone;
+}
+// larger of two floats in one instruction (fmaxf costs one more per operand the compiler cannot prove
+// quiet: values out of lane swaps, shifts and memory)
+__device__ __forceinline__ float v3_fmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 // maximum / minimum with the partner the two lane-swap instructions reach (rows of 16 lanes, halves of the wave)
 __device__ __forceinline__ float v3_max_swap16(float v)
 {
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return v3_fmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float v3_max_swap32(float v)
 {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return v3_fmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ int v3_min_swap16(int f)
 {
@@ -81,6 +91,38 @@ __device__ __forceinline__ int v3_min_swap32(int f)
 {
     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)f, (unsigned)f, false, false);
     return min((int)r[0], (int)r[1]);
+}
+// Four values per lane (one per column), to be combined over the wave's four rows of sixteen lanes, lane by
+// lane: two columns share one swap (the odd rows of one against the even rows of the other), so that three
+// swaps and three operations leave column r's result in row r, at the lane's place in the row.
+__device__ __forceinline__ float v3_rows_max4(const float (&x)[4])
+{
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[0]), __float_as_uint(x[1]), false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[2]), __float_as_uint(x[3]), false, false);
+    const float p = v3_fmax(__uint_as_float(a[0]), __uint_as_float(a[1]));      // rows: columns 0 1 0 1, of rows 0+1, 0+1, 2+3, 2+3
+    const float q = v3_fmax(__uint_as_float(b[0]), __uint_as_float(b[1]));      //       columns 2 3 2 3
+    const auto c = __builtin_amdgcn_permlane32_swap(__float_as_uint(p), __float_as_uint(q), false, false);
+    return v3_fmax(__uint_as_float(c[0]), __uint_as_float(c[1]));               // rows: columns 0 1 2 3
+}
+__device__ __forceinline__ int v3_rows_min4(const int (&x)[4])
+{
+    const auto a = __builtin_amdgcn_permlane16_swap((unsigned)x[0], (unsigned)x[1], false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap((unsigned)x[2], (unsigned)x[3], false, false);
+    const int p = min((int)a[0], (int)a[1]);
+    const int q = min((int)b[0], (int)b[1]);
+    const auto c = __builtin_amdgcn_permlane32_swap((unsigned)p, (unsigned)q, false, false);
+    return min((int)c[0], (int)c[1]);
+}
+// ... and back: row r's value to every row, as column r's
+__device__ __forceinline__ void v3_rows_spread4(float r, float (&m)[4])
+{
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(r), __float_as_uint(r), false, false);   // rows 0 1 0 1 | 2 3 2 3
+    const auto lo = __builtin_amdgcn_permlane16_swap(h[0], h[0], false, false);                               // rows 0 0 0 0 | 1 1 1 1
+    const auto hi = __builtin_amdgcn_permlane16_swap(h[1], h[1], false, false);                               // rows 2 2 2 2 | 3 3 3 3
+    m[0] = __uint_as_float(lo[0]);
+    m[1] = __uint_as_float(lo[1]);
+    m[2] = __uint_as_float(hi[0]);
+    m[3] = __uint_as_float(hi[1]);
 }
 __device__ __forceinline__ float v3_word_score(unsigned lo) { return __uint_as_float(lo); }
 __device__ __forceinline__ int v3_word_arc(unsigned hi) { return (int)(hi & 0x1FFFFu); }
@@ -120,11 +162,11 @@ __device__ __forceinline__ void v3_gather(buf_t xrs, unsigned slot_off, unsigned
     // symmetric: every lane of the quad ends up with the same values)
     const float a0 = v3_word_score(lk.q[0].x), a1 = v3_word_score(lk.q[1].x);
     const float b0 = v3_word_score(lk.q[0].z), b1 = v3_word_score(lk.q[1].z);
-    float vlo = fmaxf(a0, a1), vhi = fmaxf(b0, b1);
-    vlo = fmaxf(vlo, dpp_f<0xB1>(vlo, vlo));
-    vhi = fmaxf(vhi, dpp_f<0xB1>(vhi, vhi));
-    vlo = fmaxf(vlo, dpp_f<0x4E>(vlo, vlo));
-    vhi = fmaxf(vhi, dpp_f<0x4E>(vhi, vhi));
+    float vlo = v3_fmax(a0, a1), vhi = v3_fmax(b0, b1);
+    vlo = v3_fmax(vlo, dpp_f<0xB1>(vlo, vlo));
+    vhi = v3_fmax(vhi, dpp_f<0xB1>(vhi, vhi));
+    vlo = v3_fmax(vlo, dpp_f<0x4E>(vlo, vlo));
+    vhi = v3_fmax(vhi, dpp_f<0x4E>(vhi, vhi));
     int flo = min(v3_keep(a0, v3_word_arc(lk.q[0].y), vlo), v3_keep(a1, v3_word_arc(lk.q[1].y), vlo));
     int fhi = min(v3_keep(b0, v3_word_arc(lk.q[0].w), vhi), v3_keep(b1, v3_word_arc(lk.q[1].w), vhi));
     flo = min(flo, dpp_i<0xB1>(flo, flo));
@@ -136,10 +178,10 @@ __device__ __forceinline__ void v3_gather(buf_t xrs, unsigned slot_off, unsigned
     float vz = wz;
     int fz = kVNone;
     if (tid < 64) {
-        vz = fmaxf(vz, dpp_f<0xB1>(vz, vz));
-        vz = fmaxf(vz, dpp_f<0x4E>(vz, vz));
-        vz = fmaxf(vz, dpp_f<0x104>(LAST_NEG_INF, vz));                   // lanes 0..3 take lanes 4..7
-        const float vzall = fmaxf(vz, dpp_f<0x114>(LAST_NEG_INF, vz));    // ... and lanes 4..7 take lanes 0..3
+        vz = v3_fmax(vz, dpp_f<0xB1>(vz, vz));
+        vz = v3_fmax(vz, dpp_f<0x4E>(vz, vz));
+        vz = v3_fmax(vz, dpp_f<0x104>(LAST_NEG_INF, vz));                   // lanes 0..3 take lanes 4..7
+        const float vzall = v3_fmax(vz, dpp_f<0x114>(LAST_NEG_INF, vz));    // ... and lanes 4..7 take lanes 0..3
         fz = tid < 8 ? v3_keep(wz, v3_word_arc(lk.z.y), vzall) : kVNone;
         fz = min(fz, dpp_i<0xB1>(fz, fz));
         fz = min(fz, dpp_i<0x4E>(fz, fz));
@@ -249,35 +291,32 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                     if (j < 2) c3_load_rows_slot(EP[B2_], j, wrs, g, foP2);
                 }
                 c3_load_cols_slot(EF[B2_], 4, wrs, g, foF2);
-                // the eight lanes with these columns: the two of a group of sixteen, then the wave's four groups
+                // the eight lanes with these columns: the two of a group of sixteen (a rotation by eight inside the
+                // row, so both end up with the result), then the wave's four rows for all four columns at once
+                float M[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) M[c] = v3_fmax(best[c], dpp_f<0x128>(best[c], best[c]));
+                const float colmax = v3_rows_max4(M);          // row r: column r
+                v3_rows_spread4(colmax, M);                    // every lane: all four columns
+                int fk[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    float m = fmaxf(best[c], dpp_f<0x118>(LAST_NEG_INF, best[c]));      // lanes 8..15 of a row: both halves
-                    m = v3_max_swap16(m);
-                    m = v3_max_swap32(m);
-                    m = fmaxf(m, dpp_f<0x108>(LAST_NEG_INF, m));                        // ... handed to lanes 0..7 too
-                    int f = v3_keep(best[c], arc[c], m);
-                    f = min(f, dpp_i<0x118>(kVNone, f));
-                    f = v3_min_swap16(f);
-                    f = v3_min_swap32(f);
-                    best[c] = m;
-                    arc[c] = f;
+                    fk[c] = v3_keep(best[c], arc[c], M[c]);
+                    fk[c] = min(fk[c], dpp_i<0x128>(fk[c], fk[c]));
                 }
-                if (lane >= 8 && lane < 16) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        redv_s[(4 * g.ci + c) * 8 + wave] = best[c];
-                        redi_s[(4 * g.ci + c) * 8 + wave] = arc[c];
-                    }
+                const int colarc = v3_rows_min4(fk);           // row r: column r
+                if ((lane & 8) == 0) {
+                    const int col = 4 * g.ci + (lane >> 4);
+                    redv_s[col * 8 + wave] = colmax;
+                    redi_s[col * 8 + wave] = colarc;
                 }
                 // odd elements: the empty-label arc of an own state (lanes 0..3; lane 4: the start state's) and
                 // the start state's label arc into it (lanes 8..11, moved to lanes 0..3)
                 const bool lo = lane < 4, l4 = lane == 4 && g.xR, l8 = lane >= 8 && lane < 12;
                 const int ys = lo ? 1 + 4 * g.u + lane : (l8 ? 1 + 4 * g.u + lane - 8 : 0);     // the state the arc leads to
                 const int qs = lo ? ys : 0;                                                    // ... and leaves
-                float mv = g.mvC ? __fadd_rn(full_s[qs], EF[B_].m) : LAST_NEG_INF;
-                int mf = g.mvC ? qs * V1 + (l8 ? ys : 0) : kVNone;
-                if (!(lo || l4 || l8)) { mv = LAST_NEG_INF; mf = kVNone; }
+                const float mv = (g.mvC && (lo || l4 || l8)) ? __fadd_rn(full_s[qs], EF[B_].m) : LAST_NEG_INF;
+                const int mf = mv > LAST_NEG_INF ? qs * V1 + (l8 ? ys : 0) : kVNone;
                 const float sv = dpp_f<0x108>(LAST_NEG_INF, mv);      // lanes 0..7 take lanes 8..15
                 const int sf = dpp_i<0x108>(kVNone, mf);
                 c2_barrier();
@@ -289,8 +328,7 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                     const int4* ri = (const int4*)&redi_s[(4 * wave + lane) * 8];
                     const float4 v0 = rv[0], v1 = rv[1];
                     const int4 i0 = ri[0], i1 = ri[1];
-                    v = fmaxf(fmaxf(fmaxf(v0.x, v0.y), fmaxf(v0.z, v0.w)), fmaxf(fmaxf(v1.x, v1.y), fmaxf(v1.z, v1.w)));
-                    v = fmaxf(v, fmaxf(sv, mv));
+                    v = c3_max3(c3_max3(v0.x, v0.y, v0.z), c3_max3(v0.w, v1.x, v1.y), c3_max3(v1.z, v1.w, v3_fmax(sv, mv)));
                     f = min(min(min(v3_keep(v0.x, i0.x, v), v3_keep(v0.y, i0.y, v)), min(v3_keep(v0.z, i0.z, v), v3_keep(v0.w, i0.w, v))),
                             min(min(v3_keep(v1.x, i1.x, v), v3_keep(v1.y, i1.y, v)), min(v3_keep(v1.z, i1.z, v), v3_keep(v1.w, i1.w, v))));
                     f = min(f, min(v3_keep(sv, sf, v), v3_keep(mv, mf, v)));
@@ -298,7 +336,6 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                     v = mv;
                     f = v3_keep(mv, mf, mv);
                 }
-                if (!(v > LAST_NEG_INF)) f = kVNone;
                 own = v;
                 if (lane < 8) own_s[8 * wave + lane] = v;
                 if (BP && (lane < 4 || l4)) bpi[(size_t)tF * C + (lane < 4 ? 1 + 4 * g.u + lane : 0)] = f == kVNone ? -1 : f;
@@ -348,12 +385,10 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
 #pragma unroll
                     for (int w2 = 0; w2 < 8; ++w2) cv[w2] = pav_s[256 * w2 + tid];
                     cv[8] = pubown ? blv_s[pubbl] : LAST_NEG_INF;
-                    float pv = fmaxf(fmaxf(fmaxf(cv[0], cv[1]), fmaxf(cv[2], cv[3])), fmaxf(fmaxf(cv[4], cv[5]), fmaxf(cv[6], cv[7])));
-                    pv = fmaxf(pv, cv[8]);
+                    const float pv = c3_max3(c3_max3(cv[0], cv[1], cv[2]), c3_max3(cv[3], cv[4], cv[5]), c3_max3(cv[6], cv[7], cv[8]));
                     int pf = pubown ? v3_keep(cv[8], bli_s[pubbl], pv) : kVNone;
 #pragma unroll
                     for (int w2 = 0; w2 < 8; ++w2) pf = min(pf, v3_keep(cv[w2], pai_s[256 * w2 + tid], pv));
-                    if (!(pv > LAST_NEG_INF)) pf = kVNone;
                     c3_xstore(v2_pack(pv, tag, pf), xrs, voffpub, slot_off);
                     // the start state moves on by its empty-label arc only: workgroup 0 has it
                     if (tid == 0) {

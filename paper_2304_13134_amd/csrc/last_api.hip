@@ -295,6 +295,10 @@ ClusterWs carve_cluster(Carver& cv, const Shape& s, const ClusterPlan& p)
     return c;
 }
 
+// Set while last_globally_normalized_loss enqueues its denominator: the numerator's kernels run beside it
+// on another stream, and only the leaner instantiation of cluster3_kernel leaves them registers to do so.
+thread_local bool g_numerator_beside = false;
+
 template <bool GAMMA>
 void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, const float* w,
                     const int* lengths, float* dist, int* item_status, float* dw, float scale,
@@ -311,9 +315,11 @@ void launch_cluster(const Shape& s, const ClusterPlan& p, const ClusterWs& c, co
     a.spin_limit = opt(LAST_OPT_SPIN_LIMIT);
     if (p.gen == 3) {
         if (GAMMA && accumulate)
-            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, GAMMA>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, GAMMA, 2>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+        else if (GAMMA && !g_numerator_beside)
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, false, GAMMA ? 3 : 2>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
         else
-            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, false>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
+            hipLaunchKernelGGL(HIP_KERNEL_NAME(cluster3_kernel<GAMMA, false, 2>), dim3(p.grid), dim3(kC3Threads), 0, st, a);
         return;
     }
     if (p.gen == 2) {
@@ -1229,8 +1235,10 @@ last_status_t last_globally_normalized_loss(const last_weights_t* weights, const
                         ws_num, need_num, sd->stream, false, kNumPrepare);
     // the fork is always joined, also after an error, so that the caller's stream never loses the side work
     e = hipEventRecord(sd->join, sd->stream);
+    g_numerator_beside = true;
     const last_status_t rc_den = last_arc_posteriors(weights, lengths, context, dist, out, item_status, ws,
                                                      need_den, hip_stream);
+    g_numerator_beside = false;
     if (e == hipSuccess) e = hipStreamWaitEvent(st, sd->join, 0);
     if (e != hipSuccess) { g_last_hip_error = e; return LAST_ERR_HIP; }
     if (rc != LAST_OK) return rc;
