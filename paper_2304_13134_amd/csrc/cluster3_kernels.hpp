@@ -32,9 +32,11 @@
 //     through two DPP swaps.  The start state's eight words sit on eight lanes and are added up by a DPP
 //     scan.  The order of every addition is fixed, so the gathered vector is bit-identical in all workgroups.
 //   * Memory requests are spread over the pair instead of being issued in one burst (a wave whose request
-//     finds the address path busy stands still): the frames of the pair after the next are requested piece
-//     by piece between the pieces of the exp pass and inside the gather, the look at the exchange before
-//     them, because a wave's loads return in order.  Marginals leave as 16-byte stores.
+//     finds the address path busy stands still): the F frame of the pair after the next is requested inside
+//     the gather, the P frame of a later pair (the next with two register sets, the one after it with three)
+//     piece by piece in the F- and the P-step, the other side's state vectors between the pieces of the exp
+//     pass; the look at the exchange comes before the requests that follow it, because a wave's loads
+//     return in order.  Marginals leave as 16-byte stores.
 //
 // Per pair and workgroup (alpha; beta mirrors it): F-step sums -> barrier -> own states -> P-step sums ->
 // barrier -> publish -> marginals of the pair (second half of the item) -> exp pass of the NEXT pair ->
