@@ -570,11 +570,28 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
-            {
-                float aq[4];
+            float aq[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) aq[j] = full_s[32 * wave + 8 * j + g.rg];
-                const float am = full_s[g.midx];
+            for (int j = 0; j < 4; ++j) aq[j] = full_s[32 * wave + 8 * j + g.rg];
+            const float am = full_s[g.midx];
+            // marginals of the F frame (second half of the item); they leave after the publish of the pair, or
+            // at its end if the P frame is beyond the item
+            auto marginalsF = [&]() __attribute__((always_inline)) {
+                if (GAMMA && tF >= mid) {
+                    const unsigned gso = (unsigned)tF * frb;
+                    const float fcs = a.scale * c3_mscale(S + sF[B_] + eF4[B_], D, xwide);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float x[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) x[c] = aq[j] * EF[B_].e[j][c] * (bF4[B_][c] * fcs);
+                        c3_put4<ACC>(x, grs, g.voffC, gso + g.rowC0 + (unsigned)(8 * j) * pitch);
+                    }
+                    const float fm = a.scale * bFm[B_] * c3_mscale(S + sF[B_] + eFm[B_], D, xwide);
+                    c2_put<ACC>(am * EF[B_].m * fm, grs, g.voffMc, gso);
+                }
+            };
+            {
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -600,19 +617,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
                 c3_load_rows_slot(EP[BQ_], 0, wrs, g, foP2);
                 c3_load_rows_slot(EP[BQ_], 1, wrs, g, foP2);
-                if (GAMMA && tF >= mid) {
-                    const unsigned gso = (unsigned)tF * frb;
-                    const float fcs = a.scale * c3_mscale(S + sF[B_] + eF4[B_], D, xwide);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float x[4];
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) x[c] = aq[j] * EF[B_].e[j][c] * (bF4[B_][c] * fcs);
-                        c3_put4<ACC>(x, grs, g.voffC, gso + g.rowC0 + (unsigned)(8 * j) * pitch);
-                    }
-                    const float fm = a.scale * bFm[B_] * c3_mscale(S + sF[B_] + eFm[B_], D, xwide);
-                    c2_put<ACC>(am * EF[B_].m * fm, grs, g.voffMc, gso);
-                }
                 c2_barrier();
                 // own states: lane j < 4 adds up the eight waves' sums of column 4 wave + j
                 const int4 sh0 = *(const int4*)&ctl_s[8], sh1 = *(const int4*)&ctl_s[12];
@@ -631,7 +635,7 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 ek = ms == kShiftNone ? S : S + smax + ms;
                 if (tF + 1 <= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)(tF + 1) * kC3SP);
             }
-            if (tP >= n) return false;
+            if (tP >= n) { marginalsF(); return false; }
             // ---------------- P-step: frame tP, own rows x all columns, partial sums for every state
             if (tP == mid && !met) { meet(); after_meeting(); }
             {
@@ -679,7 +683,9 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                         c3_xstore(c2_pack(k == 0 ? __builtin_ldexpf(bl_s[4], tw0.x - tmax) : 0.f, tag, rel), xrs,
                                   (unsigned)(k * kC3XS + 256) * 8u, slot_off);
                 }
-                if (GAMMA && tP >= mid) {
+                C3Look lk;
+                auto marginalsP = [&]() __attribute__((always_inline)) {
+                  if (GAMMA && tP >= mid) {
                     const unsigned gso = (unsigned)tP * frb;
                     const float fys = a.scale * c3_mscale(tw + eP4[B_], D, xwide);
                     float fy[4];
@@ -700,11 +706,15 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                     }
                     const float fm = a.scale * bPm[B_] * c3_mscale(tw + ePm[B_], D, xwide);
                     c2_put<ACC>(own * EP[B_].m * fm, grs, g.voffMr, gso);
-                }
+                  }
+                };
+                // (the stores of both frames right behind the publish: the stretch from the gather to the publish,
+                // on which every other workgroup of the group waits, then has no store of this one in its way)
+                marginalsF();
+                marginalsP();
                 // exp pass of the next pair, with the requests for the pair after the next (into the registers
                 // this pair has finished with) between its pieces; the look at the exchange comes before the
                 // frames' requests, because a wave's loads return in order
-                C3Look lk;
                 const unsigned foF2 = (unsigned)min(2 * p + 4, nlast) * frb;
                 prep(std::integral_constant<int, B1_>(),
                      [&](int j) __attribute__((always_inline)) {
@@ -900,11 +910,36 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
+            const int tF = L - 1 - iF;
+            const float4 bq4 = *(const float4*)&full_s[4 * lane];
+            const float bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
+            const float bm = full_s[g.midx];
+            // marginals of the F frame (second half of the item); they leave after the publish of the pair, or
+            // at its end if the P frame is beyond the item
+            auto marginalsF = [&]() __attribute__((always_inline)) {
+                if (GAMMA && iF >= ph1) {
+                    const unsigned gso = (unsigned)tF * frb;
+                    const float frs = a.scale * c3_mscale(__builtin_amdgcn_readlane(eFm[B_], 0) + S + sF[B_], D, xwide);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), j)) * frs;
+                        float x[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) x[c] = EF[B_].e[j][c] * bq[c] * fr_;
+                        c3_put4<ACC>(x, grs, g.voffR, gso + g.rowR0 + (unsigned)j * pitch);
+                    }
+                    if (g.xR) {
+                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), 4)) * frs;
+                        float x[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) x[c] = EF[B_].x[c] * bq[c] * fr_;
+                        c3_put4<ACC>(x, grs, g.voffR, gso);
+                    }
+                    const float fm = a.scale * aFm[B_] * c3_mscale(eFm[B_] + S + sF[B_], D, xwide);
+                    c2_put<ACC>(bm * EF[B_].m * fm, grs, g.voffMr, gso);
+                }
+            };
             {
-                const int tF = L - 1 - iF;
-                const float4 bq4 = *(const float4*)&full_s[4 * lane];
-                const float bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
-                const float bm = full_s[g.midx];
                 float rs[5];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -931,27 +966,6 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                     c3_load_cols_slot(EP[BQ_], 0, wrs, g, foP2);
                     c3_load_cols_slot(EP[BQ_], 1, wrs, g, foP2);
                 }
-                if (GAMMA && iF >= ph1) {
-                    const unsigned gso = (unsigned)tF * frb;
-                    const float frs = a.scale * c3_mscale(__builtin_amdgcn_readlane(eFm[B_], 0) + S + sF[B_], D, xwide);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), j)) * frs;
-                        float x[4];
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) x[c] = EF[B_].e[j][c] * bq[c] * fr_;
-                        c3_put4<ACC>(x, grs, g.voffR, gso + g.rowR0 + (unsigned)j * pitch);
-                    }
-                    if (g.xR) {
-                        const float fr_ = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(aFm[B_]), 4)) * frs;
-                        float x[4];
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) x[c] = EF[B_].x[c] * bq[c] * fr_;
-                        c3_put4<ACC>(x, grs, g.voffR, gso);
-                    }
-                    const float fm = a.scale * aFm[B_] * c3_mscale(eFm[B_] + S + sF[B_], D, xwide);
-                    c2_put<ACC>(bm * EF[B_].m * fm, grs, g.voffMr, gso);
-                }
                 // own states: row sum plus the empty-label arc, lane j <-> own state j (lane 4: the start state)
                 float v = lane == 0 ? rs[0] : lane == 1 ? rs[1] : lane == 2 ? rs[2] : lane == 3 ? rs[3] : rs[4];
                 v = fmaf(bm, EF[B_].m, v);
@@ -965,7 +979,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 if (tF >= mid) c3_store_pair(own, ek, srs, g.voffS, (unsigned)tF * kC3SP);
                 c2_barrier();
             }
-            if (iP >= n) return false;
+            if (iP >= n) { marginalsF(); return false; }
             // ---------------- P-step: frame tP, all rows x own columns, partial sums for every state
             if (iP == ph1 && !met) { meet(); after_meeting(); }
             {
@@ -1036,7 +1050,9 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                         c3_xstore(c2_pack(v0, tag, rel), xrs, (unsigned)(k * kC3XS + 256) * 8u, slot_off);
                     }
                 }
-                if (GAMMA && iP >= ph1) {
+                C3Look lk;
+                auto marginalsP = [&]() __attribute__((always_inline)) {
+                  if (GAMMA && iP >= ph1) {
                     // marginals: gamma[q][y] = a_t[q] M[q][y] b_{t+1}[y] / Z, b_{t+1} = the own states of the F-step
                     const unsigned gso = (unsigned)tP * frb;
 #pragma unroll
@@ -1049,8 +1065,12 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                     }
                     const float fm = a.scale * aPm[B_] * c3_mscale(ePm[B_] + tb, D, xwide);
                     c2_put<ACC>(mo * fm, grs, g.voffMc, gso);
-                }
-                C3Look lk;
+                  }
+                };
+                // (the stores of both frames right behind the publish: the stretch from the gather to the publish,
+                // on which every other workgroup of the group waits, then has no store of this one in its way)
+                marginalsF();
+                marginalsP();
                 const unsigned foF2 = (unsigned)frameF(p + 2) * frb;
                 prep(std::integral_constant<int, B1_>(),
                      [&](int j) __attribute__((always_inline)) {
