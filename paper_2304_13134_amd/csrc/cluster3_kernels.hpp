@@ -75,6 +75,7 @@ static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl 
 // the cache lines at the ends of their row pieces), with the hint on the row-contiguous frames only it
 // ran at the same speed; a plain read sweep is what gains from the hint.
 constexpr int kC3WeightPolicy = 0;
+constexpr bool kC3AllInF = true;
 __device__ __forceinline__ float4 c3_wload4(buf_t r, unsigned voff, unsigned soff)
 {
     return __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, kC3WeightPolicy));
@@ -570,6 +571,11 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
+            if (kC3AllInF) {
+                const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
+#pragma unroll
+                for (int j = 0; j < 5; ++j) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
+            }
             float aq[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) aq[j] = full_s[32 * wave + 8 * j + g.rg];
@@ -615,8 +621,10 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // the P frame of a later pair is requested here and in the P-step, where the address path has
                 // little else to do (into registers no pair in flight uses)
                 const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
-                c3_load_rows_slot(EP[BQ_], 0, wrs, g, foP2);
-                c3_load_rows_slot(EP[BQ_], 1, wrs, g, foP2);
+                if (!(kC3AllInF)) {
+                    c3_load_rows_slot(EP[BQ_], 0, wrs, g, foP2);
+                    c3_load_rows_slot(EP[BQ_], 1, wrs, g, foP2);
+                }
                 c2_barrier();
                 // own states: lane j < 4 adds up the eight waves' sums of column 4 wave + j
                 const int4 sh0 = *(const int4*)&ctl_s[8], sh1 = *(const int4*)&ctl_s[12];
@@ -664,7 +672,8 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 {
                     const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
 #pragma unroll
-                    for (int j = 2; j < 5; ++j) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
+                    for (int j = 2; j < 5; ++j)
+                        if (!(kC3AllInF)) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
@@ -911,6 +920,11 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
             const int tF = L - 1 - iF;
+            if (kC3AllInF) {
+                const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
+#pragma unroll
+                for (int j = 0; j < 5; ++j) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
+            }
             const float4 bq4 = *(const float4*)&full_s[4 * lane];
             const float bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
             const float bm = full_s[g.midx];
@@ -963,8 +977,10 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 // little else to do (into registers no pair in flight uses)
                 {
                     const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
-                    c3_load_cols_slot(EP[BQ_], 0, wrs, g, foP2);
-                    c3_load_cols_slot(EP[BQ_], 1, wrs, g, foP2);
+                    if (!(kC3AllInF)) {
+                        c3_load_cols_slot(EP[BQ_], 0, wrs, g, foP2);
+                        c3_load_cols_slot(EP[BQ_], 1, wrs, g, foP2);
+                    }
                 }
                 // own states: row sum plus the empty-label arc, lane j <-> own state j (lane 4: the start state)
                 float v = lane == 0 ? rs[0] : lane == 1 ? rs[1] : lane == 2 ? rs[2] : lane == 3 ? rs[3] : rs[4];
@@ -1027,7 +1043,8 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 {
                     const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
 #pragma unroll
-                    for (int j = 2; j < 5; ++j) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
+                    for (int j = 2; j < 5; ++j)
+                        if (!(kC3AllInF)) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
                 }
                 c2_barrier();
                 const bool exch = !(GAMMA && iP == L - 1);
