@@ -34,9 +34,9 @@
 //   * Memory requests are spread over the pair instead of being issued in one burst (a wave whose request
 //     finds the address path busy stands still): the F frame of the pair after the next is requested inside
 //     the gather, the P frame of a later pair (the next with two register sets, the one after it with three)
-//     piece by piece in the F- and the P-step, the other side's state vectors between the pieces of the exp
-//     pass; the look at the exchange comes before the requests that follow it, because a wave's loads
-//     return in order.  Marginals leave as 16-byte stores.
+//     at the top of the F-step, the other side's state vectors between the pieces of the exp pass; a wave's
+//     loads return in order, so nothing slow may be in flight in front of a look at the exchange.  Marginals
+//     leave as 16-byte stores, those of both frames of a pair right behind its publish.
 //
 // Per pair and workgroup (alpha; beta mirrors it): F-step sums -> barrier -> own states -> P-step sums ->
 // barrier -> publish -> marginals of the pair (second half of the item) -> exp pass of the NEXT pair ->
@@ -75,7 +75,6 @@ static_assert(kC3Red % 4 == 0 && kC3Pacc % 4 == 0 && kC3OwnS % 4 == 0 && kC3Ctl 
 // the cache lines at the ends of their row pieces), with the hint on the row-contiguous frames only it
 // ran at the same speed; a plain read sweep is what gains from the hint.
 constexpr int kC3WeightPolicy = 0;
-constexpr bool kC3AllInF = true;
 __device__ __forceinline__ float4 c3_wload4(buf_t r, unsigned voff, unsigned soff)
 {
     return __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, kC3WeightPolicy));
@@ -571,7 +570,10 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
             const int S = ctl_s[0];
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
-            if (kC3AllInF) {
+            // the P frame of a later pair is requested first of all (into registers no pair in flight uses): a
+            // wave's loads return in order, and what is still in flight when the look at the exchange is issued
+            // holds up its answer
+            {
                 const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
 #pragma unroll
                 for (int j = 0; j < 5; ++j) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
@@ -618,13 +620,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 // into it (lanes 8..11, moved to lanes 0..3)
                 float mt = am * EF[B_].m;
                 mt += dpp_f<0x108>(0.f, mt);
-                // the P frame of a later pair is requested here and in the P-step, where the address path has
-                // little else to do (into registers no pair in flight uses)
-                const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
-                if (!(kC3AllInF)) {
-                    c3_load_rows_slot(EP[BQ_], 0, wrs, g, foP2);
-                    c3_load_rows_slot(EP[BQ_], 1, wrs, g, foP2);
-                }
                 c2_barrier();
                 // own states: lane j < 4 adds up the eight waves' sums of column 4 wave + j
                 const int4 sh0 = *(const int4*)&ctl_s[8], sh1 = *(const int4*)&ctl_s[12];
@@ -669,12 +664,6 @@ __device__ __forceinline__ void alpha3_role(const ClusterArgs& a, const ClusterG
                 const int tw = ek + sP[B_];                 // exponent of this wave's sums
                 if (lane == 0) ctl_s[16 + wave] = tw;
                 if (lane < 8) bl_s[8 * wave + lane] = own * EP[B_].m;      // empty-label arcs of the own states
-                {
-                    const unsigned foP2 = (unsigned)min(2 * (p + dq) + 1, nlast) * frb;
-#pragma unroll
-                    for (int j = 2; j < 5; ++j)
-                        if (!(kC3AllInF)) c3_load_rows_slot(EP[BQ_], j, wrs, g, foP2);
-                }
                 c2_barrier();
                 const bool exch = !(GAMMA && tP == L - 1);
                 if (exch && tid < 256) {
@@ -920,7 +909,7 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
             float own;        // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0); zero elsewhere
             int ek;           // their exponent
             const int tF = L - 1 - iF;
-            if (kC3AllInF) {
+            {                 // (the P frame of a later pair: see the alpha role)
                 const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
 #pragma unroll
                 for (int j = 0; j < 5; ++j) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
@@ -973,15 +962,6 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
 #pragma unroll
                 for (int j = 0; j < 4; ++j) rs[j] = wave_sum_dpp(rs[j]);
                 if (g.xR) rs[4] = wave_sum_dpp(rs[4]);
-                // the P frame of a later pair is requested here and in the P-step, where the address path has
-                // little else to do (into registers no pair in flight uses)
-                {
-                    const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
-                    if (!(kC3AllInF)) {
-                        c3_load_cols_slot(EP[BQ_], 0, wrs, g, foP2);
-                        c3_load_cols_slot(EP[BQ_], 1, wrs, g, foP2);
-                    }
-                }
                 // own states: row sum plus the empty-label arc, lane j <-> own state j (lane 4: the start state)
                 float v = lane == 0 ? rs[0] : lane == 1 ? rs[1] : lane == 2 ? rs[2] : lane == 3 ? rs[3] : rs[4];
                 v = fmaf(bm, EF[B_].m, v);
@@ -1040,12 +1020,6 @@ __device__ __forceinline__ void beta3_role(const ClusterArgs& a, const ClusterGe
                 if (lane < 8) bl_s[8 * wave + lane] = mo;
                 if (lane == 8) z_s[wave] = zt;
                 if (lane == 0) { ctl_s[16 + wave] = tw; ctl_s[24 + wave] = tb; }
-                {
-                    const unsigned foP2 = (unsigned)frameP(p + dq) * frb;
-#pragma unroll
-                    for (int j = 2; j < 5; ++j)
-                        if (!(kC3AllInF)) c3_load_cols_slot(EP[BQ_], j, wrs, g, foP2);
-                }
                 c2_barrier();
                 const bool exch = !(GAMMA && iP == L - 1);
                 if (exch && tid < 256) {
