@@ -137,11 +137,13 @@ __device__ __forceinline__ void v3_look(buf_t xrs, unsigned slot_off, unsigned v
 }
 
 // Gathering one exchange slot: the best of the eight published candidates of every state into full_s;
-// the backpointers of the states this workgroup owns into bprow (null: none wanted).  Every thread calls;
-// ends with a workgroup barrier.  `after_poll` runs once all words are there.
+// the backpointer of the thread's state (lanes 0 and 1 of a quad: state 2 (tid / 4) + (tid & 1)) comes back
+// in bp_q, that of state 256 (thread 0) in bp_z, -1 if there is none: the caller stores those of the states
+// its workgroup owns, later, where a store is in nobody's way.  Every thread calls; ends with a workgroup
+// barrier.  `after_poll` runs once all words are there.
 template <typename AfterPoll>
 __device__ __forceinline__ void v3_gather(buf_t xrs, unsigned slot_off, unsigned voffq, unsigned voffz, unsigned tag,
-                                          float* full_s, int* ctl_s, int limit, int& dead, int k, int* bprow,
+                                          float* full_s, int* ctl_s, int limit, int& dead, int& bp_q, int& bp_z,
                                           AfterPoll&& after_poll)
 {
     const int tid = threadIdx.x;
@@ -194,12 +196,11 @@ __device__ __forceinline__ void v3_gather(buf_t xrs, unsigned slot_off, unsigned
         const float v = (tid & 1) ? vhi : vlo;
         const int f = (tid & 1) ? fhi : flo;
         full_s[s] = dead ? LAST_NEG_INF : v;
-        const bool mine = s == 0 ? k == 0 : ((s - 1) >> 5) == k;
-        if (bprow && mine) bprow[s] = (f == kVNone || dead) ? -1 : f;
+        bp_q = (f == kVNone || dead) ? -1 : f;
     }
     if (tid == 0) {
         full_s[256] = dead ? LAST_NEG_INF : vz;
-        if (bprow && k == kV3K - 1) bprow[256] = (fz == kVNone || dead) ? -1 : fz;
+        bp_z = (fz == kVNone || dead) ? -1 : fz;
     }
     if (dead) ctl_s[8] = 1;
     c2_barrier();
@@ -268,11 +269,23 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
 
         int p = 0;
         float own = LAST_NEG_INF;      // lanes 0..3: the wave's own states, lane 4: the start state (sub-owner 0)
+        // backpointers out of the last gather, stored behind the next publish (or when the item ends)
+        const int gs = 2 * (tid >> 2) + (tid & 1);
+        const bool gmine = (tid & 2) == 0 && (gs == 0 ? k == 0 : ((gs - 1) >> 5) == k);
+        int pend_q = -1, pend_z = -1, pend_t = -1;
+        auto store_pending = [&]() __attribute__((always_inline)) {
+            if (BP && pend_t >= 0) {
+                if (gmine) bpi[(size_t)pend_t * C + gs] = pend_q;
+                if (tid == 0 && k == kV3K - 1) bpi[(size_t)pend_t * C + 256] = pend_z;
+            }
+            pend_t = -1;
+        };
         auto pair = [&](auto BUF) __attribute__((always_inline)) -> bool {
             constexpr int B_ = decltype(BUF)::value;
             constexpr int B2_ = (B_ + 2) % 3;
             const int tF = 2 * p, tP = 2 * p + 1;
             if (tF >= L) return false;
+            int fbp = kVNone;           // backpointer of the own state (lanes 0..3, lane 4: the start state's): stored behind the publish
             // ---------------- F-step: frame tF, all rows x own columns, from the whole vector
             {
                 float best[4];
@@ -338,9 +351,12 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 }
                 own = v;
                 if (lane < 8) own_s[8 * wave + lane] = v;
-                if (BP && (lane < 4 || l4)) bpi[(size_t)tF * C + (lane < 4 ? 1 + 4 * g.u + lane : 0)] = f == kVNone ? -1 : f;
+                fbp = f;
             }
-            if (tP >= L) return false;
+            auto store_fbp = [&]() __attribute__((always_inline)) {
+                if (BP && (lane < 4 || (lane == 4 && g.xR))) bpi[(size_t)tF * C + (lane < 4 ? 1 + 4 * g.u + lane : 0)] = fbp == kVNone ? -1 : fbp;
+            };
+            if (tP >= L) { store_fbp(); store_pending(); return false; }
             // ---------------- P-step: frame tP, own rows x all columns, best candidate for every label state
             {
                 const unsigned tag = gstep + 1;
@@ -397,9 +413,10 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                                   (unsigned)(k * kV3XS) * 8u, slot_off);
                     }
                 }
-                v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, k,
-                          BP ? bpi + (size_t)tP * C : nullptr,
-                          [] {});
+                store_fbp();
+                store_pending();
+                v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, pend_q, pend_z, [] {});
+                pend_t = tP;
                 gstep += 1;
             }
             ++p;
@@ -410,6 +427,7 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
             if (!pair(std::integral_constant<int, 1>())) break;
             if (!pair(std::integral_constant<int, 2>())) break;
         }
+        store_pending();
         __syncthreads();
         if (L & 1) {
             // the last frame was an F-step: the own scores of every workgroup make up the final vector
@@ -419,7 +437,8 @@ __global__ __launch_bounds__(kC3Threads) void cluster3v_kernel(ClusterVArgs a)
                 c3_xstore(v2_pack(pubown ? own_s[pubbl] : LAST_NEG_INF, tag, kVNone), xrs, voffpub, slot_off);
                 if (tid == 0) c3_xstore(v2_pack(k == 0 ? own_s[4] : LAST_NEG_INF, tag, kVNone), xrs, (unsigned)(k * kV3XS) * 8u, slot_off);
             }
-            v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, k, (int*)nullptr, [] {});
+            int unused_q = -1, unused_z = -1;
+            v3_gather(xrs, slot_off, voffq, voffz, tag, full_s, ctl_s, a.spin_limit, dead, unused_q, unused_z, [] {});
             gstep += 1;
         }
         // best final state, lowest index among equals (every workgroup has the whole vector; the first writes)
